@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the SLA chunked forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path (one ``sla_forward`` call: head softmax, decay products,
+intra-block scores and outputs, state read-out, gated epilogue, state update, final state) over one
+batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "tokens/sec SLA-GLA chunked fwd (B=8,T=2048,H=16,d=128 bf16); % MFMA peak"
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+BLOCK = 16                      # tokens per state step in the kernels (for the causal flop count)
+
+
+def algorithmic_bytes(w) -> int:
+    """One read of every input and one write of every output (the per-token figure of the design notes
+    times the tokens of the workload, plus the final state)."""
+    es = 2 if w.dtype == "bf16" else 4
+    per_token_head = (2 * w.dk + 2 * w.dv) * es + 8  # q, k, v, out + two fp32 gate logits
+    if w.variant == 1:
+        per_token_head += w.dk * es  # per-dimension log-decay
+    elif w.variant == 2:
+        per_token_head += 8  # scalar log-decay and beta
+    return w.B * w.T * w.H * per_token_head + w.B * w.H * w.dk * w.dv * 4
+
+
+def algorithmic_flops(w) -> int:
+    """Multiply-adds the method needs, counted as 2 flops, with only the causal half of the score tiles:
+    read-out and state update 4*dk*dv per token-head, scores and their product with V (C+1)(dk+dv) for
+    a chunk of C = 64 (the staging size); the delta rule adds its own products."""
+    C = 64
+    per = 4 * w.dk * w.dv + (C + 1) * (w.dk + w.dv)
+    if w.variant == 2:
+        per += 2 * w.dk * w.dv + (C + 1) * (w.dk + w.dv) + (C * C) // 3
+    return w.B * w.T * w.H * per
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="gla_train")
+    ap.add_argument("--dv-split", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no collectives or sharding are built)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2602_01744_amd as sla
+    import sla_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sla.load_library()  # fails loudly if the HIP library is not built
+    w = si.workload(args.workload)
+    d = si.generate(w)
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import rel_err, to_device
+
+    g, tdt = to_device(d, w.dtype, w.variant)
+    dev = torch.device("cuda:0")
+    out = torch.empty((w.B, w.T, w.H, w.dv), dtype=tdt, device=dev)
+    fin = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+
+    def step():
+        sla.forward(w.variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], g["beta"], None,
+                    dv_split=args.dv_split, out=out, final_state=fin)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # per-launch kernel time: HIP events on the stream the kernel is enqueued on (torch's current stream)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    kernel_ms = float(np.mean(per_launch_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    tokens = w.tokens()
+    value = tokens / (ms_per_step * 1e-3)
+
+    abytes = algorithmic_bytes(w)
+    aflops = algorithmic_flops(w)
+    achieved_gbs = abytes / (kernel_ms * 1e-3) / 1e9
+    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, args.dv_split, 0)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    dvw = args.dv_split or sla.sla_default_dv_split(params, cus)
+    params.dv_split = dvw
+
+    result = {
+        "metric": METRIC,
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} dk={w.dk} dv={w.dv} "
+                        f"{w.dtype} in/out, fp32 state, dual head-softmax gates",
+            "kernel": sla.sla_kernel_name(params),
+            "dv_split": dvw,
+            "compute_units": cus,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved_gbs,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved_gbs / HBM_PEAK_GBS,
+            "traffic": None,
+            "kernel_us": kernel_ms * 1e3,
+            "kernel_us_min": float(np.min(per_launch_ms)) * 1e3,
+            "algorithmic_bytes": abytes,
+            "mfma_tflops_causal": aflops / (kernel_ms * 1e-3) / 1e12,
+            "mfma_frac_of_bf16_peak": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        },
+    }
+
+    ro = None
+    if not args.no_cpu_baseline or not args.no_parity:
+        import oracle
+
+        nthreads = oracle.threads(0)
+        t0 = time.perf_counter()
+        ro, rf = oracle.forward(w.variant, d["q"], d["k"], d["v"], d["q_logits"], d["k_logits"], d["log_decay"],
+                                d["beta"], None)
+        cpu_s = time.perf_counter() - t0
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {
+                "value": tokens / cpu_s,
+                "unit": "tokens/s",
+                "cores": nthreads,
+                "kind": "oracle",
+                "sample": f"the full workload once ({tokens} tokens x {w.H} heads, {cpu_s:.2f} s wall)",
+            }
+        if not args.no_parity:
+            step()
+            torch.cuda.synchronize()
+            result["parity"] = {
+                "out_rel_err": rel_err(out.to(torch.float32).cpu().numpy().astype(np.float64), ro),
+                "state_rel_err": rel_err(fin.cpu().numpy().astype(np.float64), rf),
+                "definition": "max|x - oracle| / max|oracle| per tensor",
+            }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,123 @@
+/*
+ * libsla — Softmax Linear Attention (SLA) chunkwise-parallel forward for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer below is a DEVICE pointer unless it says "host".  The
+ * caller owns every buffer; the library never frees or keeps a pointer, never
+ * synchronises the device and enqueues all work on the stream it is given.
+ * Functions return 0 on success and a negative sla_status on failure; on
+ * failure nothing has been launched and no output has been touched.
+ *
+ * What one call computes, for every batch b and head h (row-vector convention,
+ * state S is [dk x dv], y = q S):
+ *
+ *   gates (Eq. 4)          G^Q[b,t,:] = softmax over the H heads of q_head_logits[b,t,:]
+ *                          G^K[b,t,:] = softmax over the H heads of k_head_logits[b,t,:]   (1 if NULL)
+ *   RetNet (Sec. 5.1)      S_t = gamma_h S_{t-1} + (G^K_t k_t)^T v_t            gamma_h   = exp(log_decay[h])
+ *   GLA    (Sec. 5.1)      S_t = diag(alpha_t) S_{t-1} + (G^K_t k_t)^T v_t      alpha_t,d = exp(log_decay[b,t,h,d])
+ *   GDN    (Sec. 5.1)      Sb = a_t S_{t-1};  u = beta_t (G^K_t v_t - k_t Sb);  S_t = Sb + k_t^T u
+ *                                                                               a_t = exp(log_decay[b,t,h])
+ *   read-out (Eq. 5-6)     out[b,t,h,:] = G^Q_t (q_t S_t)      -- the state after token t
+ *   final_state[b,h]       = S_T
+ *
+ * It is evaluated in the chunkwise-parallel form of Sec. 3.2 ("Chunkwise
+ * Parallel Training"): matrix products inside blocks of tokens, the state
+ * carried between blocks in fp32; the result does not depend on the blocking
+ * beyond rounding.  q and k are taken as given: the feature map, any 1/sqrt(d)
+ * scaling or L2 normalisation, and the projections that produce the gate
+ * logits (Eq. 4) and consume the output (Eq. 7) are the caller's.
+ *
+ * Domain: every log-decay must be <= 0; for GLA each must also be >= -5
+ * (a decay factor below e^-5 per token cannot be represented by the blocked
+ * evaluation without overflow; outside this range results may be inf/NaN).
+ * NaN or infinite inputs propagate to the outputs; they are not trapped.
+ */
+#ifndef SLA_H_
+#define SLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Which recurrence of Sec. 5.1 ("Instantiations on Linear Baselines") to run. */
+typedef enum { SLA_RETNET = 0, SLA_GLA = 1, SLA_GDN = 2 } sla_variant;
+
+/* Element type of q, k, v, out (and of the GLA log_decay).  Accumulation and the state are fp32. */
+typedef enum { SLA_F32 = 0, SLA_BF16 = 1 } sla_dtype;
+
+typedef enum {
+    SLA_OK = 0,
+    SLA_ERR_NULL = -1,        /* a required pointer is NULL, or a pointer that must be NULL is not */
+    SLA_ERR_SHAPE = -2,       /* a size is negative or out of range */
+    SLA_ERR_UNSUPPORTED = -3, /* variant / dtype / head dimension not built */
+    SLA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
+    SLA_ERR_HIP = -5          /* the HIP runtime refused the launch (no device, bad stream, ...) */
+} sla_status;
+
+/* Problem description (host memory, read during the call only). */
+typedef struct {
+    int32_t variant; /* sla_variant */
+    int32_t dtype;   /* sla_dtype */
+    int32_t B;       /* batch size            >= 0 */
+    int32_t T;       /* tokens per sequence   >= 0 */
+    int32_t H;       /* heads                 1..64 */
+    int32_t dk;      /* key/query head width  64 or 128 */
+    int32_t dv;      /* value head width      64 or 128 */
+    int32_t dv_split; /* 0 = let the library choose; else value columns per workgroup: 16, 32, 64 or 128 (<= dv).
+                        A scheduling knob only: the result does not depend on it beyond nothing at all
+                        (each output column is computed by exactly one workgroup in a fixed order). */
+    int32_t flags;   /* must be 0 */
+} sla_params;
+
+/*
+ * SLA forward, Eq. 3-6 with the Sec. 5.1 recurrences, chunkwise-parallel (Sec. 3.2).
+ *
+ *   q, k            [B,T,H,dk]  dtype   feature-mapped queries / keys
+ *   v               [B,T,H,dv]  dtype
+ *   q_head_logits   [B,T,H]     fp32    read-gate scores  (Q W_GQ in Eq. 4); required
+ *   k_head_logits   [B,T,H]     fp32    write-gate scores (K W_GK in Eq. 4); NULL means G^K = 1
+ *   log_decay       RetNet: fp32 [H];  GLA: dtype [B,T,H,dk];  GDN: fp32 [B,T,H]
+ *   beta            GDN: fp32 [B,T,H] in [0,1]; must be NULL for RetNet and GLA
+ *   initial_state   [B,H,dk,dv] fp32, or NULL for a zero state
+ *   out             [B,T,H,dv]  dtype   written
+ *   final_state     [B,H,dk,dv] fp32    written; NULL to skip.  May alias initial_state.
+ *   stream          a hipStream_t passed as void* (NULL = the default stream)
+ *
+ * All tensors are dense and row-major in the index order shown; pointers must
+ * be 16-byte aligned.  B == 0 is a no-op.  T == 0 copies initial_state (or
+ * zeros) to final_state.  Asynchronous: returns after enqueueing.
+ */
+int sla_forward(const sla_params* p, const void* q, const void* k, const void* v,
+                const float* q_head_logits, const float* k_head_logits,
+                const void* log_decay, const float* beta, const float* initial_state,
+                void* out, float* final_state, void* stream);
+
+/*
+ * Validates the same arguments as sla_forward (host-side checks only, touches no
+ * device and launches nothing).  Returns what sla_forward would return before
+ * its first HIP call.
+ */
+int sla_check_args(const sla_params* p, const void* q, const void* k, const void* v,
+                   const float* q_head_logits, const float* k_head_logits,
+                   const void* log_decay, const float* beta, const float* initial_state,
+                   const void* out, const float* final_state);
+
+/* Value columns per workgroup the library would choose for *p (the dv_split it resolves 0 to); <0 on error. */
+int sla_default_dv_split(const sla_params* p, int compute_units);
+
+/* Name of the device kernel that sla_forward launches for *p (static string, host memory); NULL on error.
+ * Lets a profiler summary be matched to a call. */
+const char* sla_kernel_name(const sla_params* p);
+
+/* Human-readable text for a status code (static string, host memory). */
+const char* sla_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sla_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLA_H_ */

@@ -1,0 +1,29 @@
+"""MI355X-native Softmax Linear Attention (SLA) chunkwise-parallel forward.
+
+A thin ctypes binding over ``libsla.so`` (C ABI declared in ``include/sla.h``).
+PyTorch is used for device memory and streams only; every step of the path
+runs in the library's HIP kernels.  There is no CPU fallback: without the
+built library the calls raise.
+"""
+from .binding import (  # noqa: F401
+    RETNET,
+    GLA,
+    GDN,
+    F32,
+    BF16,
+    SlaError,
+    SlaParams,
+    library_path,
+    load_library,
+    sla_check_args,
+    sla_default_dv_split,
+    sla_forward,
+    sla_kernel_name,
+    sla_status_string,
+    sla_version,
+    forward,
+)
+
+# Variants with kernels in this build (sla_forward returns SLA_ERR_UNSUPPORTED for the others).
+SUPPORTED_VARIANTS = (RETNET, GLA)
+

@@ -1,0 +1,165 @@
+"""ctypes binding for libsla.so: argument marshalling only.
+
+The functions ``sla_*`` mirror the C ABI one to one (raw integer addresses in,
+status code out).  ``forward`` is the convenience wrapper the tests and the
+benchmark use: it takes torch CUDA tensors, allocates the outputs with torch and
+passes ``data_ptr()``s and the current stream to ``sla_forward``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+RETNET, GLA, GDN = 0, 1, 2
+F32, BF16 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsla.so")
+_lib = None
+
+
+class SlaError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libsla: {text} (status {status})")
+        self.status = status
+
+
+class SlaParams(ctypes.Structure):
+    _fields_ = [
+        ("variant", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("B", ctypes.c_int32),
+        ("T", ctypes.c_int32),
+        ("H", ctypes.c_int32),
+        ("dk", ctypes.c_int32),
+        ("dv", ctypes.c_int32),
+        ("dv_split", ctypes.c_int32),
+        ("flags", ctypes.c_int32),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsla.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2602_01744_amd.build` "
+            "(or __graft_entry__.build()); there is no CPU fallback"
+        )
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp = ctypes.c_void_p
+    pp = ctypes.POINTER(SlaParams)
+    lib.sla_forward.restype = ctypes.c_int
+    lib.sla_forward.argtypes = [pp] + [vp] * 11
+    lib.sla_check_args.restype = ctypes.c_int
+    lib.sla_check_args.argtypes = [pp] + [vp] * 10
+    lib.sla_default_dv_split.restype = ctypes.c_int
+    lib.sla_default_dv_split.argtypes = [pp, ctypes.c_int]
+    lib.sla_kernel_name.restype = ctypes.c_char_p
+    lib.sla_kernel_name.argtypes = [pp]
+    lib.sla_status_string.restype = ctypes.c_char_p
+    lib.sla_status_string.argtypes = [ctypes.c_int]
+    lib.sla_version.restype = ctypes.c_int
+    lib.sla_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _p(x) -> Optional[int]:
+    return None if not x else int(x)
+
+
+def sla_status_string(status: int) -> str:
+    return load_library().sla_status_string(int(status)).decode()
+
+
+def sla_version() -> int:
+    return int(load_library().sla_version())
+
+
+def sla_default_dv_split(params: SlaParams, compute_units: int) -> int:
+    return int(load_library().sla_default_dv_split(ctypes.byref(params), int(compute_units)))
+
+
+def sla_kernel_name(params: SlaParams) -> Optional[str]:
+    s = load_library().sla_kernel_name(ctypes.byref(params))
+    return None if s is None else s.decode()
+
+
+def sla_check_args(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state) -> int:
+    """Raw call: integer addresses (0/None = NULL).  Returns the status code."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_check_args(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta),
+            _p(initial_state), _p(out), _p(final_state),
+        )
+    )
+
+
+def sla_forward(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state,
+                stream) -> int:
+    """Raw call: integer device addresses (0/None = NULL) and a hipStream_t handle.  Returns the status code."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_forward(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta),
+            _p(initial_state), _p(out), _p(final_state), _p(stream),
+        )
+    )
+
+
+def forward(
+    variant: int,
+    q,
+    k,
+    v,
+    q_head_logits,
+    k_head_logits,
+    log_decay,
+    beta=None,
+    initial_state=None,
+    *,
+    dv_split: int = 0,
+    out=None,
+    final_state=None,
+    want_final_state: bool = True,
+) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
+    """SLA forward on the current CUDA(HIP) device and stream.  Tensors must be contiguous CUDA tensors:
+    q,k [B,T,H,dk], v [B,T,H,dv] in float32 or bfloat16; logits/beta/initial_state float32."""
+    import torch
+
+    assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == (B, T, H, dk) and v.shape == (B, T, H, dv) and k.dtype == q.dtype and v.dtype == q.dtype
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+    assert q_head_logits.dtype == torch.float32 and q_head_logits.shape == (B, T, H) and q_head_logits.is_contiguous()
+    if k_head_logits is not None:
+        assert k_head_logits.dtype == torch.float32 and k_head_logits.shape == (B, T, H) and k_head_logits.is_contiguous()
+    want = {RETNET: ((H,), torch.float32), GLA: ((B, T, H, dk), q.dtype), GDN: ((B, T, H), torch.float32)}[variant]
+    assert tuple(log_decay.shape) == want[0] and log_decay.dtype == want[1] and log_decay.is_contiguous()
+    if beta is not None:
+        assert beta.dtype == torch.float32 and beta.shape == (B, T, H) and beta.is_contiguous()
+    if initial_state is not None:
+        assert initial_state.dtype == torch.float32 and initial_state.shape == (B, H, dk, dv) and initial_state.is_contiguous()
+    if out is None:
+        out = torch.empty((B, T, H, dv), dtype=q.dtype, device=q.device)
+    if final_state is None and want_final_state:
+        final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
+    params = SlaParams(variant, dtype, B, T, H, dk, dv, dv_split, 0)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_forward(
+        params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta),
+        ptr(initial_state), ptr(out), ptr(final_state), torch.cuda.current_stream(q.device).cuda_stream,
+    )
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return out, final_state

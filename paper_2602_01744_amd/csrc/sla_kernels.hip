@@ -1,0 +1,542 @@
+// SLA chunkwise-parallel forward for gfx950 (MI355X): device kernels and their launcher.
+//
+// Algorithm (Sec. 3.2 "Chunkwise Parallel Training" applied to the recurrences of Sec. 5.1, with the
+// gates of Eq. 4 absorbed into the operands as in Appendix A):
+//
+//   One workgroup owns one (batch, head) pair and DVW of its dv value columns; its state slice
+//   S[dk, DVW] lives in fp32 MFMA accumulators for the whole sequence.  Tokens are staged 64 at a
+//   time and processed as four blocks of 16.  For a block entered with state S0, with
+//   p_t = prod_{i<=t in block} alpha_i (per key dimension for GLA, scalar otherwise) and A = p_16:
+//
+//       qa_t = q_t * p_t          kd_j = k_j / p_j          kb_j = k_j * A / p_j          v'_j = G^K_j v_j
+//       P[t,j] = qa_t . kd_j  for j <= t, else 0            (decay between j and t: p_t / p_j)
+//       out_t  = G^Q_t ( qa_t S0 + sum_j P[t,j] v'_j )      (Eq. 5-6: read-out of the updated state)
+//       S_next = diag(A) S0 + sum_j kb_j^T v'_j
+//
+//   Every factor except 1/p_j is <= 1; 1/p_j is bounded by e^(16*5) because a block has 16 tokens
+//   and log-decays are required to be >= -5, so nothing overflows in fp32 or bf16.
+//
+//   Phase 1 ("producer", all four waves, one 16-token block each): global loads issued one chunk
+//   ahead into registers; head softmax (Eq. 4) with wavefront shuffles; decay products; operands
+//   written to LDS as qa, kd (row-major) and kb, v' (token-major, i.e. transposed).
+//   Phase 2 ("consumer", wave w owns value columns 16w..16w+15): P^T, read-out, epilogue store,
+//   state update, all on MFMA with fp32 accumulation; no cross-wave traffic.
+//
+// MFMA layouts relied upon (16x16 tiles, wave64; r = lane%16, g = lane/16):
+//   A operand: row r, contraction slots owned by group g;  B operand: column r, same slots;
+//   C/D: column r, rows 4g..4g+3 in the four accumulator registers.
+// A C tile of X is therefore directly the B operand of X and the A operand of X^T for a contraction
+// whose slot set for group g is {4g..4g+3}; all LDS fragments are read in that slot order.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sla.h"
+
+namespace sla {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((ext_vector_type(8))) short i16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+static constexpr float kLog2e = 1.4426950408889634f;
+static constexpr int kChunk = 64;   // tokens staged in LDS at a time
+static constexpr int kBlock = 16;   // tokens per state step
+static constexpr int kWaves = 4;
+static constexpr int kMaxHeadRegs = 16;  // H <= 4 * kMaxHeadRegs
+
+struct KArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const float* ql;
+    const float* kl;
+    const void* ld;
+    const float* beta;
+    const float* s0;
+    void* out;
+    float* sT;
+    int B, T, H, dv;
+    int nslice;
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    bf16x2 t;
+    t.x = (__bf16)lo;
+    t.y = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, t);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// ---------------------------------------------------------------------------------------------
+// Precision policies: how two adjacent elements travel through registers, LDS and MFMA.
+// ---------------------------------------------------------------------------------------------
+struct PrecBF16 {
+    typedef uint16_t elem;
+    typedef i16x4 frag;      // four consecutive contraction slots
+    typedef uint32_t pair;   // two adjacent elements
+    static __device__ __forceinline__ pair zero_pair() { return 0u; }
+    static __device__ __forceinline__ float lo(pair p) { return bf16_lo(p); }
+    static __device__ __forceinline__ float hi(pair p) { return bf16_hi(p); }
+    static __device__ __forceinline__ pair make(float a, float b) { return pack_bf16(a, b); }
+    static __device__ __forceinline__ pair load1(const elem* p) { return (uint32_t)(*p); }  // value in .lo slot
+    static __device__ __forceinline__ float lo1(pair p) { return bf16_lo(p); }
+    static __device__ __forceinline__ void store1(elem* p, float a) { *p = (uint16_t)(pack_bf16(a, 0.f) & 0xffffu); }
+    static __device__ __forceinline__ frag from_acc(f32x4 c) {
+        u32x2 t;
+        t.x = pack_bf16(c[0], c[1]);
+        t.y = pack_bf16(c[2], c[3]);
+        return __builtin_bit_cast(frag, t);
+    }
+    static __device__ __forceinline__ void mma32(f32x4& c, frag a0, frag a1, frag b0, frag b1) {
+        i16x8 a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+        i16x8 b = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                    0, 0);
+    }
+    // A 16-slot contraction is issued as the 32-slot instruction with the upper slots zero, so that
+    // every accumulation chain consists of one MFMA opcode only: a 16x16x16 issued right behind a
+    // 16x16x32 on the same accumulator read a partially written C on gfx950 (the first two result
+    // registers lacked the last 16x16x32's contribution).
+    static __device__ __forceinline__ void mma16(f32x4& c, frag a, frag b) {
+        const frag z = {0, 0, 0, 0};
+        mma32(c, a, z, b, z);
+    }
+};
+
+struct PrecF32 {
+    typedef float elem;
+    typedef f32x4 frag;
+    typedef f32x2 pair;
+    static __device__ __forceinline__ pair zero_pair() { return f32x2{0.f, 0.f}; }
+    static __device__ __forceinline__ float lo(pair p) { return p.x; }
+    static __device__ __forceinline__ float hi(pair p) { return p.y; }
+    static __device__ __forceinline__ pair make(float a, float b) { return f32x2{a, b}; }
+    static __device__ __forceinline__ pair load1(const elem* p) { return f32x2{*p, 0.f}; }
+    static __device__ __forceinline__ float lo1(pair p) { return p.x; }
+    static __device__ __forceinline__ void store1(elem* p, float a) { *p = a; }
+    static __device__ __forceinline__ frag from_acc(f32x4 c) { return c; }
+    static __device__ __forceinline__ void mma16(f32x4& c, frag a, frag b) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[i], c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void mma32(f32x4& c, frag a0, frag a1, frag b0, frag b1) {
+        mma16(c, a0, b0);
+        mma16(c, a1, b1);
+    }
+};
+
+// Store N consecutive elements (N*sizeof(elem) is 4, 8, 16, 32 or 64 bytes; dst aligned to min(16, bytes)).
+template <class P, int N>
+__device__ __forceinline__ void store_run(typename P::elem* dst, const float (&x)[N]) {
+    if constexpr (sizeof(typename P::elem) == 2) {
+        static_assert(N % 2 == 0, "bf16 runs are stored in pairs");
+        uint32_t w[N / 2];
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i) w[i] = pack_bf16(x[2 * i], x[2 * i + 1]);
+        if constexpr (N == 2) {
+            *(uint32_t*)dst = w[0];
+        } else if constexpr (N == 4) {
+            *(u32x2*)dst = u32x2{w[0], w[1]};
+        } else {
+#pragma unroll
+            for (int i = 0; i < N / 8; ++i) ((u32x4*)dst)[i] = u32x4{w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
+        }
+    } else {
+        if constexpr (N == 1) {
+            *dst = x[0];
+        } else if constexpr (N == 2) {
+            *(f32x2*)dst = f32x2{x[0], x[1]};
+        } else {
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i) ((f32x4*)dst)[i] = f32x4{x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]};
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS geometry
+// ---------------------------------------------------------------------------------------------
+template <class P, int DK, int DVW>
+struct Smem {
+    typedef typename P::elem elem;
+    static constexpr int kPad = 16 / sizeof(elem);   // 16 bytes of padding per row
+    static constexpr int RS = DK + kPad;             // row stride of the row-major [token][d] arrays
+    static constexpr int TS = kChunk + kPad;         // row stride of the token-major [d or n][token] arrays
+    static constexpr size_t oQA = 0;
+    static constexpr size_t oKD = oQA + sizeof(elem) * kChunk * RS;
+    static constexpr size_t oKBT = oKD + sizeof(elem) * kChunk * RS;
+    static constexpr size_t oVT = oKBT + sizeof(elem) * DK * TS;
+    static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
+    static constexpr size_t oGQ = oEA + sizeof(float) * (kChunk / kBlock) * DK;
+    static constexpr size_t bytes = oGQ + sizeof(float) * kChunk;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Per-lane staging registers for one 16-token block (what the producer of a wave works on).
+// Lane l owns EPL = DK/64 adjacent key dimensions (d = EPL*l ...) of all 16 tokens of the block,
+// and for V two adjacent value columns of NI = DVW/8 consecutive tokens.
+// ---------------------------------------------------------------------------------------------
+template <class P, int VAR, int DK, int DVW>
+struct Stage {
+    typedef typename P::pair pair;
+    static constexpr int NI = DVW / 8;
+    pair q[kBlock], k[kBlock];
+    pair ld[VAR == SLA_GLA ? kBlock : 1];
+    pair v[NI];
+    float ql[kMaxHeadRegs], kl[kMaxHeadRegs];
+    float ql_own, kl_own;
+};
+
+template <class P, int VAR, int DK, int DVW>
+__device__ __forceinline__ void stage_load(Stage<P, VAR, DK, DVW>& st, const KArgs& a, int b, int h, int n0, int tok0,
+                                           int lane) {
+    typedef typename P::elem elem;
+    typedef typename P::pair pair;
+    constexpr int EPL = DK / 64;
+    constexpr int NI = DVW / 8;
+    constexpr int LPR = DVW / 2;
+    const int T = a.T, H = a.H;
+    const size_t tstride = (size_t)H * DK;
+    const elem* qp = (const elem*)a.q + ((size_t)b * T * H + h) * DK + EPL * lane;
+    const elem* kp = (const elem*)a.k + ((size_t)b * T * H + h) * DK + EPL * lane;
+    const elem* lp = (const elem*)a.ld + ((size_t)b * T * H + h) * DK + EPL * lane;
+#pragma unroll
+    for (int i = 0; i < kBlock; ++i) {
+        const int t = tok0 + i;
+        const bool ok = t < T;
+        if constexpr (EPL == 2) {
+            st.q[i] = ok ? *(const pair*)(qp + t * tstride) : P::zero_pair();
+            st.k[i] = ok ? *(const pair*)(kp + t * tstride) : P::zero_pair();
+            if constexpr (VAR == SLA_GLA) st.ld[i] = ok ? *(const pair*)(lp + t * tstride) : P::zero_pair();
+        } else {
+            st.q[i] = ok ? P::load1(qp + t * tstride) : P::zero_pair();
+            st.k[i] = ok ? P::load1(kp + t * tstride) : P::zero_pair();
+            if constexpr (VAR == SLA_GLA) st.ld[i] = ok ? P::load1(lp + t * tstride) : P::zero_pair();
+        }
+    }
+    {
+        const int p = lane % LPR, tb = (lane / LPR) * NI;
+        const elem* vp = (const elem*)a.v + ((size_t)b * T * H + h) * a.dv + n0 + 2 * p;
+        const size_t vstride = (size_t)H * a.dv;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int t = tok0 + tb + i;
+            st.v[i] = (t < T) ? *(const pair*)(vp + t * vstride) : P::zero_pair();
+        }
+    }
+    {
+        // Gate logits of token tok0 + lane%16: lane group g reads heads g, g+4, ...
+        const int t = tok0 + (lane & 15), g = lane >> 4;
+        const bool ok = t < T;
+        const float* qlp = a.ql + ((size_t)b * T + (ok ? t : 0)) * H;
+        const float* klp = a.kl ? a.kl + ((size_t)b * T + (ok ? t : 0)) * H : nullptr;
+#pragma unroll
+        for (int i = 0; i < kMaxHeadRegs; ++i) {
+            const int hh = g + 4 * i;
+            // heads beyond H never win the max and add exp(-inf) = 0; padded tokens get equal scores
+            st.ql[i] = (hh < H) ? (ok ? qlp[hh] : 0.f) : -INFINITY;
+            st.kl[i] = (hh < H) ? ((ok && klp) ? klp[hh] : 0.f) : -INFINITY;
+        }
+        st.ql_own = ok ? qlp[h] : 0.f;
+        st.kl_own = (ok && klp) ? klp[h] : 0.f;
+    }
+}
+
+// softmax over heads for the token of this lane (Eq. 4); returns the gate of head h.
+__device__ __forceinline__ float head_gate(const float (&x)[kMaxHeadRegs], float own) {
+    float m = x[0];
+#pragma unroll
+    for (int i = 1; i < kMaxHeadRegs; ++i) m = fmaxf(m, x[i]);
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxHeadRegs; ++i) s += fast_exp2((x[i] - m) * kLog2e);
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    return fast_exp2((own - m) * kLog2e) / s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The kernel
+// ---------------------------------------------------------------------------------------------
+template <class P, int VAR, int DK, int DVW>
+__global__ __launch_bounds__(kWaves * 64) void sla_fwd_kernel(const KArgs a) {
+    typedef typename P::elem elem;
+    typedef typename P::frag frag;
+    typedef Smem<P, DK, DVW> L;
+    constexpr int EPL = DK / 64;
+    constexpr int NTILE = DK / 16;
+    constexpr int NI = DVW / 8;
+    constexpr int LPR = DVW / 2;
+    constexpr int NCW = DVW / 16;  // consumer waves
+    static_assert(DK == 64 || DK == 128, "dk");
+    static_assert(DVW == 16 || DVW == 32 || DVW == 64, "value columns per workgroup");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    elem* QA = (elem*)(smem + L::oQA);
+    elem* KD = (elem*)(smem + L::oKD);
+    elem* KBT = (elem*)(smem + L::oKBT);
+    elem* VT = (elem*)(smem + L::oVT);
+    float* EA = (float*)(smem + L::oEA);
+    float* GQ = (float*)(smem + L::oGQ);
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r = lane & 15, g = lane >> 4;
+
+    // Workgroup -> (batch, head, value slice).  Consecutive hardware ids go to different XCDs
+    // (id % 8), so the slices of one head -- which read the same q, k, decay and logits -- are given
+    // ids 8 apart: same XCD, hence same L2.
+    const int total = gridDim.x;
+    const int id = blockIdx.x;
+    const int logical = (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
+    const int slice = logical % a.nslice, bh = logical / a.nslice;
+    const int b = bh / a.H, h = bh % a.H;
+    const int n0 = slice * DVW;
+    const int T = a.T, H = a.H, dv = a.dv;
+
+    // State slice: tile s holds S[16s + 4g + i][n0 + 16*wave + r] in acc[s][i].
+    f32x4 S[NTILE];
+    if (wave < NCW) {
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const size_t off = ((size_t)bh * DK + 16 * s + 4 * g + i) * dv + n0 + 16 * wave + r;
+                S[s][i] = a.s0 ? a.s0[off] : 0.f;
+            }
+        }
+    }
+
+    float decay_const = 1.f;  // RetNet: gamma_h
+    if constexpr (VAR == SLA_RETNET) decay_const = fast_exp2(((const float*)a.ld)[h] * kLog2e);
+
+    const int nchunks = (T + kChunk - 1) / kChunk;
+    Stage<P, VAR, DK, DVW> cur, nxt;
+    stage_load(cur, a, b, h, n0, 16 * wave, lane);
+
+    for (int c = 0; c < nchunks; ++c) {
+        const int tok0 = c * kChunk + kBlock * wave;  // first token of this wave's block
+        // Issue the next chunk's loads before touching this chunk's registers.
+        if (c + 1 < nchunks) stage_load(nxt, a, b, h, n0, tok0 + kChunk, lane);
+
+        // ------------------------------------------------------------------ producer
+        {
+            const float gq = head_gate(cur.ql, cur.ql_own);
+            const float gk = a.kl ? head_gate(cur.kl, cur.kl_own) : 1.f;
+            if (g == 0) GQ[kBlock * wave + r] = gq;
+
+            // decay products along the 16 tokens, per owned key dimension
+            float qa[EPL][kBlock], kd[EPL][kBlock];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                float al[kBlock];
+#pragma unroll
+                for (int i = 0; i < kBlock; ++i) {
+                    if constexpr (VAR == SLA_GLA) {
+                        const float x = (EPL == 2 && e == 1) ? P::hi(cur.ld[i]) : P::lo(cur.ld[i]);
+                        al[i] = fast_exp2(x * kLog2e);
+                    } else {
+                        al[i] = (tok0 + i < T) ? decay_const : 1.f;
+                    }
+                }
+                float pre[kBlock], suf[kBlock];
+                pre[0] = al[0];
+#pragma unroll
+                for (int i = 1; i < kBlock; ++i) pre[i] = pre[i - 1] * al[i];
+                suf[kBlock - 1] = 1.f;
+#pragma unroll
+                for (int i = kBlock - 2; i >= 0; --i) suf[i] = suf[i + 1] * al[i + 1];
+                const float A = pre[kBlock - 1];
+                const float invA = fast_rcp(A);
+                const int d = EPL * lane + e;
+                EA[wave * DK + d] = A;
+                float kb[kBlock];
+#pragma unroll
+                for (int i = 0; i < kBlock; ++i) {
+                    const float qv = (EPL == 2 && e == 1) ? P::hi(cur.q[i]) : P::lo(cur.q[i]);
+                    const float kv = (EPL == 2 && e == 1) ? P::hi(cur.k[i]) : P::lo(cur.k[i]);
+                    kb[i] = kv * suf[i];
+                    qa[e][i] = qv * pre[i];
+                    kd[e][i] = kb[i] * invA;
+                }
+                store_run<P, kBlock>(KBT + d * L::TS + kBlock * wave, kb);
+            }
+#pragma unroll
+            for (int i = 0; i < kBlock; ++i) {
+                elem* qrow = QA + (kBlock * wave + i) * L::RS + EPL * lane;
+                elem* krow = KD + (kBlock * wave + i) * L::RS + EPL * lane;
+                if constexpr (EPL == 2) {
+                    *(typename P::pair*)qrow = P::make(qa[0][i], qa[1][i]);
+                    *(typename P::pair*)krow = P::make(kd[0][i], kd[1][i]);
+                } else {
+                    P::store1(qrow, qa[0][i]);
+                    P::store1(krow, kd[0][i]);
+                }
+            }
+
+            // values: scale by the write gate, transpose to [column][token]
+            {
+                const int p = lane % LPR, tb = (lane / LPR) * NI;
+                float c0[NI], c1[NI];
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const float gki = __shfl(gk, tb + i);
+                    c0[i] = P::lo(cur.v[i]) * gki;
+                    c1[i] = P::hi(cur.v[i]) * gki;
+                }
+                store_run<P, NI>(VT + (2 * p) * L::TS + kBlock * wave + tb, c0);
+                store_run<P, NI>(VT + (2 * p + 1) * L::TS + kBlock * wave + tb, c1);
+            }
+        }
+        __syncthreads();
+
+        // ------------------------------------------------------------------ consumer
+        if (wave < NCW) {
+#pragma unroll 1
+            for (int I = 0; I < kChunk / kBlock; ++I) {
+                const int trow = kBlock * I + r;
+                // fragments of qa (rows = tokens of the block) and kd
+                frag fq[NTILE];
+                f32x4 pT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < NTILE; s += 2) {
+                    fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
+                    fq[s + 1] = *(const frag*)(QA + trow * L::RS + 16 * (s + 1) + 4 * g);
+                    const frag k0 = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
+                    const frag k1 = *(const frag*)(KD + trow * L::RS + 16 * (s + 1) + 4 * g);
+                    P::mma32(pT, k0, k1, fq[s], fq[s + 1]);  // P^T[j][t] += kd[j][d] qa[t][d]
+                }
+                // causal mask: lane holds column t = r, rows j = 4g + i
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] : 0.f;
+                const frag fp = P::from_acc(pT);
+                const frag fv = *(const frag*)(VT + (16 * wave + r) * L::TS + kBlock * I + 4 * g);
+
+                // O^T[n][t] = sum_d S[d][n] qa[t][d] + sum_j v'[j][n] P[t][j]
+                f32x4 oT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < NTILE; s += 2)
+                    P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), fq[s], fq[s + 1]);
+                P::mma16(oT, fv, fp);
+
+                // epilogue: read gate, cast, store 4 adjacent value columns of token t
+                {
+                    const int t = c * kChunk + trow;
+                    const float gq = GQ[trow];
+                    float o[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = oT[i] * gq;
+                    if (t < T) {
+                        elem* op = (elem*)a.out + (((size_t)b * T + t) * H + h) * dv + n0 + 16 * wave + 4 * g;
+                        store_run<P, 4>(op, o);
+                    }
+                }
+
+                // state step: S <- diag(A_I) S + kb^T v'
+#pragma unroll
+                for (int s = 0; s < NTILE; ++s) {
+                    const f32x4 ea = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
+                    const frag fk = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) S[s][i] *= ea[i];
+                    P::mma16(S[s], fk, fv);
+                }
+            }
+        }
+        __syncthreads();
+        if (c + 1 < nchunks) cur = nxt;
+    }
+
+    if (a.sT && wave < NCW) {
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const size_t off = ((size_t)bh * DK + 16 * s + 4 * g + i) * dv + n0 + 16 * wave + r;
+                a.sT[off] = S[s][i];
+            }
+        }
+    }
+}
+
+// T == 0: the state passes through unchanged.
+__global__ void sla_state_passthrough_kernel(const float* s0, float* sT, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) sT[i] = s0 ? s0[i] : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Launch
+// ---------------------------------------------------------------------------------------------
+template <class P, int VAR, int DK, int DVW>
+static int launch(const KArgs& a, hipStream_t stream) {
+    typedef Smem<P, DK, DVW> L;
+    auto kern = sla_fwd_kernel<P, VAR, DK, DVW>;
+    static bool configured = false;  // per instantiation
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::bytes) !=
+            hipSuccess) {
+            (void)hipGetLastError();
+            return SLA_ERR_HIP;
+        }
+        configured = true;
+    }
+    const int grid = a.B * a.H * a.nslice;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), L::bytes, stream, a);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+template <class P, int VAR, int DK>
+static int dispatch_dvw(const KArgs& a, int dvw, hipStream_t stream) {
+    switch (dvw) {
+        case 16: return launch<P, VAR, DK, 16>(a, stream);
+        case 32: return launch<P, VAR, DK, 32>(a, stream);
+        case 64: return launch<P, VAR, DK, 64>(a, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+template <class P, int VAR>
+static int dispatch_dk(const KArgs& a, int dk, int dvw, hipStream_t stream) {
+    switch (dk) {
+        case 64: return dispatch_dvw<P, VAR, 64>(a, dvw, stream);
+        case 128: return dispatch_dvw<P, VAR, 128>(a, dvw, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+template <class P>
+static int dispatch_variant(const KArgs& a, int variant, int dk, int dvw, hipStream_t stream) {
+    switch (variant) {
+        case SLA_RETNET: return dispatch_dk<P, SLA_RETNET>(a, dk, dvw, stream);
+        case SLA_GLA: return dispatch_dk<P, SLA_GLA>(a, dk, dvw, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+int launch_forward(const sla_params& p, int dvw, const void* q, const void* k, const void* v, const float* ql,
+                   const float* kl, const void* ld, const float* beta, const float* s0, void* out, float* sT,
+                   hipStream_t stream) {
+    KArgs a;
+    a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = beta; a.s0 = s0; a.out = out; a.sT = sT;
+    a.B = p.B; a.T = p.T; a.H = p.H; a.dv = p.dv; a.nslice = p.dv / dvw;
+    if (p.T == 0) {
+        if (!sT) return SLA_OK;
+        const size_t n = (size_t)p.B * p.H * p.dk * p.dv;
+        hipLaunchKernelGGL(sla_state_passthrough_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, sT, n);
+        return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+    }
+    if (p.dtype == SLA_BF16) return dispatch_variant<PrecBF16>(a, p.variant, p.dk, dvw, stream);
+    return dispatch_variant<PrecF32>(a, p.variant, p.dk, dvw, stream);
+}
+
+}  // namespace sla

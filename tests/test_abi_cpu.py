@@ -1,0 +1,119 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares, and rejects bad
+calls before any device work (validation runs first)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_01744_amd as sla
+from paper_2602_01744_amd import SlaParams
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 1 << 20  # a 16-byte aligned fake address; validation never dereferences it
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sla.library_path()):
+        from paper_2602_01744_amd import build
+
+        build.build()
+    return sla.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "sla.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
+    assert set(names) >= {"sla_forward", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+                          "sla_status_string", "sla_version"}
+    for n in set(names):
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert sla.sla_version() >= 100
+    for code in (0, -1, -2, -3, -4, -5):
+        assert sla.sla_status_string(code)
+    assert "unknown" in sla.sla_status_string(-99)
+
+
+def _ok_params(**kw):
+    d = dict(variant=sla.GLA, dtype=sla.BF16, B=2, T=128, H=4, dk=128, dv=128, dv_split=0, flags=0)
+    d.update(kw)
+    return SlaParams(**d)
+
+
+def _call(p, **kw):
+    a = dict(q=A, k=A, v=A, ql=A, kl=A, ld=A, beta=0, s0=0, out=A, fin=A)
+    a.update(kw)
+    return sla.sla_check_args(p, a["q"], a["k"], a["v"], a["ql"], a["kl"], a["ld"], a["beta"], a["s0"], a["out"], a["fin"])
+
+
+def test_valid_calls_pass_validation(lib):
+    assert _call(_ok_params()) == 0
+    assert _call(_ok_params(), kl=0, fin=0) == 0
+    assert _call(_ok_params(variant=sla.GDN), beta=A) == 0
+    assert _call(_ok_params(variant=sla.RETNET, dtype=sla.F32, dk=64, dv=64, dv_split=16)) == 0
+    assert _call(_ok_params(B=0), q=0, k=0, v=0, ql=0, ld=0, out=0) == 0
+    assert _call(_ok_params(T=0), q=0, k=0, v=0, ql=0, ld=0, out=0) == 0
+
+
+def test_null_and_misplaced_pointers(lib):
+    for name in ("q", "k", "v", "ql", "ld", "out"):
+        assert _call(_ok_params(), **{name: 0}) == -1, name
+    assert sla.sla_check_args(None, A, A, A, A, A, A, 0, 0, A, A) == -1
+    assert _call(_ok_params(variant=sla.GDN)) == -1           # GDN needs beta
+    assert _call(_ok_params(), beta=A) == -1                   # beta only for GDN
+
+
+def test_shapes_and_unsupported(lib):
+    assert _call(_ok_params(B=-1)) == -2
+    assert _call(_ok_params(T=-5)) == -2
+    assert _call(_ok_params(H=0)) == -2
+    assert _call(_ok_params(H=65)) == -2
+    assert _call(_ok_params(dk=0)) == -2
+    assert _call(_ok_params(dk=96)) == -3
+    assert _call(_ok_params(dv=256)) == -3
+    assert _call(_ok_params(variant=7)) == -3
+    assert _call(_ok_params(dtype=2)) == -3
+    assert _call(_ok_params(flags=1)) == -3
+    assert _call(_ok_params(dv_split=48)) == -2
+    assert _call(_ok_params(dv=64, dv_split=128)) == -2
+    assert _call(_ok_params(dv_split=128)) == -3
+    assert _call(_ok_params(B=1 << 20, T=1 << 20)) == -2
+
+
+def test_alignment(lib):
+    for name in ("q", "k", "v", "ql", "kl", "ld", "out", "fin", "s0"):
+        assert _call(_ok_params(), **{name: A + 8}) == -4, name
+
+
+def test_forward_rejects_before_touching_the_device(lib):
+    # sla_forward runs the same checks first: a bad call returns its status even with no GPU present.
+    p = _ok_params(dk=96)
+    assert sla.sla_forward(p, A, A, A, A, A, A, 0, 0, A, A, 0) == -3
+    assert sla.sla_forward(_ok_params(), 0, A, A, A, A, A, 0, 0, A, A, 0) == -1
+    assert sla.sla_forward(_ok_params(B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
+
+
+def test_default_slice_width_fills_the_device(lib):
+    # 128 sequences on 256 CUs: two slices of 64 columns each
+    assert sla.sla_default_dv_split(_ok_params(B=8, H=16), 256) == 64
+    # 32 sequences: 8 slices of 16 columns
+    assert sla.sla_default_dv_split(_ok_params(B=4, H=8), 256) == 16
+    assert sla.sla_default_dv_split(_ok_params(B=1, H=32), 256) == 16
+    assert sla.sla_default_dv_split(_ok_params(B=64, H=16), 256) == 64
+    assert sla.sla_default_dv_split(_ok_params(), 0) == -2
+    name = sla.sla_kernel_name(_ok_params(B=8, H=16))
+    assert name.startswith("sla_fwd_kernel<") and "128, 64" in name
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2602_01744_amd.binding as b
+
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libsla.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        b.load_library()
