@@ -36,6 +36,12 @@ int check(const sla_params* p, const void* q, const void* k, const void* v, cons
     }
     // index arithmetic in the kernels uses size_t for element offsets but int for token counts
     if ((int64_t)p->B * p->T > (int64_t)1 << 30) return SLA_ERR_SHAPE;
+    {
+        // the kernels address one batch row through 32-bit byte offsets (buffer descriptors)
+        const int64_t es = p->dtype == SLA_BF16 ? 2 : 4;
+        const int64_t wide = p->dk > p->dv ? p->dk : p->dv;
+        if (((int64_t)p->T + 256) * p->H * wide * es > (int64_t)INT32_MAX) return SLA_ERR_SHAPE;
+    }
     const bool empty = (p->B == 0);
     if (!empty && p->T > 0) {
         if (!q || !k || !v || !ql || !ld || !out) return SLA_ERR_NULL;

@@ -16,9 +16,10 @@
 //   Every factor except 1/p_j is <= 1; 1/p_j is bounded by e^(16*5) because a block has 16 tokens
 //   and log-decays are required to be >= -5, so nothing overflows in fp32 or bf16.
 //
-//   Phase 1 ("producer", all four waves, one 16-token block each): global loads issued one chunk
-//   ahead into registers; head softmax (Eq. 4) with wavefront shuffles; decay products; operands
-//   written to LDS as qa, kd (row-major) and kb, v' (token-major, i.e. transposed).
+//   Phase 1 ("producer", all four waves, one 16-token block each): buffer loads (out-of-range tokens
+//   read as zero, no branches) issued one chunk ahead into registers; head softmax (Eq. 4) with
+//   wavefront shuffles; decay products; operands written to LDS as qa, kd (row-major) and kb, v'
+//   (token-major, i.e. transposed).
 //   Phase 2 ("consumer", wave w owns value columns 16w..16w+15): P^T, read-out, epilogue store,
 //   state update, all on MFMA with fp32 accumulation; no cross-wave traffic.
 //
@@ -47,7 +48,7 @@ static constexpr float kLog2e = 1.4426950408889634f;
 static constexpr int kChunk = 64;   // tokens staged in LDS at a time
 static constexpr int kBlock = 16;   // tokens per state step
 static constexpr int kWaves = 4;
-static constexpr int kMaxHeadRegs = 16;  // H <= 4 * kMaxHeadRegs
+static constexpr uint32_t kRsrcWord3 = 0x00020000u;  // raw buffer descriptor, 32-bit data format
 
 struct KArgs {
     const void* q;
@@ -86,7 +87,13 @@ struct PrecBF16 {
     static __device__ __forceinline__ float lo(pair p) { return bf16_lo(p); }
     static __device__ __forceinline__ float hi(pair p) { return bf16_hi(p); }
     static __device__ __forceinline__ pair make(float a, float b) { return pack_bf16(a, b); }
-    static __device__ __forceinline__ pair load1(const elem* p) { return (uint32_t)(*p); }  // value in .lo slot
+    // buffer loads: a pair of adjacent elements, or a single element returned in the .lo slot
+    static __device__ __forceinline__ pair bload2(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+    }
+    static __device__ __forceinline__ pair bload1(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+    }
     static __device__ __forceinline__ float lo1(pair p) { return bf16_lo(p); }
     static __device__ __forceinline__ void store1(elem* p, float a) { *p = (uint16_t)(pack_bf16(a, 0.f) & 0xffffu); }
     static __device__ __forceinline__ frag from_acc(f32x4 c) {
@@ -119,7 +126,12 @@ struct PrecF32 {
     static __device__ __forceinline__ float lo(pair p) { return p.x; }
     static __device__ __forceinline__ float hi(pair p) { return p.y; }
     static __device__ __forceinline__ pair make(float a, float b) { return f32x2{a, b}; }
-    static __device__ __forceinline__ pair load1(const elem* p) { return f32x2{*p, 0.f}; }
+    static __device__ __forceinline__ pair bload2(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+    }
+    static __device__ __forceinline__ pair bload1(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        return f32x2{__uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0)), 0.f};
+    }
     static __device__ __forceinline__ float lo1(pair p) { return p.x; }
     static __device__ __forceinline__ void store1(elem* p, float a) { *p = a; }
     static __device__ __forceinline__ frag from_acc(f32x4 c) { return c; }
@@ -182,84 +194,102 @@ struct Smem {
 // ---------------------------------------------------------------------------------------------
 // Per-lane staging registers for one 16-token block (what the producer of a wave works on).
 // Lane l owns EPL = DK/64 adjacent key dimensions (d = EPL*l ...) of all 16 tokens of the block,
-// and for V two adjacent value columns of NI = DVW/8 consecutive tokens.
+// and for V two adjacent value columns of NI = DVW/8 consecutive tokens.  For the gates, lane
+// (r = l%16, g = l/16) holds the logits of token r for heads g, g+4, ... (HG registers per gate).
 // ---------------------------------------------------------------------------------------------
-template <class P, int VAR, int DK, int DVW>
+template <class P, int VAR, int DK, int DVW, int HG>
 struct Stage {
     typedef typename P::pair pair;
     static constexpr int NI = DVW / 8;
     pair q[kBlock], k[kBlock];
     pair ld[VAR == SLA_GLA ? kBlock : 1];
     pair v[NI];
-    float ql[kMaxHeadRegs], kl[kMaxHeadRegs];
+    float ql[HG], kl[HG];
     float ql_own, kl_own;
 };
 
-template <class P, int VAR, int DK, int DVW>
-__device__ __forceinline__ void stage_load(Stage<P, VAR, DK, DVW>& st, const KArgs& a, int b, int h, int n0, int tok0,
-                                           int lane) {
+// Buffer descriptors of one batch row and the per-lane byte offsets into them.  A descriptor spans
+// exactly the T tokens of batch b, so any access to a token >= T is out of range and returns zero.
+template <class P, int VAR, int DK, int DVW, int HG>
+struct Loader {
     typedef typename P::elem elem;
-    typedef typename P::pair pair;
-    constexpr int EPL = DK / 64;
-    constexpr int NI = DVW / 8;
-    constexpr int LPR = DVW / 2;
-    const int T = a.T, H = a.H;
-    const size_t tstride = (size_t)H * DK;
-    const elem* qp = (const elem*)a.q + ((size_t)b * T * H + h) * DK + EPL * lane;
-    const elem* kp = (const elem*)a.k + ((size_t)b * T * H + h) * DK + EPL * lane;
-    const elem* lp = (const elem*)a.ld + ((size_t)b * T * H + h) * DK + EPL * lane;
-#pragma unroll
-    for (int i = 0; i < kBlock; ++i) {
-        const int t = tok0 + i;
-        const bool ok = t < T;
-        if constexpr (EPL == 2) {
-            st.q[i] = ok ? *(const pair*)(qp + t * tstride) : P::zero_pair();
-            st.k[i] = ok ? *(const pair*)(kp + t * tstride) : P::zero_pair();
-            if constexpr (VAR == SLA_GLA) st.ld[i] = ok ? *(const pair*)(lp + t * tstride) : P::zero_pair();
-        } else {
-            st.q[i] = ok ? P::load1(qp + t * tstride) : P::zero_pair();
-            st.k[i] = ok ? P::load1(kp + t * tstride) : P::zero_pair();
-            if constexpr (VAR == SLA_GLA) st.ld[i] = ok ? P::load1(lp + t * tstride) : P::zero_pair();
-        }
-    }
-    {
+    typedef Stage<P, VAR, DK, DVW, HG> stage_t;
+    static constexpr int EPL = DK / 64;
+    static constexpr int NI = DVW / 8;
+    static constexpr int LPR = DVW / 2;
+    __amdgpu_buffer_rsrc_t rq, rk, rv, rld, rql, rkl;
+    int voff_qk, voff_v, voff_lg, voff_own;
+    int tstride_qk, tstride_v, tstride_lg;  // bytes per token
+    int H;
+    bool has_kl;
+
+    __device__ __forceinline__ void init(const KArgs& a, int b, int h, int n0, int lane) {
+        const int T = a.T;
+        H = a.H;
+        has_kl = a.kl != nullptr;
+        tstride_qk = H * DK * (int)sizeof(elem);
+        tstride_v = H * a.dv * (int)sizeof(elem);
+        tstride_lg = H * 4;
+        const size_t row_qk = (size_t)b * T * H * DK, row_v = (size_t)b * T * H * a.dv, row_lg = (size_t)b * T * H;
+        rq = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.q + row_qk), 0, T * tstride_qk, kRsrcWord3);
+        rk = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.k + row_qk), 0, T * tstride_qk, kRsrcWord3);
+        rv = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.v + row_v), 0, T * tstride_v, kRsrcWord3);
+        if constexpr (VAR == SLA_GLA)
+            rld = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.ld + row_qk), 0, T * tstride_qk, kRsrcWord3);
+        rql = __builtin_amdgcn_make_buffer_rsrc((void*)(a.ql + row_lg), 0, T * tstride_lg, kRsrcWord3);
+        // without write-gate logits the descriptor is empty: every load returns 0 and the gate is forced to 1
+        rkl = __builtin_amdgcn_make_buffer_rsrc((void*)(has_kl ? a.kl + row_lg : a.ql), 0, has_kl ? T * tstride_lg : 0,
+                                                kRsrcWord3);
+        voff_qk = (h * DK + EPL * lane) * (int)sizeof(elem);
         const int p = lane % LPR, tb = (lane / LPR) * NI;
-        const elem* vp = (const elem*)a.v + ((size_t)b * T * H + h) * a.dv + n0 + 2 * p;
-        const size_t vstride = (size_t)H * a.dv;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int t = tok0 + tb + i;
-            st.v[i] = (t < T) ? *(const pair*)(vp + t * vstride) : P::zero_pair();
-        }
+        voff_v = tb * tstride_v + (h * a.dv + n0 + 2 * p) * (int)sizeof(elem);
+        voff_lg = (lane & 15) * tstride_lg + (lane >> 4) * 4;
+        voff_own = (lane & 15) * tstride_lg + h * 4;
     }
-    {
-        // Gate logits of token tok0 + lane%16: lane group g reads heads g, g+4, ...
-        const int t = tok0 + (lane & 15), g = lane >> 4;
-        const bool ok = t < T;
-        const float* qlp = a.ql + ((size_t)b * T + (ok ? t : 0)) * H;
-        const float* klp = a.kl ? a.kl + ((size_t)b * T + (ok ? t : 0)) * H : nullptr;
+
+    // tok0 must be wave-uniform (it is turned into scalar offsets).
+    __device__ __forceinline__ void load(stage_t& st, int tok0, int lane) const {
+        const int s_qk = tok0 * tstride_qk, s_v = tok0 * tstride_v, s_lg = tok0 * tstride_lg;
 #pragma unroll
-        for (int i = 0; i < kMaxHeadRegs; ++i) {
-            const int hh = g + 4 * i;
-            // heads beyond H never win the max and add exp(-inf) = 0; padded tokens get equal scores
-            st.ql[i] = (hh < H) ? (ok ? qlp[hh] : 0.f) : -INFINITY;
-            st.kl[i] = (hh < H) ? ((ok && klp) ? klp[hh] : 0.f) : -INFINITY;
+        for (int i = 0; i < kBlock; ++i) {
+            if constexpr (EPL == 2) {
+                st.q[i] = P::bload2(rq, voff_qk, s_qk + i * tstride_qk);
+                st.k[i] = P::bload2(rk, voff_qk, s_qk + i * tstride_qk);
+                if constexpr (VAR == SLA_GLA) st.ld[i] = P::bload2(rld, voff_qk, s_qk + i * tstride_qk);
+            } else {
+                st.q[i] = P::bload1(rq, voff_qk, s_qk + i * tstride_qk);
+                st.k[i] = P::bload1(rk, voff_qk, s_qk + i * tstride_qk);
+                if constexpr (VAR == SLA_GLA) st.ld[i] = P::bload1(rld, voff_qk, s_qk + i * tstride_qk);
+            }
         }
-        st.ql_own = ok ? qlp[h] : 0.f;
-        st.kl_own = (ok && klp) ? klp[h] : 0.f;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, s_v + i * tstride_v);
+        const int g = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < HG; ++i) {
+            // heads beyond H never win the max and add exp(-inf) = 0; tokens beyond T read 0 (equal scores)
+            const bool head_ok = g + 4 * i < H;
+            const float x = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_lg, s_lg + 16 * i, 0));
+            const float y = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_lg, s_lg + 16 * i, 0));
+            st.ql[i] = head_ok ? x : -INFINITY;
+            st.kl[i] = head_ok ? y : -INFINITY;
+        }
+        st.ql_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_own, s_lg, 0));
+        st.kl_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_own, s_lg, 0));
     }
-}
+};
 
 // softmax over heads for the token of this lane (Eq. 4); returns the gate of head h.
-__device__ __forceinline__ float head_gate(const float (&x)[kMaxHeadRegs], float own) {
+template <int HG>
+__device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
     float m = x[0];
 #pragma unroll
-    for (int i = 1; i < kMaxHeadRegs; ++i) m = fmaxf(m, x[i]);
+    for (int i = 1; i < HG; ++i) m = fmaxf(m, x[i]);
     m = fmaxf(m, __shfl_xor(m, 16));
     m = fmaxf(m, __shfl_xor(m, 32));
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < kMaxHeadRegs; ++i) s += fast_exp2((x[i] - m) * kLog2e);
+    for (int i = 0; i < HG; ++i) s += fast_exp2((x[i] - m) * kLog2e);
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
     return fast_exp2((own - m) * kLog2e) / s;
@@ -268,10 +298,11 @@ __device__ __forceinline__ float head_gate(const float (&x)[kMaxHeadRegs], float
 // ---------------------------------------------------------------------------------------------
 // The kernel
 // ---------------------------------------------------------------------------------------------
-template <class P, int VAR, int DK, int DVW>
-__global__ __launch_bounds__(kWaves * 64) void sla_fwd_kernel(const KArgs a) {
+template <class P, int VAR, int DK, int DVW, int HG>
+__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void sla_fwd_kernel(const KArgs a) {
     typedef typename P::elem elem;
     typedef typename P::frag frag;
+    typedef typename P::pair pair;
     typedef Smem<P, DK, DVW> L;
     constexpr int EPL = DK / 64;
     constexpr int NTILE = DK / 16;
@@ -289,7 +320,8 @@ __global__ __launch_bounds__(kWaves * 64) void sla_fwd_kernel(const KArgs a) {
     float* EA = (float*)(smem + L::oEA);
     float* GQ = (float*)(smem + L::oGQ);
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
 
     // Workgroup -> (batch, head, value slice).  Consecutive hardware ids go to different XCDs
@@ -320,68 +352,71 @@ __global__ __launch_bounds__(kWaves * 64) void sla_fwd_kernel(const KArgs a) {
     if constexpr (VAR == SLA_RETNET) decay_const = fast_exp2(((const float*)a.ld)[h] * kLog2e);
 
     const int nchunks = (T + kChunk - 1) / kChunk;
-    Stage<P, VAR, DK, DVW> cur, nxt;
-    stage_load(cur, a, b, h, n0, 16 * wave, lane);
+    Loader<P, VAR, DK, DVW, HG> ldr;
+    ldr.init(a, b, h, n0, lane);
+    Stage<P, VAR, DK, DVW, HG> st;
+    ldr.load(st, kBlock * wave, lane);
 
     for (int c = 0; c < nchunks; ++c) {
         const int tok0 = c * kChunk + kBlock * wave;  // first token of this wave's block
-        // Issue the next chunk's loads before touching this chunk's registers.
-        if (c + 1 < nchunks) stage_load(nxt, a, b, h, n0, tok0 + kChunk, lane);
 
         // ------------------------------------------------------------------ producer
         {
-            const float gq = head_gate(cur.ql, cur.ql_own);
-            const float gk = a.kl ? head_gate(cur.kl, cur.kl_own) : 1.f;
+            const float gq = head_gate<HG>(st.ql, st.ql_own);
+            const float gk = ldr.has_kl ? head_gate<HG>(st.kl, st.kl_own) : 1.f;
             if (g == 0) GQ[kBlock * wave + r] = gq;
 
-            // decay products along the 16 tokens, per owned key dimension
-            float qa[EPL][kBlock], kd[EPL][kBlock];
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                float al[kBlock];
-#pragma unroll
-                for (int i = 0; i < kBlock; ++i) {
-                    if constexpr (VAR == SLA_GLA) {
-                        const float x = (EPL == 2 && e == 1) ? P::hi(cur.ld[i]) : P::lo(cur.ld[i]);
-                        al[i] = fast_exp2(x * kLog2e);
-                    } else {
-                        al[i] = (tok0 + i < T) ? decay_const : 1.f;
-                    }
-                }
-                float pre[kBlock], suf[kBlock];
-                pre[0] = al[0];
-#pragma unroll
-                for (int i = 1; i < kBlock; ++i) pre[i] = pre[i - 1] * al[i];
-                suf[kBlock - 1] = 1.f;
-#pragma unroll
-                for (int i = kBlock - 2; i >= 0; --i) suf[i] = suf[i + 1] * al[i + 1];
-                const float A = pre[kBlock - 1];
-                const float invA = fast_rcp(A);
-                const int d = EPL * lane + e;
-                EA[wave * DK + d] = A;
-                float kb[kBlock];
-#pragma unroll
-                for (int i = 0; i < kBlock; ++i) {
-                    const float qv = (EPL == 2 && e == 1) ? P::hi(cur.q[i]) : P::lo(cur.q[i]);
-                    const float kv = (EPL == 2 && e == 1) ? P::hi(cur.k[i]) : P::lo(cur.k[i]);
-                    kb[i] = kv * suf[i];
-                    qa[e][i] = qv * pre[i];
-                    kd[e][i] = kb[i] * invA;
-                }
-                store_run<P, kBlock>(KBT + d * L::TS + kBlock * wave, kb);
-            }
+            // per-token decay factors of the owned key dimensions
+            float al[EPL][kBlock];
 #pragma unroll
             for (int i = 0; i < kBlock; ++i) {
-                elem* qrow = QA + (kBlock * wave + i) * L::RS + EPL * lane;
-                elem* krow = KD + (kBlock * wave + i) * L::RS + EPL * lane;
-                if constexpr (EPL == 2) {
-                    *(typename P::pair*)qrow = P::make(qa[0][i], qa[1][i]);
-                    *(typename P::pair*)krow = P::make(kd[0][i], kd[1][i]);
+                if constexpr (VAR == SLA_GLA) {
+                    al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
+                    if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
                 } else {
-                    P::store1(qrow, qa[0][i]);
-                    P::store1(krow, kd[0][i]);
+                    const float x = (tok0 + i < T) ? decay_const : 1.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) al[e][i] = x;
                 }
             }
+            // forward: p_t = prod_{i<=t} alpha_i ; qa_t = q_t p_t
+            float pre[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) pre[e] = 1.f;
+            elem* qrow = QA + (kBlock * wave) * L::RS + EPL * lane;
+            elem* krow = KD + (kBlock * wave) * L::RS + EPL * lane;
+#pragma unroll
+            for (int i = 0; i < kBlock; ++i) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) pre[e] *= al[e][i];
+                if constexpr (EPL == 2)
+                    *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
+                else
+                    P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
+            }
+            float invA[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                invA[e] = fast_rcp(pre[e]);
+                EA[wave * DK + EPL * lane + e] = pre[e];
+            }
+            // backward: kb_j = k_j prod_{i>j} alpha_i ; kd_j = kb_j / A
+            float suf[EPL], kb[EPL][kBlock];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) suf[e] = 1.f;
+#pragma unroll
+            for (int i = kBlock - 1; i >= 0; --i) {
+                kb[0][i] = P::lo(st.k[i]) * suf[0];
+                if constexpr (EPL == 2) kb[1][i] = P::hi(st.k[i]) * suf[1];
+                if constexpr (EPL == 2)
+                    *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
+                else
+                    P::store1(krow + i * L::RS, kb[0][i] * invA[0]);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) suf[e] *= al[e][i];
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) store_run<P, kBlock>(KBT + (EPL * lane + e) * L::TS + kBlock * wave, kb[e]);
 
             // values: scale by the write gate, transpose to [column][token]
             {
@@ -390,13 +425,16 @@ __global__ __launch_bounds__(kWaves * 64) void sla_fwd_kernel(const KArgs a) {
 #pragma unroll
                 for (int i = 0; i < NI; ++i) {
                     const float gki = __shfl(gk, tb + i);
-                    c0[i] = P::lo(cur.v[i]) * gki;
-                    c1[i] = P::hi(cur.v[i]) * gki;
+                    c0[i] = P::lo(st.v[i]) * gki;
+                    c1[i] = P::hi(st.v[i]) * gki;
                 }
                 store_run<P, NI>(VT + (2 * p) * L::TS + kBlock * wave + tb, c0);
                 store_run<P, NI>(VT + (2 * p + 1) * L::TS + kBlock * wave + tb, c1);
             }
         }
+        // The staging registers are free again: fetch the next chunk while this one is consumed.
+        // Beyond the last chunk every access is out of range and returns zero without touching memory.
+        ldr.load(st, tok0 + kChunk, lane);
         __syncthreads();
 
         // ------------------------------------------------------------------ consumer
@@ -453,7 +491,6 @@ __global__ __launch_bounds__(kWaves * 64) void sla_fwd_kernel(const KArgs a) {
             }
         }
         __syncthreads();
-        if (c + 1 < nchunks) cur = nxt;
     }
 
     if (a.sT && wave < NCW) {
@@ -477,10 +514,10 @@ __global__ void sla_state_passthrough_kernel(const float* s0, float* sT, size_t 
 // ---------------------------------------------------------------------------------------------
 // Launch
 // ---------------------------------------------------------------------------------------------
-template <class P, int VAR, int DK, int DVW>
+template <class P, int VAR, int DK, int DVW, int HG>
 static int launch(const KArgs& a, hipStream_t stream) {
     typedef Smem<P, DK, DVW> L;
-    auto kern = sla_fwd_kernel<P, VAR, DK, DVW>;
+    auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG>;
     static bool configured = false;  // per instantiation
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::bytes) !=
@@ -495,12 +532,19 @@ static int launch(const KArgs& a, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
+template <class P, int VAR, int DK, int DVW>
+static int dispatch_heads(const KArgs& a, hipStream_t stream) {
+    if (a.H <= 16) return launch<P, VAR, DK, DVW, 4>(a, stream);
+    if (a.H <= 32) return launch<P, VAR, DK, DVW, 8>(a, stream);
+    return launch<P, VAR, DK, DVW, 16>(a, stream);
+}
+
 template <class P, int VAR, int DK>
 static int dispatch_dvw(const KArgs& a, int dvw, hipStream_t stream) {
     switch (dvw) {
-        case 16: return launch<P, VAR, DK, 16>(a, stream);
-        case 32: return launch<P, VAR, DK, 32>(a, stream);
-        case 64: return launch<P, VAR, DK, 64>(a, stream);
+        case 16: return dispatch_heads<P, VAR, DK, 16>(a, stream);
+        case 32: return dispatch_heads<P, VAR, DK, 32>(a, stream);
+        case 64: return dispatch_heads<P, VAR, DK, 64>(a, stream);
         default: return SLA_ERR_UNSUPPORTED;
     }
 }
