@@ -33,6 +33,10 @@
 
 #include "sla.h"
 
+#ifndef SLA_EXP
+#define SLA_EXP 0  // timing experiments only: 1 = no consumer, 2 = no producer math, 3 = no reloads
+#endif
+
 namespace sla {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -64,6 +68,21 @@ struct KArgs {
     int B, T, H, dv;
     int nslice;
 };
+
+#ifdef SLA_TRACE
+// Developer timing builds only: every wave records s_memtime at numbered points of each chunk.
+static constexpr int kTraceRec = 512;
+__device__ unsigned long long* d_trace = nullptr;
+#define SLA_STAMP(idx)                                                                                          \
+    do {                                                                                                        \
+        if (d_trace && (idx) < kTraceRec && (threadIdx.x & 63) == 0)                                            \
+            d_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * kTraceRec + (idx)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
+#else
+#define SLA_STAMP(idx) \
+    do {               \
+    } while (0)
+#endif
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     bf16x2 t;
@@ -145,8 +164,9 @@ struct PrecF32 {
     }
 };
 
-// Store N consecutive elements (N*sizeof(elem) is 4, 8, 16, 32 or 64 bytes; dst aligned to min(16, bytes)).
-template <class P, int N>
+// Store N consecutive elements (N*sizeof(elem) is 4, 8, 16, 32 or 64 bytes; dst aligned to min(16, bytes),
+// or to min(8, bytes) with W8, which limits 2-byte element stores to 8 bytes each).
+template <class P, int N, bool W8 = false>
 __device__ __forceinline__ void store_run(typename P::elem* dst, const float (&x)[N]) {
     if constexpr (sizeof(typename P::elem) == 2) {
         static_assert(N % 2 == 0, "bf16 runs are stored in pairs");
@@ -157,6 +177,9 @@ __device__ __forceinline__ void store_run(typename P::elem* dst, const float (&x
             *(uint32_t*)dst = w[0];
         } else if constexpr (N == 4) {
             *(u32x2*)dst = u32x2{w[0], w[1]};
+        } else if constexpr (W8) {
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i) ((u32x2*)dst)[i] = u32x2{w[2 * i], w[2 * i + 1]};
         } else {
 #pragma unroll
             for (int i = 0; i < N / 8; ++i) ((u32x4*)dst)[i] = u32x4{w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
@@ -181,21 +204,26 @@ struct Smem {
     typedef typename P::elem elem;
     static constexpr int kPad = 16 / sizeof(elem);   // 16 bytes of padding per row
     static constexpr int RS = DK + kPad;             // row stride of the row-major [token][d] arrays
-    static constexpr int TS = kChunk + kPad;         // row stride of the token-major [d or n][token] arrays
+    // Token-major [d or n][token] arrays: a producer lane writes rows 2l and 2l+1, a consumer lane
+    // reads row r.  With 2-byte elements a stride of 136 bytes (34 banks) puts the 16 lanes that
+    // an 8-byte access serves per cycle on 16 distinct bank pairs for both patterns.
+    static constexpr int TS = kChunk + (sizeof(elem) == 2 ? 4 : 4);
     static constexpr size_t oQA = 0;
     static constexpr size_t oKD = oQA + sizeof(elem) * kChunk * RS;
     static constexpr size_t oKBT = oKD + sizeof(elem) * kChunk * RS;
     static constexpr size_t oVT = oKBT + sizeof(elem) * DK * TS;
     static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
     static constexpr size_t oGQ = oEA + sizeof(float) * (kChunk / kBlock) * DK;
-    static constexpr size_t bytes = oGQ + sizeof(float) * kChunk;
+    static constexpr size_t oGK = oGQ + sizeof(float) * kChunk;
+    static constexpr size_t bytes = oGK + sizeof(float) * kChunk;
 };
 
 // ---------------------------------------------------------------------------------------------
-// Per-lane staging registers for one 16-token block (what the producer of a wave works on).
+// Per-lane staging registers for one 16-token block (what a producer wave works on).
 // Lane l owns EPL = DK/64 adjacent key dimensions (d = EPL*l ...) of all 16 tokens of the block,
-// and for V two adjacent value columns of NI = DVW/8 consecutive tokens.  For the gates, lane
-// (r = l%16, g = l/16) holds the logits of token r for heads g, g+4, ... (HG registers per gate).
+// and for V two adjacent value columns of NI = DVW/8 consecutive tokens.  For the gates, lane l
+// holds the logits of token l/4 for heads l%4, l%4 + 4, ... (HG registers per gate), so that the
+// reduction over heads stays inside a quad and runs on DPP.
 // ---------------------------------------------------------------------------------------------
 template <class P, int VAR, int DK, int DVW, int HG>
 struct Stage {
@@ -243,32 +271,36 @@ struct Loader {
         voff_qk = (h * DK + EPL * lane) * (int)sizeof(elem);
         const int p = lane % LPR, tb = (lane / LPR) * NI;
         voff_v = tb * tstride_v + (h * a.dv + n0 + 2 * p) * (int)sizeof(elem);
-        voff_lg = (lane & 15) * tstride_lg + (lane >> 4) * 4;
-        voff_own = (lane & 15) * tstride_lg + h * 4;
+        voff_lg = (lane >> 2) * tstride_lg + (lane & 3) * 4;
+        voff_own = (lane >> 2) * tstride_lg + h * 4;
     }
 
-    // tok0 must be wave-uniform (it is turned into scalar offsets).
-    __device__ __forceinline__ void load(stage_t& st, int tok0, int lane) const {
-        const int s_qk = tok0 * tstride_qk, s_v = tok0 * tstride_v, s_lg = tok0 * tstride_lg;
-#pragma unroll
-        for (int i = 0; i < kBlock; ++i) {
-            if constexpr (EPL == 2) {
-                st.q[i] = P::bload2(rq, voff_qk, s_qk + i * tstride_qk);
-                st.k[i] = P::bload2(rk, voff_qk, s_qk + i * tstride_qk);
-                if constexpr (VAR == SLA_GLA) st.ld[i] = P::bload2(rld, voff_qk, s_qk + i * tstride_qk);
-            } else {
-                st.q[i] = P::bload1(rq, voff_qk, s_qk + i * tstride_qk);
-                st.k[i] = P::bload1(rk, voff_qk, s_qk + i * tstride_qk);
-                if constexpr (VAR == SLA_GLA) st.ld[i] = P::bload1(rld, voff_qk, s_qk + i * tstride_qk);
-            }
+    // Token indices passed to the loads must be wave-uniform (they become scalar offsets).
+    __device__ __forceinline__ void load_q(stage_t& st, int tok0, int i) const {
+        const int so = (tok0 + i) * tstride_qk;
+        st.q[i] = (EPL == 2) ? P::bload2(rq, voff_qk, so) : P::bload1(rq, voff_qk, so);
+    }
+    __device__ __forceinline__ void load_k(stage_t& st, int tok0, int i) const {
+        const int so = (tok0 + i) * tstride_qk;
+        st.k[i] = (EPL == 2) ? P::bload2(rk, voff_qk, so) : P::bload1(rk, voff_qk, so);
+    }
+    __device__ __forceinline__ void load_ld(stage_t& st, int tok0, int i) const {
+        if constexpr (VAR == SLA_GLA) {
+            const int so = (tok0 + i) * tstride_qk;
+            st.ld[i] = (EPL == 2) ? P::bload2(rld, voff_qk, so) : P::bload1(rld, voff_qk, so);
         }
+    }
+    __device__ __forceinline__ void load_v(stage_t& st, int tok0) const {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, s_v + i * tstride_v);
-        const int g = lane >> 4;
+        for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, (tok0 + i) * tstride_v);
+    }
+    __device__ __forceinline__ void load_logits(stage_t& st, int tok0, int lane) const {
+        const int s_lg = tok0 * tstride_lg;
+        const int sub = lane & 3;
 #pragma unroll
         for (int i = 0; i < HG; ++i) {
             // heads beyond H never win the max and add exp(-inf) = 0; tokens beyond T read 0 (equal scores)
-            const bool head_ok = g + 4 * i < H;
+            const bool head_ok = sub + 4 * i < H;
             const float x = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_lg, s_lg + 16 * i, 0));
             const float y = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_lg, s_lg + 16 * i, 0));
             st.ql[i] = head_ok ? x : -INFINITY;
@@ -277,51 +309,257 @@ struct Loader {
         st.ql_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_own, s_lg, 0));
         st.kl_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_own, s_lg, 0));
     }
+    __device__ __forceinline__ void load(stage_t& st, int tok0, int lane) const {
+        load_logits(st, tok0, lane);
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) load_ld(st, tok0, i);
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) load_q(st, tok0, i);
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) load_k(st, tok0, i);
+        load_v(st, tok0);
+    }
 };
 
-// softmax over heads for the token of this lane (Eq. 4); returns the gate of head h.
+// Exchange inside a quad of lanes on DPP: lane ^ 1 and lane ^ 2.
+__device__ __forceinline__ float quad_xor1(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float quad_xor2(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false));
+}
+
+// softmax over heads for the token of this quad (Eq. 4); returns the gate of head h.
 template <int HG>
 __device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
     float m = x[0];
 #pragma unroll
     for (int i = 1; i < HG; ++i) m = fmaxf(m, x[i]);
-    m = fmaxf(m, __shfl_xor(m, 16));
-    m = fmaxf(m, __shfl_xor(m, 32));
+    m = fmaxf(m, quad_xor1(m));
+    m = fmaxf(m, quad_xor2(m));
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < HG; ++i) s += fast_exp2((x[i] - m) * kLog2e);
-    s += __shfl_xor(s, 16);
-    s += __shfl_xor(s, 32);
-    return fast_exp2((own - m) * kLog2e) / s;
+    s += quad_xor1(s);
+    s += quad_xor2(s);
+    return fast_exp2((own - m) * kLog2e) * fast_rcp(s);
 }
 
 // ---------------------------------------------------------------------------------------------
-// The kernel
+// Producer: one 16-token block (index blk of the staged chunk) from registers to LDS.
 // ---------------------------------------------------------------------------------------------
+// Every staging register is reloaded with the same block of the next chunk (token next_tok0 + i) right
+// after its last use, so the loads are spread through the arithmetic instead of queueing up in a burst.
 template <class P, int VAR, int DK, int DVW, int HG>
-__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void sla_fwd_kernel(const KArgs a) {
+__device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
+                                              unsigned char* buf, int blk, int tok0, int next_tok0, int T,
+                                              float decay_const, int lane) {
+    const bool has_kl = ldr.has_kl;
+    [[maybe_unused]] const int trc = tok0 / kChunk;
     typedef typename P::elem elem;
-    typedef typename P::frag frag;
     typedef typename P::pair pair;
     typedef Smem<P, DK, DVW> L;
     constexpr int EPL = DK / 64;
-    constexpr int NTILE = DK / 16;
     constexpr int NI = DVW / 8;
     constexpr int LPR = DVW / 2;
-    constexpr int NCW = DVW / 16;  // consumer waves
+    elem* QA = (elem*)(buf + L::oQA);
+    elem* KD = (elem*)(buf + L::oKD);
+    elem* KBT = (elem*)(buf + L::oKBT);
+    elem* VT = (elem*)(buf + L::oVT);
+    float* EA = (float*)(buf + L::oEA);
+    float* GQ = (float*)(buf + L::oGQ);
+    float* GK = (float*)(buf + L::oGK);
+
+    // gates of the 16 tokens of the block (token lane/4); parked in LDS for the epilogue and for V
+    {
+        const float gq = head_gate<HG>(st.ql, st.ql_own);
+        const float gk = has_kl ? head_gate<HG>(st.kl, st.kl_own) : 1.f;
+        if ((lane & 3) == 0) {
+            GQ[kBlock * blk + (lane >> 2)] = gq;
+            GK[kBlock * blk + (lane >> 2)] = gk;
+        }
+        ldr.load_logits(st, next_tok0, lane);
+    }
+
+    SLA_STAMP(8 * trc + 1);
+    // per-token decay factors of the owned key dimensions
+    float al[EPL][kBlock];
+#pragma unroll
+    for (int i = 0; i < kBlock; ++i) {
+        if constexpr (VAR == SLA_GLA) {
+            al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
+            if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
+            ldr.load_ld(st, next_tok0, i);
+        } else {
+            const float x = (tok0 + i < T) ? decay_const : 1.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) al[e][i] = x;
+        }
+    }
+    SLA_STAMP(8 * trc + 2);
+    // forward: p_t = prod_{i<=t} alpha_i ; qa_t = q_t p_t
+    float pre[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) pre[e] = 1.f;
+    elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
+    elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
+#pragma unroll
+    for (int i = 0; i < kBlock; ++i) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) pre[e] *= al[e][i];
+        if constexpr (EPL == 2)
+            *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
+        else
+            P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
+        ldr.load_q(st, next_tok0, i);
+    }
+    float invA[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        invA[e] = fast_rcp(pre[e]);
+        EA[blk * DK + EPL * lane + e] = pre[e];
+    }
+    SLA_STAMP(8 * trc + 3);
+    // backward: kb_j = k_j prod_{i>j} alpha_i ; kd_j = kb_j / A
+    float suf[EPL], kb[EPL][kBlock];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) suf[e] = 1.f;
+#pragma unroll
+    for (int i = kBlock - 1; i >= 0; --i) {
+        kb[0][i] = P::lo(st.k[i]) * suf[0];
+        if constexpr (EPL == 2) kb[1][i] = P::hi(st.k[i]) * suf[1];
+        ldr.load_k(st, next_tok0, i);
+        if constexpr (EPL == 2)
+            *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
+        else
+            P::store1(krow + i * L::RS, kb[0][i] * invA[0]);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) suf[e] *= al[e][i];
+    }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) store_run<P, kBlock, true>(KBT + (EPL * lane + e) * L::TS + kBlock * blk, kb[e]);
+
+    SLA_STAMP(8 * trc + 4);
+    // values: scale by the write gate, transpose to [column][token].  The gates were written by this
+    // same wave a few instructions ago; LDS operations of one wave execute in order.
+    {
+        const int p = lane % LPR, tb = (lane / LPR) * NI;
+        __builtin_amdgcn_wave_barrier();
+        float gkv[NI];
+        if constexpr (NI >= 4) {
+#pragma unroll
+            for (int i = 0; i < NI / 4; ++i) {
+                const f32x4 t = *(const f32x4*)(GK + kBlock * blk + tb + 4 * i);
+                gkv[4 * i] = t[0]; gkv[4 * i + 1] = t[1]; gkv[4 * i + 2] = t[2]; gkv[4 * i + 3] = t[3];
+            }
+        } else {
+            const f32x2 t = *(const f32x2*)(GK + kBlock * blk + tb);
+            gkv[0] = t[0]; gkv[1] = t[1];
+        }
+        float c0[NI], c1[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            c0[i] = P::lo(st.v[i]) * gkv[i];
+            c1[i] = P::hi(st.v[i]) * gkv[i];
+        }
+        ldr.load_v(st, next_tok0);
+        store_run<P, NI, true>(VT + (2 * p) * L::TS + kBlock * blk + tb, c0);
+        store_run<P, NI, true>(VT + (2 * p + 1) * L::TS + kBlock * blk + tb, c1);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Consumer: the four 16-token blocks of one staged chunk for the 16 value columns of wave cw.
+// ---------------------------------------------------------------------------------------------
+template <class P, int DK, int DVW>
+__device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigned char* buf, int cw, int chunk_tok0,
+                                              int T, typename P::elem* out_row, size_t out_tstride, int lane) {
+    typedef typename P::elem elem;
+    typedef typename P::frag frag;
+    typedef Smem<P, DK, DVW> L;
+    constexpr int NTILE = DK / 16;
+    const elem* QA = (const elem*)(buf + L::oQA);
+    const elem* KD = (const elem*)(buf + L::oKD);
+    const elem* KBT = (const elem*)(buf + L::oKBT);
+    const elem* VT = (const elem*)(buf + L::oVT);
+    const float* EA = (const float*)(buf + L::oEA);
+    const float* GQ = (const float*)(buf + L::oGQ);
+    const int r = lane & 15, g = lane >> 4;
+    [[maybe_unused]] const int trc = chunk_tok0 / kChunk;
+#pragma unroll 1
+    for (int I = 0; I < kChunk / kBlock; ++I) {
+        SLA_STAMP(8 * trc + 1 + I);
+        const int trow = kBlock * I + r;
+        // fragments of qa (rows = tokens of the block) and kd
+        frag fq[NTILE];
+        f32x4 pT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NTILE; s += 2) {
+            fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
+            fq[s + 1] = *(const frag*)(QA + trow * L::RS + 16 * (s + 1) + 4 * g);
+            const frag k0 = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
+            const frag k1 = *(const frag*)(KD + trow * L::RS + 16 * (s + 1) + 4 * g);
+            P::mma32(pT, k0, k1, fq[s], fq[s + 1]);  // P^T[j][t] += kd[j][d] qa[t][d]
+        }
+        // causal mask: lane holds column t = r, rows j = 4g + i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] : 0.f;
+        const frag fp = P::from_acc(pT);
+        const frag fv = *(const frag*)(VT + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
+
+        // O^T[n][t] = sum_d S[d][n] qa[t][d] + sum_j v'[j][n] P[t][j]
+        f32x4 oT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NTILE; s += 2) P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), fq[s], fq[s + 1]);
+        P::mma16(oT, fv, fp);
+
+        // epilogue: read gate, cast, store 4 adjacent value columns of token t
+        {
+            const int t = chunk_tok0 + trow;
+            const float gq = GQ[trow];
+            float o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = oT[i] * gq;
+            if (t < T) store_run<P, 4>(out_row + (size_t)t * out_tstride, o);
+        }
+
+        // state step: S <- diag(A_I) S + kb^T v'
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s) {
+            const f32x4 ea = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
+            const frag fk = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[s][i] *= ea[i];
+            P::mma16(S[s], fk, fv);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The kernel: waves 0..3 consume (wave w owns value columns 16w..16w+15 of the slice and the state
+// rows x those columns), waves 4..7 produce (wave 4+p stages block p of every chunk).  With two LDS
+// buffers the producers work one chunk ahead of the consumers and one barrier per chunk separates
+// them; where two buffers do not fit in LDS the phases alternate on one buffer.
+// ---------------------------------------------------------------------------------------------
+static constexpr int kThreads = 2 * kWaves * 64;
+static constexpr size_t kLdsLimit = 160 * 1024;
+
+template <class P, int VAR, int DK, int DVW, int HG>
+__global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
+    typedef typename P::elem elem;
+    typedef Smem<P, DK, DVW> L;
+    constexpr int NTILE = DK / 16;
+    constexpr int NCW = DVW / 16;  // consumer waves that have columns
+    constexpr int NBUF = (2 * L::bytes <= kLdsLimit) ? 2 : 1;
     static_assert(DK == 64 || DK == 128, "dk");
     static_assert(DVW == 16 || DVW == 32 || DVW == 64, "value columns per workgroup");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    elem* QA = (elem*)(smem + L::oQA);
-    elem* KD = (elem*)(smem + L::oKD);
-    elem* KBT = (elem*)(smem + L::oKBT);
-    elem* VT = (elem*)(smem + L::oVT);
-    float* EA = (float*)(smem + L::oEA);
-    float* GQ = (float*)(smem + L::oGQ);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool producer = wave >= kWaves;
+    const int pw = wave - kWaves;  // producer index = block of the chunk
     const int r = lane & 15, g = lane >> 4;
 
     // Workgroup -> (batch, head, value slice).  Consecutive hardware ids go to different XCDs
@@ -334,174 +572,100 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const int b = bh / a.H, h = bh % a.H;
     const int n0 = slice * DVW;
     const int T = a.T, H = a.H, dv = a.dv;
-
-    // State slice: tile s holds S[16s + 4g + i][n0 + 16*wave + r] in acc[s][i].
-    f32x4 S[NTILE];
-    if (wave < NCW) {
-#pragma unroll
-        for (int s = 0; s < NTILE; ++s) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const size_t off = ((size_t)bh * DK + 16 * s + 4 * g + i) * dv + n0 + 16 * wave + r;
-                S[s][i] = a.s0 ? a.s0[off] : 0.f;
-            }
-        }
-    }
-
-    float decay_const = 1.f;  // RetNet: gamma_h
-    if constexpr (VAR == SLA_RETNET) decay_const = fast_exp2(((const float*)a.ld)[h] * kLog2e);
-
     const int nchunks = (T + kChunk - 1) / kChunk;
-    Loader<P, VAR, DK, DVW, HG> ldr;
-    ldr.init(a, b, h, n0, lane);
-    Stage<P, VAR, DK, DVW, HG> st;
-    ldr.load(st, kBlock * wave, lane);
 
-    for (int c = 0; c < nchunks; ++c) {
-        const int tok0 = c * kChunk + kBlock * wave;  // first token of this wave's block
-
-        // ------------------------------------------------------------------ producer
-        {
-            const float gq = head_gate<HG>(st.ql, st.ql_own);
-            const float gk = ldr.has_kl ? head_gate<HG>(st.kl, st.kl_own) : 1.f;
-            if (g == 0) GQ[kBlock * wave + r] = gq;
-
-            // per-token decay factors of the owned key dimensions
-            float al[EPL][kBlock];
-#pragma unroll
-            for (int i = 0; i < kBlock; ++i) {
-                if constexpr (VAR == SLA_GLA) {
-                    al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
-                    if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
-                } else {
-                    const float x = (tok0 + i < T) ? decay_const : 1.f;
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) al[e][i] = x;
-                }
+    if (producer) {
+        float decay_const = 1.f;  // RetNet: gamma_h
+        if constexpr (VAR == SLA_RETNET) decay_const = fast_exp2(((const float*)a.ld)[h] * kLog2e);
+        Loader<P, VAR, DK, DVW, HG> ldr;
+        ldr.init(a, b, h, n0, lane);
+        // One register stage, refilled while it is consumed: the loads of a chunk are in flight for a
+        // whole chunk period.  Past the end of the sequence every load is out of range: it returns
+        // zero without touching memory, and nothing staged from it is ever read.
+        Stage<P, VAR, DK, DVW, HG> st;
+        ldr.load(st, kBlock * pw, lane);
+        auto stage_chunk = [&](int cc) {
+            if (cc < nchunks) {
+                const int tok0 = cc * kChunk + kBlock * pw;
+#if SLA_EXP != 2
+                produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, pw, tok0,
+                                                   tok0 + kChunk, T, decay_const, lane);
+#endif
             }
-            // forward: p_t = prod_{i<=t} alpha_i ; qa_t = q_t p_t
-            float pre[EPL];
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) pre[e] = 1.f;
-            elem* qrow = QA + (kBlock * wave) * L::RS + EPL * lane;
-            elem* krow = KD + (kBlock * wave) * L::RS + EPL * lane;
-#pragma unroll
-            for (int i = 0; i < kBlock; ++i) {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) pre[e] *= al[e][i];
-                if constexpr (EPL == 2)
-                    *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
-                else
-                    P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
+        };
+        if constexpr (NBUF == 2) {
+            stage_chunk(0);
+            __syncthreads();
+            for (int c = 0; c < nchunks; c += 2) {  // consumers work on chunks c and c+1 meanwhile
+                stage_chunk(c + 1);
+                __syncthreads();
+                stage_chunk(c + 2);
+                __syncthreads();
             }
-            float invA[EPL];
+        } else {
+            // one LDS buffer (fp32 operands with dk = 128): the two phases alternate
+            for (int c = 0; c < nchunks; c += 2) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                invA[e] = fast_rcp(pre[e]);
-                EA[wave * DK + EPL * lane + e] = pre[e];
-            }
-            // backward: kb_j = k_j prod_{i>j} alpha_i ; kd_j = kb_j / A
-            float suf[EPL], kb[EPL][kBlock];
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) suf[e] = 1.f;
-#pragma unroll
-            for (int i = kBlock - 1; i >= 0; --i) {
-                kb[0][i] = P::lo(st.k[i]) * suf[0];
-                if constexpr (EPL == 2) kb[1][i] = P::hi(st.k[i]) * suf[1];
-                if constexpr (EPL == 2)
-                    *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
-                else
-                    P::store1(krow + i * L::RS, kb[0][i] * invA[0]);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) suf[e] *= al[e][i];
-            }
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) store_run<P, kBlock>(KBT + (EPL * lane + e) * L::TS + kBlock * wave, kb[e]);
-
-            // values: scale by the write gate, transpose to [column][token]
-            {
-                const int p = lane % LPR, tb = (lane / LPR) * NI;
-                float c0[NI], c1[NI];
-#pragma unroll
-                for (int i = 0; i < NI; ++i) {
-                    const float gki = __shfl(gk, tb + i);
-                    c0[i] = P::lo(st.v[i]) * gki;
-                    c1[i] = P::hi(st.v[i]) * gki;
-                }
-                store_run<P, NI>(VT + (2 * p) * L::TS + kBlock * wave + tb, c0);
-                store_run<P, NI>(VT + (2 * p + 1) * L::TS + kBlock * wave + tb, c1);
-            }
-        }
-        // The staging registers are free again: fetch the next chunk while this one is consumed.
-        // Beyond the last chunk every access is out of range and returns zero without touching memory.
-        ldr.load(st, tok0 + kChunk, lane);
-        __syncthreads();
-
-        // ------------------------------------------------------------------ consumer
-        if (wave < NCW) {
-#pragma unroll 1
-            for (int I = 0; I < kChunk / kBlock; ++I) {
-                const int trow = kBlock * I + r;
-                // fragments of qa (rows = tokens of the block) and kd
-                frag fq[NTILE];
-                f32x4 pT = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < NTILE; s += 2) {
-                    fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
-                    fq[s + 1] = *(const frag*)(QA + trow * L::RS + 16 * (s + 1) + 4 * g);
-                    const frag k0 = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
-                    const frag k1 = *(const frag*)(KD + trow * L::RS + 16 * (s + 1) + 4 * g);
-                    P::mma32(pT, k0, k1, fq[s], fq[s + 1]);  // P^T[j][t] += kd[j][d] qa[t][d]
-                }
-                // causal mask: lane holds column t = r, rows j = 4g + i
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] : 0.f;
-                const frag fp = P::from_acc(pT);
-                const frag fv = *(const frag*)(VT + (16 * wave + r) * L::TS + kBlock * I + 4 * g);
-
-                // O^T[n][t] = sum_d S[d][n] qa[t][d] + sum_j v'[j][n] P[t][j]
-                f32x4 oT = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < NTILE; s += 2)
-                    P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), fq[s], fq[s + 1]);
-                P::mma16(oT, fv, fp);
-
-                // epilogue: read gate, cast, store 4 adjacent value columns of token t
-                {
-                    const int t = c * kChunk + trow;
-                    const float gq = GQ[trow];
-                    float o[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) o[i] = oT[i] * gq;
-                    if (t < T) {
-                        elem* op = (elem*)a.out + (((size_t)b * T + t) * H + h) * dv + n0 + 16 * wave + 4 * g;
-                        store_run<P, 4>(op, o);
-                    }
-                }
-
-                // state step: S <- diag(A_I) S + kb^T v'
-#pragma unroll
-                for (int s = 0; s < NTILE; ++s) {
-                    const f32x4 ea = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
-                    const frag fk = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) S[s][i] *= ea[i];
-                    P::mma16(S[s], fk, fv);
+                for (int u = 0; u < 2; ++u) {
+                    stage_chunk(c + u);
+                    __syncthreads();
+                    __syncthreads();
                 }
             }
         }
-        __syncthreads();
+        return;
     }
 
-    if (a.sT && wave < NCW) {
+    // ---------------------------------------------------------------- consumer waves
+    const int cw = wave;
+    const bool active = cw < NCW;
+    // State slice: tile s holds S[16s + 4g + i][n0 + 16*cw + r] in S[s][i].
+    f32x4 S[NTILE];
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) {
+    for (int s = 0; s < NTILE; ++s) S[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const size_t s_off = ((size_t)bh * DK + 4 * g) * dv + n0 + 16 * cw + r;
+    if (active && a.s0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const size_t off = ((size_t)bh * DK + 16 * s + 4 * g + i) * dv + n0 + 16 * wave + r;
-                a.sT[off] = S[s][i];
+        for (int s = 0; s < NTILE; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[s][i] = a.s0[s_off + (size_t)(16 * s + i) * dv];
+    }
+    elem* out_row = (elem*)a.out + ((size_t)b * T * H + h) * dv + n0 + 16 * cw + 4 * g;
+    const size_t out_tstride = (size_t)H * dv;
+
+    // Barrier count per pair of chunks matches the producers' (two steps per pair, also for an odd tail).
+    if constexpr (NBUF == 2) {
+        __syncthreads();
+        for (int c = 0; c < nchunks; c += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                SLA_STAMP(8 * (c + u));
+#if SLA_EXP != 1
+                if (active && c + u < nchunks)
+                    consume_chunk<P, DK, DVW>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
+#endif
+                SLA_STAMP(8 * (c + u) + 6);
+                __syncthreads();
+                SLA_STAMP(8 * (c + u) + 7);
             }
         }
+    } else {
+        for (int c = 0; c < nchunks; c += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                __syncthreads();
+                if (active && c + u < nchunks)
+                    consume_chunk<P, DK, DVW>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
+                __syncthreads();
+            }
+        }
+    }
+
+    if (active && a.sT) {
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a.sT[s_off + (size_t)(16 * s + i) * dv] = S[s][i];
     }
 }
 
@@ -518,17 +682,17 @@ template <class P, int VAR, int DK, int DVW, int HG>
 static int launch(const KArgs& a, hipStream_t stream) {
     typedef Smem<P, DK, DVW> L;
     auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG>;
+    const size_t lds = (2 * L::bytes <= kLdsLimit) ? 2 * L::bytes : L::bytes;
     static bool configured = false;  // per instantiation
     if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::bytes) !=
-            hipSuccess) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return SLA_ERR_HIP;
         }
         configured = true;
     }
     const int grid = a.B * a.H * a.nslice;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), L::bytes, stream, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
