@@ -25,5 +25,5 @@ from .binding import (  # noqa: F401
 )
 
 # Variants with kernels in this build (sla_forward returns SLA_ERR_UNSUPPORTED for the others).
-SUPPORTED_VARIANTS = (RETNET, GLA)
+SUPPORTED_VARIANTS = (RETNET, GLA, GDN)
 

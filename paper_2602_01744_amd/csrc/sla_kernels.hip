@@ -121,6 +121,10 @@ struct PrecBF16 {
         t.y = pack_bf16(c[2], c[3]);
         return __builtin_bit_cast(frag, t);
     }
+    static __device__ __forceinline__ f32x4 to_acc(frag f) {
+        const u32x2 t = __builtin_bit_cast(u32x2, f);
+        return f32x4{bf16_lo(t.x), bf16_hi(t.x), bf16_lo(t.y), bf16_hi(t.y)};
+    }
     static __device__ __forceinline__ void mma32(f32x4& c, frag a0, frag a1, frag b0, frag b1) {
         i16x8 a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
         i16x8 b = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -154,6 +158,7 @@ struct PrecF32 {
     static __device__ __forceinline__ float lo1(pair p) { return p.x; }
     static __device__ __forceinline__ void store1(elem* p, float a) { *p = a; }
     static __device__ __forceinline__ frag from_acc(f32x4 c) { return c; }
+    static __device__ __forceinline__ f32x4 to_acc(frag f) { return f; }
     static __device__ __forceinline__ void mma16(f32x4& c, frag a, frag b) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[i], c, 0, 0, 0);
@@ -215,7 +220,22 @@ struct Smem {
     static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
     static constexpr size_t oGQ = oEA + sizeof(float) * (kChunk / kBlock) * DK;
     static constexpr size_t oGK = oGQ + sizeof(float) * kChunk;
-    static constexpr size_t bytes = oGK + sizeof(float) * kChunk;
+    // delta rule only (kept in every layout; 5 KB): per block the inverse Tm = (I + L)^-1 [16][16],
+    // per token p_t, beta_t p_t and beta_t
+    static constexpr size_t oTM = oGK + sizeof(float) * kChunk;
+    static constexpr size_t oP1 = oTM + sizeof(float) * (kChunk / kBlock) * kBlock * kBlock;
+    static constexpr size_t oBP = oP1 + sizeof(float) * kChunk;
+    static constexpr size_t oBT = oBP + sizeof(float) * kChunk;
+    static constexpr size_t bytes = oBT + sizeof(float) * kChunk;
+    // delta rule only, outside the double buffer: k_t p_t of the block a producer wave is working on
+    static constexpr size_t gdn_private = sizeof(elem) * kChunk * RS;
+    static constexpr size_t limit = 160 * 1024;
+    static constexpr int nbuf(int variant) {
+        return 2 * bytes + (variant == SLA_GDN ? gdn_private : 0) <= limit ? 2 : 1;
+    }
+    static constexpr size_t total(int variant) {
+        return nbuf(variant) * bytes + (variant == SLA_GDN ? gdn_private : 0);
+    }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -234,6 +254,7 @@ struct Stage {
     pair v[NI];
     float ql[HG], kl[HG];
     float ql_own, kl_own;
+    float sc_ld, sc_beta;  // delta rule: scalar log-decay and beta of token lane%16
 };
 
 // Buffer descriptors of one batch row and the per-lane byte offsets into them.  A descriptor spans
@@ -245,8 +266,8 @@ struct Loader {
     static constexpr int EPL = DK / 64;
     static constexpr int NI = DVW / 8;
     static constexpr int LPR = DVW / 2;
-    __amdgpu_buffer_rsrc_t rq, rk, rv, rld, rql, rkl;
-    int voff_qk, voff_v, voff_lg, voff_own;
+    __amdgpu_buffer_rsrc_t rq, rk, rv, rld, rql, rkl, rbt;
+    int voff_qk, voff_v, voff_lg, voff_own, voff_sc;
     int tstride_qk, tstride_v, tstride_lg;  // bytes per token
     int H;
     bool has_kl;
@@ -273,6 +294,11 @@ struct Loader {
         voff_v = tb * tstride_v + (h * a.dv + n0 + 2 * p) * (int)sizeof(elem);
         voff_lg = (lane >> 2) * tstride_lg + (lane & 3) * 4;
         voff_own = (lane >> 2) * tstride_lg + h * 4;
+        if constexpr (VAR == SLA_GDN) {
+            rld = __builtin_amdgcn_make_buffer_rsrc((void*)((const float*)a.ld + row_lg), 0, T * tstride_lg, kRsrcWord3);
+            rbt = __builtin_amdgcn_make_buffer_rsrc((void*)(a.beta + row_lg), 0, T * tstride_lg, kRsrcWord3);
+            voff_sc = (lane & 15) * tstride_lg + h * 4;
+        }
     }
 
     // Token indices passed to the loads must be wave-uniform (they become scalar offsets).
@@ -309,8 +335,16 @@ struct Loader {
         st.ql_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_own, s_lg, 0));
         st.kl_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_own, s_lg, 0));
     }
+    // delta rule: tokens beyond T read log-decay 0 (factor 1) and beta 0 (no write)
+    __device__ __forceinline__ void load_scalars(stage_t& st, int tok0) const {
+        if constexpr (VAR == SLA_GDN) {
+            st.sc_ld = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rld, voff_sc, tok0 * tstride_lg, 0));
+            st.sc_beta = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rbt, voff_sc, tok0 * tstride_lg, 0));
+        }
+    }
     __device__ __forceinline__ void load(stage_t& st, int tok0, int lane) const {
         load_logits(st, tok0, lane);
+        load_scalars(st, tok0);
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) load_ld(st, tok0, i);
 #pragma unroll
@@ -352,8 +386,8 @@ __device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
 // after its last use, so the loads are spread through the arithmetic instead of queueing up in a burst.
 template <class P, int VAR, int DK, int DVW, int HG>
 __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
-                                              unsigned char* buf, int blk, int tok0, int next_tok0, int T,
-                                              float decay_const, int lane) {
+                                              unsigned char* buf, typename P::elem* kp_scratch, int blk, int tok0,
+                                              int next_tok0, int T, float decay_const, int lane) {
     const bool has_kl = ldr.has_kl;
     [[maybe_unused]] const int trc = tok0 / kChunk;
     typedef typename P::elem elem;
@@ -369,6 +403,24 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     float* EA = (float*)(buf + L::oEA);
     float* GQ = (float*)(buf + L::oGQ);
     float* GK = (float*)(buf + L::oGK);
+    [[maybe_unused]] float* TM = (float*)(buf + L::oTM) + blk * kBlock * kBlock;
+    [[maybe_unused]] float* P1 = (float*)(buf + L::oP1) + blk * kBlock;
+    [[maybe_unused]] float* BP = (float*)(buf + L::oBP) + blk * kBlock;
+    [[maybe_unused]] float* BT = (float*)(buf + L::oBT) + blk * kBlock;
+    [[maybe_unused]] const int r = lane & 15, g = lane >> 4;
+
+    // delta rule: per-token scalars of the block as wave-uniform values
+    [[maybe_unused]] float a_u[kBlock], bt_u[kBlock];
+    if constexpr (VAR == SLA_GDN) {
+        const float a_lane = fast_exp2(st.sc_ld * kLog2e);
+        if (lane < kBlock) BT[lane] = st.sc_beta;
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) {
+            a_u[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a_lane), i));
+            bt_u[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.sc_beta), i));
+        }
+        ldr.load_scalars(st, next_tok0);
+    }
 
     // gates of the 16 tokens of the block (token lane/4); parked in LDS for the epilogue and for V
     {
@@ -390,6 +442,9 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
             al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
             if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
             ldr.load_ld(st, next_tok0, i);
+        } else if constexpr (VAR == SLA_GDN) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) al[e][i] = a_u[i];
         } else {
             const float x = (tok0 + i < T) ? decay_const : 1.f;
 #pragma unroll
@@ -403,6 +458,8 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     for (int e = 0; e < EPL; ++e) pre[e] = 1.f;
     elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
     elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
+    [[maybe_unused]] elem* kprow = kp_scratch + EPL * lane;  // delta rule: k_t p_t, private to this wave
+    [[maybe_unused]] float p_u[kBlock];
 #pragma unroll
     for (int i = 0; i < kBlock; ++i) {
 #pragma unroll
@@ -411,7 +468,24 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
             *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
         else
             P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
+        if constexpr (VAR == SLA_GDN) {
+            p_u[i] = pre[0];
+            if constexpr (EPL == 2)
+                *(pair*)(kprow + i * L::RS) = P::make(P::lo(st.k[i]) * pre[0], P::hi(st.k[i]) * pre[1]);
+            else
+                P::store1(kprow + i * L::RS, P::lo(st.k[i]) * pre[0]);
+        }
         ldr.load_q(st, next_tok0, i);
+    }
+    if constexpr (VAR == SLA_GDN) {
+        if (lane == 0) {
+#pragma unroll
+            for (int i = 0; i < kBlock; i += 4) {
+                *(f32x4*)(P1 + i) = f32x4{p_u[i], p_u[i + 1], p_u[i + 2], p_u[i + 3]};
+                *(f32x4*)(BP + i) = f32x4{bt_u[i] * p_u[i], bt_u[i + 1] * p_u[i + 1], bt_u[i + 2] * p_u[i + 2],
+                                          bt_u[i + 3] * p_u[i + 3]};
+            }
+        }
     }
     float invA[EPL];
 #pragma unroll
@@ -456,6 +530,18 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
             const f32x2 t = *(const f32x2*)(GK + kBlock * blk + tb);
             gkv[0] = t[0]; gkv[1] = t[1];
         }
+        if constexpr (VAR == SLA_GDN) {  // v' = beta G^K v
+            if constexpr (NI >= 4) {
+#pragma unroll
+                for (int i = 0; i < NI / 4; ++i) {
+                    const f32x4 t = *(const f32x4*)(BT + tb + 4 * i);
+                    gkv[4 * i] *= t[0]; gkv[4 * i + 1] *= t[1]; gkv[4 * i + 2] *= t[2]; gkv[4 * i + 3] *= t[3];
+                }
+            } else {
+                const f32x2 t = *(const f32x2*)(BT + tb);
+                gkv[0] *= t[0]; gkv[1] *= t[1];
+            }
+        }
         float c0[NI], c1[NI];
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -466,12 +552,52 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         store_run<P, NI, true>(VT + (2 * p) * L::TS + kBlock * blk + tb, c0);
         store_run<P, NI, true>(VT + (2 * p + 1) * L::TS + kBlock * blk + tb, c1);
     }
+
+    // delta rule: Tm = (I + L)^-1 with L[j][t] = beta_j (k_j p_j).(k_t / p_t) for t < j (strictly lower).
+    if constexpr (VAR == SLA_GDN) {
+        typedef typename P::frag frag;
+        constexpr int NTILE = DK / 16;
+        __builtin_amdgcn_wave_barrier();  // this wave's kp and kd rows are in LDS (its LDS operations are in order)
+        f32x4 G = {0.f, 0.f, 0.f, 0.f};   // G[j][t]: lane holds column t = r, rows j = 4g + i
+#pragma unroll
+        for (int s = 0; s < NTILE; s += 2) {
+            const frag a0 = *(const frag*)(kp_scratch + r * L::RS + 16 * s + 4 * g);
+            const frag a1 = *(const frag*)(kp_scratch + r * L::RS + 16 * (s + 1) + 4 * g);
+            const frag b0 = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
+            const frag b1 = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
+            P::mma32(G, a0, a1, b0, b1);
+        }
+        const f32x4 btj = *(const f32x4*)(BT + 4 * g);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) TM[(4 * g + i) * kBlock + r] = (4 * g + i > r) ? btj[i] * G[i] : 0.f;
+        __builtin_amdgcn_wave_barrier();
+        // forward substitution, column c = r of the inverse in every lane (the four lane groups repeat it):
+        // x_j = [j == c] - sum_{i<j} L[j][i] x_i
+        float x[kBlock];
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) {
+            float acc = (j == r) ? 1.f : 0.f;
+#pragma unroll
+            for (int i4 = 0; i4 < j; i4 += 4) {
+                const f32x4 lrow = *(const f32x4*)(TM + j * kBlock + i4);  // same address in all lanes
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (i4 + i < j) acc -= lrow[i] * x[i4 + i];
+            }
+            x[j] = acc;
+        }
+        __builtin_amdgcn_wave_barrier();  // every lane has read L before it is overwritten
+        if (g == 0) {
+#pragma unroll
+            for (int j = 0; j < kBlock; ++j) TM[j * kBlock + r] = x[j];
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Consumer: the four 16-token blocks of one staged chunk for the 16 value columns of wave cw.
 // ---------------------------------------------------------------------------------------------
-template <class P, int DK, int DVW>
+template <class P, int VAR, int DK, int DVW>
 __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigned char* buf, int cw, int chunk_tok0,
                                               int T, typename P::elem* out_row, size_t out_tstride, int lane) {
     typedef typename P::elem elem;
@@ -492,6 +618,7 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
         const int trow = kBlock * I + r;
         // fragments of qa (rows = tokens of the block) and kd
         frag fq[NTILE];
+        [[maybe_unused]] frag fkd[VAR == SLA_GDN ? NTILE : 2];
         f32x4 pT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NTILE; s += 2) {
@@ -499,13 +626,40 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
             fq[s + 1] = *(const frag*)(QA + trow * L::RS + 16 * (s + 1) + 4 * g);
             const frag k0 = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
             const frag k1 = *(const frag*)(KD + trow * L::RS + 16 * (s + 1) + 4 * g);
+            if constexpr (VAR == SLA_GDN) {
+                fkd[s] = k0;
+                fkd[s + 1] = k1;
+            }
             P::mma32(pT, k0, k1, fq[s], fq[s + 1]);  // P^T[j][t] += kd[j][d] qa[t][d]
         }
         // causal mask: lane holds column t = r, rows j = 4g + i
 #pragma unroll
         for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] : 0.f;
         const frag fp = P::from_acc(pT);
-        const frag fv = *(const frag*)(VT + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
+        frag fv = *(const frag*)(VT + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
+
+        if constexpr (VAR == SLA_GDN) {
+            // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
+            //   (I + L) U = beta G^K V - diag(beta p) K S,   K S = p (kd S)   =>   U = Tm R.
+            // U then takes the place of v' in the read-out and in the state step.
+            const float* TM = (const float*)(buf + L::oTM) + I * kBlock * kBlock;
+            const float* P1 = (const float*)(buf + L::oP1) + I * kBlock;
+            const float* BP = (const float*)(buf + L::oBP) + I * kBlock;
+            f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = kd_j S : lane holds column n = r, rows j = 4g + i
+#pragma unroll
+            for (int s = 0; s < NTILE; s += 2)
+                P::mma32(X, fkd[s], fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
+            const f32x4 p1 = *(const f32x4*)(P1 + 4 * g);
+            const f32x4 bp = *(const f32x4*)(BP + 4 * g);
+            const f32x4 vb = P::to_acc(fv);
+            f32x4 R;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) R[i] = vb[i] - bp[i] * (p1[i] * X[i]);
+            const frag ftm = P::from_acc(*(const f32x4*)(TM + r * kBlock + 4 * g));  // Tm[t = r][j = 4g + i]
+            f32x4 U = {0.f, 0.f, 0.f, 0.f};
+            P::mma16(U, ftm, P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
+            fv = P::from_acc(U);
+        }
 
         // O^T[n][t] = sum_d S[d][n] qa[t][d] + sum_j v'[j][n] P[t][j]
         f32x4 oT = {0.f, 0.f, 0.f, 0.f};
@@ -526,7 +680,9 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
         // state step: S <- diag(A_I) S + kb^T v'
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) {
-            const f32x4 ea = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
+            // the decay of a block is one number for RetNet and the delta rule, a vector over d for GLA
+            const f32x4 ea = (VAR == SLA_GLA) ? *(const f32x4*)(EA + I * DK + 16 * s + 4 * g)
+                                              : f32x4{EA[I * DK], EA[I * DK], EA[I * DK], EA[I * DK]};
             const frag fk = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
 #pragma unroll
             for (int i = 0; i < 4; ++i) S[s][i] *= ea[i];
@@ -542,7 +698,6 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
 // them; where two buffers do not fit in LDS the phases alternate on one buffer.
 // ---------------------------------------------------------------------------------------------
 static constexpr int kThreads = 2 * kWaves * 64;
-static constexpr size_t kLdsLimit = 160 * 1024;
 
 template <class P, int VAR, int DK, int DVW, int HG>
 __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
@@ -550,7 +705,7 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     typedef Smem<P, DK, DVW> L;
     constexpr int NTILE = DK / 16;
     constexpr int NCW = DVW / 16;  // consumer waves that have columns
-    constexpr int NBUF = (2 * L::bytes <= kLdsLimit) ? 2 : 1;
+    constexpr int NBUF = L::nbuf(VAR);
     static_assert(DK == 64 || DK == 128, "dk");
     static_assert(DVW == 16 || DVW == 32 || DVW == 64, "value columns per workgroup");
 
@@ -588,8 +743,9 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             if (cc < nchunks) {
                 const int tok0 = cc * kChunk + kBlock * pw;
 #if SLA_EXP != 2
-                produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, pw, tok0,
-                                                   tok0 + kChunk, T, decay_const, lane);
+                elem* kp_scratch = (elem*)(smem + NBUF * L::bytes) + kBlock * pw * L::RS;  // delta rule only
+                produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, kp_scratch, pw,
+                                                   tok0, tok0 + kChunk, T, decay_const, lane);
 #endif
             }
         };
@@ -642,7 +798,7 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
                 SLA_STAMP(8 * (c + u));
 #if SLA_EXP != 1
                 if (active && c + u < nchunks)
-                    consume_chunk<P, DK, DVW>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
+                    consume_chunk<P, VAR, DK, DVW>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
 #endif
                 SLA_STAMP(8 * (c + u) + 6);
                 __syncthreads();
@@ -655,7 +811,7 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             for (int u = 0; u < 2; ++u) {
                 __syncthreads();
                 if (active && c + u < nchunks)
-                    consume_chunk<P, DK, DVW>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
+                    consume_chunk<P, VAR, DK, DVW>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
                 __syncthreads();
             }
         }
@@ -682,7 +838,7 @@ template <class P, int VAR, int DK, int DVW, int HG>
 static int launch(const KArgs& a, hipStream_t stream) {
     typedef Smem<P, DK, DVW> L;
     auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG>;
-    const size_t lds = (2 * L::bytes <= kLdsLimit) ? 2 * L::bytes : L::bytes;
+    const size_t lds = L::total(VAR);
     static bool configured = false;  // per instantiation
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -727,6 +883,7 @@ static int dispatch_variant(const KArgs& a, int variant, int dk, int dvw, hipStr
     switch (variant) {
         case SLA_RETNET: return dispatch_dk<P, SLA_RETNET>(a, dk, dvw, stream);
         case SLA_GLA: return dispatch_dk<P, SLA_GLA>(a, dk, dvw, stream);
+        case SLA_GDN: return dispatch_dk<P, SLA_GDN>(a, dk, dvw, stream);
         default: return SLA_ERR_UNSUPPORTED;
     }
 }

@@ -7,7 +7,7 @@ from gpu_util import GDN, GLA, RETNET, TOL, check, rel_err, run_gpu, run_oracle
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [RETNET, GLA]
+VARIANTS = [RETNET, GLA, GDN]
 
 
 def _name(v):
