@@ -220,9 +220,12 @@ struct Smem {
     static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
     static constexpr size_t oGQ = oEA + sizeof(float) * (kChunk / kBlock) * DK;
     static constexpr size_t oGK = oGQ + sizeof(float) * kChunk;
+    // masked scores P^T of each block as the consumers' MFMA operand: one 4-slot fragment per lane
+    static constexpr size_t oPT = oGK + sizeof(float) * kChunk;
+    static constexpr size_t oPTend = oPT + (kChunk / kBlock) * 64 * 4 * sizeof(elem);
     // delta rule only (kept in every layout; 5 KB): per block the inverse Tm = (I + L)^-1 [16][16],
     // per token p_t, beta_t p_t and beta_t
-    static constexpr size_t oTM = oGK + sizeof(float) * kChunk;
+    static constexpr size_t oTM = oPTend;
     static constexpr size_t oP1 = oTM + sizeof(float) * (kChunk / kBlock) * kBlock * kBlock;
     static constexpr size_t oBP = oP1 + sizeof(float) * kChunk;
     static constexpr size_t oBT = oBP + sizeof(float) * kChunk;
@@ -513,6 +516,28 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
 #pragma unroll
     for (int e = 0; e < EPL; ++e) store_run<P, kBlock, true>(KBT + (EPL * lane + e) * L::TS + kBlock * blk, kb[e]);
 
+    // Scores of the block, P^T[j][t] = kd_j . qa_t for j <= t (else 0), from this wave's own rows
+    // (its LDS operations execute in order, so the rows written above are visible to it), stored as the
+    // MFMA operand every consumer wave reads: lane (r, g) keeps column t = r, rows j = 4g..4g+3.
+    {
+        typedef typename P::frag frag;
+        constexpr int NTILE = DK / 16;
+        const int r_ = lane & 15, g_ = lane >> 4;
+        __builtin_amdgcn_wave_barrier();
+        f32x4 pT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NTILE; s += 2) {
+            const frag q0 = *(const frag*)(QA + (kBlock * blk + r_) * L::RS + 16 * s + 4 * g_);
+            const frag q1 = *(const frag*)(QA + (kBlock * blk + r_) * L::RS + 16 * (s + 1) + 4 * g_);
+            const frag k0 = *(const frag*)(KD + (kBlock * blk + r_) * L::RS + 16 * s + 4 * g_);
+            const frag k1 = *(const frag*)(KD + (kBlock * blk + r_) * L::RS + 16 * (s + 1) + 4 * g_);
+            P::mma32(pT, k0, k1, q0, q1);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pT[i] = (4 * g_ + i <= r_) ? pT[i] : 0.f;
+        ((frag*)(buf + L::oPT))[blk * 64 + lane] = P::from_acc(pT);
+    }
+
     SLA_STAMP(8 * trc + 4);
     // values: scale by the write gate, transpose to [column][token].  The gates were written by this
     // same wave a few instructions ago; LDS operations of one wave execute in order.
@@ -605,7 +630,7 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
     typedef Smem<P, DK, DVW> L;
     constexpr int NTILE = DK / 16;
     const elem* QA = (const elem*)(buf + L::oQA);
-    const elem* KD = (const elem*)(buf + L::oKD);
+    [[maybe_unused]] const elem* KD = (const elem*)(buf + L::oKD);
     const elem* KBT = (const elem*)(buf + L::oKBT);
     const elem* VT = (const elem*)(buf + L::oVT);
     const float* EA = (const float*)(buf + L::oEA);
@@ -616,26 +641,15 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
     for (int I = 0; I < kChunk / kBlock; ++I) {
         SLA_STAMP(8 * trc + 1 + I);
         const int trow = kBlock * I + r;
-        // fragments of qa (rows = tokens of the block) and kd
+        // fragments of qa (rows = tokens of the block); the masked scores come ready from the producers
         frag fq[NTILE];
         [[maybe_unused]] frag fkd[VAR == SLA_GDN ? NTILE : 2];
-        f32x4 pT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < NTILE; s += 2) {
+        for (int s = 0; s < NTILE; ++s) {
             fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
-            fq[s + 1] = *(const frag*)(QA + trow * L::RS + 16 * (s + 1) + 4 * g);
-            const frag k0 = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
-            const frag k1 = *(const frag*)(KD + trow * L::RS + 16 * (s + 1) + 4 * g);
-            if constexpr (VAR == SLA_GDN) {
-                fkd[s] = k0;
-                fkd[s + 1] = k1;
-            }
-            P::mma32(pT, k0, k1, fq[s], fq[s + 1]);  // P^T[j][t] += kd[j][d] qa[t][d]
+            if constexpr (VAR == SLA_GDN) fkd[s] = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
         }
-        // causal mask: lane holds column t = r, rows j = 4g + i
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] : 0.f;
-        const frag fp = P::from_acc(pT);
+        const frag fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
         frag fv = *(const frag*)(VT + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
 
         if constexpr (VAR == SLA_GDN) {
@@ -839,6 +853,8 @@ static int launch(const KArgs& a, hipStream_t stream) {
     typedef Smem<P, DK, DVW> L;
     auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG>;
     const size_t lds = L::total(VAR);
+    static_assert(DVW == 64 || L::total(VAR) <= L::limit, "stage buffers exceed the LDS of a CU");
+    if (lds > L::limit) return SLA_ERR_UNSUPPORTED;
     static bool configured = false;  // per instantiation
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -864,7 +880,16 @@ static int dispatch_dvw(const KArgs& a, int dvw, hipStream_t stream) {
     switch (dvw) {
         case 16: return dispatch_heads<P, VAR, DK, 16>(a, stream);
         case 32: return dispatch_heads<P, VAR, DK, 32>(a, stream);
-        case 64: return dispatch_heads<P, VAR, DK, 64>(a, stream);
+        case 64:
+            // fp32 operands of the delta rule with dk = 128 need more LDS than a CU has for a 64-column
+            // slice; two 32-column slices compute the same values
+            if constexpr (Smem<P, DK, 64>::total(VAR) > Smem<P, DK, 64>::limit) {
+                KArgs b = a;
+                b.nslice = a.dv / 32;
+                return dispatch_heads<P, VAR, DK, 32>(b, stream);
+            } else {
+                return dispatch_heads<P, VAR, DK, 64>(a, stream);
+            }
         default: return SLA_ERR_UNSUPPORTED;
     }
 }
