@@ -70,17 +70,30 @@ struct KArgs {
 };
 
 #ifdef SLA_TRACE
-// Developer timing builds only: every wave records s_memtime at numbered points of each chunk.
+// Developer timing builds only: every wave records s_memtime at up to 8 points of each chunk.  The
+// values stay in registers until SLA_FLUSH, so taking a stamp does not wait for outstanding memory.
 static constexpr int kTraceRec = 512;
 __device__ unsigned long long* d_trace = nullptr;
-#define SLA_STAMP(idx)                                                                                          \
-    do {                                                                                                        \
-        if (d_trace && (idx) < kTraceRec && (threadIdx.x & 63) == 0)                                            \
-            d_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * kTraceRec + (idx)] = __builtin_amdgcn_s_memtime(); \
+#define SLA_TRACE_DECL unsigned long long trace_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define SLA_TRACE_PARAM , unsigned long long (&trace_t)[8]
+#define SLA_TRACE_PASS , trace_t
+#define SLA_STAMP(k) trace_t[k] = __builtin_amdgcn_s_memtime()
+#define SLA_FLUSH(chunk)                                                                                       \
+    do {                                                                                                       \
+        if (d_trace && (chunk) * 8 + 7 < kTraceRec && (threadIdx.x & 63) == 0) {                                \
+            for (int k_ = 0; k_ < 8; ++k_)                                                                      \
+                d_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * kTraceRec + (chunk) * 8 + k_] = trace_t[k_]; \
+        }                                                                                                      \
     } while (0)
 #else
-#define SLA_STAMP(idx) \
-    do {               \
+#define SLA_TRACE_DECL
+#define SLA_TRACE_PARAM
+#define SLA_TRACE_PASS
+#define SLA_STAMP(k) \
+    do {             \
+    } while (0)
+#define SLA_FLUSH(chunk) \
+    do {                 \
     } while (0)
 #endif
 
@@ -306,24 +319,39 @@ struct Loader {
 
     // Token indices passed to the loads must be wave-uniform (they become scalar offsets).
     __device__ __forceinline__ void load_q(stage_t& st, int tok0, int i) const {
+#ifdef SLA_NOLOAD
+        if (tok0 >= kChunk) return;
+#endif
         const int so = (tok0 + i) * tstride_qk;
         st.q[i] = (EPL == 2) ? P::bload2(rq, voff_qk, so) : P::bload1(rq, voff_qk, so);
     }
     __device__ __forceinline__ void load_k(stage_t& st, int tok0, int i) const {
+#ifdef SLA_NOLOAD
+        if (tok0 >= kChunk) return;
+#endif
         const int so = (tok0 + i) * tstride_qk;
         st.k[i] = (EPL == 2) ? P::bload2(rk, voff_qk, so) : P::bload1(rk, voff_qk, so);
     }
     __device__ __forceinline__ void load_ld(stage_t& st, int tok0, int i) const {
+#ifdef SLA_NOLOAD
+        if (tok0 >= kChunk) return;
+#endif
         if constexpr (VAR == SLA_GLA) {
             const int so = (tok0 + i) * tstride_qk;
             st.ld[i] = (EPL == 2) ? P::bload2(rld, voff_qk, so) : P::bload1(rld, voff_qk, so);
         }
     }
     __device__ __forceinline__ void load_v(stage_t& st, int tok0) const {
+#ifdef SLA_NOLOAD
+        if (tok0 >= kChunk) return;
+#endif
 #pragma unroll
         for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, (tok0 + i) * tstride_v);
     }
     __device__ __forceinline__ void load_logits(stage_t& st, int tok0, int lane) const {
+#ifdef SLA_NOLOAD
+        if (tok0 >= kChunk) return;
+#endif
         const int s_lg = tok0 * tstride_lg;
         const int sub = lane & 3;
 #pragma unroll
@@ -390,9 +418,9 @@ __device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
 template <class P, int VAR, int DK, int DVW, int HG>
 __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
                                               unsigned char* buf, typename P::elem* kp_scratch, int blk, int tok0,
-                                              int next_tok0, int T, float decay_const, int lane) {
+                                              int next_tok0, int T, float decay_const, int lane SLA_TRACE_PARAM) {
+    SLA_STAMP(0);
     const bool has_kl = ldr.has_kl;
-    [[maybe_unused]] const int trc = tok0 / kChunk;
     typedef typename P::elem elem;
     typedef typename P::pair pair;
     typedef Smem<P, DK, DVW> L;
@@ -435,8 +463,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         }
         ldr.load_logits(st, next_tok0, lane);
     }
-
-    SLA_STAMP(8 * trc + 1);
+    SLA_STAMP(1);
     // per-token decay factors of the owned key dimensions
     float al[EPL][kBlock];
 #pragma unroll
@@ -454,7 +481,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
             for (int e = 0; e < EPL; ++e) al[e][i] = x;
         }
     }
-    SLA_STAMP(8 * trc + 2);
+    SLA_STAMP(2);
     // forward: p_t = prod_{i<=t} alpha_i ; qa_t = q_t p_t
     float pre[EPL];
 #pragma unroll
@@ -496,7 +523,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         invA[e] = fast_rcp(pre[e]);
         EA[blk * DK + EPL * lane + e] = pre[e];
     }
-    SLA_STAMP(8 * trc + 3);
+    SLA_STAMP(3);
     // backward: kb_j = k_j prod_{i>j} alpha_i ; kd_j = kb_j / A
     float suf[EPL], kb[EPL][kBlock];
 #pragma unroll
@@ -516,6 +543,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
 #pragma unroll
     for (int e = 0; e < EPL; ++e) store_run<P, kBlock, true>(KBT + (EPL * lane + e) * L::TS + kBlock * blk, kb[e]);
 
+    SLA_STAMP(4);
     // Scores of the block, P^T[j][t] = kd_j . qa_t for j <= t (else 0), from this wave's own rows
     // (its LDS operations execute in order, so the rows written above are visible to it), stored as the
     // MFMA operand every consumer wave reads: lane (r, g) keeps column t = r, rows j = 4g..4g+3.
@@ -537,8 +565,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         for (int i = 0; i < 4; ++i) pT[i] = (4 * g_ + i <= r_) ? pT[i] : 0.f;
         ((frag*)(buf + L::oPT))[blk * 64 + lane] = P::from_acc(pT);
     }
-
-    SLA_STAMP(8 * trc + 4);
+    SLA_STAMP(5);
     // values: scale by the write gate, transpose to [column][token].  The gates were written by this
     // same wave a few instructions ago; LDS operations of one wave execute in order.
     {
@@ -578,6 +605,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         store_run<P, NI, true>(VT + (2 * p + 1) * L::TS + kBlock * blk + tb, c1);
     }
 
+    SLA_STAMP(6);
     // delta rule: Tm = (I + L)^-1 with L[j][t] = beta_j (k_j p_j).(k_t / p_t) for t < j (strictly lower).
     if constexpr (VAR == SLA_GDN) {
         typedef typename P::frag frag;
@@ -621,87 +649,120 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
 
 // ---------------------------------------------------------------------------------------------
 // Consumer: the four 16-token blocks of one staged chunk for the 16 value columns of wave cw.
+// The LDS fragments of block I+1 (and the state-step fragments of block I) are requested before the
+// matrix work of block I starts, so their latency is covered by it.
 // ---------------------------------------------------------------------------------------------
+template <class P, int VAR, int DK>
+struct BlockFrags {
+    typedef typename P::frag frag;
+    frag fq[DK / 16];                          // qa rows of the block (tokens), all key dimensions
+    frag fkd[VAR == SLA_GDN ? DK / 16 : 1];    // delta rule: kd rows
+    frag fp;                                   // masked scores P^T
+    frag fv;                                   // v' of this wave's columns
+    float gq;                                  // read gate of token r
+    f32x4 p1, bp, tm;                          // delta rule: p_j, beta_j p_j (j = 4g..4g+3), Tm[r][4g..4g+3]
+};
+
 template <class P, int VAR, int DK, int DVW>
-__device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigned char* buf, int cw, int chunk_tok0,
-                                              int T, typename P::elem* out_row, size_t out_tstride, int lane) {
+__device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, const unsigned char* buf, int I, int cw,
+                                                 int lane) {
     typedef typename P::elem elem;
     typedef typename P::frag frag;
     typedef Smem<P, DK, DVW> L;
     constexpr int NTILE = DK / 16;
+    const int r = lane & 15, g = lane >> 4, trow = kBlock * I + r;
     const elem* QA = (const elem*)(buf + L::oQA);
-    [[maybe_unused]] const elem* KD = (const elem*)(buf + L::oKD);
-    const elem* KBT = (const elem*)(buf + L::oKBT);
-    const elem* VT = (const elem*)(buf + L::oVT);
-    const float* EA = (const float*)(buf + L::oEA);
-    const float* GQ = (const float*)(buf + L::oGQ);
-    const int r = lane & 15, g = lane >> 4;
-    [[maybe_unused]] const int trc = chunk_tok0 / kChunk;
-#pragma unroll 1
-    for (int I = 0; I < kChunk / kBlock; ++I) {
-        SLA_STAMP(8 * trc + 1 + I);
-        const int trow = kBlock * I + r;
-        // fragments of qa (rows = tokens of the block); the masked scores come ready from the producers
-        frag fq[NTILE];
-        [[maybe_unused]] frag fkd[VAR == SLA_GDN ? NTILE : 2];
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) {
-            fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
-            if constexpr (VAR == SLA_GDN) fkd[s] = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
-        }
-        const frag fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
-        frag fv = *(const frag*)(VT + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
+    for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
+    if constexpr (VAR == SLA_GDN) {
+        const elem* KD = (const elem*)(buf + L::oKD);
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
+        f.p1 = *(const f32x4*)((const float*)(buf + L::oP1) + I * kBlock + 4 * g);
+        f.bp = *(const f32x4*)((const float*)(buf + L::oBP) + I * kBlock + 4 * g);
+        f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + I * kBlock * kBlock + r * kBlock + 4 * g);
+    }
+    f.fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
+    f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
+    f.gq = ((const float*)(buf + L::oGQ))[trow];
+}
 
+template <class P, int VAR, int DK, int DVW>
+__device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigned char* buf, int cw, int chunk_tok0,
+                                              int T, typename P::elem* out_row, size_t out_tstride,
+                                              int lane SLA_TRACE_PARAM) {
+    typedef typename P::elem elem;
+    typedef typename P::frag frag;
+    typedef Smem<P, DK, DVW> L;
+    constexpr int NTILE = DK / 16;
+    constexpr int NBLK = kChunk / kBlock;
+    const elem* KBT = (const elem*)(buf + L::oKBT);
+    const float* EA = (const float*)(buf + L::oEA);
+    const int r = lane & 15, g = lane >> 4;
+
+    SLA_STAMP(0);
+    BlockFrags<P, VAR, DK> cur, nxt;
+    load_block_frags<P, VAR, DK, DVW>(cur, buf, 0, cw, lane);
+#pragma unroll
+    for (int I = 0; I < NBLK; ++I) {
+        // requests for later: the next block's operands and this block's state-step operands
+        if (I + 1 < NBLK) load_block_frags<P, VAR, DK, DVW>(nxt, buf, I + 1, cw, lane);
+        f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
+        frag fk[NTILE];
+        if constexpr (VAR == SLA_GLA) {
+#pragma unroll
+            for (int s = 0; s < NTILE; ++s) ea[s] = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
+        } else {  // the decay of a block is one number for RetNet and the delta rule
+            const float e = EA[I * DK];
+            ea[0] = f32x4{e, e, e, e};
+        }
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s) fk[s] = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
+
+        frag fv = cur.fv;
         if constexpr (VAR == SLA_GDN) {
             // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
             //   (I + L) U = beta G^K V - diag(beta p) K S,   K S = p (kd S)   =>   U = Tm R.
             // U then takes the place of v' in the read-out and in the state step.
-            const float* TM = (const float*)(buf + L::oTM) + I * kBlock * kBlock;
-            const float* P1 = (const float*)(buf + L::oP1) + I * kBlock;
-            const float* BP = (const float*)(buf + L::oBP) + I * kBlock;
             f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = kd_j S : lane holds column n = r, rows j = 4g + i
 #pragma unroll
             for (int s = 0; s < NTILE; s += 2)
-                P::mma32(X, fkd[s], fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
-            const f32x4 p1 = *(const f32x4*)(P1 + 4 * g);
-            const f32x4 bp = *(const f32x4*)(BP + 4 * g);
+                P::mma32(X, cur.fkd[s], cur.fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
             const f32x4 vb = P::to_acc(fv);
             f32x4 R;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = vb[i] - bp[i] * (p1[i] * X[i]);
-            const frag ftm = P::from_acc(*(const f32x4*)(TM + r * kBlock + 4 * g));  // Tm[t = r][j = 4g + i]
+            for (int i = 0; i < 4; ++i) R[i] = vb[i] - cur.bp[i] * (cur.p1[i] * X[i]);
             f32x4 U = {0.f, 0.f, 0.f, 0.f};
-            P::mma16(U, ftm, P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
+            P::mma16(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
             fv = P::from_acc(U);
         }
 
         // O^T[n][t] = sum_d S[d][n] qa[t][d] + sum_j v'[j][n] P[t][j]
         f32x4 oT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < NTILE; s += 2) P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), fq[s], fq[s + 1]);
-        P::mma16(oT, fv, fp);
-
-        // epilogue: read gate, cast, store 4 adjacent value columns of token t
-        {
-            const int t = chunk_tok0 + trow;
-            const float gq = GQ[trow];
-            float o[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = oT[i] * gq;
-            if (t < T) store_run<P, 4>(out_row + (size_t)t * out_tstride, o);
-        }
+        for (int s = 0; s < NTILE; s += 2)
+            P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
+        P::mma16(oT, fv, cur.fp);
 
         // state step: S <- diag(A_I) S + kb^T v'
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) {
-            // the decay of a block is one number for RetNet and the delta rule, a vector over d for GLA
-            const f32x4 ea = (VAR == SLA_GLA) ? *(const f32x4*)(EA + I * DK + 16 * s + 4 * g)
-                                              : f32x4{EA[I * DK], EA[I * DK], EA[I * DK], EA[I * DK]};
-            const frag fk = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
+            const f32x4 e = (VAR == SLA_GLA) ? ea[s] : ea[0];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) S[s][i] *= ea[i];
-            P::mma16(S[s], fk, fv);
+            for (int i = 0; i < 4; ++i) S[s][i] *= e[i];
+            P::mma16(S[s], fk[s], fv);
         }
+
+        // epilogue: read gate, cast, store 4 adjacent value columns of token t
+        {
+            const int t = chunk_tok0 + kBlock * I + r;
+            float o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = oT[i] * cur.gq;
+            if (t < T) store_run<P, 4>(out_row + (size_t)t * out_tstride, o);
+        }
+        if (I + 1 < NBLK) cur = nxt;
+        SLA_STAMP(1 + I);
     }
 }
 
@@ -753,13 +814,14 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
         // zero without touching memory, and nothing staged from it is ever read.
         Stage<P, VAR, DK, DVW, HG> st;
         ldr.load(st, kBlock * pw, lane);
+        SLA_TRACE_DECL
         auto stage_chunk = [&](int cc) {
             if (cc < nchunks) {
                 const int tok0 = cc * kChunk + kBlock * pw;
 #if SLA_EXP != 2
                 elem* kp_scratch = (elem*)(smem + NBUF * L::bytes) + kBlock * pw * L::RS;  // delta rule only
                 produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, kp_scratch, pw,
-                                                   tok0, tok0 + kChunk, T, decay_const, lane);
+                                                   tok0, tok0 + kChunk, T, decay_const, lane SLA_TRACE_PASS);
 #endif
             }
         };
@@ -769,8 +831,12 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             for (int c = 0; c < nchunks; c += 2) {  // consumers work on chunks c and c+1 meanwhile
                 stage_chunk(c + 1);
                 __syncthreads();
+                SLA_STAMP(7);
+                SLA_FLUSH(c + 1);
                 stage_chunk(c + 2);
                 __syncthreads();
+                SLA_STAMP(7);
+                SLA_FLUSH(c + 2);
             }
         } else {
             // one LDS buffer (fp32 operands with dk = 128): the two phases alternate
@@ -804,19 +870,20 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     const size_t out_tstride = (size_t)H * dv;
 
     // Barrier count per pair of chunks matches the producers' (two steps per pair, also for an odd tail).
+    SLA_TRACE_DECL
     if constexpr (NBUF == 2) {
         __syncthreads();
         for (int c = 0; c < nchunks; c += 2) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                SLA_STAMP(8 * (c + u));
 #if SLA_EXP != 1
                 if (active && c + u < nchunks)
-                    consume_chunk<P, VAR, DK, DVW>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
+                    consume_chunk<P, VAR, DK, DVW>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride,
+                                                   lane SLA_TRACE_PASS);
 #endif
-                SLA_STAMP(8 * (c + u) + 6);
                 __syncthreads();
-                SLA_STAMP(8 * (c + u) + 7);
+                SLA_STAMP(7);
+                SLA_FLUSH(c + u);
             }
         }
     } else {
@@ -825,7 +892,7 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             for (int u = 0; u < 2; ++u) {
                 __syncthreads();
                 if (active && c + u < nchunks)
-                    consume_chunk<P, VAR, DK, DVW>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane);
+                    consume_chunk<P, VAR, DK, DVW>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane SLA_TRACE_PASS);
                 __syncthreads();
             }
         }
