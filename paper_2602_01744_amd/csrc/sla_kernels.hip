@@ -236,22 +236,16 @@ struct Smem {
     // masked scores P^T of each block as the consumers' MFMA operand: one 4-slot fragment per lane
     static constexpr size_t oPT = oGK + sizeof(float) * kChunk;
     static constexpr size_t oPTend = oPT + (kChunk / kBlock) * 64 * 4 * sizeof(elem);
-    // delta rule only (kept in every layout; 5 KB): per block the inverse Tm = (I + L)^-1 [16][16],
-    // per token p_t, beta_t p_t and beta_t
+    // scalar-decay variants (kept in every layout; 5 KB): per block the inverse Tm = (I + L)^-1 [16][16] of the
+    // delta rule; per token the cumulative log2-decay c_t (in "P1"), beta_t ("BT"); "BP" is spare
     static constexpr size_t oTM = oPTend;
     static constexpr size_t oP1 = oTM + sizeof(float) * (kChunk / kBlock) * kBlock * kBlock;
     static constexpr size_t oBP = oP1 + sizeof(float) * kChunk;
     static constexpr size_t oBT = oBP + sizeof(float) * kChunk;
     static constexpr size_t bytes = oBT + sizeof(float) * kChunk;
-    // delta rule only, outside the double buffer: k_t p_t of the block a producer wave is working on
-    static constexpr size_t gdn_private = sizeof(elem) * kChunk * RS;
     static constexpr size_t limit = 160 * 1024;
-    static constexpr int nbuf(int variant) {
-        return 2 * bytes + (variant == SLA_GDN ? gdn_private : 0) <= limit ? 2 : 1;
-    }
-    static constexpr size_t total(int variant) {
-        return nbuf(variant) * bytes + (variant == SLA_GDN ? gdn_private : 0);
-    }
+    static constexpr int nbuf(int) { return 2 * bytes <= limit ? 2 : 1; }
+    static constexpr size_t total(int variant) { return nbuf(variant) * bytes; }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -410,76 +404,233 @@ __device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
     return fast_exp2((own - m) * kLog2e) * fast_rcp(s);
 }
 
+// Gates of the 16 tokens of block blk (token lane/4) from the staged logits; parked in LDS for the
+// epilogue (read gate) and for the values (write gate).  The logits are then reloaded for next_tok0.
+template <class P, int VAR, int DK, int DVW, int HG>
+__device__ __forceinline__ void stage_gates(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
+                                            unsigned char* buf, int blk, int next_tok0, int lane) {
+    typedef Smem<P, DK, DVW> L;
+    float* GQ = (float*)(buf + L::oGQ);
+    float* GK = (float*)(buf + L::oGK);
+    const float gq = head_gate<HG>(st.ql, st.ql_own);
+    const float gk = ldr.has_kl ? head_gate<HG>(st.kl, st.kl_own) : 1.f;
+    if ((lane & 3) == 0) {
+        GQ[kBlock * blk + (lane >> 2)] = gq;
+        GK[kBlock * blk + (lane >> 2)] = gk;
+    }
+    ldr.load_logits(st, next_tok0, lane);
+}
+
+// Values of block blk: v' = G^K v (delta rule: beta G^K v), transposed to [column][token].  The gates
+// (and beta) were written by this same wave earlier; LDS operations of one wave execute in order.
+template <class P, int VAR, int DK, int DVW, int HG>
+__device__ __forceinline__ void stage_values(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
+                                             unsigned char* buf, int blk, int next_tok0, int lane) {
+    typedef typename P::elem elem;
+    typedef Smem<P, DK, DVW> L;
+    constexpr int NI = DVW / 8;
+    constexpr int LPR = DVW / 2;
+    elem* VT = (elem*)(buf + L::oVT);
+    const float* GK = (const float*)(buf + L::oGK);
+    const float* BT = (const float*)(buf + L::oBT) + blk * kBlock;
+    const int p = lane % LPR, tb = (lane / LPR) * NI;
+    __builtin_amdgcn_wave_barrier();
+    float gkv[NI];
+    if constexpr (NI >= 4) {
+#pragma unroll
+        for (int i = 0; i < NI / 4; ++i) {
+            const f32x4 t = *(const f32x4*)(GK + kBlock * blk + tb + 4 * i);
+            gkv[4 * i] = t[0]; gkv[4 * i + 1] = t[1]; gkv[4 * i + 2] = t[2]; gkv[4 * i + 3] = t[3];
+        }
+    } else {
+        const f32x2 t = *(const f32x2*)(GK + kBlock * blk + tb);
+        gkv[0] = t[0]; gkv[1] = t[1];
+    }
+    if constexpr (VAR == SLA_GDN) {
+        if constexpr (NI >= 4) {
+#pragma unroll
+            for (int i = 0; i < NI / 4; ++i) {
+                const f32x4 t = *(const f32x4*)(BT + tb + 4 * i);
+                gkv[4 * i] *= t[0]; gkv[4 * i + 1] *= t[1]; gkv[4 * i + 2] *= t[2]; gkv[4 * i + 3] *= t[3];
+            }
+        } else {
+            const f32x2 t = *(const f32x2*)(BT + tb);
+            gkv[0] *= t[0]; gkv[1] *= t[1];
+        }
+    }
+    float c0[NI], c1[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        c0[i] = P::lo(st.v[i]) * gkv[i];
+        c1[i] = P::hi(st.v[i]) * gkv[i];
+    }
+    ldr.load_v(st, next_tok0);
+    store_run<P, NI, true>(VT + (2 * p) * L::TS + kBlock * blk + tb, c0);
+    store_run<P, NI, true>(VT + (2 * p + 1) * L::TS + kBlock * blk + tb, c1);
+}
+
+// Inclusive sum over the 16 lanes of a DPP row (lane r gets x_0 + ... + x_r).
+__device__ __forceinline__ float row_prefix_sum(float x) {
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x111, 0xf, 0xf, true));
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x112, 0xf, 0xf, true));
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x114, 0xf, 0xf, true));
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x118, 0xf, 0xf, true));
+    return x;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Producer for the scalar-decay variants (RetNet, delta rule).  The decay of a token is one number per
+// head, so it is applied after the matrix products instead of being folded into q and k: q and k go
+// to LDS as loaded (k also transposed), and the block's cumulative log2-decay c_t = log2 p_t is staged
+// for the consumers, which scale the read-out by 2^c_t, the state by A = 2^c_16 and the state-step
+// values by 2^(c_16 - c_j).  Scores are scaled here: P[t,j] = (q_t . k_j) 2^(c_t - c_j) for j <= t.
+// Every factor is <= 1, whatever the decay.
+// ---------------------------------------------------------------------------------------------
+template <class P, int VAR, int DK, int DVW, int HG>
+__device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>& st,
+                                                     const Loader<P, VAR, DK, DVW, HG>& ldr, unsigned char* buf, int blk,
+                                                     int tok0, int next_tok0, int T, float log2_gamma, int lane) {
+    typedef typename P::elem elem;
+    typedef typename P::pair pair;
+    typedef typename P::frag frag;
+    typedef Smem<P, DK, DVW> L;
+    constexpr int EPL = DK / 64;
+    constexpr int NTILE = DK / 16;
+    elem* QA = (elem*)(buf + L::oQA);
+    elem* KD = (elem*)(buf + L::oKD);
+    elem* KBT = (elem*)(buf + L::oKBT);
+    float* TM = (float*)(buf + L::oTM) + blk * kBlock * kBlock;
+    float* C2 = (float*)(buf + L::oP1) + blk * kBlock;  // cumulative log2-decay of the block's tokens
+    float* BT = (float*)(buf + L::oBT) + blk * kBlock;
+    const int r = lane & 15, g = lane >> 4;
+
+    // c_t of token r (the four lane groups hold the same value)
+    float c_lane;
+    if constexpr (VAR == SLA_RETNET) {
+        int nvalid = T - tok0;
+        nvalid = nvalid < 0 ? 0 : (nvalid > kBlock ? kBlock : nvalid);
+        const int n = r + 1 < nvalid ? r + 1 : nvalid;  // tokens past T do not decay the state
+        c_lane = (float)n * log2_gamma;
+    } else {
+        c_lane = row_prefix_sum(st.sc_ld * kLog2e);
+        if (lane < kBlock) BT[lane] = st.sc_beta;
+    }
+    if (lane < kBlock) C2[lane] = c_lane;
+    ldr.load_scalars(st, next_tok0);
+
+    stage_gates<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
+
+    // q and k as loaded
+    elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
+    elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
+#pragma unroll
+    for (int i = 0; i < kBlock; ++i) {
+        if constexpr (EPL == 2) {
+            *(pair*)(qrow + i * L::RS) = st.q[i];
+            *(pair*)(krow + i * L::RS) = st.k[i];
+        } else {
+            P::store1(qrow + i * L::RS, P::lo(st.q[i]));
+            P::store1(krow + i * L::RS, P::lo(st.k[i]));
+        }
+        ldr.load_q(st, next_tok0, i);
+    }
+    // k transposed
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        float kt[kBlock];
+#pragma unroll
+        for (int i = 0; i < kBlock; ++i) kt[i] = (EPL == 2 && e == 1) ? P::hi(st.k[i]) : P::lo(st.k[i]);
+        store_run<P, kBlock, true>(KBT + (EPL * lane + e) * L::TS + kBlock * blk, kt);
+    }
+#pragma unroll
+    for (int i = 0; i < kBlock; ++i) ldr.load_k(st, next_tok0, i);
+
+    // scores of the block from this wave's own rows
+    __builtin_amdgcn_wave_barrier();
+    frag fk_[NTILE];
+    f32x4 pT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < NTILE; s += 2) {
+        const frag q0 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
+        const frag q1 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
+        fk_[s] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
+        fk_[s + 1] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
+        P::mma32(pT, fk_[s], fk_[s + 1], q0, q1);  // P^T[j][t] = k_j . q_t
+    }
+    const f32x4 cj = *(const f32x4*)(C2 + 4 * g);  // rows j = 4g + i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] * fast_exp2(c_lane - cj[i]) : 0.f;
+    ((frag*)(buf + L::oPT))[blk * 64 + lane] = P::from_acc(pT);
+
+    stage_values<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
+
+    // delta rule: Tm = (I + L)^-1 with L[j][t] = beta_j 2^(c_j - c_t) (k_j . k_t) for t < j (strictly lower)
+    if constexpr (VAR == SLA_GDN) {
+        f32x4 G = {0.f, 0.f, 0.f, 0.f};  // G[j][t] = k_j . k_t: lane holds column t = r, rows j = 4g + i
+#pragma unroll
+        for (int s = 0; s < NTILE; s += 2) P::mma32(G, fk_[s], fk_[s + 1], fk_[s], fk_[s + 1]);
+        const f32x4 btj = *(const f32x4*)(BT + 4 * g);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            TM[(4 * g + i) * kBlock + r] = (4 * g + i > r) ? btj[i] * fast_exp2(cj[i] - c_lane) * G[i] : 0.f;
+        __builtin_amdgcn_wave_barrier();
+        // forward substitution, column c = r of the inverse in every lane (the four lane groups repeat it):
+        // x_j = [j == c] - sum_{i<j} L[j][i] x_i
+        float x[kBlock];
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) {
+            float acc = (j == r) ? 1.f : 0.f;
+#pragma unroll
+            for (int i4 = 0; i4 < j; i4 += 4) {
+                const f32x4 lrow = *(const f32x4*)(TM + j * kBlock + i4);  // same address in all lanes
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (i4 + i < j) acc -= lrow[i] * x[i4 + i];
+            }
+            x[j] = acc;
+        }
+        __builtin_amdgcn_wave_barrier();  // every lane has read L before it is overwritten
+        if (g == 0) {
+#pragma unroll
+            for (int j = 0; j < kBlock; ++j) TM[j * kBlock + r] = x[j];
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Producer: one 16-token block (index blk of the staged chunk) from registers to LDS.
 // ---------------------------------------------------------------------------------------------
 // Every staging register is reloaded with the same block of the next chunk (token next_tok0 + i) right
 // after its last use, so the loads are spread through the arithmetic instead of queueing up in a burst.
+// This is the path of GLA, whose decay is a vector over the key dimensions and has to be folded into
+// q and k element by element.
 template <class P, int VAR, int DK, int DVW, int HG>
 __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
-                                              unsigned char* buf, typename P::elem* kp_scratch, int blk, int tok0,
-                                              int next_tok0, int T, float decay_const, int lane SLA_TRACE_PARAM) {
+                                              unsigned char* buf, int blk, int tok0, int next_tok0, int T,
+                                              float decay_const, int lane SLA_TRACE_PARAM) {
+    if constexpr (VAR != SLA_GLA) {
+        produce_block_scalar<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, tok0, next_tok0, T, decay_const, lane);
+        return;
+    }
     SLA_STAMP(0);
-    const bool has_kl = ldr.has_kl;
     typedef typename P::elem elem;
     typedef typename P::pair pair;
     typedef Smem<P, DK, DVW> L;
     constexpr int EPL = DK / 64;
-    constexpr int NI = DVW / 8;
-    constexpr int LPR = DVW / 2;
     elem* QA = (elem*)(buf + L::oQA);
     elem* KD = (elem*)(buf + L::oKD);
     elem* KBT = (elem*)(buf + L::oKBT);
-    elem* VT = (elem*)(buf + L::oVT);
     float* EA = (float*)(buf + L::oEA);
-    float* GQ = (float*)(buf + L::oGQ);
-    float* GK = (float*)(buf + L::oGK);
-    [[maybe_unused]] float* TM = (float*)(buf + L::oTM) + blk * kBlock * kBlock;
-    [[maybe_unused]] float* P1 = (float*)(buf + L::oP1) + blk * kBlock;
-    [[maybe_unused]] float* BP = (float*)(buf + L::oBP) + blk * kBlock;
-    [[maybe_unused]] float* BT = (float*)(buf + L::oBT) + blk * kBlock;
-    [[maybe_unused]] const int r = lane & 15, g = lane >> 4;
 
-    // delta rule: per-token scalars of the block as wave-uniform values
-    [[maybe_unused]] float a_u[kBlock], bt_u[kBlock];
-    if constexpr (VAR == SLA_GDN) {
-        const float a_lane = fast_exp2(st.sc_ld * kLog2e);
-        if (lane < kBlock) BT[lane] = st.sc_beta;
-#pragma unroll
-        for (int i = 0; i < kBlock; ++i) {
-            a_u[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a_lane), i));
-            bt_u[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.sc_beta), i));
-        }
-        ldr.load_scalars(st, next_tok0);
-    }
-
-    // gates of the 16 tokens of the block (token lane/4); parked in LDS for the epilogue and for V
-    {
-        const float gq = head_gate<HG>(st.ql, st.ql_own);
-        const float gk = has_kl ? head_gate<HG>(st.kl, st.kl_own) : 1.f;
-        if ((lane & 3) == 0) {
-            GQ[kBlock * blk + (lane >> 2)] = gq;
-            GK[kBlock * blk + (lane >> 2)] = gk;
-        }
-        ldr.load_logits(st, next_tok0, lane);
-    }
+    stage_gates<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
     SLA_STAMP(1);
     // per-token decay factors of the owned key dimensions
     float al[EPL][kBlock];
 #pragma unroll
     for (int i = 0; i < kBlock; ++i) {
-        if constexpr (VAR == SLA_GLA) {
-            al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
-            if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
-            ldr.load_ld(st, next_tok0, i);
-        } else if constexpr (VAR == SLA_GDN) {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) al[e][i] = a_u[i];
-        } else {
-            const float x = (tok0 + i < T) ? decay_const : 1.f;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) al[e][i] = x;
-        }
+        al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
+        if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
+        ldr.load_ld(st, next_tok0, i);
     }
     SLA_STAMP(2);
     // forward: p_t = prod_{i<=t} alpha_i ; qa_t = q_t p_t
@@ -488,8 +639,6 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     for (int e = 0; e < EPL; ++e) pre[e] = 1.f;
     elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
     elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
-    [[maybe_unused]] elem* kprow = kp_scratch + EPL * lane;  // delta rule: k_t p_t, private to this wave
-    [[maybe_unused]] float p_u[kBlock];
 #pragma unroll
     for (int i = 0; i < kBlock; ++i) {
 #pragma unroll
@@ -498,24 +647,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
             *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
         else
             P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
-        if constexpr (VAR == SLA_GDN) {
-            p_u[i] = pre[0];
-            if constexpr (EPL == 2)
-                *(pair*)(kprow + i * L::RS) = P::make(P::lo(st.k[i]) * pre[0], P::hi(st.k[i]) * pre[1]);
-            else
-                P::store1(kprow + i * L::RS, P::lo(st.k[i]) * pre[0]);
-        }
         ldr.load_q(st, next_tok0, i);
-    }
-    if constexpr (VAR == SLA_GDN) {
-        if (lane == 0) {
-#pragma unroll
-            for (int i = 0; i < kBlock; i += 4) {
-                *(f32x4*)(P1 + i) = f32x4{p_u[i], p_u[i + 1], p_u[i + 2], p_u[i + 3]};
-                *(f32x4*)(BP + i) = f32x4{bt_u[i] * p_u[i], bt_u[i + 1] * p_u[i + 1], bt_u[i + 2] * p_u[i + 2],
-                                          bt_u[i + 3] * p_u[i + 3]};
-            }
-        }
     }
     float invA[EPL];
 #pragma unroll
@@ -566,85 +698,8 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         ((frag*)(buf + L::oPT))[blk * 64 + lane] = P::from_acc(pT);
     }
     SLA_STAMP(5);
-    // values: scale by the write gate, transpose to [column][token].  The gates were written by this
-    // same wave a few instructions ago; LDS operations of one wave execute in order.
-    {
-        const int p = lane % LPR, tb = (lane / LPR) * NI;
-        __builtin_amdgcn_wave_barrier();
-        float gkv[NI];
-        if constexpr (NI >= 4) {
-#pragma unroll
-            for (int i = 0; i < NI / 4; ++i) {
-                const f32x4 t = *(const f32x4*)(GK + kBlock * blk + tb + 4 * i);
-                gkv[4 * i] = t[0]; gkv[4 * i + 1] = t[1]; gkv[4 * i + 2] = t[2]; gkv[4 * i + 3] = t[3];
-            }
-        } else {
-            const f32x2 t = *(const f32x2*)(GK + kBlock * blk + tb);
-            gkv[0] = t[0]; gkv[1] = t[1];
-        }
-        if constexpr (VAR == SLA_GDN) {  // v' = beta G^K v
-            if constexpr (NI >= 4) {
-#pragma unroll
-                for (int i = 0; i < NI / 4; ++i) {
-                    const f32x4 t = *(const f32x4*)(BT + tb + 4 * i);
-                    gkv[4 * i] *= t[0]; gkv[4 * i + 1] *= t[1]; gkv[4 * i + 2] *= t[2]; gkv[4 * i + 3] *= t[3];
-                }
-            } else {
-                const f32x2 t = *(const f32x2*)(BT + tb);
-                gkv[0] *= t[0]; gkv[1] *= t[1];
-            }
-        }
-        float c0[NI], c1[NI];
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            c0[i] = P::lo(st.v[i]) * gkv[i];
-            c1[i] = P::hi(st.v[i]) * gkv[i];
-        }
-        ldr.load_v(st, next_tok0);
-        store_run<P, NI, true>(VT + (2 * p) * L::TS + kBlock * blk + tb, c0);
-        store_run<P, NI, true>(VT + (2 * p + 1) * L::TS + kBlock * blk + tb, c1);
-    }
-
+    stage_values<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
     SLA_STAMP(6);
-    // delta rule: Tm = (I + L)^-1 with L[j][t] = beta_j (k_j p_j).(k_t / p_t) for t < j (strictly lower).
-    if constexpr (VAR == SLA_GDN) {
-        typedef typename P::frag frag;
-        constexpr int NTILE = DK / 16;
-        __builtin_amdgcn_wave_barrier();  // this wave's kp and kd rows are in LDS (its LDS operations are in order)
-        f32x4 G = {0.f, 0.f, 0.f, 0.f};   // G[j][t]: lane holds column t = r, rows j = 4g + i
-#pragma unroll
-        for (int s = 0; s < NTILE; s += 2) {
-            const frag a0 = *(const frag*)(kp_scratch + r * L::RS + 16 * s + 4 * g);
-            const frag a1 = *(const frag*)(kp_scratch + r * L::RS + 16 * (s + 1) + 4 * g);
-            const frag b0 = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
-            const frag b1 = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
-            P::mma32(G, a0, a1, b0, b1);
-        }
-        const f32x4 btj = *(const f32x4*)(BT + 4 * g);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) TM[(4 * g + i) * kBlock + r] = (4 * g + i > r) ? btj[i] * G[i] : 0.f;
-        __builtin_amdgcn_wave_barrier();
-        // forward substitution, column c = r of the inverse in every lane (the four lane groups repeat it):
-        // x_j = [j == c] - sum_{i<j} L[j][i] x_i
-        float x[kBlock];
-#pragma unroll
-        for (int j = 0; j < kBlock; ++j) {
-            float acc = (j == r) ? 1.f : 0.f;
-#pragma unroll
-            for (int i4 = 0; i4 < j; i4 += 4) {
-                const f32x4 lrow = *(const f32x4*)(TM + j * kBlock + i4);  // same address in all lanes
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (i4 + i < j) acc -= lrow[i] * x[i4 + i];
-            }
-            x[j] = acc;
-        }
-        __builtin_amdgcn_wave_barrier();  // every lane has read L before it is overwritten
-        if (g == 0) {
-#pragma unroll
-            for (int j = 0; j < kBlock; ++j) TM[j * kBlock + r] = x[j];
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -655,12 +710,15 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
 template <class P, int VAR, int DK>
 struct BlockFrags {
     typedef typename P::frag frag;
-    frag fq[DK / 16];                          // qa rows of the block (tokens), all key dimensions
-    frag fkd[VAR == SLA_GDN ? DK / 16 : 1];    // delta rule: kd rows
-    frag fp;                                   // masked scores P^T
+    frag fq[DK / 16];                          // q rows of the block (GLA: decay-folded), all key dimensions
+    frag fkd[VAR == SLA_GDN ? DK / 16 : 1];    // delta rule: k rows
+    frag fp;                                   // masked, decayed scores P^T
     frag fv;                                   // v' of this wave's columns
     float gq;                                  // read gate of token r
-    f32x4 p1, bp, tm;                          // delta rule: p_j, beta_j p_j (j = 4g..4g+3), Tm[r][4g..4g+3]
+    // scalar-decay variants: cumulative log2-decay of token r, of tokens 4g..4g+3, of the block's last token
+    float ct, c16;
+    f32x4 cj;
+    f32x4 bt, tm;                              // delta rule: beta_j (j = 4g..4g+3), Tm[r][4g..4g+3]
 };
 
 template <class P, int VAR, int DK, int DVW>
@@ -674,12 +732,17 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
     const elem* QA = (const elem*)(buf + L::oQA);
 #pragma unroll
     for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
+    if constexpr (VAR != SLA_GLA) {
+        const float* C2 = (const float*)(buf + L::oP1) + I * kBlock;
+        f.ct = C2[r];
+        f.c16 = C2[kBlock - 1];
+        f.cj = *(const f32x4*)(C2 + 4 * g);
+    }
     if constexpr (VAR == SLA_GDN) {
         const elem* KD = (const elem*)(buf + L::oKD);
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
-        f.p1 = *(const f32x4*)((const float*)(buf + L::oP1) + I * kBlock + 4 * g);
-        f.bp = *(const f32x4*)((const float*)(buf + L::oBP) + I * kBlock + 4 * g);
+        f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + I * kBlock + 4 * g);
         f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + I * kBlock * kBlock + r * kBlock + 4 * g);
     }
     f.fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
@@ -697,7 +760,7 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
     constexpr int NTILE = DK / 16;
     constexpr int NBLK = kChunk / kBlock;
     const elem* KBT = (const elem*)(buf + L::oKBT);
-    const float* EA = (const float*)(buf + L::oEA);
+    [[maybe_unused]] const float* EA = (const float*)(buf + L::oEA);
     const int r = lane & 15, g = lane >> 4;
 
     SLA_STAMP(0);
@@ -707,50 +770,65 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
     for (int I = 0; I < NBLK; ++I) {
         // requests for later: the next block's operands and this block's state-step operands
         if (I + 1 < NBLK) load_block_frags<P, VAR, DK, DVW>(nxt, buf, I + 1, cw, lane);
-        f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
+        [[maybe_unused]] f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
         frag fk[NTILE];
         if constexpr (VAR == SLA_GLA) {
 #pragma unroll
             for (int s = 0; s < NTILE; ++s) ea[s] = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
-        } else {  // the decay of a block is one number for RetNet and the delta rule
-            const float e = EA[I * DK];
-            ea[0] = f32x4{e, e, e, e};
         }
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) fk[s] = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
 
-        frag fv = cur.fv;
-        if constexpr (VAR == SLA_GDN) {
-            // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
-            //   (I + L) U = beta G^K V - diag(beta p) K S,   K S = p (kd S)   =>   U = Tm R.
-            // U then takes the place of v' in the read-out and in the state step.
-            f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = kd_j S : lane holds column n = r, rows j = 4g + i
+        frag fv = cur.fv;    // v' for the read-out
+        frag fv2 = cur.fv;   // v' for the state step (scalar-decay variants: times 2^(c_16 - c_j))
+        [[maybe_unused]] float p_t = 1.f, A = 1.f;
+        if constexpr (VAR != SLA_GLA) {
+            p_t = fast_exp2(cur.ct);
+            A = fast_exp2(cur.c16);
+            f32x4 vs = P::to_acc(cur.fv);
+            if constexpr (VAR == SLA_GDN) {
+                // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
+                //   (I + L) U = beta G^K V - diag(beta p) K S   =>   U = Tm R,
+                // and U takes the place of v' in the read-out and in the state step.
+                f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = k_j S : lane holds column n = r, rows j = 4g + i
 #pragma unroll
-            for (int s = 0; s < NTILE; s += 2)
-                P::mma32(X, cur.fkd[s], cur.fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
-            const f32x4 vb = P::to_acc(fv);
-            f32x4 R;
+                for (int s = 0; s < NTILE; s += 2)
+                    P::mma32(X, cur.fkd[s], cur.fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
+                f32x4 R;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = vb[i] - cur.bp[i] * (cur.p1[i] * X[i]);
-            f32x4 U = {0.f, 0.f, 0.f, 0.f};
-            P::mma16(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
-            fv = P::from_acc(U);
+                for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.bt[i] * fast_exp2(cur.cj[i]) * X[i];
+                f32x4 U = {0.f, 0.f, 0.f, 0.f};
+                P::mma16(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
+                vs = U;
+                fv = P::from_acc(U);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vs[i] *= fast_exp2(cur.c16 - cur.cj[i]);
+            fv2 = P::from_acc(vs);
         }
 
-        // O^T[n][t] = sum_d S[d][n] qa[t][d] + sum_j v'[j][n] P[t][j]
+        // O^T[n][t] = p_t sum_d S[d][n] q[t][d] + sum_j v'[j][n] P[t][j]   (GLA: p_t is folded into q)
         f32x4 oT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NTILE; s += 2)
             P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
+        if constexpr (VAR != SLA_GLA) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) oT[i] *= p_t;
+        }
         P::mma16(oT, fv, cur.fp);
 
         // state step: S <- diag(A_I) S + kb^T v'
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) {
-            const f32x4 e = (VAR == SLA_GLA) ? ea[s] : ea[0];
+            if constexpr (VAR == SLA_GLA) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) S[s][i] *= e[i];
-            P::mma16(S[s], fk[s], fv);
+                for (int i = 0; i < 4; ++i) S[s][i] *= ea[s][i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) S[s][i] *= A;
+            }
+            P::mma16(S[s], fk[s], fv2);
         }
 
         // epilogue: read gate, cast, store 4 adjacent value columns of token t
@@ -805,8 +883,8 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     const int nchunks = (T + kChunk - 1) / kChunk;
 
     if (producer) {
-        float decay_const = 1.f;  // RetNet: gamma_h
-        if constexpr (VAR == SLA_RETNET) decay_const = fast_exp2(((const float*)a.ld)[h] * kLog2e);
+        float decay_const = 0.f;  // RetNet: log2 gamma_h
+        if constexpr (VAR == SLA_RETNET) decay_const = ((const float*)a.ld)[h] * kLog2e;
         Loader<P, VAR, DK, DVW, HG> ldr;
         ldr.init(a, b, h, n0, lane);
         // One register stage, refilled while it is consumed: the loads of a chunk are in flight for a
@@ -819,9 +897,8 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             if (cc < nchunks) {
                 const int tok0 = cc * kChunk + kBlock * pw;
 #if SLA_EXP != 2
-                elem* kp_scratch = (elem*)(smem + NBUF * L::bytes) + kBlock * pw * L::RS;  // delta rule only
-                produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, kp_scratch, pw,
-                                                   tok0, tok0 + kChunk, T, decay_const, lane SLA_TRACE_PASS);
+                produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, pw, tok0,
+                                                   tok0 + kChunk, T, decay_const, lane SLA_TRACE_PASS);
 #endif
             }
         };
