@@ -57,6 +57,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="gla_train")
     ap.add_argument("--dv-split", type=int, default=0)
+    ap.add_argument("--segments", type=int, default=0,
+                    help="segment-parallel schedule: 0 = the library chooses (one pass when the batch fills the "
+                         "device, as for the headline workload), 1 = one fused pass, n = n segments")
     ap.add_argument("--copy-bytes", type=int, default=0,
                     help="also run one plain device-to-device copy of this many bytes before the timed region "
                          "(a known-size kernel to calibrate the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -89,9 +92,19 @@ def main() -> int:
     out = torch.empty((w.B, w.T, w.H, w.dv), dtype=tdt, device=dev)
     fin = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
 
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, args.dv_split, 0,
+                           args.segments)
+    nseg = sla.sla_segments(params, cus)
+    if nseg < 1:
+        print(f"bench.py: {sla.sla_status_string(nseg)}", file=sys.stderr)
+        return 2
+    ws_bytes = sla.sla_workspace_bytes(params, cus)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+
     def step():
         sla.forward(w.variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], g["beta"], None,
-                    dv_split=args.dv_split, out=out, final_state=fin)
+                    dv_split=args.dv_split, out=out, final_state=fin, segments=nseg, workspace=ws)
 
     if args.copy_bytes > 0:
         src = torch.empty(args.copy_bytes, dtype=torch.uint8, device=dev).fill_(3)
@@ -122,8 +135,7 @@ def main() -> int:
     abytes = algorithmic_bytes(w)
     aflops = algorithmic_flops(w)
     achieved_gbs = abytes / (kernel_ms * 1e-3) / 1e9
-    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, args.dv_split, 0)
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    params.segments = nseg
     dvw = args.dv_split or sla.sla_default_dv_split(params, cus)
     params.dv_split = dvw
 
@@ -145,6 +157,7 @@ def main() -> int:
                         f"{w.dtype} in/out, fp32 state, dual head-softmax gates",
             "kernel": sla.sla_kernel_name(params),
             "dv_split": dvw,
+            "segments": nseg,
             "compute_units": cus,
         },
         "roofline": {

@@ -53,7 +53,8 @@ typedef enum {
     SLA_ERR_SHAPE = -2,       /* a size is negative or out of range */
     SLA_ERR_UNSUPPORTED = -3, /* variant / dtype / head dimension not built */
     SLA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
-    SLA_ERR_HIP = -5          /* the HIP runtime refused the launch (no device, bad stream, ...) */
+    SLA_ERR_HIP = -5,         /* the HIP runtime refused the launch (no device, bad stream, ...) */
+    SLA_ERR_WORKSPACE = -6    /* segments > 1 asked for, but no workspace or too small a one was given */
 } sla_status;
 
 /* Problem description (host memory, read during the call only). */
@@ -69,6 +70,12 @@ typedef struct {
                         A scheduling knob only: the result does not depend on it beyond nothing at all
                         (each output column is computed by exactly one workgroup in a fixed order). */
     int32_t flags;   /* must be 0 */
+    int32_t segments; /* schedule for shapes with few (batch, head) pairs, RetNet and GLA only: T is cut into
+                         this many segments that run in parallel (a pre-pass computes each segment's end state
+                         from a zero entry state, a small kernel chains them through the segments' decays, the
+                         main pass starts every segment from its entry state).  0 = the library chooses when a
+                         workspace is given (1 when there are enough rows to fill the device); 1 = one fused
+                         pass.  The result is the same up to fp32 rounding of the chained states. */
 } sla_params;
 
 /*
@@ -85,6 +92,8 @@ typedef struct {
  *   final_state     [B,H,dk,dv] fp32    written; NULL to skip.  May alias initial_state.
  *   stream          a hipStream_t passed as void* (NULL = the default stream)
  *
+ * sla_forward always runs one fused pass (p->segments must be 0 or 1); see sla_forward_ws.
+ *
  * All tensors are dense and row-major in the index order shown; pointers must
  * be 16-byte aligned.  B == 0 is a no-op.  T == 0 copies initial_state (or
  * zeros) to final_state.  Asynchronous: returns after enqueueing.
@@ -93,6 +102,24 @@ int sla_forward(const sla_params* p, const void* q, const void* k, const void* v
                 const float* q_head_logits, const float* k_head_logits,
                 const void* log_decay, const float* beta, const float* initial_state,
                 void* out, float* final_state, void* stream);
+
+/*
+ * sla_forward with a workspace (device memory, 16-byte aligned, owned by the caller, contents undefined on
+ * return), which lets the library use the segment-parallel schedule described at sla_params.segments: the
+ * sequential state carry of Sec. 3.2 ("passing the recurrent state between chunks") becomes a two-level scan.
+ * workspace may be NULL (then this is sla_forward).  With p->segments == 0 a workspace that is too small makes
+ * the call fall back to one fused pass; with p->segments > 1 it is SLA_ERR_WORKSPACE.
+ */
+int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void* v,
+                   const float* q_head_logits, const float* k_head_logits,
+                   const void* log_decay, const float* beta, const float* initial_state,
+                   void* out, float* final_state, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
+size_t sla_workspace_bytes(const sla_params* p, int compute_units);
+
+/* Number of segments the library would choose for *p given a workspace (>= 1); <0 on error. */
+int sla_segments(const sla_params* p, int compute_units);
 
 /*
  * Validates the same arguments as sla_forward (host-side checks only, touches no
@@ -104,7 +131,8 @@ int sla_check_args(const sla_params* p, const void* q, const void* k, const void
                    const void* log_decay, const float* beta, const float* initial_state,
                    const void* out, const float* final_state);
 
-/* Value columns per workgroup the library would choose for *p (the dv_split it resolves 0 to); <0 on error. */
+/* Value columns per workgroup the library would choose for *p (the dv_split it resolves 0 to); <0 on error.
+ * p->segments <= 1: the choice for one fused pass; > 1: the choice for that many segments. */
 int sla_default_dv_split(const sla_params* p, int compute_units);
 
 /* Name of the device kernel that sla_forward launches for *p (static string, host memory); NULL on error.

@@ -18,6 +18,9 @@ from .binding import (  # noqa: F401
     sla_check_args,
     sla_default_dv_split,
     sla_forward,
+    sla_forward_ws,
+    sla_segments,
+    sla_workspace_bytes,
     sla_kernel_name,
     sla_status_string,
     sla_version,

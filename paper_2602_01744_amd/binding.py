@@ -36,6 +36,7 @@ class SlaParams(ctypes.Structure):
         ("dv", ctypes.c_int32),
         ("dv_split", ctypes.c_int32),
         ("flags", ctypes.c_int32),
+        ("segments", ctypes.c_int32),
     ]
 
 
@@ -58,6 +59,12 @@ def load_library():
     pp = ctypes.POINTER(SlaParams)
     lib.sla_forward.restype = ctypes.c_int
     lib.sla_forward.argtypes = [pp] + [vp] * 11
+    lib.sla_forward_ws.restype = ctypes.c_int
+    lib.sla_forward_ws.argtypes = [pp] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.sla_workspace_bytes.restype = ctypes.c_size_t
+    lib.sla_workspace_bytes.argtypes = [pp, ctypes.c_int]
+    lib.sla_segments.restype = ctypes.c_int
+    lib.sla_segments.argtypes = [pp, ctypes.c_int]
     lib.sla_check_args.restype = ctypes.c_int
     lib.sla_check_args.argtypes = [pp] + [vp] * 10
     lib.sla_default_dv_split.restype = ctypes.c_int
@@ -88,6 +95,14 @@ def sla_default_dv_split(params: SlaParams, compute_units: int) -> int:
     return int(load_library().sla_default_dv_split(ctypes.byref(params), int(compute_units)))
 
 
+def sla_workspace_bytes(params: SlaParams, compute_units: int) -> int:
+    return int(load_library().sla_workspace_bytes(ctypes.byref(params), int(compute_units)))
+
+
+def sla_segments(params: SlaParams, compute_units: int) -> int:
+    return int(load_library().sla_segments(ctypes.byref(params), int(compute_units)))
+
+
 def sla_kernel_name(params: SlaParams) -> Optional[str]:
     s = load_library().sla_kernel_name(ctypes.byref(params))
     return None if s is None else s.decode()
@@ -116,6 +131,31 @@ def sla_forward(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, 
     )
 
 
+def sla_forward_ws(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state,
+                   workspace, workspace_bytes, stream) -> int:
+    """Raw call of the workspace-taking entry point (same conventions as sla_forward)."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_forward_ws(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta),
+            _p(initial_state), _p(out), _p(final_state), _p(workspace), int(workspace_bytes), _p(stream),
+        )
+    )
+
+
+_cus = {}
+
+
+def _compute_units(device) -> int:
+    import torch
+
+    i = torch.device(device).index
+    i = torch.cuda.current_device() if i is None else i
+    if i not in _cus:
+        _cus[i] = torch.cuda.get_device_properties(i).multi_processor_count
+    return _cus[i]
+
+
 def forward(
     variant: int,
     q,
@@ -131,9 +171,15 @@ def forward(
     out=None,
     final_state=None,
     want_final_state: bool = True,
+    segments: int = 1,
+    workspace=None,
 ) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
     """SLA forward on the current CUDA(HIP) device and stream.  Tensors must be contiguous CUDA tensors:
-    q,k [B,T,H,dk], v [B,T,H,dv] in float32 or bfloat16; logits/beta/initial_state float32."""
+    q,k [B,T,H,dk], v [B,T,H,dv] in float32 or bfloat16; logits/beta/initial_state float32.
+
+    segments = 1 runs one fused pass (sla_forward).  segments = 0 lets the library choose the
+    segment-parallel schedule, segments > 1 asks for that many segments (sla_forward_ws); the workspace
+    is then taken from ``workspace`` (a CUDA tensor of at least sla_workspace_bytes bytes) or allocated here."""
     import torch
 
     assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
@@ -154,12 +200,23 @@ def forward(
         out = torch.empty((B, T, H, dv), dtype=q.dtype, device=q.device)
     if final_state is None and want_final_state:
         final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
-    params = SlaParams(variant, dtype, B, T, H, dk, dv, dv_split, 0)
+    params = SlaParams(variant, dtype, B, T, H, dk, dv, dv_split, 0, segments)
     ptr = lambda t: None if t is None else t.data_ptr()
-    rc = sla_forward(
-        params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta),
-        ptr(initial_state), ptr(out), ptr(final_state), torch.cuda.current_stream(q.device).cuda_stream,
-    )
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    if segments == 1:
+        rc = sla_forward(
+            params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta),
+            ptr(initial_state), ptr(out), ptr(final_state), stream,
+        )
+    else:
+        need = sla_workspace_bytes(params, _compute_units(q.device))
+        if workspace is None and need > 0:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        rc = sla_forward_ws(
+            params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta),
+            ptr(initial_state), ptr(out), ptr(final_state), ptr(workspace), ws_bytes, stream,
+        )
     if rc != 0:
         raise SlaError(rc, sla_status_string(rc))
     return out, final_state

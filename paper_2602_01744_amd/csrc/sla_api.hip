@@ -7,9 +7,10 @@
 #include "sla.h"
 
 namespace sla {
-int launch_forward(const sla_params& p, int dvw, const void* q, const void* k, const void* v, const float* ql,
-                   const float* kl, const void* ld, const float* beta, const float* s0, void* out, float* sT,
-                   hipStream_t stream);
+int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k, const void* v,
+                   const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
+                   float* sT, float* workspace, hipStream_t stream);
+size_t segment_workspace_floats(const sla_params& p, int nseg);
 }
 
 namespace {
@@ -19,12 +20,13 @@ constexpr int kMaxHeads = 64;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check(const sla_params* p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
-          const void* ld, const float* beta, const float* s0, const void* out, const float* sT) {
+int check_params(const sla_params* p) {
     if (!p) return SLA_ERR_NULL;
     if (p->variant != SLA_RETNET && p->variant != SLA_GLA && p->variant != SLA_GDN) return SLA_ERR_UNSUPPORTED;
     if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
     if (p->flags != 0) return SLA_ERR_UNSUPPORTED;
+    if (p->segments < 0 || p->segments > 4096) return SLA_ERR_SHAPE;
+    if (p->segments > 1 && p->variant == SLA_GDN) return SLA_ERR_UNSUPPORTED;
     if (p->B < 0 || p->T < 0 || p->H < 1 || p->H > kMaxHeads) return SLA_ERR_SHAPE;
     if (p->dk < 1 || p->dv < 1) return SLA_ERR_SHAPE;
     if ((p->dk != 64 && p->dk != 128) || (p->dv != 64 && p->dv != 128)) return SLA_ERR_UNSUPPORTED;
@@ -42,6 +44,13 @@ int check(const sla_params* p, const void* q, const void* k, const void* v, cons
         const int64_t wide = p->dk > p->dv ? p->dk : p->dv;
         if (((int64_t)p->T + 256) * p->H * wide * es > (int64_t)INT32_MAX) return SLA_ERR_SHAPE;
     }
+    return SLA_OK;
+}
+
+int check(const sla_params* p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
+          const void* ld, const float* beta, const float* s0, const void* out, const float* sT) {
+    const int rc = check_params(p);
+    if (rc != SLA_OK) return rc;
     const bool empty = (p->B == 0);
     if (!empty && p->T > 0) {
         if (!q || !k || !v || !ql || !ld || !out) return SLA_ERR_NULL;
@@ -72,11 +81,30 @@ int device_compute_units() {
     return cached[dev];
 }
 
-int choose_dv_split(const sla_params& p, int cus) {
+constexpr int kMinSegment = 256;  // tokens; shorter segments are not worth a pre-pass
+
+// Segment-parallel schedule (RetNet, GLA): how many segments to cut T into so that, with 64-column
+// slices, every compute unit gets a workgroup.  1 = single fused pass.  seg_len is a multiple of 64.
+int choose_segments(const sla_params& p, int cus, int* seg_len) {
+    *seg_len = p.T;
+    if (p.variant == SLA_GDN || p.segments == 1) return 1;
+    const int64_t rows = (int64_t)p.B * p.H * (p.dv / (p.dv >= 64 ? 64 : p.dv));
+    int want = p.segments > 1 ? p.segments : (int)((cus + rows - 1) / rows);
+    if (want <= 1) return 1;
+    int len = (p.T + want - 1) / want;
+    len = ((len + 63) / 64) * 64;
+    if (len < kMinSegment) len = kMinSegment;
+    const int nseg = (p.T + len - 1) / len;
+    if (nseg <= 1) return 1;
+    *seg_len = len;
+    return nseg;
+}
+
+int choose_dv_split(const sla_params& p, int cus, int nseg = 1) {
     if (p.dv_split != 0) return p.dv_split;
     // The widest slice that still gives every compute unit a workgroup; narrower slices repeat the
     // per-token decay work of a head in more workgroups, so never go narrower than needed.
-    const int64_t seqs = (int64_t)p.B * p.H;
+    const int64_t seqs = (int64_t)p.B * p.H * nseg;
     const int widths[] = {64, 32, 16};
     for (int w : widths) {
         if (w > p.dv) continue;
@@ -95,18 +123,53 @@ int sla_check_args(const sla_params* p, const void* q, const void* k, const void
     return check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state);
 }
 
+int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                   const float* k_head_logits, const void* log_decay, const float* beta, const float* initial_state,
+                   void* out, float* final_state, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state);
+    if (rc != SLA_OK) return rc;
+    if (workspace && !aligned16(workspace)) return SLA_ERR_ALIGN;
+    if (p->B == 0) return SLA_OK;
+    if (p->T == 0 && !final_state) return SLA_OK;
+    int seg_len = p->T;
+    if (p->segments > 1) {  // an explicit request does not depend on the device: reject it before any HIP call
+        const int n = choose_segments(*p, 1, &seg_len);
+        if (n > 1 && (!workspace || sla::segment_workspace_floats(*p, n) * sizeof(float) > workspace_bytes))
+            return SLA_ERR_WORKSPACE;
+    }
+    const int cus = device_compute_units();
+    if (cus <= 0) return SLA_ERR_HIP;
+    int nseg = choose_segments(*p, cus, &seg_len);
+    if (nseg > 1 && (!workspace || sla::segment_workspace_floats(*p, nseg) * sizeof(float) > workspace_bytes)) {
+        nseg = 1;  // the library's own choice without room for it: one fused pass
+        seg_len = p->T;
+    }
+    const int dvw = choose_dv_split(*p, cus, nseg);
+    return sla::launch_forward(*p, dvw, nseg, seg_len, q, k, v, q_head_logits, k_head_logits, log_decay, beta,
+                               initial_state, out, final_state, (float*)workspace, (hipStream_t)stream);
+}
+
 int sla_forward(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
                 const float* k_head_logits, const void* log_decay, const float* beta, const float* initial_state,
                 void* out, float* final_state, void* stream) {
-    const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state);
+    return sla_forward_ws(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state,
+                          nullptr, 0, stream);
+}
+
+size_t sla_workspace_bytes(const sla_params* p, int compute_units) {
+    if (compute_units <= 0 || check_params(p) != SLA_OK || p->B == 0 || p->T == 0) return 0;
+    int seg_len = 0;
+    const int nseg = choose_segments(*p, compute_units, &seg_len);
+    return sla::segment_workspace_floats(*p, nseg) * sizeof(float);
+}
+
+int sla_segments(const sla_params* p, int compute_units) {
+    const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->B == 0) return SLA_OK;
-    if (p->T == 0 && !final_state) return SLA_OK;
-    const int cus = device_compute_units();
-    if (cus <= 0) return SLA_ERR_HIP;
-    const int dvw = choose_dv_split(*p, cus);
-    return sla::launch_forward(*p, dvw, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out,
-                               final_state, (hipStream_t)stream);
+    if (compute_units <= 0) return SLA_ERR_SHAPE;
+    if (p->B == 0 || p->T == 0) return 1;
+    int seg_len = 0;
+    return choose_segments(*p, compute_units, &seg_len);
 }
 
 int sla_default_dv_split(const sla_params* p, int compute_units) {
@@ -115,7 +178,9 @@ int sla_default_dv_split(const sla_params* p, int compute_units) {
     if ((p->dv != 64 && p->dv != 128) || p->B < 0 || p->H < 1) return SLA_ERR_SHAPE;
     sla_params c = *p;
     c.dv_split = 0;
-    return choose_dv_split(c, compute_units);
+    int seg_len = 0;
+    const int nseg = (c.segments > 1 && c.T > 0) ? choose_segments(c, compute_units, &seg_len) : 1;
+    return choose_dv_split(c, compute_units, nseg);
 }
 
 const char* sla_kernel_name(const sla_params* p) {
@@ -123,9 +188,9 @@ const char* sla_kernel_name(const sla_params* p) {
     if (!p) return nullptr;
     if (p->variant < 0 || p->variant > 2 || (p->dtype != SLA_F32 && p->dtype != SLA_BF16)) return nullptr;
     if (p->dv != 64 && p->dv != 128) return nullptr;
-    const int dvw = choose_dv_split(*p, 256);  // dv_split == 0 is resolved as on a 256-CU device
+    const int dvw = choose_dv_split(*p, 256, 1);  // dv_split == 0 is resolved as on a 256-CU device, one pass
     const int head_regs = p->H <= 16 ? 4 : (p->H <= 32 ? 8 : 16);
-    snprintf(buf, sizeof(buf), "sla_fwd_kernel<sla::%s, %d, %d, %d, %d>", p->dtype == SLA_BF16 ? "PrecBF16" : "PrecF32",
+    snprintf(buf, sizeof(buf), "sla_fwd_kernel<sla::%s, %d, %d, %d, %d, false>", p->dtype == SLA_BF16 ? "PrecBF16" : "PrecF32",
              p->variant, p->dk, dvw, head_regs);
     return buf;
 }
@@ -138,6 +203,7 @@ const char* sla_status_string(int status) {
         case SLA_ERR_UNSUPPORTED: return "variant, dtype, head width or flag not supported";
         case SLA_ERR_ALIGN: return "a pointer is not 16-byte aligned";
         case SLA_ERR_HIP: return "the HIP runtime refused the call";
+        case SLA_ERR_WORKSPACE: return "segments requested but the workspace is missing or too small";
         default: return "unknown status";
     }
 }

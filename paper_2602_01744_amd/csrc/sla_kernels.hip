@@ -67,6 +67,15 @@ struct KArgs {
     float* sT;
     int B, T, H, dv;
     int nslice;
+    // Segment-parallel schedule: T is cut into nseg segments of Ls tokens (the last may be shorter) and
+    // every (batch, segment) pair is scheduled like a batch row.  nseg_grid is the number of segments a
+    // launch covers: nseg for the main pass, nseg - 1 for the pre-pass that only computes the end state
+    // of each segment from a zero entry state.  ws_state[b][s][h] holds that state and, after the
+    // combine kernel, the entry state of segment s + 1; ws_decay[b][s][h][4][dk] the decay of segment s
+    // as four partial products (GLA).
+    int Ls, nseg, nseg_grid;
+    float* ws_state;
+    float* ws_decay;
 };
 
 #ifdef SLA_TRACE
@@ -282,14 +291,14 @@ struct Loader {
     int H;
     bool has_kl;
 
-    __device__ __forceinline__ void init(const KArgs& a, int b, int h, int n0, int lane) {
-        const int T = a.T;
+    // row_tok: index of the first token of the row in the [B*T] token space; T: tokens of the row
+    __device__ __forceinline__ void init(const KArgs& a, size_t row_tok, int T, int h, int n0, int lane) {
         H = a.H;
         has_kl = a.kl != nullptr;
         tstride_qk = H * DK * (int)sizeof(elem);
         tstride_v = H * a.dv * (int)sizeof(elem);
         tstride_lg = H * 4;
-        const size_t row_qk = (size_t)b * T * H * DK, row_v = (size_t)b * T * H * a.dv, row_lg = (size_t)b * T * H;
+        const size_t row_qk = row_tok * H * DK, row_v = row_tok * H * a.dv, row_lg = row_tok * H;
         rq = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.q + row_qk), 0, T * tstride_qk, kRsrcWord3);
         rk = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.k + row_qk), 0, T * tstride_qk, kRsrcWord3);
         rv = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.v + row_v), 0, T * tstride_v, kRsrcWord3);
@@ -486,7 +495,7 @@ __device__ __forceinline__ float row_prefix_sum(float x) {
 // values by 2^(c_16 - c_j).  Scores are scaled here: P[t,j] = (q_t . k_j) 2^(c_t - c_j) for j <= t.
 // Every factor is <= 1, whatever the decay.
 // ---------------------------------------------------------------------------------------------
-template <class P, int VAR, int DK, int DVW, int HG>
+template <class P, int VAR, int DK, int DVW, int HG, bool SO>
 __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>& st,
                                                      const Loader<P, VAR, DK, DVW, HG>& ldr, unsigned char* buf, int blk,
                                                      int tok0, int next_tok0, int T, float log2_gamma, int lane) {
@@ -523,16 +532,18 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
     // q and k as loaded
     elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
     elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
+    if constexpr (!SO) {
 #pragma unroll
-    for (int i = 0; i < kBlock; ++i) {
-        if constexpr (EPL == 2) {
-            *(pair*)(qrow + i * L::RS) = st.q[i];
-            *(pair*)(krow + i * L::RS) = st.k[i];
-        } else {
-            P::store1(qrow + i * L::RS, P::lo(st.q[i]));
-            P::store1(krow + i * L::RS, P::lo(st.k[i]));
+        for (int i = 0; i < kBlock; ++i) {
+            if constexpr (EPL == 2) {
+                *(pair*)(qrow + i * L::RS) = st.q[i];
+                *(pair*)(krow + i * L::RS) = st.k[i];
+            } else {
+                P::store1(qrow + i * L::RS, P::lo(st.q[i]));
+                P::store1(krow + i * L::RS, P::lo(st.k[i]));
+            }
+            ldr.load_q(st, next_tok0, i);
         }
-        ldr.load_q(st, next_tok0, i);
     }
     // k transposed
 #pragma unroll
@@ -547,25 +558,28 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 
     // scores of the block from this wave's own rows
     __builtin_amdgcn_wave_barrier();
-    frag fk_[NTILE];
-    f32x4 pT = {0.f, 0.f, 0.f, 0.f};
+    [[maybe_unused]] frag fk_[NTILE];
+    [[maybe_unused]] f32x4 cj;
+    if constexpr (!SO) {
+        f32x4 pT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < NTILE; s += 2) {
-        const frag q0 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
-        const frag q1 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
-        fk_[s] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
-        fk_[s + 1] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
-        P::mma32(pT, fk_[s], fk_[s + 1], q0, q1);  // P^T[j][t] = k_j . q_t
+        for (int s = 0; s < NTILE; s += 2) {
+            const frag q0 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
+            const frag q1 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
+            fk_[s] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
+            fk_[s + 1] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
+            P::mma32(pT, fk_[s], fk_[s + 1], q0, q1);  // P^T[j][t] = k_j . q_t
+        }
+        cj = *(const f32x4*)(C2 + 4 * g);  // rows j = 4g + i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] * fast_exp2(c_lane - cj[i]) : 0.f;
+        ((frag*)(buf + L::oPT))[blk * 64 + lane] = P::from_acc(pT);
     }
-    const f32x4 cj = *(const f32x4*)(C2 + 4 * g);  // rows j = 4g + i
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pT[i] = (4 * g + i <= r) ? pT[i] * fast_exp2(c_lane - cj[i]) : 0.f;
-    ((frag*)(buf + L::oPT))[blk * 64 + lane] = P::from_acc(pT);
 
     stage_values<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
 
     // delta rule: Tm = (I + L)^-1 with L[j][t] = beta_j 2^(c_j - c_t) (k_j . k_t) for t < j (strictly lower)
-    if constexpr (VAR == SLA_GDN) {
+    if constexpr (VAR == SLA_GDN && !SO) {
         f32x4 G = {0.f, 0.f, 0.f, 0.f};  // G[j][t] = k_j . k_t: lane holds column t = r, rows j = 4g + i
 #pragma unroll
         for (int s = 0; s < NTILE; s += 2) P::mma32(G, fk_[s], fk_[s + 1], fk_[s], fk_[s + 1]);
@@ -604,12 +618,12 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 // after its last use, so the loads are spread through the arithmetic instead of queueing up in a burst.
 // This is the path of GLA, whose decay is a vector over the key dimensions and has to be folded into
 // q and k element by element.
-template <class P, int VAR, int DK, int DVW, int HG>
+template <class P, int VAR, int DK, int DVW, int HG, bool SO>
 __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
                                               unsigned char* buf, int blk, int tok0, int next_tok0, int T,
-                                              float decay_const, int lane SLA_TRACE_PARAM) {
+                                              float decay_const, float (&dacc)[DK / 64], int lane SLA_TRACE_PARAM) {
     if constexpr (VAR != SLA_GLA) {
-        produce_block_scalar<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, tok0, next_tok0, T, decay_const, lane);
+        produce_block_scalar<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, blk, tok0, next_tok0, T, decay_const, lane);
         return;
     }
     SLA_STAMP(0);
@@ -643,17 +657,20 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     for (int i = 0; i < kBlock; ++i) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) pre[e] *= al[e][i];
-        if constexpr (EPL == 2)
-            *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
-        else
-            P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
-        ldr.load_q(st, next_tok0, i);
+        if constexpr (!SO) {
+            if constexpr (EPL == 2)
+                *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
+            else
+                P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
+            ldr.load_q(st, next_tok0, i);
+        }
     }
     float invA[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
         invA[e] = fast_rcp(pre[e]);
         EA[blk * DK + EPL * lane + e] = pre[e];
+        if constexpr (SO) dacc[e] *= pre[e];
     }
     SLA_STAMP(3);
     // backward: kb_j = k_j prod_{i>j} alpha_i ; kd_j = kb_j / A
@@ -665,10 +682,12 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         kb[0][i] = P::lo(st.k[i]) * suf[0];
         if constexpr (EPL == 2) kb[1][i] = P::hi(st.k[i]) * suf[1];
         ldr.load_k(st, next_tok0, i);
-        if constexpr (EPL == 2)
-            *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
-        else
-            P::store1(krow + i * L::RS, kb[0][i] * invA[0]);
+        if constexpr (!SO) {
+            if constexpr (EPL == 2)
+                *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
+            else
+                P::store1(krow + i * L::RS, kb[0][i] * invA[0]);
+        }
 #pragma unroll
         for (int e = 0; e < EPL; ++e) suf[e] *= al[e][i];
     }
@@ -679,7 +698,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     // Scores of the block, P^T[j][t] = kd_j . qa_t for j <= t (else 0), from this wave's own rows
     // (its LDS operations execute in order, so the rows written above are visible to it), stored as the
     // MFMA operand every consumer wave reads: lane (r, g) keeps column t = r, rows j = 4g..4g+3.
-    {
+    if constexpr (!SO) {
         typedef typename P::frag frag;
         constexpr int NTILE = DK / 16;
         const int r_ = lane & 15, g_ = lane >> 4;
@@ -721,7 +740,7 @@ struct BlockFrags {
     f32x4 bt, tm;                              // delta rule: beta_j (j = 4g..4g+3), Tm[r][4g..4g+3]
 };
 
-template <class P, int VAR, int DK, int DVW>
+template <class P, int VAR, int DK, int DVW, bool SO>
 __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, const unsigned char* buf, int I, int cw,
                                                  int lane) {
     typedef typename P::elem elem;
@@ -730,8 +749,12 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
     constexpr int NTILE = DK / 16;
     const int r = lane & 15, g = lane >> 4, trow = kBlock * I + r;
     const elem* QA = (const elem*)(buf + L::oQA);
+    if constexpr (!SO) {
 #pragma unroll
-    for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
+        for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
+        f.fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
+        f.gq = ((const float*)(buf + L::oGQ))[trow];
+    }
     if constexpr (VAR != SLA_GLA) {
         const float* C2 = (const float*)(buf + L::oP1) + I * kBlock;
         f.ct = C2[r];
@@ -745,12 +768,10 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
         f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + I * kBlock + 4 * g);
         f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + I * kBlock * kBlock + r * kBlock + 4 * g);
     }
-    f.fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
     f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
-    f.gq = ((const float*)(buf + L::oGQ))[trow];
 }
 
-template <class P, int VAR, int DK, int DVW>
+template <class P, int VAR, int DK, int DVW, bool SO>
 __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigned char* buf, int cw, int chunk_tok0,
                                               int T, typename P::elem* out_row, size_t out_tstride,
                                               int lane SLA_TRACE_PARAM) {
@@ -765,11 +786,11 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
 
     SLA_STAMP(0);
     BlockFrags<P, VAR, DK> cur, nxt;
-    load_block_frags<P, VAR, DK, DVW>(cur, buf, 0, cw, lane);
+    load_block_frags<P, VAR, DK, DVW, SO>(cur, buf, 0, cw, lane);
 #pragma unroll
     for (int I = 0; I < NBLK; ++I) {
         // requests for later: the next block's operands and this block's state-step operands
-        if (I + 1 < NBLK) load_block_frags<P, VAR, DK, DVW>(nxt, buf, I + 1, cw, lane);
+        if (I + 1 < NBLK) load_block_frags<P, VAR, DK, DVW, SO>(nxt, buf, I + 1, cw, lane);
         [[maybe_unused]] f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
         frag fk[NTILE];
         if constexpr (VAR == SLA_GLA) {
@@ -809,14 +830,16 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
 
         // O^T[n][t] = p_t sum_d S[d][n] q[t][d] + sum_j v'[j][n] P[t][j]   (GLA: p_t is folded into q)
         f32x4 oT = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (!SO) {
 #pragma unroll
-        for (int s = 0; s < NTILE; s += 2)
-            P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
-        if constexpr (VAR != SLA_GLA) {
+            for (int s = 0; s < NTILE; s += 2)
+                P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
+            if constexpr (VAR != SLA_GLA) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) oT[i] *= p_t;
+                for (int i = 0; i < 4; ++i) oT[i] *= p_t;
+            }
+            P::mma16(oT, fv, cur.fp);
         }
-        P::mma16(oT, fv, cur.fp);
 
         // state step: S <- diag(A_I) S + kb^T v'
 #pragma unroll
@@ -832,7 +855,7 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
         }
 
         // epilogue: read gate, cast, store 4 adjacent value columns of token t
-        {
+        if constexpr (!SO) {
             const int t = chunk_tok0 + kBlock * I + r;
             float o[4];
 #pragma unroll
@@ -852,7 +875,7 @@ __device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigne
 // ---------------------------------------------------------------------------------------------
 static constexpr int kThreads = 2 * kWaves * 64;
 
-template <class P, int VAR, int DK, int DVW, int HG>
+template <class P, int VAR, int DK, int DVW, int HG, bool SO>
 __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     typedef typename P::elem elem;
     typedef Smem<P, DK, DVW> L;
@@ -876,29 +899,35 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     const int total = gridDim.x;
     const int id = blockIdx.x;
     const int logical = (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
-    const int slice = logical % a.nslice, bh = logical / a.nslice;
-    const int b = bh / a.H, h = bh % a.H;
+    const int slice = logical % a.nslice, rowh = logical / a.nslice;
+    const int row = rowh / a.H, h = rowh % a.H;          // row = (batch, segment)
+    const int b = row / a.nseg_grid, seg = row % a.nseg_grid;
     const int n0 = slice * DVW;
-    const int T = a.T, H = a.H, dv = a.dv;
+    const int H = a.H, dv = a.dv;
+    const int T = min(a.Ls, a.T - seg * a.Ls);            // tokens of this row
+    const size_t row_tok = (size_t)b * a.T + (size_t)seg * a.Ls;
     const int nchunks = (T + kChunk - 1) / kChunk;
 
     if (producer) {
         float decay_const = 0.f;  // RetNet: log2 gamma_h
         if constexpr (VAR == SLA_RETNET) decay_const = ((const float*)a.ld)[h] * kLog2e;
         Loader<P, VAR, DK, DVW, HG> ldr;
-        ldr.init(a, b, h, n0, lane);
+        ldr.init(a, row_tok, T, h, n0, lane);
         // One register stage, refilled while it is consumed: the loads of a chunk are in flight for a
         // whole chunk period.  Past the end of the sequence every load is out of range: it returns
         // zero without touching memory, and nothing staged from it is ever read.
         Stage<P, VAR, DK, DVW, HG> st;
         ldr.load(st, kBlock * pw, lane);
+        float dacc[DK / 64];  // pre-pass, GLA: decay of the blocks this wave staged, per owned key dimension
+#pragma unroll
+        for (int e = 0; e < DK / 64; ++e) dacc[e] = 1.f;
         SLA_TRACE_DECL
         auto stage_chunk = [&](int cc) {
             if (cc < nchunks) {
                 const int tok0 = cc * kChunk + kBlock * pw;
 #if SLA_EXP != 2
-                produce_block<P, VAR, DK, DVW, HG>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, pw, tok0,
-                                                   tok0 + kChunk, T, decay_const, lane SLA_TRACE_PASS);
+                produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, pw, tok0,
+                                                       tok0 + kChunk, T, decay_const, dacc, lane SLA_TRACE_PASS);
 #endif
             }
         };
@@ -926,6 +955,11 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
                 }
             }
         }
+        if constexpr (SO && VAR == SLA_GLA) {
+            float* dp = a.ws_decay + (((size_t)(b * (a.nseg - 1) + seg) * H + h) * kWaves + pw) * DK + (DK / 64) * lane;
+#pragma unroll
+            for (int e = 0; e < DK / 64; ++e) dp[e] = dacc[e];
+        }
         return;
     }
 
@@ -936,14 +970,29 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     f32x4 S[NTILE];
 #pragma unroll
     for (int s = 0; s < NTILE; ++s) S[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const size_t s_off = ((size_t)bh * DK + 4 * g) * dv + n0 + 16 * cw + r;
-    if (active && a.s0) {
+    // Entry state: the caller's (or zero) in a single pass; with segments, slot seg of the workspace, which
+    // the combine kernel has filled (slot 0 with the caller's state, so that final_state may alias it).
+    // The pre-pass starts from zero and leaves the end state of segment seg in slot seg + 1.
+    const size_t lane_off = (size_t)(4 * g) * dv + n0 + 16 * cw + r;
+    const size_t head_sz = (size_t)DK * dv;
+    const float* s_in = nullptr;
+    float* s_out = nullptr;
+    if constexpr (SO) {
+        s_out = a.ws_state + ((size_t)(b * a.nseg + seg + 1) * H + h) * head_sz + lane_off;
+    } else {
+        if (a.nseg > 1)
+            s_in = a.ws_state + ((size_t)(b * a.nseg + seg) * H + h) * head_sz + lane_off;
+        else if (a.s0)
+            s_in = a.s0 + ((size_t)b * H + h) * head_sz + lane_off;
+        if (seg == a.nseg - 1 && a.sT) s_out = a.sT + ((size_t)b * H + h) * head_sz + lane_off;
+    }
+    if (active && s_in) {
 #pragma unroll
         for (int s = 0; s < NTILE; ++s)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) S[s][i] = a.s0[s_off + (size_t)(16 * s + i) * dv];
+            for (int i = 0; i < 4; ++i) S[s][i] = s_in[(size_t)(16 * s + i) * dv];
     }
-    elem* out_row = (elem*)a.out + ((size_t)b * T * H + h) * dv + n0 + 16 * cw + 4 * g;
+    elem* out_row = (elem*)a.out + (row_tok * H + h) * dv + n0 + 16 * cw + 4 * g;
     const size_t out_tstride = (size_t)H * dv;
 
     // Barrier count per pair of chunks matches the producers' (two steps per pair, also for an odd tail).
@@ -955,7 +1004,7 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             for (int u = 0; u < 2; ++u) {
 #if SLA_EXP != 1
                 if (active && c + u < nchunks)
-                    consume_chunk<P, VAR, DK, DVW>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride,
+                    consume_chunk<P, VAR, DK, DVW, SO>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride,
                                                    lane SLA_TRACE_PASS);
 #endif
                 __syncthreads();
@@ -969,17 +1018,17 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             for (int u = 0; u < 2; ++u) {
                 __syncthreads();
                 if (active && c + u < nchunks)
-                    consume_chunk<P, VAR, DK, DVW>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane SLA_TRACE_PASS);
+                    consume_chunk<P, VAR, DK, DVW, SO>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane SLA_TRACE_PASS);
                 __syncthreads();
             }
         }
     }
 
-    if (active && a.sT) {
+    if (active && s_out) {
 #pragma unroll
         for (int s = 0; s < NTILE; ++s)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a.sT[s_off + (size_t)(16 * s + i) * dv] = S[s][i];
+            for (int i = 0; i < 4; ++i) s_out[(size_t)(16 * s + i) * dv] = S[s][i];
     }
 }
 
@@ -992,10 +1041,10 @@ __global__ void sla_state_passthrough_kernel(const float* s0, float* sT, size_t 
 // ---------------------------------------------------------------------------------------------
 // Launch
 // ---------------------------------------------------------------------------------------------
-template <class P, int VAR, int DK, int DVW, int HG>
-static int launch(const KArgs& a, hipStream_t stream) {
+template <class P, int VAR, int DK, int DVW, int HG, bool SO>
+static int launch_one(const KArgs& a, hipStream_t stream) {
     typedef Smem<P, DK, DVW> L;
-    auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG>;
+    auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG, SO>;
     const size_t lds = L::total(VAR);
     static_assert(DVW == 64 || L::total(VAR) <= L::limit, "stage buffers exceed the LDS of a CU");
     if (lds > L::limit) return SLA_ERR_UNSUPPORTED;
@@ -1007,9 +1056,59 @@ static int launch(const KArgs& a, hipStream_t stream) {
         }
         configured = true;
     }
-    const int grid = a.B * a.H * a.nslice;
+    const int grid = a.B * a.nseg_grid * a.H * a.nslice;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+// Segment combine (between the pre-pass and the main pass of the segment-parallel schedule):
+//   E_0 = initial state,  E_{s+1} = diag(D_s) E_s + L_s,
+// with L_s the end state of segment s from a zero entry state (the pre-pass left it in slot s + 1) and
+// D_s its total decay.  Slot s ends up holding E_s.  One thread per (batch, head, d, 4 value columns).
+template <int VAR>
+__global__ void sla_segment_combine_kernel(const KArgs a, int dk) {
+    const int dv4 = a.dv / 4;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t per_head = (size_t)dk * dv4;
+    if (idx >= (size_t)a.B * a.H * per_head) return;
+    const int bh = (int)(idx / per_head), b = bh / a.H, h = bh % a.H;
+    const int d = (int)((idx % per_head) / dv4), n = (int)(idx % dv4) * 4;
+    const size_t head_sz = (size_t)dk * a.dv, off = (size_t)d * a.dv + n;
+    f32x4 E = {0.f, 0.f, 0.f, 0.f};
+    if (a.s0) E = *(const f32x4*)(a.s0 + (size_t)bh * head_sz + off);
+    *(f32x4*)(a.ws_state + ((size_t)(b * a.nseg) * a.H + h) * head_sz + off) = E;
+    for (int s = 0; s + 1 < a.nseg; ++s) {
+        float D;
+        if constexpr (VAR == SLA_GLA) {
+            const float* dp = a.ws_decay + ((size_t)(b * (a.nseg - 1) + s) * a.H + h) * kWaves * dk + d;
+            D = dp[0] * dp[dk] * dp[2 * dk] * dp[3 * dk];
+        } else {
+            D = fast_exp2(((const float*)a.ld)[h] * kLog2e * (float)a.Ls);  // segments before the last are full
+        }
+        f32x4* Lp = (f32x4*)(a.ws_state + ((size_t)(b * a.nseg + s + 1) * a.H + h) * head_sz + off);
+        const f32x4 Lseg = *Lp;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) E[i] = D * E[i] + Lseg[i];
+        *Lp = E;
+    }
+}
+
+// One call = one fused launch, or (segment-parallel schedule, RetNet and GLA) pre-pass + combine + main pass.
+template <class P, int VAR, int DK, int DVW, int HG>
+static int launch(const KArgs& a, hipStream_t stream) {
+    if (a.nseg <= 1) return launch_one<P, VAR, DK, DVW, HG, false>(a, stream);
+    if constexpr (VAR == SLA_GDN) {
+        return SLA_ERR_UNSUPPORTED;  // the delta rule's segment transition is a dense matrix; not built
+    } else {
+        KArgs pre = a;
+        pre.nseg_grid = a.nseg - 1;
+        int rc = launch_one<P, VAR, DK, DVW, HG, true>(pre, stream);
+        if (rc != SLA_OK) return rc;
+        const size_t n = (size_t)a.B * a.H * DK * (a.dv / 4);
+        hipLaunchKernelGGL(sla_segment_combine_kernel<VAR>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a, DK);
+        if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
+        return launch_one<P, VAR, DK, DVW, HG, false>(a, stream);
+    }
 }
 
 template <class P, int VAR, int DK, int DVW>
@@ -1057,12 +1156,22 @@ static int dispatch_variant(const KArgs& a, int variant, int dk, int dvw, hipStr
     }
 }
 
-int launch_forward(const sla_params& p, int dvw, const void* q, const void* k, const void* v, const float* ql,
-                   const float* kl, const void* ld, const float* beta, const float* s0, void* out, float* sT,
-                   hipStream_t stream) {
+// Floats of workspace the segment-parallel schedule needs for nseg segments.
+size_t segment_workspace_floats(const sla_params& p, int nseg) {
+    if (nseg <= 1) return 0;
+    const size_t heads = (size_t)p.B * p.H;
+    return heads * nseg * p.dk * p.dv + heads * (nseg - 1) * kWaves * p.dk;  // entry states, decay products
+}
+
+int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k, const void* v,
+                   const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
+                   float* sT, float* workspace, hipStream_t stream) {
     KArgs a;
     a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = beta; a.s0 = s0; a.out = out; a.sT = sT;
     a.B = p.B; a.T = p.T; a.H = p.H; a.dv = p.dv; a.nslice = p.dv / dvw;
+    a.nseg = nseg; a.nseg_grid = nseg; a.Ls = nseg > 1 ? seg_len : p.T;
+    a.ws_state = workspace;
+    a.ws_decay = workspace ? workspace + (size_t)p.B * nseg * p.H * p.dk * p.dv : nullptr;
     if (p.T == 0) {
         if (!sT) return SLA_OK;
         const size_t n = (size_t)p.B * p.H * p.dk * p.dv;

@@ -40,14 +40,14 @@ def to_device(d, dtype: str, variant: int):
     ), tdt
 
 
-def run_gpu(variant, d, dtype, initial_state=None, dv_split=0, want_final_state=True):
+def run_gpu(variant, d, dtype, initial_state=None, dv_split=0, want_final_state=True, segments=1):
     import torch
     import paper_2602_01744_amd as sla
 
     g, _ = to_device(d, dtype, variant)
     s0 = None if initial_state is None else torch.from_numpy(np.ascontiguousarray(initial_state, dtype=np.float32)).to("cuda:0")
     out, fin = sla.forward(variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], g["beta"],
-                           s0, dv_split=dv_split, want_final_state=want_final_state)
+                           s0, dv_split=dv_split, want_final_state=want_final_state, segments=segments)
     torch.cuda.synchronize()
     o = out.to(torch.float32).cpu().numpy().astype(np.float64)
     f = None if fin is None else fin.cpu().numpy().astype(np.float64)
@@ -76,14 +76,14 @@ def worst_slice_err(x, ref, head_axis):
     return float(np.max(r))
 
 
-def check(variant, d, dtype, initial_state=None, dv_split=0, tol=None, label=""):
+def check(variant, d, dtype, initial_state=None, dv_split=0, tol=None, label="", segments=1):
     tol = TOL[dtype] if tol is None else tol
-    o, f = run_gpu(variant, d, dtype, initial_state, dv_split)
+    o, f = run_gpu(variant, d, dtype, initial_state, dv_split, segments=segments)
     ro, rf = run_oracle(variant, d, initial_state)
     assert np.all(np.isfinite(o)), f"{label}: non-finite output"
     assert np.all(np.isfinite(f)), f"{label}: non-finite state"
     eo, ef = rel_err(o, ro), rel_err(f, rf)
-    print(f"[parity] {label} dtype={dtype} dv_split={dv_split} out_err={eo:.3e} state_err={ef:.3e} "
+    print(f"[parity] {label} dtype={dtype} dv_split={dv_split} segments={segments} out_err={eo:.3e} state_err={ef:.3e} "
           f"worst_head_out={worst_slice_err(o, ro, 2):.3e}", flush=True)
     assert eo <= tol, f"{label}: output error {eo:.3e} > {tol}"
     assert ef <= tol, f"{label}: state error {ef:.3e} > {tol}"

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert sla.sla_version() >= 100
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         assert sla.sla_status_string(code)
     assert "unknown" in sla.sla_status_string(-99)
 
@@ -108,6 +108,39 @@ def test_default_slice_width_fills_the_device(lib):
     assert sla.sla_default_dv_split(_ok_params(), 0) == -2
     name = sla.sla_kernel_name(_ok_params(B=8, H=16))
     assert name.startswith("sla_fwd_kernel<") and "128, 64" in name
+
+
+def test_segment_schedule_choice_and_workspace_size(lib):
+    # enough rows to fill the device: one pass, no workspace
+    assert sla.sla_segments(_ok_params(B=8, T=2048, H=16), 256) == 1
+    assert sla.sla_workspace_bytes(_ok_params(B=8, T=2048, H=16), 256) == 0
+    # 32 (batch, head) pairs x 2 slices of 64 columns on 256 CUs: 4 segments of 512 tokens
+    p = _ok_params(B=4, T=2048, H=8)
+    assert sla.sla_segments(p, 256) == 4
+    heads = 4 * 8
+    assert sla.sla_workspace_bytes(p, 256) == 4 * (heads * 4 * 128 * 128 + heads * 3 * 4 * 128)
+    # segments are at least 256 tokens and a multiple of 64; short sequences stay in one pass
+    assert sla.sla_segments(_ok_params(B=1, T=300, H=1), 256) == 2
+    assert sla.sla_segments(_ok_params(B=1, T=256, H=1), 256) == 1
+    assert sla.sla_segments(_ok_params(B=1, T=16384, H=4), 256) == 32
+    # an explicit request is honoured down to the minimum segment length
+    assert sla.sla_segments(_ok_params(B=8, T=2048, H=16, segments=3), 256) == 3
+    assert sla.sla_segments(_ok_params(B=8, T=2048, H=16, segments=64), 256) == 8
+    assert sla.sla_segments(_ok_params(B=8, T=2048, H=16, segments=1), 256) == 1
+    # the delta rule has no segment schedule
+    assert sla.sla_segments(_ok_params(variant=sla.GDN, B=1, T=4096, H=4), 256) == 1
+    assert sla.sla_segments(_ok_params(variant=sla.GDN, segments=2), 256) == -3
+    assert sla.sla_segments(_ok_params(segments=-1), 256) == -2
+    assert sla.sla_workspace_bytes(_ok_params(segments=-1), 256) == 0
+
+
+def test_segments_need_a_workspace(lib):
+    p = _ok_params(B=1, T=1024, H=2, segments=2)
+    assert sla.sla_forward(p, A, A, A, A, A, A, 0, 0, A, A, 0) == -6
+    assert _call(_ok_params(variant=sla.GDN, segments=2), beta=A) == -3
+    assert sla.sla_forward_ws(_ok_params(dk=96), A, A, A, A, A, A, 0, 0, A, A, A, 1 << 30, 0) == -3
+    assert sla.sla_forward_ws(_ok_params(), A, A, A, A, A, A, 0, 0, A, A, A + 4, 1 << 30, 0) == -4
+    assert sla.sla_forward_ws(_ok_params(B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):
