@@ -49,7 +49,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 static constexpr float kLog2e = 1.4426950408889634f;
-static constexpr int kChunk = 64;   // tokens staged in LDS at a time
+static constexpr int kMaxSlots = 8; // LDS ring slots = producer waves (at most)
 static constexpr int kBlock = 16;   // tokens per state step
 static constexpr int kWaves = 4;
 static constexpr uint32_t kRsrcWord3 = 0x00020000u;  // raw buffer descriptor, 32-bit data format
@@ -71,9 +71,10 @@ struct KArgs {
     // every (batch, segment) pair is scheduled like a batch row.  nseg_grid is the number of segments a
     // launch covers: nseg for the main pass, nseg - 1 for the pre-pass that only computes the end state
     // of each segment from a zero entry state.  ws_state[b][s][h] holds that state and, after the
-    // combine kernel, the entry state of segment s + 1; ws_decay[b][s][h][4][dk] the decay of segment s
-    // as four partial products (GLA).
+    // combine kernel, the entry state of segment s + 1; ws_decay[b][s][h][8][dk] the decay of segment s
+    // as partial products, one per producer wave (GLA).
     int Ls, nseg, nseg_grid;
+    int nparts;  // producer waves of the pre-pass: partial decay products per segment in ws_decay
     float* ws_state;
     float* ws_decay;
 };
@@ -91,7 +92,7 @@ __device__ unsigned long long* d_trace = nullptr;
     do {                                                                                                       \
         if (d_trace && (chunk) * 8 + 7 < kTraceRec && (threadIdx.x & 63) == 0) {                                \
             for (int k_ = 0; k_ < 8; ++k_)                                                                      \
-                d_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * kTraceRec + (chunk) * 8 + k_] = trace_t[k_]; \
+                d_trace[((size_t)blockIdx.x * 12 + (threadIdx.x >> 6)) * kTraceRec + (chunk) * 8 + k_] = trace_t[k_]; \
         }                                                                                                      \
     } while (0)
 #else
@@ -161,6 +162,10 @@ struct PrecBF16 {
         const frag z = {0, 0, 0, 0};
         mma32(c, a, z, b, z);
     }
+    // The 16-slot opcode itself, for accumulators that the 32-slot opcode never writes (the state tiles).
+    static __device__ __forceinline__ void mma16_only(f32x4& c, frag a, frag b) {
+        c = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+    }
 };
 
 struct PrecF32 {
@@ -185,6 +190,7 @@ struct PrecF32 {
 #pragma unroll
         for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[i], c, 0, 0, 0);
     }
+    static __device__ __forceinline__ void mma16_only(f32x4& c, frag a, frag b) { mma16(c, a, b); }
     static __device__ __forceinline__ void mma32(f32x4& c, frag a0, frag a1, frag b0, frag b1) {
         mma16(c, a0, b0);
         mma16(c, a1, b1);
@@ -226,35 +232,40 @@ __device__ __forceinline__ void store_run(typename P::elem* dst, const float (&x
 // ---------------------------------------------------------------------------------------------
 // LDS geometry
 // ---------------------------------------------------------------------------------------------
-template <class P, int DK, int DVW>
+template <class P, int VAR, int DK, int DVW>
 struct Smem {
     typedef typename P::elem elem;
     static constexpr int kPad = 16 / sizeof(elem);   // 16 bytes of padding per row
     static constexpr int RS = DK + kPad;             // row stride of the row-major [token][d] arrays
     // Token-major [d or n][token] arrays: a producer lane writes rows 2l and 2l+1, a consumer lane
-    // reads row r.  With 2-byte elements a stride of 136 bytes (34 banks) puts the 16 lanes that
-    // an 8-byte access serves per cycle on 16 distinct bank pairs for both patterns.
-    static constexpr int TS = kChunk + (sizeof(elem) == 2 ? 4 : 4);
+    // reads row r.  With 2-byte elements a stride of 40 bytes (10 banks) puts the 16 lanes that an
+    // 8-byte access serves per cycle on 16 distinct bank pairs for the consumers' pattern.
+    static constexpr int TS = kBlock + 4;
+    // One slot holds the operands of one 16-token block.
     static constexpr size_t oQA = 0;
-    static constexpr size_t oKD = oQA + sizeof(elem) * kChunk * RS;
-    static constexpr size_t oKBT = oKD + sizeof(elem) * kChunk * RS;
+    static constexpr size_t oKD = oQA + sizeof(elem) * kBlock * RS;
+    static constexpr size_t oKBT = oKD + sizeof(elem) * kBlock * RS;
     static constexpr size_t oVT = oKBT + sizeof(elem) * DK * TS;
     static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
-    static constexpr size_t oGQ = oEA + sizeof(float) * (kChunk / kBlock) * DK;
-    static constexpr size_t oGK = oGQ + sizeof(float) * kChunk;
-    // masked scores P^T of each block as the consumers' MFMA operand: one 4-slot fragment per lane
-    static constexpr size_t oPT = oGK + sizeof(float) * kChunk;
-    static constexpr size_t oPTend = oPT + (kChunk / kBlock) * 64 * 4 * sizeof(elem);
-    // scalar-decay variants (kept in every layout; 5 KB): per block the inverse Tm = (I + L)^-1 [16][16] of the
-    // delta rule; per token the cumulative log2-decay c_t (in "P1"), beta_t ("BT"); "BP" is spare
-    static constexpr size_t oTM = oPTend;
-    static constexpr size_t oP1 = oTM + sizeof(float) * (kChunk / kBlock) * kBlock * kBlock;
-    static constexpr size_t oBP = oP1 + sizeof(float) * kChunk;
-    static constexpr size_t oBT = oBP + sizeof(float) * kChunk;
-    static constexpr size_t bytes = oBT + sizeof(float) * kChunk;
+    static constexpr size_t oGQ = oEA + (VAR == SLA_GLA ? sizeof(float) * DK : 0);
+    static constexpr size_t oGK = oGQ + sizeof(float) * kBlock;
+    // masked scores P^T of the block as the consumers' MFMA operand: one 4-slot fragment per lane
+    static constexpr size_t oPT = oGK + sizeof(float) * kBlock;
+    // scalar-decay variants: per token the cumulative log2-decay c_t ("P1") and beta_t ("BT"); delta
+    // rule: the inverse Tm = (I + L)^-1 [16][16] of the block
+    static constexpr size_t oP1 = oPT + 64 * 4 * sizeof(elem);
+    static constexpr size_t oBT = oP1 + sizeof(float) * kBlock;
+    static constexpr size_t oTM = oBT + sizeof(float) * kBlock;
+    static constexpr size_t bytes = oTM + (VAR == SLA_GDN ? sizeof(float) * kBlock * kBlock : 0);
+    static_assert(bytes % 16 == 0, "slots keep 16-byte alignment");
     static constexpr size_t limit = 160 * 1024;
-    static constexpr int nbuf(int) { return 2 * bytes <= limit ? 2 : 1; }
-    static constexpr size_t total(int variant) { return nbuf(variant) * bytes; }
+    static constexpr size_t flag_bytes = 2 * kMaxSlots * sizeof(int);  // ready[] and done[] counters
+    // Ring of slots, one producer wave per slot: eight where they fit in the LDS of a CU, else four.
+    // The delta rule keeps four: its waves need more registers than twelve waves per CU leave each.
+    static constexpr int slots = (VAR != SLA_GDN && kMaxSlots * bytes + flag_bytes <= limit) ? kMaxSlots : 4;
+    static constexpr size_t oFlags = slots * bytes;
+    static constexpr size_t total = oFlags + flag_bytes;
+    static constexpr int threads = (kWaves + slots) * 64;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -323,21 +334,21 @@ struct Loader {
     // Token indices passed to the loads must be wave-uniform (they become scalar offsets).
     __device__ __forceinline__ void load_q(stage_t& st, int tok0, int i) const {
 #ifdef SLA_NOLOAD
-        if (tok0 >= kChunk) return;
+        if (tok0 >= kBlock * kMaxSlots) return;
 #endif
         const int so = (tok0 + i) * tstride_qk;
         st.q[i] = (EPL == 2) ? P::bload2(rq, voff_qk, so) : P::bload1(rq, voff_qk, so);
     }
     __device__ __forceinline__ void load_k(stage_t& st, int tok0, int i) const {
 #ifdef SLA_NOLOAD
-        if (tok0 >= kChunk) return;
+        if (tok0 >= kBlock * kMaxSlots) return;
 #endif
         const int so = (tok0 + i) * tstride_qk;
         st.k[i] = (EPL == 2) ? P::bload2(rk, voff_qk, so) : P::bload1(rk, voff_qk, so);
     }
     __device__ __forceinline__ void load_ld(stage_t& st, int tok0, int i) const {
 #ifdef SLA_NOLOAD
-        if (tok0 >= kChunk) return;
+        if (tok0 >= kBlock * kMaxSlots) return;
 #endif
         if constexpr (VAR == SLA_GLA) {
             const int so = (tok0 + i) * tstride_qk;
@@ -346,14 +357,14 @@ struct Loader {
     }
     __device__ __forceinline__ void load_v(stage_t& st, int tok0) const {
 #ifdef SLA_NOLOAD
-        if (tok0 >= kChunk) return;
+        if (tok0 >= kBlock * kMaxSlots) return;
 #endif
 #pragma unroll
         for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, (tok0 + i) * tstride_v);
     }
     __device__ __forceinline__ void load_logits(stage_t& st, int tok0, int lane) const {
 #ifdef SLA_NOLOAD
-        if (tok0 >= kChunk) return;
+        if (tok0 >= kBlock * kMaxSlots) return;
 #endif
         const int s_lg = tok0 * tstride_lg;
         const int sub = lane & 3;
@@ -418,7 +429,7 @@ __device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
 template <class P, int VAR, int DK, int DVW, int HG>
 __device__ __forceinline__ void stage_gates(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
                                             unsigned char* buf, int blk, int next_tok0, int lane) {
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     float* GQ = (float*)(buf + L::oGQ);
     float* GK = (float*)(buf + L::oGK);
     const float gq = head_gate<HG>(st.ql, st.ql_own);
@@ -436,7 +447,7 @@ template <class P, int VAR, int DK, int DVW, int HG>
 __device__ __forceinline__ void stage_values(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
                                              unsigned char* buf, int blk, int next_tok0, int lane) {
     typedef typename P::elem elem;
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int NI = DVW / 8;
     constexpr int LPR = DVW / 2;
     elem* VT = (elem*)(buf + L::oVT);
@@ -502,7 +513,7 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
     typedef typename P::elem elem;
     typedef typename P::pair pair;
     typedef typename P::frag frag;
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int EPL = DK / 64;
     constexpr int NTILE = DK / 16;
     elem* QA = (elem*)(buf + L::oQA);
@@ -629,7 +640,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     SLA_STAMP(0);
     typedef typename P::elem elem;
     typedef typename P::pair pair;
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int EPL = DK / 64;
     elem* QA = (elem*)(buf + L::oQA);
     elem* KD = (elem*)(buf + L::oKD);
@@ -741,22 +752,21 @@ struct BlockFrags {
 };
 
 template <class P, int VAR, int DK, int DVW, bool SO>
-__device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, const unsigned char* buf, int I, int cw,
-                                                 int lane) {
+__device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, const unsigned char* buf, int cw, int lane) {
     typedef typename P::elem elem;
     typedef typename P::frag frag;
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int NTILE = DK / 16;
-    const int r = lane & 15, g = lane >> 4, trow = kBlock * I + r;
+    const int r = lane & 15, g = lane >> 4;
     const elem* QA = (const elem*)(buf + L::oQA);
     if constexpr (!SO) {
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + trow * L::RS + 16 * s + 4 * g);
-        f.fp = ((const frag*)(buf + L::oPT))[I * 64 + lane];
-        f.gq = ((const float*)(buf + L::oGQ))[trow];
+        for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + r * L::RS + 16 * s + 4 * g);
+        f.fp = ((const frag*)(buf + L::oPT))[lane];
+        f.gq = ((const float*)(buf + L::oGQ))[r];
     }
     if constexpr (VAR != SLA_GLA) {
-        const float* C2 = (const float*)(buf + L::oP1) + I * kBlock;
+        const float* C2 = (const float*)(buf + L::oP1);
         f.ct = C2[r];
         f.c16 = C2[kBlock - 1];
         f.cj = *(const f32x4*)(C2 + 4 * g);
@@ -764,134 +774,159 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
     if constexpr (VAR == SLA_GDN) {
         const elem* KD = (const elem*)(buf + L::oKD);
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + trow * L::RS + 16 * s + 4 * g);
-        f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + I * kBlock + 4 * g);
-        f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + I * kBlock * kBlock + r * kBlock + 4 * g);
+        for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + r * L::RS + 16 * s + 4 * g);
+        f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + 4 * g);
+        f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + r * kBlock + 4 * g);
     }
-    f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + kBlock * I + 4 * g);
+    f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + 4 * g);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Producer/consumer hand-over through two counters per LDS slot.  ready[s] counts the blocks a
+// producer has finished writing into slot s, done[s] the consumer waves that have finished reading
+// it; both only grow, so a waiter compares against the value its own block index implies.  The LDS
+// operations of a wave complete in order: once lgkmcnt has drained, everything the wave wrote is in
+// LDS and everything it read is in its registers, and the counter update that follows is ordered
+// behind them.  Every wait is bounded: the hand-over cannot deadlock (a block depends only on blocks
+// with smaller indices), and should a wait ever exhaust its budget the wave goes on rather than hang.
+// ---------------------------------------------------------------------------------------------
+static constexpr int kSpinLimit = 1 << 22;
+typedef __attribute__((address_space(3))) int lds_int;  // the counters are addressed as LDS, never as flat memory
+
+__device__ __forceinline__ int flag_peek(const lds_int* f) { return *(const volatile lds_int*)f; }
+
+__device__ __forceinline__ void flag_wait(const lds_int* f, int target) {
+    int spin = 0;
+    while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
+    asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ void flag_signal(lds_int* f, int lane) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) __hip_atomic_fetch_add(f, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    asm volatile("" ::: "memory");
+}
+
+// One 16-token block: read-out with the entry state, state step, epilogue store.  cur holds the
+// fragments requested a block earlier.  Everything that reads cur comes first; then the LDS requests go
+// out in one go -- this block's state-step operands, the next block's fragments (into nxt) and the
+// counter of the block after that -- behind matrix work that is already in flight.  No branch from
+// here to the epilogue, so the whole block is one scheduling region.
 template <class P, int VAR, int DK, int DVW, bool SO>
-__device__ __forceinline__ void consume_chunk(f32x4 (&S)[DK / 16], const unsigned char* buf, int cw, int chunk_tok0,
-                                              int T, typename P::elem* out_row, size_t out_tstride,
-                                              int lane SLA_TRACE_PARAM) {
+__device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFrags<P, VAR, DK>& cur,
+                                              BlockFrags<P, VAR, DK>& nxt, const unsigned char* buf,
+                                              const unsigned char* buf_next, const lds_int* peek_at, int& seen,
+                                              bool in_range, typename P::elem* out_ptr, int cw, int lane) {
     typedef typename P::elem elem;
     typedef typename P::frag frag;
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int NTILE = DK / 16;
-    constexpr int NBLK = kChunk / kBlock;
     const elem* KBT = (const elem*)(buf + L::oKBT);
     [[maybe_unused]] const float* EA = (const float*)(buf + L::oEA);
     const int r = lane & 15, g = lane >> 4;
 
-    SLA_STAMP(0);
-    BlockFrags<P, VAR, DK> cur, nxt;
-    load_block_frags<P, VAR, DK, DVW, SO>(cur, buf, 0, cw, lane);
-#pragma unroll
-    for (int I = 0; I < NBLK; ++I) {
-        // requests for later: the next block's operands and this block's state-step operands
-        if (I + 1 < NBLK) load_block_frags<P, VAR, DK, DVW, SO>(nxt, buf, I + 1, cw, lane);
-        [[maybe_unused]] f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
-        frag fk[NTILE];
-        if constexpr (VAR == SLA_GLA) {
-#pragma unroll
-            for (int s = 0; s < NTILE; ++s) ea[s] = *(const f32x4*)(EA + I * DK + 16 * s + 4 * g);
-        }
-#pragma unroll
-        for (int s = 0; s < NTILE; ++s) fk[s] = *(const frag*)(KBT + (16 * s + r) * L::TS + kBlock * I + 4 * g);
-
-        frag fv = cur.fv;    // v' for the read-out
-        frag fv2 = cur.fv;   // v' for the state step (scalar-decay variants: times 2^(c_16 - c_j))
-        [[maybe_unused]] float p_t = 1.f, A = 1.f;
-        if constexpr (VAR != SLA_GLA) {
-            p_t = fast_exp2(cur.ct);
-            A = fast_exp2(cur.c16);
-            f32x4 vs = P::to_acc(cur.fv);
-            if constexpr (VAR == SLA_GDN) {
-                // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
-                //   (I + L) U = beta G^K V - diag(beta p) K S   =>   U = Tm R,
-                // and U takes the place of v' in the read-out and in the state step.
-                f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = k_j S : lane holds column n = r, rows j = 4g + i
-#pragma unroll
-                for (int s = 0; s < NTILE; s += 2)
-                    P::mma32(X, cur.fkd[s], cur.fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
-                f32x4 R;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.bt[i] * fast_exp2(cur.cj[i]) * X[i];
-                f32x4 U = {0.f, 0.f, 0.f, 0.f};
-                P::mma16(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
-                vs = U;
-                fv = P::from_acc(U);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) vs[i] *= fast_exp2(cur.c16 - cur.cj[i]);
-            fv2 = P::from_acc(vs);
-        }
-
-        // O^T[n][t] = p_t sum_d S[d][n] q[t][d] + sum_j v'[j][n] P[t][j]   (GLA: p_t is folded into q)
-        f32x4 oT = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (!SO) {
+    frag fv = cur.fv;    // v' for the read-out
+    frag fv2 = cur.fv;   // v' for the state step (scalar-decay variants: times 2^(c_16 - c_j))
+    [[maybe_unused]] float p_t = 1.f, A = 1.f;
+    if constexpr (VAR != SLA_GLA) {
+        p_t = fast_exp2(cur.ct);
+        A = fast_exp2(cur.c16);
+        f32x4 vs = P::to_acc(cur.fv);
+        if constexpr (VAR == SLA_GDN) {
+            // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
+            //   (I + L) U = beta G^K V - diag(beta p) K S   =>   U = Tm R,
+            // and U takes the place of v' in the read-out and in the state step.
+            f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = k_j S : lane holds column n = r, rows j = 4g + i
 #pragma unroll
             for (int s = 0; s < NTILE; s += 2)
-                P::mma32(oT, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
-            if constexpr (VAR != SLA_GLA) {
+                P::mma32(X, cur.fkd[s], cur.fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
+            f32x4 R;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) oT[i] *= p_t;
-            }
-            P::mma16(oT, fv, cur.fp);
+            for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.bt[i] * fast_exp2(cur.cj[i]) * X[i];
+            f32x4 U = {0.f, 0.f, 0.f, 0.f};
+            P::mma16(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
+            vs = U;
+            fv = P::from_acc(U);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vs[i] *= fast_exp2(cur.c16 - cur.cj[i]);
+        fv2 = P::from_acc(vs);
+    }
 
-        // state step: S <- diag(A_I) S + kb^T v'
+    // O^T[n][t] = p_t sum_d S[d][n] q[t][d] + sum_j v'[j][n] P[t][j]   (GLA: p_t is folded into q)
+    // as two independent accumulation chains, added in the epilogue
+    f32x4 oS = {0.f, 0.f, 0.f, 0.f}, oP = {0.f, 0.f, 0.f, 0.f};
+    const float gq = cur.gq;
+    if constexpr (!SO) {
+        P::mma16_only(oP, fv, cur.fp);
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) {
-            if constexpr (VAR == SLA_GLA) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) S[s][i] *= ea[s][i];
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) S[s][i] *= A;
-            }
-            P::mma16(S[s], fk[s], fv2);
-        }
+        for (int s = 0; s < NTILE; s += 2)
+            P::mma32(oS, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
+    }
 
-        // epilogue: read gate, cast, store 4 adjacent value columns of token t
-        if constexpr (!SO) {
-            const int t = chunk_tok0 + kBlock * I + r;
-            float o[4];
+    // LDS requests: state-step operands of this block, fragments of the next, the counter after that
+    [[maybe_unused]] f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
+    frag fk[NTILE];
+    if constexpr (VAR == SLA_GLA) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = oT[i] * cur.gq;
-            if (t < T) store_run<P, 4>(out_row + (size_t)t * out_tstride, o);
+        for (int s = 0; s < NTILE; ++s) ea[s] = *(const f32x4*)(EA + 16 * s + 4 * g);
+    }
+#pragma unroll
+    for (int s = 0; s < NTILE; ++s) fk[s] = *(const frag*)(KBT + (16 * s + r) * L::TS + 4 * g);
+    load_block_frags<P, VAR, DK, DVW, SO>(nxt, buf_next, cw, lane);
+    seen = flag_peek(peek_at);
+
+    // state step: S <- diag(A) S + kb^T v'
+#pragma unroll
+    for (int s = 0; s < NTILE; ++s) {
+        if constexpr (VAR == SLA_GLA) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[s][i] *= ea[s][i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[s][i] *= A;
         }
-        if (I + 1 < NBLK) cur = nxt;
-        SLA_STAMP(1 + I);
+        P::mma16_only(S[s], fk[s], fv2);
+    }
+
+    // epilogue: read gate, cast, store 4 adjacent value columns of token t
+    if constexpr (!SO) {
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (VAR != SLA_GLA ? oS[i] * p_t + oP[i] : oS[i] + oP[i]) * gq;
+        if (in_range) store_run<P, 4>(out_ptr, o);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // The kernel: waves 0..3 consume (wave w owns value columns 16w..16w+15 of the slice and the state
-// rows x those columns), waves 4..7 produce (wave 4+p stages block p of every chunk).  With two LDS
-// buffers the producers work one chunk ahead of the consumers and one barrier per chunk separates
-// them; where two buffers do not fit in LDS the phases alternate on one buffer.
+// rows x those columns), the other waves produce: producer p stages blocks p, p + NP, p + 2 NP, ...
+// into slot p of an LDS ring, up to NP blocks ahead of the consumers.  There is no workgroup barrier
+// after start-up: a consumer waits for the block it needs, a producer for its slot to be free.
 // ---------------------------------------------------------------------------------------------
-static constexpr int kThreads = 2 * kWaves * 64;
-
 template <class P, int VAR, int DK, int DVW, int HG, bool SO>
-__global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
+__global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kernel(const KArgs a) {
     typedef typename P::elem elem;
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int NTILE = DK / 16;
     constexpr int NCW = DVW / 16;  // consumer waves that have columns
-    constexpr int NBUF = L::nbuf(VAR);
+    constexpr int NP = L::slots;   // producer waves = ring slots
     static_assert(DK == 64 || DK == 128, "dk");
     static_assert(DVW == 16 || DVW == 32 || DVW == 64, "value columns per workgroup");
+    static_assert((NP & (NP - 1)) == 0, "slot index is taken with a mask");
 
     extern __shared__ __align__(16) unsigned char smem[];
+    lds_int* ready = (lds_int*)(smem + L::oFlags);
+    lds_int* done = ready + kMaxSlots;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool producer = wave >= kWaves;
-    const int pw = wave - kWaves;  // producer index = block of the chunk
+    const int pw = wave - kWaves;  // producer index = slot
     const int r = lane & 15, g = lane >> 4;
+
+    if (tid < 2 * kMaxSlots) ready[tid] = 0;
+    __syncthreads();
 
     // Workgroup -> (batch, head, value slice).  Consecutive hardware ids go to different XCDs
     // (id % 8), so the slices of one head -- which read the same q, k, decay and logits -- are given
@@ -906,57 +941,35 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
     const int H = a.H, dv = a.dv;
     const int T = min(a.Ls, a.T - seg * a.Ls);            // tokens of this row
     const size_t row_tok = (size_t)b * a.T + (size_t)seg * a.Ls;
-    const int nchunks = (T + kChunk - 1) / kChunk;
+    const int nblocks = (T + kBlock - 1) / kBlock;
 
     if (producer) {
         float decay_const = 0.f;  // RetNet: log2 gamma_h
         if constexpr (VAR == SLA_RETNET) decay_const = ((const float*)a.ld)[h] * kLog2e;
         Loader<P, VAR, DK, DVW, HG> ldr;
         ldr.init(a, row_tok, T, h, n0, lane);
-        // One register stage, refilled while it is consumed: the loads of a chunk are in flight for a
-        // whole chunk period.  Past the end of the sequence every load is out of range: it returns
-        // zero without touching memory, and nothing staged from it is ever read.
+        // One register stage, refilled while it is consumed: the loads of a block are in flight while
+        // the other producers' blocks are staged.  Past the end of the sequence every load is out of
+        // range: it returns zero without touching memory, and nothing staged from it is ever read.
         Stage<P, VAR, DK, DVW, HG> st;
         ldr.load(st, kBlock * pw, lane);
         float dacc[DK / 64];  // pre-pass, GLA: decay of the blocks this wave staged, per owned key dimension
 #pragma unroll
         for (int e = 0; e < DK / 64; ++e) dacc[e] = 1.f;
+        unsigned char* buf = smem + (size_t)pw * L::bytes;
         SLA_TRACE_DECL
-        auto stage_chunk = [&](int cc) {
-            if (cc < nchunks) {
-                const int tok0 = cc * kChunk + kBlock * pw;
+        for (int I = pw, use = 0; I < nblocks; I += NP, ++use) {
+            SLA_STAMP(7);
+            flag_wait(done + pw, NCW * use);  // the consumers have finished the block that was here
 #if SLA_EXP != 2
-                produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, smem + (NBUF == 2 ? (cc & 1) : 0) * L::bytes, pw, tok0,
-                                                       tok0 + kChunk, T, decay_const, dacc, lane SLA_TRACE_PASS);
+            produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, 0, kBlock * I, kBlock * (I + NP), T, decay_const, dacc,
+                                                   lane SLA_TRACE_PASS);
 #endif
-            }
-        };
-        if constexpr (NBUF == 2) {
-            stage_chunk(0);
-            __syncthreads();
-            for (int c = 0; c < nchunks; c += 2) {  // consumers work on chunks c and c+1 meanwhile
-                stage_chunk(c + 1);
-                __syncthreads();
-                SLA_STAMP(7);
-                SLA_FLUSH(c + 1);
-                stage_chunk(c + 2);
-                __syncthreads();
-                SLA_STAMP(7);
-                SLA_FLUSH(c + 2);
-            }
-        } else {
-            // one LDS buffer (fp32 operands with dk = 128): the two phases alternate
-            for (int c = 0; c < nchunks; c += 2) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    stage_chunk(c + u);
-                    __syncthreads();
-                    __syncthreads();
-                }
-            }
+            flag_signal(ready + pw, lane);
+            SLA_FLUSH(use);
         }
         if constexpr (SO && VAR == SLA_GLA) {
-            float* dp = a.ws_decay + (((size_t)(b * (a.nseg - 1) + seg) * H + h) * kWaves + pw) * DK + (DK / 64) * lane;
+            float* dp = a.ws_decay + (((size_t)(b * (a.nseg - 1) + seg) * H + h) * kMaxSlots + pw) * DK + (DK / 64) * lane;
 #pragma unroll
             for (int e = 0; e < DK / 64; ++e) dp[e] = dacc[e];
         }
@@ -965,7 +978,8 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
 
     // ---------------------------------------------------------------- consumer waves
     const int cw = wave;
-    const bool active = cw < NCW;
+    if (cw >= NCW) return;
+    __builtin_amdgcn_s_setprio(2);  // the state recurrence is the serial part: let it issue first
     // State slice: tile s holds S[16s + 4g + i][n0 + 16*cw + r] in S[s][i].
     f32x4 S[NTILE];
 #pragma unroll
@@ -986,45 +1000,47 @@ __global__ __launch_bounds__(kThreads) void sla_fwd_kernel(const KArgs a) {
             s_in = a.s0 + ((size_t)b * H + h) * head_sz + lane_off;
         if (seg == a.nseg - 1 && a.sT) s_out = a.sT + ((size_t)b * H + h) * head_sz + lane_off;
     }
-    if (active && s_in) {
+    if (s_in) {
 #pragma unroll
         for (int s = 0; s < NTILE; ++s)
 #pragma unroll
             for (int i = 0; i < 4; ++i) S[s][i] = s_in[(size_t)(16 * s + i) * dv];
     }
-    elem* out_row = (elem*)a.out + (row_tok * H + h) * dv + n0 + 16 * cw + 4 * g;
+    // this lane stores 4 adjacent value columns of token r of every block
     const size_t out_tstride = (size_t)H * dv;
+    elem* out_ptr = (elem*)a.out + (row_tok * H + h) * dv + n0 + 16 * cw + 4 * g + (size_t)r * out_tstride;
 
-    // Barrier count per pair of chunks matches the producers' (two steps per pair, also for an odd tail).
     SLA_TRACE_DECL
-    if constexpr (NBUF == 2) {
-        __syncthreads();
-        for (int c = 0; c < nchunks; c += 2) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
+    BlockFrags<P, VAR, DK> fa, fb;
+    // Block I: make sure block I + 1 has been staged (its counter was requested a block ago), then do
+    // the block, which also requests block I + 1's fragments and block I + 2's counter, then hand slot
+    // I % NP back.  Past the last block the requests read slots that hold older data; nothing uses it.
+    int seen = 0;
+    auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
+        SLA_STAMP(0);
+        const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
+        if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
+        asm volatile("" ::: "memory");
+        SLA_STAMP(1);
 #if SLA_EXP != 1
-                if (active && c + u < nchunks)
-                    consume_chunk<P, VAR, DK, DVW, SO>(S, smem + u * L::bytes, cw, (c + u) * kChunk, T, out_row, out_tstride,
-                                                   lane SLA_TRACE_PASS);
+        consume_block<P, VAR, DK, DVW, SO>(S, cur, nxt, smem + (size_t)sl * L::bytes, smem + (size_t)sl1 * L::bytes,
+                                           ready + sl2, seen, kBlock * I + r < T, out_ptr, cw, lane);
 #endif
-                __syncthreads();
-                SLA_STAMP(7);
-                SLA_FLUSH(c + u);
-            }
-        }
-    } else {
-        for (int c = 0; c < nchunks; c += 2) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                __syncthreads();
-                if (active && c + u < nchunks)
-                    consume_chunk<P, VAR, DK, DVW, SO>(S, smem, cw, (c + u) * kChunk, T, out_row, out_tstride, lane SLA_TRACE_PASS);
-                __syncthreads();
-            }
-        }
+        out_ptr += (size_t)kBlock * out_tstride;
+        SLA_STAMP(2);
+        flag_signal(done + sl, lane);
+        SLA_STAMP(3);
+        SLA_FLUSH(I);
+    };
+    flag_wait(ready, 1);
+    load_block_frags<P, VAR, DK, DVW, SO>(fa, smem, cw, lane);
+    seen = flag_peek(ready + (1 & (NP - 1)));
+    for (int I = 0; I < nblocks; I += 2) {
+        step(I, fa, fb);
+        if (I + 1 < nblocks) step(I + 1, fb, fa);
     }
 
-    if (active && s_out) {
+    if (s_out) {
 #pragma unroll
         for (int s = 0; s < NTILE; ++s)
 #pragma unroll
@@ -1043,11 +1059,10 @@ __global__ void sla_state_passthrough_kernel(const float* s0, float* sT, size_t 
 // ---------------------------------------------------------------------------------------------
 template <class P, int VAR, int DK, int DVW, int HG, bool SO>
 static int launch_one(const KArgs& a, hipStream_t stream) {
-    typedef Smem<P, DK, DVW> L;
+    typedef Smem<P, VAR, DK, DVW> L;
     auto kern = sla_fwd_kernel<P, VAR, DK, DVW, HG, SO>;
-    const size_t lds = L::total(VAR);
-    static_assert(DVW == 64 || L::total(VAR) <= L::limit, "stage buffers exceed the LDS of a CU");
-    if (lds > L::limit) return SLA_ERR_UNSUPPORTED;
+    const size_t lds = L::total;
+    static_assert(L::total <= L::limit, "ring slots exceed the LDS of a CU");
     static bool configured = false;  // per instantiation
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -1057,7 +1072,7 @@ static int launch_one(const KArgs& a, hipStream_t stream) {
         configured = true;
     }
     const int grid = a.B * a.nseg_grid * a.H * a.nslice;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(L::threads), lds, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
@@ -1080,8 +1095,9 @@ __global__ void sla_segment_combine_kernel(const KArgs a, int dk) {
     for (int s = 0; s + 1 < a.nseg; ++s) {
         float D;
         if constexpr (VAR == SLA_GLA) {
-            const float* dp = a.ws_decay + ((size_t)(b * (a.nseg - 1) + s) * a.H + h) * kWaves * dk + d;
-            D = dp[0] * dp[dk] * dp[2 * dk] * dp[3 * dk];
+            const float* dp = a.ws_decay + ((size_t)(b * (a.nseg - 1) + s) * a.H + h) * kMaxSlots * dk + d;
+            D = 1.f;
+            for (int w = 0; w < a.nparts; ++w) D *= dp[w * dk];
         } else {
             D = fast_exp2(((const float*)a.ld)[h] * kLog2e * (float)a.Ls);  // segments before the last are full
         }
@@ -1102,10 +1118,12 @@ static int launch(const KArgs& a, hipStream_t stream) {
     } else {
         KArgs pre = a;
         pre.nseg_grid = a.nseg - 1;
+        KArgs mid = a;
+        mid.nparts = Smem<P, VAR, DK, DVW>::slots;
         int rc = launch_one<P, VAR, DK, DVW, HG, true>(pre, stream);
         if (rc != SLA_OK) return rc;
         const size_t n = (size_t)a.B * a.H * DK * (a.dv / 4);
-        hipLaunchKernelGGL(sla_segment_combine_kernel<VAR>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a, DK);
+        hipLaunchKernelGGL(sla_segment_combine_kernel<VAR>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, mid, DK);
         if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
         return launch_one<P, VAR, DK, DVW, HG, false>(a, stream);
     }
@@ -1123,16 +1141,7 @@ static int dispatch_dvw(const KArgs& a, int dvw, hipStream_t stream) {
     switch (dvw) {
         case 16: return dispatch_heads<P, VAR, DK, 16>(a, stream);
         case 32: return dispatch_heads<P, VAR, DK, 32>(a, stream);
-        case 64:
-            // fp32 operands of the delta rule with dk = 128 need more LDS than a CU has for a 64-column
-            // slice; two 32-column slices compute the same values
-            if constexpr (Smem<P, DK, 64>::total(VAR) > Smem<P, DK, 64>::limit) {
-                KArgs b = a;
-                b.nslice = a.dv / 32;
-                return dispatch_heads<P, VAR, DK, 32>(b, stream);
-            } else {
-                return dispatch_heads<P, VAR, DK, 64>(a, stream);
-            }
+        case 64: return dispatch_heads<P, VAR, DK, 64>(a, stream);
         default: return SLA_ERR_UNSUPPORTED;
     }
 }
@@ -1160,7 +1169,7 @@ static int dispatch_variant(const KArgs& a, int variant, int dk, int dvw, hipStr
 size_t segment_workspace_floats(const sla_params& p, int nseg) {
     if (nseg <= 1) return 0;
     const size_t heads = (size_t)p.B * p.H;
-    return heads * nseg * p.dk * p.dv + heads * (nseg - 1) * kWaves * p.dk;  // entry states, decay products
+    return heads * nseg * p.dk * p.dv + heads * (nseg - 1) * kMaxSlots * p.dk;  // entry states, decay products
 }
 
 int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k, const void* v,
@@ -1169,7 +1178,7 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
     KArgs a;
     a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = beta; a.s0 = s0; a.out = out; a.sT = sT;
     a.B = p.B; a.T = p.T; a.H = p.H; a.dv = p.dv; a.nslice = p.dv / dvw;
-    a.nseg = nseg; a.nseg_grid = nseg; a.Ls = nseg > 1 ? seg_len : p.T;
+    a.nseg = nseg; a.nseg_grid = nseg; a.nparts = 0; a.Ls = nseg > 1 ? seg_len : p.T;
     a.ws_state = workspace;
     a.ws_decay = workspace ? workspace + (size_t)p.B * nseg * p.H * p.dk * p.dv : nullptr;
     if (p.T == 0) {
