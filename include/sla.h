@@ -27,8 +27,9 @@
  * logits (Eq. 4) and consume the output (Eq. 7) are the caller's.
  *
  * Domain: every log-decay must be <= 0; for GLA each must also be >= -5
- * (a decay factor below e^-5 per token cannot be represented by the blocked
- * evaluation without overflow; outside this range results may be inf/NaN).
+ * (the blocked evaluation divides keys by the decay accumulated inside a block of
+ * 16 tokens; below e^-5 per token that quotient leaves the fp32 range and results
+ * may be inf/NaN).  RetNet and GDN take any decay <= 0.
  * NaN or infinite inputs propagate to the outputs; they are not trapped.
  */
 #ifndef SLA_H_

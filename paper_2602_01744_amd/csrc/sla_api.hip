@@ -188,7 +188,9 @@ const char* sla_kernel_name(const sla_params* p) {
     if (!p) return nullptr;
     if (p->variant < 0 || p->variant > 2 || (p->dtype != SLA_F32 && p->dtype != SLA_BF16)) return nullptr;
     if (p->dv != 64 && p->dv != 128) return nullptr;
-    const int dvw = choose_dv_split(*p, 256, 1);  // dv_split == 0 is resolved as on a 256-CU device, one pass
+    int seg_len = 0;  // dv_split == 0 is resolved as on a 256-CU device, for the schedule p->segments asks for
+    const int nseg = (p->segments > 1 && p->T > 0 && p->variant != SLA_GDN) ? choose_segments(*p, 256, &seg_len) : 1;
+    const int dvw = choose_dv_split(*p, 256, nseg);
     const int head_regs = p->H <= 16 ? 4 : (p->H <= 32 ? 8 : 16);
     snprintf(buf, sizeof(buf), "sla_fwd_kernel<sla::%s, %d, %d, %d, %d, false>", p->dtype == SLA_BF16 ? "PrecBF16" : "PrecF32",
              p->variant, p->dk, dvw, head_regs);

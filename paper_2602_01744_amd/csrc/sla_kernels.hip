@@ -14,7 +14,9 @@
 //       S_next = diag(A) S0 + sum_j kb_j^T v'_j
 //
 //   Every factor except 1/p_j is <= 1; 1/p_j is bounded by e^(16*5) because a block has 16 tokens
-//   and log-decays are required to be >= -5, so nothing overflows in fp32 or bf16.
+//   and GLA log-decays are required to be >= -5, so nothing overflows in fp32 or bf16.
+//   (The scalar-decay variants apply their decay after the matrix products, as factors <= 1 only, and
+//   have no such bound.)
 //
 //   Phase 1 ("producer", all four waves, one 16-token block each): buffer loads (out-of-range tokens
 //   read as zero, no branches) issued one chunk ahead into registers; head softmax (Eq. 4) with
@@ -232,6 +234,14 @@ __device__ __forceinline__ void store_run(typename P::elem* dst, const float (&x
 // ---------------------------------------------------------------------------------------------
 // LDS geometry
 // ---------------------------------------------------------------------------------------------
+// Key dimensions inside the row-major q and k rows are stored permuted within groups of 32:
+// d = 32 S + 16 u + 4 g + i sits at 32 S + 8 g + 4 u + i.  Lane group g of an MFMA feeds the slots
+// {4g..4g+3} of two adjacent 16-dimension tiles; with this order they are 8 adjacent elements (one
+// 16-byte read with 2-byte elements).  Adjacent even/odd dimensions stay adjacent.
+__host__ __device__ constexpr int perm32(int d) { return (d & ~31) | ((d & 12) << 1) | ((d & 16) >> 2) | (d & 3); }
+// Row and column (of token group 0) of key dimension d in the k^T array.
+__host__ __device__ constexpr int kbt_row(int d) { return ((d >> 5) << 4) | (d & 15); }
+__host__ __device__ constexpr int kbt_col(int d) { return ((d >> 4) & 1) * 4; }
 template <class P, int VAR, int DK, int DVW>
 struct Smem {
     typedef typename P::elem elem;
@@ -241,11 +251,15 @@ struct Smem {
     // reads row r.  With 2-byte elements a stride of 40 bytes (10 banks) puts the 16 lanes that an
     // 8-byte access serves per cycle on 16 distinct bank pairs for the consumers' pattern.
     static constexpr int TS = kBlock + 4;
+    // k^T of the block ("KBT"): row (d / 32) * 16 + d % 16 holds key dimensions d and d + 16 of the 16
+    // tokens, ordered [token / 4][(d / 16) % 2][token % 4], so that the two 4-token fragments a consumer
+    // lane feeds to the tiles of d and d + 16 are one 16-byte read.  Rows are padded to 40 elements.
+    static constexpr int KTS = 2 * kBlock + 8;
     // One slot holds the operands of one 16-token block.
     static constexpr size_t oQA = 0;
     static constexpr size_t oKD = oQA + sizeof(elem) * kBlock * RS;
     static constexpr size_t oKBT = oKD + sizeof(elem) * kBlock * RS;
-    static constexpr size_t oVT = oKBT + sizeof(elem) * DK * TS;
+    static constexpr size_t oVT = oKBT + sizeof(elem) * (DK / 2) * KTS;
     static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
     static constexpr size_t oGQ = oEA + (VAR == SLA_GLA ? sizeof(float) * DK : 0);
     static constexpr size_t oGK = oGQ + sizeof(float) * kBlock;
@@ -262,7 +276,11 @@ struct Smem {
     static constexpr size_t flag_bytes = 2 * kMaxSlots * sizeof(int);  // ready[] and done[] counters
     // Ring of slots, one producer wave per slot: eight where they fit in the LDS of a CU, else four.
     // The delta rule keeps four: its waves need more registers than twelve waves per CU leave each.
+#ifdef SLA_SLOTS
+    static constexpr int slots = SLA_SLOTS;
+#else
     static constexpr int slots = (VAR != SLA_GDN && kMaxSlots * bytes + flag_bytes <= limit) ? kMaxSlots : 4;
+#endif
     static constexpr size_t oFlags = slots * bytes;
     static constexpr size_t total = oFlags + flag_bytes;
     static constexpr int threads = (kWaves + slots) * 64;
@@ -331,72 +349,79 @@ struct Loader {
         }
     }
 
-    // Token indices passed to the loads must be wave-uniform (they become scalar offsets).
-    __device__ __forceinline__ void load_q(stage_t& st, int tok0, int i) const {
+    // The loads address token (base + i) of the row: base lives in the per-lane byte offsets, which
+    // advance() moves from block to block; i * stride is wave-uniform and loop-invariant, so the scalar
+    // offsets of all loads are constants held in SGPRs.
+    __device__ __forceinline__ void advance(int ntok) {
+        voff_qk += ntok * tstride_qk;
+        voff_v += ntok * tstride_v;
+        voff_lg += ntok * tstride_lg;
+        voff_own += ntok * tstride_lg;
+        if constexpr (VAR == SLA_GDN) voff_sc += ntok * tstride_lg;
 #ifdef SLA_NOLOAD
-        if (tok0 >= kBlock * kMaxSlots) return;
+        dev_tok += ntok;
 #endif
-        const int so = (tok0 + i) * tstride_qk;
+    }
+#ifdef SLA_NOLOAD
+    int dev_tok = 0;
+    __device__ __forceinline__ bool skip() const { return dev_tok >= kBlock * kMaxSlots; }
+#else
+    __device__ __forceinline__ bool skip() const { return false; }
+#endif
+    __device__ __forceinline__ void load_q(stage_t& st, int i) const {
+        if (skip()) return;
+        const int so = i * tstride_qk;
         st.q[i] = (EPL == 2) ? P::bload2(rq, voff_qk, so) : P::bload1(rq, voff_qk, so);
     }
-    __device__ __forceinline__ void load_k(stage_t& st, int tok0, int i) const {
-#ifdef SLA_NOLOAD
-        if (tok0 >= kBlock * kMaxSlots) return;
-#endif
-        const int so = (tok0 + i) * tstride_qk;
+    __device__ __forceinline__ void load_k(stage_t& st, int i) const {
+        if (skip()) return;
+        const int so = i * tstride_qk;
         st.k[i] = (EPL == 2) ? P::bload2(rk, voff_qk, so) : P::bload1(rk, voff_qk, so);
     }
-    __device__ __forceinline__ void load_ld(stage_t& st, int tok0, int i) const {
-#ifdef SLA_NOLOAD
-        if (tok0 >= kBlock * kMaxSlots) return;
-#endif
+    __device__ __forceinline__ void load_ld(stage_t& st, int i) const {
+        if (skip()) return;
         if constexpr (VAR == SLA_GLA) {
-            const int so = (tok0 + i) * tstride_qk;
+            const int so = i * tstride_qk;
             st.ld[i] = (EPL == 2) ? P::bload2(rld, voff_qk, so) : P::bload1(rld, voff_qk, so);
         }
     }
-    __device__ __forceinline__ void load_v(stage_t& st, int tok0) const {
-#ifdef SLA_NOLOAD
-        if (tok0 >= kBlock * kMaxSlots) return;
-#endif
+    __device__ __forceinline__ void load_v(stage_t& st) const {
+        if (skip()) return;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, (tok0 + i) * tstride_v);
+        for (int i = 0; i < NI; ++i) st.v[i] = P::bload2(rv, voff_v, i * tstride_v);
     }
-    __device__ __forceinline__ void load_logits(stage_t& st, int tok0, int lane) const {
-#ifdef SLA_NOLOAD
-        if (tok0 >= kBlock * kMaxSlots) return;
-#endif
-        const int s_lg = tok0 * tstride_lg;
+    __device__ __forceinline__ void load_logits(stage_t& st, int lane) const {
+        if (skip()) return;
         const int sub = lane & 3;
 #pragma unroll
         for (int i = 0; i < HG; ++i) {
             // heads beyond H never win the max and add exp(-inf) = 0; tokens beyond T read 0 (equal scores)
             const bool head_ok = sub + 4 * i < H;
-            const float x = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_lg, s_lg + 16 * i, 0));
-            const float y = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_lg, s_lg + 16 * i, 0));
+            const float x = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_lg, 16 * i, 0));
+            const float y = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_lg, 16 * i, 0));
             st.ql[i] = head_ok ? x : -INFINITY;
             st.kl[i] = head_ok ? y : -INFINITY;
         }
-        st.ql_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_own, s_lg, 0));
-        st.kl_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_own, s_lg, 0));
+        st.ql_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rql, voff_own, 0, 0));
+        st.kl_own = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rkl, voff_own, 0, 0));
     }
     // delta rule: tokens beyond T read log-decay 0 (factor 1) and beta 0 (no write)
-    __device__ __forceinline__ void load_scalars(stage_t& st, int tok0) const {
+    __device__ __forceinline__ void load_scalars(stage_t& st) const {
         if constexpr (VAR == SLA_GDN) {
-            st.sc_ld = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rld, voff_sc, tok0 * tstride_lg, 0));
-            st.sc_beta = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rbt, voff_sc, tok0 * tstride_lg, 0));
+            st.sc_ld = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rld, voff_sc, 0, 0));
+            st.sc_beta = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rbt, voff_sc, 0, 0));
         }
     }
-    __device__ __forceinline__ void load(stage_t& st, int tok0, int lane) const {
-        load_logits(st, tok0, lane);
-        load_scalars(st, tok0);
+    __device__ __forceinline__ void load(stage_t& st, int lane) const {
+        load_logits(st, lane);
+        load_scalars(st);
 #pragma unroll
-        for (int i = 0; i < kBlock; ++i) load_ld(st, tok0, i);
+        for (int i = 0; i < kBlock; ++i) load_ld(st, i);
 #pragma unroll
-        for (int i = 0; i < kBlock; ++i) load_q(st, tok0, i);
+        for (int i = 0; i < kBlock; ++i) load_q(st, i);
 #pragma unroll
-        for (int i = 0; i < kBlock; ++i) load_k(st, tok0, i);
-        load_v(st, tok0);
+        for (int i = 0; i < kBlock; ++i) load_k(st, i);
+        load_v(st);
     }
 };
 
@@ -406,6 +431,26 @@ __device__ __forceinline__ float quad_xor1(float x) {
 }
 __device__ __forceinline__ float quad_xor2(float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false));
+}
+
+// Value of lane N of this lane's row of 16 lanes.
+template <int N>
+__device__ __forceinline__ float row_bcast(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + N, 0xf, 0xf, false));
+}
+
+// GLA state decay: S[16s + 4g + i][.] *= A[16s + 4g + i], the factor taken from lane 4(s%4) + i of the
+// row, register ea0 (s < 4) or ea1.
+template <int NT, int s = 0>
+__device__ __forceinline__ void scale_state_rows(f32x4 (&S)[NT], float ea0, float ea1) {
+    if constexpr (s < NT) {
+        const float e = s < 4 ? ea0 : ea1;
+        S[s][0] *= row_bcast<4 * (s & 3) + 0>(e);
+        S[s][1] *= row_bcast<4 * (s & 3) + 1>(e);
+        S[s][2] *= row_bcast<4 * (s & 3) + 2>(e);
+        S[s][3] *= row_bcast<4 * (s & 3) + 3>(e);
+        scale_state_rows<NT, s + 1>(S, ea0, ea1);
+    }
 }
 
 // softmax over heads for the token of this quad (Eq. 4); returns the gate of head h.
@@ -438,7 +483,7 @@ __device__ __forceinline__ void stage_gates(Stage<P, VAR, DK, DVW, HG>& st, cons
         GQ[kBlock * blk + (lane >> 2)] = gq;
         GK[kBlock * blk + (lane >> 2)] = gk;
     }
-    ldr.load_logits(st, next_tok0, lane);
+    ldr.load_logits(st, lane);
 }
 
 // Values of block blk: v' = G^K v (delta rule: beta G^K v), transposed to [column][token].  The gates
@@ -484,7 +529,7 @@ __device__ __forceinline__ void stage_values(Stage<P, VAR, DK, DVW, HG>& st, con
         c0[i] = P::lo(st.v[i]) * gkv[i];
         c1[i] = P::hi(st.v[i]) * gkv[i];
     }
-    ldr.load_v(st, next_tok0);
+    ldr.load_v(st);
     store_run<P, NI, true>(VT + (2 * p) * L::TS + kBlock * blk + tb, c0);
     store_run<P, NI, true>(VT + (2 * p + 1) * L::TS + kBlock * blk + tb, c1);
 }
@@ -536,13 +581,13 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
         if (lane < kBlock) BT[lane] = st.sc_beta;
     }
     if (lane < kBlock) C2[lane] = c_lane;
-    ldr.load_scalars(st, next_tok0);
+    ldr.load_scalars(st);
 
     stage_gates<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
 
     // q and k as loaded
-    elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
-    elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
+    elem* qrow = QA + (kBlock * blk) * L::RS + perm32(EPL * lane);
+    elem* krow = KD + (kBlock * blk) * L::RS + perm32(EPL * lane);
     if constexpr (!SO) {
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) {
@@ -553,7 +598,7 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
                 P::store1(qrow + i * L::RS, P::lo(st.q[i]));
                 P::store1(krow + i * L::RS, P::lo(st.k[i]));
             }
-            ldr.load_q(st, next_tok0, i);
+            ldr.load_q(st, i);
         }
     }
     // k transposed
@@ -562,10 +607,15 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
         float kt[kBlock];
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) kt[i] = (EPL == 2 && e == 1) ? P::hi(st.k[i]) : P::lo(st.k[i]);
-        store_run<P, kBlock, true>(KBT + (EPL * lane + e) * L::TS + kBlock * blk, kt);
+        elem* dst = KBT + kbt_row(EPL * lane + e) * L::KTS + kbt_col(EPL * lane + e);
+#pragma unroll
+        for (int tg = 0; tg < 4; ++tg) {
+            const float four[4] = {kt[4 * tg], kt[4 * tg + 1], kt[4 * tg + 2], kt[4 * tg + 3]};
+            store_run<P, 4>(dst + 8 * tg, four);
+        }
     }
 #pragma unroll
-    for (int i = 0; i < kBlock; ++i) ldr.load_k(st, next_tok0, i);
+    for (int i = 0; i < kBlock; ++i) ldr.load_k(st, i);
 
     // scores of the block from this wave's own rows
     __builtin_amdgcn_wave_barrier();
@@ -575,10 +625,10 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
         f32x4 pT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NTILE; s += 2) {
-            const frag q0 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
-            const frag q1 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
-            fk_[s] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 4 * g);
-            fk_[s + 1] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * (s + 1) + 4 * g);
+            const frag q0 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * s + 8 * g);
+            const frag q1 = *(const frag*)(QA + (kBlock * blk + r) * L::RS + 16 * s + 8 * g + 4);
+            fk_[s] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 8 * g);
+            fk_[s + 1] = *(const frag*)(KD + (kBlock * blk + r) * L::RS + 16 * s + 8 * g + 4);
             P::mma32(pT, fk_[s], fk_[s + 1], q0, q1);  // P^T[j][t] = k_j . q_t
         }
         cj = *(const f32x4*)(C2 + 4 * g);  // rows j = 4g + i
@@ -655,15 +705,15 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     for (int i = 0; i < kBlock; ++i) {
         al[0][i] = fast_exp2(P::lo(st.ld[i]) * kLog2e);
         if constexpr (EPL == 2) al[1][i] = fast_exp2(P::hi(st.ld[i]) * kLog2e);
-        ldr.load_ld(st, next_tok0, i);
+        ldr.load_ld(st, i);
     }
     SLA_STAMP(2);
     // forward: p_t = prod_{i<=t} alpha_i ; qa_t = q_t p_t
     float pre[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) pre[e] = 1.f;
-    elem* qrow = QA + (kBlock * blk) * L::RS + EPL * lane;
-    elem* krow = KD + (kBlock * blk) * L::RS + EPL * lane;
+    elem* qrow = QA + (kBlock * blk) * L::RS + perm32(EPL * lane);
+    elem* krow = KD + (kBlock * blk) * L::RS + perm32(EPL * lane);
 #pragma unroll
     for (int i = 0; i < kBlock; ++i) {
 #pragma unroll
@@ -673,7 +723,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
                 *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
             else
                 P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
-            ldr.load_q(st, next_tok0, i);
+            ldr.load_q(st, i);
         }
     }
     float invA[EPL];
@@ -692,7 +742,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     for (int i = kBlock - 1; i >= 0; --i) {
         kb[0][i] = P::lo(st.k[i]) * suf[0];
         if constexpr (EPL == 2) kb[1][i] = P::hi(st.k[i]) * suf[1];
-        ldr.load_k(st, next_tok0, i);
+        ldr.load_k(st, i);
         if constexpr (!SO) {
             if constexpr (EPL == 2)
                 *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
@@ -703,7 +753,14 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         for (int e = 0; e < EPL; ++e) suf[e] *= al[e][i];
     }
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) store_run<P, kBlock, true>(KBT + (EPL * lane + e) * L::TS + kBlock * blk, kb[e]);
+    for (int e = 0; e < EPL; ++e) {
+        elem* dst = KBT + kbt_row(EPL * lane + e) * L::KTS + kbt_col(EPL * lane + e);
+#pragma unroll
+        for (int tg = 0; tg < 4; ++tg) {
+            const float four[4] = {kb[e][4 * tg], kb[e][4 * tg + 1], kb[e][4 * tg + 2], kb[e][4 * tg + 3]};
+            store_run<P, 4>(dst + 8 * tg, four);
+        }
+    }
 
     SLA_STAMP(4);
     // Scores of the block, P^T[j][t] = kd_j . qa_t for j <= t (else 0), from this wave's own rows
@@ -717,10 +774,10 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         f32x4 pT = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NTILE; s += 2) {
-            const frag q0 = *(const frag*)(QA + (kBlock * blk + r_) * L::RS + 16 * s + 4 * g_);
-            const frag q1 = *(const frag*)(QA + (kBlock * blk + r_) * L::RS + 16 * (s + 1) + 4 * g_);
-            const frag k0 = *(const frag*)(KD + (kBlock * blk + r_) * L::RS + 16 * s + 4 * g_);
-            const frag k1 = *(const frag*)(KD + (kBlock * blk + r_) * L::RS + 16 * (s + 1) + 4 * g_);
+            const frag q0 = *(const frag*)(QA + (kBlock * blk + r_) * L::RS + 16 * s + 8 * g_);
+            const frag q1 = *(const frag*)(QA + (kBlock * blk + r_) * L::RS + 16 * s + 8 * g_ + 4);
+            const frag k0 = *(const frag*)(KD + (kBlock * blk + r_) * L::RS + 16 * s + 8 * g_);
+            const frag k1 = *(const frag*)(KD + (kBlock * blk + r_) * L::RS + 16 * s + 8 * g_ + 4);
             P::mma32(pT, k0, k1, q0, q1);
         }
 #pragma unroll
@@ -741,10 +798,12 @@ template <class P, int VAR, int DK>
 struct BlockFrags {
     typedef typename P::frag frag;
     frag fq[DK / 16];                          // q rows of the block (GLA: decay-folded), all key dimensions
+    frag fk[DK / 16];                          // k^T of the block (GLA: decayed to the block's end) for the state step
     frag fkd[VAR == SLA_GDN ? DK / 16 : 1];    // delta rule: k rows
     frag fp;                                   // masked, decayed scores P^T
     frag fv;                                   // v' of this wave's columns
     float gq;                                  // read gate of token r
+    float ea0, ea1;                            // GLA: block decay of the state rows this lane hands out by DPP
     // scalar-decay variants: cumulative log2-decay of token r, of tokens 4g..4g+3, of the block's last token
     float ct, c16;
     f32x4 cj;
@@ -761,7 +820,7 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
     const elem* QA = (const elem*)(buf + L::oQA);
     if constexpr (!SO) {
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + r * L::RS + 16 * s + 4 * g);
+        for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + r * L::RS + 32 * (s / 2) + 8 * g + 4 * (s & 1));
         f.fp = ((const frag*)(buf + L::oPT))[lane];
         f.gq = ((const float*)(buf + L::oGQ))[r];
     }
@@ -774,11 +833,22 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
     if constexpr (VAR == SLA_GDN) {
         const elem* KD = (const elem*)(buf + L::oKD);
 #pragma unroll
-        for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + r * L::RS + 16 * s + 4 * g);
+        for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + r * L::RS + 32 * (s / 2) + 8 * g + 4 * (s & 1));
         f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + 4 * g);
         f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + r * kBlock + 4 * g);
     }
     f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + 4 * g);
+    const elem* KBT = (const elem*)(buf + L::oKBT);
+#pragma unroll
+    for (int s = 0; s < NTILE; ++s) f.fk[s] = *(const frag*)(KBT + (16 * (s / 2) + r) * L::KTS + 8 * g + 4 * (s & 1));
+    // GLA: the block's decay per state row.  Lane group g needs A[16s + 4g + i] for every tile s; lane r
+    // of the group fetches two of them (s = r/4 and s = 4 + r/4, i = r%4) and the multiply takes its
+    // factor from the lane that holds it through a DPP row broadcast.
+    if constexpr (VAR == SLA_GLA) {
+        const float* EA = (const float*)(buf + L::oEA);
+        f.ea0 = EA[16 * (r >> 2) + 4 * g + (r & 3)];
+        if constexpr (NTILE > 4) f.ea1 = EA[64 + 16 * (r >> 2) + 4 * g + (r & 3)];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -795,35 +865,51 @@ typedef __attribute__((address_space(3))) int lds_int;  // the counters are addr
 
 __device__ __forceinline__ int flag_peek(const lds_int* f) { return *(const volatile lds_int*)f; }
 
+#ifndef SLA_SLEEP
+#define SLA_SLEEP 1
+#endif
+template <int SLEEP = 1>
 __device__ __forceinline__ void flag_wait(const lds_int* f, int target) {
     int spin = 0;
-    while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
+    while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(SLEEP);
     asm volatile("" ::: "memory");
 }
 
-__device__ __forceinline__ void flag_signal(lds_int* f, int lane) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (lane == 0) __hip_atomic_fetch_add(f, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    asm volatile("" ::: "memory");
+// Called with all 64 lanes active; lane 0 alone performs the add.  flag_signal_now skips the drain: for
+// a caller whose LDS accesses are known to have completed.
+__device__ __forceinline__ void flag_signal_now(lds_int* f) {
+    const uint32_t addr = (uint32_t)(uintptr_t)f;
+    const int one = 1;
+    asm volatile(
+        "s_mov_b64 exec, 1\n"
+        "ds_add_u32 %0, %1\n"
+        "s_mov_b64 exec, -1"
+        :
+        : "v"(addr), "v"(one)
+        : "memory");
 }
 
-// One 16-token block: read-out with the entry state, state step, epilogue store.  cur holds the
-// fragments requested a block earlier.  Everything that reads cur comes first; then the LDS requests go
-// out in one go -- this block's state-step operands, the next block's fragments (into nxt) and the
-// counter of the block after that -- behind matrix work that is already in flight.  No branch from
-// here to the epilogue, so the whole block is one scheduling region.
+__device__ __forceinline__ void flag_signal(lds_int* f, int) {
+    const uint32_t addr = (uint32_t)(uintptr_t)f;
+    const int one = 1;
+    asm volatile(
+        "s_waitcnt lgkmcnt(0)\n"
+        "s_mov_b64 exec, 1\n"
+        "ds_add_u32 %0, %1\n"
+        "s_mov_b64 exec, -1"
+        :
+        : "v"(addr), "v"(one)
+        : "memory");
+}
+
+// One 16-token block, entirely from registers: read-out with the entry state, state step, epilogue
+// store.  cur holds every LDS operand of the block (requested a block earlier), so nothing in here
+// waits for LDS and the whole block is one scheduling region.
 template <class P, int VAR, int DK, int DVW, bool SO>
-__device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFrags<P, VAR, DK>& cur,
-                                              BlockFrags<P, VAR, DK>& nxt, const unsigned char* buf,
-                                              const unsigned char* buf_next, const lds_int* peek_at, int& seen,
-                                              bool in_range, typename P::elem* out_ptr, int cw, int lane) {
-    typedef typename P::elem elem;
+__device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFrags<P, VAR, DK>& cur, bool in_range,
+                                              typename P::elem* out_ptr) {
     typedef typename P::frag frag;
-    typedef Smem<P, VAR, DK, DVW> L;
     constexpr int NTILE = DK / 16;
-    const elem* KBT = (const elem*)(buf + L::oKBT);
-    [[maybe_unused]] const float* EA = (const float*)(buf + L::oEA);
-    const int r = lane & 15, g = lane >> 4;
 
     frag fv = cur.fv;    // v' for the read-out
     frag fv2 = cur.fv;   // v' for the state step (scalar-decay variants: times 2^(c_16 - c_j))
@@ -856,7 +942,6 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
     // O^T[n][t] = p_t sum_d S[d][n] q[t][d] + sum_j v'[j][n] P[t][j]   (GLA: p_t is folded into q)
     // as two independent accumulation chains, added in the epilogue
     f32x4 oS = {0.f, 0.f, 0.f, 0.f}, oP = {0.f, 0.f, 0.f, 0.f};
-    const float gq = cur.gq;
     if constexpr (!SO) {
         P::mma16_only(oP, fv, cur.fp);
 #pragma unroll
@@ -864,36 +949,22 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
             P::mma32(oS, P::from_acc(S[s]), P::from_acc(S[s + 1]), cur.fq[s], cur.fq[s + 1]);
     }
 
-    // LDS requests: state-step operands of this block, fragments of the next, the counter after that
-    [[maybe_unused]] f32x4 ea[VAR == SLA_GLA ? NTILE : 1];
-    frag fk[NTILE];
-    if constexpr (VAR == SLA_GLA) {
-#pragma unroll
-        for (int s = 0; s < NTILE; ++s) ea[s] = *(const f32x4*)(EA + 16 * s + 4 * g);
-    }
-#pragma unroll
-    for (int s = 0; s < NTILE; ++s) fk[s] = *(const frag*)(KBT + (16 * s + r) * L::TS + 4 * g);
-    load_block_frags<P, VAR, DK, DVW, SO>(nxt, buf_next, cw, lane);
-    seen = flag_peek(peek_at);
-
     // state step: S <- diag(A) S + kb^T v'
+    if constexpr (VAR == SLA_GLA) scale_state_rows<NTILE>(S, cur.ea0, cur.ea1);
 #pragma unroll
     for (int s = 0; s < NTILE; ++s) {
-        if constexpr (VAR == SLA_GLA) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) S[s][i] *= ea[s][i];
-        } else {
+        if constexpr (VAR != SLA_GLA) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) S[s][i] *= A;
         }
-        P::mma16_only(S[s], fk[s], fv2);
+        P::mma16_only(S[s], cur.fk[s], fv2);
     }
 
     // epilogue: read gate, cast, store 4 adjacent value columns of token t
     if constexpr (!SO) {
         float o[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (VAR != SLA_GLA ? oS[i] * p_t + oP[i] : oS[i] + oP[i]) * gq;
+        for (int i = 0; i < 4; ++i) o[i] = (VAR != SLA_GLA ? oS[i] * p_t + oP[i] : oS[i] + oP[i]) * cur.gq;
         if (in_range) store_run<P, 4>(out_ptr, o);
     }
 }
@@ -952,7 +1023,8 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         // the other producers' blocks are staged.  Past the end of the sequence every load is out of
         // range: it returns zero without touching memory, and nothing staged from it is ever read.
         Stage<P, VAR, DK, DVW, HG> st;
-        ldr.load(st, kBlock * pw, lane);
+        ldr.advance(kBlock * pw);
+        ldr.load(st, lane);
         float dacc[DK / 64];  // pre-pass, GLA: decay of the blocks this wave staged, per owned key dimension
 #pragma unroll
         for (int e = 0; e < DK / 64; ++e) dacc[e] = 1.f;
@@ -960,7 +1032,8 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         SLA_TRACE_DECL
         for (int I = pw, use = 0; I < nblocks; I += NP, ++use) {
             SLA_STAMP(7);
-            flag_wait(done + pw, NCW * use);  // the consumers have finished the block that was here
+            flag_wait<SLA_SLEEP>(done + pw, NCW * use);  // the consumers have finished the block that was here
+            ldr.advance(kBlock * NP);          // every staging register is refilled for block I + NP
 #if SLA_EXP != 2
             produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, 0, kBlock * I, kBlock * (I + NP), T, decay_const, dacc,
                                                    lane SLA_TRACE_PASS);
@@ -979,7 +1052,10 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
     // ---------------------------------------------------------------- consumer waves
     const int cw = wave;
     if (cw >= NCW) return;
-    __builtin_amdgcn_s_setprio(2);  // the state recurrence is the serial part: let it issue first
+#ifndef SLA_CPRIO
+#define SLA_CPRIO 2
+#endif
+    __builtin_amdgcn_s_setprio(SLA_CPRIO);  // the state recurrence is the serial part: let it issue first
     // State slice: tile s holds S[16s + 4g + i][n0 + 16*cw + r] in S[s][i].
     f32x4 S[NTILE];
 #pragma unroll
@@ -1012,23 +1088,27 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
 
     SLA_TRACE_DECL
     BlockFrags<P, VAR, DK> fa, fb;
-    // Block I: make sure block I + 1 has been staged (its counter was requested a block ago), then do
-    // the block, which also requests block I + 1's fragments and block I + 2's counter, then hand slot
-    // I % NP back.  Past the last block the requests read slots that hold older data; nothing uses it.
+    // Block I.  On entry every LDS operand of the block has been requested (a block ago, into cur) and
+    // so has the counter of block I + 1.  Once they have landed, slot I % NP is handed back at once --
+    // the block is computed from registers -- and, block I + 1 being staged, its operands are
+    // requested into nxt together with the counter of block I + 2.  Past the last block the requests
+    // read slots that hold older data; nothing uses it.
     int seen = 0;
     auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
         SLA_STAMP(0);
         const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        flag_signal_now(done + sl);
         if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
         asm volatile("" ::: "memory");
         SLA_STAMP(1);
+        load_block_frags<P, VAR, DK, DVW, SO>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
+        seen = flag_peek(ready + sl2);
 #if SLA_EXP != 1
-        consume_block<P, VAR, DK, DVW, SO>(S, cur, nxt, smem + (size_t)sl * L::bytes, smem + (size_t)sl1 * L::bytes,
-                                           ready + sl2, seen, kBlock * I + r < T, out_ptr, cw, lane);
+        consume_block<P, VAR, DK, DVW, SO>(S, cur, kBlock * I + r < T, out_ptr);
 #endif
         out_ptr += (size_t)kBlock * out_tstride;
         SLA_STAMP(2);
-        flag_signal(done + sl, lane);
         SLA_STAMP(3);
         SLA_FLUSH(I);
     };

@@ -137,7 +137,7 @@ def test_zero_length_passes_state_through():
 
 # ------------------------------------------------------------------ robustness
 def test_strong_decay_within_documented_range():
-    """log-decay down to -4 per token (documented bound: -5): the 1/p factors reach e^60 and must not overflow."""
+    """log-decay down to -4 per token (documented bound: -5): the 1/p factors reach e^64 and must not overflow."""
     d = si.custom(GLA, "bf16", B=1, T=100, H=2, dk=128, dv=64, seed=1000)
     rng = np.random.default_rng(5)
     ld = -rng.uniform(0.0, 4.0, size=d["log_decay"].shape).astype(np.float32)
