@@ -22,7 +22,13 @@ METRIC = "tokens/sec SLA-GLA chunked fwd (B=8,T=2048,H=16,d=128 bf16); % MFMA pe
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for a workload, calibrated
 # against a plain copy of known size in the same run (figures and commands: profiles/*.md).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"gla_train": 346.3e6}  # profiles/sla_fwd_bf16_gla_train.md
+MEASURED_TRAFFIC_BYTES = {
+    "gla_train": 346.2e6,     # profiles/sla_fwd_bf16_gla_train.md
+    "retnet_train": 279.1e6,  # profiles/sla_fwd_bf16_retnet_train.md
+    "gdn": 553.8e6,           # profiles/sla_fwd_bf16_gdn.md
+    "retnet": 125.1e6,        # profiles/sla_fwd_bf16_segmented_retnet_gla_long.md (three kernels)
+    "gla_long": 4.063e9,      # same file
+}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 BLOCK = 16                      # tokens per state step in the kernels (for the causal flop count)
 

@@ -16,6 +16,19 @@ def test_full_size_workload(name):
     check(w.variant, si.generate(w), w.dtype, label=f"full {name}")
 
 
+@pytest.mark.parametrize("name", ["retnet", "gla_long"])
+def test_full_size_segmented(name):
+    """The 32-sequence workloads in the schedule bench.py times: the library's own choice of segments."""
+    import torch
+    import paper_2602_01744_amd as sla
+
+    w = si.workload(name)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    p = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 0)
+    assert sla.sla_segments(p, cus) > 1
+    check(w.variant, si.generate(w), w.dtype, label=f"full {name}, segments chosen by the library", segments=0)
+
+
 def test_full_size_long_context():
     """B=1, T=65536, H=32: 1024 chunks of state carry in the winner-take-all regime (peaked logits)."""
     w = si.workload("gla_long")
