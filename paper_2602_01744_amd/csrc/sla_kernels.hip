@@ -276,11 +276,7 @@ struct Smem {
     static constexpr size_t flag_bytes = 2 * kMaxSlots * sizeof(int);  // ready[] and done[] counters
     // Ring of slots, one producer wave per slot: eight where they fit in the LDS of a CU, else four.
     // The delta rule keeps four: its waves need more registers than twelve waves per CU leave each.
-#ifdef SLA_SLOTS
-    static constexpr int slots = SLA_SLOTS;
-#else
     static constexpr int slots = (VAR != SLA_GDN && kMaxSlots * bytes + flag_bytes <= limit) ? kMaxSlots : 4;
-#endif
     static constexpr size_t oFlags = slots * bytes;
     static constexpr size_t total = oFlags + flag_bytes;
     static constexpr int threads = (kWaves + slots) * 64;
@@ -865,13 +861,9 @@ typedef __attribute__((address_space(3))) int lds_int;  // the counters are addr
 
 __device__ __forceinline__ int flag_peek(const lds_int* f) { return *(const volatile lds_int*)f; }
 
-#ifndef SLA_SLEEP
-#define SLA_SLEEP 1
-#endif
-template <int SLEEP = 1>
 __device__ __forceinline__ void flag_wait(const lds_int* f, int target) {
     int spin = 0;
-    while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(SLEEP);
+    while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
     asm volatile("" ::: "memory");
 }
 
@@ -1032,7 +1024,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         SLA_TRACE_DECL
         for (int I = pw, use = 0; I < nblocks; I += NP, ++use) {
             SLA_STAMP(7);
-            flag_wait<SLA_SLEEP>(done + pw, NCW * use);  // the consumers have finished the block that was here
+            flag_wait(done + pw, NCW * use);  // the consumers have finished the block that was here
             ldr.advance(kBlock * NP);          // every staging register is refilled for block I + NP
 #if SLA_EXP != 2
             produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, 0, kBlock * I, kBlock * (I + NP), T, decay_const, dacc,
@@ -1052,10 +1044,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
     // ---------------------------------------------------------------- consumer waves
     const int cw = wave;
     if (cw >= NCW) return;
-#ifndef SLA_CPRIO
-#define SLA_CPRIO 2
-#endif
-    __builtin_amdgcn_s_setprio(SLA_CPRIO);  // the state recurrence is the serial part: let it issue first
+    __builtin_amdgcn_s_setprio(2);  // the state recurrence is the serial part: let it issue first
     // State slice: tile s holds S[16s + 4g + i][n0 + 16*cw + r] in S[s][i].
     f32x4 S[NTILE];
 #pragma unroll
