@@ -28,6 +28,8 @@ MEASURED_TRAFFIC_BYTES = {
     "gdn": 553.8e6,           # profiles/sla_fwd_bf16_gdn.md
     "retnet": 125.1e6,        # profiles/sla_fwd_bf16_segmented_retnet_gla_long.md (three kernels)
     "gla_long": 4.063e9,      # same file
+    "decode_gla": 135.7e6,    # profiles/sla_decode_bf16.md
+    "decode_gdn": 135.7e6,    # same file
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 BLOCK = 16                      # tokens per state step in the kernels (for the causal flop count)
@@ -54,6 +56,124 @@ def algorithmic_flops(w) -> int:
     if w.variant == 2:
         per += 2 * w.dk * w.dv + (C + 1) * (w.dk + w.dv) + (C * C) // 3
     return w.B * w.T * w.H * per
+
+
+def decode_bytes(w) -> int:
+    """One decode step: the fp32 state is read and rewritten; q, k, v, out, decay, logits once."""
+    es = 2 if w.dtype == "bf16" else 4
+    per_head = 2 * w.dk * w.dv * 4 + (2 * w.dk + 2 * w.dv) * es + 8
+    if w.variant == 1:
+        per_head += w.dk * es
+    elif w.variant == 2:
+        per_head += 8
+    return w.B * w.H * per_head
+
+
+def bench_decode(args, w, sla, si, torch, np) -> int:
+    """--workload decode_*: a step is one recurrent decode step (sla_decode_step) over the batch; the state
+    stays resident and is updated in place, as in serving."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import rel_err, to_device
+
+    d = si.generate(w)
+    s0 = si.initial_state(w.B, w.H, w.dk, w.dv, seed=w.seed)
+    g, tdt = to_device(d, w.dtype, w.variant)
+    dev = torch.device("cuda:0")
+    sq = lambda t: None if t is None else (t if t.dim() == 1 else t[:, 0].contiguous())
+    q, k, v, ql, kl, beta = (sq(g[n]) for n in ("q", "k", "v", "q_logits", "k_logits", "beta"))
+    ld = sq(g["log_decay"])
+    state = torch.from_numpy(s0).to(dev)
+    out = torch.empty((w.B, w.H, w.dv), dtype=tdt, device=dev)
+    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, 1, w.H, w.dk, w.dv, 0, 0, 1)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    raw = (ptr(q), ptr(k), ptr(v), ptr(ql), ptr(kl), ptr(ld), ptr(beta), ptr(state), ptr(out),
+           torch.cuda.current_stream(dev).cuda_stream)
+
+    def step():
+        rc = sla.sla_decode_step(params, *raw)
+        if rc != 0:
+            raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    result_parity = None
+    if not args.no_parity or not args.no_cpu_baseline:
+        import oracle
+
+        nthreads = oracle.threads(0)
+        passes, cpu_s = 0, 0.0
+        while True:
+            t0 = time.perf_counter()
+            ro, rf = oracle.forward(w.variant, d["q"], d["k"], d["v"], d["q_logits"], d["k_logits"], d["log_decay"],
+                                    d["beta"], s0)
+            cpu_s += time.perf_counter() - t0
+            passes += 1
+            if args.no_cpu_baseline or cpu_s * nthreads >= 15.0 or passes >= 200:
+                break
+        step()  # the first step from the seeded state is the one compared
+        torch.cuda.synchronize()
+        result_parity = {
+            "out_rel_err": rel_err(out.to(torch.float32).cpu().numpy().astype(np.float64), ro[:, 0]),
+            "state_rel_err": rel_err(state.cpu().numpy().astype(np.float64), rf),
+            "definition": "max|x - oracle| / max|oracle| per tensor, first step from the seeded state",
+        }
+    for _ in range(args.settle + args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    kernel_ms = float(np.mean(per_launch_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    abytes = decode_bytes(w)
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "tokens/sec SLA decode step (one token per sequence)",
+        "value": w.B / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "settle_launches": args.settle,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: SLA-{si.VARIANT_NAMES[w.variant].upper()} decode step B={w.B} H={w.H} dk={w.dk} "
+                        f"dv={w.dv} {w.dtype} in/out, fp32 state updated in place, dual head-softmax gates",
+            "kernel": "sla_decode_kernel",
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "kernel_us": kernel_ms * 1e3,
+            "kernel_us_min": float(np.min(per_launch_ms)) * 1e3,
+            "algorithmic_bytes": abytes,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = {
+            "value": w.B * passes / cpu_s,
+            "unit": "tokens/s",
+            "cores": nthreads,
+            "kind": "oracle",
+            "sample": f"the full decode batch, {passes} pass(es) ({w.B} tokens x {w.H} heads each, {cpu_s:.2f} s wall)",
+        }
+    if result_parity is not None and not args.no_parity:
+        result["parity"] = result_parity
+    print(json.dumps(result), flush=True)
+    return 0
 
 
 def main() -> int:
@@ -91,6 +211,8 @@ def main() -> int:
         return 2
     sla.load_library()  # fails loudly if the HIP library is not built
     w = si.workload(args.workload)
+    if w.name in si.DECODE_WORKLOAD_NAMES:
+        return bench_decode(args, w, sla, si, torch, np)
     d = si.generate(w)
 
     sys.path.insert(0, os.path.join(ROOT, "tests"))

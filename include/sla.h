@@ -116,6 +116,24 @@ int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void
                    const void* log_decay, const float* beta, const float* initial_state,
                    void* out, float* final_state, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * One recurrent decode step: Eq. 5-6 with the Sec. 5.1 recurrences for a single token per (batch, head), the
+ * constant-memory inference form of Appendix A ("Recurrent Form"; Sec. 5.7 "Inference latency").  Exactly
+ * sla_forward for T = 1 with initial_state = final_state = state, as one streaming read-modify-write of the
+ * state.  p->T must be 1; dv_split and segments are ignored.
+ *
+ *   q, k            [B,H,dk]    dtype
+ *   v               [B,H,dv]    dtype
+ *   q_head_logits   [B,H]       fp32; k_head_logits [B,H] fp32 or NULL (G^K = 1)
+ *   log_decay       RetNet: fp32 [H];  GLA: dtype [B,H,dk];  GDN: fp32 [B,H]
+ *   beta            GDN: fp32 [B,H]; NULL otherwise
+ *   state           [B,H,dk,dv] fp32    read and overwritten with the state after the token; required
+ *   out             [B,H,dv]    dtype   written
+ */
+int sla_decode_step(const sla_params* p, const void* q, const void* k, const void* v,
+                    const float* q_head_logits, const float* k_head_logits,
+                    const void* log_decay, const float* beta, float* state, void* out, void* stream);
+
 /* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
 size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 

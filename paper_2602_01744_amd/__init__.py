@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     sla_check_args,
+    sla_decode_step,
     sla_default_dv_split,
     sla_forward,
     sla_forward_ws,
@@ -25,6 +26,7 @@ from .binding import (  # noqa: F401
     sla_status_string,
     sla_version,
     forward,
+    decode_step,
 )
 
 # Variants with kernels in this build (sla_forward returns SLA_ERR_UNSUPPORTED for the others).

@@ -61,6 +61,8 @@ def load_library():
     lib.sla_forward.argtypes = [pp] + [vp] * 11
     lib.sla_forward_ws.restype = ctypes.c_int
     lib.sla_forward_ws.argtypes = [pp] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.sla_decode_step.restype = ctypes.c_int
+    lib.sla_decode_step.argtypes = [pp] + [vp] * 10
     lib.sla_workspace_bytes.restype = ctypes.c_size_t
     lib.sla_workspace_bytes.argtypes = [pp, ctypes.c_int]
     lib.sla_segments.restype = ctypes.c_int
@@ -141,6 +143,48 @@ def sla_forward_ws(params, q, k, v, q_head_logits, k_head_logits, log_decay, bet
             _p(initial_state), _p(out), _p(final_state), _p(workspace), int(workspace_bytes), _p(stream),
         )
     )
+
+
+def sla_decode_step(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out, stream) -> int:
+    """Raw call of the decode entry point (same conventions as sla_forward)."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_decode_step(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta), _p(state),
+            _p(out), _p(stream),
+        )
+    )
+
+
+def decode_step(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, *, out=None):
+    """One recurrent step on the current CUDA(HIP) device and stream: q, k [B,H,dk], v [B,H,dv], logits / beta
+    [B,H] float32, state [B,H,dk,dv] float32 (updated in place).  Returns out [B,H,dv]."""
+    import torch
+
+    assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == (B, H, dk) and v.shape == (B, H, dv) and k.dtype == q.dtype and v.dtype == q.dtype
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+    assert q_head_logits.dtype == torch.float32 and q_head_logits.shape == (B, H) and q_head_logits.is_contiguous()
+    if k_head_logits is not None:
+        assert k_head_logits.dtype == torch.float32 and k_head_logits.shape == (B, H) and k_head_logits.is_contiguous()
+    want = {RETNET: ((H,), torch.float32), GLA: ((B, H, dk), q.dtype), GDN: ((B, H), torch.float32)}[variant]
+    assert tuple(log_decay.shape) == want[0] and log_decay.dtype == want[1] and log_decay.is_contiguous()
+    if beta is not None:
+        assert beta.dtype == torch.float32 and beta.shape == (B, H) and beta.is_contiguous()
+    assert state.dtype == torch.float32 and state.shape == (B, H, dk, dv) and state.is_contiguous()
+    if out is None:
+        out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+    params = SlaParams(variant, dtype, B, 1, H, dk, dv, 0, 0, 1)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_decode_step(
+        params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta), ptr(state),
+        ptr(out), torch.cuda.current_stream(q.device).cuda_stream,
+    )
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return out
 
 
 _cus = {}

@@ -11,6 +11,8 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
                    const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
                    float* sT, float* workspace, hipStream_t stream);
 size_t segment_workspace_floats(const sla_params& p, int nseg);
+int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
+                  const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
 
 namespace {
@@ -154,6 +156,18 @@ int sla_forward(const sla_params* p, const void* q, const void* k, const void* v
                 void* out, float* final_state, void* stream) {
     return sla_forward_ws(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state,
                           nullptr, 0, stream);
+}
+
+int sla_decode_step(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                    const float* k_head_logits, const void* log_decay, const float* beta, float* state, void* out,
+                    void* stream) {
+    const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out, state);
+    if (rc != SLA_OK) return rc;
+    if (p->T != 1) return SLA_ERR_SHAPE;
+    if (p->B == 0) return SLA_OK;
+    if (!state) return SLA_ERR_NULL;
+    return sla::launch_decode(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out,
+                              (hipStream_t)stream);
 }
 
 size_t sla_workspace_bytes(const sla_params* p, int compute_units) {

@@ -97,11 +97,18 @@ def workload(name: str) -> Workload:
         "gdn_train": Workload(
             "gdn_train", GDN, "bf16", 8, 2048, 16, 128, 128, SEED_BASE + 6, qk_prep="l2", decay_div=8.0
         ),
+        # One decode step (T = 1) over a serving-sized batch: the recurrent form, one token per sequence.
+        "decode_gla": Workload("decode_gla", GLA, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 7),
+        "decode_retnet": Workload("decode_retnet", RETNET, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 8),
+        "decode_gdn": Workload(
+            "decode_gdn", GDN, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 9, qk_prep="l2", decay_div=8.0
+        ),
     }
     return dataclasses.replace(table[name])
 
 
 WORKLOAD_NAMES = ("gla_tiny", "retnet", "gla_train", "gdn", "gla_long", "retnet_train", "gdn_train")
+DECODE_WORKLOAD_NAMES = ("decode_gla", "decode_retnet", "decode_gdn")
 
 
 def _normal(rng: np.random.Generator, shape) -> np.ndarray:

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -142,6 +142,18 @@ def test_segments_need_a_workspace(lib):
     assert sla.sla_forward_ws(_ok_params(dk=96), A, A, A, A, A, A, 0, 0, A, A, A, 1 << 30, 0) == -3
     assert sla.sla_forward_ws(_ok_params(), A, A, A, A, A, A, 0, 0, A, A, A + 4, 1 << 30, 0) == -4
     assert sla.sla_forward_ws(_ok_params(B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
+
+
+def test_decode_step_validation(lib):
+    one = _ok_params(T=1)
+    args = (A, A, A, A, A, A, 0)
+    assert sla.sla_decode_step(_ok_params(T=2), *args, A, A, 0) == -2          # one token per call
+    assert sla.sla_decode_step(_ok_params(T=1, dk=96), *args, A, A, 0) == -3
+    assert sla.sla_decode_step(one, 0, A, A, A, A, A, 0, A, A, 0) == -1        # q missing
+    assert sla.sla_decode_step(one, *args, 0, A, 0) == -1                      # the state is required
+    assert sla.sla_decode_step(one, *args, A + 4, A, 0) == -4
+    assert sla.sla_decode_step(_ok_params(T=1, variant=sla.GDN), *args, A, A, 0) == -1   # GDN needs beta
+    assert sla.sla_decode_step(_ok_params(T=1, B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):

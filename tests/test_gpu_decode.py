@@ -1,0 +1,124 @@
+"""GPU parity of the recurrent decode step (sla_decode_step through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import sla_inputs as si
+from gpu_util import GDN, GLA, RETNET, TOL, rel_err, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [RETNET, GLA, GDN]
+
+
+def _name(v):
+    return si.VARIANT_NAMES[v]
+
+
+def _dev(a, dtype, narrow):
+    import torch
+
+    if a is None:
+        return None
+    x = torch.from_numpy(np.ascontiguousarray(a))
+    if narrow and dtype == "bf16":
+        y = x.to(torch.bfloat16)
+        assert torch.equal(y.to(torch.float32), x), "inputs must be bf16-representable"
+        x = y
+    return x.cuda().contiguous()
+
+
+def decode_chain(variant, d, dtype, state0):
+    """Feeds the T tokens of d one at a time; returns (out [B,T,H,dv], final state) as float64."""
+    import torch
+    import paper_2602_01744_amd as sla
+
+    B, T, H, dk = d["q"].shape
+    state = torch.from_numpy(np.ascontiguousarray(state0, dtype=np.float32)).cuda()
+    outs = []
+    ld_all = d["log_decay"]
+    for t in range(T):
+        q, k, v = (_dev(d[n][:, t], dtype, True) for n in ("q", "k", "v"))
+        ql = _dev(d["q_logits"][:, t], dtype, False)
+        kl = None if d["k_logits"] is None else _dev(d["k_logits"][:, t], dtype, False)
+        ld = _dev(ld_all if variant == RETNET else ld_all[:, t], dtype, variant == GLA)
+        beta = None if d["beta"] is None else _dev(d["beta"][:, t], dtype, False)
+        o = sla.decode_step(variant, q, k, v, ql, kl, ld, beta, state)
+        outs.append(o.to(torch.float32).cpu().numpy().astype(np.float64))
+    torch.cuda.synchronize()
+    return np.stack(outs, 1), state.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dk,dv", [(128, 128), (64, 64), (64, 128), (128, 64)])
+def test_single_step_matches_oracle(variant, dtype, dk, dv):
+    d = si.custom(variant, dtype, B=3, T=1, H=5, dk=dk, dv=dv, seed=2100 + variant + dk + dv)
+    s0 = si.initial_state(3, 5, dk, dv, seed=21)
+    o, f = decode_chain(variant, d, dtype, s0)
+    ro, rf = run_oracle(variant, d, s0)
+    eo, ef = rel_err(o, ro), rel_err(f, rf)
+    print(f"[parity] decode {_name(variant)} {dtype} dk={dk} dv={dv} out_err={eo:.3e} state_err={ef:.3e}", flush=True)
+    assert eo <= TOL[dtype] and ef <= 1e-5  # the state stays fp32 end to end
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("H", [1, 2, 7, 16, 33, 64])
+def test_head_counts(variant, H):
+    d = si.custom(variant, "bf16", B=2, T=1, H=H, dk=64, dv=64, seed=2200 + H)
+    s0 = si.initial_state(2, H, 64, 64, seed=22)
+    o, f = decode_chain(variant, d, "bf16", s0)
+    ro, rf = run_oracle(variant, d, s0)
+    assert rel_err(o, ro) <= TOL["bf16"] and rel_err(f, rf) <= 1e-5
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_chain_of_steps_equals_the_sequence_forward(variant):
+    """24 decode steps from a given state: every output and the final state against the oracle's forward over
+    the same 24 tokens, and against the chunked GPU forward."""
+    T = 24
+    d = si.custom(variant, "bf16", B=2, T=T, H=4, dk=128, dv=128, seed=2300 + variant)
+    s0 = si.initial_state(2, 4, 128, 128, seed=23)
+    o, f = decode_chain(variant, d, "bf16", s0)
+    ro, rf = run_oracle(variant, d, s0)
+    assert rel_err(o, ro) <= TOL["bf16"]
+    assert rel_err(f, rf) <= 1e-5
+    go, gf = run_gpu(variant, d, "bf16", s0)
+    assert rel_err(go, o) <= TOL["bf16"] and rel_err(gf, f) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_read_gate_only_and_saturated_gates(variant):
+    H, sel = 4, 2
+    d = si.custom(variant, "bf16", B=2, T=3, H=H, dk=64, dv=128, seed=2400, dual_gates=False)
+    s0 = si.initial_state(2, H, 64, 128, seed=24)
+    o, f = decode_chain(variant, d, "bf16", s0)
+    ro, rf = run_oracle(variant, d, s0)
+    assert rel_err(o, ro) <= TOL["bf16"] and rel_err(f, rf) <= 1e-5
+    # a saturated read gate selects one head: the others output exact zeros (Thm 4.2 limit)
+    sat = np.zeros_like(d["q_logits"]); sat[..., sel] = 1e4
+    d["q_logits"] = sat
+    o, f = decode_chain(variant, d, "bf16", s0)
+    assert np.all(o[:, :, [h for h in range(H) if h != sel]] == 0.0)
+    assert np.abs(o[:, :, sel]).max() > 0
+
+
+def test_zero_decay_zero_beta_leaves_the_state_alone():
+    """Delta rule with beta = 0 and log-decay 0: the state must come back bit for bit."""
+    d = si.custom(GDN, "f32", B=1, T=2, H=2, dk=64, dv=64, seed=2500)
+    d["beta"] = np.zeros_like(d["beta"]); d["log_decay"] = np.zeros_like(d["log_decay"])
+    s0 = si.initial_state(1, 2, 64, 64, seed=25)
+    o, f = decode_chain(GDN, d, "f32", s0)
+    np.testing.assert_array_equal(f, s0.astype(np.float64))
+
+
+def test_full_size_decode_batch():
+    """The shape bench.py times for the decode step (B=64, H=16, d=128, bf16): sampled heads against the oracle."""
+    import torch
+    import paper_2602_01744_amd as sla
+
+    B, H, dk, dv = 64, 16, 128, 128
+    d = si.custom(GLA, "bf16", B=B, T=1, H=H, dk=dk, dv=dv, seed=2600)
+    s0 = si.initial_state(B, H, dk, dv, seed=26)
+    o, f = decode_chain(GLA, d, "bf16", s0)
+    ro, rf = run_oracle(GLA, d, s0)
+    assert rel_err(o, ro) <= TOL["bf16"] and rel_err(f, rf) <= 1e-5
