@@ -449,6 +449,29 @@ __device__ __forceinline__ void scale_state_rows(f32x4 (&S)[NT], float ea0, floa
     }
 }
 
+// Forward substitution for the 16x16 unit-lower-triangular inverse of the delta rule, one column per lane:
+// x[j] = [j == c] - sum_{i<j} L[j][i] x[i], where lane i of the row holds Lc[j] = -L[j][i].
+template <int J, int I>
+__device__ __forceinline__ float tm_row(const float (&x)[kBlock], float neg_lcj, float acc) {
+    if constexpr (I < J) {
+        // acc += (-L[j][i] from lane i of the row) * x[i] in one instruction.  neg_lcj was written long before,
+        // so the DPP read needs no wait states; x and acc are ordinary operands.
+        asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+            : "+v"(acc)
+            : "v"(neg_lcj), "v"(x[I]), "n"(I));
+        return tm_row<J, I + 1>(x, neg_lcj, acc);
+    } else {
+        return acc;
+    }
+}
+template <int J>
+__device__ __forceinline__ void tm_substitute(float (&x)[kBlock], const float (&Lc)[kBlock], int c) {
+    if constexpr (J < kBlock) {
+        x[J] = tm_row<J, 0>(x, Lc[J], (J == c) ? 1.f : 0.f);  // Lc holds -L
+        tm_substitute<J + 1>(x, Lc, c);
+    }
+}
+
 // softmax over heads for the token of this quad (Eq. 4); returns the gate of head h.
 template <int HG>
 __device__ __forceinline__ float head_gate(const float (&x)[HG], float own) {
@@ -641,25 +664,30 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 #pragma unroll
         for (int s = 0; s < NTILE; s += 2) P::mma32(G, fk_[s], fk_[s + 1], fk_[s], fk_[s + 1]);
         const f32x4 btj = *(const f32x4*)(BT + 4 * g);
+        // L goes through LDS once, transposed, so that every lane ends up with a whole column of it:
+        // Lc[j] = L[j][r].  The substitution then runs on registers: the factor L[j][i] of step (j, i) is
+        // taken from lane i of the row by a DPP broadcast.
+        f32x4 lv;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            TM[(4 * g + i) * kBlock + r] = (4 * g + i > r) ? btj[i] * fast_exp2(cj[i] - c_lane) * G[i] : 0.f;
+        for (int i = 0; i < 4; ++i) lv[i] = (4 * g + i > r) ? btj[i] * fast_exp2(cj[i] - c_lane) * G[i] : 0.f;
+        *(f32x4*)(TM + r * kBlock + 4 * g) = lv;
         __builtin_amdgcn_wave_barrier();
+        float Lc[kBlock];
+#pragma unroll
+        for (int j4 = 0; j4 < kBlock; j4 += 4) {
+            const f32x4 t = *(const f32x4*)(TM + r * kBlock + j4);
+            Lc[j4] = -t[0]; Lc[j4 + 1] = -t[1]; Lc[j4 + 2] = -t[2]; Lc[j4 + 3] = -t[3];  // negated for the fmac
+        }
         // forward substitution, column c = r of the inverse in every lane (the four lane groups repeat it):
         // x_j = [j == c] - sum_{i<j} L[j][i] x_i
+        // A DPP operand must not have been written by the two instructions before its use: pin all sixteen
+        // factors behind two wait states before the first of them is read across lanes.
+        asm volatile("s_nop 1"
+                     : "+v"(Lc[0]), "+v"(Lc[1]), "+v"(Lc[2]), "+v"(Lc[3]), "+v"(Lc[4]), "+v"(Lc[5]), "+v"(Lc[6]), "+v"(Lc[7]),
+                       "+v"(Lc[8]), "+v"(Lc[9]), "+v"(Lc[10]), "+v"(Lc[11]), "+v"(Lc[12]), "+v"(Lc[13]), "+v"(Lc[14]),
+                       "+v"(Lc[15]));
         float x[kBlock];
-#pragma unroll
-        for (int j = 0; j < kBlock; ++j) {
-            float acc = (j == r) ? 1.f : 0.f;
-#pragma unroll
-            for (int i4 = 0; i4 < j; i4 += 4) {
-                const f32x4 lrow = *(const f32x4*)(TM + j * kBlock + i4);  // same address in all lanes
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (i4 + i < j) acc -= lrow[i] * x[i4 + i];
-            }
-            x[j] = acc;
-        }
+        tm_substitute<0>(x, Lc, r);
         __builtin_amdgcn_wave_barrier();  // every lane has read L before it is overwritten
         if (g == 0) {
 #pragma unroll
