@@ -66,7 +66,7 @@ typedef struct {
     int32_t T;       /* tokens per sequence   >= 0 */
     int32_t H;       /* heads                 1..64 */
     int32_t dk;      /* key/query head width  64 or 128 */
-    int32_t dv;      /* value head width      64 or 128 */
+    int32_t dv;      /* value head width      64, 128 or 256 */
     int32_t dv_split; /* 0 = let the library choose; else value columns per workgroup: 16, 32, 64 or 128 (<= dv).
                         A scheduling knob only: the result does not depend on it beyond nothing at all
                         (each output column is computed by exactly one workgroup in a fixed order). */

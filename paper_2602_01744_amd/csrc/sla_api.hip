@@ -31,7 +31,7 @@ int check_params(const sla_params* p) {
     if (p->segments > 1 && p->variant == SLA_GDN) return SLA_ERR_UNSUPPORTED;
     if (p->B < 0 || p->T < 0 || p->H < 1 || p->H > kMaxHeads) return SLA_ERR_SHAPE;
     if (p->dk < 1 || p->dv < 1) return SLA_ERR_SHAPE;
-    if ((p->dk != 64 && p->dk != 128) || (p->dv != 64 && p->dv != 128)) return SLA_ERR_UNSUPPORTED;
+    if ((p->dk != 64 && p->dk != 128) || (p->dv != 64 && p->dv != 128 && p->dv != 256)) return SLA_ERR_UNSUPPORTED;
     if (p->dv_split != 0) {
         const int s = p->dv_split;
         if (s != 16 && s != 32 && s != 64 && s != 128) return SLA_ERR_SHAPE;
@@ -189,7 +189,7 @@ int sla_segments(const sla_params* p, int compute_units) {
 int sla_default_dv_split(const sla_params* p, int compute_units) {
     if (!p) return SLA_ERR_NULL;
     if (compute_units <= 0) return SLA_ERR_SHAPE;
-    if ((p->dv != 64 && p->dv != 128) || p->B < 0 || p->H < 1) return SLA_ERR_SHAPE;
+    if ((p->dv != 64 && p->dv != 128 && p->dv != 256) || p->B < 0 || p->H < 1) return SLA_ERR_SHAPE;
     sla_params c = *p;
     c.dv_split = 0;
     int seg_len = 0;
@@ -201,7 +201,7 @@ const char* sla_kernel_name(const sla_params* p) {
     static thread_local char buf[128];
     if (!p) return nullptr;
     if (p->variant < 0 || p->variant > 2 || (p->dtype != SLA_F32 && p->dtype != SLA_BF16)) return nullptr;
-    if (p->dv != 64 && p->dv != 128) return nullptr;
+    if (p->dv != 64 && p->dv != 128 && p->dv != 256) return nullptr;
     int seg_len = 0;  // dv_split == 0 is resolved as on a 256-CU device, for the schedule p->segments asks for
     const int nseg = (p->segments > 1 && p->T > 0 && p->variant != SLA_GDN) ? choose_segments(*p, 256, &seg_len) : 1;
     const int dvw = choose_dv_split(*p, 256, nseg);

@@ -166,6 +166,7 @@ int launch_dv(const DArgs& a, int dv, hipStream_t stream) {
     switch (dv) {
         case 64: hipLaunchKernelGGL((sla_decode_kernel<BF16, VAR, DK, 64>), grid, block, 0, stream, a); break;
         case 128: hipLaunchKernelGGL((sla_decode_kernel<BF16, VAR, DK, 128>), grid, block, 0, stream, a); break;
+        case 256: hipLaunchKernelGGL((sla_decode_kernel<BF16, VAR, DK, 256>), grid, block, 0, stream, a); break;
         default: return SLA_ERR_UNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;

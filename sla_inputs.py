@@ -97,6 +97,10 @@ def workload(name: str) -> Workload:
         "gdn_train": Workload(
             "gdn_train", GDN, "bf16", 8, 2048, 16, 128, 128, SEED_BASE + 6, qk_prep="l2", decay_div=8.0
         ),
+        # The paper's 340M-class model shapes (Sec. 5.2 "Model Configuration": hidden 1024, few wide heads; GLA keys
+        # at half width) at its training length, and the H = 8 point of its head ablation at the same width.
+        "gla_paper_h4": Workload("gla_paper_h4", GLA, "bf16", 8, 4096, 4, 128, 256, SEED_BASE + 10),
+        "gla_paper_h8": Workload("gla_paper_h8", GLA, "bf16", 8, 4096, 8, 64, 128, SEED_BASE + 11),
         # One decode step (T = 1) over a serving-sized batch: the recurrent form, one token per sequence.
         "decode_gla": Workload("decode_gla", GLA, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 7),
         "decode_retnet": Workload("decode_retnet", RETNET, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 8),
@@ -107,7 +111,8 @@ def workload(name: str) -> Workload:
     return dataclasses.replace(table[name])
 
 
-WORKLOAD_NAMES = ("gla_tiny", "retnet", "gla_train", "gdn", "gla_long", "retnet_train", "gdn_train")
+WORKLOAD_NAMES = ("gla_tiny", "retnet", "gla_train", "gdn", "gla_long", "retnet_train", "gdn_train", "gla_paper_h4",
+                  "gla_paper_h8")
 DECODE_WORKLOAD_NAMES = ("decode_gla", "decode_retnet", "decode_gdn")
 
 

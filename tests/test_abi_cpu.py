@@ -75,7 +75,8 @@ def test_shapes_and_unsupported(lib):
     assert _call(_ok_params(H=65)) == -2
     assert _call(_ok_params(dk=0)) == -2
     assert _call(_ok_params(dk=96)) == -3
-    assert _call(_ok_params(dv=256)) == -3
+    assert _call(_ok_params(dv=512)) == -3
+    assert _call(_ok_params(dv=256)) == 0
     assert _call(_ok_params(variant=7)) == -3
     assert _call(_ok_params(dtype=2)) == -3
     assert _call(_ok_params(flags=1)) == -3

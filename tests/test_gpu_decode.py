@@ -50,7 +50,7 @@ def decode_chain(variant, d, dtype, state0):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("dk,dv", [(128, 128), (64, 64), (64, 128), (128, 64)])
+@pytest.mark.parametrize("dk,dv", [(128, 128), (64, 64), (64, 128), (128, 64), (128, 256), (64, 256)])
 def test_single_step_matches_oracle(variant, dtype, dk, dv):
     d = si.custom(variant, dtype, B=3, T=1, H=5, dk=dk, dv=dv, seed=2100 + variant + dk + dv)
     s0 = si.initial_state(3, 5, dk, dv, seed=21)

@@ -16,7 +16,7 @@ def test_full_size_workload(name):
     check(w.variant, si.generate(w), w.dtype, label=f"full {name}")
 
 
-@pytest.mark.parametrize("name", ["retnet", "gla_long"])
+@pytest.mark.parametrize("name", ["retnet", "gla_long", "gla_paper_h4", "gla_paper_h8"])
 def test_full_size_segmented(name):
     """The 32-sequence workloads in the schedule bench.py times: the library's own choice of segments."""
     import torch

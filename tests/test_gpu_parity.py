@@ -39,6 +39,16 @@ def test_head_widths(variant, dk, dv):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dk", [64, 128])
+def test_wide_values(variant, dk):
+    """dv = 256 (the paper's 340M-class GLA shape has dk = 128, dv = 256): four 64-column slices per head."""
+    for dtype in ("f32", "bf16"):
+        d = si.custom(variant, dtype, B=1, T=150, H=2, dk=dk, dv=256, seed=250 + dk)
+        s0 = si.initial_state(1, 2, dk, 256, seed=8)
+        check(variant, d, dtype, s0, label=f"{_name(variant)} dk={dk} dv=256")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 63, 64, 65])
 def test_short_sequences(variant, T):
     d = si.custom(variant, "bf16", B=2, T=T, H=4, dk=128, dv=64, seed=300 + T)
