@@ -275,8 +275,10 @@ struct Smem {
     static constexpr size_t limit = 160 * 1024;
     static constexpr size_t flag_bytes = 2 * kMaxSlots * sizeof(int);  // ready[] and done[] counters
     // Ring of slots, one producer wave per slot: eight where they fit in the LDS of a CU, else four.
-    // The delta rule keeps four: its waves need more registers than twelve waves per CU leave each.
-    static constexpr int slots = (VAR != SLA_GDN && kMaxSlots * bytes + flag_bytes <= limit) ? kMaxSlots : 4;
+    static constexpr int slots = (kMaxSlots * bytes + flag_bytes <= limit) ? kMaxSlots : 4;
+    // Consumers request a block's operands a block ahead into a second set of registers -- except for the
+    // delta rule, whose operand set is large: with twelve waves per CU there are 168 registers per lane.
+    static constexpr bool prefetch = VAR != SLA_GDN;
     static constexpr size_t oFlags = slots * bytes;
     static constexpr size_t total = oFlags + flag_bytes;
     static constexpr int threads = (kWaves + slots) * 64;
@@ -834,41 +836,47 @@ struct BlockFrags {
     f32x4 bt, tm;                              // delta rule: beta_j (j = 4g..4g+3), Tm[r][4g..4g+3]
 };
 
-template <class P, int VAR, int DK, int DVW, bool SO>
+// Requests the LDS operands of one block.  PART 0: all of them.  The delta rule asks in two parts: 1 = what
+// its dependent chain starts with (k rows, v', decays, beta, Tm), 2 = the rest (q rows, k^T, scores, gate).
+template <class P, int VAR, int DK, int DVW, bool SO, int PART = 0>
 __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, const unsigned char* buf, int cw, int lane) {
     typedef typename P::elem elem;
     typedef typename P::frag frag;
     typedef Smem<P, VAR, DK, DVW> L;
     constexpr int NTILE = DK / 16;
+    constexpr bool EARLY = PART != 2, LATE = PART != 1;
     const int r = lane & 15, g = lane >> 4;
     const elem* QA = (const elem*)(buf + L::oQA);
-    if constexpr (!SO) {
+    if constexpr (!SO && LATE) {
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) f.fq[s] = *(const frag*)(QA + r * L::RS + 32 * (s / 2) + 8 * g + 4 * (s & 1));
         f.fp = ((const frag*)(buf + L::oPT))[lane];
         f.gq = ((const float*)(buf + L::oGQ))[r];
     }
-    if constexpr (VAR != SLA_GLA) {
+    if constexpr (VAR != SLA_GLA && EARLY) {
         const float* C2 = (const float*)(buf + L::oP1);
         f.ct = C2[r];
         f.c16 = C2[kBlock - 1];
         f.cj = *(const f32x4*)(C2 + 4 * g);
     }
-    if constexpr (VAR == SLA_GDN) {
+    if constexpr (VAR == SLA_GDN && EARLY) {
         const elem* KD = (const elem*)(buf + L::oKD);
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + r * L::RS + 32 * (s / 2) + 8 * g + 4 * (s & 1));
         f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + 4 * g);
         f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + r * kBlock + 4 * g);
     }
-    f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + 4 * g);
-    const elem* KBT = (const elem*)(buf + L::oKBT);
+    if constexpr (EARLY) f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + 4 * g);
+    if constexpr (LATE) {
+        const elem* KBT = (const elem*)(buf + L::oKBT);
 #pragma unroll
-    for (int s = 0; s < NTILE; ++s) f.fk[s] = *(const frag*)(KBT + (16 * (s / 2) + r) * L::KTS + 8 * g + 4 * (s & 1));
+        for (int s = 0; s < NTILE; ++s)
+            f.fk[s] = *(const frag*)(KBT + (16 * (s / 2) + r) * L::KTS + 8 * g + 4 * (s & 1));
+    }
     // GLA: the block's decay per state row.  Lane group g needs A[16s + 4g + i] for every tile s; lane r
     // of the group fetches two of them (s = r/4 and s = 4 + r/4, i = r%4) and the multiply takes its
     // factor from the lane that holds it through a DPP row broadcast.
-    if constexpr (VAR == SLA_GLA) {
+    if constexpr (VAR == SLA_GLA && LATE) {
         const float* EA = (const float*)(buf + L::oEA);
         f.ea0 = EA[16 * (r >> 2) + 4 * g + (r & 3)];
         if constexpr (NTILE > 4) f.ea1 = EA[64 + 16 * (r >> 2) + 4 * g + (r & 3)];
@@ -942,15 +950,19 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
             // Delta rule (Sec. 5.1, Softmax-GatedDeltaNet), all 16 tokens of the block at once:
             //   (I + L) U = beta G^K V - diag(beta p) K S   =>   U = Tm R,
             // and U takes the place of v' in the read-out and in the state step.
-            f32x4 X = {0.f, 0.f, 0.f, 0.f};  // X[j][n] = k_j S : lane holds column n = r, rows j = 4g + i
+            // X[j][n] = k_j S : lane holds column n = r, rows j = 4g + i; two accumulation chains
+            f32x4 X = {0.f, 0.f, 0.f, 0.f}, X2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < NTILE; s += 2)
+            for (int s = 0; s < NTILE; s += 4) {
                 P::mma32(X, cur.fkd[s], cur.fkd[s + 1], P::from_acc(S[s]), P::from_acc(S[s + 1]));
+                if (s + 2 < NTILE)
+                    P::mma32(X2, cur.fkd[s + 2], cur.fkd[s + 3], P::from_acc(S[s + 2]), P::from_acc(S[s + 3]));
+            }
             f32x4 R;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.bt[i] * fast_exp2(cur.cj[i]) * X[i];
+            for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.bt[i] * fast_exp2(cur.cj[i]) * (X[i] + X2[i]);
             f32x4 U = {0.f, 0.f, 0.f, 0.f};
-            P::mma16(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
+            P::mma16_only(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
             vs = U;
             fv = P::from_acc(U);
         }
@@ -1104,37 +1116,71 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
     elem* out_ptr = (elem*)a.out + (row_tok * H + h) * dv + n0 + 16 * cw + 4 * g + (size_t)r * out_tstride;
 
     SLA_TRACE_DECL
-    BlockFrags<P, VAR, DK> fa, fb;
-    // Block I.  On entry every LDS operand of the block has been requested (a block ago, into cur) and
-    // so has the counter of block I + 1.  Once they have landed, slot I % NP is handed back at once --
-    // the block is computed from registers -- and, block I + 1 being staged, its operands are
-    // requested into nxt together with the counter of block I + 2.  Past the last block the requests
-    // read slots that hold older data; nothing uses it.
     int seen = 0;
-    auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
-        SLA_STAMP(0);
-        const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        flag_signal_now(done + sl);
-        if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
-        asm volatile("" ::: "memory");
-        SLA_STAMP(1);
-        load_block_frags<P, VAR, DK, DVW, SO>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
-        seen = flag_peek(ready + sl2);
+    if constexpr (L::prefetch) {
+        BlockFrags<P, VAR, DK> fa, fb;
+        // Block I.  On entry every LDS operand of the block has been requested (a block ago, into cur) and
+        // so has the counter of block I + 1.  Once they have landed, slot I % NP is handed back at once --
+        // the block is computed from registers -- and, block I + 1 being staged, its operands are
+        // requested into nxt together with the counter of block I + 2.  Past the last block the requests
+        // read slots that hold older data; nothing uses it.
+        auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
+            SLA_STAMP(0);
+            const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            flag_signal_now(done + sl);
+            if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
+            asm volatile("" ::: "memory");
+            SLA_STAMP(1);
+            load_block_frags<P, VAR, DK, DVW, SO>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
+            seen = flag_peek(ready + sl2);
 #if SLA_EXP != 1
-        consume_block<P, VAR, DK, DVW, SO>(S, cur, kBlock * I + r < T, out_ptr);
+            consume_block<P, VAR, DK, DVW, SO>(S, cur, kBlock * I + r < T, out_ptr);
 #endif
-        out_ptr += (size_t)kBlock * out_tstride;
-        SLA_STAMP(2);
-        SLA_STAMP(3);
-        SLA_FLUSH(I);
-    };
-    flag_wait(ready, 1);
-    load_block_frags<P, VAR, DK, DVW, SO>(fa, smem, cw, lane);
-    seen = flag_peek(ready + (1 & (NP - 1)));
-    for (int I = 0; I < nblocks; I += 2) {
-        step(I, fa, fb);
-        if (I + 1 < nblocks) step(I + 1, fb, fa);
+            out_ptr += (size_t)kBlock * out_tstride;
+            SLA_STAMP(2);
+            SLA_STAMP(3);
+            SLA_FLUSH(I);
+        };
+        flag_wait(ready, 1);
+        load_block_frags<P, VAR, DK, DVW, SO>(fa, smem, cw, lane);
+        seen = flag_peek(ready + (1 & (NP - 1)));
+        for (int I = 0; I < nblocks; I += 2) {
+            step(I, fa, fb);
+            if (I + 1 < nblocks) step(I + 1, fb, fa);
+        }
+    } else {
+        // Delta rule: two full sets of operand registers would cost the registers that eight producer waves
+        // need.  Only what the block's long dependent chain starts with (k S, the triangular solve's
+        // product) is requested a block ahead; the rest (q rows, k^T, scores, gate) at the top of the
+        // block itself, where that chain covers its latency.  The slot goes back at the end of the block.
+        BlockFrags<P, VAR, DK> fa, fb;
+        auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
+            SLA_STAMP(0);
+            const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
+            if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
+            asm volatile("" ::: "memory");
+            SLA_STAMP(1);
+            load_block_frags<P, VAR, DK, DVW, SO, 2>(cur, smem + (size_t)sl * L::bytes, cw, lane);
+            load_block_frags<P, VAR, DK, DVW, SO, 1>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
+            seen = flag_peek(ready + sl2);
+#if SLA_EXP != 1
+            consume_block<P, VAR, DK, DVW, SO>(S, cur, kBlock * I + r < T, out_ptr);
+#endif
+            out_ptr += (size_t)kBlock * out_tstride;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            flag_signal_now(done + sl);
+            SLA_STAMP(2);
+            SLA_STAMP(3);
+            SLA_FLUSH(I);
+        };
+        flag_wait(ready, 1);
+        load_block_frags<P, VAR, DK, DVW, SO, 1>(fa, smem, cw, lane);
+        seen = flag_peek(ready + (1 & (NP - 1)));
+        for (int I = 0; I < nblocks; I += 2) {
+            step(I, fa, fb);
+            if (I + 1 < nblocks) step(I + 1, fb, fa);
+        }
     }
 
     if (s_out) {
