@@ -115,18 +115,33 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
             "state_rel_err": rel_err(state.cpu().numpy().astype(np.float64), rf),
             "definition": "max|x - oracle| / max|oracle| per tensor, first step from the seeded state",
         }
-    for _ in range(args.settle + args.warmup):
-        step()
+    per = args.graph if args.graph > 0 else 1  # steps per timed launch
+    if args.steps % per:
+        print(f"bench.py: --steps must be a multiple of --graph ({per})", file=sys.stderr)
+        return 2
+    launch = step
+    if args.graph > 0:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        raw = raw[:-1] + (side.cuda_stream,)  # the captured calls go to the capture stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(per):
+                step()
+        launch = graph.replay
+    for _ in range((args.settle + args.warmup + per - 1) // per):
+        launch()
     torch.cuda.synchronize()
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    nl = args.steps // per
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(nl + 1)]
     t0 = time.perf_counter()
     evs[0].record()
-    for i in range(args.steps):
-        step()
+    for i in range(nl):
+        launch()
         evs[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) / per for i in range(nl)]
     kernel_ms = float(np.mean(per_launch_ms))
     ms_per_step = wall * 1e3 / args.steps
     abytes = decode_bytes(w)
@@ -149,6 +164,7 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
             "workload": f"{w.name}: SLA-{si.VARIANT_NAMES[w.variant].upper()} decode step B={w.B} H={w.H} dk={w.dk} "
                         f"dv={w.dv} {w.dtype} in/out, fp32 state updated in place, dual head-softmax gates",
             "kernel": "sla_decode_kernel",
+            "launch": f"HIP graph of {per} steps per replay" if args.graph > 0 else "one launch per step",
         },
         "roofline": {
             "bound": "hbm",
@@ -192,6 +208,9 @@ def main() -> int:
     ap.add_argument("--copy-bytes", type=int, default=0,
                     help="also run one plain device-to-device copy of this many bytes before the timed region "
                          "(a known-size kernel to calibrate the profiler's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--graph", type=int, default=50,
+                    help="decode workloads only: steps per captured HIP graph (0 = plain launches).  A decode step "
+                         "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     args = ap.parse_args()
