@@ -4,6 +4,9 @@
                    loaded through ctypes; the function the GPU library is
                    compared against and the one timed as the CPU baseline.
 ``sla_numpy``    – independent numpy statements used to pin it.
+``sla_backward`` – gradients of the recurrence (RetNet, GLA) by reverse-mode
+                   differentiation token by token, fp64 numpy; pinned by finite
+                   differences and by autograd through the parallel form.
 
 Nothing under the GPU package imports this package; only ``tests/``, the smoke
 check and the benchmark's cpu_baseline leg do.
@@ -17,7 +20,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-from . import sla_numpy  # noqa: F401
+from . import sla_backward, sla_numpy  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sla_oracle.c")

@@ -1,0 +1,132 @@
+"""Gradients of the SLA forward pass (RetNet and GLA instantiations of Sec. 5.1), fp64 numpy.
+
+TEST INFRASTRUCTURE ONLY: the GPU library never imports this module and shares no code with it.
+
+The training objective reaches the mixer only through its outputs, so the backward pass of the
+chunkwise form of Sec. 3.2 ("Chunkwise Parallel Form") is, by definition, the derivative of the
+recurrence of Eq. 5-6.  ``backward`` is that derivative taken the plain way: reverse-mode
+differentiation of the token-by-token recurrence, one token at a time, in the order the recurrence
+was run.  With the scalar objective
+
+    L = sum(out * d_out) + sum(final_state * d_final_state)
+
+and, per head, ``S_t = diag(alpha_t) S_{t-1} + G^K_t k_t^T v_t``, ``out_t = G^Q_t q_t S_t``
+(alpha_t = gamma_h for RetNet, exp(log_decay_t) for GLA), walking t = T-1 .. 0 with ``dS`` the
+gradient with respect to ``S_t``:
+
+    dS      += G^Q_t q_t^T d_out_t
+    dG^Q_t   = d_out_t . (q_t S_t)             dq_t = G^Q_t d_out_t S_t^T
+    dk_t     = G^K_t dS v_t                    dv_t = G^K_t k_t dS          dG^K_t = k_t dS v_t
+    dalpha_t = rowsum(dS * S_{t-1})            dlog_decay_t = alpha_t dalpha_t
+    dS       = diag(alpha_t) dS                (now the gradient with respect to S_{t-1})
+
+and the gate gradients go through the head softmax of Eq. 4:
+``dlogits = G * (dG - sum_h G dG)``.
+
+States are kept at every ``checkpoint``-th token and recomputed in between, so memory stays
+bounded at full workload sizes; the arithmetic is the same for every choice of ``checkpoint``.
+
+Layouts as in ``sla_numpy``: q,k [B,T,H,dk]; v, d_out [B,T,H,dv]; logits [B,T,H];
+RetNet log_decay [H]; GLA log_decay [B,T,H,dk]; states [B,H,dk,dv].
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+
+from .sla_numpy import GLA, RETNET, head_softmax
+
+
+def _alpha(variant: int, ld: np.ndarray, t: int) -> np.ndarray:
+    """Decay of token t, broadcastable against a state [B,H,dk,dv]."""
+    if variant == RETNET:
+        return np.exp(ld)[None, :, None, None]
+    return np.exp(ld[:, t])[..., :, None]
+
+
+def backward(
+    variant: int,
+    q,
+    k,
+    v,
+    q_logits,
+    k_logits,
+    log_decay,
+    d_out,
+    initial_state=None,
+    d_final_state=None,
+    checkpoint: int = 64,
+) -> Dict[str, Optional[np.ndarray]]:
+    """Gradients of L with respect to every differentiable input.
+
+    Returns a dict with dq, dk, dv, dq_logits, dk_logits (None when ``k_logits`` is None),
+    dlog_decay (RetNet: [H]; GLA: [B,T,H,dk]) and dinitial_state.
+    """
+    if variant not in (RETNET, GLA):
+        raise ValueError("gradients are defined here for RetNet and GLA")
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    do = np.asarray(d_out, dtype=np.float64)
+    ld = np.asarray(log_decay, dtype=np.float64)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    gq = head_softmax(q_logits)
+    gk = head_softmax(k_logits, (B, T, H))
+
+    def step(S, t):
+        return _alpha(variant, ld, t) * S + (gk[:, t, :, None] * k[:, t])[..., :, None] * v[:, t][..., None, :]
+
+    # forward sweep: keep the state entering every checkpoint-th token
+    S = np.zeros((B, H, dk, dv)) if initial_state is None else np.array(initial_state, dtype=np.float64)
+    kept = {}
+    for t in range(T):
+        if t % checkpoint == 0:
+            kept[t] = S
+        S = step(S, t)
+
+    dq = np.zeros_like(q)
+    dkk = np.zeros_like(k)
+    dvv = np.zeros_like(v)
+    dgq = np.zeros((B, T, H))
+    dgk = np.zeros((B, T, H))
+    dld = np.zeros(H) if variant == RETNET else np.zeros((B, T, H, dk))
+    dS = np.zeros((B, H, dk, dv)) if d_final_state is None else np.array(d_final_state, dtype=np.float64)
+
+    for seg in sorted(kept.keys(), reverse=True):
+        end = min(T, seg + checkpoint)
+        before = [kept[seg]]  # before[i] = state entering token seg + i
+        for t in range(seg, end):
+            before.append(step(before[-1], t))
+        for t in range(end - 1, seg - 1, -1):
+            S_prev, S_t = before[t - seg], before[t - seg + 1]
+            y = np.einsum("bhd,bhdn->bhn", q[:, t], S_t)
+            dgq[:, t] = np.sum(do[:, t] * y, axis=-1)
+            dy = gq[:, t, :, None] * do[:, t]
+            dq[:, t] = np.einsum("bhn,bhdn->bhd", dy, S_t)
+            dS = dS + q[:, t][..., :, None] * dy[..., None, :]
+            dSv = np.einsum("bhdn,bhn->bhd", dS, v[:, t])
+            dkk[:, t] = gk[:, t, :, None] * dSv
+            dvv[:, t] = gk[:, t, :, None] * np.einsum("bhd,bhdn->bhn", k[:, t], dS)
+            dgk[:, t] = np.sum(k[:, t] * dSv, axis=-1)
+            a = _alpha(variant, ld, t)
+            dalpha = np.sum(dS * S_prev, axis=-1)  # [B,H,dk]
+            if variant == RETNET:
+                dld += np.exp(ld) * np.sum(dalpha, axis=(0, 2))
+            else:
+                dld[:, t] = a[..., 0] * dalpha
+            dS = a * dS
+
+    def softmax_backward(g, dg):
+        return g * (dg - np.sum(g * dg, axis=-1, keepdims=True))
+
+    return {
+        "dq": dq,
+        "dk": dkk,
+        "dv": dvv,
+        "dq_logits": softmax_backward(gq, dgq),
+        "dk_logits": None if k_logits is None else softmax_backward(gk, dgk),
+        "dlog_decay": dld,
+        "dinitial_state": dS,
+    }
