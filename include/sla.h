@@ -134,6 +134,39 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
                     const float* q_head_logits, const float* k_head_logits,
                     const void* log_decay, const float* beta, float* state, void* out, void* stream);
 
+/*
+ * Backward pass of sla_forward for the RetNet and GLA recurrences (Sec. 5.1) with the gates of Eq. 4-6: the
+ * gradients that training through the chunkwise form of Sec. 3.2 ("Chunkwise Parallel Form") needs.  With the
+ * scalar objective L = sum(out * d_out) + sum(final_state * d_final_state) it writes dL/d(input) for every
+ * differentiable input of the forward call made with the same p, q, k, v, logits, log_decay and initial_state.
+ * bf16 tensors only (p->dtype == SLA_BF16); the delta rule is not covered (SLA_ERR_UNSUPPORTED).
+ * p->dv_split and p->segments are ignored.
+ *
+ *   q, k, v, q_head_logits, k_head_logits, log_decay, initial_state   as for sla_forward (device, read only)
+ *   d_out            [B,T,H,dv]  dtype   cotangent of out; required
+ *   d_final_state    [B,H,dk,dv] fp32    cotangent of final_state, or NULL (zero)
+ *   dq, dk           [B,T,H,dk]  dtype   written
+ *   dv               [B,T,H,dv]  dtype   written
+ *   dq_head_logits   [B,T,H]     fp32    written (through the head softmax)
+ *   dk_head_logits   [B,T,H]     fp32    written; required when k_head_logits is given, NULL otherwise
+ *   dlog_decay       GLA: [B,T,H,dk] dtype, written, required;  RetNet: must be NULL (the decay is a constant)
+ *   d_initial_state  [B,H,dk,dv] fp32    written, or NULL (not wanted)
+ *   workspace        device memory of at least sla_backward_workspace_bytes(p) bytes, 16-byte aligned; holds
+ *                    the gates, partial gate gradients and (GLA) q * dq in fp32.  Contents on entry are ignored;
+ *                    calls that share a workspace must not overlap.
+ * No output may overlap an input or another output.  Everything is enqueued on `stream`; nothing is allocated,
+ * freed or synchronised.  Returns a status code; on error nothing is launched.
+ */
+int sla_backward(const sla_params* p, const void* q, const void* k, const void* v,
+                 const float* q_head_logits, const float* k_head_logits, const void* log_decay,
+                 const float* initial_state, const void* d_out, const float* d_final_state,
+                 void* dq, void* dk, void* dv, float* dq_head_logits, float* dk_head_logits,
+                 void* dlog_decay, float* d_initial_state,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace sla_backward needs for *p (0 when *p is not a shape it supports). */
+size_t sla_backward_workspace_bytes(const sla_params* p);
+
 /* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
 size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 

@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     SlaParams,
     library_path,
     load_library,
+    sla_backward,
+    sla_backward_workspace_bytes,
     sla_check_args,
     sla_decode_step,
     sla_default_dv_split,
@@ -26,6 +28,7 @@ from .binding import (  # noqa: F401
     sla_status_string,
     sla_version,
     forward,
+    backward,
     decode_step,
 )
 

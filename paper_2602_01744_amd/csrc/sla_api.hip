@@ -11,6 +11,10 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
                    const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
                    float* sT, float* workspace, hipStream_t stream);
 size_t segment_workspace_floats(const sla_params& p, int nseg);
+size_t backward_workspace_floats(const sla_params& p);
+int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
+                    const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
+                    float* dql, float* dkl, void* dld, float* ds0, float* ws, hipStream_t stream);
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
@@ -168,6 +172,38 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
     if (!state) return SLA_ERR_NULL;
     return sla::launch_decode(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out,
                               (hipStream_t)stream);
+}
+
+int sla_backward(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                 const float* k_head_logits, const void* log_decay, const float* initial_state, const void* d_out,
+                 const float* d_final_state, void* dq, void* dk, void* dv, float* dq_head_logits,
+                 float* dk_head_logits, void* dlog_decay, float* d_initial_state, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    int rc = check_params(p);
+    if (rc != SLA_OK) return rc;
+    if (p->variant == SLA_GDN || p->dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
+    if (p->B > 0 && p->T > 0) {
+        if (!q || !k || !v || !q_head_logits || !log_decay || !d_out || !dq || !dk || !dv || !dq_head_logits)
+            return SLA_ERR_NULL;
+        if (p->variant == SLA_GLA && !dlog_decay) return SLA_ERR_NULL;
+    }
+    if (p->variant == SLA_RETNET && dlog_decay) return SLA_ERR_NULL;
+    if ((k_head_logits != nullptr) != (dk_head_logits != nullptr)) return SLA_ERR_NULL;
+    const void* ptrs[] = {q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out, d_final_state,
+                          dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, d_initial_state, workspace};
+    for (const void* x : ptrs)
+        if (x && !aligned16(x)) return SLA_ERR_ALIGN;
+    if (p->B == 0) return SLA_OK;
+    if (p->T == 0 && !d_initial_state) return SLA_OK;
+    if (!workspace || sla::backward_workspace_floats(*p) * sizeof(float) > workspace_bytes) return SLA_ERR_WORKSPACE;
+    return sla::launch_backward(*p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out,
+                                d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
+                                d_initial_state, (float*)workspace, (hipStream_t)stream);
+}
+
+size_t sla_backward_workspace_bytes(const sla_params* p) {
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16) return 0;
+    return sla::backward_workspace_floats(*p) * sizeof(float);
 }
 
 size_t sla_workspace_bytes(const sla_params* p, int compute_units) {

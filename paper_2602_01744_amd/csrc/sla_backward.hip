@@ -1,0 +1,805 @@
+// SLA backward pass for gfx950 (MI355X): gradients of the chunkwise forward of Sec. 3.2 ("Chunkwise Parallel
+// Form") with the head-softmax gates of Eq. 4-6, for the RetNet and GLA recurrences of Sec. 5.1.
+//
+// With S_t = diag(alpha_t) S_{t-1} + G^K_t k_t^T v_t and out_t = G^Q_t q_t S_t, and dS_t the gradient with respect
+// to S_t (dS_t = G^Q_t q_t^T dout_t + diag(alpha_{t+1}) dS_{t+1}):
+//     dq_t = G^Q_t dout_t S_t^T      dG^Q_t = q_t . (dout_t S_t^T)
+//     dv_t = G^K_t k_t dS_t          dG^K_t = v_t . (k_t dS_t)
+//     dk_t = G^K_t dS_t v_t^T
+//     dlog_decay_t = sum_{s >= t} (q_s * dq_s - k_s * dk_s)  [+ rowsum(dS_T * S_T) when the final state has a
+//                    cotangent]: every pair (writer j < t <= reader s) crosses token t's decay exactly once.
+// dq contracts the state over its value columns, dv over its key rows, dk again over the value columns of dS: each
+// is a sweep over the tokens that carries one [dk, dv] tile in registers, sliced over the dimension that is NOT
+// contracted, exactly like the forward.  So the pass is three sweeps in 16-token blocks,
+//     F  (forward in time,  carries S^T,  64 key columns per workgroup)   -> dq, dG^Q, q*dq
+//     R1 (backward in time, carries dS,   64 value columns per workgroup) -> dv, dG^K, d initial state
+//     R2 (backward in time, carries dS^T, 64 key columns per workgroup)   -> dk, dlog_decay
+// between a small kernel that evaluates the gates (Eq. 4) and one that takes dG through the softmax.
+//
+// Block algebra (tokens 0..15 of a block, c_t the running sum of log-decay inside it, p_t = e^{c_t}, A = p_15,
+// qa = q p, kd = k / p, kb = k A / p, all products on bf16 MFMA with fp32 accumulation, decays in fp32):
+//   F : P'[t][j] = dout_t . v_j (j <= t);  dq'_t = p_t * (dout_t S0^T + sum_j P'[t][j] G^K_j kd_j);
+//       S^T <- S^T A + v^T (G^K kb)
+//   R1: Pq[t][j] = qa_t . kd_j (j <= t);   dv'_j = kb_j dS + sum_t Pq[t][j] G^Q_t dout_t;
+//       dS <- diag(A) dS + qa^T (G^Q dout)
+//   R2: dk'_j = (1/p_j) * sum_t G^Q_t P'[t][j] qa_t + (A/p_j) * (v_j dS^T);   dS^T <- dS^T A + (G^Q dout)^T qa
+// Every workgroup has four consumer waves (16 columns of the slice each, their state tile in registers) and four
+// producer waves that stage the next block's operands in LDS while the consumers work on the current one; the two
+// halves meet at one barrier per block.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sla.h"
+
+namespace sla {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f4;
+typedef __attribute__((ext_vector_type(4))) short s4;
+typedef __attribute__((ext_vector_type(8))) short s8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+
+constexpr int kTok = 16;        // tokens per block
+constexpr int kBwdThreads = 512;
+constexpr int kCols = 64;       // columns of the sliced dimension per workgroup
+constexpr int kTS = 20;         // token stride (elements) of the transposed [column][token] tiles
+constexpr int kFS = 68;         // row stride (elements) of the [token][64 columns] tiles
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct BArgs {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    const uint16_t* dout;
+    const uint16_t* ld;      // GLA: [B,T,H,dk] bf16
+    const float* ld_head;    // RetNet: [H]
+    const float* gq;         // gates, [B,T,H]
+    const float* gk;
+    const float* s0;         // [B,H,dk,dv] or null
+    const float* dsf;        // cotangent of the final state or null
+    uint16_t* dq;
+    uint16_t* dk;
+    uint16_t* dv;
+    uint16_t* dld;
+    float* ds0;
+    float* part_q;           // [dk/16][B,T,H] partial dG^Q
+    float* part_k;           // [dv/16][B,T,H] partial dG^K
+    float* qdq;              // [B,T,H,dk] fp32 q * dq (GLA)
+    float* corr;             // [B,H,dk] rowsum(dS_T * S_T) (GLA with a final-state cotangent)
+    int B, T, H;
+};
+
+__device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+__device__ __forceinline__ float bf_at(const u4& x, int i) { return (i & 1) ? bf_hi(x[i >> 1]) : bf_lo(x[i >> 1]); }
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    bf2 t;
+    t.x = (__bf16)lo;
+    t.y = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, t);
+}
+__device__ __forceinline__ uint16_t bf_bits(float x) { return (uint16_t)(pack2(x, 0.f) & 0xffffu); }
+__device__ __forceinline__ s4 pack4(f4 c) {
+    u2 t;
+    t.x = pack2(c[0], c[1]);
+    t.y = pack2(c[2], c[3]);
+    return __builtin_bit_cast(s4, t);
+}
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 16x16x32: lane (r = lane % 16, g = lane / 16) holds row r of A / column r of B, contraction slots 8g..8g+7.
+__device__ __forceinline__ void mma32(f4& c, s8 a, s8 b) {
+    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), c, 0, 0, 0);
+}
+// 16x16x16: slots 4g..4g+3.  Never issued on an accumulator that the 32-slot opcode also writes.
+__device__ __forceinline__ void mma16(f4& c, s4 a, s4 b) { c = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ s8 join(s4 a, s4 b) { return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+// inclusive sums over the 16 lanes of a row (tokens): from lane 0 up / from lane 15 down
+__device__ __forceinline__ float row_prefix(float x) {
+    x += dpp<0x111>(x);
+    x += dpp<0x112>(x);
+    x += dpp<0x114>(x);
+    x += dpp<0x118>(x);
+    return x;
+}
+__device__ __forceinline__ float row_suffix(float x) {
+    x += dpp<0x101>(x);
+    x += dpp<0x102>(x);
+    x += dpp<0x104>(x);
+    x += dpp<0x108>(x);
+    return x;
+}
+__device__ __forceinline__ float row_last(float x) { return dpp<0x15F>(x); }   // lane 15 of the row, to all
+__device__ __forceinline__ float row_first(float x) { return dpp<0x150>(x); }  // lane 0 of the row, to all
+
+// Row-major [16][KD + 8] operand tile whose contraction index is permuted in groups of 32 so that the eight slots
+// a lane feeds to one 16x16x32 MFMA are adjacent: index 32S + 16u + 4g + i sits at 32S + 8g + 4u + i.  The state
+// tiles (two 16-row accumulators per 32 slots) then pair up with it without any shuffle.
+template <int KD>
+__device__ __forceinline__ void put_perm(uint16_t* tile, int t, int e8, u4 x) {
+    const int S = e8 >> 2, u = (e8 >> 1) & 1, g0 = (e8 & 1) * 2;
+    uint16_t* row = tile + t * (KD + 8) + 32 * S + 4 * u;
+    *(u2*)(row + 8 * g0) = u2{x[0], x[1]};
+    *(u2*)(row + 8 * (g0 + 1)) = u2{x[2], x[3]};
+}
+template <int KD>
+__device__ __forceinline__ s8 get_perm(const uint16_t* tile, int r, int g, int c) {
+    return *(const s8*)(tile + r * (KD + 8) + 32 * c + 8 * g);
+}
+// [column][kTS] tile: eight columns of one token
+__device__ __forceinline__ void put_T(uint16_t* tile, int col0, int t, u4 x) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        tile[(col0 + 2 * i) * kTS + t] = (uint16_t)(x[i] & 0xffffu);
+        tile[(col0 + 2 * i + 1) * kTS + t] = (uint16_t)(x[i] >> 16);
+    }
+}
+__device__ __forceinline__ s4 get_T(const uint16_t* tile, int col, int g) { return *(const s4*)(tile + col * kTS + 4 * g); }
+
+__device__ __forceinline__ u4 load16(const uint16_t* p, bool ok) {
+    return ok ? *(const u4*)p : u4{0u, 0u, 0u, 0u};
+}
+
+// log2-domain decay steps of eight key columns of one token (zero outside the sequence)
+template <int VAR>
+__device__ __forceinline__ void load_steps(const BArgs& a, size_t row, int h, int dk, int d0, bool ok, float* l) {
+    if constexpr (VAR == SLA_GLA) {
+        const u4 x = load16(a.ld + row * dk + d0, ok);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) l[i] = bf_at(x, i) * kLog2e;
+    } else {
+        const float s = ok ? a.ld_head[h] * kLog2e : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) l[i] = s;
+    }
+}
+
+__device__ __forceinline__ float reduce_groups(float x) {  // sum over the four 16-lane groups
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Sweep F: forward in time, state S^T[n][d] (value rows, 16 key columns per wave).
+// ------------------------------------------------------------------------------------------------------------
+template <int DV>
+struct SmemF {
+    static constexpr int oDO = 0;
+    static constexpr int oV = oDO + kTok * (DV + 8) * 2;
+    static constexpr int oVT = oV + kTok * (DV + 8) * 2;
+    static constexpr int oKDT = oVT + DV * kTS * 2;
+    static constexpr int oKBT = oKDT + kCols * kTS * 2;
+    static constexpr int oCUM = oKBT + kCols * kTS * 2;
+    static constexpr int oTOT = oCUM + kTok * kFS * 4;
+    static constexpr int oQS = oTOT + kCols * 4;
+    static constexpr int oGQ = oQS + kTok * kFS * 2;
+    static constexpr int bytes = oGQ + kTok * 4;
+    static_assert(oV % 16 == 0 && oVT % 16 == 0 && oKDT % 16 == 0 && oCUM % 16 == 0 && oTOT % 16 == 0 &&
+                      oQS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
+                  "tiles stay 16-byte aligned");
+};
+
+template <int VAR, int DK, int DV>
+__global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) {
+    typedef SmemF<DV> L;
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int NSL = DK / kCols;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
+    const int sbase = slice * kCols;
+    const int T = a.T, H = a.H;
+    const int nb = (T + kTok - 1) / kTok;
+    const bool producer = wave >= 4;
+    const int cb = 16 * (wave & 3);
+
+    f4 ST[DV / 16];
+    if (!producer) {
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) {
+            if (a.s0)
+                ST[i] = *(const f4*)(a.s0 + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
+            else
+                ST[i] = f4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    for (int it = 0; it <= nb; ++it) {
+        if (producer) {
+            if (it < nb) {
+                unsigned char* buf = smem + (it & 1) * L::bytes;
+                const int t0 = it * kTok, ptid = tid - 256;
+                if (ptid < 128) {
+                    const int e8 = ptid >> 4, t = ptid & 15, tok = t0 + t;
+                    const bool ok = tok < T;
+                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+                    const int d0 = sbase + 8 * e8;
+                    float l[8];
+                    load_steps<VAR>(a, row, h, DK, d0, ok, l);
+                    const u4 kx = load16(a.k + row * DK + d0, ok);
+                    const u4 qx = load16(a.q + row * DK + d0, ok);
+                    const float gk = ok ? a.gk[row] : 0.f;
+                    float c[8], tot[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        c[i] = row_prefix(l[i]);
+                        tot[i] = row_last(c[i]);
+                    }
+                    float* cum = (float*)(buf + L::oCUM) + t * kFS + 8 * e8;
+                    *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
+                    *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
+                    if (t == 0) {
+                        float* tt = (float*)(buf + L::oTOT) + 8 * e8;
+                        *(f4*)tt = f4{tot[0], tot[1], tot[2], tot[3]};
+                        *(f4*)(tt + 4) = f4{tot[4], tot[5], tot[6], tot[7]};
+                    }
+                    uint16_t* kdt = (uint16_t*)(buf + L::oKDT);
+                    uint16_t* kbt = (uint16_t*)(buf + L::oKBT);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float kf = bf_at(kx, i) * gk;
+                        kdt[(8 * e8 + i) * kTS + t] = bf_bits(kf * ex2(-c[i]));
+                        kbt[(8 * e8 + i) * kTS + t] = bf_bits(kf * ex2(tot[i] - c[i]));
+                    }
+                    uint16_t* qs = (uint16_t*)(buf + L::oQS) + t * kFS + 8 * e8;
+                    *(u2*)qs = u2{qx[0], qx[1]};
+                    *(u2*)(qs + 4) = u2{qx[2], qx[3]};
+                    if (e8 == 0) ((float*)(buf + L::oGQ))[t] = ok ? a.gq[row] : 0.f;
+                } else {
+                    const int x = ptid - 128;
+#pragma unroll
+                    for (int rep = 0; rep < (DV / 8 * kTok) / 128; ++rep) {
+                        const int c = x + 128 * rep, t = c / (DV / 8), e8 = c % (DV / 8), tok = t0 + t;
+                        const bool ok = tok < T;
+                        const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+                        const u4 dx = load16(a.dout + row * DV + 8 * e8, ok);
+                        const u4 vx = load16(a.v + row * DV + 8 * e8, ok);
+                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                        put_T((uint16_t*)(buf + L::oVT), 8 * e8, t, vx);
+                    }
+                }
+            }
+        } else if (it > 0) {
+            const int blk = it - 1;
+            const unsigned char* buf = smem + (blk & 1) * L::bytes;
+            const int t0 = blk * kTok;
+            const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
+            const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
+            // P'^T[j][t] = v_j . dout_t, kept for j <= t
+            f4 pT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DV / 32; ++c) mma32(pT, get_perm<DV>(Vp, r, g, c), get_perm<DV>(DOp, r, g, c));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (4 * g + i > r) pT[i] = 0.f;
+            const s4 fp = pack4(pT);
+            // dqa^T[d][t] = sum_n S^T[n][d] dout_t[n] + sum_j kd'_j[d] P'[t][j]
+            f4 oS = {0.f, 0.f, 0.f, 0.f}, oP = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DV / 32; ++c)
+                mma32(oS, join(pack4(ST[2 * c]), pack4(ST[2 * c + 1])), get_perm<DV>(DOp, r, g, c));
+            const s4 fkd = get_T((const uint16_t*)(buf + L::oKDT), cb + r, g);
+            mma16(oP, fkd, fp);
+            const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
+            const u2 qx = *(const u2*)((const uint16_t*)(buf + L::oQS) + r * kFS + cb + 4 * g);
+            const float gq = ((const float*)(buf + L::oGQ))[r];
+            float dqp[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * ex2(cum[i]);
+            const float qf[4] = {bf_lo(qx[0]), bf_hi(qx[0]), bf_lo(qx[1]), bf_hi(qx[1])};
+            float part = qf[0] * dqp[0] + qf[1] * dqp[1] + qf[2] * dqp[2] + qf[3] * dqp[3];
+            part = reduce_groups(part);
+            const int tok = t0 + r;
+            if (tok < T) {
+                const size_t row = ((size_t)b * T + tok) * H + h;
+                if (g == 0) a.part_q[((size_t)(slice * 4 + (wave & 3)) * a.B * T * H) + row] = part;
+                float dqv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dqv[i] = gq * dqp[i];
+                *(u2*)(a.dq + row * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
+                if constexpr (VAR == SLA_GLA)
+                    *(f4*)(a.qdq + row * DK + sbase + cb + 4 * g) =
+                        f4{qf[0] * dqv[0], qf[1] * dqv[1], qf[2] * dqv[2], qf[3] * dqv[3]};
+            }
+            // S^T <- S^T A + v^T kb'
+            const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
+            const s4 fkb = get_T((const uint16_t*)(buf + L::oKBT), cb + r, g);
+            const uint16_t* VT = (const uint16_t*)(buf + L::oVT);
+#pragma unroll
+            for (int i = 0; i < DV / 16; ++i) {
+                ST[i] = ST[i] * Ad;
+                mma16(ST[i], get_T(VT, 16 * i + r, g), fkb);
+            }
+        }
+        __syncthreads();
+    }
+
+    if constexpr (VAR == SLA_GLA) {
+        if (!producer && a.dsf) {  // rowsum(dS_T * S_T) for the key columns of this wave
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < DV / 16; ++i) {
+                const f4 x = *(const f4*)(a.dsf + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
+                s += x[0] * ST[i][0] + x[1] * ST[i][1] + x[2] * ST[i][2] + x[3] * ST[i][3];
+            }
+            s = reduce_groups(s);
+            if (g == 0) a.corr[(size_t)bh * DK + sbase + cb + r] = s;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Sweep R2: backward in time, state dS^T[n][d] (value rows, 16 key columns per wave) -> dk, dlog_decay.
+// ------------------------------------------------------------------------------------------------------------
+template <int DV>
+struct SmemK {
+    static constexpr int oDO = 0;
+    static constexpr int oV = oDO + kTok * (DV + 8) * 2;
+    static constexpr int oDYT = oV + kTok * (DV + 8) * 2;
+    static constexpr int oQAT = oDYT + DV * kTS * 2;
+    static constexpr int oCUM = oQAT + kCols * kTS * 2;
+    static constexpr int oTOT = oCUM + kTok * kFS * 4;
+    static constexpr int oKS = oTOT + kCols * 4;
+    static constexpr int oGQ = oKS + kTok * kFS * 2;
+    static constexpr int oGK = oGQ + kTok * 4;
+    static constexpr int bytes = oGK + kTok * 4;
+    static_assert(oV % 16 == 0 && oDYT % 16 == 0 && oQAT % 16 == 0 && oCUM % 16 == 0 && oTOT % 16 == 0 &&
+                      oKS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
+                  "tiles stay 16-byte aligned");
+};
+
+template <int VAR, int DK, int DV>
+__global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) {
+    typedef SmemK<DV> L;
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int NSL = DK / kCols;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
+    const int sbase = slice * kCols;
+    const int T = a.T, H = a.H;
+    const int nb = (T + kTok - 1) / kTok;
+    const bool producer = wave >= 4;
+    const int cb = 16 * (wave & 3);
+
+    f4 DST[DV / 16];
+    float run[4] = {0.f, 0.f, 0.f, 0.f};  // sum over later tokens of q*dq - k*dk, for key columns cb + 4g + i
+    if (!producer) {
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) {
+            if (a.dsf)
+                DST[i] = *(const f4*)(a.dsf + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
+            else
+                DST[i] = f4{0.f, 0.f, 0.f, 0.f};
+        }
+        if constexpr (VAR == SLA_GLA) {
+            if (a.dsf) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) run[i] = a.corr[(size_t)bh * DK + sbase + cb + 4 * g + i];
+            }
+        }
+    }
+
+    for (int it = 0; it <= nb; ++it) {
+        if (producer) {
+            if (it < nb) {
+                unsigned char* buf = smem + (it & 1) * L::bytes;
+                const int t0 = (nb - 1 - it) * kTok, ptid = tid - 256;
+                if (ptid < 128) {
+                    const int e8 = ptid >> 4, t = ptid & 15, tok = t0 + t;
+                    const bool ok = tok < T;
+                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+                    const int d0 = sbase + 8 * e8;
+                    float l[8];
+                    load_steps<VAR>(a, row, h, DK, d0, ok, l);
+                    const u4 kx = load16(a.k + row * DK + d0, ok);
+                    const u4 qx = load16(a.q + row * DK + d0, ok);
+                    float c[8], tot[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        c[i] = row_prefix(l[i]);
+                        tot[i] = row_last(c[i]);
+                    }
+                    float* cum = (float*)(buf + L::oCUM) + t * kFS + 8 * e8;
+                    *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
+                    *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
+                    if (t == 0) {
+                        float* tt = (float*)(buf + L::oTOT) + 8 * e8;
+                        *(f4*)tt = f4{tot[0], tot[1], tot[2], tot[3]};
+                        *(f4*)(tt + 4) = f4{tot[4], tot[5], tot[6], tot[7]};
+                    }
+                    uint16_t* qat = (uint16_t*)(buf + L::oQAT);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) qat[(8 * e8 + i) * kTS + t] = bf_bits(bf_at(qx, i) * ex2(c[i]));
+                    uint16_t* ks = (uint16_t*)(buf + L::oKS) + t * kFS + 8 * e8;
+                    *(u2*)ks = u2{kx[0], kx[1]};
+                    *(u2*)(ks + 4) = u2{kx[2], kx[3]};
+                    if (e8 == 0) {
+                        ((float*)(buf + L::oGQ))[t] = ok ? a.gq[row] : 0.f;
+                        ((float*)(buf + L::oGK))[t] = ok ? a.gk[row] : 0.f;
+                    }
+                } else {
+                    const int x = ptid - 128;
+#pragma unroll
+                    for (int rep = 0; rep < (DV / 8 * kTok) / 128; ++rep) {
+                        const int c = x + 128 * rep, t = c / (DV / 8), e8 = c % (DV / 8), tok = t0 + t;
+                        const bool ok = tok < T;
+                        const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+                        const u4 dx = load16(a.dout + row * DV + 8 * e8, ok);
+                        const u4 vx = load16(a.v + row * DV + 8 * e8, ok);
+                        const float gq = ok ? a.gq[row] : 0.f;
+                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                        u4 dy;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) dy[i] = pack2(gq * bf_lo(dx[i]), gq * bf_hi(dx[i]));
+                        put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
+                    }
+                }
+            }
+        } else if (it > 0) {
+            const int blk = it - 1;
+            const unsigned char* buf = smem + (blk & 1) * L::bytes;
+            const int t0 = (nb - 1 - blk) * kTok;
+            const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
+            const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
+            const float* GQ = (const float*)(buf + L::oGQ);
+            // dP[t][j] = G^Q_t (dout_t . v_j), kept for j <= t
+            f4 dP = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DV / 32; ++c) mma32(dP, get_perm<DV>(DOp, r, g, c), get_perm<DV>(Vp, r, g, c));
+            const f4 gq4 = *(const f4*)(GQ + 4 * g);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dP[i] = (r > 4 * g + i) ? 0.f : dP[i] * gq4[i];
+            const s4 fp = pack4(dP);
+            // Xs^T[d][j] = sum_n dS^T[n][d] v_j[n];  Xi^T[d][j] = sum_t qa_t[d] dP[t][j]
+            f4 Xs = {0.f, 0.f, 0.f, 0.f}, Xi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DV / 32; ++c)
+                mma32(Xs, join(pack4(DST[2 * c]), pack4(DST[2 * c + 1])), get_perm<DV>(Vp, r, g, c));
+            const s4 fqa = get_T((const uint16_t*)(buf + L::oQAT), cb + r, g);
+            mma16(Xi, fqa, fp);
+            const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
+            const f4 tot = *(const f4*)((const float*)(buf + L::oTOT) + cb + 4 * g);
+            const float gk = ((const float*)(buf + L::oGK))[r];
+            float dkv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dkv[i] = gk * (Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]));
+            const int tok = t0 + r;
+            const bool ok = tok < T;
+            const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+            if (ok) *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+            if constexpr (VAR == SLA_GLA) {
+                const u2 kx = *(const u2*)((const uint16_t*)(buf + L::oKS) + r * kFS + cb + 4 * g);
+                const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
+                f4 e = {0.f, 0.f, 0.f, 0.f};
+                if (ok) e = *(const f4*)(a.qdq + row * DK + sbase + cb + 4 * g);
+                float dl[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float s = row_suffix(e[i] - kf[i] * dkv[i]) + run[i];
+                    dl[i] = s;
+                    run[i] = row_first(s);
+                }
+                if (ok) *(u2*)(a.dld + row * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
+            }
+            // dS^T <- dS^T A + dy^T qa
+            const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
+            const uint16_t* DYT = (const uint16_t*)(buf + L::oDYT);
+#pragma unroll
+            for (int i = 0; i < DV / 16; ++i) {
+                DST[i] = DST[i] * Ad;
+                mma16(DST[i], get_T(DYT, 16 * i + r, g), fqa);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Sweep R1: backward in time, state dS[d][n] (key rows, 16 value columns per wave) -> dv, dG^K, d initial state.
+// ------------------------------------------------------------------------------------------------------------
+template <int DK>
+struct SmemV {
+    static constexpr int oQA = 0;
+    static constexpr int oKD = oQA + kTok * (DK + 8) * 2;
+    static constexpr int oKB = oKD + kTok * (DK + 8) * 2;
+    static constexpr int oQAT = oKB + kTok * (DK + 8) * 2;
+    static constexpr int oDYT = oQAT + DK * kTS * 2;
+    static constexpr int oVS = oDYT + kCols * kTS * 2;
+    static constexpr int oAT = oVS + kTok * kFS * 2;
+    static constexpr int oGK = oAT + DK * 4;
+    static constexpr int bytes = oGK + kTok * 4;
+    static_assert(oKD % 16 == 0 && oKB % 16 == 0 && oQAT % 16 == 0 && oDYT % 16 == 0 && oVS % 16 == 0 &&
+                      oAT % 16 == 0 && oGK % 16 == 0 && bytes % 16 == 0,
+                  "tiles stay 16-byte aligned");
+};
+
+template <int VAR, int DK, int DV>
+__global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) {
+    typedef SmemV<DK> L;
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int NSL = DV / kCols;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
+    const int sbase = slice * kCols;
+    const int T = a.T, H = a.H;
+    const int nb = (T + kTok - 1) / kTok;
+    const bool producer = wave >= 4;
+    const int cb = 16 * (wave & 3);
+
+    f4 DS[DK / 16];  // rows d = 16 i + 4 g + (0..3), column n = sbase + cb + r
+    if (!producer) {
+#pragma unroll
+        for (int i = 0; i < DK / 16; ++i) {
+            DS[i] = f4{0.f, 0.f, 0.f, 0.f};
+            if (a.dsf) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    DS[i][j] = a.dsf[((size_t)bh * DK + 16 * i + 4 * g + j) * DV + sbase + cb + r];
+            }
+        }
+    }
+
+    for (int it = 0; it <= nb; ++it) {
+        if (producer) {
+            if (it < nb) {
+                unsigned char* buf = smem + (it & 1) * L::bytes;
+                const int t0 = (nb - 1 - it) * kTok, ptid = tid - 256;
+                if (ptid < DK * 2) {  // 16 tokens x DK/8 groups of eight key columns
+                    const int e8 = ptid >> 4, t = ptid & 15, tok = t0 + t;
+                    const bool ok = tok < T;
+                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+                    float l[8];
+                    load_steps<VAR>(a, row, h, DK, 8 * e8, ok, l);
+                    const u4 kx = load16(a.k + row * DK + 8 * e8, ok);
+                    const u4 qx = load16(a.q + row * DK + 8 * e8, ok);
+                    float c[8], tot[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        c[i] = row_prefix(l[i]);
+                        tot[i] = row_last(c[i]);
+                    }
+                    u4 qa, kd, kb;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        qa[i] = pack2(bf_lo(qx[i]) * ex2(c[2 * i]), bf_hi(qx[i]) * ex2(c[2 * i + 1]));
+                        kd[i] = pack2(bf_lo(kx[i]) * ex2(-c[2 * i]), bf_hi(kx[i]) * ex2(-c[2 * i + 1]));
+                        kb[i] = pack2(bf_lo(kx[i]) * ex2(tot[2 * i] - c[2 * i]),
+                                      bf_hi(kx[i]) * ex2(tot[2 * i + 1] - c[2 * i + 1]));
+                    }
+                    put_perm<DK>((uint16_t*)(buf + L::oQA), t, e8, qa);
+                    put_perm<DK>((uint16_t*)(buf + L::oKD), t, e8, kd);
+                    put_perm<DK>((uint16_t*)(buf + L::oKB), t, e8, kb);
+                    put_T((uint16_t*)(buf + L::oQAT), 8 * e8, t, qa);
+                    if (t == 0) {
+                        float* at = (float*)(buf + L::oAT) + 8 * e8;
+                        *(f4*)at = f4{ex2(tot[0]), ex2(tot[1]), ex2(tot[2]), ex2(tot[3])};
+                        *(f4*)(at + 4) = f4{ex2(tot[4]), ex2(tot[5]), ex2(tot[6]), ex2(tot[7])};
+                    }
+                    if (e8 == 0) ((float*)(buf + L::oGK))[t] = ok ? a.gk[row] : 0.f;
+                }
+                {  // the 64-column slice of dout (gated) and of v: 128 chunks each
+                    const int x = ptid & 127, t = x >> 3, e8 = x & 7, tok = t0 + t;
+                    const bool ok = tok < T;
+                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+                    if (ptid < 128) {
+                        const u4 dx = load16(a.dout + row * DV + sbase + 8 * e8, ok);
+                        const float gq = ok ? a.gq[row] : 0.f;
+                        u4 dy;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) dy[i] = pack2(gq * bf_lo(dx[i]), gq * bf_hi(dx[i]));
+                        put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
+                    } else {
+                        const u4 vx = load16(a.v + row * DV + sbase + 8 * e8, ok);
+                        uint16_t* vs = (uint16_t*)(buf + L::oVS) + t * kFS + 8 * e8;
+                        *(u2*)vs = u2{vx[0], vx[1]};
+                        *(u2*)(vs + 4) = u2{vx[2], vx[3]};
+                    }
+                }
+            }
+        } else if (it > 0) {
+            const int blk = it - 1;
+            const unsigned char* buf = smem + (blk & 1) * L::bytes;
+            const int t0 = (nb - 1 - blk) * kTok;
+            const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
+            const uint16_t* KDp = (const uint16_t*)(buf + L::oKD);
+            const uint16_t* KBp = (const uint16_t*)(buf + L::oKB);
+            // Pq[t][j] = qa_t . kd_j, kept for j <= t
+            f4 Pq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DK / 32; ++c) mma32(Pq, get_perm<DK>(QAp, r, g, c), get_perm<DK>(KDp, r, g, c));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (r > 4 * g + i) Pq[i] = 0.f;
+            const s4 fp = pack4(Pq);
+            // dv'^T[n][j] = sum_d dS[d][n] kb_j[d] + sum_t dy_t[n] Pq[t][j]
+            f4 Ys = {0.f, 0.f, 0.f, 0.f}, Yi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DK / 32; ++c)
+                mma32(Ys, join(pack4(DS[2 * c]), pack4(DS[2 * c + 1])), get_perm<DK>(KBp, r, g, c));
+            const s4 fdy = get_T((const uint16_t*)(buf + L::oDYT), cb + r, g);
+            mma16(Yi, fdy, fp);
+            const u2 vx = *(const u2*)((const uint16_t*)(buf + L::oVS) + r * kFS + cb + 4 * g);
+            const float vf[4] = {bf_lo(vx[0]), bf_hi(vx[0]), bf_lo(vx[1]), bf_hi(vx[1])};
+            const float gk = ((const float*)(buf + L::oGK))[r];
+            float dvp[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dvp[i] = Ys[i] + Yi[i];
+            float part = vf[0] * dvp[0] + vf[1] * dvp[1] + vf[2] * dvp[2] + vf[3] * dvp[3];
+            part = reduce_groups(part);
+            const int tok = t0 + r;
+            if (tok < T) {
+                const size_t row = ((size_t)b * T + tok) * H + h;
+                if (g == 0) a.part_k[((size_t)(slice * 4 + (wave & 3)) * a.B * T * H) + row] = part;
+                *(u2*)(a.dv + row * DV + sbase + cb + 4 * g) =
+                    u2{pack2(gk * dvp[0], gk * dvp[1]), pack2(gk * dvp[2], gk * dvp[3])};
+            }
+            // dS <- diag(A) dS + qa^T dy
+            const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
+            const float* AT = (const float*)(buf + L::oAT);
+#pragma unroll
+            for (int i = 0; i < DK / 16; ++i) {
+                const f4 Ad = *(const f4*)(AT + 16 * i + 4 * g);
+                DS[i] = DS[i] * Ad;
+                mma16(DS[i], get_T(QAT, 16 * i + r, g), fdy);
+            }
+        }
+        __syncthreads();
+    }
+
+    if (!producer && a.ds0) {
+#pragma unroll
+        for (int i = 0; i < DK / 16; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a.ds0[((size_t)bh * DK + 16 * i + 4 * g + j) * DV + sbase + cb + r] = DS[i][j];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Gates (Eq. 4) and their backward.
+// ------------------------------------------------------------------------------------------------------------
+__global__ void sla_bwd_gates_kernel(const float* ql, const float* kl, float* gq, float* gk, size_t rows, int H) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    for (int which = 0; which < 2; ++which) {
+        const float* x = which ? kl : ql;
+        float* g = which ? gk : gq;
+        if (!x) {
+            for (int h = 0; h < H; ++h) g[i * H + h] = 1.f;
+            continue;
+        }
+        float m = -INFINITY;
+        for (int h = 0; h < H; ++h) m = fmaxf(m, x[i * H + h]);
+        float s = 0.f;
+        for (int h = 0; h < H; ++h) s += ex2((x[i * H + h] - m) * kLog2e);
+        const float inv = 1.f / s;
+        for (int h = 0; h < H; ++h) g[i * H + h] = ex2((x[i * H + h] - m) * kLog2e) * inv;
+    }
+}
+
+// dlogits = G * (dG - sum_h G dG), dG summed over its partial planes
+__global__ void sla_bwd_logits_kernel(const float* g, const float* part, int planes, float* dl, size_t rows, int H) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    float dot = 0.f;
+    for (int h = 0; h < H; ++h) {
+        float dg = 0.f;
+        for (int p = 0; p < planes; ++p) dg += part[(size_t)p * rows * H + i * H + h];
+        dl[i * H + h] = dg;
+        dot += g[i * H + h] * dg;
+    }
+    for (int h = 0; h < H; ++h) dl[i * H + h] = g[i * H + h] * (dl[i * H + h] - dot);
+}
+
+size_t round4(size_t n) { return (n + 3) & ~(size_t)3; }
+
+template <typename K>
+bool allow_lds(K kernel, int lds) {
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess)
+        return true;
+    (void)hipGetLastError();
+    return false;
+}
+
+template <int VAR, int DK, int DV>
+int launch_sweeps(const BArgs& a, hipStream_t stream) {
+    constexpr int ldsF = 2 * SmemF<DV>::bytes, ldsV = 2 * SmemV<DK>::bytes, ldsK = 2 * SmemK<DV>::bytes;
+    static bool configured = false;  // once per instantiation; not a stream operation
+    if (!configured) {
+        if (!allow_lds(sla_bwd_dq_kernel<VAR, DK, DV>, ldsF) || !allow_lds(sla_bwd_dv_kernel<VAR, DK, DV>, ldsV) ||
+            !allow_lds(sla_bwd_dk_kernel<VAR, DK, DV>, ldsK))
+            return SLA_ERR_HIP;
+        configured = true;
+    }
+    const unsigned bh = (unsigned)(a.B * a.H);
+    const dim3 block(kBwdThreads);
+    hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), dim3(bh * (DK / kCols)), block, (size_t)ldsF, stream, a);
+    hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), dim3(bh * (DV / kCols)), block, (size_t)ldsV, stream, a);
+    hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), dim3(bh * (DK / kCols)), block, (size_t)ldsK, stream, a);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+template <int VAR, int DK>
+int launch_dv(const BArgs& a, int dv, hipStream_t stream) {
+    switch (dv) {
+        case 64: return launch_sweeps<VAR, DK, 64>(a, stream);
+        case 128: return launch_sweeps<VAR, DK, 128>(a, stream);
+        case 256: return launch_sweeps<VAR, DK, 256>(a, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+template <int VAR>
+int launch_dk(const BArgs& a, int dk, int dv, hipStream_t stream) {
+    switch (dk) {
+        case 64: return launch_dv<VAR, 64>(a, dv, stream);
+        case 128: return launch_dv<VAR, 128>(a, dv, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+// Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q (dk/16 planes) and dG^K (dv/16 planes); for GLA
+// q*dq [B,T,H,dk] and the final-state term of dlog_decay [B,H,dk].
+size_t backward_workspace_floats(const sla_params& p) {
+    const size_t n = round4((size_t)p.B * p.T * p.H);
+    size_t total = n * (2 + p.dk / 16 + p.dv / 16);
+    if (p.variant == SLA_GLA) total += round4((size_t)p.B * p.T * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk);
+    return total;
+}
+
+int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
+                    const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
+                    float* dql, float* dkl, void* dld, float* ds0, float* ws, hipStream_t stream) {
+    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H);
+    BArgs a;
+    a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
+    a.ld = p.variant == SLA_GLA ? (const uint16_t*)ld : nullptr;
+    a.ld_head = p.variant == SLA_RETNET ? (const float*)ld : nullptr;
+    float* w = ws;
+    float* gq = w; w += n;
+    float* gk = w; w += n;
+    a.gq = gq; a.gk = gk;
+    a.part_q = w; w += n * (p.dk / 16);
+    a.part_k = w; w += n * (p.dv / 16);
+    a.qdq = nullptr; a.corr = nullptr;
+    if (p.variant == SLA_GLA) {
+        a.qdq = w; w += round4(rows * p.H * p.dk);
+        a.corr = w;
+    }
+    a.s0 = s0; a.dsf = dsf;
+    a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.dld = (uint16_t*)dld; a.ds0 = ds0;
+    a.B = p.B; a.T = p.T; a.H = p.H;
+
+    const unsigned eb = 256, eg = (unsigned)((rows + eb - 1) / eb);
+    if (rows > 0) {
+        hipLaunchKernelGGL(sla_bwd_gates_kernel, dim3(eg), dim3(eb), 0, stream, ql, kl, gq, gk, rows, p.H);
+        if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
+    }
+    const int rc = p.variant == SLA_GLA ? launch_dk<SLA_GLA>(a, p.dk, p.dv, stream)
+                                        : launch_dk<SLA_RETNET>(a, p.dk, p.dv, stream);
+    if (rc != SLA_OK || rows == 0) return rc;
+    // the planes of one gate are n floats apart (n >= rows * H); the kernel indexes them by rows * H
+    hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gq, (const float*)a.part_q,
+                       p.dk / 16, dql, rows, p.H);
+    if (kl)
+        hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gk,
+                           (const float*)a.part_k, p.dv / 16, dkl, rows, p.H);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+}  // namespace sla

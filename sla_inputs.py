@@ -211,3 +211,17 @@ def initial_state(B: int, H: int, dk: int, dv: int, seed: int, scale: float = 0.
     """A random fp32 entry state ``[B,H,dk,dv]`` for the chaining tests."""
     rng = np.random.default_rng(seed)
     return (rng.standard_normal(size=(B, H, dk, dv), dtype=np.float32) * np.float32(scale)).astype(np.float32)
+
+
+def cotangents(B: int, T: int, H: int, dk: int, dv: int, seed: int, dtype: str = "bf16",
+               final_state: bool = False) -> Dict[str, Optional[np.ndarray]]:
+    """Seeded cotangents for the backward pass: ``d_out [B,T,H,dv]`` ~ N(0,1) (rounded to bf16 when the
+    workload is bf16) and, when asked for, ``d_final_state [B,H,dk,dv]`` ~ N(0, 0.25) in fp32."""
+    rng = np.random.default_rng(seed)
+    d_out = rng.standard_normal(size=(B, T, H, dv), dtype=np.float32)
+    if dtype == "bf16":
+        d_out = round_to_bf16(d_out)
+    dsf = None
+    if final_state:
+        dsf = (rng.standard_normal(size=(B, H, dk, dv), dtype=np.float32) * np.float32(0.5)).astype(np.float32)
+    return {"d_out": np.ascontiguousarray(d_out, dtype=np.float32), "d_final_state": dsf}
