@@ -23,7 +23,7 @@
 //   R1: Pq[t][j] = qa_t . kd_j (j <= t);   dv'_j = kb_j dS + sum_t Pq[t][j] G^Q_t dout_t;
 //       dS <- diag(A) dS + qa^T (G^Q dout)
 //   R2: dk'_j = (1/p_j) * sum_t G^Q_t P'[t][j] qa_t + (A/p_j) * (v_j dS^T);   dS^T <- dS^T A + (G^Q dout)^T qa
-// Every workgroup has four consumer waves (16 columns of the slice each, their state tile in registers) and four
+// Every workgroup has four consumer waves (16 columns of the slice each, their state tile in registers) and eight
 // producer waves that stage the next block's operands in LDS while the consumers work on the current one; the two
 // halves meet at one barrier per block.
 #include <hip/hip_runtime.h>
@@ -44,7 +44,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u2;
 
 constexpr int kTok = 16;        // tokens per block
-constexpr int kBwdThreads = 512;
+constexpr int kBwdThreads = 768;  // four consumer waves, eight producer waves
 constexpr int kCols = 64;       // columns of the sliced dimension per workgroup
 constexpr int kTS = 20;         // token stride (elements) of the transposed [column][token] tiles
 constexpr int kFS = 68;         // row stride (elements) of the [token][64 columns] tiles
@@ -131,6 +131,12 @@ __device__ __forceinline__ void put_perm(uint16_t* tile, int t, int e8, u4 x) {
     *(u2*)(row + 8 * g0) = u2{x[0], x[1]};
     *(u2*)(row + 8 * (g0 + 1)) = u2{x[2], x[3]};
 }
+// the same tile, four adjacent columns 4 e4 .. 4 e4 + 3 of one token
+template <int KD>
+__device__ __forceinline__ void put_perm4(uint16_t* tile, int t, int e4, u2 x) {
+    const int S = e4 >> 3, u = (e4 >> 2) & 1, g = e4 & 3;
+    *(u2*)(tile + t * (KD + 8) + 32 * S + 8 * g + 4 * u) = x;
+}
 template <int KD>
 __device__ __forceinline__ s8 get_perm(const uint16_t* tile, int r, int g, int c) {
     return *(const s8*)(tile + r * (KD + 8) + 32 * c + 8 * g);
@@ -143,30 +149,105 @@ __device__ __forceinline__ void put_T(uint16_t* tile, int col0, int t, u4 x) {
         tile[(col0 + 2 * i + 1) * kTS + t] = (uint16_t)(x[i] >> 16);
     }
 }
-__device__ __forceinline__ s4 get_T(const uint16_t* tile, int col, int g) { return *(const s4*)(tile + col * kTS + 4 * g); }
-
-__device__ __forceinline__ u4 load16(const uint16_t* p, bool ok) {
-    return ok ? *(const u4*)p : u4{0u, 0u, 0u, 0u};
-}
-
-// log2-domain decay steps of eight key columns of one token (zero outside the sequence)
-template <int VAR>
-__device__ __forceinline__ void load_steps(const BArgs& a, size_t row, int h, int dk, int d0, bool ok, float* l) {
-    if constexpr (VAR == SLA_GLA) {
-        const u4 x = load16(a.ld + row * dk + d0, ok);
+__device__ __forceinline__ void put_T4(uint16_t* tile, int col0, int t, u2 x) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) l[i] = bf_at(x, i) * kLog2e;
-    } else {
-        const float s = ok ? a.ld_head[h] * kLog2e : 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) l[i] = s;
+    for (int i = 0; i < 2; ++i) {
+        tile[(col0 + 2 * i) * kTS + t] = (uint16_t)(x[i] & 0xffffu);
+        tile[(col0 + 2 * i + 1) * kTS + t] = (uint16_t)(x[i] >> 16);
     }
 }
+__device__ __forceinline__ s4 get_T(const uint16_t* tile, int col, int g) { return *(const s4*)(tile + col * kTS + 4 * g); }
 
-__device__ __forceinline__ float reduce_groups(float x) {  // sum over the four 16-lane groups
-    x += __shfl_xor(x, 16);
-    x += __shfl_xor(x, 32);
-    return x;
+// Producer loads are unconditional (tokens past the end read the last token's row) and are zeroed when they are
+// staged: a load under a lane mask would have to complete at the join, which defeats loading blocks ahead.
+__device__ __forceinline__ u4 load16(const uint16_t* p) { return *(const u4*)p; }
+__device__ __forceinline__ u2 load8(const uint16_t* p) { return *(const u2*)p; }
+__device__ __forceinline__ u4 keep(u4 x, bool ok) { return u4{ok ? x[0] : 0u, ok ? x[1] : 0u, ok ? x[2] : 0u, ok ? x[3] : 0u}; }
+__device__ __forceinline__ u2 keep(u2 x, bool ok) { return u2{ok ? x[0] : 0u, ok ? x[1] : 0u}; }
+
+// Sum over the four 16-lane rows of a wave, returned in every lane: two register swaps (odd rows against even
+// rows, then the upper half against the lower half) instead of a trip through LDS.
+__device__ __forceinline__ float reduce_groups(float x) {
+    const uint32_t xi = __float_as_uint(x);
+    const u2 a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    const uint32_t yi = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    const u2 b = __builtin_amdgcn_permlane32_swap(yi, yi, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// One barrier per block: the producers fill buffer (i & 1) with block i while the consumers work on block i - 1.
+// Both halves of the workgroup execute the same number of barriers (nb + 1).  The barrier waits for LDS traffic
+// only, so the producers' global loads for later blocks stay in flight across it.
+__device__ __forceinline__ void block_barrier() { __syncthreads(); }
+
+// Developer switch for timing one half of a workgroup alone (results are then meaningless): 1 = consumers only
+// pass the barriers, 2 = producers only issue their loads.
+#ifndef SLA_BWD_EXP
+#define SLA_BWD_EXP 0
+#endif
+constexpr int kExp = SLA_BWD_EXP;
+
+constexpr int kAhead = 3;  // blocks whose global loads a producer has in flight
+
+// Runs issue(block, set) kAhead blocks ahead of stage(block, set, buffer).  The register sets are separate named
+// objects, and every step issues exactly one set of loads (past the end it re-reads the last block): the number
+// of loads in flight behind the set being staged is then the same on every path, which is what lets the wait in
+// front of stage() leave the newer sets in flight.
+template <typename Pre, typename Issue, typename Stage>
+__device__ __forceinline__ void producer_loop(int nb, Issue issue, Stage stage) {
+    static_assert(kAhead == 3, "three register sets are written out below");
+    if (nb == 0) {
+        block_barrier();
+        return;
+    }
+    Pre p0, p1, p2;
+    issue(0, p0);
+    issue(min(1, nb - 1), p1);
+    issue(min(2, nb - 1), p2);
+    int it = 0;
+    while (true) {
+        if (kExp != 2) stage(it, p0, it & 1);
+        issue(min(it + kAhead, nb - 1), p0);
+        block_barrier();
+        if (++it == nb) break;
+        if (kExp != 2) stage(it, p1, it & 1);
+        issue(min(it + kAhead, nb - 1), p1);
+        block_barrier();
+        if (++it == nb) break;
+        if (kExp != 2) stage(it, p2, it & 1);
+        issue(min(it + kAhead, nb - 1), p2);
+        block_barrier();
+        if (++it == nb) break;
+    }
+    block_barrier();
+}
+
+// What a decay-side producer thread holds for one token and eight key columns; a copy-side thread holds up to
+// four 16-byte pieces of two tensors.
+struct PreKeys {
+    u2 ld, kx, qx;
+    float gq, gk;
+};
+template <int R>
+struct PreRows {
+    u4 a[R], b[R];
+    float gq[R];
+};
+
+// Inclusive running sums c[i] of the log2-domain decay steps of four key columns over the 16 tokens of the block
+// (token = lane % 16), and their totals.
+template <int VAR>
+__device__ __forceinline__ void block_decay(const u2& ldx, float head_step, bool ok, float* c, float* tot) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float l;
+        if constexpr (VAR == SLA_GLA)
+            l = ((i & 1) ? bf_hi(ldx[i >> 1]) : bf_lo(ldx[i >> 1])) * kLog2e;  // zero outside the sequence
+        else
+            l = ok ? head_step : 0.f;
+        c[i] = row_prefix(l);
+        tot[i] = row_last(c[i]);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -194,139 +275,154 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     typedef SmemF<DV> L;
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NSL = DK / kCols;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int R = (DV / 8 * kTok + 255) / 256;  // 16-byte pieces of dout (and of v) per copy thread
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
     const int r = lane & 15, g = lane >> 4;
     const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
     const int T = a.T, H = a.H;
     const int nb = (T + kTok - 1) / kTok;
-    const bool producer = wave >= 4;
     const int cb = 16 * (wave & 3);
 
-    f4 ST[DV / 16];
-    if (!producer) {
+    if (wave >= 4) {
+        const int ptid = tid - 256;
+        if (wave < 8) {  // decay, keys and queries of the slice: token t = lane % 16, four columns
+            const int e4 = ptid >> 4, t = ptid & 15, d0 = sbase + 4 * e4;
+            const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
+            producer_loop<PreKeys>(
+                nb,
+                [&](int blk, PreKeys& p) {
+                    const int tok = min(blk * kTok + t, T - 1);
+                    const size_t row = ((size_t)b * T + tok) * H + h;
+                    if constexpr (VAR == SLA_GLA) p.ld = load8(a.ld + row * DK + d0);
+                    p.kx = load8(a.k + row * DK + d0);
+                    p.qx = load8(a.q + row * DK + d0);
+                    p.gk = a.gk[row];
+                    p.gq = a.gq[row];
+                },
+                [&](int blk, const PreKeys& pp, int which) {
+                    unsigned char* buf = smem + which * L::bytes;
+                    const bool ok = blk * kTok + t < T;
+                    PreKeys p;
+                    p.ld = keep(pp.ld, ok); p.kx = keep(pp.kx, ok); p.qx = keep(pp.qx, ok);
+                    p.gk = ok ? pp.gk : 0.f; p.gq = ok ? pp.gq : 0.f;
+                    float c[4], tot[4];
+                    block_decay<VAR>(p.ld, head_step, ok, c, tot);
+                    *(f4*)((float*)(buf + L::oCUM) + t * kFS + 4 * e4) = f4{c[0], c[1], c[2], c[3]};
+                    if (t == 0) *(f4*)((float*)(buf + L::oTOT) + 4 * e4) = f4{tot[0], tot[1], tot[2], tot[3]};
+                    u2 kd, kb;
 #pragma unroll
-        for (int i = 0; i < DV / 16; ++i) {
-            if (a.s0)
-                ST[i] = *(const f4*)(a.s0 + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
-            else
-                ST[i] = f4{0.f, 0.f, 0.f, 0.f};
+                    for (int i = 0; i < 2; ++i) {
+                        const float k0 = bf_lo(p.kx[i]) * p.gk, k1 = bf_hi(p.kx[i]) * p.gk;
+                        kd[i] = pack2(k0 * ex2(-c[2 * i]), k1 * ex2(-c[2 * i + 1]));
+                        kb[i] = pack2(k0 * ex2(tot[2 * i] - c[2 * i]), k1 * ex2(tot[2 * i + 1] - c[2 * i + 1]));
+                    }
+                    put_T4((uint16_t*)(buf + L::oKDT), 4 * e4, t, kd);
+                    put_T4((uint16_t*)(buf + L::oKBT), 4 * e4, t, kb);
+                    *(u2*)((uint16_t*)(buf + L::oQS) + t * kFS + 4 * e4) = p.qx;
+                    if (e4 == 0) ((float*)(buf + L::oGQ))[t] = p.gq;
+                });
+        } else {  // dout and v, all value columns
+            const int x = ptid - 256;
+            producer_loop<PreRows<R>>(
+                nb,
+                [&](int blk, PreRows<R>& p) {
+#pragma unroll
+                    for (int rep = 0; rep < R; ++rep) {
+                        const int c = (x + 256 * rep) % (kTok * DV / 8), t = c / (DV / 8), e8 = c % (DV / 8);
+                        const int tok = min(blk * kTok + t, T - 1);
+                        const size_t row = ((size_t)b * T + tok) * H + h;
+                        p.a[rep] = load16(a.dout + row * DV + 8 * e8);
+                        p.b[rep] = load16(a.v + row * DV + 8 * e8);
+                    }
+                },
+                [&](int blk, const PreRows<R>& p, int which) {
+                    unsigned char* buf = smem + which * L::bytes;
+#pragma unroll
+                    for (int rep = 0; rep < R; ++rep) {
+                        const int c = x + 256 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        if (c < kTok * DV / 8) {
+                            const bool ok = blk * kTok + t < T;
+                            const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
+                            put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                            put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                            put_T((uint16_t*)(buf + L::oVT), 8 * e8, t, vx);
+                        }
+                    }
+                });
         }
+        return;
     }
 
-    for (int it = 0; it <= nb; ++it) {
-        if (producer) {
-            if (it < nb) {
-                unsigned char* buf = smem + (it & 1) * L::bytes;
-                const int t0 = it * kTok, ptid = tid - 256;
-                if (ptid < 128) {
-                    const int e8 = ptid >> 4, t = ptid & 15, tok = t0 + t;
-                    const bool ok = tok < T;
-                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-                    const int d0 = sbase + 8 * e8;
-                    float l[8];
-                    load_steps<VAR>(a, row, h, DK, d0, ok, l);
-                    const u4 kx = load16(a.k + row * DK + d0, ok);
-                    const u4 qx = load16(a.q + row * DK + d0, ok);
-                    const float gk = ok ? a.gk[row] : 0.f;
-                    float c[8], tot[8];
+    f4 ST[DV / 16];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        c[i] = row_prefix(l[i]);
-                        tot[i] = row_last(c[i]);
-                    }
-                    float* cum = (float*)(buf + L::oCUM) + t * kFS + 8 * e8;
-                    *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
-                    *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
-                    if (t == 0) {
-                        float* tt = (float*)(buf + L::oTOT) + 8 * e8;
-                        *(f4*)tt = f4{tot[0], tot[1], tot[2], tot[3]};
-                        *(f4*)(tt + 4) = f4{tot[4], tot[5], tot[6], tot[7]};
-                    }
-                    uint16_t* kdt = (uint16_t*)(buf + L::oKDT);
-                    uint16_t* kbt = (uint16_t*)(buf + L::oKBT);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float kf = bf_at(kx, i) * gk;
-                        kdt[(8 * e8 + i) * kTS + t] = bf_bits(kf * ex2(-c[i]));
-                        kbt[(8 * e8 + i) * kTS + t] = bf_bits(kf * ex2(tot[i] - c[i]));
-                    }
-                    uint16_t* qs = (uint16_t*)(buf + L::oQS) + t * kFS + 8 * e8;
-                    *(u2*)qs = u2{qx[0], qx[1]};
-                    *(u2*)(qs + 4) = u2{qx[2], qx[3]};
-                    if (e8 == 0) ((float*)(buf + L::oGQ))[t] = ok ? a.gq[row] : 0.f;
-                } else {
-                    const int x = ptid - 128;
-#pragma unroll
-                    for (int rep = 0; rep < (DV / 8 * kTok) / 128; ++rep) {
-                        const int c = x + 128 * rep, t = c / (DV / 8), e8 = c % (DV / 8), tok = t0 + t;
-                        const bool ok = tok < T;
-                        const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-                        const u4 dx = load16(a.dout + row * DV + 8 * e8, ok);
-                        const u4 vx = load16(a.v + row * DV + 8 * e8, ok);
-                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
-                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
-                        put_T((uint16_t*)(buf + L::oVT), 8 * e8, t, vx);
-                    }
-                }
-            }
-        } else if (it > 0) {
-            const int blk = it - 1;
-            const unsigned char* buf = smem + (blk & 1) * L::bytes;
-            const int t0 = blk * kTok;
-            const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
-            const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
-            // P'^T[j][t] = v_j . dout_t, kept for j <= t
-            f4 pT = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < DV / 32; ++c) mma32(pT, get_perm<DV>(Vp, r, g, c), get_perm<DV>(DOp, r, g, c));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (4 * g + i > r) pT[i] = 0.f;
-            const s4 fp = pack4(pT);
-            // dqa^T[d][t] = sum_n S^T[n][d] dout_t[n] + sum_j kd'_j[d] P'[t][j]
-            f4 oS = {0.f, 0.f, 0.f, 0.f}, oP = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < DV / 32; ++c)
-                mma32(oS, join(pack4(ST[2 * c]), pack4(ST[2 * c + 1])), get_perm<DV>(DOp, r, g, c));
-            const s4 fkd = get_T((const uint16_t*)(buf + L::oKDT), cb + r, g);
-            mma16(oP, fkd, fp);
-            const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
-            const u2 qx = *(const u2*)((const uint16_t*)(buf + L::oQS) + r * kFS + cb + 4 * g);
-            const float gq = ((const float*)(buf + L::oGQ))[r];
-            float dqp[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * ex2(cum[i]);
-            const float qf[4] = {bf_lo(qx[0]), bf_hi(qx[0]), bf_lo(qx[1]), bf_hi(qx[1])};
-            float part = qf[0] * dqp[0] + qf[1] * dqp[1] + qf[2] * dqp[2] + qf[3] * dqp[3];
-            part = reduce_groups(part);
-            const int tok = t0 + r;
-            if (tok < T) {
-                const size_t row = ((size_t)b * T + tok) * H + h;
-                if (g == 0) a.part_q[((size_t)(slice * 4 + (wave & 3)) * a.B * T * H) + row] = part;
-                float dqv[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) dqv[i] = gq * dqp[i];
-                *(u2*)(a.dq + row * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
-                if constexpr (VAR == SLA_GLA)
-                    *(f4*)(a.qdq + row * DK + sbase + cb + 4 * g) =
-                        f4{qf[0] * dqv[0], qf[1] * dqv[1], qf[2] * dqv[2], qf[3] * dqv[3]};
-            }
-            // S^T <- S^T A + v^T kb'
-            const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
-            const s4 fkb = get_T((const uint16_t*)(buf + L::oKBT), cb + r, g);
-            const uint16_t* VT = (const uint16_t*)(buf + L::oVT);
-#pragma unroll
-            for (int i = 0; i < DV / 16; ++i) {
-                ST[i] = ST[i] * Ad;
-                mma16(ST[i], get_T(VT, 16 * i + r, g), fkb);
-            }
+    for (int i = 0; i < DV / 16; ++i) {
+        if (a.s0)
+            ST[i] = *(const f4*)(a.s0 + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
+        else
+            ST[i] = f4{0.f, 0.f, 0.f, 0.f};
+    }
+    block_barrier();
+    for (int blk = 0; blk < nb; ++blk) {
+        if (kExp == 1) {
+            block_barrier();
+            continue;
         }
-        __syncthreads();
+        const unsigned char* buf = smem + (blk & 1) * L::bytes;
+        const int t0 = blk * kTok;
+        const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
+        const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
+        // P'^T[j][t] = v_j . dout_t, kept for j <= t
+        f4 pT = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < DV / 32; ++c) mma32(pT, get_perm<DV>(Vp, r, g, c), get_perm<DV>(DOp, r, g, c));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * g + i > r) pT[i] = 0.f;
+        const s4 fp = pack4(pT);
+        // dqa^T[d][t] = sum_n S^T[n][d] dout_t[n] + sum_j kd'_j[d] P'[t][j]
+        f4 oS = {0.f, 0.f, 0.f, 0.f}, oP = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < DV / 32; ++c)
+            mma32(oS, join(pack4(ST[2 * c]), pack4(ST[2 * c + 1])), get_perm<DV>(DOp, r, g, c));
+        const s4 fkd = get_T((const uint16_t*)(buf + L::oKDT), cb + r, g);
+        mma16(oP, fkd, fp);
+        const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
+        const u2 qx = *(const u2*)((const uint16_t*)(buf + L::oQS) + r * kFS + cb + 4 * g);
+        const float gq = ((const float*)(buf + L::oGQ))[r];
+        float dqp[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * ex2(cum[i]);
+        const float qf[4] = {bf_lo(qx[0]), bf_hi(qx[0]), bf_lo(qx[1]), bf_hi(qx[1])};
+        float part = qf[0] * dqp[0] + qf[1] * dqp[1] + qf[2] * dqp[2] + qf[3] * dqp[3];
+        part = reduce_groups(part);
+        const int tok = t0 + r;
+        if (tok < T) {
+            const size_t row = ((size_t)b * T + tok) * H + h;
+            if (g == 0) a.part_q[((size_t)(slice * 4 + wave) * a.B * T * H) + row] = part;
+            float dqv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dqv[i] = gq * dqp[i];
+            *(u2*)(a.dq + row * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
+            if constexpr (VAR == SLA_GLA)
+                *(f4*)(a.qdq + row * DK + sbase + cb + 4 * g) =
+                    f4{qf[0] * dqv[0], qf[1] * dqv[1], qf[2] * dqv[2], qf[3] * dqv[3]};
+        }
+        // S^T <- S^T A + v^T kb'
+        const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
+        const s4 fkb = get_T((const uint16_t*)(buf + L::oKBT), cb + r, g);
+        const uint16_t* VT = (const uint16_t*)(buf + L::oVT);
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) {
+            ST[i] = ST[i] * Ad;
+            mma16(ST[i], get_T(VT, 16 * i + r, g), fkb);
+        }
+        block_barrier();
     }
 
     if constexpr (VAR == SLA_GLA) {
-        if (!producer && a.dsf) {  // rowsum(dS_T * S_T) for the key columns of this wave
+        if (a.dsf) {  // rowsum(dS_T * S_T) for the key columns of this wave
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < DV / 16; ++i) {
@@ -364,146 +460,175 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     typedef SmemK<DV> L;
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NSL = DK / kCols;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int R = (DV / 8 * kTok + 255) / 256;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
     const int r = lane & 15, g = lane >> 4;
     const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
     const int T = a.T, H = a.H;
     const int nb = (T + kTok - 1) / kTok;
-    const bool producer = wave >= 4;
     const int cb = 16 * (wave & 3);
+
+    if (wave >= 4) {  // block number i of the sweep covers tokens (nb - 1 - i) * 16 ...
+        const int ptid = tid - 256;
+        if (wave < 8) {
+            const int e4 = ptid >> 4, t = ptid & 15, d0 = sbase + 4 * e4;
+            const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
+            producer_loop<PreKeys>(
+                nb,
+                [&](int i, PreKeys& p) {
+                    const int tok = min((nb - 1 - i) * kTok + t, T - 1);
+                    const size_t row = ((size_t)b * T + tok) * H + h;
+                    if constexpr (VAR == SLA_GLA) p.ld = load8(a.ld + row * DK + d0);
+                    p.kx = load8(a.k + row * DK + d0);
+                    p.qx = load8(a.q + row * DK + d0);
+                    p.gk = a.gk[row];
+                    p.gq = a.gq[row];
+                },
+                [&](int i, const PreKeys& pp, int which) {
+                    unsigned char* buf = smem + which * L::bytes;
+                    const bool ok = (nb - 1 - i) * kTok + t < T;
+                    PreKeys p;
+                    p.ld = keep(pp.ld, ok); p.kx = keep(pp.kx, ok); p.qx = keep(pp.qx, ok);
+                    p.gk = ok ? pp.gk : 0.f; p.gq = ok ? pp.gq : 0.f;
+                    float c[4], tot[4];
+                    block_decay<VAR>(p.ld, head_step, ok, c, tot);
+                    *(f4*)((float*)(buf + L::oCUM) + t * kFS + 4 * e4) = f4{c[0], c[1], c[2], c[3]};
+                    if (t == 0) *(f4*)((float*)(buf + L::oTOT) + 4 * e4) = f4{tot[0], tot[1], tot[2], tot[3]};
+                    u2 qa;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        qa[j] = pack2(bf_lo(p.qx[j]) * ex2(c[2 * j]), bf_hi(p.qx[j]) * ex2(c[2 * j + 1]));
+                    put_T4((uint16_t*)(buf + L::oQAT), 4 * e4, t, qa);
+                    *(u2*)((uint16_t*)(buf + L::oKS) + t * kFS + 4 * e4) = p.kx;
+                    if (e4 == 0) {
+                        ((float*)(buf + L::oGQ))[t] = p.gq;
+                        ((float*)(buf + L::oGK))[t] = p.gk;
+                    }
+                });
+        } else {
+            const int x = ptid - 256;
+            producer_loop<PreRows<R>>(
+                nb,
+                [&](int i, PreRows<R>& p) {
+#pragma unroll
+                    for (int rep = 0; rep < R; ++rep) {
+                        const int c = (x + 256 * rep) % (kTok * DV / 8), t = c / (DV / 8), e8 = c % (DV / 8);
+                        const int tok = min((nb - 1 - i) * kTok + t, T - 1);
+                        const size_t row = ((size_t)b * T + tok) * H + h;
+                        p.a[rep] = load16(a.dout + row * DV + 8 * e8);
+                        p.b[rep] = load16(a.v + row * DV + 8 * e8);
+                        p.gq[rep] = a.gq[row];
+                    }
+                },
+                [&](int i, const PreRows<R>& p, int which) {
+                    unsigned char* buf = smem + which * L::bytes;
+#pragma unroll
+                    for (int rep = 0; rep < R; ++rep) {
+                        const int c = x + 256 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        if (c < kTok * DV / 8) {
+                            const bool ok = (nb - 1 - i) * kTok + t < T;
+                            const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
+                            put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                            put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                            u4 dy;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                dy[j] = pack2(p.gq[rep] * bf_lo(dx[j]), p.gq[rep] * bf_hi(dx[j]));
+                            put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
+                        }
+                    }
+                });
+        }
+        return;
+    }
 
     f4 DST[DV / 16];
     float run[4] = {0.f, 0.f, 0.f, 0.f};  // sum over later tokens of q*dq - k*dk, for key columns cb + 4g + i
-    if (!producer) {
 #pragma unroll
-        for (int i = 0; i < DV / 16; ++i) {
-            if (a.dsf)
-                DST[i] = *(const f4*)(a.dsf + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
-            else
-                DST[i] = f4{0.f, 0.f, 0.f, 0.f};
-        }
-        if constexpr (VAR == SLA_GLA) {
-            if (a.dsf) {
+    for (int i = 0; i < DV / 16; ++i) {
+        if (a.dsf)
+            DST[i] = *(const f4*)(a.dsf + ((size_t)bh * DK + sbase + cb + r) * DV + 16 * i + 4 * g);
+        else
+            DST[i] = f4{0.f, 0.f, 0.f, 0.f};
+    }
+    if constexpr (VAR == SLA_GLA) {
+        if (a.dsf) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) run[i] = a.corr[(size_t)bh * DK + sbase + cb + 4 * g + i];
-            }
+            for (int i = 0; i < 4; ++i) run[i] = a.corr[(size_t)bh * DK + sbase + cb + 4 * g + i];
         }
     }
-
-    for (int it = 0; it <= nb; ++it) {
-        if (producer) {
-            if (it < nb) {
-                unsigned char* buf = smem + (it & 1) * L::bytes;
-                const int t0 = (nb - 1 - it) * kTok, ptid = tid - 256;
-                if (ptid < 128) {
-                    const int e8 = ptid >> 4, t = ptid & 15, tok = t0 + t;
-                    const bool ok = tok < T;
-                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-                    const int d0 = sbase + 8 * e8;
-                    float l[8];
-                    load_steps<VAR>(a, row, h, DK, d0, ok, l);
-                    const u4 kx = load16(a.k + row * DK + d0, ok);
-                    const u4 qx = load16(a.q + row * DK + d0, ok);
-                    float c[8], tot[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        c[i] = row_prefix(l[i]);
-                        tot[i] = row_last(c[i]);
-                    }
-                    float* cum = (float*)(buf + L::oCUM) + t * kFS + 8 * e8;
-                    *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
-                    *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
-                    if (t == 0) {
-                        float* tt = (float*)(buf + L::oTOT) + 8 * e8;
-                        *(f4*)tt = f4{tot[0], tot[1], tot[2], tot[3]};
-                        *(f4*)(tt + 4) = f4{tot[4], tot[5], tot[6], tot[7]};
-                    }
-                    uint16_t* qat = (uint16_t*)(buf + L::oQAT);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) qat[(8 * e8 + i) * kTS + t] = bf_bits(bf_at(qx, i) * ex2(c[i]));
-                    uint16_t* ks = (uint16_t*)(buf + L::oKS) + t * kFS + 8 * e8;
-                    *(u2*)ks = u2{kx[0], kx[1]};
-                    *(u2*)(ks + 4) = u2{kx[2], kx[3]};
-                    if (e8 == 0) {
-                        ((float*)(buf + L::oGQ))[t] = ok ? a.gq[row] : 0.f;
-                        ((float*)(buf + L::oGK))[t] = ok ? a.gk[row] : 0.f;
-                    }
-                } else {
-                    const int x = ptid - 128;
-#pragma unroll
-                    for (int rep = 0; rep < (DV / 8 * kTok) / 128; ++rep) {
-                        const int c = x + 128 * rep, t = c / (DV / 8), e8 = c % (DV / 8), tok = t0 + t;
-                        const bool ok = tok < T;
-                        const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-                        const u4 dx = load16(a.dout + row * DV + 8 * e8, ok);
-                        const u4 vx = load16(a.v + row * DV + 8 * e8, ok);
-                        const float gq = ok ? a.gq[row] : 0.f;
-                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
-                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
-                        u4 dy;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) dy[i] = pack2(gq * bf_lo(dx[i]), gq * bf_hi(dx[i]));
-                        put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
-                    }
-                }
-            }
-        } else if (it > 0) {
-            const int blk = it - 1;
-            const unsigned char* buf = smem + (blk & 1) * L::bytes;
-            const int t0 = (nb - 1 - blk) * kTok;
-            const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
-            const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
-            const float* GQ = (const float*)(buf + L::oGQ);
-            // dP[t][j] = G^Q_t (dout_t . v_j), kept for j <= t
-            f4 dP = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < DV / 32; ++c) mma32(dP, get_perm<DV>(DOp, r, g, c), get_perm<DV>(Vp, r, g, c));
-            const f4 gq4 = *(const f4*)(GQ + 4 * g);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dP[i] = (r > 4 * g + i) ? 0.f : dP[i] * gq4[i];
-            const s4 fp = pack4(dP);
-            // Xs^T[d][j] = sum_n dS^T[n][d] v_j[n];  Xi^T[d][j] = sum_t qa_t[d] dP[t][j]
-            f4 Xs = {0.f, 0.f, 0.f, 0.f}, Xi = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < DV / 32; ++c)
-                mma32(Xs, join(pack4(DST[2 * c]), pack4(DST[2 * c + 1])), get_perm<DV>(Vp, r, g, c));
-            const s4 fqa = get_T((const uint16_t*)(buf + L::oQAT), cb + r, g);
-            mma16(Xi, fqa, fp);
-            const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
-            const f4 tot = *(const f4*)((const float*)(buf + L::oTOT) + cb + 4 * g);
-            const float gk = ((const float*)(buf + L::oGK))[r];
-            float dkv[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dkv[i] = gk * (Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]));
-            const int tok = t0 + r;
-            const bool ok = tok < T;
-            const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-            if (ok) *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
-            if constexpr (VAR == SLA_GLA) {
-                const u2 kx = *(const u2*)((const uint16_t*)(buf + L::oKS) + r * kFS + cb + 4 * g);
-                const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
-                f4 e = {0.f, 0.f, 0.f, 0.f};
-                if (ok) e = *(const f4*)(a.qdq + row * DK + sbase + cb + 4 * g);
-                float dl[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float s = row_suffix(e[i] - kf[i] * dkv[i]) + run[i];
-                    dl[i] = s;
-                    run[i] = row_first(s);
-                }
-                if (ok) *(u2*)(a.dld + row * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
-            }
-            // dS^T <- dS^T A + dy^T qa
-            const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
-            const uint16_t* DYT = (const uint16_t*)(buf + L::oDYT);
-#pragma unroll
-            for (int i = 0; i < DV / 16; ++i) {
-                DST[i] = DST[i] * Ad;
-                mma16(DST[i], get_T(DYT, 16 * i + r, g), fqa);
-            }
+    auto qdq_at = [&](int blk) {  // q * dq (fp32, written by the dq sweep) for this lane's token of block blk
+        f4 e = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (VAR == SLA_GLA) {  // unconditional, clamped into the sequence; masked where it is used
+            const int tok = max(0, min((nb - 1 - blk) * kTok + r, T - 1));
+            e = *(const f4*)(a.qdq + (((size_t)b * T + tok) * H + h) * DK + sbase + cb + 4 * g);
         }
-        __syncthreads();
+        return e;
+    };
+    f4 e_next = {0.f, 0.f, 0.f, 0.f};
+    if (nb > 0) e_next = qdq_at(0);
+    block_barrier();
+    for (int blk = 0; blk < nb; ++blk) {
+        if (kExp == 1) {
+            block_barrier();
+            continue;
+        }
+        const unsigned char* buf = smem + (blk & 1) * L::bytes;
+        const int t0 = (nb - 1 - blk) * kTok;
+        const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
+        const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
+        const float* GQ = (const float*)(buf + L::oGQ);
+        // dP[t][j] = G^Q_t (dout_t . v_j), kept for j <= t
+        f4 dP = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < DV / 32; ++c) mma32(dP, get_perm<DV>(DOp, r, g, c), get_perm<DV>(Vp, r, g, c));
+        const f4 gq4 = *(const f4*)(GQ + 4 * g);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dP[i] = (r > 4 * g + i) ? 0.f : dP[i] * gq4[i];
+        const s4 fp = pack4(dP);
+        // Xs^T[d][j] = sum_n dS^T[n][d] v_j[n];  Xi^T[d][j] = sum_t qa_t[d] dP[t][j]
+        f4 Xs = {0.f, 0.f, 0.f, 0.f}, Xi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < DV / 32; ++c)
+            mma32(Xs, join(pack4(DST[2 * c]), pack4(DST[2 * c + 1])), get_perm<DV>(Vp, r, g, c));
+        const s4 fqa = get_T((const uint16_t*)(buf + L::oQAT), cb + r, g);
+        mma16(Xi, fqa, fp);
+        const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
+        const f4 tot = *(const f4*)((const float*)(buf + L::oTOT) + cb + 4 * g);
+        const float gk = ((const float*)(buf + L::oGK))[r];
+        float dkv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dkv[i] = gk * (Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]));
+        const int tok = t0 + r;
+        const bool ok = tok < T;
+        const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+        if (ok) *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+        if constexpr (VAR == SLA_GLA) {
+            const u2 kx = *(const u2*)((const uint16_t*)(buf + L::oKS) + r * kFS + cb + 4 * g);
+            const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
+            f4 e = e_next;  // q * dq of this block, requested one block ago
+            if (!ok) e = f4{0.f, 0.f, 0.f, 0.f};
+            e_next = qdq_at(blk + 1);
+            float dl[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float s = row_suffix(e[i] - kf[i] * dkv[i]) + run[i];
+                dl[i] = s;
+                run[i] = row_first(s);
+            }
+            if (ok) *(u2*)(a.dld + row * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
+        }
+        // dS^T <- dS^T A + dy^T qa
+        const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
+        const uint16_t* DYT = (const uint16_t*)(buf + L::oDYT);
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) {
+            DST[i] = DST[i] * Ad;
+            mma16(DST[i], get_T(DYT, 16 * i + r, g), fqa);
+        }
+        block_barrier();
     }
 }
 
@@ -526,141 +651,159 @@ struct SmemV {
                   "tiles stay 16-byte aligned");
 };
 
+struct PreVals {  // key-side thread of sweep R1: its token's keys, queries, decay, and one piece of dout or v
+    u2 ld, kx, qx;
+    u4 sl;
+    float gq, gk;
+};
+
 template <int VAR, int DK, int DV>
 __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) {
     typedef SmemV<DK> L;
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NSL = DV / kCols;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
     const int r = lane & 15, g = lane >> 4;
     const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
     const int T = a.T, H = a.H;
     const int nb = (T + kTok - 1) / kTok;
-    const bool producer = wave >= 4;
     const int cb = 16 * (wave & 3);
 
+    if (wave >= 4) {
+        const int ptid = tid - 256;
+        // key side: 16 tokens x DK/4 groups of four key columns (the first DK/16 producer waves);
+        // slice side: thread x < 128 carries a piece of dout, 128 <= x < 256 a piece of v (token x/8 % 16,
+        // columns 8 (x % 8) .. of the slice)
+        // Every producer thread issues the same loads (threads without a role repeat another thread's), so that
+        // the number of loads in flight does not depend on the role; only the staging does.
+        const bool keys = wave - 4 < DK / 16;
+        const int kp = ptid % (DK * 4), e4 = kp >> 4, t = kp & 15;
+        const int st = (ptid & 127) >> 3, se8 = ptid & 7;
+        const bool is_dout = wave < 6, is_v = wave >= 6 && wave < 8;
+        const uint16_t* slice_src = ((ptid & 128) ? a.v : a.dout) + sbase + 8 * se8;
+        const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
+        producer_loop<PreVals>(
+            nb,
+            [&](int i, PreVals& p) {
+                const int t0 = (nb - 1 - i) * kTok;
+                const size_t row = ((size_t)b * T + min(t0 + t, T - 1)) * H + h;
+                if constexpr (VAR == SLA_GLA) p.ld = load8(a.ld + row * DK + 4 * e4);
+                p.kx = load8(a.k + row * DK + 4 * e4);
+                p.qx = load8(a.q + row * DK + 4 * e4);
+                p.gk = a.gk[row];
+                const size_t srow = ((size_t)b * T + min(t0 + st, T - 1)) * H + h;
+                p.sl = load16(slice_src + srow * DV);
+                p.gq = a.gq[srow];
+            },
+            [&](int i, const PreVals& pp, int which) {
+                unsigned char* buf = smem + which * L::bytes;
+                const int t0 = (nb - 1 - i) * kTok;
+                PreVals p;
+                {
+                    const bool ok = t0 + t < T, oks = t0 + st < T;
+                    p.ld = keep(pp.ld, ok); p.kx = keep(pp.kx, ok); p.qx = keep(pp.qx, ok);
+                    p.gk = ok ? pp.gk : 0.f;
+                    p.sl = keep(pp.sl, oks);
+                    p.gq = oks ? pp.gq : 0.f;
+                }
+                if (keys) {
+                    float c[4], tot[4];
+                    block_decay<VAR>(p.ld, head_step, t0 + t < T, c, tot);
+                    u2 qa, kd, kb;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        qa[j] = pack2(bf_lo(p.qx[j]) * ex2(c[2 * j]), bf_hi(p.qx[j]) * ex2(c[2 * j + 1]));
+                        kd[j] = pack2(bf_lo(p.kx[j]) * ex2(-c[2 * j]), bf_hi(p.kx[j]) * ex2(-c[2 * j + 1]));
+                        kb[j] = pack2(bf_lo(p.kx[j]) * ex2(tot[2 * j] - c[2 * j]),
+                                      bf_hi(p.kx[j]) * ex2(tot[2 * j + 1] - c[2 * j + 1]));
+                    }
+                    put_perm4<DK>((uint16_t*)(buf + L::oQA), t, e4, qa);
+                    put_perm4<DK>((uint16_t*)(buf + L::oKD), t, e4, kd);
+                    put_perm4<DK>((uint16_t*)(buf + L::oKB), t, e4, kb);
+                    put_T4((uint16_t*)(buf + L::oQAT), 4 * e4, t, qa);
+                    if (t == 0)
+                        *(f4*)((float*)(buf + L::oAT) + 4 * e4) = f4{ex2(tot[0]), ex2(tot[1]), ex2(tot[2]), ex2(tot[3])};
+                    if (e4 == 0) ((float*)(buf + L::oGK))[t] = p.gk;
+                }
+                if (is_dout) {
+                    u4 dy;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dy[j] = pack2(p.gq * bf_lo(p.sl[j]), p.gq * bf_hi(p.sl[j]));
+                    put_T((uint16_t*)(buf + L::oDYT), 8 * se8, st, dy);
+                } else if (is_v) {
+                    uint16_t* vs = (uint16_t*)(buf + L::oVS) + st * kFS + 8 * se8;
+                    *(u2*)vs = u2{p.sl[0], p.sl[1]};
+                    *(u2*)(vs + 4) = u2{p.sl[2], p.sl[3]};
+                }
+            });
+        return;
+    }
+
     f4 DS[DK / 16];  // rows d = 16 i + 4 g + (0..3), column n = sbase + cb + r
-    if (!producer) {
+#pragma unroll
+    for (int i = 0; i < DK / 16; ++i) {
+        DS[i] = f4{0.f, 0.f, 0.f, 0.f};
+        if (a.dsf) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) DS[i][j] = a.dsf[((size_t)bh * DK + 16 * i + 4 * g + j) * DV + sbase + cb + r];
+        }
+    }
+    block_barrier();
+    for (int blk = 0; blk < nb; ++blk) {
+        if (kExp == 1) {
+            block_barrier();
+            continue;
+        }
+        const unsigned char* buf = smem + (blk & 1) * L::bytes;
+        const int t0 = (nb - 1 - blk) * kTok;
+        const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
+        const uint16_t* KDp = (const uint16_t*)(buf + L::oKD);
+        const uint16_t* KBp = (const uint16_t*)(buf + L::oKB);
+        // Pq[t][j] = qa_t . kd_j, kept for j <= t
+        f4 Pq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < DK / 32; ++c) mma32(Pq, get_perm<DK>(QAp, r, g, c), get_perm<DK>(KDp, r, g, c));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (r > 4 * g + i) Pq[i] = 0.f;
+        const s4 fp = pack4(Pq);
+        // dv'^T[n][j] = sum_d dS[d][n] kb_j[d] + sum_t dy_t[n] Pq[t][j]
+        f4 Ys = {0.f, 0.f, 0.f, 0.f}, Yi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < DK / 32; ++c)
+            mma32(Ys, join(pack4(DS[2 * c]), pack4(DS[2 * c + 1])), get_perm<DK>(KBp, r, g, c));
+        const s4 fdy = get_T((const uint16_t*)(buf + L::oDYT), cb + r, g);
+        mma16(Yi, fdy, fp);
+        const u2 vx = *(const u2*)((const uint16_t*)(buf + L::oVS) + r * kFS + cb + 4 * g);
+        const float vf[4] = {bf_lo(vx[0]), bf_hi(vx[0]), bf_lo(vx[1]), bf_hi(vx[1])};
+        const float gk = ((const float*)(buf + L::oGK))[r];
+        float dvp[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dvp[i] = Ys[i] + Yi[i];
+        float part = vf[0] * dvp[0] + vf[1] * dvp[1] + vf[2] * dvp[2] + vf[3] * dvp[3];
+        part = reduce_groups(part);
+        const int tok = t0 + r;
+        if (tok < T) {
+            const size_t row = ((size_t)b * T + tok) * H + h;
+            if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.B * T * H) + row] = part;
+            *(u2*)(a.dv + row * DV + sbase + cb + 4 * g) =
+                u2{pack2(gk * dvp[0], gk * dvp[1]), pack2(gk * dvp[2], gk * dvp[3])};
+        }
+        // dS <- diag(A) dS + qa^T dy
+        const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
+        const float* AT = (const float*)(buf + L::oAT);
 #pragma unroll
         for (int i = 0; i < DK / 16; ++i) {
-            DS[i] = f4{0.f, 0.f, 0.f, 0.f};
-            if (a.dsf) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    DS[i][j] = a.dsf[((size_t)bh * DK + 16 * i + 4 * g + j) * DV + sbase + cb + r];
-            }
+            const f4 Ad = *(const f4*)(AT + 16 * i + 4 * g);
+            DS[i] = DS[i] * Ad;
+            mma16(DS[i], get_T(QAT, 16 * i + r, g), fdy);
         }
+        block_barrier();
     }
 
-    for (int it = 0; it <= nb; ++it) {
-        if (producer) {
-            if (it < nb) {
-                unsigned char* buf = smem + (it & 1) * L::bytes;
-                const int t0 = (nb - 1 - it) * kTok, ptid = tid - 256;
-                if (ptid < DK * 2) {  // 16 tokens x DK/8 groups of eight key columns
-                    const int e8 = ptid >> 4, t = ptid & 15, tok = t0 + t;
-                    const bool ok = tok < T;
-                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-                    float l[8];
-                    load_steps<VAR>(a, row, h, DK, 8 * e8, ok, l);
-                    const u4 kx = load16(a.k + row * DK + 8 * e8, ok);
-                    const u4 qx = load16(a.q + row * DK + 8 * e8, ok);
-                    float c[8], tot[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        c[i] = row_prefix(l[i]);
-                        tot[i] = row_last(c[i]);
-                    }
-                    u4 qa, kd, kb;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        qa[i] = pack2(bf_lo(qx[i]) * ex2(c[2 * i]), bf_hi(qx[i]) * ex2(c[2 * i + 1]));
-                        kd[i] = pack2(bf_lo(kx[i]) * ex2(-c[2 * i]), bf_hi(kx[i]) * ex2(-c[2 * i + 1]));
-                        kb[i] = pack2(bf_lo(kx[i]) * ex2(tot[2 * i] - c[2 * i]),
-                                      bf_hi(kx[i]) * ex2(tot[2 * i + 1] - c[2 * i + 1]));
-                    }
-                    put_perm<DK>((uint16_t*)(buf + L::oQA), t, e8, qa);
-                    put_perm<DK>((uint16_t*)(buf + L::oKD), t, e8, kd);
-                    put_perm<DK>((uint16_t*)(buf + L::oKB), t, e8, kb);
-                    put_T((uint16_t*)(buf + L::oQAT), 8 * e8, t, qa);
-                    if (t == 0) {
-                        float* at = (float*)(buf + L::oAT) + 8 * e8;
-                        *(f4*)at = f4{ex2(tot[0]), ex2(tot[1]), ex2(tot[2]), ex2(tot[3])};
-                        *(f4*)(at + 4) = f4{ex2(tot[4]), ex2(tot[5]), ex2(tot[6]), ex2(tot[7])};
-                    }
-                    if (e8 == 0) ((float*)(buf + L::oGK))[t] = ok ? a.gk[row] : 0.f;
-                }
-                {  // the 64-column slice of dout (gated) and of v: 128 chunks each
-                    const int x = ptid & 127, t = x >> 3, e8 = x & 7, tok = t0 + t;
-                    const bool ok = tok < T;
-                    const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
-                    if (ptid < 128) {
-                        const u4 dx = load16(a.dout + row * DV + sbase + 8 * e8, ok);
-                        const float gq = ok ? a.gq[row] : 0.f;
-                        u4 dy;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) dy[i] = pack2(gq * bf_lo(dx[i]), gq * bf_hi(dx[i]));
-                        put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
-                    } else {
-                        const u4 vx = load16(a.v + row * DV + sbase + 8 * e8, ok);
-                        uint16_t* vs = (uint16_t*)(buf + L::oVS) + t * kFS + 8 * e8;
-                        *(u2*)vs = u2{vx[0], vx[1]};
-                        *(u2*)(vs + 4) = u2{vx[2], vx[3]};
-                    }
-                }
-            }
-        } else if (it > 0) {
-            const int blk = it - 1;
-            const unsigned char* buf = smem + (blk & 1) * L::bytes;
-            const int t0 = (nb - 1 - blk) * kTok;
-            const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
-            const uint16_t* KDp = (const uint16_t*)(buf + L::oKD);
-            const uint16_t* KBp = (const uint16_t*)(buf + L::oKB);
-            // Pq[t][j] = qa_t . kd_j, kept for j <= t
-            f4 Pq = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < DK / 32; ++c) mma32(Pq, get_perm<DK>(QAp, r, g, c), get_perm<DK>(KDp, r, g, c));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (r > 4 * g + i) Pq[i] = 0.f;
-            const s4 fp = pack4(Pq);
-            // dv'^T[n][j] = sum_d dS[d][n] kb_j[d] + sum_t dy_t[n] Pq[t][j]
-            f4 Ys = {0.f, 0.f, 0.f, 0.f}, Yi = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < DK / 32; ++c)
-                mma32(Ys, join(pack4(DS[2 * c]), pack4(DS[2 * c + 1])), get_perm<DK>(KBp, r, g, c));
-            const s4 fdy = get_T((const uint16_t*)(buf + L::oDYT), cb + r, g);
-            mma16(Yi, fdy, fp);
-            const u2 vx = *(const u2*)((const uint16_t*)(buf + L::oVS) + r * kFS + cb + 4 * g);
-            const float vf[4] = {bf_lo(vx[0]), bf_hi(vx[0]), bf_lo(vx[1]), bf_hi(vx[1])};
-            const float gk = ((const float*)(buf + L::oGK))[r];
-            float dvp[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dvp[i] = Ys[i] + Yi[i];
-            float part = vf[0] * dvp[0] + vf[1] * dvp[1] + vf[2] * dvp[2] + vf[3] * dvp[3];
-            part = reduce_groups(part);
-            const int tok = t0 + r;
-            if (tok < T) {
-                const size_t row = ((size_t)b * T + tok) * H + h;
-                if (g == 0) a.part_k[((size_t)(slice * 4 + (wave & 3)) * a.B * T * H) + row] = part;
-                *(u2*)(a.dv + row * DV + sbase + cb + 4 * g) =
-                    u2{pack2(gk * dvp[0], gk * dvp[1]), pack2(gk * dvp[2], gk * dvp[3])};
-            }
-            // dS <- diag(A) dS + qa^T dy
-            const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
-            const float* AT = (const float*)(buf + L::oAT);
-#pragma unroll
-            for (int i = 0; i < DK / 16; ++i) {
-                const f4 Ad = *(const f4*)(AT + 16 * i + 4 * g);
-                DS[i] = DS[i] * Ad;
-                mma16(DS[i], get_T(QAT, 16 * i + r, g), fdy);
-            }
-        }
-        __syncthreads();
-    }
-
-    if (!producer && a.ds0) {
+    if (a.ds0) {
 #pragma unroll
         for (int i = 0; i < DK / 16; ++i)
 #pragma unroll
@@ -671,37 +814,60 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
 // ------------------------------------------------------------------------------------------------------------
 // Gates (Eq. 4) and their backward.
 // ------------------------------------------------------------------------------------------------------------
-__global__ void sla_bwd_gates_kernel(const float* ql, const float* kl, float* gq, float* gk, size_t rows, int H) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows) return;
+// One thread per (token, head); the 256-thread block covers whole tokens (256 / H of them) and the sums over the
+// heads of a token go through LDS.
+constexpr int kEwThreads = 256;
+
+__global__ __launch_bounds__(kEwThreads) void sla_bwd_gates_kernel(const float* ql, const float* kl, float* gq,
+                                                                    float* gk, size_t rows, int H) {
+    __shared__ float sx[kEwThreads];
+    const int per = kEwThreads / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
+    const size_t row = (size_t)blockIdx.x * per + lr;
+    const bool ok = lr < per && row < rows;
     for (int which = 0; which < 2; ++which) {
         const float* x = which ? kl : ql;
         float* g = which ? gk : gq;
-        if (!x) {
-            for (int h = 0; h < H; ++h) g[i * H + h] = 1.f;
+        if (!x) {  // uniform: G = 1
+            if (ok) g[row * H + h] = 1.f;
             continue;
         }
+        const float v = ok ? x[row * H + h] : 0.f;
+        sx[tid] = v;
+        __syncthreads();
         float m = -INFINITY;
-        for (int h = 0; h < H; ++h) m = fmaxf(m, x[i * H + h]);
+        if (ok)
+            for (int i = 0; i < H; ++i) m = fmaxf(m, sx[lr * H + i]);
+        __syncthreads();
+        const float e = ok ? ex2((v - m) * kLog2e) : 0.f;
+        sx[tid] = e;
+        __syncthreads();
         float s = 0.f;
-        for (int h = 0; h < H; ++h) s += ex2((x[i * H + h] - m) * kLog2e);
-        const float inv = 1.f / s;
-        for (int h = 0; h < H; ++h) g[i * H + h] = ex2((x[i * H + h] - m) * kLog2e) * inv;
+        if (ok)
+            for (int i = 0; i < H; ++i) s += sx[lr * H + i];
+        if (ok) g[row * H + h] = e / s;
+        __syncthreads();
     }
 }
 
 // dlogits = G * (dG - sum_h G dG), dG summed over its partial planes
-__global__ void sla_bwd_logits_kernel(const float* g, const float* part, int planes, float* dl, size_t rows, int H) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows) return;
-    float dot = 0.f;
-    for (int h = 0; h < H; ++h) {
-        float dg = 0.f;
-        for (int p = 0; p < planes; ++p) dg += part[(size_t)p * rows * H + i * H + h];
-        dl[i * H + h] = dg;
-        dot += g[i * H + h] * dg;
+__global__ __launch_bounds__(kEwThreads) void sla_bwd_logits_kernel(const float* g, const float* part, int planes,
+                                                                     float* dl, size_t rows, int H) {
+    __shared__ float sx[kEwThreads];
+    const int per = kEwThreads / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
+    const size_t row = (size_t)blockIdx.x * per + lr;
+    const bool ok = lr < per && row < rows;
+    float dg = 0.f, gv = 0.f;
+    if (ok) {
+        for (int p = 0; p < planes; ++p) dg += part[(size_t)p * rows * H + row * H + h];
+        gv = g[row * H + h];
     }
-    for (int h = 0; h < H; ++h) dl[i * H + h] = g[i * H + h] * (dl[i * H + h] - dot);
+    sx[tid] = gv * dg;
+    __syncthreads();
+    if (ok) {
+        float dot = 0.f;
+        for (int i = 0; i < H; ++i) dot += sx[lr * H + i];
+        dl[row * H + h] = gv * (dg - dot);
+    }
 }
 
 size_t round4(size_t n) { return (n + 3) & ~(size_t)3; }
@@ -785,7 +951,7 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
     a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.dld = (uint16_t*)dld; a.ds0 = ds0;
     a.B = p.B; a.T = p.T; a.H = p.H;
 
-    const unsigned eb = 256, eg = (unsigned)((rows + eb - 1) / eb);
+    const unsigned eb = kEwThreads, per = eb / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
     if (rows > 0) {
         hipLaunchKernelGGL(sla_bwd_gates_kernel, dim3(eg), dim3(eb), 0, stream, ql, kl, gq, gk, rows, p.H);
         if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
