@@ -30,6 +30,8 @@ MEASURED_TRAFFIC_BYTES = {
     "gla_long": 4.063e9,      # same file
     "decode_gla": 135.7e6,    # profiles/sla_decode_bf16.md
     "decode_gdn": 135.7e6,    # same file
+    "gla_train:backward": 1.628e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
+    "retnet_train:backward": 1.055e9,  # same file
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 BLOCK = 16                      # tokens per state step in the kernels (for the causal flop count)
@@ -67,6 +69,129 @@ def decode_bytes(w) -> int:
     elif w.variant == 2:
         per_head += 8
     return w.B * w.H * per_head
+
+
+def backward_bytes(w) -> int:
+    """One read of every input of sla_backward (q, k, v, d_out, logits, GLA decay) and one write of every
+    gradient (dq, dk, dv, logit gradients, GLA decay gradient)."""
+    es = 2
+    per = (2 * w.dk + 2 * w.dv) * es + 8 + (2 * w.dk + w.dv) * es + 8
+    if w.variant == 1:
+        per += 2 * w.dk * es
+    return w.B * w.T * w.H * per
+
+
+def bench_backward(args, w, sla, si, torch, np) -> int:
+    """--backward: a step is one sla_backward call (gate evaluation, the dq / dv / dk sweeps, softmax backward)
+    over the workload's batch, inputs and cotangents resident in HBM."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import rel_err, to_device
+
+    if w.variant == 2 or w.dtype != "bf16":
+        print("bench.py: --backward covers the bf16 RetNet and GLA workloads", file=sys.stderr)
+        return 2
+    d = si.generate(w)
+    cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
+    g, tdt = to_device(d, w.dtype, w.variant)
+    dev = torch.device("cuda:0")
+    dout = torch.from_numpy(cot["d_out"]).to(torch.bfloat16).to(dev)
+    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 1)
+    need = sla.sla_backward_workspace_bytes(params)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    gr = {
+        "dq": torch.empty_like(g["q"]), "dk": torch.empty_like(g["k"]), "dv": torch.empty_like(g["v"]),
+        "dq_logits": torch.empty_like(g["q_logits"]), "dk_logits": torch.empty_like(g["k_logits"]),
+        "dlog_decay": torch.empty_like(g["log_decay"]) if w.variant == 1 else None,
+    }
+    ptr = lambda t: None if t is None else t.data_ptr()
+    raw = (ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(g["q_logits"]), ptr(g["k_logits"]), ptr(g["log_decay"]), None,
+           ptr(dout), None, ptr(gr["dq"]), ptr(gr["dk"]), ptr(gr["dv"]), ptr(gr["dq_logits"]), ptr(gr["dk_logits"]),
+           ptr(gr["dlog_decay"]), None, ptr(ws), need, torch.cuda.current_stream(dev).cuda_stream)
+
+    def step():
+        rc = sla.sla_backward(params, *raw)
+        if rc != 0:
+            raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    for _ in range(args.settle + args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_call_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    call_ms = float(np.mean(per_call_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    abytes = backward_bytes(w)
+    achieved = abytes / (call_ms * 1e-3) / 1e9
+    result = {
+        "metric": f"tokens/sec SLA-{si.VARIANT_NAMES[w.variant].upper()} chunked bwd",
+        "value": w.tokens() / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "settle_launches": args.settle,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: backward of SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} "
+                        f"dk={w.dk} dv={w.dv} bf16 in/out, dual head-softmax gates, no state cotangents",
+            "kernel": "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
+                      "sla_bwd_logits_kernel x2",
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name + ":backward"),
+            "kernel_us": call_ms * 1e3,
+            "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
+            "algorithmic_bytes": abytes,
+            "note": "whole call (six launches); achieved = algorithmic bytes / call time",
+        },
+    }
+    if not args.no_cpu_baseline or not args.no_parity:
+        from oracle import sla_backward as ob
+
+        rows, Ts = min(w.B, 2), w.T  # a bounded sample: two batch rows (about 25 s for the headline shape)
+        t0 = time.perf_counter()
+        ob.backward(w.variant, d["q"][:rows, :Ts], d["k"][:rows, :Ts], d["v"][:rows, :Ts], d["q_logits"][:rows, :Ts],
+                    d["k_logits"][:rows, :Ts], d["log_decay"] if w.variant == 0 else d["log_decay"][:rows, :Ts],
+                    cot["d_out"][:rows, :Ts])
+        cpu_s = time.perf_counter() - t0
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {
+                "value": rows * Ts / cpu_s,
+                "unit": "tokens/s",
+                "cores": 1,
+                "kind": "oracle",
+                "sample": f"gradient oracle (numpy fp64) on {rows} batch row(s), {Ts} tokens, all {w.H} heads, {cpu_s:.2f} s wall",
+            }
+        if not args.no_parity:
+            ref = ob.backward(w.variant, d["q"][:1], d["k"][:1], d["v"][:1], d["q_logits"][:1], d["k_logits"][:1],
+                              d["log_decay"] if w.variant == 0 else d["log_decay"][:1], cot["d_out"][:1])
+            step()
+            torch.cuda.synchronize()
+            f64 = lambda t: t[:1].to(torch.float32).cpu().numpy().astype(np.float64)
+            names = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_logits": "dq_logits", "dk_logits": "dk_logits"}
+            if w.variant == 1:
+                names["dlog_decay"] = "dlog_decay"
+            result["parity"] = {n + "_rel_err": rel_err(f64(gr[n]), ref[rn]) for n, rn in names.items()}
+            result["parity"]["definition"] = "max|x - oracle| / max|oracle| per gradient tensor, batch row 0"
+    print(json.dumps(result), flush=True)
+    return 0
 
 
 def bench_decode(args, w, sla, si, torch, np) -> int:
@@ -211,6 +336,8 @@ def main() -> int:
     ap.add_argument("--graph", type=int, default=50,
                     help="decode workloads only: steps per captured HIP graph (0 = plain launches).  A decode step "
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
+    ap.add_argument("--backward", action="store_true",
+                    help="time sla_backward (RetNet / GLA training workloads) instead of the forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     args = ap.parse_args()
@@ -232,6 +359,8 @@ def main() -> int:
     w = si.workload(args.workload)
     if w.name in si.DECODE_WORKLOAD_NAMES:
         return bench_decode(args, w, sla, si, torch, np)
+    if args.backward:
+        return bench_backward(args, w, sla, si, torch, np)
     d = si.generate(w)
 
     sys.path.insert(0, os.path.join(ROOT, "tests"))

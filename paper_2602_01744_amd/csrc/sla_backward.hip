@@ -24,8 +24,9 @@
 //       dS <- diag(A) dS + qa^T (G^Q dout)
 //   R2: dk'_j = (1/p_j) * sum_t G^Q_t P'[t][j] qa_t + (A/p_j) * (v_j dS^T);   dS^T <- dS^T A + (G^Q dout)^T qa
 // Every workgroup has four consumer waves (16 columns of the slice each, their state tile in registers) and eight
-// producer waves that stage the next block's operands in LDS while the consumers work on the current one; the two
-// halves meet at one barrier per block.
+// producer waves in four teams of two; team i stages blocks i, i + 4, ... into slot i of a four-slot LDS ring, so
+// four blocks are being staged while the consumers work through the ring.  No barrier after start-up: the
+// hand-over is two counters per slot.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -131,12 +132,6 @@ __device__ __forceinline__ void put_perm(uint16_t* tile, int t, int e8, u4 x) {
     *(u2*)(row + 8 * g0) = u2{x[0], x[1]};
     *(u2*)(row + 8 * (g0 + 1)) = u2{x[2], x[3]};
 }
-// the same tile, four adjacent columns 4 e4 .. 4 e4 + 3 of one token
-template <int KD>
-__device__ __forceinline__ void put_perm4(uint16_t* tile, int t, int e4, u2 x) {
-    const int S = e4 >> 3, u = (e4 >> 2) & 1, g = e4 & 3;
-    *(u2*)(tile + t * (KD + 8) + 32 * S + 8 * g + 4 * u) = x;
-}
 template <int KD>
 __device__ __forceinline__ s8 get_perm(const uint16_t* tile, int r, int g, int c) {
     return *(const s8*)(tile + r * (KD + 8) + 32 * c + 8 * g);
@@ -145,13 +140,6 @@ __device__ __forceinline__ s8 get_perm(const uint16_t* tile, int r, int g, int c
 __device__ __forceinline__ void put_T(uint16_t* tile, int col0, int t, u4 x) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        tile[(col0 + 2 * i) * kTS + t] = (uint16_t)(x[i] & 0xffffu);
-        tile[(col0 + 2 * i + 1) * kTS + t] = (uint16_t)(x[i] >> 16);
-    }
-}
-__device__ __forceinline__ void put_T4(uint16_t* tile, int col0, int t, u2 x) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
         tile[(col0 + 2 * i) * kTS + t] = (uint16_t)(x[i] & 0xffffu);
         tile[(col0 + 2 * i + 1) * kTS + t] = (uint16_t)(x[i] >> 16);
     }
@@ -165,6 +153,14 @@ __device__ __forceinline__ u2 load8(const uint16_t* p) { return *(const u2*)p; }
 __device__ __forceinline__ u4 keep(u4 x, bool ok) { return u4{ok ? x[0] : 0u, ok ? x[1] : 0u, ok ? x[2] : 0u, ok ? x[3] : 0u}; }
 __device__ __forceinline__ u2 keep(u2 x, bool ok) { return u2{ok ? x[0] : 0u, ok ? x[1] : 0u}; }
 
+// Workgroups are dealt to the eight XCDs round-robin by blockIdx, and each XCD has its own L2.  The slices of one
+// (batch, head) read the same dout / v (or q / k / decay) rows, so they are given consecutive places on ONE XCD:
+// the grid is padded to a multiple of eight and place p of XCD x is logical workgroup x * (grid / 8) + p.
+__device__ __forceinline__ int logical_workgroup() {
+    const int per = gridDim.x >> 3;
+    return (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+}
+
 // Sum over the four 16-lane rows of a wave, returned in every lane: two register swaps (odd rows against even
 // rows, then the upper half against the lower half) instead of a trip through LDS.
 __device__ __forceinline__ float reduce_groups(float x) {
@@ -175,74 +171,118 @@ __device__ __forceinline__ float reduce_groups(float x) {
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// One barrier per block: the producers fill buffer (i & 1) with block i while the consumers work on block i - 1.
-// Both halves of the workgroup execute the same number of barriers (nb + 1).  The barrier waits for LDS traffic
-// only, so the producers' global loads for later blocks stay in flight across it.
-__device__ __forceinline__ void block_barrier() { __syncthreads(); }
+// ------------------------------------------------------------------------------------------------------------
+// Hand-over between producer and consumer waves: a ring of kSlots LDS slots, one 16-token block each, and two
+// counters per slot.  Block I of a sweep lives in slot I % kSlots and is staged by producer team I % kSlots (two
+// waves that fill disjoint tiles of the slot).  ready[s] counts member-fills of slot s (two per block), done[s]
+// the consumer waves that have finished a block in it (four per block); both only grow, so a waiter compares with
+// the value its own block index implies.  The LDS operations of a wave complete in order: once lgkmcnt has
+// drained, what the wave wrote is in LDS and what it read is in registers, and the counter update behind the
+// drain is ordered after them.  Every wait is bounded: a block depends only on earlier blocks, so the hand-over
+// cannot deadlock, and a wait that exhausts its budget lets the wave go on rather than hang.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int kSlots = 4;
+constexpr int kTeamWaves = 2;
+constexpr int kConsumers = 4;
+constexpr int kSpinLimit = 1 << 22;
+typedef __attribute__((address_space(3))) int lds_int;
 
-// Developer switch for timing one half of a workgroup alone (results are then meaningless): 1 = consumers only
-// pass the barriers, 2 = producers only issue their loads.
+__device__ __forceinline__ void flag_wait(const lds_int* f, int target) {
+    int spin = 0;
+    while (*(const volatile lds_int*)f < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
+    asm volatile("" ::: "memory");
+}
+// All 64 lanes active on entry; drains the wave's LDS traffic, then lane 0 alone adds one.
+__device__ __forceinline__ void flag_signal(lds_int* f) {
+    const uint32_t addr = (uint32_t)(uintptr_t)f;
+    const int one = 1;
+    asm volatile(
+        "s_waitcnt lgkmcnt(0)\n"
+        "s_mov_b64 exec, 1\n"
+        "ds_add_u32 %0, %1\n"
+        "s_mov_b64 exec, -1"
+        :
+        : "v"(addr), "v"(one)
+        : "memory");
+}
+
+// Developer switch for timing one half of a workgroup alone (results are then meaningless): 1 = the consumers
+// only pass the hand-over, 2 = the producers only load and signal.
 #ifndef SLA_BWD_EXP
 #define SLA_BWD_EXP 0
 #endif
 constexpr int kExp = SLA_BWD_EXP;
 
-constexpr int kAhead = 3;  // blocks whose global loads a producer has in flight
-
-// Runs issue(block, set) kAhead blocks ahead of stage(block, set, buffer).  The register sets are separate named
-// objects, and every step issues exactly one set of loads (past the end it re-reads the last block): the number
-// of loads in flight behind the set being staged is then the same on every path, which is what lets the wait in
-// front of stage() leave the newer sets in flight.
-template <typename Pre, typename Issue, typename Stage>
-__device__ __forceinline__ void producer_loop(int nb, Issue issue, Stage stage) {
-    static_assert(kAhead == 3, "three register sets are written out below");
-    if (nb == 0) {
-        block_barrier();
-        return;
-    }
-    Pre p0, p1, p2;
-    issue(0, p0);
-    issue(min(1, nb - 1), p1);
-    issue(min(2, nb - 1), p2);
-    int it = 0;
-    while (true) {
-        if (kExp != 2) stage(it, p0, it & 1);
-        issue(min(it + kAhead, nb - 1), p0);
-        block_barrier();
-        if (++it == nb) break;
-        if (kExp != 2) stage(it, p1, it & 1);
-        issue(min(it + kAhead, nb - 1), p1);
-        block_barrier();
-        if (++it == nb) break;
-        if (kExp != 2) stage(it, p2, it & 1);
-        issue(min(it + kAhead, nb - 1), p2);
-        block_barrier();
-        if (++it == nb) break;
-    }
-    block_barrier();
+struct Ring {
+    lds_int* ready;
+    lds_int* done;
+};
+// The counters sit behind the slots; zeroed by the first eight threads before anyone uses them.
+__device__ __forceinline__ Ring ring_init(unsigned char* smem, int slot_bytes, int tid) {
+    lds_int* f = (lds_int*)(smem + kSlots * slot_bytes);
+    if (tid < 2 * kSlots) f[tid] = 0;
+    __syncthreads();
+    return Ring{f, f + kSlots};
 }
 
-// What a decay-side producer thread holds for one token and eight key columns; a copy-side thread holds up to
-// four 16-byte pieces of two tensors.
-struct PreKeys {
-    u2 ld, kx, qx;
+// One member wave of a producer team: load(block, regs) issues the global loads of a block, stage(block, regs,
+// slot) turns them into LDS tiles.  Two register sets: the loads of the team's next two blocks are in flight while
+// a block is staged, and every step issues exactly one set of loads (past the end it re-reads the last block), so
+// the wait in front of stage() leaves the newer set in flight on every path.
+template <typename Pre, typename Load, typename Stage>
+__device__ __forceinline__ void producer_run(const Ring& ring, unsigned char* smem, int slot_bytes, int team, int nb,
+                                             Load load, Stage stage) {
+    if (team >= nb) return;
+    Pre ra, rb;
+    load(team, ra);
+    load(min(team + kSlots, nb - 1), rb);
+    int I = team, use = 0;
+    while (true) {
+        flag_wait(ring.done + team, kConsumers * use);  // the consumers have left the block that was here
+        if (kExp != 2) stage(I, ra, smem + team * slot_bytes);
+        load(min(I + 2 * kSlots, nb - 1), ra);
+        flag_signal(ring.ready + team);
+        I += kSlots, ++use;
+        if (I >= nb) break;
+        flag_wait(ring.done + team, kConsumers * use);
+        if (kExp != 2) stage(I, rb, smem + team * slot_bytes);
+        load(min(I + 2 * kSlots, nb - 1), rb);
+        flag_signal(ring.ready + team);
+        I += kSlots, ++use;
+        if (I >= nb) break;
+    }
+}
+
+__device__ __forceinline__ void consumer_acquire(const Ring& ring, int I) {
+    flag_wait(ring.ready + (I & (kSlots - 1)), kTeamWaves * (I / kSlots + 1));
+}
+__device__ __forceinline__ void consumer_release(const Ring& ring, int I) { flag_signal(ring.done + (I & (kSlots - 1))); }
+
+// Producer loads are unconditional (tokens past the end read the last token's row) and are zeroed when they are
+// staged, so no load sits under a lane mask.
+template <int N>
+struct PreKeys {  // N groups of eight key columns of one token: decay steps, keys, queries, and the gates
+    u4 ld[N], kx[N], qx[N];
     float gq, gk;
 };
-template <int R>
-struct PreRows {
-    u4 a[R], b[R];
-    float gq[R];
+struct PreKeysE : PreKeys<2> {  // ... and the fp32 q * dq of the same 16 columns (dk sweep, GLA)
+    f4 e[4];
+};
+template <int N>
+struct PreRows {  // N 16-byte pieces of dout and of v
+    u4 a[N], b[N];
+    float gq[N];
 };
 
-// Inclusive running sums c[i] of the log2-domain decay steps of four key columns over the 16 tokens of the block
+// Inclusive running sums c[i] of the log2-domain decay steps of eight key columns over the 16 tokens of the block
 // (token = lane % 16), and their totals.
 template <int VAR>
-__device__ __forceinline__ void block_decay(const u2& ldx, float head_step, bool ok, float* c, float* tot) {
+__device__ __forceinline__ void block_decay(const u4& ldx, float head_step, bool ok, float* c, float* tot) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 8; ++i) {
         float l;
         if constexpr (VAR == SLA_GLA)
-            l = ((i & 1) ? bf_hi(ldx[i >> 1]) : bf_lo(ldx[i >> 1])) * kLog2e;  // zero outside the sequence
+            l = bf_at(ldx, i) * kLog2e;  // zero outside the sequence
         else
             l = ok ? head_step : 0.f;
         c[i] = row_prefix(l);
@@ -265,9 +305,11 @@ struct SmemF {
     static constexpr int oQS = oTOT + kCols * 4;
     static constexpr int oGQ = oQS + kTok * kFS * 2;
     static constexpr int bytes = oGQ + kTok * 4;
+    static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
     static_assert(oV % 16 == 0 && oVT % 16 == 0 && oKDT % 16 == 0 && oCUM % 16 == 0 && oTOT % 16 == 0 &&
                       oQS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
+    static_assert(total <= 160 * 1024, "the ring fits the LDS of a compute unit");
 };
 
 template <int VAR, int DK, int DV>
@@ -275,86 +317,99 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     typedef SmemF<DV> L;
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NSL = DK / kCols;
-    constexpr int R = (DV / 8 * kTok + 255) / 256;  // 16-byte pieces of dout (and of v) per copy thread
+    constexpr int R = DV / 32;  // 16-byte pieces of dout (and of v) per lane of the copy wave
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
     const int r = lane & 15, g = lane >> 4;
-    const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
+    const int wg = logical_workgroup();
+    if (wg >= a.B * a.H * NSL) return;
+    const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
     const int T = a.T, H = a.H;
     const int nb = (T + kTok - 1) / kTok;
-    const int cb = 16 * (wave & 3);
+    const Ring ring = ring_init(smem, L::bytes, tid);
 
-    if (wave >= 4) {
-        const int ptid = tid - 256;
-        if (wave < 8) {  // decay, keys and queries of the slice: token t = lane % 16, four columns
-            const int e4 = ptid >> 4, t = ptid & 15, d0 = sbase + 4 * e4;
+    if (wave >= kConsumers) {
+        const int team = (wave - kConsumers) >> 1;
+        if (((wave - kConsumers) & 1) == 0) {
+            // decay, keys and queries of the slice: token t = lane % 16, columns 16 (lane / 16) ... + 15
+            const int t = r, d0 = sbase + 16 * g;
             const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
-            producer_loop<PreKeys>(
-                nb,
-                [&](int blk, PreKeys& p) {
-                    const int tok = min(blk * kTok + t, T - 1);
-                    const size_t row = ((size_t)b * T + tok) * H + h;
-                    if constexpr (VAR == SLA_GLA) p.ld = load8(a.ld + row * DK + d0);
-                    p.kx = load8(a.k + row * DK + d0);
-                    p.qx = load8(a.q + row * DK + d0);
+            producer_run<PreKeys<2>>(
+                ring, smem, L::bytes, team, nb,
+                [&](int blk, PreKeys<2>& p) {
+                    const size_t row = ((size_t)b * T + min(blk * kTok + t, T - 1)) * H + h;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
+                        p.kx[j] = load16(a.k + row * DK + d0 + 8 * j);
+                        p.qx[j] = load16(a.q + row * DK + d0 + 8 * j);
+                    }
                     p.gk = a.gk[row];
                     p.gq = a.gq[row];
                 },
-                [&](int blk, const PreKeys& pp, int which) {
-                    unsigned char* buf = smem + which * L::bytes;
+                [&](int blk, const PreKeys<2>& p, unsigned char* buf) {
                     const bool ok = blk * kTok + t < T;
-                    PreKeys p;
-                    p.ld = keep(pp.ld, ok); p.kx = keep(pp.kx, ok); p.qx = keep(pp.qx, ok);
-                    p.gk = ok ? pp.gk : 0.f; p.gq = ok ? pp.gq : 0.f;
-                    float c[4], tot[4];
-                    block_decay<VAR>(p.ld, head_step, ok, c, tot);
-                    *(f4*)((float*)(buf + L::oCUM) + t * kFS + 4 * e4) = f4{c[0], c[1], c[2], c[3]};
-                    if (t == 0) *(f4*)((float*)(buf + L::oTOT) + 4 * e4) = f4{tot[0], tot[1], tot[2], tot[3]};
-                    u2 kd, kb;
+                    const float gk = ok ? p.gk : 0.f;
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const float k0 = bf_lo(p.kx[i]) * p.gk, k1 = bf_hi(p.kx[i]) * p.gk;
-                        kd[i] = pack2(k0 * ex2(-c[2 * i]), k1 * ex2(-c[2 * i + 1]));
-                        kb[i] = pack2(k0 * ex2(tot[2 * i] - c[2 * i]), k1 * ex2(tot[2 * i + 1] - c[2 * i + 1]));
+                    for (int j = 0; j < 2; ++j) {
+                        const int c0 = 16 * g + 8 * j;
+                        const u4 kx = keep(p.kx[j], ok);
+                        float c[8], tot[8];
+                        block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
+                        float* cum = (float*)(buf + L::oCUM) + t * kFS + c0;
+                        *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
+                        *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
+                        if (t == 0) {
+                            float* tt = (float*)(buf + L::oTOT) + c0;
+                            *(f4*)tt = f4{tot[0], tot[1], tot[2], tot[3]};
+                            *(f4*)(tt + 4) = f4{tot[4], tot[5], tot[6], tot[7]};
+                        }
+                        u4 kd, kb;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float k0 = bf_lo(kx[i]) * gk, k1 = bf_hi(kx[i]) * gk;
+                            kd[i] = pack2(k0 * ex2(-c[2 * i]), k1 * ex2(-c[2 * i + 1]));
+                            kb[i] = pack2(k0 * ex2(tot[2 * i] - c[2 * i]), k1 * ex2(tot[2 * i + 1] - c[2 * i + 1]));
+                        }
+                        put_T((uint16_t*)(buf + L::oKDT), c0, t, kd);
+                        put_T((uint16_t*)(buf + L::oKBT), c0, t, kb);
+                        const u4 qx = keep(p.qx[j], ok);
+                        uint16_t* qs = (uint16_t*)(buf + L::oQS) + t * kFS + c0;
+                        *(u2*)qs = u2{qx[0], qx[1]};
+                        *(u2*)(qs + 4) = u2{qx[2], qx[3]};
                     }
-                    put_T4((uint16_t*)(buf + L::oKDT), 4 * e4, t, kd);
-                    put_T4((uint16_t*)(buf + L::oKBT), 4 * e4, t, kb);
-                    *(u2*)((uint16_t*)(buf + L::oQS) + t * kFS + 4 * e4) = p.qx;
-                    if (e4 == 0) ((float*)(buf + L::oGQ))[t] = p.gq;
+                    if (g == 0) ((float*)(buf + L::oGQ))[t] = ok ? p.gq : 0.f;
                 });
         } else {  // dout and v, all value columns
-            const int x = ptid - 256;
-            producer_loop<PreRows<R>>(
-                nb,
+            producer_run<PreRows<R>>(
+                ring, smem, L::bytes, team, nb,
                 [&](int blk, PreRows<R>& p) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = (x + 256 * rep) % (kTok * DV / 8), t = c / (DV / 8), e8 = c % (DV / 8);
-                        const int tok = min(blk * kTok + t, T - 1);
-                        const size_t row = ((size_t)b * T + tok) * H + h;
+                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const size_t row = ((size_t)b * T + min(blk * kTok + t, T - 1)) * H + h;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
                     }
                 },
-                [&](int blk, const PreRows<R>& p, int which) {
-                    unsigned char* buf = smem + which * L::bytes;
+                [&](int blk, const PreRows<R>& p, unsigned char* buf) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = x + 256 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
-                        if (c < kTok * DV / 8) {
-                            const bool ok = blk * kTok + t < T;
-                            const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
-                            put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
-                            put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
-                            put_T((uint16_t*)(buf + L::oVT), 8 * e8, t, vx);
-                        }
+                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const bool ok = blk * kTok + t < T;
+                        const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
+                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                        put_T((uint16_t*)(buf + L::oVT), 8 * e8, t, vx);
                     }
                 });
         }
         return;
     }
 
+    const int cb = 16 * wave;
+    __builtin_amdgcn_s_setprio(2);  // the state recurrence is the serial part: let it issue first
     f4 ST[DV / 16];
 #pragma unroll
     for (int i = 0; i < DV / 16; ++i) {
@@ -363,13 +418,13 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
         else
             ST[i] = f4{0.f, 0.f, 0.f, 0.f};
     }
-    block_barrier();
     for (int blk = 0; blk < nb; ++blk) {
+        consumer_acquire(ring, blk);
         if (kExp == 1) {
-            block_barrier();
+            consumer_release(ring, blk);
             continue;
         }
-        const unsigned char* buf = smem + (blk & 1) * L::bytes;
+        const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = blk * kTok;
         const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
         const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
@@ -391,6 +446,13 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
         const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
         const u2 qx = *(const u2*)((const uint16_t*)(buf + L::oQS) + r * kFS + cb + 4 * g);
         const float gq = ((const float*)(buf + L::oGQ))[r];
+        const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
+        const s4 fkb = get_T((const uint16_t*)(buf + L::oKBT), cb + r, g);
+        const uint16_t* VT = (const uint16_t*)(buf + L::oVT);
+        s4 fvt[DV / 16];
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) fvt[i] = get_T(VT, 16 * i + r, g);
+        consumer_release(ring, blk);  // every operand of the block is in registers
         float dqp[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * ex2(cum[i]);
@@ -410,15 +472,11 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
                     f4{qf[0] * dqv[0], qf[1] * dqv[1], qf[2] * dqv[2], qf[3] * dqv[3]};
         }
         // S^T <- S^T A + v^T kb'
-        const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
-        const s4 fkb = get_T((const uint16_t*)(buf + L::oKBT), cb + r, g);
-        const uint16_t* VT = (const uint16_t*)(buf + L::oVT);
 #pragma unroll
         for (int i = 0; i < DV / 16; ++i) {
             ST[i] = ST[i] * Ad;
-            mma16(ST[i], get_T(VT, 16 * i + r, g), fkb);
+            mma16(ST[i], fvt[i], fkb);
         }
-        block_barrier();
     }
 
     if constexpr (VAR == SLA_GLA) {
@@ -444,15 +502,17 @@ struct SmemK {
     static constexpr int oV = oDO + kTok * (DV + 8) * 2;
     static constexpr int oDYT = oV + kTok * (DV + 8) * 2;
     static constexpr int oQAT = oDYT + DV * kTS * 2;
-    static constexpr int oCUM = oQAT + kCols * kTS * 2;
-    static constexpr int oTOT = oCUM + kTok * kFS * 4;
-    static constexpr int oKS = oTOT + kCols * 4;
+    static constexpr int oCUM = oQAT + kCols * kTS * 2;   // running log2-decay; its last row is the block total
+    static constexpr int oQDQ = oCUM + kTok * kFS * 4;    // q * dq in fp32 (GLA), from the dq sweep
+    static constexpr int oKS = oQDQ + kTok * kFS * 4;
     static constexpr int oGQ = oKS + kTok * kFS * 2;
     static constexpr int oGK = oGQ + kTok * 4;
     static constexpr int bytes = oGK + kTok * 4;
-    static_assert(oV % 16 == 0 && oDYT % 16 == 0 && oQAT % 16 == 0 && oCUM % 16 == 0 && oTOT % 16 == 0 &&
+    static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
+    static_assert(oV % 16 == 0 && oDYT % 16 == 0 && oQAT % 16 == 0 && oCUM % 16 == 0 && oQDQ % 16 == 0 &&
                       oKS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
+    static_assert(total <= 160 * 1024, "the ring fits the LDS of a compute unit");
 };
 
 template <int VAR, int DK, int DV>
@@ -460,90 +520,104 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     typedef SmemK<DV> L;
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NSL = DK / kCols;
-    constexpr int R = (DV / 8 * kTok + 255) / 256;
+    constexpr int R = DV / 32;
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
-    const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
+    const int wg = logical_workgroup();
+    if (wg >= a.B * a.H * NSL) return;
+    const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
     const int T = a.T, H = a.H;
     const int nb = (T + kTok - 1) / kTok;
-    const int cb = 16 * (wave & 3);
+    const Ring ring = ring_init(smem, L::bytes, tid);
 
-    if (wave >= 4) {  // block number i of the sweep covers tokens (nb - 1 - i) * 16 ...
-        const int ptid = tid - 256;
-        if (wave < 8) {
-            const int e4 = ptid >> 4, t = ptid & 15, d0 = sbase + 4 * e4;
+    if (wave >= kConsumers) {  // block number I of the sweep covers tokens (nb - 1 - I) * 16 ...
+        const int team = (wave - kConsumers) >> 1;
+        if (((wave - kConsumers) & 1) == 0) {
+            const int t = r, d0 = sbase + 16 * g;
             const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
-            producer_loop<PreKeys>(
-                nb,
-                [&](int i, PreKeys& p) {
-                    const int tok = min((nb - 1 - i) * kTok + t, T - 1);
-                    const size_t row = ((size_t)b * T + tok) * H + h;
-                    if constexpr (VAR == SLA_GLA) p.ld = load8(a.ld + row * DK + d0);
-                    p.kx = load8(a.k + row * DK + d0);
-                    p.qx = load8(a.q + row * DK + d0);
+            producer_run<PreKeysE>(
+                ring, smem, L::bytes, team, nb,
+                [&](int I, PreKeysE& p) {
+                    const size_t row = ((size_t)b * T + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
+                        p.kx[j] = load16(a.k + row * DK + d0 + 8 * j);
+                        p.qx[j] = load16(a.q + row * DK + d0 + 8 * j);
+                    }
+                    if constexpr (VAR == SLA_GLA) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) p.e[j] = *(const f4*)(a.qdq + row * DK + d0 + 4 * j);
+                    }
                     p.gk = a.gk[row];
                     p.gq = a.gq[row];
                 },
-                [&](int i, const PreKeys& pp, int which) {
-                    unsigned char* buf = smem + which * L::bytes;
-                    const bool ok = (nb - 1 - i) * kTok + t < T;
-                    PreKeys p;
-                    p.ld = keep(pp.ld, ok); p.kx = keep(pp.kx, ok); p.qx = keep(pp.qx, ok);
-                    p.gk = ok ? pp.gk : 0.f; p.gq = ok ? pp.gq : 0.f;
-                    float c[4], tot[4];
-                    block_decay<VAR>(p.ld, head_step, ok, c, tot);
-                    *(f4*)((float*)(buf + L::oCUM) + t * kFS + 4 * e4) = f4{c[0], c[1], c[2], c[3]};
-                    if (t == 0) *(f4*)((float*)(buf + L::oTOT) + 4 * e4) = f4{tot[0], tot[1], tot[2], tot[3]};
-                    u2 qa;
+                [&](int I, const PreKeysE& p, unsigned char* buf) {
+                    const bool ok = (nb - 1 - I) * kTok + t < T;
+                    if constexpr (VAR == SLA_GLA) {
+                        float* qd = (float*)(buf + L::oQDQ) + t * kFS + 16 * g;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        qa[j] = pack2(bf_lo(p.qx[j]) * ex2(c[2 * j]), bf_hi(p.qx[j]) * ex2(c[2 * j + 1]));
-                    put_T4((uint16_t*)(buf + L::oQAT), 4 * e4, t, qa);
-                    *(u2*)((uint16_t*)(buf + L::oKS) + t * kFS + 4 * e4) = p.kx;
-                    if (e4 == 0) {
-                        ((float*)(buf + L::oGQ))[t] = p.gq;
-                        ((float*)(buf + L::oGK))[t] = p.gk;
+                        for (int j = 0; j < 4; ++j) *(f4*)(qd + 4 * j) = ok ? p.e[j] : f4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int c0 = 16 * g + 8 * j;
+                        float c[8], tot[8];
+                        block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
+                        float* cum = (float*)(buf + L::oCUM) + t * kFS + c0;
+                        *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
+                        *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
+                        const u4 qx = keep(p.qx[j], ok), kx = keep(p.kx[j], ok);
+                        u4 qa;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            qa[i] = pack2(bf_lo(qx[i]) * ex2(c[2 * i]), bf_hi(qx[i]) * ex2(c[2 * i + 1]));
+                        put_T((uint16_t*)(buf + L::oQAT), c0, t, qa);
+                        uint16_t* ks = (uint16_t*)(buf + L::oKS) + t * kFS + c0;
+                        *(u2*)ks = u2{kx[0], kx[1]};
+                        *(u2*)(ks + 4) = u2{kx[2], kx[3]};
+                    }
+                    if (g == 0) {
+                        ((float*)(buf + L::oGQ))[t] = ok ? p.gq : 0.f;
+                        ((float*)(buf + L::oGK))[t] = ok ? p.gk : 0.f;
                     }
                 });
         } else {
-            const int x = ptid - 256;
-            producer_loop<PreRows<R>>(
-                nb,
-                [&](int i, PreRows<R>& p) {
+            producer_run<PreRows<R>>(
+                ring, smem, L::bytes, team, nb,
+                [&](int I, PreRows<R>& p) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = (x + 256 * rep) % (kTok * DV / 8), t = c / (DV / 8), e8 = c % (DV / 8);
-                        const int tok = min((nb - 1 - i) * kTok + t, T - 1);
-                        const size_t row = ((size_t)b * T + tok) * H + h;
+                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const size_t row = ((size_t)b * T + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
                         p.gq[rep] = a.gq[row];
                     }
                 },
-                [&](int i, const PreRows<R>& p, int which) {
-                    unsigned char* buf = smem + which * L::bytes;
+                [&](int I, const PreRows<R>& p, unsigned char* buf) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = x + 256 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
-                        if (c < kTok * DV / 8) {
-                            const bool ok = (nb - 1 - i) * kTok + t < T;
-                            const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
-                            put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
-                            put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
-                            u4 dy;
+                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const bool ok = (nb - 1 - I) * kTok + t < T;
+                        const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
+                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                        u4 dy;
 #pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                dy[j] = pack2(p.gq[rep] * bf_lo(dx[j]), p.gq[rep] * bf_hi(dx[j]));
-                            put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
-                        }
+                        for (int j = 0; j < 4; ++j)
+                            dy[j] = pack2(p.gq[rep] * bf_lo(dx[j]), p.gq[rep] * bf_hi(dx[j]));
+                        put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
                     }
                 });
         }
         return;
     }
 
+    const int cb = 16 * wave;
+    __builtin_amdgcn_s_setprio(2);  // the state recurrence is the serial part: let it issue first
     f4 DST[DV / 16];
     float run[4] = {0.f, 0.f, 0.f, 0.f};  // sum over later tokens of q*dq - k*dk, for key columns cb + 4g + i
 #pragma unroll
@@ -559,23 +633,13 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
             for (int i = 0; i < 4; ++i) run[i] = a.corr[(size_t)bh * DK + sbase + cb + 4 * g + i];
         }
     }
-    auto qdq_at = [&](int blk) {  // q * dq (fp32, written by the dq sweep) for this lane's token of block blk
-        f4 e = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (VAR == SLA_GLA) {  // unconditional, clamped into the sequence; masked where it is used
-            const int tok = max(0, min((nb - 1 - blk) * kTok + r, T - 1));
-            e = *(const f4*)(a.qdq + (((size_t)b * T + tok) * H + h) * DK + sbase + cb + 4 * g);
-        }
-        return e;
-    };
-    f4 e_next = {0.f, 0.f, 0.f, 0.f};
-    if (nb > 0) e_next = qdq_at(0);
-    block_barrier();
     for (int blk = 0; blk < nb; ++blk) {
+        consumer_acquire(ring, blk);
         if (kExp == 1) {
-            block_barrier();
+            consumer_release(ring, blk);
             continue;
         }
-        const unsigned char* buf = smem + (blk & 1) * L::bytes;
+        const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
         const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
         const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
@@ -596,8 +660,17 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         const s4 fqa = get_T((const uint16_t*)(buf + L::oQAT), cb + r, g);
         mma16(Xi, fqa, fp);
         const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
-        const f4 tot = *(const f4*)((const float*)(buf + L::oTOT) + cb + 4 * g);
+        const f4 tot = *(const f4*)((const float*)(buf + L::oCUM) + (kTok - 1) * kFS + cb + 4 * g);
+        f4 e = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (VAR == SLA_GLA) e = *(const f4*)((const float*)(buf + L::oQDQ) + r * kFS + cb + 4 * g);
         const float gk = ((const float*)(buf + L::oGK))[r];
+        const u2 kx = *(const u2*)((const uint16_t*)(buf + L::oKS) + r * kFS + cb + 4 * g);
+        const float Ad = ex2(((const float*)(buf + L::oCUM))[(kTok - 1) * kFS + cb + r]);
+        const uint16_t* DYT = (const uint16_t*)(buf + L::oDYT);
+        s4 fdy[DV / 16];
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) fdy[i] = get_T(DYT, 16 * i + r, g);
+        consumer_release(ring, blk);  // every operand of the block is in registers
         float dkv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) dkv[i] = gk * (Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]));
@@ -606,11 +679,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
         if (ok) *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
         if constexpr (VAR == SLA_GLA) {
-            const u2 kx = *(const u2*)((const uint16_t*)(buf + L::oKS) + r * kFS + cb + 4 * g);
             const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
-            f4 e = e_next;  // q * dq of this block, requested one block ago
-            if (!ok) e = f4{0.f, 0.f, 0.f, 0.f};
-            e_next = qdq_at(blk + 1);
             float dl[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -621,14 +690,11 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
             if (ok) *(u2*)(a.dld + row * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
         }
         // dS^T <- dS^T A + dy^T qa
-        const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
-        const uint16_t* DYT = (const uint16_t*)(buf + L::oDYT);
 #pragma unroll
         for (int i = 0; i < DV / 16; ++i) {
             DST[i] = DST[i] * Ad;
-            mma16(DST[i], get_T(DYT, 16 * i + r, g), fqa);
+            mma16(DST[i], fdy[i], fqa);
         }
-        block_barrier();
     }
 }
 
@@ -646,15 +712,18 @@ struct SmemV {
     static constexpr int oAT = oVS + kTok * kFS * 2;
     static constexpr int oGK = oAT + DK * 4;
     static constexpr int bytes = oGK + kTok * 4;
+    static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
     static_assert(oKD % 16 == 0 && oKB % 16 == 0 && oQAT % 16 == 0 && oDYT % 16 == 0 && oVS % 16 == 0 &&
                       oAT % 16 == 0 && oGK % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
+    static_assert(total <= 160 * 1024, "the ring fits the LDS of a compute unit");
 };
 
-struct PreVals {  // key-side thread of sweep R1: its token's keys, queries, decay, and one piece of dout or v
-    u2 ld, kx, qx;
-    u4 sl;
-    float gq, gk;
+template <int N>
+struct PreVals {  // N groups of eight key columns of one token, and two pieces of the dout or v slice
+    u4 ld[N], kx[N], qx[N];
+    u4 sl[2];
+    float gq[2], gk;
 };
 
 template <int VAR, int DK, int DV>
@@ -662,85 +731,95 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     typedef SmemV<DK> L;
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NSL = DV / kCols;
+    constexpr int N = DK / 64;  // each member wave stages half of the key columns: DK / 8 per lane
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
-    const int slice = blockIdx.x % NSL, bh = blockIdx.x / NSL, b = bh / a.H, h = bh % a.H;
+    const int wg = logical_workgroup();
+    if (wg >= a.B * a.H * NSL) return;
+    const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
     const int T = a.T, H = a.H;
     const int nb = (T + kTok - 1) / kTok;
-    const int cb = 16 * (wave & 3);
+    const Ring ring = ring_init(smem, L::bytes, tid);
 
-    if (wave >= 4) {
-        const int ptid = tid - 256;
-        // key side: 16 tokens x DK/4 groups of four key columns (the first DK/16 producer waves);
-        // slice side: thread x < 128 carries a piece of dout, 128 <= x < 256 a piece of v (token x/8 % 16,
-        // columns 8 (x % 8) .. of the slice)
-        // Every producer thread issues the same loads (threads without a role repeat another thread's), so that
-        // the number of loads in flight does not depend on the role; only the staging does.
-        const bool keys = wave - 4 < DK / 16;
-        const int kp = ptid % (DK * 4), e4 = kp >> 4, t = kp & 15;
-        const int st = (ptid & 127) >> 3, se8 = ptid & 7;
-        const bool is_dout = wave < 6, is_v = wave >= 6 && wave < 8;
-        const uint16_t* slice_src = ((ptid & 128) ? a.v : a.dout) + sbase + 8 * se8;
+    if (wave >= kConsumers) {
+        // member m: key columns m DK/2 + (DK/8) (lane / 16) ..., token lane % 16; member 0 also stages the slice of
+        // dout (gated, transposed), member 1 the slice of v: two 16-byte pieces per lane each
+        const int team = (wave - kConsumers) >> 1, m = (wave - kConsumers) & 1;
+        const int t = r, d0 = m * (DK / 2) + (DK / 8) * g;
+        const uint16_t* slice_src = (m ? a.v : a.dout) + sbase;
         const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
-        producer_loop<PreVals>(
-            nb,
-            [&](int i, PreVals& p) {
-                const int t0 = (nb - 1 - i) * kTok;
+        producer_run<PreVals<N>>(
+            ring, smem, L::bytes, team, nb,
+            [&](int I, PreVals<N>& p) {
+                const int t0 = (nb - 1 - I) * kTok;
                 const size_t row = ((size_t)b * T + min(t0 + t, T - 1)) * H + h;
-                if constexpr (VAR == SLA_GLA) p.ld = load8(a.ld + row * DK + 4 * e4);
-                p.kx = load8(a.k + row * DK + 4 * e4);
-                p.qx = load8(a.q + row * DK + 4 * e4);
+#pragma unroll
+                for (int j = 0; j < N; ++j) {
+                    if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
+                    p.kx[j] = load16(a.k + row * DK + d0 + 8 * j);
+                    p.qx[j] = load16(a.q + row * DK + d0 + 8 * j);
+                }
                 p.gk = a.gk[row];
-                const size_t srow = ((size_t)b * T + min(t0 + st, T - 1)) * H + h;
-                p.sl = load16(slice_src + srow * DV);
-                p.gq = a.gq[srow];
+#pragma unroll
+                for (int rep = 0; rep < 2; ++rep) {
+                    const int c = lane + 64 * rep, st = c >> 3, se8 = c & 7;
+                    const size_t srow = ((size_t)b * T + min(t0 + st, T - 1)) * H + h;
+                    p.sl[rep] = load16(slice_src + srow * DV + 8 * se8);
+                    p.gq[rep] = a.gq[srow];
+                }
             },
-            [&](int i, const PreVals& pp, int which) {
-                unsigned char* buf = smem + which * L::bytes;
-                const int t0 = (nb - 1 - i) * kTok;
-                PreVals p;
-                {
-                    const bool ok = t0 + t < T, oks = t0 + st < T;
-                    p.ld = keep(pp.ld, ok); p.kx = keep(pp.kx, ok); p.qx = keep(pp.qx, ok);
-                    p.gk = ok ? pp.gk : 0.f;
-                    p.sl = keep(pp.sl, oks);
-                    p.gq = oks ? pp.gq : 0.f;
-                }
-                if (keys) {
-                    float c[4], tot[4];
-                    block_decay<VAR>(p.ld, head_step, t0 + t < T, c, tot);
-                    u2 qa, kd, kb;
+            [&](int I, const PreVals<N>& p, unsigned char* buf) {
+                const int t0 = (nb - 1 - I) * kTok;
+                const bool ok = t0 + t < T;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        qa[j] = pack2(bf_lo(p.qx[j]) * ex2(c[2 * j]), bf_hi(p.qx[j]) * ex2(c[2 * j + 1]));
-                        kd[j] = pack2(bf_lo(p.kx[j]) * ex2(-c[2 * j]), bf_hi(p.kx[j]) * ex2(-c[2 * j + 1]));
-                        kb[j] = pack2(bf_lo(p.kx[j]) * ex2(tot[2 * j] - c[2 * j]),
-                                      bf_hi(p.kx[j]) * ex2(tot[2 * j + 1] - c[2 * j + 1]));
+                for (int j = 0; j < N; ++j) {
+                    const int c0 = d0 + 8 * j;
+                    float c[8], tot[8];
+                    block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
+                    const u4 qx = keep(p.qx[j], ok), kx = keep(p.kx[j], ok);
+                    u4 qa, kd, kb;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        qa[i] = pack2(bf_lo(qx[i]) * ex2(c[2 * i]), bf_hi(qx[i]) * ex2(c[2 * i + 1]));
+                        kd[i] = pack2(bf_lo(kx[i]) * ex2(-c[2 * i]), bf_hi(kx[i]) * ex2(-c[2 * i + 1]));
+                        kb[i] = pack2(bf_lo(kx[i]) * ex2(tot[2 * i] - c[2 * i]),
+                                      bf_hi(kx[i]) * ex2(tot[2 * i + 1] - c[2 * i + 1]));
                     }
-                    put_perm4<DK>((uint16_t*)(buf + L::oQA), t, e4, qa);
-                    put_perm4<DK>((uint16_t*)(buf + L::oKD), t, e4, kd);
-                    put_perm4<DK>((uint16_t*)(buf + L::oKB), t, e4, kb);
-                    put_T4((uint16_t*)(buf + L::oQAT), 4 * e4, t, qa);
-                    if (t == 0)
-                        *(f4*)((float*)(buf + L::oAT) + 4 * e4) = f4{ex2(tot[0]), ex2(tot[1]), ex2(tot[2]), ex2(tot[3])};
-                    if (e4 == 0) ((float*)(buf + L::oGK))[t] = p.gk;
+                    put_perm<DK>((uint16_t*)(buf + L::oQA), t, c0 >> 3, qa);
+                    put_perm<DK>((uint16_t*)(buf + L::oKD), t, c0 >> 3, kd);
+                    put_perm<DK>((uint16_t*)(buf + L::oKB), t, c0 >> 3, kb);
+                    put_T((uint16_t*)(buf + L::oQAT), c0, t, qa);
+                    if (t == 0) {
+                        float* at = (float*)(buf + L::oAT) + c0;
+                        *(f4*)at = f4{ex2(tot[0]), ex2(tot[1]), ex2(tot[2]), ex2(tot[3])};
+                        *(f4*)(at + 4) = f4{ex2(tot[4]), ex2(tot[5]), ex2(tot[6]), ex2(tot[7])};
+                    }
                 }
-                if (is_dout) {
-                    u4 dy;
+                if (m == 0 && g == 0) ((float*)(buf + L::oGK))[t] = ok ? p.gk : 0.f;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) dy[j] = pack2(p.gq * bf_lo(p.sl[j]), p.gq * bf_hi(p.sl[j]));
-                    put_T((uint16_t*)(buf + L::oDYT), 8 * se8, st, dy);
-                } else if (is_v) {
-                    uint16_t* vs = (uint16_t*)(buf + L::oVS) + st * kFS + 8 * se8;
-                    *(u2*)vs = u2{p.sl[0], p.sl[1]};
-                    *(u2*)(vs + 4) = u2{p.sl[2], p.sl[3]};
+                for (int rep = 0; rep < 2; ++rep) {
+                    const int c = lane + 64 * rep, st = c >> 3, se8 = c & 7;
+                    const bool oks = t0 + st < T;
+                    const u4 sl = keep(p.sl[rep], oks);
+                    if (m == 0) {
+                        u4 dy;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) dy[j] = pack2(p.gq[rep] * bf_lo(sl[j]), p.gq[rep] * bf_hi(sl[j]));
+                        put_T((uint16_t*)(buf + L::oDYT), 8 * se8, st, dy);
+                    } else {
+                        uint16_t* vs = (uint16_t*)(buf + L::oVS) + st * kFS + 8 * se8;
+                        *(u2*)vs = u2{sl[0], sl[1]};
+                        *(u2*)(vs + 4) = u2{sl[2], sl[3]};
+                    }
                 }
             });
         return;
     }
 
+    const int cb = 16 * wave;
+    __builtin_amdgcn_s_setprio(2);  // the state recurrence is the serial part: let it issue first
     f4 DS[DK / 16];  // rows d = 16 i + 4 g + (0..3), column n = sbase + cb + r
 #pragma unroll
     for (int i = 0; i < DK / 16; ++i) {
@@ -750,13 +829,13 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
             for (int j = 0; j < 4; ++j) DS[i][j] = a.dsf[((size_t)bh * DK + 16 * i + 4 * g + j) * DV + sbase + cb + r];
         }
     }
-    block_barrier();
     for (int blk = 0; blk < nb; ++blk) {
+        consumer_acquire(ring, blk);
         if (kExp == 1) {
-            block_barrier();
+            consumer_release(ring, blk);
             continue;
         }
-        const unsigned char* buf = smem + (blk & 1) * L::bytes;
+        const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
         const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
         const uint16_t* KDp = (const uint16_t*)(buf + L::oKD);
@@ -777,8 +856,18 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
         const s4 fdy = get_T((const uint16_t*)(buf + L::oDYT), cb + r, g);
         mma16(Yi, fdy, fp);
         const u2 vx = *(const u2*)((const uint16_t*)(buf + L::oVS) + r * kFS + cb + 4 * g);
-        const float vf[4] = {bf_lo(vx[0]), bf_hi(vx[0]), bf_lo(vx[1]), bf_hi(vx[1])};
         const float gk = ((const float*)(buf + L::oGK))[r];
+        const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
+        const float* AT = (const float*)(buf + L::oAT);
+        s4 fqat[DK / 16];
+        f4 Ad[DK / 16];
+#pragma unroll
+        for (int i = 0; i < DK / 16; ++i) {
+            fqat[i] = get_T(QAT, 16 * i + r, g);
+            Ad[i] = *(const f4*)(AT + 16 * i + 4 * g);
+        }
+        consumer_release(ring, blk);  // every operand of the block is in registers
+        const float vf[4] = {bf_lo(vx[0]), bf_hi(vx[0]), bf_lo(vx[1]), bf_hi(vx[1])};
         float dvp[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) dvp[i] = Ys[i] + Yi[i];
@@ -792,15 +881,11 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                 u2{pack2(gk * dvp[0], gk * dvp[1]), pack2(gk * dvp[2], gk * dvp[3])};
         }
         // dS <- diag(A) dS + qa^T dy
-        const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
-        const float* AT = (const float*)(buf + L::oAT);
 #pragma unroll
         for (int i = 0; i < DK / 16; ++i) {
-            const f4 Ad = *(const f4*)(AT + 16 * i + 4 * g);
-            DS[i] = DS[i] * Ad;
-            mma16(DS[i], get_T(QAT, 16 * i + r, g), fdy);
+            DS[i] = DS[i] * Ad[i];
+            mma16(DS[i], fqat[i], fdy);
         }
-        block_barrier();
     }
 
     if (a.ds0) {
@@ -882,7 +967,7 @@ bool allow_lds(K kernel, int lds) {
 
 template <int VAR, int DK, int DV>
 int launch_sweeps(const BArgs& a, hipStream_t stream) {
-    constexpr int ldsF = 2 * SmemF<DV>::bytes, ldsV = 2 * SmemV<DK>::bytes, ldsK = 2 * SmemK<DV>::bytes;
+    constexpr int ldsF = SmemF<DV>::total, ldsV = SmemV<DK>::total, ldsK = SmemK<DV>::total;
     static bool configured = false;  // once per instantiation; not a stream operation
     if (!configured) {
         if (!allow_lds(sla_bwd_dq_kernel<VAR, DK, DV>, ldsF) || !allow_lds(sla_bwd_dv_kernel<VAR, DK, DV>, ldsV) ||
@@ -892,9 +977,10 @@ int launch_sweeps(const BArgs& a, hipStream_t stream) {
     }
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kBwdThreads);
-    hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), dim3(bh * (DK / kCols)), block, (size_t)ldsF, stream, a);
-    hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), dim3(bh * (DV / kCols)), block, (size_t)ldsV, stream, a);
-    hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), dim3(bh * (DK / kCols)), block, (size_t)ldsK, stream, a);
+    auto padded = [](unsigned n) { return dim3((n + 7u) & ~7u); };  // see logical_workgroup()
+    hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), padded(bh * (DK / kCols)), block, (size_t)ldsF, stream, a);
+    hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), padded(bh * (DV / kCols)), block, (size_t)ldsV, stream, a);
+    hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), padded(bh * (DK / kCols)), block, (size_t)ldsK, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -164,3 +164,43 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libsla.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         b.load_library()
+
+
+# ------------------------------------------------------------------ sla_backward: validation before any device work
+def _bwd(p, **kw):
+    a = dict(q=A, k=A, v=A, ql=A, kl=A, ld=A, s0=0, dout=A, dsf=0, dq=A, dk=A, dv=A, dql=A, dkl=A, dld=A, ds0=0,
+             ws=A, ws_bytes=1 << 40)
+    a.update(kw)
+    return sla.sla_backward(p, a["q"], a["k"], a["v"], a["ql"], a["kl"], a["ld"], a["s0"], a["dout"], a["dsf"],
+                            a["dq"], a["dk"], a["dv"], a["dql"], a["dkl"], a["dld"], a["ds0"], a["ws"], a["ws_bytes"], 0)
+
+
+def test_backward_rejects_bad_calls(lib):
+    ok = _ok_params()
+    assert _bwd(_ok_params(variant=sla.GDN)) == -3           # the delta rule has no backward here
+    assert _bwd(_ok_params(dtype=sla.F32)) == -3             # bf16 only
+    assert _bwd(_ok_params(dk=96)) == -3
+    assert _bwd(ok, dout=0) == -1
+    assert _bwd(ok, dq=0) == -1
+    assert _bwd(ok, dld=0) == -1                             # GLA needs the decay gradient buffer
+    assert _bwd(_ok_params(variant=sla.RETNET), dld=A) == -1  # RetNet's decay is a constant
+    assert _bwd(ok, kl=0) == -1 and _bwd(ok, dkl=0) == -1    # write-gate logits and their gradient go together
+    assert _bwd(ok, dv=A + 4) == -4
+    assert _bwd(ok, ws=0) == -6
+    assert _bwd(ok, ws_bytes=1024) == -6
+    assert _bwd(None) == -1
+    # empty problems are accepted without touching the device
+    assert _bwd(_ok_params(B=0)) == 0
+    assert _bwd(_ok_params(T=0)) == 0
+
+
+def test_backward_workspace_size(lib):
+    B, T, H, dk, dv = 2, 128, 4, 128, 64
+    n = B * T * H
+    gla = sla.sla_backward_workspace_bytes(_ok_params(B=B, T=T, H=H, dk=dk, dv=dv))
+    ret = sla.sla_backward_workspace_bytes(_ok_params(variant=sla.RETNET, B=B, T=T, H=H, dk=dk, dv=dv))
+    # gates (2 planes), partial gate gradients (dk/16 + dv/16 planes); GLA adds q*dq [B,T,H,dk] and [B,H,dk]
+    assert ret == 4 * n * (2 + dk // 16 + dv // 16)
+    assert gla == ret + 4 * (n * dk + B * H * dk)
+    assert sla.sla_backward_workspace_bytes(_ok_params(variant=sla.GDN)) == 0
+    assert sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32)) == 0
