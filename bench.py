@@ -32,6 +32,7 @@ MEASURED_TRAFFIC_BYTES = {
     "decode_gdn": 135.7e6,    # same file
     "gla_train:backward": 1.628e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
     "retnet_train:backward": 1.055e9,  # same file
+    "gla_train:prologue": 136.5e6,     # profiles/sla_gate_logits_bf16_gla_train.md
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 BLOCK = 16                      # tokens per state step in the kernels (for the causal flop count)
@@ -194,6 +195,107 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     return 0
 
 
+def bench_prologue(args, w, sla, si, torch, np) -> int:
+    """--prologue: a step is one sla_gate_logits call (both gates) over the workload's q and k."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import rel_err, to_device
+
+    d = si.generate(w)
+    gw = si.gate_weights(w.H, w.dk, seed=w.seed + 60)
+    g, tdt = to_device(d, w.dtype, w.variant)
+    dev = torch.device("cuda:0")
+    wq, wk = torch.from_numpy(gw["w_gq"]).to(dev), torch.from_numpy(gw["w_gk"]).to(dev)
+    ql = torch.empty((w.B, w.T, w.H), dtype=torch.float32, device=dev)
+    kl = torch.empty_like(ql)
+    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 1)
+    raw = (g["q"].data_ptr(), g["k"].data_ptr(), wq.data_ptr(), wk.data_ptr(), ql.data_ptr(), kl.data_ptr(),
+           torch.cuda.current_stream(dev).cuda_stream)
+
+    def step():
+        rc = sla.sla_gate_logits(params, *raw)
+        if rc != 0:
+            raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    for _ in range(args.settle + args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    kernel_ms = float(np.mean(per_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    es = 2 if w.dtype == "bf16" else 4
+    abytes = 2 * w.B * w.T * w.H * (w.dk * es + 4) + 2 * w.H * w.dk * 4
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "tokens/sec SLA gate logits (q W_GQ, k W_GK)",
+        "value": w.tokens() / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "settle_launches": args.settle,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: gate logits of both gates, B={w.B} T={w.T} H={w.H} dk={w.dk} {w.dtype} q and k, "
+                        f"fp32 weights [H,dk] and logits",
+            "kernel": f"sla_gate_logits_kernel<{'true' if w.dtype == 'bf16' else 'false'}, {w.dk}>",
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name + ":prologue"),
+            "kernel_us": kernel_ms * 1e3,
+            "kernel_us_min": float(np.min(per_ms)) * 1e3,
+            "algorithmic_bytes": abytes,
+        },
+    }
+    if not args.no_cpu_baseline or not args.no_parity:
+        from oracle import sla_numpy
+
+        passes, cpu_s = 0, 0.0
+        while True:
+            t0 = time.perf_counter()
+            rq = sla_numpy.gate_logits(d["q"], gw["w_gq"])
+            rk = sla_numpy.gate_logits(d["k"], gw["w_gk"])
+            cpu_s += time.perf_counter() - t0
+            passes += 1
+            if args.no_cpu_baseline or cpu_s >= 10.0 or passes >= 50:
+                break
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {
+                "value": w.tokens() * passes / cpu_s,
+                "unit": "tokens/s",
+                "cores": 1,
+                "kind": "oracle",
+                "sample": f"the full workload, {passes} pass(es) of the numpy fp64 statement, {cpu_s:.2f} s wall",
+            }
+        if not args.no_parity:
+            step()
+            torch.cuda.synchronize()
+            result["parity"] = {
+                "q_logits_rel_err": rel_err(ql.cpu().numpy().astype(np.float64), rq),
+                "k_logits_rel_err": rel_err(kl.cpu().numpy().astype(np.float64), rk),
+                "definition": "max|x - oracle| / max|oracle| per tensor",
+            }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def bench_decode(args, w, sla, si, torch, np) -> int:
     """--workload decode_*: a step is one recurrent decode step (sla_decode_step) over the batch; the state
     stays resident and is updated in place, as in serving."""
@@ -338,6 +440,8 @@ def main() -> int:
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--backward", action="store_true",
                     help="time sla_backward (RetNet / GLA training workloads) instead of the forward")
+    ap.add_argument("--prologue", action="store_true",
+                    help="time sla_gate_logits (the projections in front of the head softmax) on the workload's q, k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     args = ap.parse_args()
@@ -361,6 +465,8 @@ def main() -> int:
         return bench_decode(args, w, sla, si, torch, np)
     if args.backward:
         return bench_backward(args, w, sla, si, torch, np)
+    if args.prologue:
+        return bench_prologue(args, w, sla, si, torch, np)
     d = si.generate(w)
 
     sys.path.insert(0, os.path.join(ROOT, "tests"))

@@ -167,6 +167,23 @@ int sla_backward(const sla_params* p, const void* q, const void* k, const void* 
 /* Bytes of workspace sla_backward needs for *p (0 when *p is not a shape it supports). */
 size_t sla_backward_workspace_bytes(const sla_params* p);
 
+/*
+ * Gate logits: the scores Eq. 4 takes the head softmax of, from the (feature-mapped) queries and keys and the
+ * two gate matrices W_GQ, W_GK in R^{d x H} of Sec. 3.2, with d the head width (the reading under which the two
+ * matrices add the 0.05 M parameters that the "Parameter Efficiency" paragraph counts):
+ *     q_head_logits[b,t,h] = q[b,t,h,:] . W_GQ[:,h]        k_head_logits[b,t,h] = k[b,t,h,:] . W_GK[:,h]
+ * One streaming pass over q and k; the result is what sla_forward / sla_backward take as logits.
+ *
+ *   q, k             [B,T,H,dk]  dtype   device, read only; k may be NULL (then w_gk and k_head_logits must be too)
+ *   w_gq, w_gk       [H,dk]      fp32    device, read only: row h is column h of the paper's matrix
+ *   q_head_logits    [B,T,H]     fp32    written
+ *   k_head_logits    [B,T,H]     fp32    written, or NULL with k
+ * Uses p->dtype, B, T, H, dk (dv, variant, dv_split, segments are validated as for sla_forward and otherwise
+ * ignored).  Enqueued on `stream`; nothing is allocated or synchronised.  Returns a status code.
+ */
+int sla_gate_logits(const sla_params* p, const void* q, const void* k, const float* w_gq, const float* w_gk,
+                    float* q_head_logits, float* k_head_logits, void* stream);
+
 /* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
 size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 

@@ -4,7 +4,8 @@ TEST INFRASTRUCTURE ONLY: these functions define what the GPU library must
 compute and are used to pin the C oracle (``sla_oracle.c``); the GPU library
 never imports this package and shares no code with it.
 
-Three independent statements of the same mathematics live here:
+``gate_logits`` states the projection in front of Eq. 4's softmax.  Three independent statements of the forward
+mathematics live here:
 
 * ``recurrent``     – the token-by-token recurrence (Eq. 5-6 and the three
                       instantiations of Sec. 5.1), vectorised over (batch, head)
@@ -38,6 +39,19 @@ def head_softmax(logits: Optional[np.ndarray], shape=None) -> np.ndarray:
     x = np.asarray(logits, dtype=np.float64)
     e = np.exp(x - np.max(x, axis=-1, keepdims=True))
     return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def gate_logits(x, w) -> np.ndarray:
+    """The scores of Eq. 4 under the per-head reading of W in R^{d x H} (d = head width, Sec. 3.2 "Parameter
+    Efficiency"): logits[b,t,h] = sum_d x[b,t,h,d] * W[d,h].  ``w`` is given as ``[H,d]`` (row h = column h of W)."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    B, T, H, d = x.shape
+    assert w.shape == (H, d)
+    out = np.zeros((B, T, H))
+    for h in range(H):
+        out[:, :, h] = x[:, :, h, :] @ w[h]
+    return out
 
 
 def recurrent(

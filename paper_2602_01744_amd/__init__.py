@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     sla_backward,
     sla_backward_workspace_bytes,
     sla_check_args,
+    sla_gate_logits,
     sla_decode_step,
     sla_default_dv_split,
     sla_forward,
@@ -29,6 +30,7 @@ from .binding import (  # noqa: F401
     sla_version,
     forward,
     backward,
+    gate_logits,
     decode_step,
 )
 

@@ -63,6 +63,8 @@ def load_library():
     lib.sla_forward_ws.argtypes = [pp] + [vp] * 11 + [ctypes.c_size_t, vp]
     lib.sla_decode_step.restype = ctypes.c_int
     lib.sla_decode_step.argtypes = [pp] + [vp] * 10
+    lib.sla_gate_logits.restype = ctypes.c_int
+    lib.sla_gate_logits.argtypes = [pp] + [vp] * 7
     lib.sla_backward.restype = ctypes.c_int
     lib.sla_backward.argtypes = [pp] + [vp] * 17 + [ctypes.c_size_t, vp]
     lib.sla_backward_workspace_bytes.restype = ctypes.c_size_t
@@ -158,6 +160,37 @@ def sla_decode_step(params, q, k, v, q_head_logits, k_head_logits, log_decay, be
             _p(out), _p(stream),
         )
     )
+
+
+def sla_gate_logits(params, q, k, w_gq, w_gk, q_head_logits, k_head_logits, stream) -> int:
+    """Raw call of the gate-logit entry point: every pointer argument is an integer device address or None."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(load_library().sla_gate_logits(pr, _p(q), _p(k), _p(w_gq), _p(w_gk), _p(q_head_logits),
+                                               _p(k_head_logits), _p(stream)))
+
+
+def gate_logits(q, k, w_gq, w_gk, *, dv: int = 0):
+    """q, k [B,T,H,dk] (float32 or bfloat16; k may be None), w_gq, w_gk [H,dk] float32 -> (q_head_logits,
+    k_head_logits) [B,T,H] float32 on the current CUDA(HIP) device and stream."""
+    import torch
+
+    assert q.is_cuda and q.is_contiguous()
+    B, T, H, dk = q.shape
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+    assert w_gq.dtype == torch.float32 and tuple(w_gq.shape) == (H, dk) and w_gq.is_contiguous()
+    ql = torch.empty((B, T, H), dtype=torch.float32, device=q.device)
+    kl = None
+    if k is not None:
+        assert k.shape == q.shape and k.dtype == q.dtype and k.is_contiguous()
+        assert w_gk.dtype == torch.float32 and tuple(w_gk.shape) == (H, dk) and w_gk.is_contiguous()
+        kl = torch.empty_like(ql)
+    params = SlaParams(GLA, dtype, B, T, H, dk, dv or dk, 0, 0, 1)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_gate_logits(params, ptr(q), ptr(k), ptr(w_gq), ptr(w_gk), ptr(ql), ptr(kl),
+                         torch.cuda.current_stream(q.device).cuda_stream)
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return ql, kl
 
 
 def sla_backward_workspace_bytes(params: SlaParams) -> int:

@@ -15,6 +15,8 @@ size_t backward_workspace_floats(const sla_params& p);
 int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                     const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
                     float* dql, float* dkl, void* dld, float* ds0, float* ws, hipStream_t stream);
+int launch_gate_logits(const sla_params& p, const void* q, const void* k, const float* wq, const float* wk, float* ql,
+                       float* kl, int compute_units, hipStream_t stream);
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
@@ -199,6 +201,22 @@ int sla_backward(const sla_params* p, const void* q, const void* k, const void* 
     return sla::launch_backward(*p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out,
                                 d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
                                 d_initial_state, (float*)workspace, (hipStream_t)stream);
+}
+
+int sla_gate_logits(const sla_params* p, const void* q, const void* k, const float* w_gq, const float* w_gk,
+                    float* q_head_logits, float* k_head_logits, void* stream) {
+    const int rc = check_params(p);
+    if (rc != SLA_OK) return rc;
+    const bool work = p->B > 0 && p->T > 0;
+    if (work && (!q || !w_gq || !q_head_logits)) return SLA_ERR_NULL;
+    if ((k != nullptr) != (w_gk != nullptr) || (k != nullptr) != (k_head_logits != nullptr)) return SLA_ERR_NULL;
+    const void* ptrs[] = {q, k, w_gq, w_gk, q_head_logits, k_head_logits};
+    for (const void* x : ptrs)
+        if (x && !aligned16(x)) return SLA_ERR_ALIGN;
+    if (!work) return SLA_OK;
+    const int cus = device_compute_units();
+    if (cus <= 0) return SLA_ERR_HIP;
+    return sla::launch_gate_logits(*p, q, k, w_gq, w_gk, q_head_logits, k_head_logits, cus, (hipStream_t)stream);
 }
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {

@@ -225,3 +225,11 @@ def cotangents(B: int, T: int, H: int, dk: int, dv: int, seed: int, dtype: str =
     if final_state:
         dsf = (rng.standard_normal(size=(B, H, dk, dv), dtype=np.float32) * np.float32(0.5)).astype(np.float32)
     return {"d_out": np.ascontiguousarray(d_out, dtype=np.float32), "d_final_state": dsf}
+
+
+def gate_weights(H: int, dk: int, seed: int) -> Dict[str, np.ndarray]:
+    """Seeded gate matrices of Sec. 3.2 as ``[H,dk]`` fp32 (row h = column h of W_GQ / W_GK), N(0,1): with q, k
+    of variance 1/dk per element the logits come out with unit variance, as the workloads' logits have."""
+    rng = np.random.default_rng(seed)
+    return {"w_gq": rng.standard_normal(size=(H, dk), dtype=np.float32),
+            "w_gk": rng.standard_normal(size=(H, dk), dtype=np.float32)}

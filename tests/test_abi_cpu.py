@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_gate_logits", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -204,3 +204,14 @@ def test_backward_workspace_size(lib):
     assert gla == ret + 4 * (n * dk + B * H * dk)
     assert sla.sla_backward_workspace_bytes(_ok_params(variant=sla.GDN)) == 0
     assert sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32)) == 0
+
+
+def test_gate_logits_rejects_bad_calls(lib):
+    ok = _ok_params()
+    call = lambda p, q=A, k=A, wq=A, wk=A, ql=A, kl=A: sla.sla_gate_logits(p, q, k, wq, wk, ql, kl, 0)
+    assert call(ok, q=0) == -1 and call(ok, wq=0) == -1 and call(ok, ql=0) == -1
+    assert call(ok, k=0) == -1 and call(ok, wk=0) == -1 and call(ok, kl=0) == -1  # k, w_gk, k logits go together
+    assert call(ok, wq=A + 8) == -4
+    assert call(_ok_params(dk=32)) == -3
+    assert call(None) == -1
+    assert call(_ok_params(B=0)) == 0 and call(_ok_params(T=0)) == 0

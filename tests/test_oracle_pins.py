@@ -368,3 +368,24 @@ def test_generators_are_seeded_and_bf16_exact():
     g = si.generate(si.workload("gdn"), T=16, B=1)
     assert np.all((g["beta"] > 0) & (g["beta"] < 1))
     np.testing.assert_allclose(np.linalg.norm(g["k"].astype(np.float64), axis=-1), 1.0, atol=1e-2)
+
+
+# ------------------------------------------------------------------ gate logits (the projection in front of Eq. 4)
+def test_gate_logits_brute_force_and_selection():
+    r = np.random.default_rng(77)
+    x = r.normal(size=(2, 5, 3, 4))
+    w = r.normal(size=(3, 4))
+    got = ref.gate_logits(x, w)
+    for b in range(2):
+        for t in range(5):
+            for h in range(3):
+                assert abs(got[b, t, h] - sum(x[b, t, h, d] * w[h, d] for d in range(4))) < 1e-12
+    # a one-hot weight row reads out one coordinate of its own head and nothing of the others
+    sel = np.zeros((3, 4))
+    sel[0, 2] = sel[1, 0] = sel[2, 3] = 1.0
+    got = ref.gate_logits(x, sel)
+    assert np.array_equal(got[..., 0], x[:, :, 0, 2]) and np.array_equal(got[..., 1], x[:, :, 1, 0])
+    assert np.array_equal(got[..., 2], x[:, :, 2, 3])
+    # linear in x and in w
+    np.testing.assert_allclose(ref.gate_logits(2 * x, w) + ref.gate_logits(x, 3 * w), 5 * ref.gate_logits(x, w),
+                               rtol=1e-13, atol=1e-13)
