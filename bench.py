@@ -440,6 +440,9 @@ def main() -> int:
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--backward", action="store_true",
                     help="time sla_backward (RetNet / GLA training workloads) instead of the forward")
+    ap.add_argument("--varlen", action="store_true",
+                    help="forward only: the workload's B*T tokens as one packed batch of mixed-length sequences "
+                         "(sla_forward_varlen; lengths from sla_inputs.packed_lengths)")
     ap.add_argument("--prologue", action="store_true",
                     help="time sla_gate_logits (the projections in front of the head softmax) on the workload's q, k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -475,7 +478,9 @@ def main() -> int:
     g, tdt = to_device(d, w.dtype, w.variant)
     dev = torch.device("cuda:0")
     out = torch.empty((w.B, w.T, w.H, w.dv), dtype=tdt, device=dev)
-    fin = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+    lengths = si.packed_lengths(w.B * w.T, seed=w.seed + 70) if args.varlen else None
+    nstates = len(lengths) if args.varlen else w.B
+    fin = torch.empty((nstates, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
 
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, args.dv_split, 0,
@@ -499,6 +504,18 @@ def main() -> int:
         rc = sla.sla_forward_ws(params, *raw)
         if rc != 0:
             raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    if args.varlen:
+        # the same tensors read as one row of B*T tokens (the generator's batch rows laid end to end)
+        cu_host = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+        cu = torch.from_numpy(cu_host).to(dev)
+        vparams = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, len(lengths), w.B * w.T, w.H, w.dk, w.dv, 0, 0, 1)
+        vraw = raw[:7] + (cu.data_ptr(), None, ptr(out), ptr(fin), stream)
+
+        def step():  # noqa: F811
+            rc = sla.sla_forward_varlen(vparams, *vraw)
+            if rc != 0:
+                raise sla.SlaError(rc, sla.sla_status_string(rc))
 
     if args.copy_bytes > 0:
         src = torch.empty(args.copy_bytes, dtype=torch.uint8, device=dev).fill_(3)
@@ -552,6 +569,7 @@ def main() -> int:
             "dv_split": dvw,
             "segments": nseg,
             "compute_units": cus,
+            **({"packed_lengths": [int(x) for x in lengths], "entry_point": "sla_forward_varlen"} if args.varlen else {}),
         },
         "roofline": {
             "bound": "hbm",
@@ -590,7 +608,7 @@ def main() -> int:
                 "kind": "oracle",
                 "sample": f"the full workload, {passes} pass(es) ({tokens} tokens x {w.H} heads each, {cpu_s:.2f} s wall)",
             }
-        if not args.no_parity:
+        if not args.no_parity and not args.varlen:
             step()
             torch.cuda.synchronize()
             result["parity"] = {
@@ -598,6 +616,22 @@ def main() -> int:
                 "state_rel_err": rel_err(fin.cpu().numpy().astype(np.float64), rf),
                 "definition": "max|x - oracle| / max|oracle| per tensor",
             }
+        if not args.no_parity and args.varlen:
+            step()
+            torch.cuda.synchronize()
+            flat = lambda a: None if a is None else (a if a.ndim == 1 else a.reshape((1, w.B * w.T) + a.shape[2:]))
+            og = out.to(torch.float32).cpu().numpy().astype(np.float64).reshape((w.B * w.T, w.H, w.dv))
+            fg = fin.cpu().numpy().astype(np.float64)
+            eo = ef = 0.0
+            for i in (0, len(lengths) // 2, len(lengths) - 1):  # the longest, a middle and the shortest sequence
+                a0, a1 = int(cu_host[i]), int(cu_host[i + 1])
+                cut = lambda x: None if x is None else (x if x.ndim == 1 else flat(x)[:, a0:a1])
+                so, sf = oracle.forward(w.variant, cut(d["q"]), cut(d["k"]), cut(d["v"]), cut(d["q_logits"]),
+                                        cut(d["k_logits"]), cut(d["log_decay"]), cut(d["beta"]), None)
+                eo, ef = max(eo, rel_err(og[a0:a1], so[0])), max(ef, rel_err(fg[i], sf[0]))
+            result["parity"] = {"out_rel_err": eo, "state_rel_err": ef,
+                                "definition": "max|x - oracle| / max|oracle| over three sequences of the pack, each "
+                                              "against the oracle run on that sequence alone"}
     print(json.dumps(result), flush=True)
     return 0
 

@@ -184,6 +184,34 @@ size_t sla_backward_workspace_bytes(const sla_params* p);
 int sla_gate_logits(const sla_params* p, const void* q, const void* k, const float* w_gq, const float* w_gk,
                     float* q_head_logits, float* k_head_logits, void* stream);
 
+/*
+ * Packed variable-length batches: p->B sequences laid end to end along the token axis, as language-model
+ * training on documents of mixed length feeds the mixer (the training runs of Sec. 5.2 use 4K-token contexts;
+ * Sec. 5.3's retrieval lengths range from 1K to 8K and beyond).  p->T is the TOTAL number of tokens, the tensors
+ * have the layouts of sla_forward with a single batch row of p->T tokens, and sequence b covers tokens
+ * cu_seqlens[b] .. cu_seqlens[b+1]-1.  Every sequence has its own state: the recurrence of Eq. 5 restarts at each
+ * boundary from initial_state[b] (zero if NULL) and leaves final_state[b].
+ *
+ *   cu_seqlens       [B+1] int32, DEVICE memory, read by the kernels: non-decreasing, cu_seqlens[0] >= 0,
+ *                    cu_seqlens[B] <= p->T (tokens outside every sequence are neither read nor written; offsets
+ *                    are clamped into [0, p->T], so no content of this array makes the kernels leave the tensors)
+ *   initial_state, final_state, d_final_state, d_initial_state   [B,H,dk,dv] fp32, one per sequence
+ *   everything else as for sla_forward / sla_backward with batch size 1 and T = p->T
+ * One fused pass per sequence and slice (p->segments > 1 is SLA_ERR_UNSUPPORTED); empty sequences pass their
+ * state through.  sla_backward_varlen needs sla_backward_varlen_workspace_bytes(p) bytes of workspace.
+ */
+int sla_forward_varlen(const sla_params* p, const void* q, const void* k, const void* v,
+                       const float* q_head_logits, const float* k_head_logits,
+                       const void* log_decay, const float* beta, const int32_t* cu_seqlens,
+                       const float* initial_state, void* out, float* final_state, void* stream);
+int sla_backward_varlen(const sla_params* p, const void* q, const void* k, const void* v,
+                        const float* q_head_logits, const float* k_head_logits, const void* log_decay,
+                        const int32_t* cu_seqlens, const float* initial_state, const void* d_out,
+                        const float* d_final_state, void* dq, void* dk, void* dv, float* dq_head_logits,
+                        float* dk_head_logits, void* dlog_decay, float* d_initial_state,
+                        void* workspace, size_t workspace_bytes, void* stream);
+size_t sla_backward_varlen_workspace_bytes(const sla_params* p);
+
 /* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
 size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 

@@ -23,13 +23,18 @@ from .binding import (  # noqa: F401
     sla_default_dv_split,
     sla_forward,
     sla_forward_ws,
+    sla_forward_varlen,
+    sla_backward_varlen,
+    sla_backward_varlen_workspace_bytes,
     sla_segments,
     sla_workspace_bytes,
     sla_kernel_name,
     sla_status_string,
     sla_version,
     forward,
+    forward_varlen,
     backward,
+    backward_varlen,
     gate_logits,
     decode_step,
 )

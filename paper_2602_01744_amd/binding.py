@@ -63,6 +63,12 @@ def load_library():
     lib.sla_forward_ws.argtypes = [pp] + [vp] * 11 + [ctypes.c_size_t, vp]
     lib.sla_decode_step.restype = ctypes.c_int
     lib.sla_decode_step.argtypes = [pp] + [vp] * 10
+    lib.sla_forward_varlen.restype = ctypes.c_int
+    lib.sla_forward_varlen.argtypes = [pp] + [vp] * 12
+    lib.sla_backward_varlen.restype = ctypes.c_int
+    lib.sla_backward_varlen.argtypes = [pp] + [vp] * 18 + [ctypes.c_size_t, vp]
+    lib.sla_backward_varlen_workspace_bytes.restype = ctypes.c_size_t
+    lib.sla_backward_varlen_workspace_bytes.argtypes = [pp]
     lib.sla_gate_logits.restype = ctypes.c_int
     lib.sla_gate_logits.argtypes = [pp] + [vp] * 7
     lib.sla_backward.restype = ctypes.c_int
@@ -160,6 +166,89 @@ def sla_decode_step(params, q, k, v, q_head_logits, k_head_logits, log_decay, be
             _p(out), _p(stream),
         )
     )
+
+
+def sla_forward_varlen(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, cu_seqlens, initial_state, out,
+                       final_state, stream) -> int:
+    """Raw call of the packed variable-length forward (same conventions as sla_forward)."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(load_library().sla_forward_varlen(
+        pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta), _p(cu_seqlens),
+        _p(initial_state), _p(out), _p(final_state), _p(stream)))
+
+
+def sla_backward_varlen_workspace_bytes(params: SlaParams) -> int:
+    return int(load_library().sla_backward_varlen_workspace_bytes(ctypes.byref(params)))
+
+
+def sla_backward_varlen(params, q, k, v, q_head_logits, k_head_logits, log_decay, cu_seqlens, initial_state, d_out,
+                        d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, d_initial_state,
+                        workspace, workspace_bytes, stream) -> int:
+    """Raw call of the packed variable-length backward (same conventions as sla_backward)."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(load_library().sla_backward_varlen(
+        pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(cu_seqlens),
+        _p(initial_state), _p(d_out), _p(d_final_state), _p(dq), _p(dk), _p(dv), _p(dq_head_logits),
+        _p(dk_head_logits), _p(dlog_decay), _p(d_initial_state), _p(workspace), int(workspace_bytes), _p(stream)))
+
+
+def forward_varlen(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, beta, cu_seqlens,
+                   initial_state=None, *, want_final_state: bool = True):
+    """Packed sequences: q, k [T,H,dk], v [T,H,dv], logits (beta, GDN decay) [T,H], cu_seqlens int32 [B+1] on the
+    device, initial_state [B,H,dk,dv] or None.  Returns (out [T,H,dv], final_state [B,H,dk,dv] or None)."""
+    import torch
+
+    assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert cu_seqlens.is_cuda and cu_seqlens.dtype == torch.int32 and cu_seqlens.dim() == 1 and cu_seqlens.is_contiguous()
+    B = cu_seqlens.numel() - 1
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+    out = torch.empty((T, H, dv), dtype=q.dtype, device=q.device)
+    fin = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
+    params = SlaParams(variant, dtype, B, T, H, dk, dv, 0, 0, 1)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_forward_varlen(params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay),
+                            ptr(beta), ptr(cu_seqlens), ptr(initial_state), ptr(out), ptr(fin),
+                            torch.cuda.current_stream(q.device).cuda_stream)
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return out, fin
+
+
+def backward_varlen(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_out, cu_seqlens,
+                    initial_state=None, d_final_state=None, *, want_d_initial_state: bool = False):
+    """Gradients of ``forward_varlen`` (RetNet, GLA; bfloat16); tensors packed as there.  Returns a dict as
+    ``backward`` does, with d_initial_state [B,H,dk,dv]."""
+    import torch
+
+    assert q.is_cuda and q.dtype == torch.bfloat16
+    T, H, dk = q.shape
+    dv = v.shape[-1]
+    B = cu_seqlens.numel() - 1
+    dev = q.device
+    g = {
+        "dq": torch.empty_like(q),
+        "dk": torch.empty_like(k),
+        "dv": torch.empty_like(v),
+        "dq_head_logits": torch.empty_like(q_head_logits),
+        "dk_head_logits": None if k_head_logits is None else torch.empty_like(k_head_logits),
+        "dlog_decay": torch.empty_like(log_decay) if variant == GLA else None,
+        "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
+    }
+    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, 0, 1)
+    need = sla_backward_varlen_workspace_bytes(params)
+    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_backward_varlen(
+        params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(cu_seqlens),
+        ptr(initial_state), ptr(d_out), ptr(d_final_state), ptr(g["dq"]), ptr(g["dk"]), ptr(g["dv"]),
+        ptr(g["dq_head_logits"]), ptr(g["dk_head_logits"]), ptr(g["dlog_decay"]), ptr(g["d_initial_state"]),
+        ptr(workspace), workspace.numel(), torch.cuda.current_stream(dev).cuda_stream,
+    )
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return g
 
 
 def sla_gate_logits(params, q, k, w_gq, w_gk, q_head_logits, k_head_logits, stream) -> int:

@@ -9,12 +9,12 @@
 namespace sla {
 int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k, const void* v,
                    const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
-                   float* sT, float* workspace, hipStream_t stream);
+                   float* sT, float* workspace, const int* cu, hipStream_t stream);
 size_t segment_workspace_floats(const sla_params& p, int nseg);
-size_t backward_workspace_floats(const sla_params& p);
+size_t backward_workspace_floats(const sla_params& p, bool packed);
 int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                     const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
-                    float* dql, float* dkl, void* dld, float* ds0, float* ws, hipStream_t stream);
+                    float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu, hipStream_t stream);
 int launch_gate_logits(const sla_params& p, const void* q, const void* k, const float* wq, const float* wk, float* ql,
                        float* kl, int compute_units, hipStream_t stream);
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
@@ -154,7 +154,25 @@ int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void
     }
     const int dvw = choose_dv_split(*p, cus, nseg);
     return sla::launch_forward(*p, dvw, nseg, seg_len, q, k, v, q_head_logits, k_head_logits, log_decay, beta,
-                               initial_state, out, final_state, (float*)workspace, (hipStream_t)stream);
+                               initial_state, out, final_state, (float*)workspace, nullptr, (hipStream_t)stream);
+}
+
+int sla_forward_varlen(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                       const float* k_head_logits, const void* log_decay, const float* beta,
+                       const int32_t* cu_seqlens, const float* initial_state, void* out, float* final_state,
+                       void* stream) {
+    const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state);
+    if (rc != SLA_OK) return rc;
+    if (p->segments > 1) return SLA_ERR_UNSUPPORTED;
+    if (p->B > 0 && !cu_seqlens) return SLA_ERR_NULL;
+    if (cu_seqlens && (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u)) return SLA_ERR_ALIGN;
+    if (p->B == 0) return SLA_OK;
+    if (p->T == 0 && !final_state) return SLA_OK;
+    const int cus = device_compute_units();
+    if (cus <= 0) return SLA_ERR_HIP;
+    const int dvw = choose_dv_split(*p, cus, 1);
+    return sla::launch_forward(*p, dvw, 1, p->T, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state,
+                               out, final_state, nullptr, p->T == 0 ? nullptr : cu_seqlens, (hipStream_t)stream);
 }
 
 int sla_forward(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
@@ -176,11 +194,11 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
                               (hipStream_t)stream);
 }
 
-int sla_backward(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
-                 const float* k_head_logits, const void* log_decay, const float* initial_state, const void* d_out,
-                 const float* d_final_state, void* dq, void* dk, void* dv, float* dq_head_logits,
-                 float* dk_head_logits, void* dlog_decay, float* d_initial_state, void* workspace,
-                 size_t workspace_bytes, void* stream) {
+static int backward_impl(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                         const float* k_head_logits, const void* log_decay, const float* initial_state,
+                         const void* d_out, const float* d_final_state, void* dq, void* dk, void* dv,
+                         float* dq_head_logits, float* dk_head_logits, void* dlog_decay, float* d_initial_state,
+                         void* workspace, size_t workspace_bytes, const int32_t* cu, bool packed, void* stream) {
     int rc = check_params(p);
     if (rc != SLA_OK) return rc;
     if (p->variant == SLA_GDN || p->dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
@@ -191,16 +209,40 @@ int sla_backward(const sla_params* p, const void* q, const void* k, const void* 
     }
     if (p->variant == SLA_RETNET && dlog_decay) return SLA_ERR_NULL;
     if ((k_head_logits != nullptr) != (dk_head_logits != nullptr)) return SLA_ERR_NULL;
+    if (packed && p->B > 0 && !cu) return SLA_ERR_NULL;
     const void* ptrs[] = {q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out, d_final_state,
                           dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, d_initial_state, workspace};
     for (const void* x : ptrs)
         if (x && !aligned16(x)) return SLA_ERR_ALIGN;
+    if (cu && (reinterpret_cast<uintptr_t>(cu) & 3u)) return SLA_ERR_ALIGN;
     if (p->B == 0) return SLA_OK;
     if (p->T == 0 && !d_initial_state) return SLA_OK;
-    if (!workspace || sla::backward_workspace_floats(*p) * sizeof(float) > workspace_bytes) return SLA_ERR_WORKSPACE;
+    if (!workspace || sla::backward_workspace_floats(*p, packed) * sizeof(float) > workspace_bytes)
+        return SLA_ERR_WORKSPACE;
     return sla::launch_backward(*p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out,
                                 d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
-                                d_initial_state, (float*)workspace, (hipStream_t)stream);
+                                d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr,
+                                (hipStream_t)stream);
+}
+
+int sla_backward(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                 const float* k_head_logits, const void* log_decay, const float* initial_state, const void* d_out,
+                 const float* d_final_state, void* dq, void* dk, void* dv, float* dq_head_logits,
+                 float* dk_head_logits, void* dlog_decay, float* d_initial_state, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    return backward_impl(p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out, d_final_state, dq,
+                         dk, dv, dq_head_logits, dk_head_logits, dlog_decay, d_initial_state, workspace,
+                         workspace_bytes, nullptr, false, stream);
+}
+
+int sla_backward_varlen(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                        const float* k_head_logits, const void* log_decay, const int32_t* cu_seqlens,
+                        const float* initial_state, const void* d_out, const float* d_final_state, void* dq, void* dk,
+                        void* dv, float* dq_head_logits, float* dk_head_logits, void* dlog_decay,
+                        float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out, d_final_state, dq,
+                         dk, dv, dq_head_logits, dk_head_logits, dlog_decay, d_initial_state, workspace,
+                         workspace_bytes, cu_seqlens, true, stream);
 }
 
 int sla_gate_logits(const sla_params* p, const void* q, const void* k, const float* w_gq, const float* w_gk,
@@ -221,7 +263,12 @@ int sla_gate_logits(const sla_params* p, const void* q, const void* k, const flo
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {
     if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16) return 0;
-    return sla::backward_workspace_floats(*p) * sizeof(float);
+    return sla::backward_workspace_floats(*p, false) * sizeof(float);
+}
+
+size_t sla_backward_varlen_workspace_bytes(const sla_params* p) {
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16) return 0;
+    return sla::backward_workspace_floats(*p, true) * sizeof(float);
 }
 
 size_t sla_workspace_bytes(const sla_params* p, int compute_units) {

@@ -72,6 +72,8 @@ struct BArgs {
     float* qdq;              // [B,T,H,dk] fp32 q * dq (GLA)
     float* corr;             // [B,H,dk] rowsum(dS_T * S_T) (GLA with a final-state cotangent)
     int B, T, H;
+    size_t rows;             // tokens in all: B * T, or the packed total
+    const int* cu;           // packed variable-length batch: sequence b is tokens cu[b] .. cu[b+1]-1 of T; else null
 };
 
 __device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
@@ -154,11 +156,18 @@ __device__ __forceinline__ u4 keep(u4 x, bool ok) { return u4{ok ? x[0] : 0u, ok
 __device__ __forceinline__ u2 keep(u2 x, bool ok) { return u2{ok ? x[0] : 0u, ok ? x[1] : 0u}; }
 
 // Workgroups are dealt to the eight XCDs round-robin by blockIdx, and each XCD has its own L2.  The slices of one
-// (batch, head) read the same dout / v (or q / k / decay) rows, so they are given consecutive places on ONE XCD:
-// the grid is padded to a multiple of eight and place p of XCD x is logical workgroup x * (grid / 8) + p.
-__device__ __forceinline__ int logical_workgroup() {
-    const int per = gridDim.x >> 3;
-    return (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+// (batch, head) read the same dout / v (or q / k / decay) rows, so they always share an XCD.  Rectangular batches
+// give every XCD a contiguous range of (batch, head) pairs; packed batches deal the pairs round-robin over the
+// XCDs, so the heads of one long sequence are spread over all of them.  The grid is 8 * slices * ceil(pairs / 8);
+// returns pair * slices + slice, or -1 for the padding.
+__device__ __forceinline__ int logical_workgroup(int slices, int pairs, bool packed) {
+    const int xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
+    if (packed) {
+        const int pair = (place / slices) * 8 + xcd;
+        return pair < pairs ? pair * slices + place % slices : -1;
+    }
+    const int wg = xcd * (gridDim.x >> 3) + place;
+    return wg < pairs * slices ? wg : -1;
 }
 
 // Sum over the four 16-lane rows of a wave, returned in every lane: two register swaps (odd rows against even
@@ -321,11 +330,18 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: role branches are uniform
     const int r = lane & 15, g = lane >> 4;
-    const int wg = logical_workgroup();
-    if (wg >= a.B * a.H * NSL) return;
+    const int wg = logical_workgroup(NSL, a.B * a.H, a.cu != nullptr);
+    if (wg < 0) return;
     const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
-    const int T = a.T, H = a.H;
+    const int H = a.H;
+    int T = a.T;                    // tokens of this sequence and the index of its first token
+    size_t tok0 = (size_t)b * a.T;
+    if (a.cu) {  // packed sequences; offsets are clamped into the tensors whatever cu holds
+        const int start = min(max(a.cu[b], 0), a.T), end = min(max(a.cu[b + 1], start), a.T);
+        T = end - start;
+        tok0 = (size_t)start;
+    }
     const int nb = (T + kTok - 1) / kTok;
     const Ring ring = ring_init(smem, L::bytes, tid);
 
@@ -338,7 +354,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
             producer_run<PreKeys<2>>(
                 ring, smem, L::bytes, team, nb,
                 [&](int blk, PreKeys<2>& p) {
-                    const size_t row = ((size_t)b * T + min(blk * kTok + t, T - 1)) * H + h;
+                    const size_t row = (tok0 + min(blk * kTok + t, T - 1)) * H + h;
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
@@ -388,7 +404,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
                         const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
-                        const size_t row = ((size_t)b * T + min(blk * kTok + t, T - 1)) * H + h;
+                        const size_t row = (tok0 + min(blk * kTok + t, T - 1)) * H + h;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
                     }
@@ -461,8 +477,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
         part = reduce_groups(part);
         const int tok = t0 + r;
         if (tok < T) {
-            const size_t row = ((size_t)b * T + tok) * H + h;
-            if (g == 0) a.part_q[((size_t)(slice * 4 + wave) * a.B * T * H) + row] = part;
+            const size_t row = (tok0 + tok) * H + h;
+            if (g == 0) a.part_q[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
             float dqv[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) dqv[i] = gq * dqp[i];
@@ -524,11 +540,18 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
-    const int wg = logical_workgroup();
-    if (wg >= a.B * a.H * NSL) return;
+    const int wg = logical_workgroup(NSL, a.B * a.H, a.cu != nullptr);
+    if (wg < 0) return;
     const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
-    const int T = a.T, H = a.H;
+    const int H = a.H;
+    int T = a.T;                    // tokens of this sequence and the index of its first token
+    size_t tok0 = (size_t)b * a.T;
+    if (a.cu) {  // packed sequences; offsets are clamped into the tensors whatever cu holds
+        const int start = min(max(a.cu[b], 0), a.T), end = min(max(a.cu[b + 1], start), a.T);
+        T = end - start;
+        tok0 = (size_t)start;
+    }
     const int nb = (T + kTok - 1) / kTok;
     const Ring ring = ring_init(smem, L::bytes, tid);
 
@@ -540,7 +563,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
             producer_run<PreKeysE>(
                 ring, smem, L::bytes, team, nb,
                 [&](int I, PreKeysE& p) {
-                    const size_t row = ((size_t)b * T + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
+                    const size_t row = (tok0 + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
@@ -591,7 +614,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
                         const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
-                        const size_t row = ((size_t)b * T + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
+                        const size_t row = (tok0 + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
                         p.gq[rep] = a.gq[row];
@@ -676,7 +699,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         for (int i = 0; i < 4; ++i) dkv[i] = gk * (Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]));
         const int tok = t0 + r;
         const bool ok = tok < T;
-        const size_t row = ((size_t)b * T + (ok ? tok : 0)) * H + h;
+        const size_t row = (tok0 + (ok ? tok : 0)) * H + h;
         if (ok) *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
         if constexpr (VAR == SLA_GLA) {
             const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
@@ -735,11 +758,18 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
-    const int wg = logical_workgroup();
-    if (wg >= a.B * a.H * NSL) return;
+    const int wg = logical_workgroup(NSL, a.B * a.H, a.cu != nullptr);
+    if (wg < 0) return;
     const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
     const int sbase = slice * kCols;
-    const int T = a.T, H = a.H;
+    const int H = a.H;
+    int T = a.T;                    // tokens of this sequence and the index of its first token
+    size_t tok0 = (size_t)b * a.T;
+    if (a.cu) {  // packed sequences; offsets are clamped into the tensors whatever cu holds
+        const int start = min(max(a.cu[b], 0), a.T), end = min(max(a.cu[b + 1], start), a.T);
+        T = end - start;
+        tok0 = (size_t)start;
+    }
     const int nb = (T + kTok - 1) / kTok;
     const Ring ring = ring_init(smem, L::bytes, tid);
 
@@ -754,7 +784,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
             ring, smem, L::bytes, team, nb,
             [&](int I, PreVals<N>& p) {
                 const int t0 = (nb - 1 - I) * kTok;
-                const size_t row = ((size_t)b * T + min(t0 + t, T - 1)) * H + h;
+                const size_t row = (tok0 + min(t0 + t, T - 1)) * H + h;
 #pragma unroll
                 for (int j = 0; j < N; ++j) {
                     if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
@@ -765,7 +795,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
 #pragma unroll
                 for (int rep = 0; rep < 2; ++rep) {
                     const int c = lane + 64 * rep, st = c >> 3, se8 = c & 7;
-                    const size_t srow = ((size_t)b * T + min(t0 + st, T - 1)) * H + h;
+                    const size_t srow = (tok0 + min(t0 + st, T - 1)) * H + h;
                     p.sl[rep] = load16(slice_src + srow * DV + 8 * se8);
                     p.gq[rep] = a.gq[srow];
                 }
@@ -875,8 +905,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
         part = reduce_groups(part);
         const int tok = t0 + r;
         if (tok < T) {
-            const size_t row = ((size_t)b * T + tok) * H + h;
-            if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.B * T * H) + row] = part;
+            const size_t row = (tok0 + tok) * H + h;
+            if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
             *(u2*)(a.dv + row * DV + sbase + cb + 4 * g) =
                 u2{pack2(gk * dvp[0], gk * dvp[1]), pack2(gk * dvp[2], gk * dvp[3])};
         }
@@ -977,10 +1007,10 @@ int launch_sweeps(const BArgs& a, hipStream_t stream) {
     }
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kBwdThreads);
-    auto padded = [](unsigned n) { return dim3((n + 7u) & ~7u); };  // see logical_workgroup()
-    hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), padded(bh * (DK / kCols)), block, (size_t)ldsF, stream, a);
-    hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), padded(bh * (DV / kCols)), block, (size_t)ldsV, stream, a);
-    hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), padded(bh * (DK / kCols)), block, (size_t)ldsK, stream, a);
+    auto grid = [bh](unsigned slices) { return dim3(((bh + 7u) / 8u) * 8u * slices); };  // see logical_workgroup()
+    hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), grid(DK / kCols), block, (size_t)ldsF, stream, a);
+    hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), grid(DV / kCols), block, (size_t)ldsV, stream, a);
+    hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), grid(DK / kCols), block, (size_t)ldsK, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
@@ -1007,17 +1037,18 @@ int launch_dk(const BArgs& a, int dk, int dv, hipStream_t stream) {
 
 // Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q (dk/16 planes) and dG^K (dv/16 planes); for GLA
 // q*dq [B,T,H,dk] and the final-state term of dlog_decay [B,H,dk].
-size_t backward_workspace_floats(const sla_params& p) {
-    const size_t n = round4((size_t)p.B * p.T * p.H);
+size_t backward_workspace_floats(const sla_params& p, bool packed) {
+    const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T;
+    const size_t n = round4(rows * p.H);
     size_t total = n * (2 + p.dk / 16 + p.dv / 16);
-    if (p.variant == SLA_GLA) total += round4((size_t)p.B * p.T * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk);
+    if (p.variant == SLA_GLA) total += round4(rows * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk);
     return total;
 }
 
 int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                     const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
-                    float* dql, float* dkl, void* dld, float* ds0, float* ws, hipStream_t stream) {
-    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H);
+                    float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu, hipStream_t stream) {
+    const size_t rows = cu ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
     BArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
     a.ld = p.variant == SLA_GLA ? (const uint16_t*)ld : nullptr;
@@ -1035,7 +1066,7 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
     }
     a.s0 = s0; a.dsf = dsf;
     a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.dld = (uint16_t*)dld; a.ds0 = ds0;
-    a.B = p.B; a.T = p.T; a.H = p.H;
+    a.B = p.B; a.T = p.T; a.H = p.H; a.rows = rows; a.cu = cu;
 
     const unsigned eb = kEwThreads, per = eb / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
     if (rows > 0) {

@@ -79,6 +79,9 @@ struct KArgs {
     int nparts;  // producer waves of the pre-pass: partial decay products per segment in ws_decay
     float* ws_state;
     float* ws_decay;
+    // Packed variable-length batch: B sequences laid end to end in tensors of T tokens in all; sequence b covers
+    // tokens cu[b] .. cu[b + 1] - 1.  Null for the rectangular layout.
+    const int* cu;
 };
 
 #ifdef SLA_TRACE
@@ -1031,19 +1034,34 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
     if (tid < 2 * kMaxSlots) ready[tid] = 0;
     __syncthreads();
 
-    // Workgroup -> (batch, head, value slice).  Consecutive hardware ids go to different XCDs
-    // (id % 8), so the slices of one head -- which read the same q, k, decay and logits -- are given
-    // ids 8 apart: same XCD, hence same L2.
-    const int total = gridDim.x;
-    const int id = blockIdx.x;
-    const int logical = (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
-    const int slice = logical % a.nslice, rowh = logical / a.nslice;
+    // Workgroup -> (batch row, head, value slice).  Consecutive hardware ids go to different XCDs (id % 8),
+    // each with its own L2; the grid is padded to a multiple of 8 * nslice and ids past the last pair have
+    // nothing to do.  The slices of one (row, head) read the same q, k, decay and logits, so they always share
+    // an XCD.  Rectangular batches give every XCD a contiguous range of (row, head) pairs (the heads of a token
+    // also share its logits).  Packed batches deal the pairs round-robin over the XCDs instead: the heads of one
+    // long sequence would otherwise pile onto a single XCD's share of the memory bandwidth while the others idle.
+    const int xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
+    int slice, rowh;
+    if (a.cu) {
+        slice = place % a.nslice;
+        rowh = (place / a.nslice) * 8 + xcd;
+    } else {
+        const int logical = xcd * (gridDim.x >> 3) + place;
+        slice = logical % a.nslice;
+        rowh = logical / a.nslice;
+    }
+    if (rowh >= a.B * a.nseg_grid * a.H) return;
     const int row = rowh / a.H, h = rowh % a.H;          // row = (batch, segment)
     const int b = row / a.nseg_grid, seg = row % a.nseg_grid;
     const int n0 = slice * DVW;
     const int H = a.H, dv = a.dv;
-    const int T = min(a.Ls, a.T - seg * a.Ls);            // tokens of this row
-    const size_t row_tok = (size_t)b * a.T + (size_t)seg * a.Ls;
+    int T = min(a.Ls, a.T - seg * a.Ls);                  // tokens of this row
+    size_t row_tok = (size_t)b * a.T + (size_t)seg * a.Ls;
+    if (a.cu) {  // packed sequences (one segment each); offsets are clamped into the tensors whatever cu holds
+        const int start = min(max(a.cu[b], 0), a.T), end = min(max(a.cu[b + 1], start), a.T);
+        T = end - start;
+        row_tok = (size_t)start;
+    }
     const int nblocks = (T + kBlock - 1) / kBlock;
 
     if (producer) {
@@ -1142,7 +1160,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             SLA_STAMP(3);
             SLA_FLUSH(I);
         };
-        flag_wait(ready, 1);
+        if (nblocks > 0) flag_wait(ready, 1);
         load_block_frags<P, VAR, DK, DVW, SO>(fa, smem, cw, lane);
         seen = flag_peek(ready + (1 & (NP - 1)));
         for (int I = 0; I < nblocks; I += 2) {
@@ -1174,7 +1192,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             SLA_STAMP(3);
             SLA_FLUSH(I);
         };
-        flag_wait(ready, 1);
+        if (nblocks > 0) flag_wait(ready, 1);
         load_block_frags<P, VAR, DK, DVW, SO, 1>(fa, smem, cw, lane);
         seen = flag_peek(ready + (1 & (NP - 1)));
         for (int I = 0; I < nblocks; I += 2) {
@@ -1214,7 +1232,8 @@ static int launch_one(const KArgs& a, hipStream_t stream) {
         }
         configured = true;
     }
-    const int grid = a.B * a.nseg_grid * a.H * a.nslice;
+    const int pairs = a.B * a.nseg_grid * a.H;
+    const int grid = ((pairs + 7) / 8) * 8 * a.nslice;  // see the workgroup mapping in the kernel
     hipLaunchKernelGGL(kern, dim3(grid), dim3(L::threads), lds, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
@@ -1317,13 +1336,14 @@ size_t segment_workspace_floats(const sla_params& p, int nseg) {
 
 int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k, const void* v,
                    const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
-                   float* sT, float* workspace, hipStream_t stream) {
+                   float* sT, float* workspace, const int* cu, hipStream_t stream) {
     KArgs a;
     a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = beta; a.s0 = s0; a.out = out; a.sT = sT;
     a.B = p.B; a.T = p.T; a.H = p.H; a.dv = p.dv; a.nslice = p.dv / dvw;
     a.nseg = nseg; a.nseg_grid = nseg; a.nparts = 0; a.Ls = nseg > 1 ? seg_len : p.T;
     a.ws_state = workspace;
     a.ws_decay = workspace ? workspace + (size_t)p.B * nseg * p.H * p.dk * p.dv : nullptr;
+    a.cu = cu;
     if (p.T == 0) {
         if (!sT) return SLA_OK;
         const size_t n = (size_t)p.B * p.H * p.dk * p.dv;

@@ -233,3 +233,25 @@ def gate_weights(H: int, dk: int, seed: int) -> Dict[str, np.ndarray]:
     rng = np.random.default_rng(seed)
     return {"w_gq": rng.standard_normal(size=(H, dk), dtype=np.float32),
             "w_gk": rng.standard_normal(size=(H, dk), dtype=np.float32)}
+
+
+def packed_lengths(total: int, seed: int, longest: int = 4096, shortest: int = 64) -> np.ndarray:
+    """A seeded mix of sequence lengths that sums to ``total``: powers of two between ``shortest`` and
+    ``longest`` drawn with probability proportional to 1/length until the budget is used, the remainder as one last
+    sequence; sorted longest first.  Stands in for packing documents of mixed length into a 2K-8K token budget
+    (Sec. 5.2 trains on 4K contexts, Sec. 5.3 evaluates 1K-8K)."""
+    rng = np.random.default_rng(seed)
+    sizes = []
+    s = shortest
+    while s <= longest:
+        sizes.append(s)
+        s *= 2
+    sizes = np.array(sizes)
+    prob = (1.0 / sizes) / np.sum(1.0 / sizes)
+    out, left = [], int(total)
+    while left > 0:
+        n = int(rng.choice(sizes, p=prob))
+        n = min(n, left)
+        out.append(n)
+        left -= n
+    return np.array(sorted(out, reverse=True), dtype=np.int32)

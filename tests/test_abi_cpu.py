@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_gate_logits", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_gate_logits", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -215,3 +215,21 @@ def test_gate_logits_rejects_bad_calls(lib):
     assert call(_ok_params(dk=32)) == -3
     assert call(None) == -1
     assert call(_ok_params(B=0)) == 0 and call(_ok_params(T=0)) == 0
+
+
+def test_varlen_rejects_bad_calls(lib):
+    ok = _ok_params()
+    fwd = lambda p, cu=A, q=A: sla.sla_forward_varlen(p, q, A, A, A, A, A, 0, cu, 0, A, A, 0)
+    assert fwd(ok, cu=0) == -1                       # the offsets are required
+    assert fwd(ok, cu=A + 2) == -4
+    assert fwd(ok, q=0) == -1
+    assert fwd(_ok_params(segments=3)) == -3         # packed batches run one pass per sequence
+    assert fwd(_ok_params(B=0), cu=0) == 0
+    bwd = lambda p, cu=A: sla.sla_backward_varlen(p, A, A, A, A, A, A, cu, 0, A, 0, A, A, A, A, A, A, 0, A, 1 << 40, 0)
+    assert bwd(ok, cu=0) == -1
+    assert bwd(_ok_params(variant=sla.GDN)) == -3
+    # the packed workspace is sized by the total token count p->T, not B * T
+    p = _ok_params(B=5, T=1000)
+    one = _ok_params(B=1, T=1000)
+    extra = 4 * (5 - 1) * p.H * p.dk  # one [H,dk] row of final-state terms per sequence
+    assert sla.sla_backward_varlen_workspace_bytes(p) == sla.sla_backward_workspace_bytes(one) + extra
