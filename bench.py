@@ -577,7 +577,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "traffic": None if args.varlen else MEASURED_TRAFFIC_BYTES.get(w.name),
             "kernel_us": kernel_ms * 1e3,
             "kernel_us_min": float(np.min(per_launch_ms)) * 1e3,
             "algorithmic_bytes": abytes,
