@@ -84,3 +84,56 @@ def test_decode_steps_replay_identically():
     graph.replay()
     torch.cuda.synchronize()
     assert torch.equal(state, eager_state) and torch.equal(out, eager_out)
+
+
+@pytest.mark.parametrize("variant", [RETNET, GLA])
+def test_training_step_replays_identically(variant):
+    """Gate logits, forward and backward captured as one graph (raw entry points, buffers allocated up front); the
+    workspace is dirtied between replays."""
+    import torch
+    import paper_2602_01744_amd as sla
+
+    B, T, H, dk, dv = 2, 300, 4, 128, 128
+    d = si.custom(variant, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=2900 + variant)
+    g = _forward_args(variant, d, "bf16")
+    gw = si.gate_weights(H, dk, seed=2901)
+    wq, wk = torch.from_numpy(gw["w_gq"]).cuda(), torch.from_numpy(gw["w_gk"]).cuda()
+    dout = torch.from_numpy(si.cotangents(B, T, H, dk, dv, seed=2902)["d_out"]).to(torch.bfloat16).cuda()
+    p = sla.SlaParams(variant, sla.BF16, B, T, H, dk, dv, 0, 0, 1)
+    ql = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+    kl = torch.empty_like(ql)
+    out = torch.empty_like(g["v"])
+    fin = torch.empty((B, H, dk, dv), dtype=torch.float32, device="cuda")
+    grads = [torch.empty_like(g["q"]), torch.empty_like(g["k"]), torch.empty_like(g["v"]), torch.empty_like(ql),
+             torch.empty_like(kl)]
+    dld = torch.empty_like(g["log_decay"]) if variant == GLA else None
+    ws = torch.empty(sla.sla_backward_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    ptr = lambda t: None if t is None else t.data_ptr()
+
+    def step(stream):
+        assert sla.sla_gate_logits(p, ptr(g["q"]), ptr(g["k"]), ptr(wq), ptr(wk), ptr(ql), ptr(kl), stream) == 0
+        assert sla.sla_forward(p, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]), None,
+                               None, ptr(out), ptr(fin), stream) == 0
+        assert sla.sla_backward(p, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]), None,
+                                ptr(dout), None, *(ptr(t) for t in grads), ptr(dld), None, ptr(ws), ws.numel(),
+                                stream) == 0
+
+    step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    everything = [ql, kl, out, fin] + grads + ([dld] if dld is not None else [])
+    ref = [t.clone() for t in everything]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(side.cuda_stream)
+    for rep in range(3):
+        for t in everything:
+            t.zero_()
+        ws.fill_(rep + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, r in zip(everything, ref):
+            assert torch.equal(t, r), f"replay {rep}"
