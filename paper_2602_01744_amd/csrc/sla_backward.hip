@@ -348,8 +348,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     if (wave >= kConsumers) {
         const int team = (wave - kConsumers) >> 1;
         if (((wave - kConsumers) & 1) == 0) {
-            // decay, keys and queries of the slice: token t = lane % 16, columns 16 (lane / 16) ... + 15
-            const int t = r, d0 = sbase + 16 * g;
+            // decay, keys and queries of the slice: token t = lane % 16, columns 8 (lane / 16) + 32 j ... + 7
+            const int t = r, d0 = sbase + 8 * g;  // piece j adds 32 columns: a store instruction's four lane groups sit 8 columns apart, on disjoint banks
             const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
             producer_run<PreKeys<2>>(
                 ring, smem, L::bytes, team, nb,
@@ -357,9 +357,9 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
                     const size_t row = (tok0 + min(blk * kTok + t, T - 1)) * H + h;
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
-                        p.kx[j] = load16(a.k + row * DK + d0 + 8 * j);
-                        p.qx[j] = load16(a.q + row * DK + d0 + 8 * j);
+                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 32 * j);
+                        p.kx[j] = load16(a.k + row * DK + d0 + 32 * j);
+                        p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
                     }
                     p.gk = a.gk[row];
                     p.gq = a.gq[row];
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
                     const float gk = ok ? p.gk : 0.f;
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        const int c0 = 16 * g + 8 * j;
+                        const int c0 = 8 * g + 32 * j;
                         const u4 kx = keep(p.kx[j], ok);
                         float c[8], tot[8];
                         block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
                 [&](int blk, PreRows<R>& p) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
                         const size_t row = (tok0 + min(blk * kTok + t, T - 1)) * H + h;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
                 [&](int blk, const PreRows<R>& p, unsigned char* buf) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
                         const bool ok = blk * kTok + t < T;
                         const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
                         put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     if (wave >= kConsumers) {  // block number I of the sweep covers tokens (nb - 1 - I) * 16 ...
         const int team = (wave - kConsumers) >> 1;
         if (((wave - kConsumers) & 1) == 0) {
-            const int t = r, d0 = sbase + 16 * g;
+            const int t = r, d0 = sbase + 8 * g;  // piece j adds 32 columns: a store instruction's four lane groups sit 8 columns apart, on disjoint banks
             const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
             producer_run<PreKeysE>(
                 ring, smem, L::bytes, team, nb,
@@ -566,13 +566,13 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                     const size_t row = (tok0 + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
-                        p.kx[j] = load16(a.k + row * DK + d0 + 8 * j);
-                        p.qx[j] = load16(a.q + row * DK + d0 + 8 * j);
+                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 32 * j);
+                        p.kx[j] = load16(a.k + row * DK + d0 + 32 * j);
+                        p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
                     }
                     if constexpr (VAR == SLA_GLA) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) p.e[j] = *(const f4*)(a.qdq + row * DK + d0 + 4 * j);
+                        for (int j = 0; j < 4; ++j) p.e[j] = *(const f4*)(a.qdq + row * DK + d0 + 32 * (j >> 1) + 4 * (j & 1));
                     }
                     p.gk = a.gk[row];
                     p.gq = a.gq[row];
@@ -580,13 +580,14 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                 [&](int I, const PreKeysE& p, unsigned char* buf) {
                     const bool ok = (nb - 1 - I) * kTok + t < T;
                     if constexpr (VAR == SLA_GLA) {
-                        float* qd = (float*)(buf + L::oQDQ) + t * kFS + 16 * g;
+                        float* qd = (float*)(buf + L::oQDQ) + t * kFS + 8 * g;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) *(f4*)(qd + 4 * j) = ok ? p.e[j] : f4{0.f, 0.f, 0.f, 0.f};
+                        for (int j = 0; j < 4; ++j)
+                            *(f4*)(qd + 32 * (j >> 1) + 4 * (j & 1)) = ok ? p.e[j] : f4{0.f, 0.f, 0.f, 0.f};
                     }
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        const int c0 = 16 * g + 8 * j;
+                        const int c0 = 8 * g + 32 * j;
                         float c[8], tot[8];
                         block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
                         float* cum = (float*)(buf + L::oCUM) + t * kFS + c0;
@@ -613,7 +614,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                 [&](int I, PreRows<R>& p) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
                         const size_t row = (tok0 + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                 [&](int I, const PreRows<R>& p, unsigned char* buf) {
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
-                        const int c = lane + 64 * rep, t = c / (DV / 8), e8 = c % (DV / 8);
+                        const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
                         const bool ok = (nb - 1 - I) * kTok + t < T;
                         const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
                         put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
@@ -774,10 +775,10 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     const Ring ring = ring_init(smem, L::bytes, tid);
 
     if (wave >= kConsumers) {
-        // member m: key columns m DK/2 + (DK/8) (lane / 16) ..., token lane % 16; member 0 also stages the slice of
+        // member m: key columns m DK/2 + 8 (lane / 16) + 32 j ..., token lane % 16; member 0 also stages the slice of
         // dout (gated, transposed), member 1 the slice of v: two 16-byte pieces per lane each
         const int team = (wave - kConsumers) >> 1, m = (wave - kConsumers) & 1;
-        const int t = r, d0 = m * (DK / 2) + (DK / 8) * g;
+        const int t = r, d0 = m * (DK / 2) + 8 * g;  // piece j adds 32 columns
         const uint16_t* slice_src = (m ? a.v : a.dout) + sbase;
         const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
         producer_run<PreVals<N>>(
@@ -787,14 +788,14 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                 const size_t row = (tok0 + min(t0 + t, T - 1)) * H + h;
 #pragma unroll
                 for (int j = 0; j < N; ++j) {
-                    if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 8 * j);
-                    p.kx[j] = load16(a.k + row * DK + d0 + 8 * j);
-                    p.qx[j] = load16(a.q + row * DK + d0 + 8 * j);
+                    if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 32 * j);
+                    p.kx[j] = load16(a.k + row * DK + d0 + 32 * j);
+                    p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
                 }
                 p.gk = a.gk[row];
 #pragma unroll
                 for (int rep = 0; rep < 2; ++rep) {
-                    const int c = lane + 64 * rep, st = c >> 3, se8 = c & 7;
+                    const int st = r, se8 = g + 4 * rep;
                     const size_t srow = (tok0 + min(t0 + st, T - 1)) * H + h;
                     p.sl[rep] = load16(slice_src + srow * DV + 8 * se8);
                     p.gq[rep] = a.gq[srow];
@@ -805,7 +806,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                 const bool ok = t0 + t < T;
 #pragma unroll
                 for (int j = 0; j < N; ++j) {
-                    const int c0 = d0 + 8 * j;
+                    const int c0 = d0 + 32 * j;
                     float c[8], tot[8];
                     block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
                     const u4 qx = keep(p.qx[j], ok), kx = keep(p.kx[j], ok);
@@ -830,7 +831,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                 if (m == 0 && g == 0) ((float*)(buf + L::oGK))[t] = ok ? p.gk : 0.f;
 #pragma unroll
                 for (int rep = 0; rep < 2; ++rep) {
-                    const int c = lane + 64 * rep, st = c >> 3, se8 = c & 7;
+                    const int st = r, se8 = g + 4 * rep;
                     const bool oks = t0 + st < T;
                     const u4 sl = keep(p.sl[rep], oks);
                     if (m == 0) {
