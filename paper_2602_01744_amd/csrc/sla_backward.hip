@@ -68,8 +68,8 @@ struct BArgs {
     uint16_t* dld;
     float* ds0;
     float* part_q;           // [dk/16][B,T,H] partial dG^Q
-    float* part_k;           // [dv/16][B,T,H] partial dG^K
-    float* qdq;              // [B,T,H,dk] fp32 q * dq (GLA)
+    float* part_k;           // [dk/16][B,T,H] partial dG^K
+    float* bsum;             // [blocks][H][dk] fp32: sum of q * dq over each 16-token block (GLA); block id below
     float* corr;             // [B,H,dk] rowsum(dS_T * S_T) (GLA with a final-state cotangent)
     int B, T, H;
     size_t rows;             // tokens in all: B * T, or the packed total
@@ -169,6 +169,10 @@ __device__ __forceinline__ int logical_workgroup(int slices, int pairs, bool pac
     const int wg = xcd * (gridDim.x >> 3) + place;
     return wg < pairs * slices ? wg : -1;
 }
+
+// Identity of a 16-token block in the q * dq block-sum array: sequences need not start on a multiple of 16, so
+// the sequence index is added; ids are unique and at most rows / 16 + B of them exist.
+__device__ __forceinline__ size_t block_id(size_t tok0, int t0, int b) { return (tok0 + (size_t)t0) / kTok + (size_t)b; }
 
 // Sum over the four 16-lane rows of a wave, returned in every lane: two register swaps (odd rows against even
 // rows, then the upper half against the lower half) instead of a trip through LDS.
@@ -274,14 +278,86 @@ struct PreKeys {  // N groups of eight key columns of one token: decay steps, ke
     u4 ld[N], kx[N], qx[N];
     float gq, gk;
 };
-struct PreKeysE : PreKeys<2> {  // ... and the fp32 q * dq of the same 16 columns (dk sweep, GLA)
-    f4 e[4];
+struct PreKeysE : PreKeys<2> {  // ... and, for the dk sweep of GLA, dq of the same 16 columns and the block's q * dq sums
+    u4 dq[2];
+    f4 bs[4];
 };
 template <int N>
 struct PreRows {  // N 16-byte pieces of dout and of v
     u4 a[N], b[N];
     float gq[N];
 };
+
+// Key-side staging, one key column per lane and the 16 tokens of the block in registers: the decay products along
+// the tokens are running multiplications (one exponential per element, one reciprocal per column), and the
+// transposed [column][token] tiles are plain row writes.  Loads go through buffer descriptors that span the
+// sequence, so tokens past its end read as zero (decay factor 1) without any masking.
+constexpr uint32_t kRsrcWord3 = 0x00020000u;  // raw buffer descriptor, 32-bit data format
+struct PreCol {
+    uint32_t ld[kTok], k[kTok], q[kTok];  // 16-bit values as loaded, in the low halves
+    float gq, gk;                         // lane i < 16: the gates of token i of the block
+};
+struct ColLoader {
+    __amdgpu_buffer_rsrc_t rq, rk, rld;
+    const float* gq;  // gates of this head, token 0 of the sequence; H floats between tokens
+    const float* gk;
+    int tstride;      // bytes between tokens of q, k and the decay
+    int voff;         // byte offset of this lane's column in token 0
+    int T, H, lane;
+    // tokens t0 .. t0 + 15 of the sequence
+    template <int VAR>
+    __device__ __forceinline__ void load(int t0, PreCol& p) const {
+        const int base = voff + t0 * tstride;
+#pragma unroll
+        for (int i = 0; i < kTok; ++i) {
+            if constexpr (VAR == SLA_GLA)
+                p.ld[i] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rld, base, i * tstride, 0);
+            p.k[i] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rk, base, i * tstride, 0);
+            p.q[i] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rq, base, i * tstride, 0);
+        }
+        const size_t tok = (size_t)min(t0 + (lane & 15), T - 1);  // clamped; masked when staged
+        p.gq = gq[tok * H];
+        p.gk = gk[tok * H];
+    }
+};
+template <int DK>
+__device__ __forceinline__ ColLoader make_col_loader(const BArgs& a, size_t tok0, int T, int h, int col, int lane) {
+    ColLoader c;
+    const int tstride = a.H * DK * 2;
+    const size_t base = tok0 * a.H * DK;
+    c.rq = __builtin_amdgcn_make_buffer_rsrc((void*)(a.q + base), 0, T * tstride, kRsrcWord3);
+    c.rk = __builtin_amdgcn_make_buffer_rsrc((void*)(a.k + base), 0, T * tstride, kRsrcWord3);
+    c.rld = __builtin_amdgcn_make_buffer_rsrc((void*)((a.ld ? a.ld : a.q) + base), 0, a.ld ? T * tstride : 0, kRsrcWord3);
+    c.gq = a.gq + tok0 * a.H + h;
+    c.gk = a.gk + tok0 * a.H + h;
+    c.tstride = tstride;
+    c.voff = (h * DK + col) * 2;
+    c.T = T;
+    c.lane = lane;
+    c.H = a.H;
+    return c;
+}
+__device__ __forceinline__ float bf16_low(uint32_t x) { return __uint_as_float(x << 16); }
+__device__ __forceinline__ float lane_value(float x, int i) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), i));
+}
+// decay factors of the 16 tokens of one column: alpha_i, or 1 past the end of the sequence
+template <int VAR>
+__device__ __forceinline__ void column_decay(const PreCol& p, float head_alpha, int t0, int T, float* al) {
+#pragma unroll
+    for (int i = 0; i < kTok; ++i) {
+        if constexpr (VAR == SLA_GLA)
+            al[i] = ex2(bf16_low(p.ld[i]) * kLog2e);
+        else
+            al[i] = t0 + i < T ? head_alpha : 1.f;
+    }
+}
+// sixteen values of one column as a row of a [column][kTS] bf16 tile
+__device__ __forceinline__ void put_row(uint16_t* row, const float* x) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        *(u2*)(row + 4 * m) = u2{pack2(x[4 * m], x[4 * m + 1]), pack2(x[4 * m + 2], x[4 * m + 3])};
+}
 
 // Inclusive running sums c[i] of the log2-domain decay steps of eight key columns over the 16 tokens of the block
 // (token = lane % 16), and their totals.
@@ -309,13 +385,13 @@ struct SmemF {
     static constexpr int oVT = oV + kTok * (DV + 8) * 2;
     static constexpr int oKDT = oVT + DV * kTS * 2;
     static constexpr int oKBT = oKDT + kCols * kTS * 2;
-    static constexpr int oCUM = oKBT + kCols * kTS * 2;
-    static constexpr int oTOT = oCUM + kTok * kFS * 4;
+    static constexpr int oPF = oKBT + kCols * kTS * 2;   // p_t per token and key column, fp32
+    static constexpr int oTOT = oPF + kTok * kFS * 4;    // A = p_15 per key column
     static constexpr int oQS = oTOT + kCols * 4;
     static constexpr int oGQ = oQS + kTok * kFS * 2;
     static constexpr int bytes = oGQ + kTok * 4;
     static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
-    static_assert(oV % 16 == 0 && oVT % 16 == 0 && oKDT % 16 == 0 && oCUM % 16 == 0 && oTOT % 16 == 0 &&
+    static_assert(oV % 16 == 0 && oVT % 16 == 0 && oKDT % 16 == 0 && oPF % 16 == 0 && oTOT % 16 == 0 &&
                       oQS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
     static_assert(total <= 160 * 1024, "the ring fits the LDS of a compute unit");
@@ -348,54 +424,40 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     if (wave >= kConsumers) {
         const int team = (wave - kConsumers) >> 1;
         if (((wave - kConsumers) & 1) == 0) {
-            // decay, keys and queries of the slice: token t = lane % 16, columns 8 (lane / 16) + 32 j ... + 7
-            const int t = r, d0 = sbase + 8 * g;  // piece j adds 32 columns: a store instruction's four lane groups sit 8 columns apart, on disjoint banks
-            const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
-            producer_run<PreKeys<2>>(
-                ring, smem, L::bytes, team, nb,
-                [&](int blk, PreKeys<2>& p) {
-                    const size_t row = (tok0 + min(blk * kTok + t, T - 1)) * H + h;
+            // decay, keys and queries of the slice: key column sbase + lane, the 16 tokens in registers
+            const float head_alpha = VAR == SLA_RETNET ? ex2(a.ld_head[h] * kLog2e) : 1.f;
+            const ColLoader ldr = make_col_loader<DK>(a, tok0, T, h, sbase + lane, lane);
+            producer_run<PreCol>(
+                ring, smem, L::bytes, team, nb, [&](int blk, PreCol& p) { ldr.template load<VAR>(blk * kTok, p); },
+                [&](int blk, const PreCol& p, unsigned char* buf) {
+                    const int t0 = blk * kTok;
+                    const bool ok = t0 + (lane & 15) < T;
+                    const float gk_own = ok ? p.gk : 0.f;
+                    float al[kTok];
+                    column_decay<VAR>(p, head_alpha, t0, T, al);
+                    float* pf = (float*)(buf + L::oPF) + lane;
+                    float pre = 1.f;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 32 * j);
-                        p.kx[j] = load16(a.k + row * DK + d0 + 32 * j);
-                        p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
+                    for (int i = 0; i < kTok; ++i) {
+                        pre *= al[i];
+                        pf[i * kFS] = pre;  // p_t
                     }
-                    p.gk = a.gk[row];
-                    p.gq = a.gq[row];
-                },
-                [&](int blk, const PreKeys<2>& p, unsigned char* buf) {
-                    const bool ok = blk * kTok + t < T;
-                    const float gk = ok ? p.gk : 0.f;
+                    ((float*)(buf + L::oTOT))[lane] = pre;  // A
+                    const float invA = __builtin_amdgcn_rcpf(pre);
+                    float suf = 1.f, kd[kTok], kb[kTok];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int c0 = 8 * g + 32 * j;
-                        const u4 kx = keep(p.kx[j], ok);
-                        float c[8], tot[8];
-                        block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
-                        float* cum = (float*)(buf + L::oCUM) + t * kFS + c0;
-                        *(f4*)cum = f4{c[0], c[1], c[2], c[3]};
-                        *(f4*)(cum + 4) = f4{c[4], c[5], c[6], c[7]};
-                        if (t == 0) {
-                            float* tt = (float*)(buf + L::oTOT) + c0;
-                            *(f4*)tt = f4{tot[0], tot[1], tot[2], tot[3]};
-                            *(f4*)(tt + 4) = f4{tot[4], tot[5], tot[6], tot[7]};
-                        }
-                        u4 kd, kb;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float k0 = bf_lo(kx[i]) * gk, k1 = bf_hi(kx[i]) * gk;
-                            kd[i] = pack2(k0 * ex2(-c[2 * i]), k1 * ex2(-c[2 * i + 1]));
-                            kb[i] = pack2(k0 * ex2(tot[2 * i] - c[2 * i]), k1 * ex2(tot[2 * i + 1] - c[2 * i + 1]));
-                        }
-                        put_T((uint16_t*)(buf + L::oKDT), c0, t, kd);
-                        put_T((uint16_t*)(buf + L::oKBT), c0, t, kb);
-                        const u4 qx = keep(p.qx[j], ok);
-                        uint16_t* qs = (uint16_t*)(buf + L::oQS) + t * kFS + c0;
-                        *(u2*)qs = u2{qx[0], qx[1]};
-                        *(u2*)(qs + 4) = u2{qx[2], qx[3]};
+                    for (int i = kTok - 1; i >= 0; --i) {
+                        const float x = bf16_low(p.k[i]) * lane_value(gk_own, i) * suf;  // G^K k A / p
+                        kb[i] = x;
+                        kd[i] = x * invA;                                              // G^K k / p
+                        suf *= al[i];
                     }
-                    if (g == 0) ((float*)(buf + L::oGQ))[t] = ok ? p.gq : 0.f;
+                    put_row((uint16_t*)(buf + L::oKDT) + lane * kTS, kd);
+                    put_row((uint16_t*)(buf + L::oKBT) + lane * kTS, kb);
+                    uint16_t* qs = (uint16_t*)(buf + L::oQS) + lane;
+#pragma unroll
+                    for (int i = 0; i < kTok; ++i) qs[i * kFS] = (uint16_t)p.q[i];
+                    if (lane < kTok) ((float*)(buf + L::oGQ))[lane] = ok ? p.gq : 0.f;
                 });
         } else {  // dout and v, all value columns
             producer_run<PreRows<R>>(
@@ -459,10 +521,10 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
             mma32(oS, join(pack4(ST[2 * c]), pack4(ST[2 * c + 1])), get_perm<DV>(DOp, r, g, c));
         const s4 fkd = get_T((const uint16_t*)(buf + L::oKDT), cb + r, g);
         mma16(oP, fkd, fp);
-        const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
+        const f4 pt = *(const f4*)((const float*)(buf + L::oPF) + r * kFS + cb + 4 * g);
         const u2 qx = *(const u2*)((const uint16_t*)(buf + L::oQS) + r * kFS + cb + 4 * g);
         const float gq = ((const float*)(buf + L::oGQ))[r];
-        const float Ad = ex2(((const float*)(buf + L::oTOT))[cb + r]);
+        const float Ad = ((const float*)(buf + L::oTOT))[cb + r];
         const s4 fkb = get_T((const uint16_t*)(buf + L::oKBT), cb + r, g);
         const uint16_t* VT = (const uint16_t*)(buf + L::oVT);
         s4 fvt[DV / 16];
@@ -471,7 +533,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
         consumer_release(ring, blk);  // every operand of the block is in registers
         float dqp[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * ex2(cum[i]);
+        for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * pt[i];
         const float qf[4] = {bf_lo(qx[0]), bf_hi(qx[0]), bf_lo(qx[1]), bf_hi(qx[1])};
         float part = qf[0] * dqp[0] + qf[1] * dqp[1] + qf[2] * dqp[2] + qf[3] * dqp[3];
         part = reduce_groups(part);
@@ -483,9 +545,14 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
 #pragma unroll
             for (int i = 0; i < 4; ++i) dqv[i] = gq * dqp[i];
             *(u2*)(a.dq + row * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
-            if constexpr (VAR == SLA_GLA)
-                *(f4*)(a.qdq + row * DK + sbase + cb + 4 * g) =
-                    f4{qf[0] * dqv[0], qf[1] * dqv[1], qf[2] * dqv[2], qf[3] * dqv[3]};
+        }
+        if constexpr (VAR == SLA_GLA) {
+            // sum of q * dq over the block (fp32, from the unrounded dq): the dk sweep needs it exactly for the
+            // running sum behind dlog_decay, and takes the per-token values from the bf16 dq
+            f4 bs;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bs[i] = row_suffix(tok < T ? qf[i] * gq * dqp[i] : 0.f);
+            if (r == 0) *(f4*)(a.bsum + (block_id(tok0, t0, b) * H + h) * DK + sbase + cb + 4 * g) = bs;
         }
         // S^T <- S^T A + v^T kb'
 #pragma unroll
@@ -524,6 +591,9 @@ struct SmemK {
     static constexpr int oGQ = oKS + kTok * kFS * 2;
     static constexpr int oGK = oGQ + kTok * 4;
     static constexpr int bytes = oGK + kTok * 4;
+    // The block's q * dq sums (64 floats, GLA) live in the four padding columns of the 16 rows of the q * dq tile:
+    // the sums of key columns 4 m .. 4 m + 3 are floats 64 .. 67 of row m.
+    static constexpr int bs_offset(int d) { return oQDQ + ((d >> 2) * kFS + kCols + (d & 3)) * 4; }
     static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
     static_assert(oV % 16 == 0 && oDYT % 16 == 0 && oQAT % 16 == 0 && oCUM % 16 == 0 && oQDQ % 16 == 0 &&
                       oKS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
@@ -571,19 +641,33 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                         p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
                     }
                     if constexpr (VAR == SLA_GLA) {
+                        const float* bs = a.bsum + (block_id(tok0, (nb - 1 - I) * kTok, b) * H + h) * DK + d0;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) p.e[j] = *(const f4*)(a.qdq + row * DK + d0 + 32 * (j >> 1) + 4 * (j & 1));
+                        for (int j = 0; j < 2; ++j) {
+                            p.dq[j] = load16(a.dq + row * DK + d0 + 32 * j);
+                            p.bs[2 * j] = *(const f4*)(bs + 32 * j);  // the same address in all 16 token lanes
+                            p.bs[2 * j + 1] = *(const f4*)(bs + 32 * j + 4);
+                        }
                     }
                     p.gk = a.gk[row];
                     p.gq = a.gq[row];
                 },
                 [&](int I, const PreKeysE& p, unsigned char* buf) {
                     const bool ok = (nb - 1 - I) * kTok + t < T;
-                    if constexpr (VAR == SLA_GLA) {
+                    if constexpr (VAR == SLA_GLA) {  // q * dq per token from the bf16 dq; the block's exact sums
                         float* qd = (float*)(buf + L::oQDQ) + t * kFS + 8 * g;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            *(f4*)(qd + 32 * (j >> 1) + 4 * (j & 1)) = ok ? p.e[j] : f4{0.f, 0.f, 0.f, 0.f};
+                        for (int j = 0; j < 2; ++j) {
+                            const u4 qx = keep(p.qx[j], ok), dx = keep(p.dq[j], ok);
+                            *(f4*)(qd + 32 * j) = f4{bf_lo(qx[0]) * bf_lo(dx[0]), bf_hi(qx[0]) * bf_hi(dx[0]),
+                                                     bf_lo(qx[1]) * bf_lo(dx[1]), bf_hi(qx[1]) * bf_hi(dx[1])};
+                            *(f4*)(qd + 32 * j + 4) = f4{bf_lo(qx[2]) * bf_lo(dx[2]), bf_hi(qx[2]) * bf_hi(dx[2]),
+                                                         bf_lo(qx[3]) * bf_lo(dx[3]), bf_hi(qx[3]) * bf_hi(dx[3])};
+                            if (t == 0) {
+                                *(f4*)(buf + L::bs_offset(8 * g + 32 * j)) = p.bs[2 * j];
+                                *(f4*)(buf + L::bs_offset(8 * g + 32 * j + 4)) = p.bs[2 * j + 1];
+                            }
+                        }
                     }
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
@@ -685,8 +769,11 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         mma16(Xi, fqa, fp);
         const f4 cum = *(const f4*)((const float*)(buf + L::oCUM) + r * kFS + cb + 4 * g);
         const f4 tot = *(const f4*)((const float*)(buf + L::oCUM) + (kTok - 1) * kFS + cb + 4 * g);
-        f4 e = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (VAR == SLA_GLA) e = *(const f4*)((const float*)(buf + L::oQDQ) + r * kFS + cb + 4 * g);
+        f4 e = {0.f, 0.f, 0.f, 0.f}, bs4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (VAR == SLA_GLA) {
+            e = *(const f4*)((const float*)(buf + L::oQDQ) + r * kFS + cb + 4 * g);
+            bs4 = *(const f4*)(buf + L::bs_offset(cb + 4 * g));
+        }
         const float gk = ((const float*)(buf + L::oGK))[r];
         const u2 kx = *(const u2*)((const uint16_t*)(buf + L::oKS) + r * kFS + cb + 4 * g);
         const float Ad = ex2(((const float*)(buf + L::oCUM))[(kTok - 1) * kFS + cb + r]);
@@ -695,21 +782,31 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
 #pragma unroll
         for (int i = 0; i < DV / 16; ++i) fdy[i] = get_T(DYT, 16 * i + r, g);
         consumer_release(ring, blk);  // every operand of the block is in registers
-        float dkv[4];
+        float dkp[4], dkv[4];  // before and after the write gate
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dkv[i] = gk * (Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]));
+        for (int i = 0; i < 4; ++i) {
+            dkp[i] = Xi[i] * ex2(-cum[i]) + Xs[i] * ex2(tot[i] - cum[i]);
+            dkv[i] = gk * dkp[i];
+        }
+        const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
+        float part = kf[0] * dkp[0] + kf[1] * dkp[1] + kf[2] * dkp[2] + kf[3] * dkp[3];  // dG^K = k . dk'
+        part = reduce_groups(part);
         const int tok = t0 + r;
         const bool ok = tok < T;
         const size_t row = (tok0 + (ok ? tok : 0)) * H + h;
-        if (ok) *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+        if (ok) {
+            if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
+            *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+        }
         if constexpr (VAR == SLA_GLA) {
-            const float kf[4] = {bf_lo(kx[0]), bf_hi(kx[0]), bf_lo(kx[1]), bf_hi(kx[1])};
+            // dlog_decay_t = sum_{s >= t} (q_s dq_s - k_s dk_s): inside the block from the staged per-token values,
+            // beyond it from the running sum, which advances by the block's exact q * dq sum
             float dl[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float s = row_suffix(e[i] - kf[i] * dkv[i]) + run[i];
-                dl[i] = s;
-                run[i] = row_first(s);
+                const float sq = row_suffix(e[i]), sk = row_suffix(kf[i] * dkv[i]);
+                dl[i] = sq - sk + run[i];
+                run[i] += bs4[i] - row_first(sk);
             }
             if (ok) *(u2*)(a.dld + row * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
         }
@@ -732,19 +829,18 @@ struct SmemV {
     static constexpr int oKB = oKD + kTok * (DK + 8) * 2;
     static constexpr int oQAT = oKB + kTok * (DK + 8) * 2;
     static constexpr int oDYT = oQAT + DK * kTS * 2;
-    static constexpr int oVS = oDYT + kCols * kTS * 2;
-    static constexpr int oAT = oVS + kTok * kFS * 2;
+    static constexpr int oAT = oDYT + kCols * kTS * 2;
     static constexpr int oGK = oAT + DK * 4;
     static constexpr int bytes = oGK + kTok * 4;
     static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
-    static_assert(oKD % 16 == 0 && oKB % 16 == 0 && oQAT % 16 == 0 && oDYT % 16 == 0 && oVS % 16 == 0 &&
+    static_assert(oKD % 16 == 0 && oKB % 16 == 0 && oQAT % 16 == 0 && oDYT % 16 == 0 &&
                       oAT % 16 == 0 && oGK % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
     static_assert(total <= 160 * 1024, "the ring fits the LDS of a compute unit");
 };
 
 template <int N>
-struct PreVals {  // N groups of eight key columns of one token, and two pieces of the dout or v slice
+struct PreVals {  // N groups of eight key columns of one token, and (member 0) two pieces of the dout slice
     u4 ld[N], kx[N], qx[N];
     u4 sl[2];
     float gq[2], gk;
@@ -776,10 +872,10 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
 
     if (wave >= kConsumers) {
         // member m: key columns m DK/2 + 8 (lane / 16) + 32 j ..., token lane % 16; member 0 also stages the slice of
-        // dout (gated, transposed), member 1 the slice of v: two 16-byte pieces per lane each
+        // dout (gated, transposed): two 16-byte pieces per lane
         const int team = (wave - kConsumers) >> 1, m = (wave - kConsumers) & 1;
         const int t = r, d0 = m * (DK / 2) + 8 * g;  // piece j adds 32 columns
-        const uint16_t* slice_src = (m ? a.v : a.dout) + sbase;
+        const uint16_t* slice_src = a.dout + sbase;
         const float head_step = VAR == SLA_RETNET ? a.ld_head[h] * kLog2e : 0.f;
         producer_run<PreVals<N>>(
             ring, smem, L::bytes, team, nb,
@@ -793,12 +889,14 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                     p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
                 }
                 p.gk = a.gk[row];
+                if (m == 0) {  // uniform over the wave
 #pragma unroll
-                for (int rep = 0; rep < 2; ++rep) {
-                    const int st = r, se8 = g + 4 * rep;
-                    const size_t srow = (tok0 + min(t0 + st, T - 1)) * H + h;
-                    p.sl[rep] = load16(slice_src + srow * DV + 8 * se8);
-                    p.gq[rep] = a.gq[srow];
+                    for (int rep = 0; rep < 2; ++rep) {
+                        const int st = r, se8 = g + 4 * rep;
+                        const size_t srow = (tok0 + min(t0 + st, T - 1)) * H + h;
+                        p.sl[rep] = load16(slice_src + srow * DV + 8 * se8);
+                        p.gq[rep] = a.gq[srow];
+                    }
                 }
             },
             [&](int I, const PreVals<N>& p, unsigned char* buf) {
@@ -829,20 +927,15 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                     }
                 }
                 if (m == 0 && g == 0) ((float*)(buf + L::oGK))[t] = ok ? p.gk : 0.f;
+                if (m == 0) {
 #pragma unroll
-                for (int rep = 0; rep < 2; ++rep) {
-                    const int st = r, se8 = g + 4 * rep;
-                    const bool oks = t0 + st < T;
-                    const u4 sl = keep(p.sl[rep], oks);
-                    if (m == 0) {
+                    for (int rep = 0; rep < 2; ++rep) {
+                        const int st = r, se8 = g + 4 * rep;
+                        const u4 sl = keep(p.sl[rep], t0 + st < T);
                         u4 dy;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) dy[j] = pack2(p.gq[rep] * bf_lo(sl[j]), p.gq[rep] * bf_hi(sl[j]));
                         put_T((uint16_t*)(buf + L::oDYT), 8 * se8, st, dy);
-                    } else {
-                        uint16_t* vs = (uint16_t*)(buf + L::oVS) + st * kFS + 8 * se8;
-                        *(u2*)vs = u2{sl[0], sl[1]};
-                        *(u2*)(vs + 4) = u2{sl[2], sl[3]};
                     }
                 }
             });
@@ -886,7 +979,6 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
             mma32(Ys, join(pack4(DS[2 * c]), pack4(DS[2 * c + 1])), get_perm<DK>(KBp, r, g, c));
         const s4 fdy = get_T((const uint16_t*)(buf + L::oDYT), cb + r, g);
         mma16(Yi, fdy, fp);
-        const u2 vx = *(const u2*)((const uint16_t*)(buf + L::oVS) + r * kFS + cb + 4 * g);
         const float gk = ((const float*)(buf + L::oGK))[r];
         const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
         const float* AT = (const float*)(buf + L::oAT);
@@ -898,18 +990,11 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
             Ad[i] = *(const f4*)(AT + 16 * i + 4 * g);
         }
         consumer_release(ring, blk);  // every operand of the block is in registers
-        const float vf[4] = {bf_lo(vx[0]), bf_hi(vx[0]), bf_lo(vx[1]), bf_hi(vx[1])};
-        float dvp[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) dvp[i] = Ys[i] + Yi[i];
-        float part = vf[0] * dvp[0] + vf[1] * dvp[1] + vf[2] * dvp[2] + vf[3] * dvp[3];
-        part = reduce_groups(part);
         const int tok = t0 + r;
         if (tok < T) {
             const size_t row = (tok0 + tok) * H + h;
-            if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
             *(u2*)(a.dv + row * DV + sbase + cb + 4 * g) =
-                u2{pack2(gk * dvp[0], gk * dvp[1]), pack2(gk * dvp[2], gk * dvp[3])};
+                u2{pack2(gk * (Ys[0] + Yi[0]), gk * (Ys[1] + Yi[1])), pack2(gk * (Ys[2] + Yi[2]), gk * (Ys[3] + Yi[3]))};
         }
         // dS <- diag(A) dS + qa^T dy
 #pragma unroll
@@ -1036,13 +1121,14 @@ int launch_dk(const BArgs& a, int dk, int dv, hipStream_t stream) {
 
 }  // namespace
 
-// Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q (dk/16 planes) and dG^K (dv/16 planes); for GLA
-// q*dq [B,T,H,dk] and the final-state term of dlog_decay [B,H,dk].
+// Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q and dG^K (dk/16 planes each); for GLA the sums of
+// q * dq over every 16-token block [rows/16 + B + 1][H,dk] and the final-state term of dlog_decay [B,H,dk].
 size_t backward_workspace_floats(const sla_params& p, bool packed) {
     const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T;
     const size_t n = round4(rows * p.H);
-    size_t total = n * (2 + p.dk / 16 + p.dv / 16);
-    if (p.variant == SLA_GLA) total += round4(rows * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk);
+    size_t total = n * (2 + 2 * (p.dk / 16));
+    if (p.variant == SLA_GLA)
+        total += round4((rows / kTok + p.B + 1) * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk);
     return total;
 }
 
@@ -1059,10 +1145,10 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
     float* gk = w; w += n;
     a.gq = gq; a.gk = gk;
     a.part_q = w; w += n * (p.dk / 16);
-    a.part_k = w; w += n * (p.dv / 16);
-    a.qdq = nullptr; a.corr = nullptr;
+    a.part_k = w; w += n * (p.dk / 16);
+    a.bsum = nullptr; a.corr = nullptr;
     if (p.variant == SLA_GLA) {
-        a.qdq = w; w += round4(rows * p.H * p.dk);
+        a.bsum = w; w += round4((rows / kTok + p.B + 1) * p.H * p.dk);
         a.corr = w;
     }
     a.s0 = s0; a.dsf = dsf;
@@ -1082,7 +1168,7 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
                        p.dk / 16, dql, rows, p.H);
     if (kl)
         hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gk,
-                           (const float*)a.part_k, p.dv / 16, dkl, rows, p.H);
+                           (const float*)a.part_k, p.dk / 16, dkl, rows, p.H);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 

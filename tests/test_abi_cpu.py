@@ -199,9 +199,10 @@ def test_backward_workspace_size(lib):
     n = B * T * H
     gla = sla.sla_backward_workspace_bytes(_ok_params(B=B, T=T, H=H, dk=dk, dv=dv))
     ret = sla.sla_backward_workspace_bytes(_ok_params(variant=sla.RETNET, B=B, T=T, H=H, dk=dk, dv=dv))
-    # gates (2 planes), partial gate gradients (dk/16 + dv/16 planes); GLA adds q*dq [B,T,H,dk] and [B,H,dk]
-    assert ret == 4 * n * (2 + dk // 16 + dv // 16)
-    assert gla == ret + 4 * (n * dk + B * H * dk)
+    # gates (2 planes), partial gate gradients (dk/16 planes each); GLA adds the q*dq block sums
+    # [B*T/16 + B + 1][H,dk] and [B,H,dk]
+    assert ret == 4 * n * (2 + 2 * (dk // 16))
+    assert gla == ret + 4 * ((B * T // 16 + B + 1) * H * dk + B * H * dk)
     assert sla.sla_backward_workspace_bytes(_ok_params(variant=sla.GDN)) == 0
     assert sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32)) == 0
 
@@ -231,5 +232,5 @@ def test_varlen_rejects_bad_calls(lib):
     # the packed workspace is sized by the total token count p->T, not B * T
     p = _ok_params(B=5, T=1000)
     one = _ok_params(B=1, T=1000)
-    extra = 4 * (5 - 1) * p.H * p.dk  # one [H,dk] row of final-state terms per sequence
+    extra = 4 * (5 - 1) * p.H * p.dk * 2  # per sequence: one [H,dk] row of final-state terms, one more block of sums
     assert sla.sla_backward_varlen_workspace_bytes(p) == sla.sla_backward_workspace_bytes(one) + extra
