@@ -30,8 +30,8 @@ MEASURED_TRAFFIC_BYTES = {
     "gla_long": 4.063e9,      # same file
     "decode_gla": 135.7e6,    # profiles/sla_decode_bf16.md
     "decode_gdn": 135.7e6,    # same file
-    "gla_train:backward": 1.628e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
-    "retnet_train:backward": 1.055e9,  # same file
+    "gla_train:backward": 1.369e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
+    "retnet_train:backward": 0.990e9,  # same file
     "gla_train:prologue": 136.5e6,     # profiles/sla_gate_logits_bf16_gla_train.md
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
