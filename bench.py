@@ -440,6 +440,9 @@ def main() -> int:
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--backward", action="store_true",
                     help="time sla_backward (RetNet / GLA training workloads) instead of the forward")
+    ap.add_argument("--head-major", action="store_true",
+                    help="forward only: q, k, v, out (and the GLA decay) in the [B,H,T,d] layout (SLA_FLAG_HEAD_MAJOR) "
+                         "instead of the benchmark definition's [B,T,H,d]; a secondary figure, not the headline")
     ap.add_argument("--varlen", action="store_true",
                     help="forward only: the workload's B*T tokens as one packed batch of mixed-length sequences "
                          "(sla_forward_varlen; lengths from sla_inputs.packed_lengths)")
@@ -478,13 +481,20 @@ def main() -> int:
     g, tdt = to_device(d, w.dtype, w.variant)
     dev = torch.device("cuda:0")
     out = torch.empty((w.B, w.T, w.H, w.dv), dtype=tdt, device=dev)
+    if args.head_major:
+        if args.varlen:
+            print("bench.py: --head-major and --varlen do not combine", file=sys.stderr)
+            return 2
+        for n in ("q", "k", "v") + (("log_decay",) if w.variant == 1 else ()):
+            g[n] = g[n].permute(0, 2, 1, 3).contiguous()
+        out = torch.empty((w.B, w.H, w.T, w.dv), dtype=tdt, device=dev)
     lengths = si.packed_lengths(w.B * w.T, seed=w.seed + 70) if args.varlen else None
     nstates = len(lengths) if args.varlen else w.B
     fin = torch.empty((nstates, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
 
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, args.dv_split, 0,
-                           args.segments)
+    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, args.dv_split,
+                           sla.FLAG_HEAD_MAJOR if args.head_major else 0, args.segments)
     nseg = sla.sla_segments(params, cus)
     if nseg < 1:
         print(f"bench.py: {sla.sla_status_string(nseg)}", file=sys.stderr)
@@ -564,7 +574,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": f"{w.name}: SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} dk={w.dk} dv={w.dv} "
-                        f"{w.dtype} in/out, fp32 state, dual head-softmax gates",
+                        f"{w.dtype} in/out, fp32 state, dual head-softmax gates"
+                        + (", q/k/v/out/decay laid out [B,H,T,d]" if args.head_major else ""),
             "kernel": sla.sla_kernel_name(params),
             "dv_split": dvw,
             "segments": nseg,
@@ -577,7 +588,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
-            "traffic": None if args.varlen else MEASURED_TRAFFIC_BYTES.get(w.name),
+            "traffic": None if (args.varlen or args.head_major) else MEASURED_TRAFFIC_BYTES.get(w.name),
             "kernel_us": kernel_ms * 1e3,
             "kernel_us_min": float(np.min(per_launch_ms)) * 1e3,
             "algorithmic_bytes": abytes,
@@ -611,8 +622,9 @@ def main() -> int:
         if not args.no_parity and not args.varlen:
             step()
             torch.cuda.synchronize()
+            og = out.permute(0, 2, 1, 3) if args.head_major else out
             result["parity"] = {
-                "out_rel_err": rel_err(out.to(torch.float32).cpu().numpy().astype(np.float64), ro),
+                "out_rel_err": rel_err(og.to(torch.float32).cpu().numpy().astype(np.float64), ro),
                 "state_rel_err": rel_err(fin.cpu().numpy().astype(np.float64), rf),
                 "definition": "max|x - oracle| / max|oracle| per tensor",
             }

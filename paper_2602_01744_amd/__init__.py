@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     GDN,
     F32,
     BF16,
+    FLAG_HEAD_MAJOR,
     SlaError,
     SlaParams,
     library_path,

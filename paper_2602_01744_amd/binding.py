@@ -12,6 +12,7 @@ import os
 from typing import Optional, Tuple
 
 RETNET, GLA, GDN = 0, 1, 2
+FLAG_HEAD_MAJOR = 1
 F32, BF16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -404,34 +405,40 @@ def forward(
     want_final_state: bool = True,
     segments: int = 1,
     workspace=None,
+    head_major: bool = False,
 ) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
     """SLA forward on the current CUDA(HIP) device and stream.  Tensors must be contiguous CUDA tensors:
     q,k [B,T,H,dk], v [B,T,H,dv] in float32 or bfloat16; logits/beta/initial_state float32.
 
     segments = 1 runs one fused pass (sla_forward).  segments = 0 lets the library choose the
     segment-parallel schedule, segments > 1 asks for that many segments (sla_forward_ws); the workspace
-    is then taken from ``workspace`` (a CUDA tensor of at least sla_workspace_bytes bytes) or allocated here."""
+    is then taken from ``workspace`` (a CUDA tensor of at least sla_workspace_bytes bytes) or allocated here.
+
+    head_major = True: q, k, v (and the GLA log_decay, and the returned out) are [B,H,T,d] (SLA_FLAG_HEAD_MAJOR)."""
     import torch
 
     assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
-    B, T, H, dk = q.shape
+    if head_major:
+        B, H, T, dk = q.shape
+    else:
+        B, T, H, dk = q.shape
     dv = v.shape[-1]
-    assert k.shape == (B, T, H, dk) and v.shape == (B, T, H, dv) and k.dtype == q.dtype and v.dtype == q.dtype
+    assert k.shape == q.shape and v.shape == q.shape[:3] + (dv,) and k.dtype == q.dtype and v.dtype == q.dtype
     dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
     assert q_head_logits.dtype == torch.float32 and q_head_logits.shape == (B, T, H) and q_head_logits.is_contiguous()
     if k_head_logits is not None:
         assert k_head_logits.dtype == torch.float32 and k_head_logits.shape == (B, T, H) and k_head_logits.is_contiguous()
-    want = {RETNET: ((H,), torch.float32), GLA: ((B, T, H, dk), q.dtype), GDN: ((B, T, H), torch.float32)}[variant]
+    want = {RETNET: ((H,), torch.float32), GLA: (tuple(q.shape), q.dtype), GDN: ((B, T, H), torch.float32)}[variant]
     assert tuple(log_decay.shape) == want[0] and log_decay.dtype == want[1] and log_decay.is_contiguous()
     if beta is not None:
         assert beta.dtype == torch.float32 and beta.shape == (B, T, H) and beta.is_contiguous()
     if initial_state is not None:
         assert initial_state.dtype == torch.float32 and initial_state.shape == (B, H, dk, dv) and initial_state.is_contiguous()
     if out is None:
-        out = torch.empty((B, T, H, dv), dtype=q.dtype, device=q.device)
+        out = torch.empty(tuple(v.shape), dtype=q.dtype, device=q.device)
     if final_state is None and want_final_state:
         final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
-    params = SlaParams(variant, dtype, B, T, H, dk, dv, dv_split, 0, segments)
+    params = SlaParams(variant, dtype, B, T, H, dk, dv, dv_split, FLAG_HEAD_MAJOR if head_major else 0, segments)
     ptr = lambda t: None if t is None else t.data_ptr()
     stream = torch.cuda.current_stream(q.device).cuda_stream
     if segments == 1:

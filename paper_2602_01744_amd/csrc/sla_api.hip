@@ -32,7 +32,7 @@ int check_params(const sla_params* p) {
     if (!p) return SLA_ERR_NULL;
     if (p->variant != SLA_RETNET && p->variant != SLA_GLA && p->variant != SLA_GDN) return SLA_ERR_UNSUPPORTED;
     if (p->dtype != SLA_F32 && p->dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
-    if (p->flags != 0) return SLA_ERR_UNSUPPORTED;
+    if ((p->flags & ~SLA_FLAG_HEAD_MAJOR) != 0) return SLA_ERR_UNSUPPORTED;
     if (p->segments < 0 || p->segments > 4096) return SLA_ERR_SHAPE;
     if (p->segments > 1 && p->variant == SLA_GDN) return SLA_ERR_UNSUPPORTED;
     if (p->B < 0 || p->T < 0 || p->H < 1 || p->H > kMaxHeads) return SLA_ERR_SHAPE;
@@ -163,7 +163,7 @@ int sla_forward_varlen(const sla_params* p, const void* q, const void* k, const 
                        void* stream) {
     const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state);
     if (rc != SLA_OK) return rc;
-    if (p->segments > 1) return SLA_ERR_UNSUPPORTED;
+    if (p->segments > 1 || p->flags != 0) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && !cu_seqlens) return SLA_ERR_NULL;
     if (cu_seqlens && (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u)) return SLA_ERR_ALIGN;
     if (p->B == 0) return SLA_OK;
@@ -190,6 +190,7 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
     if (p->T != 1) return SLA_ERR_SHAPE;
     if (p->B == 0) return SLA_OK;
     if (!state) return SLA_ERR_NULL;
+    // one token per sequence: [B,1,H,d] and [B,H,1,d] are the same memory, so the layout flag changes nothing
     return sla::launch_decode(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out,
                               (hipStream_t)stream);
 }
@@ -201,7 +202,7 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
                          void* workspace, size_t workspace_bytes, const int32_t* cu, bool packed, void* stream) {
     int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant == SLA_GDN || p->dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
+    if (p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->flags != 0) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !d_out || !dq || !dk || !dv || !dq_head_logits)
             return SLA_ERR_NULL;
@@ -249,6 +250,7 @@ int sla_gate_logits(const sla_params* p, const void* q, const void* k, const flo
                     float* q_head_logits, float* k_head_logits, void* stream) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
+    if (p->flags != 0) return SLA_ERR_UNSUPPORTED;
     const bool work = p->B > 0 && p->T > 0;
     if (work && (!q || !w_gq || !q_head_logits)) return SLA_ERR_NULL;
     if ((k != nullptr) != (w_gk != nullptr) || (k != nullptr) != (k_head_logits != nullptr)) return SLA_ERR_NULL;

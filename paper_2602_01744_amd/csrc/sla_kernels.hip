@@ -82,6 +82,9 @@ struct KArgs {
     // Packed variable-length batch: B sequences laid end to end in tensors of T tokens in all; sequence b covers
     // tokens cu[b] .. cu[b + 1] - 1.  Null for the rectangular layout.
     const int* cu;
+    // q, k, v, out and the GLA decay laid out [B,H,T,d] instead of [B,T,H,d]: every (batch, head) streams one
+    // contiguous region.  Logits, beta, the delta rule's decay and the states keep their layouts.
+    bool head_major;
 };
 
 #ifdef SLA_TRACE
@@ -321,14 +324,24 @@ struct Loader {
     int H;
     bool has_kl;
 
-    // row_tok: index of the first token of the row in the [B*T] token space; T: tokens of the row
+    // row_tok: index of the first token of the row in the [B*T] token space; T: tokens of the row.  With the
+    // head-major layout the descriptors of q, k, v and the GLA decay start at this head's own rows.
     __device__ __forceinline__ void init(const KArgs& a, size_t row_tok, int T, int h, int n0, int lane) {
         H = a.H;
         has_kl = a.kl != nullptr;
-        tstride_qk = H * DK * (int)sizeof(elem);
-        tstride_v = H * a.dv * (int)sizeof(elem);
+        const int head = h;  // the logits keep their [B,T,H] layout
+        const int HW = a.head_major ? 1 : H;  // heads interleaved within a token of q, k, v
+        tstride_qk = HW * DK * (int)sizeof(elem);
+        tstride_v = HW * a.dv * (int)sizeof(elem);
         tstride_lg = H * 4;
-        const size_t row_qk = row_tok * H * DK, row_v = row_tok * H * a.dv, row_lg = row_tok * H;
+        size_t row_qk = row_tok * H * DK, row_v = row_tok * H * a.dv;
+        const size_t row_lg = row_tok * H;
+        if (a.head_major) {  // row_tok = b * T_all + t0  ->  ((b * H + h) * T_all + t0) tokens of width d
+            const size_t bb = row_tok / a.T, t0 = row_tok % a.T, tok = (bb * H + h) * a.T + t0;
+            row_qk = tok * DK;
+            row_v = tok * a.dv;
+            h = 0;
+        }
         rq = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.q + row_qk), 0, T * tstride_qk, kRsrcWord3);
         rk = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.k + row_qk), 0, T * tstride_qk, kRsrcWord3);
         rv = __builtin_amdgcn_make_buffer_rsrc((void*)((const elem*)a.v + row_v), 0, T * tstride_v, kRsrcWord3);
@@ -342,11 +355,11 @@ struct Loader {
         const int p = lane % LPR, tb = (lane / LPR) * NI;
         voff_v = tb * tstride_v + (h * a.dv + n0 + 2 * p) * (int)sizeof(elem);
         voff_lg = (lane >> 2) * tstride_lg + (lane & 3) * 4;
-        voff_own = (lane >> 2) * tstride_lg + h * 4;
+        voff_own = (lane >> 2) * tstride_lg + head * 4;
         if constexpr (VAR == SLA_GDN) {
             rld = __builtin_amdgcn_make_buffer_rsrc((void*)((const float*)a.ld + row_lg), 0, T * tstride_lg, kRsrcWord3);
             rbt = __builtin_amdgcn_make_buffer_rsrc((void*)(a.beta + row_lg), 0, T * tstride_lg, kRsrcWord3);
-            voff_sc = (lane & 15) * tstride_lg + h * 4;
+            voff_sc = (lane & 15) * tstride_lg + head * 4;
         }
     }
 
@@ -1130,8 +1143,9 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             for (int i = 0; i < 4; ++i) S[s][i] = s_in[(size_t)(16 * s + i) * dv];
     }
     // this lane stores 4 adjacent value columns of token r of every block
-    const size_t out_tstride = (size_t)H * dv;
-    elem* out_ptr = (elem*)a.out + (row_tok * H + h) * dv + n0 + 16 * cw + 4 * g + (size_t)r * out_tstride;
+    const size_t out_tstride = a.head_major ? (size_t)dv : (size_t)H * dv;
+    const size_t out_tok = a.head_major ? ((row_tok / a.T) * H + h) * a.T + row_tok % a.T : row_tok * H + h;
+    elem* out_ptr = (elem*)a.out + out_tok * dv + n0 + 16 * cw + 4 * g + (size_t)r * out_tstride;
 
     SLA_TRACE_DECL
     int seen = 0;
@@ -1338,6 +1352,7 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
                    const float* ql, const float* kl, const void* ld, const float* beta, const float* s0, void* out,
                    float* sT, float* workspace, const int* cu, hipStream_t stream) {
     KArgs a;
+    a.head_major = (p.flags & SLA_FLAG_HEAD_MAJOR) != 0;
     a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = beta; a.s0 = s0; a.out = out; a.sT = sT;
     a.B = p.B; a.T = p.T; a.H = p.H; a.dv = p.dv; a.nslice = p.dv / dvw;
     a.nseg = nseg; a.nseg_grid = nseg; a.nparts = 0; a.Ls = nseg > 1 ? seg_len : p.T;

@@ -79,7 +79,7 @@ def test_shapes_and_unsupported(lib):
     assert _call(_ok_params(dv=256)) == 0
     assert _call(_ok_params(variant=7)) == -3
     assert _call(_ok_params(dtype=2)) == -3
-    assert _call(_ok_params(flags=1)) == -3
+    assert _call(_ok_params(flags=4)) == -3
     assert _call(_ok_params(dv_split=48)) == -2
     assert _call(_ok_params(dv=64, dv_split=128)) == -2
     assert _call(_ok_params(dv_split=128)) == -3
@@ -234,3 +234,12 @@ def test_varlen_rejects_bad_calls(lib):
     one = _ok_params(B=1, T=1000)
     extra = 4 * (5 - 1) * p.H * p.dk * 2  # per sequence: one [H,dk] row of final-state terms, one more block of sums
     assert sla.sla_backward_varlen_workspace_bytes(p) == sla.sla_backward_workspace_bytes(one) + extra
+
+
+def test_layout_flag_is_a_forward_only_option(lib):
+    hm = _ok_params(flags=1)
+    assert _call(hm) == 0                                    # sla_forward accepts SLA_FLAG_HEAD_MAJOR
+    assert _call(_ok_params(flags=2)) == -3                  # unknown flag bits
+    assert _bwd(hm) == -3
+    assert sla.sla_forward_varlen(hm, A, A, A, A, A, A, 0, A, 0, A, A, 0) == -3
+    assert sla.sla_gate_logits(hm, A, A, A, A, A, A, 0) == -3
