@@ -440,6 +440,13 @@ def main() -> int:
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--backward", action="store_true",
                     help="time sla_backward (RetNet / GLA training workloads) instead of the forward")
+    ap.add_argument("--flush-mb", type=int, default=0,
+                    help="forward only: overwrite a scratch buffer of this many MB between the timed launches, so that "
+                         "no input is left in the 256 MB memory-side cache from the previous launch; each launch is "
+                         "then timed by its own pair of events and `value` is computed from that time")
+    ap.add_argument("--flush-kind", choices=("read", "write"), default="read",
+                    help="how --flush-mb displaces the cache: by reading the scratch buffer (lines left clean) or by "
+                         "rewriting it (lines left dirty: their write-back then overlaps the timed launch)")
     ap.add_argument("--head-major", action="store_true",
                     help="forward only: q, k, v, out (and the GLA decay) in the [B,H,T,d] layout (SLA_FLAG_HEAD_MAJOR) "
                          "instead of the benchmark definition's [B,T,H,d]; a secondary figure, not the headline")
@@ -539,17 +546,34 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     # per-launch kernel time: HIP events on the stream the kernel is enqueued on (torch's current stream)
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    evs[0].record()
-    for i in range(args.steps):
-        step()
-        evs[i + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
-    kernel_ms = float(np.mean(per_launch_ms))
-    ms_per_step = wall * 1e3 / args.steps
+    if args.flush_mb > 0:
+        scratch = torch.zeros(args.flush_mb * (1 << 20) // 4, dtype=torch.float32, device=dev)
+        flush_sink = torch.zeros((), dtype=torch.float32, device=dev)
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in pairs:
+            if args.flush_kind == "write":
+                scratch.add_(1.0)  # reads and rewrites the buffer: the cache holds (dirty) scratch, not inputs
+            else:
+                flush_sink.copy_(scratch.max())  # reads the buffer: the cache holds clean scratch lines
+            e0.record()
+            step()
+            e1.record()
+        torch.cuda.synchronize()
+        per_launch_ms = [e0.elapsed_time(e1) for e0, e1 in pairs]
+        kernel_ms = float(np.mean(per_launch_ms))
+        ms_per_step = kernel_ms
+    else:
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        t0 = time.perf_counter()
+        evs[0].record()
+        for i in range(args.steps):
+            step()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+        kernel_ms = float(np.mean(per_launch_ms))
+        ms_per_step = wall * 1e3 / args.steps
     tokens = w.tokens()
     value = tokens / (ms_per_step * 1e-3)
 
@@ -580,6 +604,8 @@ def main() -> int:
             "dv_split": dvw,
             "segments": nseg,
             "compute_units": cus,
+            **({"cache_flush_mb_between_launches": args.flush_mb, "cache_flush_kind": args.flush_kind}
+               if args.flush_mb > 0 else {}),
             **({"packed_lengths": [int(x) for x in lengths], "entry_point": "sla_forward_varlen"} if args.varlen else {}),
         },
         "roofline": {
