@@ -96,7 +96,12 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     g, tdt = to_device(d, w.dtype, w.variant)
     dev = torch.device("cuda:0")
     dout = torch.from_numpy(cot["d_out"]).to(torch.bfloat16).to(dev)
-    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 1)
+    hm = args.head_major
+    if hm:  # the same values, q / k / v / d_out / decay (and the gradients) laid out [B,H,T,d]
+        for n in ("q", "k", "v") + (("log_decay",) if w.variant == 1 else ()):
+            g[n] = g[n].permute(0, 2, 1, 3).contiguous()
+        dout = dout.permute(0, 2, 1, 3).contiguous()
+    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, sla.FLAG_HEAD_MAJOR if hm else 0, 1)
     need = sla.sla_backward_workspace_bytes(params)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     gr = {
@@ -146,7 +151,8 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
         "data": "synthetic",
         "config": {
             "workload": f"{w.name}: backward of SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} "
-                        f"dk={w.dk} dv={w.dv} bf16 in/out, dual head-softmax gates, no state cotangents",
+                        f"dk={w.dk} dv={w.dv} bf16 in/out, dual head-softmax gates, no state cotangents"
+                        + (", wide tensors laid out [B,H,T,d]" if hm else ""),
             "kernel": "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
                       "sla_bwd_logits_kernel x2",
         },
@@ -156,7 +162,7 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name + ":backward"),
+            "traffic": None if hm else MEASURED_TRAFFIC_BYTES.get(w.name + ":backward"),
             "kernel_us": call_ms * 1e3,
             "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
             "algorithmic_bytes": abytes,
@@ -185,7 +191,10 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
                               d["log_decay"] if w.variant == 0 else d["log_decay"][:1], cot["d_out"][:1])
             step()
             torch.cuda.synchronize()
-            f64 = lambda t: t[:1].to(torch.float32).cpu().numpy().astype(np.float64)
+            def f64(t):
+                if hm and t.dim() == 4:
+                    t = t.permute(0, 2, 1, 3)
+                return t[:1].to(torch.float32).cpu().numpy().astype(np.float64)
             names = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_logits": "dq_logits", "dk_logits": "dk_logits"}
             if w.variant == 1:
                 names["dlog_decay"] = "dlog_decay"

@@ -60,7 +60,8 @@ typedef enum {
 
 /* sla_params.flags.  SLA_FLAG_HEAD_MAJOR: q, k, v, out and the GLA log_decay are laid out [B,H,T,d] instead of
  * [B,T,H,d], so that every (batch, head) pair streams one contiguous region of memory (measurably kinder to the
- * DRAM than 256-byte pieces 4 KB apart).  Logits, beta, the delta rule's decay and the states keep their layouts. */
+ * DRAM than 256-byte pieces 4 KB apart).  For sla_backward the same holds for d_out, dq, dk, dv and dlog_decay.
+ * Logits and their gradients, beta, the delta rule's decay and the states keep their layouts. */
 #define SLA_FLAG_HEAD_MAJOR 1
 
 /* Problem description (host memory, read during the call only). */
@@ -75,7 +76,8 @@ typedef struct {
     int32_t dv_split; /* 0 = let the library choose; else value columns per workgroup: 16, 32, 64 or 128 (<= dv).
                         A scheduling knob only: the result does not depend on it beyond nothing at all
                         (each output column is computed by exactly one workgroup in a fixed order). */
-    int32_t flags;   /* 0, or SLA_FLAG_HEAD_MAJOR for sla_forward / sla_forward_ws (every other entry point: 0) */
+    int32_t flags;   /* 0, or SLA_FLAG_HEAD_MAJOR for sla_forward / sla_forward_ws / sla_backward (every other entry
+                        point: 0) */
     int32_t segments; /* schedule for shapes with few (batch, head) pairs, RetNet and GLA only: T is cut into
                          this many segments that run in parallel (a pre-pass computes each segment's end state
                          from a zero entry state, a small kernel chains them through the segments' decays, the

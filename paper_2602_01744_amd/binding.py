@@ -302,21 +302,25 @@ def sla_backward(params, q, k, v, q_head_logits, k_head_logits, log_decay, initi
 
 
 def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_out, initial_state=None,
-             d_final_state=None, *, want_d_initial_state: bool = False, workspace=None):
+             d_final_state=None, *, want_d_initial_state: bool = False, workspace=None, head_major: bool = False):
     """Gradients of ``forward`` (RetNet, GLA; bfloat16) on the current CUDA(HIP) device and stream.  Returns a dict
     of new tensors: dq, dk, dv, dq_head_logits, dk_head_logits (None without k_head_logits), dlog_decay (GLA only,
     else None) and d_initial_state (None unless asked for)."""
     import torch
 
     assert q.is_cuda and q.dtype == torch.bfloat16
-    B, T, H, dk = q.shape
+    if head_major:  # q, k, v, d_out, the GLA decay and their gradients are [B,H,T,d]
+        B, H, T, dk = q.shape
+    else:
+        B, T, H, dk = q.shape
     dv = v.shape[-1]
-    for t, shape, dt in ((q, (B, T, H, dk), q.dtype), (k, (B, T, H, dk), q.dtype), (v, (B, T, H, dv), q.dtype),
-                         (d_out, (B, T, H, dv), q.dtype), (q_head_logits, (B, T, H), torch.float32),
+    wide = (lambda d: (B, H, T, d)) if head_major else (lambda d: (B, T, H, d))
+    for t, shape, dt in ((q, wide(dk), q.dtype), (k, wide(dk), q.dtype), (v, wide(dv), q.dtype),
+                         (d_out, wide(dv), q.dtype), (q_head_logits, (B, T, H), torch.float32),
                          (k_head_logits, (B, T, H), torch.float32), (initial_state, (B, H, dk, dv), torch.float32),
                          (d_final_state, (B, H, dk, dv), torch.float32)):
         assert t is None or (tuple(t.shape) == shape and t.dtype == dt and t.is_contiguous() and t.is_cuda)
-    want = {RETNET: ((H,), torch.float32), GLA: ((B, T, H, dk), q.dtype)}[variant]
+    want = {RETNET: ((H,), torch.float32), GLA: (tuple(q.shape), q.dtype)}[variant]
     assert tuple(log_decay.shape) == want[0] and log_decay.dtype == want[1] and log_decay.is_contiguous()
     dev = q.device
     g = {
@@ -328,7 +332,7 @@ def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_o
         "dlog_decay": torch.empty_like(log_decay) if variant == GLA else None,
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, 0, 1)
+    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, FLAG_HEAD_MAJOR if head_major else 0, 1)
     need = sla_backward_workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)

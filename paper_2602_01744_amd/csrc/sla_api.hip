@@ -202,7 +202,7 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
                          void* workspace, size_t workspace_bytes, const int32_t* cu, bool packed, void* stream) {
     int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->flags != 0) return SLA_ERR_UNSUPPORTED;
+    if (p->variant == SLA_GDN || p->dtype != SLA_BF16 || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !d_out || !dq || !dk || !dv || !dq_head_logits)
             return SLA_ERR_NULL;

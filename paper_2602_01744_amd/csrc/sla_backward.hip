@@ -74,6 +74,7 @@ struct BArgs {
     int B, T, H;
     size_t rows;             // tokens in all: B * T, or the packed total
     const int* cu;           // packed variable-length batch: sequence b is tokens cu[b] .. cu[b+1]-1 of T; else null
+    bool head_major;         // q, k, v, d_out, the GLA decay and their gradients are [B,H,T,d] instead of [B,T,H,d]
 };
 
 __device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
@@ -323,15 +324,15 @@ struct ColLoader {
 template <int DK>
 __device__ __forceinline__ ColLoader make_col_loader(const BArgs& a, size_t tok0, int T, int h, int col, int lane) {
     ColLoader c;
-    const int tstride = a.H * DK * 2;
-    const size_t base = tok0 * a.H * DK;
+    const int tstride = (a.head_major ? 1 : a.H) * DK * 2;
+    const size_t base = a.head_major ? ((tok0 / a.T) * a.H + h) * (size_t)a.T * DK : tok0 * a.H * DK;
     c.rq = __builtin_amdgcn_make_buffer_rsrc((void*)(a.q + base), 0, T * tstride, kRsrcWord3);
     c.rk = __builtin_amdgcn_make_buffer_rsrc((void*)(a.k + base), 0, T * tstride, kRsrcWord3);
     c.rld = __builtin_amdgcn_make_buffer_rsrc((void*)((a.ld ? a.ld : a.q) + base), 0, a.ld ? T * tstride : 0, kRsrcWord3);
     c.gq = a.gq + tok0 * a.H + h;
     c.gk = a.gk + tok0 * a.H + h;
     c.tstride = tstride;
-    c.voff = (h * DK + col) * 2;
+    c.voff = ((a.head_major ? 0 : h * DK) + col) * 2;
     c.T = T;
     c.lane = lane;
     c.H = a.H;
@@ -418,6 +419,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
         T = end - start;
         tok0 = (size_t)start;
     }
+    // rows of the d-wide tensors: token tau of this sequence and head is row wide0 + tau * wstep
+    const size_t wide0 = a.head_major ? (size_t)bh * a.T : tok0 * H + h, wstep = a.head_major ? 1 : H;
     const int nb = (T + kTok - 1) / kTok;
     const Ring ring = ring_init(smem, L::bytes, tid);
 
@@ -466,7 +469,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
                         const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
-                        const size_t row = (tok0 + min(blk * kTok + t, T - 1)) * H + h;
+                        const size_t row = wide0 + (size_t)min(blk * kTok + t, T - 1) * wstep;
                         p.a[rep] = load16(a.dout + row * DV + 8 * e8);
                         p.b[rep] = load16(a.v + row * DV + 8 * e8);
                     }
@@ -539,12 +542,12 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
         part = reduce_groups(part);
         const int tok = t0 + r;
         if (tok < T) {
-            const size_t row = (tok0 + tok) * H + h;
+            const size_t row = (tok0 + tok) * H + h, wrow = wide0 + (size_t)tok * wstep;
             if (g == 0) a.part_q[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
             float dqv[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) dqv[i] = gq * dqp[i];
-            *(u2*)(a.dq + row * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
+            *(u2*)(a.dq + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
         }
         if constexpr (VAR == SLA_GLA) {
             // sum of q * dq over the block (fp32, from the unrounded dq): the dk sweep needs it exactly for the
@@ -622,6 +625,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         T = end - start;
         tok0 = (size_t)start;
     }
+    // rows of the d-wide tensors: token tau of this sequence and head is row wide0 + tau * wstep
+    const size_t wide0 = a.head_major ? (size_t)bh * a.T : tok0 * H + h, wstep = a.head_major ? 1 : H;
     const int nb = (T + kTok - 1) / kTok;
     const Ring ring = ring_init(smem, L::bytes, tid);
 
@@ -633,18 +638,19 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
             producer_run<PreKeysE>(
                 ring, smem, L::bytes, team, nb,
                 [&](int I, PreKeysE& p) {
-                    const size_t row = (tok0 + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
+                    const int tau = min((nb - 1 - I) * kTok + t, T - 1);
+                    const size_t row = (tok0 + tau) * H + h, wrow = wide0 + (size_t)tau * wstep;
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 32 * j);
-                        p.kx[j] = load16(a.k + row * DK + d0 + 32 * j);
-                        p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
+                        if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + wrow * DK + d0 + 32 * j);
+                        p.kx[j] = load16(a.k + wrow * DK + d0 + 32 * j);
+                        p.qx[j] = load16(a.q + wrow * DK + d0 + 32 * j);
                     }
                     if constexpr (VAR == SLA_GLA) {
                         const float* bs = a.bsum + (block_id(tok0, (nb - 1 - I) * kTok, b) * H + h) * DK + d0;
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            p.dq[j] = load16(a.dq + row * DK + d0 + 32 * j);
+                            p.dq[j] = load16(a.dq + wrow * DK + d0 + 32 * j);
                             p.bs[2 * j] = *(const f4*)(bs + 32 * j);  // the same address in all 16 token lanes
                             p.bs[2 * j + 1] = *(const f4*)(bs + 32 * j + 4);
                         }
@@ -699,9 +705,10 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
 #pragma unroll
                     for (int rep = 0; rep < R; ++rep) {
                         const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
-                        const size_t row = (tok0 + min((nb - 1 - I) * kTok + t, T - 1)) * H + h;
-                        p.a[rep] = load16(a.dout + row * DV + 8 * e8);
-                        p.b[rep] = load16(a.v + row * DV + 8 * e8);
+                        const int tau = min((nb - 1 - I) * kTok + t, T - 1);
+                        const size_t row = (tok0 + tau) * H + h, wrow = wide0 + (size_t)tau * wstep;
+                        p.a[rep] = load16(a.dout + wrow * DV + 8 * e8);
+                        p.b[rep] = load16(a.v + wrow * DV + 8 * e8);
                         p.gq[rep] = a.gq[row];
                     }
                 },
@@ -793,10 +800,10 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         part = reduce_groups(part);
         const int tok = t0 + r;
         const bool ok = tok < T;
-        const size_t row = (tok0 + (ok ? tok : 0)) * H + h;
+        const size_t row = (tok0 + (ok ? tok : 0)) * H + h, wrow = wide0 + (size_t)(ok ? tok : 0) * wstep;
         if (ok) {
             if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
-            *(u2*)(a.dk + row * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+            *(u2*)(a.dk + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
         }
         if constexpr (VAR == SLA_GLA) {
             // dlog_decay_t = sum_{s >= t} (q_s dq_s - k_s dk_s): inside the block from the staged per-token values,
@@ -808,7 +815,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                 dl[i] = sq - sk + run[i];
                 run[i] += bs4[i] - row_first(sk);
             }
-            if (ok) *(u2*)(a.dld + row * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
+            if (ok) *(u2*)(a.dld + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
         }
         // dS^T <- dS^T A + dy^T qa
 #pragma unroll
@@ -867,6 +874,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
         T = end - start;
         tok0 = (size_t)start;
     }
+    // rows of the d-wide tensors: token tau of this sequence and head is row wide0 + tau * wstep
+    const size_t wide0 = a.head_major ? (size_t)bh * a.T : tok0 * H + h, wstep = a.head_major ? 1 : H;
     const int nb = (T + kTok - 1) / kTok;
     const Ring ring = ring_init(smem, L::bytes, tid);
 
@@ -881,20 +890,22 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
             ring, smem, L::bytes, team, nb,
             [&](int I, PreVals<N>& p) {
                 const int t0 = (nb - 1 - I) * kTok;
-                const size_t row = (tok0 + min(t0 + t, T - 1)) * H + h;
+                const int tau = min(t0 + t, T - 1);
+                const size_t row = (tok0 + tau) * H + h, wrow = wide0 + (size_t)tau * wstep;
 #pragma unroll
                 for (int j = 0; j < N; ++j) {
-                    if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + row * DK + d0 + 32 * j);
-                    p.kx[j] = load16(a.k + row * DK + d0 + 32 * j);
-                    p.qx[j] = load16(a.q + row * DK + d0 + 32 * j);
+                    if constexpr (VAR == SLA_GLA) p.ld[j] = load16(a.ld + wrow * DK + d0 + 32 * j);
+                    p.kx[j] = load16(a.k + wrow * DK + d0 + 32 * j);
+                    p.qx[j] = load16(a.q + wrow * DK + d0 + 32 * j);
                 }
                 p.gk = a.gk[row];
                 if (m == 0) {  // uniform over the wave
 #pragma unroll
                     for (int rep = 0; rep < 2; ++rep) {
                         const int st = r, se8 = g + 4 * rep;
-                        const size_t srow = (tok0 + min(t0 + st, T - 1)) * H + h;
-                        p.sl[rep] = load16(slice_src + srow * DV + 8 * se8);
+                        const int stau = min(t0 + st, T - 1);
+                        const size_t srow = (tok0 + stau) * H + h;
+                        p.sl[rep] = load16(slice_src + (wide0 + (size_t)stau * wstep) * DV + 8 * se8);
                         p.gq[rep] = a.gq[srow];
                     }
                 }
@@ -992,8 +1003,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
         consumer_release(ring, blk);  // every operand of the block is in registers
         const int tok = t0 + r;
         if (tok < T) {
-            const size_t row = (tok0 + tok) * H + h;
-            *(u2*)(a.dv + row * DV + sbase + cb + 4 * g) =
+            *(u2*)(a.dv + (wide0 + (size_t)tok * wstep) * DV + sbase + cb + 4 * g) =
                 u2{pack2(gk * (Ys[0] + Yi[0]), gk * (Ys[1] + Yi[1])), pack2(gk * (Ys[2] + Yi[2]), gk * (Ys[3] + Yi[3]))};
         }
         // dS <- diag(A) dS + qa^T dy
@@ -1154,6 +1164,7 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
     a.s0 = s0; a.dsf = dsf;
     a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.dld = (uint16_t*)dld; a.ds0 = ds0;
     a.B = p.B; a.T = p.T; a.H = p.H; a.rows = rows; a.cu = cu;
+    a.head_major = (p.flags & SLA_FLAG_HEAD_MAJOR) != 0;
 
     const unsigned eb = kEwThreads, per = eb / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
     if (rows > 0) {

@@ -236,10 +236,10 @@ def test_varlen_rejects_bad_calls(lib):
     assert sla.sla_backward_varlen_workspace_bytes(p) == sla.sla_backward_workspace_bytes(one) + extra
 
 
-def test_layout_flag_is_a_forward_only_option(lib):
+def test_layout_flag_is_for_rectangular_forward_and_backward(lib):
     hm = _ok_params(flags=1)
     assert _call(hm) == 0                                    # sla_forward accepts SLA_FLAG_HEAD_MAJOR
     assert _call(_ok_params(flags=2)) == -3                  # unknown flag bits
-    assert _bwd(hm) == -3
+    assert _bwd(hm, ws_bytes=16) == -6                       # sla_backward too: validation gets as far as the workspace
     assert sla.sla_forward_varlen(hm, A, A, A, A, A, A, 0, A, 0, A, A, 0) == -3
     assert sla.sla_gate_logits(hm, A, A, A, A, A, A, 0) == -3

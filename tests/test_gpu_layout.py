@@ -47,3 +47,29 @@ def test_head_major_widths_and_ragged_length():
                                hm(g["log_decay"]), head_major=True)
         torch.cuda.synchronize()
         assert torch.equal(out.permute(0, 2, 1, 3), ref_out) and torch.equal(fin, ref_fin)
+
+
+@pytest.mark.parametrize("variant", [RETNET, GLA])
+def test_backward_head_major_matches_token_major(variant):
+    import torch
+    import paper_2602_01744_amd as sla
+
+    B, T, H, dk, dv = 2, 203, 5, 128, 64
+    d = si.custom(variant, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=3300 + variant)
+    g, _ = to_device(d, "bf16", variant)
+    cot = si.cotangents(B, T, H, dk, dv, seed=3301, final_state=True)
+    dout = torch.from_numpy(cot["d_out"]).to(torch.bfloat16).cuda()
+    dsf = torch.from_numpy(cot["d_final_state"]).cuda()
+    s0 = torch.from_numpy(si.initial_state(B, H, dk, dv, seed=33)).cuda()
+    ref = sla.backward(variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], dout, s0, dsf,
+                       want_d_initial_state=True)
+    hm = lambda t: t.permute(0, 2, 1, 3).contiguous()
+    ld = hm(g["log_decay"]) if variant == GLA else g["log_decay"]
+    got = sla.backward(variant, hm(g["q"]), hm(g["k"]), hm(g["v"]), g["q_logits"], g["k_logits"], ld, hm(dout), s0, dsf,
+                       want_d_initial_state=True, head_major=True)
+    torch.cuda.synchronize()
+    for n in ("dq", "dk", "dv", "dlog_decay"):
+        if ref[n] is not None and ref[n].dim() == 4:
+            assert torch.equal(got[n].permute(0, 2, 1, 3), ref[n]), n
+    for n in ("dq_head_logits", "dk_head_logits", "d_initial_state"):
+        assert torch.equal(got[n], ref[n]), n
