@@ -86,7 +86,6 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     t.y = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, t);
 }
-__device__ __forceinline__ uint16_t bf_bits(float x) { return (uint16_t)(pack2(x, 0.f) & 0xffffu); }
 __device__ __forceinline__ s4 pack4(f4 c) {
     u2 t;
     t.x = pack2(c[0], c[1]);
@@ -152,9 +151,7 @@ __device__ __forceinline__ s4 get_T(const uint16_t* tile, int col, int g) { retu
 // Producer loads are unconditional (tokens past the end read the last token's row) and are zeroed when they are
 // staged: a load under a lane mask would have to complete at the join, which defeats loading blocks ahead.
 __device__ __forceinline__ u4 load16(const uint16_t* p) { return *(const u4*)p; }
-__device__ __forceinline__ u2 load8(const uint16_t* p) { return *(const u2*)p; }
 __device__ __forceinline__ u4 keep(u4 x, bool ok) { return u4{ok ? x[0] : 0u, ok ? x[1] : 0u, ok ? x[2] : 0u, ok ? x[3] : 0u}; }
-__device__ __forceinline__ u2 keep(u2 x, bool ok) { return u2{ok ? x[0] : 0u, ok ? x[1] : 0u}; }
 
 // Workgroups are dealt to the eight XCDs round-robin by blockIdx, and each XCD has its own L2.  The slices of one
 // (batch, head) read the same dout / v (or q / k / decay) rows, so they always share an XCD.  Rectangular batches
