@@ -305,6 +305,103 @@ def bench_prologue(args, w, sla, si, torch, np) -> int:
     return 0
 
 
+def bench_short_conv(args, w, sla, si, torch, np) -> int:
+    """--short-conv: a step is one sla_short_conv_silu call (4 taps) over a [B, T, H*dk] tensor of the workload's
+    dtype, the shape of the query projection in front of the mixer."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import rel_err
+
+    dev = torch.device("cuda:0")
+    C, taps = w.H * w.dk, 4
+    r = np.random.default_rng(w.seed + 80)
+    x = r.standard_normal(size=(w.B, w.T, C), dtype=np.float32)
+    if w.dtype == "bf16":
+        x = si.round_to_bf16(x)
+    wt = (r.standard_normal(size=(C, taps), dtype=np.float32) / 2).astype(np.float32)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    xt, wtt = torch.from_numpy(x).to(tdt).to(dev), torch.from_numpy(wt).to(dev)
+    y = torch.empty_like(xt)
+    raw = (1 if w.dtype == "bf16" else 0, w.B, w.T, C, taps, xt.data_ptr(), wtt.data_ptr(), y.data_ptr(),
+           torch.cuda.current_stream(dev).cuda_stream)
+
+    def step():
+        rc = sla.sla_short_conv_silu(*raw)
+        if rc != 0:
+            raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    for _ in range(args.settle + args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    kernel_ms = float(np.mean(per_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    es = 2 if w.dtype == "bf16" else 4
+    abytes = 2 * w.B * w.T * C * es + C * taps * 4
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "tokens/sec short causal convolution + SiLU (4 taps)",
+        "value": w.tokens() / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "settle_launches": args.settle,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: short convolution + SiLU over [B={w.B}, T={w.T}, C={C}] {w.dtype}, {taps} taps, fp32 weights",
+            "kernel": f"sla_short_conv_silu_kernel<{'true' if w.dtype == 'bf16' else 'false'}, {taps}>",
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "kernel_us": kernel_ms * 1e3,
+            "kernel_us_min": float(np.min(per_ms)) * 1e3,
+            "algorithmic_bytes": abytes,
+        },
+    }
+    if not args.no_cpu_baseline or not args.no_parity:
+        from oracle import sla_numpy
+
+        rows = min(w.B, 2)
+        t0 = time.perf_counter()
+        want = sla_numpy.short_conv_silu(x[:rows], wt)
+        cpu_s = time.perf_counter() - t0
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {
+                "value": rows * w.T / cpu_s,
+                "unit": "tokens/s",
+                "cores": 1,
+                "kind": "oracle",
+                "sample": f"numpy fp64 statement on {rows} batch row(s), {cpu_s:.2f} s wall",
+            }
+        if not args.no_parity:
+            step()
+            torch.cuda.synchronize()
+            result["parity"] = {
+                "rel_err": rel_err(y[:rows].to(torch.float32).cpu().numpy().astype(np.float64), want),
+                "definition": "max|x - oracle| / max|oracle|",
+            }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def bench_decode(args, w, sla, si, torch, np) -> int:
     """--workload decode_*: a step is one recurrent decode step (sla_decode_step) over the batch; the state
     stays resident and is updated in place, as in serving."""
@@ -462,6 +559,8 @@ def main() -> int:
     ap.add_argument("--varlen", action="store_true",
                     help="forward only: the workload's B*T tokens as one packed batch of mixed-length sequences "
                          "(sla_forward_varlen; lengths from sla_inputs.packed_lengths)")
+    ap.add_argument("--short-conv", action="store_true",
+                    help="time sla_short_conv_silu (the delta-rule blocks' feature map) on a [B,T,H*dk] tensor")
     ap.add_argument("--prologue", action="store_true",
                     help="time sla_gate_logits (the projections in front of the head softmax) on the workload's q, k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -489,6 +588,8 @@ def main() -> int:
         return bench_backward(args, w, sla, si, torch, np)
     if args.prologue:
         return bench_prologue(args, w, sla, si, torch, np)
+    if args.short_conv:
+        return bench_short_conv(args, w, sla, si, torch, np)
     d = si.generate(w)
 
     sys.path.insert(0, os.path.join(ROOT, "tests"))

@@ -219,6 +219,20 @@ int sla_backward_varlen(const sla_params* p, const void* q, const void* k, const
                         void* workspace, size_t workspace_bytes, void* stream);
 size_t sla_backward_varlen_workspace_bytes(const sla_params* p);
 
+/*
+ * Short causal convolution along the tokens followed by SiLU, per channel: the feature map that the Gated DeltaNet
+ * blocks of Sec. 5.1 ("Model Configuration": short-convolution module and SiLU) apply in front of q and k (and v),
+ *     y[b,t,c] = silu( sum_{i < taps} w[c,i] * x[b, t - (taps-1) + i, c] ),   x = 0 before the sequence.
+ * One streaming pass; call it once per tensor.  Rectangular batches only (a packed batch would need the window to
+ * stop at sequence boundaries).
+ *
+ *   x, y    [B,T,channels]  dtype   device; y written; must not overlap
+ *   w       [channels,taps] fp32    device; tap taps-1 multiplies the current token
+ *   channels a multiple of 8, 8 .. 65536;  taps 1 .. 4;  dtype SLA_F32 or SLA_BF16;  B, T >= 0
+ */
+int sla_short_conv_silu(int dtype, int B, int T, int channels, int taps, const void* x, const float* w, void* y,
+                        void* stream);
+
 /* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
 size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 

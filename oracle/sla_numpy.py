@@ -54,6 +54,23 @@ def gate_logits(x, w) -> np.ndarray:
     return out
 
 
+def short_conv_silu(x, w) -> np.ndarray:
+    """The feature map of the Gated DeltaNet blocks (Sec. 5.1, "Model Configuration"): a short causal convolution
+    along the tokens, per channel, followed by SiLU.  x [B,T,C], w [C,K]; tap K-1 multiplies the current token,
+    inputs before the sequence are zero."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    B, T, C = x.shape
+    K = w.shape[1]
+    s = np.zeros_like(x)
+    for t in range(T):
+        for i in range(K):
+            src = t - (K - 1) + i
+            if src >= 0:
+                s[:, t, :] += w[:, i] * x[:, src, :]
+    return s / (1.0 + np.exp(-s))
+
+
 def recurrent(
     variant: int,
     q,

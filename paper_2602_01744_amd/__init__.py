@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     sla_backward_workspace_bytes,
     sla_check_args,
     sla_gate_logits,
+    sla_short_conv_silu,
     sla_decode_step,
     sla_default_dv_split,
     sla_forward,
@@ -37,6 +38,7 @@ from .binding import (  # noqa: F401
     backward,
     backward_varlen,
     gate_logits,
+    short_conv_silu,
     decode_step,
 )
 

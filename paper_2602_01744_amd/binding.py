@@ -70,6 +70,8 @@ def load_library():
     lib.sla_backward_varlen.argtypes = [pp] + [vp] * 18 + [ctypes.c_size_t, vp]
     lib.sla_backward_varlen_workspace_bytes.restype = ctypes.c_size_t
     lib.sla_backward_varlen_workspace_bytes.argtypes = [pp]
+    lib.sla_short_conv_silu.restype = ctypes.c_int
+    lib.sla_short_conv_silu.argtypes = [ctypes.c_int] * 5 + [vp] * 4
     lib.sla_gate_logits.restype = ctypes.c_int
     lib.sla_gate_logits.argtypes = [pp] + [vp] * 7
     lib.sla_backward.restype = ctypes.c_int
@@ -250,6 +252,28 @@ def backward_varlen(variant: int, q, k, v, q_head_logits, k_head_logits, log_dec
     if rc != 0:
         raise SlaError(rc, sla_status_string(rc))
     return g
+
+
+def sla_short_conv_silu(dtype: int, B: int, T: int, channels: int, taps: int, x, w, y, stream) -> int:
+    """Raw call of the short-convolution + SiLU entry point (integer device addresses or None)."""
+    return int(load_library().sla_short_conv_silu(int(dtype), int(B), int(T), int(channels), int(taps), _p(x), _p(w),
+                                                   _p(y), _p(stream)))
+
+
+def short_conv_silu(x, w):
+    """x [B,T,C] (float32 or bfloat16), w [C,taps] float32 -> silu(causal depthwise convolution) [B,T,C]."""
+    import torch
+
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 3
+    B, T, C = x.shape
+    assert w.dtype == torch.float32 and w.is_contiguous() and w.shape[0] == C
+    y = torch.empty_like(x)
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    rc = sla_short_conv_silu(dtype, B, T, C, w.shape[1], x.data_ptr(), w.data_ptr(), y.data_ptr(),
+                             torch.cuda.current_stream(x.device).cuda_stream)
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return y
 
 
 def sla_gate_logits(params, q, k, w_gq, w_gk, q_head_logits, k_head_logits, stream) -> int:

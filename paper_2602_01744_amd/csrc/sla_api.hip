@@ -17,6 +17,8 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
                     float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu, hipStream_t stream);
 int launch_gate_logits(const sla_params& p, const void* q, const void* k, const float* wq, const float* wk, float* ql,
                        float* kl, int compute_units, hipStream_t stream);
+int launch_short_conv_silu(int dtype, int B, int T, int C, int taps, const void* x, const float* w, void* y,
+                           hipStream_t stream);
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
@@ -261,6 +263,18 @@ int sla_gate_logits(const sla_params* p, const void* q, const void* k, const flo
     const int cus = device_compute_units();
     if (cus <= 0) return SLA_ERR_HIP;
     return sla::launch_gate_logits(*p, q, k, w_gq, w_gk, q_head_logits, k_head_logits, cus, (hipStream_t)stream);
+}
+
+int sla_short_conv_silu(int dtype, int B, int T, int channels, int taps, const void* x, const float* w, void* y,
+                        void* stream) {
+    if (dtype != SLA_F32 && dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0 || channels < 8 || channels > 65536 || (channels & 7)) return SLA_ERR_SHAPE;
+    if (taps < 1 || taps > 4) return SLA_ERR_UNSUPPORTED;
+    if ((int64_t)B * T > (int64_t)1 << 30) return SLA_ERR_SHAPE;
+    if (B > 0 && T > 0 && (!x || !w || !y)) return SLA_ERR_NULL;
+    if ((x && !aligned16(x)) || (y && !aligned16(y)) || (w && !aligned16(w))) return SLA_ERR_ALIGN;
+    if (B == 0 || T == 0) return SLA_OK;
+    return sla::launch_short_conv_silu(dtype, B, T, channels, taps, x, w, y, (hipStream_t)stream);
 }
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {

@@ -116,7 +116,131 @@ int launch_dk(int dk, dim3 grid, hipStream_t stream, const void* q, const void* 
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Short causal convolution along the tokens followed by SiLU, per channel: the feature map Sec. 5.1 ("Model
+// Configuration") names for the Gated DeltaNet blocks in front of q, k (and v),
+//     y[b,t,c] = silu( sum_{i < K} w[c,i] * x[b, t - (K-1) + i, c] ),    x = 0 before the sequence.
+// A streaming kernel: one thread owns eight adjacent channels (16 bytes of a token row) and walks a segment of
+// 64 tokens with the last K-1 inputs in registers; a wave covers 1 KB of every token row it touches.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int kConvSeg = 64;   // tokens per thread
+constexpr int kConvMaxTaps = 4;
+
+template <bool BF16>
+__device__ __forceinline__ void load8(const void* x, size_t off, float* f) {
+    if constexpr (BF16) {
+        const pu4 v = *(const pu4*)((const uint16_t*)x + off);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(v[i] << 16);
+            f[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+        }
+    } else {
+        const pf4 a = *(const pf4*)((const float*)x + off), b = *(const pf4*)((const float*)x + off + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[i] = a[i];
+            f[4 + i] = b[i];
+        }
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store8(void* y, size_t off, const float* f) {
+    if constexpr (BF16) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 pbf2;
+        pu4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pbf2 t;
+            t.x = (__bf16)f[2 * i];
+            t.y = (__bf16)f[2 * i + 1];
+            v[i] = __builtin_bit_cast(uint32_t, t);
+        }
+        *(pu4*)((uint16_t*)y + off) = v;
+    } else {
+        *(pf4*)((float*)y + off) = pf4{f[0], f[1], f[2], f[3]};
+        *(pf4*)((float*)y + off + 4) = pf4{f[4], f[5], f[6], f[7]};
+    }
+}
+
+template <bool BF16, int K>
+__global__ __launch_bounds__(kPThreads) void sla_short_conv_silu_kernel(const void* x, const float* w, void* y, int B,
+                                                                         int T, int C) {
+    const int groups = C / 8, segs = (T + kConvSeg - 1) / kConvSeg;
+    const size_t idx = (size_t)blockIdx.x * kPThreads + threadIdx.x;
+    if (idx >= (size_t)B * segs * groups) return;
+    const int cg = (int)(idx % groups), seg = (int)((idx / groups) % segs), b = (int)(idx / ((size_t)groups * segs));
+    float wt[K][8];  // wt[i][c]: tap i of channel 8 cg + c
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int i = 0; i < K; ++i) wt[i][c] = w[(size_t)(8 * cg + c) * K + i];
+    const int t0 = seg * kConvSeg, t1 = min(T, t0 + kConvSeg);
+    const size_t row0 = (size_t)b * T;
+    float hist[K][8];  // hist[i] = x[t - (K-1) + i] for the token t being produced
+#pragma unroll
+    for (int i = 0; i < K - 1; ++i) {
+        const int t = t0 - (K - 1) + i;
+        if (t >= 0) {
+            load8<BF16>(x, (row0 + t) * C + 8 * cg, hist[i + 1]);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) hist[i + 1][c] = 0.f;
+        }
+    }
+    // eight tokens at a time: their loads are issued together, before any of them is used
+    constexpr int U = 8;
+    for (int tb = t0; tb < t1; tb += U) {
+        float in[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = min(tb + u, t1 - 1);  // past the segment: a repeat of its last token, never stored
+            load8<BF16>(x, (row0 + t) * C + 8 * cg, in[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int i = 0; i < K - 1; ++i)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) hist[i][c] = hist[i + 1][c];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) hist[K - 1][c] = in[u][c];
+            float out[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                float s = 0.f;
+#pragma unroll
+                for (int i = 0; i < K; ++i) s += wt[i][c] * hist[i][c];
+                out[c] = s / (1.f + __builtin_amdgcn_exp2f(-s * 1.4426950408889634f));  // silu(s) = s * sigmoid(s)
+            }
+            if (tb + u < t1) store8<BF16>(y, (row0 + tb + u) * C + 8 * cg, out);
+        }
+    }
+}
+
+template <bool BF16>
+int launch_conv_taps(int taps, dim3 grid, hipStream_t stream, const void* x, const float* w, void* y, int B, int T,
+                     int C) {
+    switch (taps) {
+        case 1: hipLaunchKernelGGL((sla_short_conv_silu_kernel<BF16, 1>), grid, dim3(kPThreads), 0, stream, x, w, y, B, T, C); break;
+        case 2: hipLaunchKernelGGL((sla_short_conv_silu_kernel<BF16, 2>), grid, dim3(kPThreads), 0, stream, x, w, y, B, T, C); break;
+        case 3: hipLaunchKernelGGL((sla_short_conv_silu_kernel<BF16, 3>), grid, dim3(kPThreads), 0, stream, x, w, y, B, T, C); break;
+        case 4: hipLaunchKernelGGL((sla_short_conv_silu_kernel<BF16, 4>), grid, dim3(kPThreads), 0, stream, x, w, y, B, T, C); break;
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
 }  // namespace
+
+int launch_short_conv_silu(int dtype, int B, int T, int C, int taps, const void* x, const float* w, void* y,
+                           hipStream_t stream) {
+    const size_t threads = (size_t)B * ((T + kConvSeg - 1) / kConvSeg) * (C / 8);
+    const dim3 grid((unsigned)((threads + kPThreads - 1) / kPThreads));
+    if (dtype == SLA_BF16) return launch_conv_taps<true>(taps, grid, stream, x, w, y, B, T, C);
+    return launch_conv_taps<false>(taps, grid, stream, x, w, y, B, T, C);
+}
 
 int launch_gate_logits(const sla_params& p, const void* q, const void* k, const float* wq, const float* wk, float* ql,
                        float* kl, int compute_units, hipStream_t stream) {

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_gate_logits", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -243,3 +243,12 @@ def test_layout_flag_is_for_rectangular_forward_and_backward(lib):
     assert _bwd(hm, ws_bytes=16) == -6                       # sla_backward too: validation gets as far as the workspace
     assert sla.sla_forward_varlen(hm, A, A, A, A, A, A, 0, A, 0, A, A, 0) == -3
     assert sla.sla_gate_logits(hm, A, A, A, A, A, A, 0) == -3
+
+
+def test_short_conv_rejects_bad_calls(lib):
+    call = lambda dtype=sla.BF16, B=2, T=64, C=256, taps=4, x=A, w=A, y=A: sla.sla_short_conv_silu(dtype, B, T, C, taps, x, w, y, 0)
+    assert call(dtype=5) == -3 and call(taps=0) == -3 and call(taps=5) == -3
+    assert call(C=12) == -2 and call(C=0) == -2 and call(B=-1) == -2
+    assert call(x=0) == -1 and call(w=0) == -1 and call(y=0) == -1
+    assert call(y=A + 4) == -4
+    assert call(B=0) == 0 and call(T=0) == 0

@@ -78,3 +78,40 @@ def test_full_size():
     rows = slice(0, 2)  # the oracle on two batch rows
     assert rel_err(ql[rows], sla_numpy.gate_logits(d["q"][rows], w["w_gq"])) <= LOGIT_TOL
     assert rel_err(kl[rows], sla_numpy.gate_logits(d["k"][rows], w["w_gk"])) <= LOGIT_TOL
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("taps", [1, 2, 3, 4])
+@pytest.mark.parametrize("B,T,C", [(2, 203, 256), (1, 64, 8), (3, 1, 64), (1, 129, 2048)])
+def test_short_conv_silu_parity(dtype, taps, B, T, C):
+    import torch
+    import paper_2602_01744_amd as sla
+
+    r = np.random.default_rng(1500 + taps + T)
+    x = r.standard_normal(size=(B, T, C)).astype(np.float32)
+    if dtype == "bf16":
+        x = si.round_to_bf16(x)
+    w = (r.standard_normal(size=(C, taps)) / np.sqrt(taps)).astype(np.float32)
+    xt = torch.from_numpy(x).to(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda()
+    y = sla.short_conv_silu(xt, torch.from_numpy(w).cuda())
+    torch.cuda.synchronize()
+    got = y.float().cpu().numpy().astype(np.float64)
+    want = sla_numpy.short_conv_silu(x, w)
+    # fp32: summation order and the hardware exp2 (1 ulp); bf16: the output is rounded to bf16 (2^-9 relative)
+    tol = 1e-5 if dtype == "f32" else 4e-3
+    assert rel_err(got, want) <= tol
+
+
+def test_short_conv_silu_full_size():
+    import torch
+    import paper_2602_01744_amd as sla
+
+    w0 = si.workload("gdn")  # the delta-rule workload's q: [B, T, H * dk]
+    r = np.random.default_rng(1600)
+    C = w0.H * w0.dk
+    x = si.round_to_bf16(r.standard_normal(size=(w0.B, w0.T, C)).astype(np.float32))
+    w = (r.standard_normal(size=(C, 4)) / 2).astype(np.float32)
+    y = sla.short_conv_silu(torch.from_numpy(x).to(torch.bfloat16).cuda(), torch.from_numpy(w).cuda())
+    torch.cuda.synchronize()
+    got = y[:1].float().cpu().numpy().astype(np.float64)  # the oracle on batch row 0
+    assert rel_err(got, sla_numpy.short_conv_silu(x[:1], w)) <= 4e-3

@@ -389,3 +389,29 @@ def test_gate_logits_brute_force_and_selection():
     # linear in x and in w
     np.testing.assert_allclose(ref.gate_logits(2 * x, w) + ref.gate_logits(x, 3 * w), 5 * ref.gate_logits(x, w),
                                rtol=1e-13, atol=1e-13)
+
+
+# ------------------------------------------------------------------ short causal convolution + SiLU (Sec. 5.1, GDN blocks)
+def test_short_conv_silu_against_library_filters():
+    from scipy.signal import lfilter
+    import torch
+
+    r = np.random.default_rng(88)
+    x = r.normal(size=(2, 37, 6))
+    for K in (1, 2, 3, 4):
+        w = r.normal(size=(6, K))
+        got = ref.short_conv_silu(x, w)
+        # an FIR filter per channel: coefficient of x[t - m] is w[c, K-1-m]
+        pre = np.stack([np.stack([lfilter(w[c, ::-1], [1.0], x[b, :, c]) for c in range(6)], axis=-1) for b in range(2)])
+        np.testing.assert_allclose(got, pre / (1.0 + np.exp(-pre)), rtol=1e-12, atol=1e-13)
+        # torch's depthwise conv1d with left padding, then its own SiLU
+        xt = torch.tensor(x).permute(0, 2, 1)
+        yt = torch.nn.functional.conv1d(torch.nn.functional.pad(xt, (K - 1, 0)), torch.tensor(w)[:, None, :], groups=6)
+        np.testing.assert_allclose(got, torch.nn.functional.silu(yt).permute(0, 2, 1).numpy(), rtol=1e-12, atol=1e-13)
+    # one tap of weight 1 is SiLU itself; causality: changing a later input leaves earlier outputs alone
+    one = np.ones((6, 1))
+    np.testing.assert_allclose(ref.short_conv_silu(x, one), x / (1.0 + np.exp(-x)), rtol=1e-14)
+    w = r.normal(size=(6, 4))
+    x2 = x.copy()
+    x2[:, 20:] += 1.0
+    assert np.array_equal(ref.short_conv_silu(x, w)[:, :20], ref.short_conv_silu(x2, w)[:, :20])
