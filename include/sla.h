@@ -159,8 +159,10 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
  *   dlog_decay       GLA: [B,T,H,dk] dtype, written, required;  RetNet: must be NULL (the decay is a constant)
  *   d_initial_state  [B,H,dk,dv] fp32    written, or NULL (not wanted)
  *   workspace        device memory of at least sla_backward_workspace_bytes(p) bytes, 16-byte aligned; holds
- *                    the gates, partial gate gradients and (GLA) q * dq in fp32.  Contents on entry are ignored;
- *                    calls that share a workspace must not overlap.
+ *                    the gates, partial gate gradients and (GLA) block sums of q * dq and the state entering
+ *                    every 512th token of a sequence (dlog_decay is re-derived from rowsum(dS * S) there, so its
+ *                    error does not grow with the sequence length).  Contents on entry are ignored; calls that
+ *                    share a workspace must not overlap.
  * No output may overlap an input or another output.  Everything is enqueued on `stream`; nothing is allocated,
  * freed or synchronised.  Returns a status code; on error nothing is launched.
  */

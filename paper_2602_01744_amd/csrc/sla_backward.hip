@@ -71,6 +71,7 @@ struct BArgs {
     float* part_k;           // [dk/16][B,T,H] partial dG^K
     float* bsum;             // [blocks][H][dk] fp32: sum of q * dq over each 16-token block (GLA); block id below
     float* corr;             // [B,H,dk] rowsum(dS_T * S_T) (GLA with a final-state cotangent)
+    u4* anchor;              // [anchors][H] states (dk x dv, bf16) entering every kAnchor-th block (GLA); layout below
     int B, T, H;
     size_t rows;             // tokens in all: B * T, or the packed total
     const int* cu;           // packed variable-length batch: sequence b is tokens cu[b] .. cu[b+1]-1 of T; else null
@@ -172,6 +173,15 @@ __device__ __forceinline__ int logical_workgroup(int slices, int pairs, bool pac
 // the sequence index is added; ids are unique and at most rows / 16 + B of them exist.
 __device__ __forceinline__ size_t block_id(size_t tok0, int t0, int b) { return (tok0 + (size_t)t0) / kTok + (size_t)b; }
 
+// dlog_decay is a running difference of two sums that nearly cancel, so its rounding error would grow with the
+// distance from the end of the sequence.  Every kAnchor blocks the dq sweep keeps the state entering the block and
+// the dk sweep replaces its running sum by the exact value there, rowsum(dS * S): the error stays that of one span.
+// Anchors sit kAnchor * 16 tokens apart inside a sequence and sequences do not overlap, so the token position
+// divided by the span numbers them without collisions; there are fewer than rows / span + 1 of them.
+constexpr int kAnchor = 32;
+__device__ __forceinline__ bool is_anchor(int blk) { return blk > 0 && (blk & (kAnchor - 1)) == 0; }
+__device__ __forceinline__ size_t anchor_id(size_t tok0, int t0) { return (tok0 + (size_t)t0) / (kAnchor * kTok); }
+
 // Sum over the four 16-lane rows of a wave, returned in every lane: two register swaps (odd rows against even
 // rows, then the upper half against the lower half) instead of a trip through LDS.
 __device__ __forceinline__ float reduce_groups(float x) {
@@ -195,6 +205,13 @@ __device__ __forceinline__ float reduce_groups(float x) {
 constexpr int kSlots = 4;
 constexpr int kTeamWaves = 2;
 constexpr int kConsumers = 4;
+// A kept state is private to the two sweeps, which hold it in the same per-lane tiles: 16-byte piece c of the lane
+// (tiles 2c and 2c+1 as eight bf16) of wave w of slice s sits at [state][s][w][c][lane], so a store or load
+// instruction of a wave covers 1 KiB without gaps.
+template <int DK, int DV>
+__device__ __forceinline__ size_t anchor_offset(size_t state, int slice, int wave) {
+    return ((state * (DK / kCols) + slice) * kConsumers + wave) * (DV / 32) * 64;
+}
 constexpr int kSpinLimit = 1 << 22;
 typedef __attribute__((address_space(3))) int lds_int;
 
@@ -554,6 +571,16 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
             for (int i = 0; i < 4; ++i) bs[i] = row_suffix(tok < T ? qf[i] * gq * dqp[i] : 0.f);
             if (r == 0) *(f4*)(a.bsum + (block_id(tok0, t0, b) * H + h) * DK + sbase + cb + 4 * g) = bs;
         }
+        if constexpr (VAR == SLA_GLA) {
+            if (is_anchor(blk)) {  // the state entering this block, for the dk sweep: bf16, each lane its own tiles
+                u4* st = a.anchor + anchor_offset<DK, DV>(anchor_id(tok0, t0) * H + h, slice, wave) + lane;
+#pragma unroll
+                for (int c = 0; c < DV / 32; ++c) {
+                    const s8 x = join(pack4(ST[2 * c]), pack4(ST[2 * c + 1]));
+                    st[64 * c] = *(const u4*)&x;
+                }
+            }
+        }
         // S^T <- S^T A + v^T kb'
 #pragma unroll
         for (int i = 0; i < DV / 16; ++i) {
@@ -753,6 +780,19 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         }
         const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
+        const bool anchored = VAR == SLA_GLA && is_anchor(nb - 1 - blk);
+        // The state entering this block, kept by the dq sweep: asked for here and used after the update, where the
+        // registers allow it (the widest value dimension reads it at the point of use instead).
+        constexpr bool kEarly = DV <= 128;
+        u4 SA[kEarly ? DV / 32 : 1];
+        const u4* st = a.anchor;
+        if (anchored) {
+            st += anchor_offset<DK, DV>(anchor_id(tok0, t0) * H + h, slice, wave) + lane;
+            if constexpr (kEarly) {
+#pragma unroll
+                for (int c = 0; c < DV / 32; ++c) SA[c] = st[64 * c];
+            }
+        }
         const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
         const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
         const float* GQ = (const float*)(buf + L::oGQ);
@@ -819,6 +859,19 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         for (int i = 0; i < DV / 16; ++i) {
             DST[i] = DST[i] * Ad;
             mma16(DST[i], fdy[i], fqa);
+        }
+        if (anchored) {  // the sum over all later tokens equals rowsum(dS * S) at this boundary: take it from there
+            float z = 0.f;
+#pragma unroll
+            for (int c = 0; c < DV / 32; ++c) {
+                const u4 x = kEarly ? SA[kEarly ? c : 0] : st[64 * c];
+                z += DST[2 * c][0] * bf_lo(x[0]) + DST[2 * c][1] * bf_hi(x[0]) + DST[2 * c][2] * bf_lo(x[1]) +
+                     DST[2 * c][3] * bf_hi(x[1]) + DST[2 * c + 1][0] * bf_lo(x[2]) + DST[2 * c + 1][1] * bf_hi(x[2]) +
+                     DST[2 * c + 1][2] * bf_lo(x[3]) + DST[2 * c + 1][3] * bf_hi(x[3]);
+            }
+            z = reduce_groups(z);  // every lane: the value of key column cb + lane % 16
+#pragma unroll
+            for (int i = 0; i < 4; ++i) run[i] = __shfl(z, 4 * g + i);
         }
     }
 }
@@ -1129,13 +1182,15 @@ int launch_dk(const BArgs& a, int dk, int dv, hipStream_t stream) {
 }  // namespace
 
 // Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q and dG^K (dk/16 planes each); for GLA the sums of
-// q * dq over every 16-token block [rows/16 + B + 1][H,dk] and the final-state term of dlog_decay [B,H,dk].
+// q * dq over every 16-token block [rows/16 + B + 1][H,dk], the final-state term of dlog_decay [B,H,dk] and the
+// states kept every 512 tokens [rows/512 + 1][H,dk,dv] in bf16.
 size_t backward_workspace_floats(const sla_params& p, bool packed) {
     const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T;
     const size_t n = round4(rows * p.H);
     size_t total = n * (2 + 2 * (p.dk / 16));
     if (p.variant == SLA_GLA)
-        total += round4((rows / kTok + p.B + 1) * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk);
+        total += round4((rows / kTok + p.B + 1) * p.H * p.dk) + round4((size_t)p.B * p.H * p.dk) +
+                 round4((rows / (kAnchor * kTok) + 1) * p.H * p.dk * p.dv / 2);
     return total;
 }
 
@@ -1153,10 +1208,11 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
     a.gq = gq; a.gk = gk;
     a.part_q = w; w += n * (p.dk / 16);
     a.part_k = w; w += n * (p.dk / 16);
-    a.bsum = nullptr; a.corr = nullptr;
+    a.bsum = nullptr; a.corr = nullptr; a.anchor = nullptr;
     if (p.variant == SLA_GLA) {
         a.bsum = w; w += round4((rows / kTok + p.B + 1) * p.H * p.dk);
-        a.corr = w;
+        a.corr = w; w += round4((size_t)p.B * p.H * p.dk);
+        a.anchor = (u4*)w;  // 16-byte aligned: every part before it is a multiple of four floats
     }
     a.s0 = s0; a.dsf = dsf;
     a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.dld = (uint16_t*)dld; a.ds0 = ds0;

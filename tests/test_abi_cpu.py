@@ -200,9 +200,11 @@ def test_backward_workspace_size(lib):
     gla = sla.sla_backward_workspace_bytes(_ok_params(B=B, T=T, H=H, dk=dk, dv=dv))
     ret = sla.sla_backward_workspace_bytes(_ok_params(variant=sla.RETNET, B=B, T=T, H=H, dk=dk, dv=dv))
     # gates (2 planes), partial gate gradients (dk/16 planes each); GLA adds the q*dq block sums
-    # [B*T/16 + B + 1][H,dk] and [B,H,dk]
+    # [B*T/16 + B + 1][H,dk], [B,H,dk] and the bf16 states kept every 512 tokens [B*T/512 + 1][H,dk,dv]
     assert ret == 4 * n * (2 + 2 * (dk // 16))
-    assert gla == ret + 4 * ((B * T // 16 + B + 1) * H * dk + B * H * dk)
+    assert gla == ret + 4 * ((B * T // 16 + B + 1) * H * dk + B * H * dk + (B * T // 512 + 1) * H * dk * dv // 2)
+    big = sla.sla_backward_workspace_bytes(_ok_params(B=8, T=2048, H=16, dk=128, dv=128))
+    assert big == 4 * (8 * 2048 * 16 * 18 + (1024 + 9) * 2048 + 8 * 2048 + 33 * 16 * 128 * 128 // 2)
     assert sla.sla_backward_workspace_bytes(_ok_params(variant=sla.GDN)) == 0
     assert sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32)) == 0
 

@@ -131,6 +131,21 @@ def test_strong_decay_domain():
     check_backward(GLA, d, cot, label="decay in [-5, 0]")
 
 
+@pytest.mark.parametrize("T,dv,states", [(4096, 128, False), (8192 + 40, 128, True), (2048 + 512, 256, True)])
+def test_long_sequences_keep_the_decay_gradient_accurate(T, dv, states):
+    """dlog_decay at token t sums q dq - k dk over every later token, two sums that nearly cancel: without the
+    exact re-anchoring every 512 tokens its error grows with the sequence length and passes the bar near 4k tokens."""
+    B, H, dk = 1, 2, 128
+    d = si.custom(GLA, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=77)
+    cot = si.cotangents(B, T, H, dk, dv, seed=78, final_state=states)
+    s0 = si.initial_state(B, H, dk, dv, seed=79) if states else None
+    got, ref = check_backward(GLA, d, cot, s0=s0, want_ds0=states, label=f"long T={T} dv={dv}")
+    # the error of the earliest tokens (the longest sums) is no worse than the bar either
+    scale = np.abs(ref["dlog_decay"]).max()
+    early = np.abs(got["dlog_decay"][:, :512] - ref["dlog_decay"][:, :512]).max() / scale
+    assert early <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("name", ["gla_train", "retnet_train"])
 def test_full_size(name):
     """The bench workload, in the launch configuration bench.py times; the oracle runs on two batch rows."""
