@@ -1,4 +1,4 @@
-"""Gradients of the SLA forward pass (RetNet and GLA instantiations of Sec. 5.1), fp64 numpy.
+"""Gradients of the SLA forward pass (the three instantiations of Sec. 5.1), fp64 numpy.
 
 TEST INFRASTRUCTURE ONLY: the GPU library never imports this module and shares no code with it.
 
@@ -23,6 +23,19 @@ gradient with respect to ``S_t``:
 and the gate gradients go through the head softmax of Eq. 4:
 ``dlogits = G * (dG - sum_h G dG)``.
 
+Gated delta rule (Softmax-GatedDeltaNet, Sec. 5.1), whose step is, with a scalar decay ``alpha_t`` and write
+strength ``beta_t`` per head,
+
+    Sb = alpha_t S_{t-1}       u = beta_t (G^K_t v_t - k_t Sb)       S_t = Sb + k_t^T u
+
+the same walk undoes these three assignments in reverse order:
+
+    du       = k_t dS                  dk_t  = dS u                  (from S_t = Sb + k_t^T u; dSb = dS)
+    dbeta_t  = du . (G^K_t v_t - k_t Sb)
+    dG^K_t   = beta_t du . v_t         dv_t  = beta_t G^K_t du       w = beta_t du
+    dk_t    -= w Sb^T                  dSb  -= k_t^T w               (from the term -beta_t k_t Sb of u)
+    dlog_decay_t = sum(dSb * Sb)       dS    = alpha_t dSb           (from Sb = alpha_t S_{t-1})
+
 States are kept at every ``checkpoint``-th token and recomputed in between, so memory stays
 bounded at full workload sizes; the arithmetic is the same for every choice of ``checkpoint``.
 
@@ -35,13 +48,15 @@ from typing import Dict, Optional
 
 import numpy as np
 
-from .sla_numpy import GLA, RETNET, head_softmax
+from .sla_numpy import GDN, GLA, RETNET, head_softmax
 
 
 def _alpha(variant: int, ld: np.ndarray, t: int) -> np.ndarray:
     """Decay of token t, broadcastable against a state [B,H,dk,dv]."""
     if variant == RETNET:
         return np.exp(ld)[None, :, None, None]
+    if variant == GDN:
+        return np.exp(ld[:, t])[..., None, None]
     return np.exp(ld[:, t])[..., :, None]
 
 
@@ -57,14 +72,18 @@ def backward(
     initial_state=None,
     d_final_state=None,
     checkpoint: int = 64,
+    beta=None,
 ) -> Dict[str, Optional[np.ndarray]]:
     """Gradients of L with respect to every differentiable input.
 
     Returns a dict with dq, dk, dv, dq_logits, dk_logits (None when ``k_logits`` is None),
-    dlog_decay (RetNet: [H]; GLA: [B,T,H,dk]) and dinitial_state.
+    dlog_decay (RetNet: [H]; GLA: [B,T,H,dk]; GDN: [B,T,H]), dbeta (GDN: [B,T,H], else None)
+    and dinitial_state.
     """
-    if variant not in (RETNET, GLA):
-        raise ValueError("gradients are defined here for RetNet and GLA")
+    if variant not in (RETNET, GLA, GDN):
+        raise ValueError(variant)
+    if variant == GDN:
+        bt = np.asarray(beta, dtype=np.float64)
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -76,6 +95,10 @@ def backward(
     gk = head_softmax(k_logits, (B, T, H))
 
     def step(S, t):
+        if variant == GDN:
+            Sb = _alpha(variant, ld, t) * S
+            u = bt[:, t, :, None] * (gk[:, t, :, None] * v[:, t] - np.einsum("bhd,bhdn->bhn", k[:, t], Sb))
+            return Sb + k[:, t][..., :, None] * u[..., None, :]
         return _alpha(variant, ld, t) * S + (gk[:, t, :, None] * k[:, t])[..., :, None] * v[:, t][..., None, :]
 
     # forward sweep: keep the state entering every checkpoint-th token
@@ -91,7 +114,8 @@ def backward(
     dvv = np.zeros_like(v)
     dgq = np.zeros((B, T, H))
     dgk = np.zeros((B, T, H))
-    dld = np.zeros(H) if variant == RETNET else np.zeros((B, T, H, dk))
+    dld = np.zeros(H) if variant == RETNET else np.zeros((B, T, H) if variant == GDN else (B, T, H, dk))
+    dbt = np.zeros((B, T, H)) if variant == GDN else None
     dS = np.zeros((B, H, dk, dv)) if d_final_state is None else np.array(d_final_state, dtype=np.float64)
 
     for seg in sorted(kept.keys(), reverse=True):
@@ -106,6 +130,21 @@ def backward(
             dy = gq[:, t, :, None] * do[:, t]
             dq[:, t] = np.einsum("bhn,bhdn->bhd", dy, S_t)
             dS = dS + q[:, t][..., :, None] * dy[..., None, :]
+            if variant == GDN:
+                a = _alpha(variant, ld, t)
+                Sb = a * S_prev
+                resid = gk[:, t, :, None] * v[:, t] - np.einsum("bhd,bhdn->bhn", k[:, t], Sb)
+                u = bt[:, t, :, None] * resid
+                du = np.einsum("bhd,bhdn->bhn", k[:, t], dS)
+                dbt[:, t] = np.sum(du * resid, axis=-1)
+                dgk[:, t] = bt[:, t] * np.sum(du * v[:, t], axis=-1)
+                dvv[:, t] = (bt[:, t] * gk[:, t])[..., None] * du
+                w = bt[:, t, :, None] * du
+                dkk[:, t] = np.einsum("bhdn,bhn->bhd", dS, u) - np.einsum("bhn,bhdn->bhd", w, Sb)
+                dSb = dS - k[:, t][..., :, None] * w[..., None, :]
+                dld[:, t] = np.sum(dSb * Sb, axis=(-1, -2))
+                dS = a * dSb
+                continue
             dSv = np.einsum("bhdn,bhn->bhd", dS, v[:, t])
             dkk[:, t] = gk[:, t, :, None] * dSv
             dvv[:, t] = gk[:, t, :, None] * np.einsum("bhd,bhdn->bhn", k[:, t], dS)
@@ -128,5 +167,6 @@ def backward(
         "dq_logits": softmax_backward(gq, dgq),
         "dk_logits": None if k_logits is None else softmax_backward(gk, dgk),
         "dlog_decay": dld,
+        "dbeta": dbt,
         "dinitial_state": dS,
     }
