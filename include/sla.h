@@ -177,6 +177,33 @@ int sla_backward(const sla_params* p, const void* q, const void* k, const void* 
 size_t sla_backward_workspace_bytes(const sla_params* p);
 
 /*
+ * Backward pass of sla_forward for the gated delta rule (Softmax-GatedDeltaNet, Sec. 5.1, with the gates of
+ * Eq. 4-6): p->variant must be SLA_GDN, p->dtype SLA_BF16, p->flags 0 (else SLA_ERR_UNSUPPORTED).  Same objective
+ * and conventions as sla_backward; the step differentiated is
+ *     Sb = exp(log_decay_t) S_{t-1},  u = beta_t (G^K_t v_t - k_t Sb),  S_t = Sb + k_t^T u,  out_t = G^Q_t q_t S_t.
+ *
+ *   q, k, v, q_head_logits, k_head_logits, initial_state, d_out, d_final_state,
+ *   dq, dk, dv, dq_head_logits, dk_head_logits, d_initial_state      as for sla_backward
+ *   log_decay, beta  [B,T,H] fp32   as for sla_forward; required
+ *   dlog_decay       [B,T,H] fp32   written; required
+ *   dbeta            [B,T,H] fp32   written; required
+ *   workspace        device memory of at least sla_backward_gdn_workspace_bytes(p) bytes, 16-byte aligned (gates,
+ *                    partial sums, and three fp32 tensors the size of v, v and k that pass the delta rule's
+ *                    feedback terms between the four sweeps).  Contents on entry are ignored; calls that share a
+ *                    workspace must not overlap.
+ * The sweeps run token by token in fp32 vector arithmetic (inputs are read as bf16, outputs rounded once).
+ * Everything is enqueued on `stream`; nothing is allocated, freed or synchronised.  Returns a status code; on error
+ * nothing is launched.
+ */
+int sla_backward_gdn(const sla_params* p, const void* q, const void* k, const void* v,
+                     const float* q_head_logits, const float* k_head_logits, const float* log_decay,
+                     const float* beta, const float* initial_state, const void* d_out,
+                     const float* d_final_state, void* dq, void* dk, void* dv, float* dq_head_logits,
+                     float* dk_head_logits, float* dlog_decay, float* dbeta, float* d_initial_state,
+                     void* workspace, size_t workspace_bytes, void* stream);
+size_t sla_backward_gdn_workspace_bytes(const sla_params* p);
+
+/*
  * Gate logits: the scores Eq. 4 takes the head softmax of, from the (feature-mapped) queries and keys and the
  * two gate matrices W_GQ, W_GK in R^{d x H} of Sec. 3.2, with d the head width (the reading under which the two
  * matrices add the 0.05 M parameters that the "Parameter Efficiency" paragraph counts):

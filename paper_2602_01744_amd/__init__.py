@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     load_library,
     sla_backward,
     sla_backward_workspace_bytes,
+    sla_backward_gdn,
+    sla_backward_gdn_workspace_bytes,
     sla_check_args,
     sla_gate_logits,
     sla_short_conv_silu,
@@ -36,6 +38,7 @@ from .binding import (  # noqa: F401
     forward,
     forward_varlen,
     backward,
+    backward_gdn,
     backward_varlen,
     gate_logits,
     short_conv_silu,

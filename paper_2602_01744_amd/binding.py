@@ -76,6 +76,10 @@ def load_library():
     lib.sla_gate_logits.argtypes = [pp] + [vp] * 7
     lib.sla_backward.restype = ctypes.c_int
     lib.sla_backward.argtypes = [pp] + [vp] * 17 + [ctypes.c_size_t, vp]
+    lib.sla_backward_gdn.restype = ctypes.c_int
+    lib.sla_backward_gdn.argtypes = [pp] + [vp] * 19 + [ctypes.c_size_t, vp]
+    lib.sla_backward_gdn_workspace_bytes.restype = ctypes.c_size_t
+    lib.sla_backward_gdn_workspace_bytes.argtypes = [pp]
     lib.sla_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.sla_backward_workspace_bytes.argtypes = [pp]
     lib.sla_workspace_bytes.restype = ctypes.c_size_t
@@ -366,6 +370,70 @@ def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_o
         ptr(d_out), ptr(d_final_state), ptr(g["dq"]), ptr(g["dk"]), ptr(g["dv"]), ptr(g["dq_head_logits"]),
         ptr(g["dk_head_logits"]), ptr(g["dlog_decay"]), ptr(g["d_initial_state"]), ptr(workspace),
         workspace.numel() * workspace.element_size(), torch.cuda.current_stream(dev).cuda_stream,
+    )
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return g
+
+
+def sla_backward_gdn_workspace_bytes(params: SlaParams) -> int:
+    return int(load_library().sla_backward_gdn_workspace_bytes(ctypes.byref(params)))
+
+
+def sla_backward_gdn(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, d_out,
+                     d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, dbeta, d_initial_state,
+                     workspace, workspace_bytes, stream) -> int:
+    """Raw call of the gated delta rule's backward: every pointer argument is an integer device address or None."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_backward_gdn(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta),
+            _p(initial_state), _p(d_out), _p(d_final_state), _p(dq), _p(dk), _p(dv), _p(dq_head_logits),
+            _p(dk_head_logits), _p(dlog_decay), _p(dbeta), _p(d_initial_state), _p(workspace),
+            ctypes.c_size_t(int(workspace_bytes)), _p(stream),
+        )
+    )
+
+
+def backward_gdn(q, k, v, q_head_logits, k_head_logits, log_decay, beta, d_out, initial_state=None,
+                 d_final_state=None, *, want_d_initial_state: bool = False, workspace=None):
+    """Gradients of ``forward(GDN, ...)`` (bfloat16 q, k, v, d_out [B,T,H,d]; float32 logits, log_decay and beta
+    [B,T,H]) on the current CUDA(HIP) device and stream.  Returns a dict of new tensors: dq, dk, dv,
+    dq_head_logits, dk_head_logits (None without k_head_logits), dlog_decay, dbeta and d_initial_state (None unless
+    asked for)."""
+    import torch
+
+    assert q.is_cuda and q.dtype == torch.bfloat16
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    for t, shape, dt in ((q, (B, T, H, dk), q.dtype), (k, (B, T, H, dk), q.dtype), (v, (B, T, H, dv), q.dtype),
+                         (d_out, (B, T, H, dv), q.dtype), (q_head_logits, (B, T, H), torch.float32),
+                         (k_head_logits, (B, T, H), torch.float32), (log_decay, (B, T, H), torch.float32),
+                         (beta, (B, T, H), torch.float32), (initial_state, (B, H, dk, dv), torch.float32),
+                         (d_final_state, (B, H, dk, dv), torch.float32)):
+        assert t is None or (tuple(t.shape) == shape and t.dtype == dt and t.is_contiguous() and t.is_cuda)
+    dev = q.device
+    g = {
+        "dq": torch.empty_like(q),
+        "dk": torch.empty_like(k),
+        "dv": torch.empty_like(v),
+        "dq_head_logits": torch.empty_like(q_head_logits),
+        "dk_head_logits": None if k_head_logits is None else torch.empty_like(k_head_logits),
+        "dlog_decay": torch.empty_like(log_decay),
+        "dbeta": torch.empty_like(beta),
+        "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
+    }
+    params = SlaParams(GDN, BF16, B, T, H, dk, dv, 0, 0, 1)
+    need = sla_backward_gdn_workspace_bytes(params)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_backward_gdn(
+        params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta),
+        ptr(initial_state), ptr(d_out), ptr(d_final_state), ptr(g["dq"]), ptr(g["dk"]), ptr(g["dv"]),
+        ptr(g["dq_head_logits"]), ptr(g["dk_head_logits"]), ptr(g["dlog_decay"]), ptr(g["dbeta"]),
+        ptr(g["d_initial_state"]), ptr(workspace), workspace.numel() * workspace.element_size(),
+        torch.cuda.current_stream(dev).cuda_stream,
     )
     if rc != 0:
         raise SlaError(rc, sla_status_string(rc))

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsla.so")
-SOURCES = ["sla_api.hip", "sla_kernels.hip", "sla_decode.hip", "sla_backward.hip", "sla_prologue.hip"]
+SOURCES = ["sla_api.hip", "sla_kernels.hip", "sla_decode.hip", "sla_backward.hip", "sla_backward_gdn.hip", "sla_prologue.hip"]
 
 # Packed-fp32 VALU instructions are switched off for all device code (a hipcc flag; the host pass
 # prints a harmless "not a recognized feature" note).

@@ -1181,6 +1181,14 @@ int launch_dk(const BArgs& a, int dk, int dv, hipStream_t stream) {
 
 }  // namespace
 
+// Eq. 4 for both gates (G^K = 1 when kl is null), shared with the delta rule's backward.
+int launch_bwd_gates(const float* ql, const float* kl, float* gq, float* gk, size_t rows, int H, hipStream_t stream) {
+    if (rows == 0) return SLA_OK;
+    const unsigned per = kEwThreads / (unsigned)H, eg = (unsigned)((rows + per - 1) / per);
+    hipLaunchKernelGGL(sla_bwd_gates_kernel, dim3(eg), dim3(kEwThreads), 0, stream, ql, kl, gq, gk, rows, H);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
 // Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q and dG^K (dk/16 planes each); for GLA the sums of
 // q * dq over every 16-token block [rows/16 + B + 1][H,dk], the final-state term of dlog_decay [B,H,dk] and the
 // states kept every 512 tokens [rows/512 + 1][H,dk,dv] in bf16.

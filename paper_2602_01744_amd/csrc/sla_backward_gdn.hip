@@ -1,0 +1,684 @@
+// Backward pass of the gated delta rule with SLA's head gates (Softmax-GatedDeltaNet, Sec. 5.1), bf16 tensors.
+//
+// Forward step, per head, with a scalar decay a_t = exp(log_decay_t) and write strength beta_t:
+//     Sb = a_t S_{t-1}      res_t = G^K_t v_t - k_t Sb      u_t = beta_t res_t      S_t = Sb + k_t^T u_t
+//     out_t = G^Q_t q_t S_t
+// and, walking back with X_t the gradient with respect to S_t (including token t's own read-out term):
+//     X_t = dS + q_t^T dy_t (dy = G^Q dout)      du_t = k_t X_t       w_t = beta_t du_t
+//     dv_t = G^K_t w_t     dG^K_t = beta_t du_t . v_t     dbeta_t = du_t . res_t
+//     dk_t = X_t u_t - a_t w_t S_{t-1}^T          dq_t = dy_t S_t^T   dG^Q_t = dout_t . (q_t S_t)
+//     dS   = a_t (X_t - k_t^T w_t)
+//     dlog_decay_t = <d_final, S_T> + sum_{s >= t} (G^Q_s dG^Q_s - G^K_s dG^K_s)
+// (the last line: <X_t, S_t> changes by exactly these token-local scalars from one token to the next).
+//
+// Only two quantities depend on a state through the delta rule's own feedback: res_t (forward) and w_t (backward).
+// Once they are known every state recurrence is linear, so the pass is four sweeps that each carry one state tile in
+// registers, token by token, in plain fp32 vector arithmetic (the feedback makes tokens of a block depend on each
+// other; no matrix-core block form is used here):
+//   1. state sweep, forward in time, state tile [dk rows, 16 value columns] per wave: res_t, partial dG^Q,
+//      <d_final, S_T>;
+//   2. cotangent sweep, backward in time, same tile shape: w_t, dv, partial dG^K and dbeta, d_initial_state;
+//   3. key sweep, backward in time, tile [dv rows, 16 key columns] of X^T: the first part of dk, X_t u_t;
+//   4. query sweep, forward in time, tile [dv rows, 16 key columns] of S^T: dq, and dk completed.
+// A finishing kernel sums the partial planes, takes the gate gradients through the head softmax of Eq. 4 and writes
+// dbeta; a scan kernel forms dlog_decay.
+//
+// Tile layout of a wave (all four sweeps): lane = 16 * (column group) + (row group); a lane holds ROWS/16 rows by
+// 4 columns of the tile.  A product that contracts the rows is a per-lane partial sum followed by a rotate-and-add
+// over the 16 lanes of a DPP row, which leaves the total in every lane.  A workgroup is four such waves (64 columns)
+// plus four loader waves that stage the next 16 tokens (as fp32) into the other half of a double-buffered LDS area
+// while the compute waves work; one barrier per 16 tokens.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sla.h"
+
+namespace sla {
+
+int launch_bwd_gates(const float* ql, const float* kl, float* gq, float* gk, size_t rows, int H, hipStream_t stream);
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+
+constexpr int kChunk = 16;          // tokens staged per barrier
+constexpr int kWaves = 4;           // compute waves (16 columns each); as many loader waves
+constexpr int kLoaders = 64 * kWaves;
+constexpr int kThreads = 2 * kLoaders;
+constexpr int kSlice = 16 * kWaves; // columns per workgroup
+constexpr int kEw = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct GArgs {
+    const uint16_t* q;      // [B,T,H,dk]
+    const uint16_t* k;
+    const uint16_t* v;      // [B,T,H,dv]
+    const uint16_t* dout;
+    const float* ld;        // [B,T,H]
+    const float* beta;
+    const float* gq;        // gates [B,T,H]
+    const float* gk;
+    const float* s0;        // [B,H,dk,dv] or null
+    const float* dsf;
+    uint16_t* dq;
+    uint16_t* dk;
+    uint16_t* dv;
+    float* ds0;
+    float* res;             // [B,T,H,dv] fp32: G^K v - k Sb
+    float* w;               // [B,T,H,dv] fp32: beta * (k X)
+    float* dk1;             // [B,T,H,dk] fp32: X u
+    float* part_q;          // [dv/16][plane]: partial dout . (q S)
+    float* part_k;          // [dv/16][plane]: partial beta du . v
+    float* part_b;          // [dv/16][plane]: partial du . res
+    float* corr;            // [dv/16][B*H]: partial <d_final, S_T>
+    size_t plane;           // floats between partial planes (>= B*T*H)
+    int B, T, H;
+};
+
+__device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+__device__ __forceinline__ uint32_t bf16_bits(float x) {  // round to nearest even
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xf, 0xf, true));
+}
+// Sum over the 16 lanes of a DPP row (the row groups of a tile); every lane gets the total.
+__device__ __forceinline__ float row_all(float x) {
+    x += dpp_move<0x128>(x);  // row_ror:8
+    x += dpp_move<0x124>(x);  // row_ror:4
+    x += dpp_move<0x122>(x);  // row_ror:2
+    x += dpp_move<0x121>(x);  // row_ror:1
+    return x;
+}
+// Sum over the four DPP rows of the wave (the column groups); every lane gets the total.
+__device__ __forceinline__ float all_groups(float x) {
+    const uint32_t xi = __float_as_uint(x);
+    const u2 a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    const uint32_t yi = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    const u2 b = __builtin_amdgcn_permlane32_swap(yi, yi, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// ---- staging: NC columns of 16 tokens of one head, global -> registers -> LDS (fp32 [16][NC]) ----------------
+// Loads are unconditional (token clamped into the sequence) and zeroed when written; `lt` is the loader thread.
+template <int NC>
+struct RegsB {
+    static constexpr int items = kChunk * NC / 8, N = (items + kLoaders - 1) / kLoaders;
+    u4 x[N];
+    __device__ __forceinline__ void load(const uint16_t* base, size_t tokstride, int t0, int T, int lt) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = min(lt + kLoaders * n, items - 1), tok = it / (NC / 8), c8 = it % (NC / 8);
+            x[n] = *(const u4*)(base + (size_t)min(t0 + tok, T - 1) * tokstride + 8 * c8);
+        }
+    }
+    __device__ __forceinline__ void put(float* dst, int t0, int T, int lt) const {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = lt + kLoaders * n, tok = it / (NC / 8), c8 = it % (NC / 8);
+            if (it < items) {
+                const bool ok = t0 + tok < T;
+                const u4 y = ok ? x[n] : u4{0u, 0u, 0u, 0u};
+                float* d = dst + tok * NC + 8 * c8;
+                *(f4*)d = f4{bf_lo(y[0]), bf_hi(y[0]), bf_lo(y[1]), bf_hi(y[1])};
+                *(f4*)(d + 4) = f4{bf_lo(y[2]), bf_hi(y[2]), bf_lo(y[3]), bf_hi(y[3])};
+            }
+        }
+    }
+};
+template <int NC>
+struct RegsF {
+    static constexpr int items = kChunk * NC / 4, N = (items + kLoaders - 1) / kLoaders;
+    f4 x[N];
+    __device__ __forceinline__ void load(const float* base, size_t tokstride, int t0, int T, int lt) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = min(lt + kLoaders * n, items - 1), tok = it / (NC / 4), c4 = it % (NC / 4);
+            x[n] = *(const f4*)(base + (size_t)min(t0 + tok, T - 1) * tokstride + 4 * c4);
+        }
+    }
+    __device__ __forceinline__ void put(float* dst, int t0, int T, int lt) const {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = lt + kLoaders * n, tok = it / (NC / 4), c4 = it % (NC / 4);
+            if (it < items) *(f4*)(dst + tok * NC + 4 * c4) = t0 + tok < T ? x[n] : f4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+};
+// Per-token scalars {a, beta, G^Q, G^K}; a token past the end leaves every state unchanged (a = 1, the rest 0).
+struct RegsS {
+    float ld, be, gq, gk;
+    __device__ __forceinline__ void load(const GArgs& a, size_t tok0, int h, int t0, int T, int lt) {
+        const size_t i = (tok0 + (size_t)min(t0 + (lt & (kChunk - 1)), T - 1)) * a.H + h;
+        ld = a.ld[i]; be = a.beta[i]; gq = a.gq[i]; gk = a.gk[i];
+    }
+    __device__ __forceinline__ void put(float* dst, int t0, int T, int lt) const {
+        if (lt < kChunk) {
+            const bool ok = t0 + lt < T;
+            *(f4*)(dst + 4 * lt) = ok ? f4{__builtin_amdgcn_exp2f(ld * kLog2e), be, gq, gk} : f4{1.f, 0.f, 0.f, 0.f};
+        }
+    }
+};
+
+template <int RT>
+__device__ __forceinline__ void get_rows(float (&x)[RT], const float* src) {  // RT consecutive floats, RT % 4 == 0
+#pragma unroll
+    for (int i = 0; i < RT / 4; ++i) {
+        const f4 y = *(const f4*)(src + 4 * i);
+        x[4 * i] = y[0]; x[4 * i + 1] = y[1]; x[4 * i + 2] = y[2]; x[4 * i + 3] = y[3];
+    }
+}
+
+struct Where {  // what a workgroup and its lanes own
+    int tid, wave, lane, rg, cg, slice, bh, b, h, col;  // col: first of the lane's 4 columns inside the sliced dim
+    size_t tok0;
+};
+__device__ __forceinline__ Where where(const GArgs& a, int nslices) {
+    Where w;
+    w.tid = threadIdx.x;
+    w.wave = __builtin_amdgcn_readfirstlane(w.tid >> 6);
+    w.lane = w.tid & 63;
+    w.rg = w.lane & 15;
+    w.cg = w.lane >> 4;
+    w.slice = blockIdx.x % nslices;
+    w.bh = blockIdx.x / nslices;
+    w.b = w.bh / a.H;
+    w.h = w.bh % a.H;
+    w.col = w.slice * kSlice + (w.wave & (kWaves - 1)) * 16 + w.cg * 4;
+    w.tok0 = (size_t)w.b * a.T;
+    return w;
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Sweep 1: forward in time, S[dk rows, value columns] -> res, partial dG^Q, <d_final, S_T>.
+// ------------------------------------------------------------------------------------------------------------
+template <int DK, int DV>
+__global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) {
+    constexpr int RT = DK / 16;
+    constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
+                  oSC = oDO + kChunk * kSlice, kBuf = oSC + 4 * kChunk;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* lds = (float*)smem;
+    const Where me = where(a, DV / kSlice);
+    const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
+    const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
+    if (me.wave >= kWaves) {
+        const int lt = me.tid - kLoaders;
+        const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK;
+        const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK;
+        const uint16_t* vb = a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        for (int c = 0; c <= nch; ++c) {
+            if (c < nch) {
+                const int t0 = c * kChunk;
+                float* buf = lds + (c & 1) * kBuf;
+                RegsB<DK> rk, rq;
+                RegsB<kSlice> rv, rd;
+                RegsS rs;
+                rk.load(kb, sk, t0, T, lt); rq.load(qb, sk, t0, T, lt);
+                rv.load(vb, sv, t0, T, lt); rd.load(db, sv, t0, T, lt);
+                rs.load(a, me.tok0, me.h, t0, T, lt);
+                rk.put(buf + oK, t0, T, lt); rq.put(buf + oQ, t0, T, lt);
+                rv.put(buf + oV, t0, T, lt); rd.put(buf + oDO, t0, T, lt);
+                rs.put(buf + oSC, t0, T, lt);
+            }
+            __syncthreads();
+        }
+        return;
+    }
+    float M[RT][4];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        const f4 x = a.s0 ? *(const f4*)(a.s0 + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col)
+                          : f4{0.f, 0.f, 0.f, 0.f};
+        M[r][0] = x[0]; M[r][1] = x[1]; M[r][2] = x[2]; M[r][3] = x[3];
+    }
+    __syncthreads();  // chunk 0 staged
+    for (int c = 0; c < nch; ++c) {
+        const float* buf = lds + (c & 1) * kBuf;
+#pragma unroll 2
+        for (int i = 0; i < kChunk; ++i) {
+            const f4 sc = *(const f4*)(buf + oSC + 4 * i);
+            const float al = sc[0], be = sc[1], gk = sc[3];
+            float kf[RT], qf[RT];
+            get_rows<RT>(kf, buf + oK + i * DK + me.rg * RT);
+            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * RT);
+            const f4 vv = *(const f4*)(buf + oV + i * kSlice + me.wave * 16 + me.cg * 4);
+            const f4 dd = *(const f4*)(buf + oDO + i * kSlice + me.wave * 16 + me.cg * 4);
+            float p[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) p[j] += kf[r] * M[r][j];
+            f4 res;
+            float u[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                res[j] = gk * vv[j] - al * row_all(p[j]);
+                u[j] = be * res[j];
+            }
+            float y[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    M[r][j] = al * M[r][j] + kf[r] * u[j];
+                    y[j] += qf[r] * M[r][j];
+                }
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s += dd[j] * row_all(y[j]);
+            s = all_groups(s);
+            const int t = c * kChunk + i;
+            if (t < T) {
+                const size_t row = (me.tok0 + t) * H + me.h;
+                if (me.lane == 0) a.part_q[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = s;
+                if (me.rg == 0) *(f4*)(a.res + row * DV + me.col) = res;
+            }
+        }
+        __syncthreads();
+    }
+    if (a.dsf) {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const f4 x = *(const f4*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col);
+            s += x[0] * M[r][0] + x[1] * M[r][1] + x[2] * M[r][2] + x[3] * M[r][3];
+        }
+        s = all_groups(row_all(s));
+        if (me.lane == 0) a.corr[(size_t)(me.slice * kWaves + me.wave) * a.B * H + me.bh] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Sweep 2: backward in time, X[dk rows, value columns] -> w, dv, partial dG^K and dbeta, d_initial_state.
+// ------------------------------------------------------------------------------------------------------------
+template <int DK, int DV>
+__global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs a) {
+    constexpr int RT = DK / 16;
+    constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
+                  oR = oDO + kChunk * kSlice, oSC = oR + kChunk * kSlice, kBuf = oSC + 4 * kChunk;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* lds = (float*)smem;
+    const Where me = where(a, DV / kSlice);
+    const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
+    const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
+    if (me.wave >= kWaves) {  // step c of the sweep covers tokens (nch - 1 - c) * 16 ...
+        const int lt = me.tid - kLoaders;
+        const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK;
+        const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK;
+        const uint16_t* vb = a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const float* rb = a.res + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        for (int c = 0; c <= nch; ++c) {
+            if (c < nch) {
+                const int t0 = (nch - 1 - c) * kChunk;
+                float* buf = lds + (c & 1) * kBuf;
+                RegsB<DK> rk, rq;
+                RegsB<kSlice> rv, rd;
+                RegsF<kSlice> rr;
+                RegsS rs;
+                rk.load(kb, sk, t0, T, lt); rq.load(qb, sk, t0, T, lt);
+                rv.load(vb, sv, t0, T, lt); rd.load(db, sv, t0, T, lt);
+                rr.load(rb, sv, t0, T, lt);
+                rs.load(a, me.tok0, me.h, t0, T, lt);
+                rk.put(buf + oK, t0, T, lt); rq.put(buf + oQ, t0, T, lt);
+                rv.put(buf + oV, t0, T, lt); rd.put(buf + oDO, t0, T, lt);
+                rr.put(buf + oR, t0, T, lt);
+                rs.put(buf + oSC, t0, T, lt);
+            }
+            __syncthreads();
+        }
+        return;
+    }
+    float X[RT][4];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        const f4 x = a.dsf ? *(const f4*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col)
+                           : f4{0.f, 0.f, 0.f, 0.f};
+        X[r][0] = x[0]; X[r][1] = x[1]; X[r][2] = x[2]; X[r][3] = x[3];
+    }
+    __syncthreads();
+    for (int c = 0; c < nch; ++c) {
+        const float* buf = lds + (c & 1) * kBuf;
+#pragma unroll 2
+        for (int i = kChunk - 1; i >= 0; --i) {
+            const f4 sc = *(const f4*)(buf + oSC + 4 * i);
+            const float al = sc[0], be = sc[1], gq = sc[2], gk = sc[3];
+            float kf[RT], qf[RT];
+            get_rows<RT>(kf, buf + oK + i * DK + me.rg * RT);
+            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * RT);
+            const int lc = i * kSlice + me.wave * 16 + me.cg * 4;
+            const f4 vv = *(const f4*)(buf + oV + lc), dd = *(const f4*)(buf + oDO + lc), rr = *(const f4*)(buf + oR + lc);
+            float du[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    X[r][j] += qf[r] * (gq * dd[j]);
+                    du[j] += kf[r] * X[r][j];
+                }
+            f4 w;
+            float pk = 0.f, pb = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                du[j] = row_all(du[j]);
+                w[j] = be * du[j];
+                pk += du[j] * vv[j];
+                pb += du[j] * rr[j];
+            }
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) X[r][j] = al * (X[r][j] - kf[r] * w[j]);
+            pk = all_groups(pk) * be;
+            pb = all_groups(pb);
+            const int t = (nch - 1 - c) * kChunk + i;
+            if (t < T) {
+                const size_t row = (me.tok0 + t) * H + me.h;
+                if (me.lane == 0) {
+                    a.part_k[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = pk;
+                    a.part_b[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = pb;
+                }
+                if (me.rg == 0) {
+                    *(f4*)(a.w + row * DV + me.col) = w;
+                    *(u2*)(a.dv + row * DV + me.col) = u2{pack2(gk * w[0], gk * w[1]), pack2(gk * w[2], gk * w[3])};
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (a.ds0) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            *(f4*)(a.ds0 + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col) = f4{X[r][0], X[r][1], X[r][2], X[r][3]};
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Sweeps 3 and 4 carry the transposed tiles: rows are the dv value columns, a workgroup owns 64 key columns.
+//   FWD = false (sweep 3, backward in time):  X^T += dy^T q;  dk1 = u X^T;   X^T = a (X^T - w^T k)
+//   FWD = true  (sweep 4, forward in time):   pk = w S^T;     S^T = a S^T + u^T k;   dq = G^Q dout S^T;
+//                                             dk = dk1 - a pk
+// ------------------------------------------------------------------------------------------------------------
+template <int DK, int DV, bool FWD>
+__global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
+    constexpr int RT = DV / 16;
+    constexpr int oDO = 0, oR = oDO + kChunk * DV, oW = oR + kChunk * DV, oK = oW + kChunk * DV,
+                  oX = oK + kChunk * kSlice,  // sweep 3: q slice; sweep 4: dk1 slice
+        oSC = oX + kChunk * kSlice, kBuf = oSC + 4 * kChunk;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* lds = (float*)smem;
+    const Where me = where(a, DK / kSlice);
+    const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
+    const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
+    if (me.wave >= kWaves) {
+        const int lt = me.tid - kLoaders;
+        const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV;
+        const float* rb = a.res + (me.tok0 * H + me.h) * DV;
+        const float* wb = a.w + (me.tok0 * H + me.h) * DV;
+        const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
+        const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
+        const float* d1 = a.dk1 + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
+        for (int c = 0; c <= nch; ++c) {
+            if (c < nch) {
+                const int t0 = (FWD ? c : nch - 1 - c) * kChunk;
+                float* buf = lds + (c & 1) * kBuf;
+                RegsB<DV> rd;
+                RegsF<DV> rr, rw;
+                RegsB<kSlice> rk, rq;
+                RegsF<kSlice> r1;
+                RegsS rs;
+                rd.load(db, sv, t0, T, lt); rr.load(rb, sv, t0, T, lt); rw.load(wb, sv, t0, T, lt);
+                rk.load(kb, sk, t0, T, lt);
+                if constexpr (FWD) r1.load(d1, sk, t0, T, lt);
+                else rq.load(qb, sk, t0, T, lt);
+                rs.load(a, me.tok0, me.h, t0, T, lt);
+                rd.put(buf + oDO, t0, T, lt); rr.put(buf + oR, t0, T, lt); rw.put(buf + oW, t0, T, lt);
+                rk.put(buf + oK, t0, T, lt);
+                if constexpr (FWD) r1.put(buf + oX, t0, T, lt);
+                else rq.put(buf + oX, t0, T, lt);
+                rs.put(buf + oSC, t0, T, lt);
+            }
+            __syncthreads();
+        }
+        return;
+    }
+    // tile element [r][j]: value column n = rg * RT + r, key column d = col + j
+    float M[RT][4];
+    const float* init = FWD ? a.s0 : a.dsf;
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            M[r][j] = init ? init[((size_t)me.bh * DK + me.col + j) * DV + me.rg * RT + r] : 0.f;
+    __syncthreads();
+    for (int c = 0; c < nch; ++c) {
+        const float* buf = lds + (c & 1) * kBuf;
+#pragma unroll 2
+        for (int ii = 0; ii < kChunk; ++ii) {
+            const int i = FWD ? ii : kChunk - 1 - ii;
+            const f4 sc = *(const f4*)(buf + oSC + 4 * i);
+            const float al = sc[0], be = sc[1], gq = sc[2];
+            float dd[RT], rr[RT], ww[RT];
+            get_rows<RT>(dd, buf + oDO + i * DV + me.rg * RT);
+            get_rows<RT>(rr, buf + oR + i * DV + me.rg * RT);
+            get_rows<RT>(ww, buf + oW + i * DV + me.rg * RT);
+            const int lc = i * kSlice + me.wave * 16 + me.cg * 4;
+            const f4 kf = *(const f4*)(buf + oK + lc), xf = *(const f4*)(buf + oX + lc);
+            const int t = (FWD ? c : nch - 1 - c) * kChunk + i;
+            const size_t row = (me.tok0 + min(t, T - 1)) * H + me.h;
+            if constexpr (FWD) {
+                float pk[4] = {0.f, 0.f, 0.f, 0.f}, y[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        pk[j] += ww[r] * M[r][j];
+                        M[r][j] = al * M[r][j] + (be * rr[r]) * kf[j];
+                        y[j] += dd[r] * M[r][j];
+                    }
+                float dq[4], dk[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    dq[j] = gq * row_all(y[j]);
+                    dk[j] = xf[j] - al * row_all(pk[j]);
+                }
+                if (t < T && me.rg == 0) {
+                    *(u2*)(a.dq + row * DK + me.col) = u2{pack2(dq[0], dq[1]), pack2(dq[2], dq[3])};
+                    *(u2*)(a.dk + row * DK + me.col) = u2{pack2(dk[0], dk[1]), pack2(dk[2], dk[3])};
+                }
+            } else {
+                float d1[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        M[r][j] += (gq * dd[r]) * xf[j];
+                        d1[j] += (be * rr[r]) * M[r][j];
+                        M[r][j] = al * (M[r][j] - ww[r] * kf[j]);
+                    }
+                f4 o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] = row_all(d1[j]);
+                if (t < T && me.rg == 0) *(f4*)(a.dk1 + row * DK + me.col) = o;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Finishing: sums of the partial planes; gate gradients through the head softmax (Eq. 4); dbeta; the per-token
+// scalar G^Q dG^Q - G^K dG^K whose suffix sums are dlog_decay.
+// ------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int planes, float* dql, float* dkl,
+                                                             float* dbeta, float* e) {
+    __shared__ float sx[kEw];
+    const int H = a.H, per = kEw / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
+    const size_t rows = (size_t)a.B * a.T, row = (size_t)blockIdx.x * per + lr;
+    const bool ok = lr < per && row < rows;
+    const size_t i = ok ? row * H + h : 0;
+    float dgq = 0.f, dgk = 0.f, db = 0.f, gq = 0.f, gk = 0.f;
+    if (ok) {
+        for (int p = 0; p < planes; ++p) {
+            dgq += a.part_q[(size_t)p * a.plane + i];
+            dgk += a.part_k[(size_t)p * a.plane + i];
+            db += a.part_b[(size_t)p * a.plane + i];
+        }
+        gq = a.gq[i];
+        gk = a.gk[i];
+        dbeta[i] = db;
+        e[i] = gq * dgq - gk * dgk;
+    }
+    sx[tid] = gq * dgq;
+    __syncthreads();
+    if (ok) {
+        float dot = 0.f;
+        for (int j = 0; j < H; ++j) dot += sx[lr * H + j];
+        dql[i] = gq * (dgq - dot);
+    }
+    __syncthreads();
+    if (!dkl) return;
+    sx[tid] = gk * dgk;
+    __syncthreads();
+    if (ok) {
+        float dot = 0.f;
+        for (int j = 0; j < H; ++j) dot += sx[lr * H + j];
+        dkl[i] = gk * (dgk - dot);
+    }
+}
+
+// dlog_decay[b,t,h] = <d_final, S_T>[b,h] + sum_{s >= t} e[b,s,h]; one workgroup per (b, h).
+__global__ __launch_bounds__(kEw) void gdn_bwd_decay_scan_kernel(const float* e, const float* corr, int planes, int B,
+                                                                 int T, int H, float* dld) {
+    __shared__ float sx[kEw];
+    const int bh = blockIdx.x, b = bh / H, h = bh % H, tid = threadIdx.x;
+    const int per = (T + kEw - 1) / kEw, lo = min(tid * per, T), hi = min(lo + per, T);
+    const float* src = e + (size_t)b * T * H + h;
+    float own = 0.f;
+    for (int t = lo; t < hi; ++t) own += src[(size_t)t * H];
+    sx[tid] = own;
+    __syncthreads();
+    float run = 0.f;
+    if (corr)
+        for (int p = 0; p < planes; ++p) run += corr[(size_t)p * B * H + bh];
+    for (int j = tid + 1; j < kEw; ++j) run += sx[j];
+    float* dst = dld + (size_t)b * T * H + h;
+    for (int t = hi - 1; t >= lo; --t) {
+        run += src[(size_t)t * H];
+        dst[(size_t)t * H] = run;
+    }
+}
+
+__global__ __launch_bounds__(kEw) void gdn_bwd_pass_state_kernel(const f4* src, f4* dst, size_t count) {
+    const size_t i = (size_t)blockIdx.x * kEw + threadIdx.x;
+    if (i < count) dst[i] = src ? src[i] : f4{0.f, 0.f, 0.f, 0.f};
+}
+
+size_t round4(size_t n) { return (n + 3) & ~(size_t)3; }
+
+template <typename K>
+bool allow_lds(K kernel, int lds) {
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess)
+        return true;
+    (void)hipGetLastError();
+    return false;
+}
+
+template <int DK, int DV>
+int launch_sweeps(const GArgs& a, hipStream_t stream) {
+    constexpr int lds1 = 2 * 4 * (2 * kChunk * DK + 2 * kChunk * kSlice + 4 * kChunk);
+    constexpr int lds2 = 2 * 4 * (2 * kChunk * DK + 3 * kChunk * kSlice + 4 * kChunk);
+    constexpr int lds3 = 2 * 4 * (3 * kChunk * DV + 2 * kChunk * kSlice + 4 * kChunk);
+    static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024, "fits the LDS of a compute unit");
+    static bool configured = false;  // once per instantiation; not a stream operation
+    if (!configured) {
+        if (!allow_lds(gdn_bwd_state_kernel<DK, DV>, lds1) || !allow_lds(gdn_bwd_cotangent_kernel<DK, DV>, lds2) ||
+            !allow_lds(gdn_bwd_key_kernel<DK, DV, false>, lds3) || !allow_lds(gdn_bwd_key_kernel<DK, DV, true>, lds3))
+            return SLA_ERR_HIP;
+        configured = true;
+    }
+    const unsigned bh = (unsigned)(a.B * a.H);
+    const dim3 block(kThreads);
+    hipLaunchKernelGGL((gdn_bwd_state_kernel<DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds1, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_cotangent_kernel<DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds2, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_key_kernel<DK, DV, false>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_key_kernel<DK, DV, true>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+template <int DK>
+int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
+    switch (dv) {
+        case 64: return launch_sweeps<DK, 64>(a, stream);
+        case 128: return launch_sweeps<DK, 128>(a, stream);
+        case 256: return launch_sweeps<DK, 256>(a, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+// Workspace, in floats: gates 2 [B,T,H]; three sets of dv/16 partial planes; the decay scalar [B,T,H];
+// dv/16 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
+size_t backward_gdn_workspace_floats(const sla_params& p) {
+    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H), planes = (size_t)p.dv / 16;
+    return n * (3 + 3 * planes) + round4(planes * p.B * p.H) + 2 * round4(rows * p.H * p.dv) +
+           round4(rows * p.H * p.dk);
+}
+
+int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
+                        const float* kl, const float* ld, const float* beta, const float* s0, const void* dout,
+                        const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
+                        float* dbeta, float* ds0, float* ws, hipStream_t stream) {
+    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H);
+    const int planes = p.dv / 16;
+    if (rows == 0) {
+        if (ds0 && p.B > 0) {  // no tokens: the cotangent of the final state is that of the initial state
+            const size_t count = (size_t)p.B * p.H * p.dk * p.dv / 4;
+            hipLaunchKernelGGL(gdn_bwd_pass_state_kernel, dim3((unsigned)((count + kEw - 1) / kEw)), dim3(kEw), 0,
+                               stream, (const f4*)dsf, (f4*)ds0, count);
+            if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
+        }
+        return SLA_OK;
+    }
+    GArgs a;
+    a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
+    a.ld = ld; a.beta = beta; a.s0 = s0; a.dsf = dsf;
+    a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.ds0 = ds0;
+    float* w = ws;
+    float* gq = w; w += n;
+    float* gk = w; w += n;
+    float* e = w; w += n;
+    a.gq = gq; a.gk = gk;
+    a.part_q = w; w += n * planes;
+    a.part_k = w; w += n * planes;
+    a.part_b = w; w += n * planes;
+    a.corr = w; w += round4((size_t)planes * p.B * p.H);
+    a.res = w; w += round4(rows * p.H * p.dv);
+    a.w = w; w += round4(rows * p.H * p.dv);
+    a.dk1 = w;
+    a.plane = n;
+    a.B = p.B; a.T = p.T; a.H = p.H;
+
+    int rc = launch_bwd_gates(ql, kl, gq, gk, rows, p.H, stream);
+    if (rc != SLA_OK) return rc;
+    rc = p.dk == 64 ? launch_dv<64>(a, p.dv, stream) : launch_dv<128>(a, p.dv, stream);
+    if (rc != SLA_OK) return rc;
+    const unsigned per = kEw / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
+    hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, planes, dql, kl ? dkl : nullptr,
+                       dbeta, e);
+    hipLaunchKernelGGL(gdn_bwd_decay_scan_kernel, dim3((unsigned)(p.B * p.H)), dim3(kEw), 0, stream, (const float*)e,
+                       dsf ? (const float*)a.corr : nullptr, planes, p.B, p.T, p.H, dld);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+}  // namespace sla

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -254,3 +254,36 @@ def test_short_conv_rejects_bad_calls(lib):
     assert call(x=0) == -1 and call(w=0) == -1 and call(y=0) == -1
     assert call(y=A + 4) == -4
     assert call(B=0) == 0 and call(T=0) == 0
+
+
+def test_backward_gdn_rejects_bad_calls(lib):
+    ok = _ok_params(variant=sla.GDN)
+    big = 1 << 40
+
+    def call(p, q=A, ld=A, beta=A, kl=A, dkl=A, dld=A, dbeta=A, ws=A, ws_bytes=big):
+        return sla.sla_backward_gdn(p, q, A, A, A, kl, ld, beta, 0, A, 0, A, A, A, A, dkl, dld, dbeta, 0, ws,
+                                    ws_bytes, 0)
+
+    assert call(None) == -1
+    assert call(_ok_params(variant=sla.GLA)) == -3 and call(_ok_params(variant=sla.RETNET)) == -3
+    assert call(_ok_params(variant=sla.GDN, dtype=sla.F32)) == -3
+    assert call(_ok_params(variant=sla.GDN, flags=1)) == -3
+    assert call(ok, q=0) == -1 and call(ok, ld=0) == -1 and call(ok, beta=0) == -1
+    assert call(ok, dld=0) == -1 and call(ok, dbeta=0) == -1
+    assert call(ok, kl=0) == -1 and call(ok, dkl=0) == -1 and call(ok, kl=0, dkl=0) != -1
+    assert call(ok, beta=A + 4) == -4
+    assert call(ok, ws=0) == -6 and call(ok, ws_bytes=16) == -6
+    assert call(_ok_params(variant=sla.GDN, B=0)) == 0
+    assert call(_ok_params(variant=sla.GDN, T=0), ws=0) == 0    # no tokens, no initial-state gradient asked for
+
+
+def test_backward_gdn_workspace_size(lib):
+    B, T, H, dk, dv = 2, 100, 4, 128, 64
+    n = B * T * H
+    got = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, B=B, T=T, H=H, dk=dk, dv=dv))
+    planes = dv // 16
+    # gates and the decay scalar (3 planes), three sets of dv/16 partial planes, <d_final, S_T> partials,
+    # two fp32 tensors like v and one like k
+    assert got == 4 * (n * (3 + 3 * planes) + planes * B * H + 2 * n * dv + n * dk)
+    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
+    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32)) == 0

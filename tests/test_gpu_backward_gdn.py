@@ -1,0 +1,122 @@
+"""GPU parity of the gated delta rule's backward pass (sla_backward_gdn through the C ABI) against the gradient
+oracle on the same seeded inputs and cotangents.  Tolerance: the bf16 bar of the other parity tests,
+max|x - x*| / max|x*| <= 2e-2 per gradient tensor; the sweeps compute in fp32 from bf16 inputs, so the measured
+errors are those of rounding dq, dk, dv to bf16 once (about 2e-3) and fp32 summation for the fp32 outputs."""
+import numpy as np
+import pytest
+
+import sla_inputs as si
+from gpu_util import GDN, TOL, rel_err, to_device
+from oracle import sla_backward as ob
+
+pytestmark = pytest.mark.gpu
+
+NAMES = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_head_logits": "dq_logits", "dk_head_logits": "dk_logits",
+         "dlog_decay": "dlog_decay", "dbeta": "dbeta", "d_initial_state": "dinitial_state"}
+# fp32 outputs of fp32 arithmetic: far below the bf16 bar
+TIGHT = {"dq_head_logits": 1e-4, "dk_head_logits": 1e-4, "dlog_decay": 1e-4, "dbeta": 1e-4, "d_initial_state": 1e-4}
+
+
+def run_backward_gdn(d, cot, s0=None, want_ds0=False):
+    import torch
+    import paper_2602_01744_amd as sla
+
+    g, _ = to_device(d, "bf16", GDN)
+    dev = torch.device("cuda:0")
+    up = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
+    res = sla.backward_gdn(g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], g["beta"],
+                           up(cot["d_out"], torch.bfloat16), up(s0, torch.float32),
+                           up(cot["d_final_state"], torch.float32), want_d_initial_state=want_ds0)
+    torch.cuda.synchronize()
+    return {n: None if t is None else t.to(torch.float32).cpu().numpy().astype(np.float64) for n, t in res.items()}
+
+
+def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=None):
+    got = run_backward_gdn(d, cot, s0, want_ds0)
+    rows = slice(None) if batch_rows is None else batch_rows
+    sub = lambda a: None if a is None else a[rows]
+    ref = ob.backward(GDN, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
+                      sub(d["log_decay"]), sub(cot["d_out"]), sub(s0), sub(cot["d_final_state"]), beta=sub(d["beta"]))
+    errs = {}
+    for n, rn in NAMES.items():
+        x, r = got[n], ref[rn]
+        if n == "d_initial_state" and not want_ds0:
+            continue
+        if r is None:
+            assert x is None, n
+            continue
+        x = x[rows]
+        assert np.all(np.isfinite(x)), f"{label}: non-finite {n}"
+        errs[n] = rel_err(x, r)
+    print(f"[gdn backward parity] {label} " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
+    for n, e in errs.items():
+        assert e <= TOL["bf16"], f"{label}: {n} error {e:.3e} > {TOL['bf16']}"
+        if n in TIGHT:
+            assert e <= TIGHT[n], f"{label}: {n} error {e:.3e} > {TIGHT[n]} (fp32 output)"
+    return got, ref
+
+
+def make(B, T, H, dk, dv, seed, states=False, k_logits=True):
+    d = si.custom(GDN, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=seed)
+    if not k_logits:
+        d["k_logits"] = None
+    cot = si.cotangents(B, T, H, dk, dv, seed=seed + 1, final_state=states)
+    s0 = si.initial_state(B, H, dk, dv, seed=seed + 2) if states else None
+    return d, cot, s0
+
+
+def test_small_block_aligned():
+    d, cot, s0 = make(2, 64, 4, 64, 64, seed=1100)
+    check_backward_gdn(d, cot, label="B2 T64 H4 d64")
+
+
+@pytest.mark.parametrize("states", [False, True])
+def test_ragged_multi_chunk(states):
+    d, cot, s0 = make(2, 203, 3, 128, 128, seed=1110, states=states)
+    check_backward_gdn(d, cot, s0=s0, want_ds0=states, label=f"B2 T203 H3 d128 states={states}")
+
+
+@pytest.mark.parametrize("dk,dv", [(64, 64), (64, 128), (128, 64), (128, 256), (64, 256)])
+def test_head_widths(dk, dv):
+    d, cot, s0 = make(1, 77, 2, dk, dv, seed=1120 + dk + dv, states=True)
+    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"dk={dk} dv={dv}")
+
+
+@pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 33])
+def test_short_sequences(T):
+    d, cot, s0 = make(2, T, 2, 64, 64, seed=1130 + T, states=True)
+    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"T={T}")
+
+
+@pytest.mark.parametrize("H", [1, 7, 64])
+def test_head_counts(H):
+    d, cot, s0 = make(1, 40, H, 64, 64, seed=1140 + H)
+    check_backward_gdn(d, cot, label=f"H={H}")
+
+
+def test_read_gate_only():
+    d, cot, s0 = make(2, 50, 4, 64, 128, seed=1150, k_logits=False)
+    got, _ = check_backward_gdn(d, cot, label="no k logits")
+    assert got["dk_head_logits"] is None
+
+
+def test_beta_zero_tokens_write_nothing():
+    # beta = 0: the token neither erases nor writes, so dk and dv vanish there (exactly) while dbeta does not
+    d, cot, s0 = make(1, 48, 2, 64, 64, seed=1160)
+    d["beta"][:, ::3] = 0.0
+    got, ref = check_backward_gdn(d, cot, label="beta = 0 on every third token")
+    assert np.all(got["dv"][:, ::3] == 0.0)
+    assert np.max(np.abs(ref["dbeta"][:, ::3])) > 0.0
+
+
+def test_long_sequence():
+    d, cot, s0 = make(1, 4096 + 24, 2, 128, 128, seed=1170, states=True)
+    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label="T=4120")
+
+
+def test_full_size():
+    """The bench workload (gdn: B=8, T=4096, H=16, d=128), as bench.py launches it; the oracle runs on one row."""
+    w = si.workload("gdn")
+    d = si.generate(w)
+    cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
+    check_backward_gdn(d, cot, label="gdn", batch_rows=slice(0, 1))
