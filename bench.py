@@ -20,6 +20,7 @@ sys.path.insert(0, ROOT)
 
 METRIC = "tokens/sec SLA-GLA chunked fwd (B=8,T=2048,H=16,d=128 bf16); % MFMA peak"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flops x 2.4 GHz)
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for a workload, calibrated
 # against a plain copy of known size in the same run (figures and commands: profiles/*.md).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
@@ -79,6 +80,8 @@ def backward_bytes(w) -> int:
     per = (2 * w.dk + 2 * w.dv) * es + 8 + (2 * w.dk + w.dv) * es + 8
     if w.variant == 1:
         per += 2 * w.dk * es
+    if w.variant == 2:  # scalar decay and beta read, their gradients written (fp32)
+        per += 16
     return w.B * w.T * w.H * per
 
 
@@ -88,8 +91,9 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from gpu_util import rel_err, to_device
 
-    if w.variant == 2 or w.dtype != "bf16":
-        print("bench.py: --backward covers the bf16 RetNet and GLA workloads", file=sys.stderr)
+    if w.dtype != "bf16" or (w.variant == 2 and args.head_major):
+        print("bench.py: --backward covers the bf16 workloads ([B,T,H,d] layout only for the delta rule)",
+              file=sys.stderr)
         return 2
     d = si.generate(w)
     cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
@@ -102,20 +106,26 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             g[n] = g[n].permute(0, 2, 1, 3).contiguous()
         dout = dout.permute(0, 2, 1, 3).contiguous()
     params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, sla.FLAG_HEAD_MAJOR if hm else 0, 1)
-    need = sla.sla_backward_workspace_bytes(params)
+    gdn = w.variant == 2
+    need = sla.sla_backward_gdn_workspace_bytes(params) if gdn else sla.sla_backward_workspace_bytes(params)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     gr = {
         "dq": torch.empty_like(g["q"]), "dk": torch.empty_like(g["k"]), "dv": torch.empty_like(g["v"]),
         "dq_logits": torch.empty_like(g["q_logits"]), "dk_logits": torch.empty_like(g["k_logits"]),
-        "dlog_decay": torch.empty_like(g["log_decay"]) if w.variant == 1 else None,
+        "dlog_decay": torch.empty_like(g["log_decay"]) if w.variant != 0 else None,
+        "dbeta": torch.empty_like(g["beta"]) if gdn else None,
     }
     ptr = lambda t: None if t is None else t.data_ptr()
+    raw_gdn = (ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(g["q_logits"]), ptr(g["k_logits"]), ptr(g["log_decay"]),
+               ptr(g["beta"]), None, ptr(dout), None, ptr(gr["dq"]), ptr(gr["dk"]), ptr(gr["dv"]), ptr(gr["dq_logits"]),
+               ptr(gr["dk_logits"]), ptr(gr["dlog_decay"]), ptr(gr["dbeta"]), None, ptr(ws), need,
+               torch.cuda.current_stream(dev).cuda_stream)
     raw = (ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(g["q_logits"]), ptr(g["k_logits"]), ptr(g["log_decay"]), None,
            ptr(dout), None, ptr(gr["dq"]), ptr(gr["dk"]), ptr(gr["dv"]), ptr(gr["dq_logits"]), ptr(gr["dk_logits"]),
            ptr(gr["dlog_decay"]), None, ptr(ws), need, torch.cuda.current_stream(dev).cuda_stream)
 
     def step():
-        rc = sla.sla_backward(params, *raw)
+        rc = sla.sla_backward_gdn(params, *raw_gdn) if gdn else sla.sla_backward(params, *raw)
         if rc != 0:
             raise sla.SlaError(rc, sla.sla_status_string(rc))
 
@@ -135,6 +145,11 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     ms_per_step = wall * 1e3 / args.steps
     abytes = backward_bytes(w)
     achieved = abytes / (call_ms * 1e-3) / 1e9
+    # The delta rule's backward runs token by token in fp32 vector arithmetic: its bound is the vector ALU.
+    # Arithmetic of the recurrence and its reverse walk, per token and head, in units of dk * dv: forward step
+    # a S (1), k Sb (2), S + k^T u (2), q S (2); reverse step dS + q^T dy (2), k dS (2), dS u (2), w Sb^T (2),
+    # dSb - k^T w (2), a dSb (1), dy S^T (2): 20 dk dv flops.
+    gdn_flops = 20 * w.dk * w.dv * w.B * w.T * w.H
     result = {
         "metric": f"tokens/sec SLA-{si.VARIANT_NAMES[w.variant].upper()} chunked bwd",
         "value": w.tokens() / (ms_per_step * 1e-3),
@@ -153,10 +168,26 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "workload": f"{w.name}: backward of SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} "
                         f"dk={w.dk} dv={w.dv} bf16 in/out, dual head-softmax gates, no state cotangents"
                         + (", wide tensors laid out [B,H,T,d]" if hm else ""),
-            "kernel": "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
+            "kernel": ("sla_backward_gdn: sla_bwd_gates_kernel, gdn_bwd_state_kernel, gdn_bwd_cotangent_kernel, "
+                       "gdn_bwd_key_kernel x2, gdn_bwd_finish_kernel, gdn_bwd_decay_scan_kernel") if gdn else
+                      "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
                       "sla_bwd_logits_kernel x2",
         },
         "roofline": {
+            "bound": "alu",
+            "achieved": gdn_flops / (call_ms * 1e-3) / 1e12,
+            "peak": FP32_VECTOR_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": gdn_flops / (call_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
+            "traffic": None,
+            "kernel_us": call_ms * 1e3,
+            "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
+            "algorithmic_flops": gdn_flops,
+            "algorithmic_bytes": abytes,
+            "hbm_frac": achieved / HBM_PEAK_GBS,
+            "note": "whole call (seven launches); achieved = 20 dk dv flops per token and head / call time, against "
+                    "the published fp32 vector peak (which counts packed issue; this build issues unpacked fp32)",
+        } if gdn else {
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
@@ -172,11 +203,12 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     if not args.no_cpu_baseline or not args.no_parity:
         from oracle import sla_backward as ob
 
-        rows, Ts = min(w.B, 2), w.T  # a bounded sample: two batch rows (about 25 s for the headline shape)
+        rows, Ts = min(w.B, 1 if gdn else 2), w.T  # a bounded sample: about 25 s for the headline shape
+        bt = lambda n: d["beta"][:n] if gdn else None
         t0 = time.perf_counter()
-        ob.backward(w.variant, d["q"][:rows, :Ts], d["k"][:rows, :Ts], d["v"][:rows, :Ts], d["q_logits"][:rows, :Ts],
+        timed = ob.backward(w.variant, d["q"][:rows, :Ts], d["k"][:rows, :Ts], d["v"][:rows, :Ts], d["q_logits"][:rows, :Ts],
                     d["k_logits"][:rows, :Ts], d["log_decay"] if w.variant == 0 else d["log_decay"][:rows, :Ts],
-                    cot["d_out"][:rows, :Ts])
+                    cot["d_out"][:rows, :Ts], beta=bt(rows))
         cpu_s = time.perf_counter() - t0
         if not args.no_cpu_baseline:
             result["cpu_baseline"] = {
@@ -187,8 +219,9 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
                 "sample": f"gradient oracle (numpy fp64) on {rows} batch row(s), {Ts} tokens, all {w.H} heads, {cpu_s:.2f} s wall",
             }
         if not args.no_parity:
-            ref = ob.backward(w.variant, d["q"][:1], d["k"][:1], d["v"][:1], d["q_logits"][:1], d["k_logits"][:1],
-                              d["log_decay"] if w.variant == 0 else d["log_decay"][:1], cot["d_out"][:1])
+            ref = timed if rows == 1 else ob.backward(
+                w.variant, d["q"][:1], d["k"][:1], d["v"][:1], d["q_logits"][:1], d["k_logits"][:1],
+                d["log_decay"] if w.variant == 0 else d["log_decay"][:1], cot["d_out"][:1], beta=bt(1))
             step()
             torch.cuda.synchronize()
             def f64(t):
@@ -196,8 +229,10 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
                     t = t.permute(0, 2, 1, 3)
                 return t[:1].to(torch.float32).cpu().numpy().astype(np.float64)
             names = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_logits": "dq_logits", "dk_logits": "dk_logits"}
-            if w.variant == 1:
+            if w.variant != 0:
                 names["dlog_decay"] = "dlog_decay"
+            if gdn:
+                names["dbeta"] = "dbeta"
             result["parity"] = {n + "_rel_err": rel_err(f64(gr[n]), ref[rn]) for n, rn in names.items()}
             result["parity"]["definition"] = "max|x - oracle| / max|oracle| per gradient tensor, batch row 0"
     print(json.dumps(result), flush=True)
@@ -545,7 +580,7 @@ def main() -> int:
                     help="decode workloads only: steps per captured HIP graph (0 = plain launches).  A decode step "
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--backward", action="store_true",
-                    help="time sla_backward (RetNet / GLA training workloads) instead of the forward")
+                    help="time sla_backward (RetNet / GLA) or sla_backward_gdn (--workload gdn) instead of the forward")
     ap.add_argument("--flush-mb", type=int, default=0,
                     help="forward only: overwrite a scratch buffer of this many MB between the timed launches, so that "
                          "no input is left in the 256 MB memory-side cache from the previous launch; each launch is "

@@ -15,19 +15,20 @@
 // Once they are known every state recurrence is linear, so the pass is four sweeps that each carry one state tile in
 // registers, token by token, in plain fp32 vector arithmetic (the feedback makes tokens of a block depend on each
 // other; no matrix-core block form is used here):
-//   1. state sweep, forward in time, state tile [dk rows, 16 value columns] per wave: res_t, partial dG^Q,
+//   1. state sweep, forward in time, state tile [dk rows, 8 value columns] per wave: res_t, partial dG^Q,
 //      <d_final, S_T>;
 //   2. cotangent sweep, backward in time, same tile shape: w_t, dv, partial dG^K and dbeta, d_initial_state;
-//   3. key sweep, backward in time, tile [dv rows, 16 key columns] of X^T: the first part of dk, X_t u_t;
-//   4. query sweep, forward in time, tile [dv rows, 16 key columns] of S^T: dq, and dk completed.
+//   3. key sweep, backward in time, tile [dv rows, 8 key columns] of X^T: the first part of dk, X_t u_t;
+//   4. query sweep, forward in time, tile [dv rows, 8 key columns] of S^T: dq, and dk completed.
 // A finishing kernel sums the partial planes, takes the gate gradients through the head softmax of Eq. 4 and writes
 // dbeta; a scan kernel forms dlog_decay.
 //
 // Tile layout of a wave (all four sweeps): lane = 16 * (column group) + (row group); a lane holds ROWS/16 rows by
-// 4 columns of the tile.  A product that contracts the rows is a per-lane partial sum followed by a rotate-and-add
-// over the 16 lanes of a DPP row, which leaves the total in every lane.  A workgroup is four such waves (64 columns)
-// plus four loader waves that stage the next 16 tokens (as fp32) into the other half of a double-buffered LDS area
-// while the compute waves work; one barrier per 16 tokens.
+// 2 columns of the tile, a wave 8 columns.  A product that contracts the rows is a per-lane partial sum followed by
+// a rotate-and-add over the 16 lanes of a DPP row, which leaves the total in every lane.  A workgroup is eight such
+// waves (64 columns, two waves per SIMD so that one computes while the other waits for the LDS) plus four loader
+// waves that stage the next 16 tokens (as fp32) into the other half of a double-buffered LDS area while the compute
+// waves work; one barrier per 16 tokens.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -42,12 +43,15 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) float f4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+typedef __attribute__((ext_vector_type(2))) float fc;  // the CW columns of a lane
 
 constexpr int kChunk = 16;          // tokens staged per barrier
-constexpr int kWaves = 4;           // compute waves (16 columns each); as many loader waves
-constexpr int kLoaders = 64 * kWaves;
-constexpr int kThreads = 2 * kLoaders;
-constexpr int kSlice = 16 * kWaves; // columns per workgroup
+constexpr int CW = 2;               // columns of the tile per lane
+constexpr int kWaves = 8;           // compute waves (4 * CW columns each): two per SIMD, to hide each other's LDS latency
+constexpr int kLoaders = 256;       // threads of the four loader waves
+constexpr int kThreads = 64 * kWaves + kLoaders;
+constexpr int kSlice = 4 * CW * kWaves;  // columns per workgroup
+static_assert(CW == 2 && kSlice == 64, "the staging of the sliced tensors is sized for 64 columns");
 constexpr int kEw = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -69,10 +73,10 @@ struct GArgs {
     float* res;             // [B,T,H,dv] fp32: G^K v - k Sb
     float* w;               // [B,T,H,dv] fp32: beta * (k X)
     float* dk1;             // [B,T,H,dk] fp32: X u
-    float* part_q;          // [dv/16][plane]: partial dout . (q S)
-    float* part_k;          // [dv/16][plane]: partial beta du . v
-    float* part_b;          // [dv/16][plane]: partial du . res
-    float* corr;            // [dv/16][B*H]: partial <d_final, S_T>
+    float* part_q;          // [dv/8][plane]: partial dout . (q S)
+    float* part_k;          // [dv/8][plane]: partial beta du . v
+    float* part_b;          // [dv/8][plane]: partial du . res
+    float* corr;            // [dv/8][B*H]: partial <d_final, S_T>
     size_t plane;           // floats between partial planes (>= B*T*H)
     int B, T, H;
 };
@@ -177,7 +181,8 @@ __device__ __forceinline__ void get_rows(float (&x)[RT], const float* src) {  //
 }
 
 struct Where {  // what a workgroup and its lanes own
-    int tid, wave, lane, rg, cg, slice, bh, b, h, col;  // col: first of the lane's 4 columns inside the sliced dim
+    int tid, wave, lane, rg, cg, slice, bh, b, h, col;  // col: first of the lane's CW columns of the sliced dim
+    int lcol;                                            // the same inside the workgroup's 64-column slice
     size_t tok0;
 };
 __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
@@ -191,7 +196,8 @@ __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
     w.bh = blockIdx.x / nslices;
     w.b = w.bh / a.H;
     w.h = w.bh % a.H;
-    w.col = w.slice * kSlice + (w.wave & (kWaves - 1)) * 16 + w.cg * 4;
+    w.col = w.slice * kSlice + (w.wave & (kWaves - 1)) * 4 * CW + w.cg * CW;
+    w.lcol = w.col - w.slice * kSlice;
     w.tok0 = (size_t)w.b * a.T;
     return w;
 }
@@ -210,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
     const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
-        const int lt = me.tid - kLoaders;
+        const int lt = me.tid - 64 * kWaves;
         const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK;
         const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK;
         const uint16_t* vb = a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
@@ -233,12 +239,12 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
         }
         return;
     }
-    float M[RT][4];
+    float M[RT][CW];
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
-        const f4 x = a.s0 ? *(const f4*)(a.s0 + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col)
-                          : f4{0.f, 0.f, 0.f, 0.f};
-        M[r][0] = x[0]; M[r][1] = x[1]; M[r][2] = x[2]; M[r][3] = x[3];
+        const fc x = a.s0 ? *(const fc*)(a.s0 + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col) : fc{0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < CW; ++j) M[r][j] = x[j];
     }
     __syncthreads();  // chunk 0 staged
     for (int c = 0; c < nch; ++c) {
@@ -250,37 +256,37 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
             float kf[RT], qf[RT];
             get_rows<RT>(kf, buf + oK + i * DK + me.rg * RT);
             get_rows<RT>(qf, buf + oQ + i * DK + me.rg * RT);
-            const f4 vv = *(const f4*)(buf + oV + i * kSlice + me.wave * 16 + me.cg * 4);
-            const f4 dd = *(const f4*)(buf + oDO + i * kSlice + me.wave * 16 + me.cg * 4);
-            float p[4] = {0.f, 0.f, 0.f, 0.f};
+            const fc vv = *(const fc*)(buf + oV + i * kSlice + me.lcol);
+            const fc dd = *(const fc*)(buf + oDO + i * kSlice + me.lcol);
+            float p[CW] = {};
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) p[j] += kf[r] * M[r][j];
-            f4 res;
-            float u[4];
+                for (int j = 0; j < CW; ++j) p[j] += kf[r] * M[r][j];
+            fc res;
+            float u[CW];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CW; ++j) {
                 res[j] = gk * vv[j] - al * row_all(p[j]);
                 u[j] = be * res[j];
             }
-            float y[4] = {0.f, 0.f, 0.f, 0.f};
+            float y[CW] = {};
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < CW; ++j) {
                     M[r][j] = al * M[r][j] + kf[r] * u[j];
                     y[j] += qf[r] * M[r][j];
                 }
             float s = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) s += dd[j] * row_all(y[j]);
+            for (int j = 0; j < CW; ++j) s += dd[j] * row_all(y[j]);
             s = all_groups(s);
             const int t = c * kChunk + i;
             if (t < T) {
                 const size_t row = (me.tok0 + t) * H + me.h;
                 if (me.lane == 0) a.part_q[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = s;
-                if (me.rg == 0) *(f4*)(a.res + row * DV + me.col) = res;
+                if (me.rg == 0) *(fc*)(a.res + row * DV + me.col) = res;
             }
         }
         __syncthreads();
@@ -289,8 +295,9 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
         float s = 0.f;
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
-            const f4 x = *(const f4*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col);
-            s += x[0] * M[r][0] + x[1] * M[r][1] + x[2] * M[r][2] + x[3] * M[r][3];
+            const fc x = *(const fc*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col);
+#pragma unroll
+            for (int j = 0; j < CW; ++j) s += x[j] * M[r][j];
         }
         s = all_groups(row_all(s));
         if (me.lane == 0) a.corr[(size_t)(me.slice * kWaves + me.wave) * a.B * H + me.bh] = s;
@@ -311,7 +318,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
     const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {  // step c of the sweep covers tokens (nch - 1 - c) * 16 ...
-        const int lt = me.tid - kLoaders;
+        const int lt = me.tid - 64 * kWaves;
         const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK;
         const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK;
         const uint16_t* vb = a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
@@ -338,12 +345,12 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
         }
         return;
     }
-    float X[RT][4];
+    float X[RT][CW];
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
-        const f4 x = a.dsf ? *(const f4*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col)
-                           : f4{0.f, 0.f, 0.f, 0.f};
-        X[r][0] = x[0]; X[r][1] = x[1]; X[r][2] = x[2]; X[r][3] = x[3];
+        const fc x = a.dsf ? *(const fc*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col) : fc{0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < CW; ++j) X[r][j] = x[j];
     }
     __syncthreads();
     for (int c = 0; c < nch; ++c) {
@@ -355,20 +362,20 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
             float kf[RT], qf[RT];
             get_rows<RT>(kf, buf + oK + i * DK + me.rg * RT);
             get_rows<RT>(qf, buf + oQ + i * DK + me.rg * RT);
-            const int lc = i * kSlice + me.wave * 16 + me.cg * 4;
-            const f4 vv = *(const f4*)(buf + oV + lc), dd = *(const f4*)(buf + oDO + lc), rr = *(const f4*)(buf + oR + lc);
-            float du[4] = {0.f, 0.f, 0.f, 0.f};
+            const int lc = i * kSlice + me.lcol;
+            const fc vv = *(const fc*)(buf + oV + lc), dd = *(const fc*)(buf + oDO + lc), rr = *(const fc*)(buf + oR + lc);
+            float du[CW] = {};
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < CW; ++j) {
                     X[r][j] += qf[r] * (gq * dd[j]);
                     du[j] += kf[r] * X[r][j];
                 }
-            f4 w;
+            fc w;
             float pk = 0.f, pb = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CW; ++j) {
                 du[j] = row_all(du[j]);
                 w[j] = be * du[j];
                 pk += du[j] * vv[j];
@@ -377,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) X[r][j] = al * (X[r][j] - kf[r] * w[j]);
+                for (int j = 0; j < CW; ++j) X[r][j] = al * (X[r][j] - kf[r] * w[j]);
             pk = all_groups(pk) * be;
             pb = all_groups(pb);
             const int t = (nch - 1 - c) * kChunk + i;
@@ -388,8 +395,8 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
                     a.part_b[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = pb;
                 }
                 if (me.rg == 0) {
-                    *(f4*)(a.w + row * DV + me.col) = w;
-                    *(u2*)(a.dv + row * DV + me.col) = u2{pack2(gk * w[0], gk * w[1]), pack2(gk * w[2], gk * w[3])};
+                    *(fc*)(a.w + row * DV + me.col) = w;
+                    *(uint32_t*)(a.dv + row * DV + me.col) = pack2(gk * w[0], gk * w[1]);
                 }
             }
         }
@@ -398,7 +405,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
     if (a.ds0) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
-            *(f4*)(a.ds0 + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col) = f4{X[r][0], X[r][1], X[r][2], X[r][3]};
+            *(fc*)(a.ds0 + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col) = fc{X[r][0], X[r][1]};
     }
 }
 
@@ -420,7 +427,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
-        const int lt = me.tid - kLoaders;
+        const int lt = me.tid - 64 * kWaves;
         const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV;
         const float* rb = a.res + (me.tok0 * H + me.h) * DV;
         const float* wb = a.w + (me.tok0 * H + me.h) * DV;
@@ -452,12 +459,12 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
         return;
     }
     // tile element [r][j]: value column n = rg * RT + r, key column d = col + j
-    float M[RT][4];
+    float M[RT][CW];
     const float* init = FWD ? a.s0 : a.dsf;
 #pragma unroll
     for (int r = 0; r < RT; ++r)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < CW; ++j)
             M[r][j] = init ? init[((size_t)me.bh * DK + me.col + j) * DV + me.rg * RT + r] : 0.f;
     __syncthreads();
     for (int c = 0; c < nch; ++c) {
@@ -471,44 +478,44 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
             get_rows<RT>(dd, buf + oDO + i * DV + me.rg * RT);
             get_rows<RT>(rr, buf + oR + i * DV + me.rg * RT);
             get_rows<RT>(ww, buf + oW + i * DV + me.rg * RT);
-            const int lc = i * kSlice + me.wave * 16 + me.cg * 4;
-            const f4 kf = *(const f4*)(buf + oK + lc), xf = *(const f4*)(buf + oX + lc);
+            const int lc = i * kSlice + me.lcol;
+            const fc kf = *(const fc*)(buf + oK + lc), xf = *(const fc*)(buf + oX + lc);
             const int t = (FWD ? c : nch - 1 - c) * kChunk + i;
             const size_t row = (me.tok0 + min(t, T - 1)) * H + me.h;
             if constexpr (FWD) {
-                float pk[4] = {0.f, 0.f, 0.f, 0.f}, y[4] = {0.f, 0.f, 0.f, 0.f};
+                float pk[CW] = {}, y[CW] = {};
 #pragma unroll
                 for (int r = 0; r < RT; ++r)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
+                    for (int j = 0; j < CW; ++j) {
                         pk[j] += ww[r] * M[r][j];
                         M[r][j] = al * M[r][j] + (be * rr[r]) * kf[j];
                         y[j] += dd[r] * M[r][j];
                     }
-                float dq[4], dk[4];
+                float dq[CW], dk[CW];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < CW; ++j) {
                     dq[j] = gq * row_all(y[j]);
                     dk[j] = xf[j] - al * row_all(pk[j]);
                 }
                 if (t < T && me.rg == 0) {
-                    *(u2*)(a.dq + row * DK + me.col) = u2{pack2(dq[0], dq[1]), pack2(dq[2], dq[3])};
-                    *(u2*)(a.dk + row * DK + me.col) = u2{pack2(dk[0], dk[1]), pack2(dk[2], dk[3])};
+                    *(uint32_t*)(a.dq + row * DK + me.col) = pack2(dq[0], dq[1]);
+                    *(uint32_t*)(a.dk + row * DK + me.col) = pack2(dk[0], dk[1]);
                 }
             } else {
-                float d1[4] = {0.f, 0.f, 0.f, 0.f};
+                float d1[CW] = {};
 #pragma unroll
                 for (int r = 0; r < RT; ++r)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
+                    for (int j = 0; j < CW; ++j) {
                         M[r][j] += (gq * dd[r]) * xf[j];
                         d1[j] += (be * rr[r]) * M[r][j];
                         M[r][j] = al * (M[r][j] - ww[r] * kf[j]);
                     }
-                f4 o;
+                fc o;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] = row_all(d1[j]);
-                if (t < T && me.rg == 0) *(f4*)(a.dk1 + row * DK + me.col) = o;
+                for (int j = 0; j < CW; ++j) o[j] = row_all(d1[j]);
+                if (t < T && me.rg == 0) *(fc*)(a.dk1 + row * DK + me.col) = o;
             }
         }
         __syncthreads();
@@ -627,10 +634,10 @@ int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
 
 }  // namespace
 
-// Workspace, in floats: gates 2 [B,T,H]; three sets of dv/16 partial planes; the decay scalar [B,T,H];
-// dv/16 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
+// Workspace, in floats: gates 2 [B,T,H]; three sets of dv/8 partial planes; the decay scalar [B,T,H];
+// dv/8 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
 size_t backward_gdn_workspace_floats(const sla_params& p) {
-    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H), planes = (size_t)p.dv / 16;
+    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H), planes = (size_t)p.dv / (4 * CW);
     return n * (3 + 3 * planes) + round4(planes * p.B * p.H) + 2 * round4(rows * p.H * p.dv) +
            round4(rows * p.H * p.dk);
 }
@@ -640,7 +647,7 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
                         const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
                         float* dbeta, float* ds0, float* ws, hipStream_t stream) {
     const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H);
-    const int planes = p.dv / 16;
+    const int planes = p.dv / (4 * CW);  // one per compute wave and slice
     if (rows == 0) {
         if (ds0 && p.B > 0) {  // no tokens: the cotangent of the final state is that of the initial state
             const size_t count = (size_t)p.B * p.H * p.dk * p.dv / 4;

@@ -281,8 +281,8 @@ def test_backward_gdn_workspace_size(lib):
     B, T, H, dk, dv = 2, 100, 4, 128, 64
     n = B * T * H
     got = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, B=B, T=T, H=H, dk=dk, dv=dv))
-    planes = dv // 16
-    # gates and the decay scalar (3 planes), three sets of dv/16 partial planes, <d_final, S_T> partials,
+    planes = dv // 8
+    # gates and the decay scalar (3 planes), three sets of dv/8 partial planes, <d_final, S_T> partials,
     # two fp32 tensors like v and one like k
     assert got == 4 * (n * (3 + 3 * planes) + planes * B * H + 2 * n * dv + n * dk)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
