@@ -86,7 +86,7 @@ def test_decode_steps_replay_identically():
     assert torch.equal(state, eager_state) and torch.equal(out, eager_out)
 
 
-@pytest.mark.parametrize("variant", [RETNET, GLA])
+@pytest.mark.parametrize("variant", [RETNET, GLA, GDN])
 def test_training_step_replays_identically(variant):
     """Gate logits, forward and backward captured as one graph (raw entry points, buffers allocated up front); the
     workspace is dirtied between replays."""
@@ -106,21 +106,29 @@ def test_training_step_replays_identically(variant):
     fin = torch.empty((B, H, dk, dv), dtype=torch.float32, device="cuda")
     grads = [torch.empty_like(g["q"]), torch.empty_like(g["k"]), torch.empty_like(g["v"]), torch.empty_like(ql),
              torch.empty_like(kl)]
-    dld = torch.empty_like(g["log_decay"]) if variant == GLA else None
-    ws = torch.empty(sla.sla_backward_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    dld = torch.empty_like(g["log_decay"]) if variant != RETNET else None
+    dbeta = torch.empty_like(g["beta"]) if variant == GDN else None
+    need = sla.sla_backward_gdn_workspace_bytes(p) if variant == GDN else sla.sla_backward_workspace_bytes(p)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     ptr = lambda t: None if t is None else t.data_ptr()
 
     def step(stream):
         assert sla.sla_gate_logits(p, ptr(g["q"]), ptr(g["k"]), ptr(wq), ptr(wk), ptr(ql), ptr(kl), stream) == 0
-        assert sla.sla_forward(p, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]), None,
-                               None, ptr(out), ptr(fin), stream) == 0
+        assert sla.sla_forward(p, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]),
+                               ptr(g["beta"]), None, ptr(out), ptr(fin), stream) == 0
+        if variant == GDN:
+            assert sla.sla_backward_gdn(p, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl),
+                                        ptr(g["log_decay"]), ptr(g["beta"]), None, ptr(dout), None,
+                                        *(ptr(t) for t in grads), ptr(dld), ptr(dbeta), None, ptr(ws), ws.numel(),
+                                        stream) == 0
+            return
         assert sla.sla_backward(p, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]), None,
                                 ptr(dout), None, *(ptr(t) for t in grads), ptr(dld), None, ptr(ws), ws.numel(),
                                 stream) == 0
 
     step(torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
-    everything = [ql, kl, out, fin] + grads + ([dld] if dld is not None else [])
+    everything = [ql, kl, out, fin] + grads + [t for t in (dld, dbeta) if t is not None]
     ref = [t.clone() for t in everything]
 
     side = torch.cuda.Stream()
