@@ -83,11 +83,13 @@ struct GArgs {
 
 __device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
-__device__ __forceinline__ uint32_t bf16_bits(float x) {  // round to nearest even
-    const uint32_t u = __float_as_uint(x);
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // the hardware conversion: nearest even, NaN kept
+    bf2 t;
+    t.x = (__bf16)lo;
+    t.y = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, t);
 }
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x) {
@@ -108,6 +110,14 @@ __device__ __forceinline__ float all_groups(float x) {
     const uint32_t yi = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
     const u2 b = __builtin_amdgcn_permlane32_swap(yi, yi, false, false);
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// A token's row-side vector (length 16 * RT: the dimension the tile contracts) is stored so that the 16 lanes of a
+// DPP row, which own RT consecutive elements each, read 16 consecutive 16-byte pieces per instruction (no bank
+// conflicts): element c = rg * RT + 4 m + e sits at float m * 64 + rg * 4 + e.  `c` is a multiple of 4.
+template <int RT>
+__device__ __forceinline__ int row_slot(int c) {
+    return ((c % RT) >> 2) * 64 + (c / RT) * 4;
 }
 
 // ---- staging: NC columns of 16 tokens of one head, global -> registers -> LDS (fp32 [16][NC]) ----------------
@@ -136,6 +146,20 @@ struct RegsB {
             }
         }
     }
+    // The same for a tensor whose columns are the ROWS of the tile: see row_slot().
+    __device__ __forceinline__ void put_rows(float* dst, int t0, int T, int lt) const {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = lt + kLoaders * n, tok = it / (NC / 8), c8 = it % (NC / 8);
+            if (it < items) {
+                const bool ok = t0 + tok < T;
+                const u4 y = ok ? x[n] : u4{0u, 0u, 0u, 0u};
+                float* d = dst + tok * NC;
+                *(f4*)(d + row_slot<NC / 16>(8 * c8)) = f4{bf_lo(y[0]), bf_hi(y[0]), bf_lo(y[1]), bf_hi(y[1])};
+                *(f4*)(d + row_slot<NC / 16>(8 * c8 + 4)) = f4{bf_lo(y[2]), bf_hi(y[2]), bf_lo(y[3]), bf_hi(y[3])};
+            }
+        }
+    }
 };
 template <int NC>
 struct RegsF {
@@ -155,8 +179,23 @@ struct RegsF {
             if (it < items) *(f4*)(dst + tok * NC + 4 * c4) = t0 + tok < T ? x[n] : f4{0.f, 0.f, 0.f, 0.f};
         }
     }
+    __device__ __forceinline__ void put_rows(float* dst, int t0, int T, int lt) const {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = lt + kLoaders * n, tok = it / (NC / 4), c4 = it % (NC / 4);
+            if (it < items)
+                *(f4*)(dst + tok * NC + row_slot<NC / 16>(4 * c4)) = t0 + tok < T ? x[n] : f4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
 };
-// Per-token scalars {a, beta, G^Q, G^K}; a token past the end leaves every state unchanged (a = 1, the rest 0).
+// Per-token scalars {a, beta, G^Q, G^K, F, 1/F, R, 1/R}; a token past the end leaves every state unchanged (a = 1,
+// the gates and beta 0).  The sweeps keep their state tile divided by a running decay product so that the decay costs
+// no multiplication per tile element: inside a group of kNorm tokens a forward sweep holds S / F_t with
+// F_t = product of a over the group's tokens up to t, a backward sweep holds X / R_t with R_t = product of a over the
+// group's tokens after t; at the end of a group the tile is multiplied out.  With log_decay >= -20 per token the
+// products stay above e^-80, inside fp32's range.
+constexpr int kNorm = 4;
+constexpr int kScal = 8;
 struct RegsS {
     float ld, be, gq, gk;
     __device__ __forceinline__ void load(const GArgs& a, size_t tok0, int h, int t0, int T, int lt) {
@@ -164,18 +203,28 @@ struct RegsS {
         ld = a.ld[i]; be = a.beta[i]; gq = a.gq[i]; gk = a.gk[i];
     }
     __device__ __forceinline__ void put(float* dst, int t0, int T, int lt) const {
+        const bool ok = t0 + (lt & (kChunk - 1)) < T;
+        const float al = ok ? __builtin_amdgcn_exp2f(ld * kLog2e) : 1.f;
+        float F = 1.f, R = 1.f;  // lanes 0..15 of the first loader wave hold the chunk's 16 tokens
+#pragma unroll
+        for (int j = 0; j < kNorm; ++j) {
+            const float x = __shfl(al, (lt & (kChunk - kNorm)) + j);
+            if (j <= (lt & (kNorm - 1))) F *= x;
+            else R *= x;
+        }
         if (lt < kChunk) {
-            const bool ok = t0 + lt < T;
-            *(f4*)(dst + 4 * lt) = ok ? f4{__builtin_amdgcn_exp2f(ld * kLog2e), be, gq, gk} : f4{1.f, 0.f, 0.f, 0.f};
+            float* d = dst + kScal * lt;
+            *(f4*)d = ok ? f4{al, be, gq, gk} : f4{1.f, 0.f, 0.f, 0.f};
+            *(f4*)(d + 4) = f4{F, __builtin_amdgcn_rcpf(F), R, __builtin_amdgcn_rcpf(R)};
         }
     }
 };
 
 template <int RT>
-__device__ __forceinline__ void get_rows(float (&x)[RT], const float* src) {  // RT consecutive floats, RT % 4 == 0
+__device__ __forceinline__ void get_rows(float (&x)[RT], const float* src) {  // src: the token's vector + 4 * rg
 #pragma unroll
     for (int i = 0; i < RT / 4; ++i) {
-        const f4 y = *(const f4*)(src + 4 * i);
+        const f4 y = *(const f4*)(src + 64 * i);
         x[4 * i] = y[0]; x[4 * i + 1] = y[1]; x[4 * i + 2] = y[2]; x[4 * i + 3] = y[3];
     }
 }
@@ -209,7 +258,7 @@ template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) {
     constexpr int RT = DK / 16;
     constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
-                  oSC = oDO + kChunk * kSlice, kBuf = oSC + 4 * kChunk;
+                  oSC = oDO + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
@@ -231,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
                 rk.load(kb, sk, t0, T, lt); rq.load(qb, sk, t0, T, lt);
                 rv.load(vb, sv, t0, T, lt); rd.load(db, sv, t0, T, lt);
                 rs.load(a, me.tok0, me.h, t0, T, lt);
-                rk.put(buf + oK, t0, T, lt); rq.put(buf + oQ, t0, T, lt);
+                rk.put_rows(buf + oK, t0, T, lt); rq.put_rows(buf + oQ, t0, T, lt);
                 rv.put(buf + oV, t0, T, lt); rd.put(buf + oDO, t0, T, lt);
                 rs.put(buf + oSC, t0, T, lt);
             }
@@ -249,13 +298,13 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
     __syncthreads();  // chunk 0 staged
     for (int c = 0; c < nch; ++c) {
         const float* buf = lds + (c & 1) * kBuf;
-#pragma unroll 2
+#pragma unroll kNorm
         for (int i = 0; i < kChunk; ++i) {
-            const f4 sc = *(const f4*)(buf + oSC + 4 * i);
-            const float al = sc[0], be = sc[1], gk = sc[3];
+            const f4 sc = *(const f4*)(buf + oSC + kScal * i), sn = *(const f4*)(buf + oSC + kScal * i + 4);
+            const float be = sc[1], gk = sc[3], F = sn[0], Fi = sn[1];  // M holds S / F
             float kf[RT], qf[RT];
-            get_rows<RT>(kf, buf + oK + i * DK + me.rg * RT);
-            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * RT);
+            get_rows<RT>(kf, buf + oK + i * DK + me.rg * 4);
+            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * 4);
             const fc vv = *(const fc*)(buf + oV + i * kSlice + me.lcol);
             const fc dd = *(const fc*)(buf + oDO + i * kSlice + me.lcol);
             float p[CW] = {};
@@ -267,21 +316,27 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
             float u[CW];
 #pragma unroll
             for (int j = 0; j < CW; ++j) {
-                res[j] = gk * vv[j] - al * row_all(p[j]);
-                u[j] = be * res[j];
+                res[j] = gk * vv[j] - F * row_all(p[j]);  // k Sb = a k S_{t-1} = F_t k (S_{t-1} / F_{t-1})
+                u[j] = be * res[j] * Fi;
             }
             float y[CW] = {};
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
                 for (int j = 0; j < CW; ++j) {
-                    M[r][j] = al * M[r][j] + kf[r] * u[j];
+                    M[r][j] += kf[r] * u[j];
                     y[j] += qf[r] * M[r][j];
                 }
             float s = 0.f;
 #pragma unroll
             for (int j = 0; j < CW; ++j) s += dd[j] * row_all(y[j]);
-            s = all_groups(s);
+            s = all_groups(s) * F;
+            if ((i & (kNorm - 1)) == kNorm - 1) {
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+#pragma unroll
+                    for (int j = 0; j < CW; ++j) M[r][j] *= F;
+            }
             const int t = c * kChunk + i;
             if (t < T) {
                 const size_t row = (me.tok0 + t) * H + me.h;
@@ -311,7 +366,7 @@ template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs a) {
     constexpr int RT = DK / 16;
     constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
-                  oR = oDO + kChunk * kSlice, oSC = oR + kChunk * kSlice, kBuf = oSC + 4 * kChunk;
+                  oR = oDO + kChunk * kSlice, oSC = oR + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
@@ -336,7 +391,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
                 rv.load(vb, sv, t0, T, lt); rd.load(db, sv, t0, T, lt);
                 rr.load(rb, sv, t0, T, lt);
                 rs.load(a, me.tok0, me.h, t0, T, lt);
-                rk.put(buf + oK, t0, T, lt); rq.put(buf + oQ, t0, T, lt);
+                rk.put_rows(buf + oK, t0, T, lt); rq.put_rows(buf + oQ, t0, T, lt);
                 rv.put(buf + oV, t0, T, lt); rd.put(buf + oDO, t0, T, lt);
                 rr.put(buf + oR, t0, T, lt);
                 rs.put(buf + oSC, t0, T, lt);
@@ -355,13 +410,13 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
     __syncthreads();
     for (int c = 0; c < nch; ++c) {
         const float* buf = lds + (c & 1) * kBuf;
-#pragma unroll 2
+#pragma unroll kNorm
         for (int i = kChunk - 1; i >= 0; --i) {
-            const f4 sc = *(const f4*)(buf + oSC + 4 * i);
-            const float al = sc[0], be = sc[1], gq = sc[2], gk = sc[3];
+            const f4 sc = *(const f4*)(buf + oSC + kScal * i), sn = *(const f4*)(buf + oSC + kScal * i + 4);
+            const float al = sc[0], be = sc[1], gq = sc[2], gk = sc[3], R = sn[2], Ri = sn[3];  // X holds X_t / R
             float kf[RT], qf[RT];
-            get_rows<RT>(kf, buf + oK + i * DK + me.rg * RT);
-            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * RT);
+            get_rows<RT>(kf, buf + oK + i * DK + me.rg * 4);
+            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * 4);
             const int lc = i * kSlice + me.lcol;
             const fc vv = *(const fc*)(buf + oV + lc), dd = *(const fc*)(buf + oDO + lc), rr = *(const fc*)(buf + oR + lc);
             float du[CW] = {};
@@ -369,22 +424,28 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
             for (int r = 0; r < RT; ++r)
 #pragma unroll
                 for (int j = 0; j < CW; ++j) {
-                    X[r][j] += qf[r] * (gq * dd[j]);
+                    X[r][j] += qf[r] * (gq * Ri * dd[j]);
                     du[j] += kf[r] * X[r][j];
                 }
             fc w;
-            float pk = 0.f, pb = 0.f;
+            float pk = 0.f, pb = 0.f, wr[CW];
 #pragma unroll
             for (int j = 0; j < CW; ++j) {
-                du[j] = row_all(du[j]);
+                du[j] = R * row_all(du[j]);
                 w[j] = be * du[j];
+                wr[j] = w[j] * Ri;
                 pk += du[j] * vv[j];
                 pb += du[j] * rr[j];
             }
+            const bool out_of_group = (i & (kNorm - 1)) == 0;  // then multiply out: X_{t-1} = a R (X/R - k w/R)
+            const float mul = R * al;
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < CW; ++j) X[r][j] = al * (X[r][j] - kf[r] * w[j]);
+                for (int j = 0; j < CW; ++j) {
+                    X[r][j] -= kf[r] * wr[j];
+                    if (out_of_group) X[r][j] *= mul;
+                }
             pk = all_groups(pk) * be;
             pb = all_groups(pb);
             const int t = (nch - 1 - c) * kChunk + i;
@@ -420,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     constexpr int RT = DV / 16;
     constexpr int oDO = 0, oR = oDO + kChunk * DV, oW = oR + kChunk * DV, oK = oW + kChunk * DV,
                   oX = oK + kChunk * kSlice,  // sweep 3: q slice; sweep 4: dk1 slice
-        oSC = oX + kChunk * kSlice, kBuf = oSC + 4 * kChunk;
+        oSC = oX + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DK / kSlice);
@@ -448,7 +509,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
                 if constexpr (FWD) r1.load(d1, sk, t0, T, lt);
                 else rq.load(qb, sk, t0, T, lt);
                 rs.load(a, me.tok0, me.h, t0, T, lt);
-                rd.put(buf + oDO, t0, T, lt); rr.put(buf + oR, t0, T, lt); rw.put(buf + oW, t0, T, lt);
+                rd.put_rows(buf + oDO, t0, T, lt); rr.put_rows(buf + oR, t0, T, lt); rw.put_rows(buf + oW, t0, T, lt);
                 rk.put(buf + oK, t0, T, lt);
                 if constexpr (FWD) r1.put(buf + oX, t0, T, lt);
                 else rq.put(buf + oX, t0, T, lt);
@@ -469,15 +530,16 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     __syncthreads();
     for (int c = 0; c < nch; ++c) {
         const float* buf = lds + (c & 1) * kBuf;
-#pragma unroll 2
+#pragma unroll kNorm
         for (int ii = 0; ii < kChunk; ++ii) {
             const int i = FWD ? ii : kChunk - 1 - ii;
-            const f4 sc = *(const f4*)(buf + oSC + 4 * i);
+            const f4 sc = *(const f4*)(buf + oSC + kScal * i), sn = *(const f4*)(buf + oSC + kScal * i + 4);
             const float al = sc[0], be = sc[1], gq = sc[2];
+            const float N = FWD ? sn[0] : sn[2], Ni = FWD ? sn[1] : sn[3];  // M holds S^T / F or X^T / R
             float dd[RT], rr[RT], ww[RT];
-            get_rows<RT>(dd, buf + oDO + i * DV + me.rg * RT);
-            get_rows<RT>(rr, buf + oR + i * DV + me.rg * RT);
-            get_rows<RT>(ww, buf + oW + i * DV + me.rg * RT);
+            get_rows<RT>(dd, buf + oDO + i * DV + me.rg * 4);
+            get_rows<RT>(rr, buf + oR + i * DV + me.rg * 4);
+            get_rows<RT>(ww, buf + oW + i * DV + me.rg * 4);
             const int lc = i * kSlice + me.lcol;
             const fc kf = *(const fc*)(buf + oK + lc), xf = *(const fc*)(buf + oX + lc);
             const int t = (FWD ? c : nch - 1 - c) * kChunk + i;
@@ -489,14 +551,20 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
 #pragma unroll
                     for (int j = 0; j < CW; ++j) {
                         pk[j] += ww[r] * M[r][j];
-                        M[r][j] = al * M[r][j] + (be * rr[r]) * kf[j];
+                        M[r][j] += (be * Ni * rr[r]) * kf[j];
                         y[j] += dd[r] * M[r][j];
                     }
                 float dq[CW], dk[CW];
 #pragma unroll
                 for (int j = 0; j < CW; ++j) {
-                    dq[j] = gq * row_all(y[j]);
-                    dk[j] = xf[j] - al * row_all(pk[j]);
+                    dq[j] = gq * N * row_all(y[j]);
+                    dk[j] = xf[j] - N * row_all(pk[j]);  // a w S_{t-1}^T = F_t w (S_{t-1} / F_{t-1})^T
+                }
+                if ((i & (kNorm - 1)) == kNorm - 1) {
+#pragma unroll
+                    for (int r = 0; r < RT; ++r)
+#pragma unroll
+                        for (int j = 0; j < CW; ++j) M[r][j] *= N;
                 }
                 if (t < T && me.rg == 0) {
                     *(uint32_t*)(a.dq + row * DK + me.col) = pack2(dq[0], dq[1]);
@@ -508,13 +576,20 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
                 for (int r = 0; r < RT; ++r)
 #pragma unroll
                     for (int j = 0; j < CW; ++j) {
-                        M[r][j] += (gq * dd[r]) * xf[j];
+                        M[r][j] += (gq * Ni * dd[r]) * xf[j];
                         d1[j] += (be * rr[r]) * M[r][j];
-                        M[r][j] = al * (M[r][j] - ww[r] * kf[j]);
+                        M[r][j] -= (Ni * ww[r]) * kf[j];
                     }
                 fc o;
 #pragma unroll
-                for (int j = 0; j < CW; ++j) o[j] = row_all(d1[j]);
+                for (int j = 0; j < CW; ++j) o[j] = N * row_all(d1[j]);
+                if ((i & (kNorm - 1)) == 0) {
+                    const float mul = N * al;
+#pragma unroll
+                    for (int r = 0; r < RT; ++r)
+#pragma unroll
+                        for (int j = 0; j < CW; ++j) M[r][j] *= mul;
+                }
                 if (t < T && me.rg == 0) *(fc*)(a.dk1 + row * DK + me.col) = o;
             }
         }
@@ -602,9 +677,9 @@ bool allow_lds(K kernel, int lds) {
 
 template <int DK, int DV>
 int launch_sweeps(const GArgs& a, hipStream_t stream) {
-    constexpr int lds1 = 2 * 4 * (2 * kChunk * DK + 2 * kChunk * kSlice + 4 * kChunk);
-    constexpr int lds2 = 2 * 4 * (2 * kChunk * DK + 3 * kChunk * kSlice + 4 * kChunk);
-    constexpr int lds3 = 2 * 4 * (3 * kChunk * DV + 2 * kChunk * kSlice + 4 * kChunk);
+    constexpr int lds1 = 2 * 4 * (2 * kChunk * DK + 2 * kChunk * kSlice + kScal * kChunk);
+    constexpr int lds2 = 2 * 4 * (2 * kChunk * DK + 3 * kChunk * kSlice + kScal * kChunk);
+    constexpr int lds3 = 2 * 4 * (3 * kChunk * DV + 2 * kChunk * kSlice + kScal * kChunk);
     static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024, "fits the LDS of a compute unit");
     static bool configured = false;  // once per instantiation; not a stream operation
     if (!configured) {
