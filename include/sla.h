@@ -184,7 +184,8 @@ size_t sla_backward_workspace_bytes(const sla_params* p);
  *
  *   q, k, v, q_head_logits, k_head_logits, initial_state, d_out, d_final_state,
  *   dq, dk, dv, dq_head_logits, dk_head_logits, d_initial_state      as for sla_backward
- *   log_decay, beta  [B,T,H] fp32   as for sla_forward; required
+ *   log_decay, beta  [B,T,H] fp32   as for sla_forward; required.  log_decay >= -20 per token (the sweeps keep
+ *                                   their state divided by the decay product of up to four tokens)
  *   dlog_decay       [B,T,H] fp32   written; required
  *   dbeta            [B,T,H] fp32   written; required
  *   workspace        device memory of at least sla_backward_gdn_workspace_bytes(p) bytes, 16-byte aligned (gates,

@@ -109,6 +109,17 @@ def test_beta_zero_tokens_write_nothing():
     assert np.max(np.abs(ref["dbeta"][:, ::3])) > 0.0
 
 
+def test_strong_decay_domain():
+    # log-decay down to -5 per token (and a few at -20): the sweeps keep their tiles divided by a running decay
+    # product over 4 tokens, which must stay inside fp32's range
+    B, T, H = 1, 100, 2
+    d, cot, s0 = make(B, T, H, 64, 128, seed=1165, states=True)
+    r = np.random.default_rng(1166)
+    d["log_decay"] = (-5.0 * r.random(size=d["log_decay"].shape)).astype(np.float32)
+    d["log_decay"][:, 40:48] = -20.0
+    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label="decay in [-5, 0], eight tokens at -20")
+
+
 def test_long_sequence():
     d, cot, s0 = make(1, 4096 + 24, 2, 128, 128, seed=1170, states=True)
     check_backward_gdn(d, cot, s0=s0, want_ds0=True, label="T=4120")
