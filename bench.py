@@ -105,8 +105,9 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
         for n in ("q", "k", "v") + (("log_decay",) if w.variant == 1 else ()):
             g[n] = g[n].permute(0, 2, 1, 3).contiguous()
         dout = dout.permute(0, 2, 1, 3).contiguous()
-    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, sla.FLAG_HEAD_MAJOR if hm else 0, 1)
     gdn = w.variant == 2
+    nseg = max(args.segments, 1) if not (gdn or hm) else 1  # the backward cuts rows into segments only on request
+    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, sla.FLAG_HEAD_MAJOR if hm else 0, nseg)
     need = sla.sla_backward_gdn_workspace_bytes(params) if gdn else sla.sla_backward_workspace_bytes(params)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     gr = {
@@ -167,11 +168,14 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
         "config": {
             "workload": f"{w.name}: backward of SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} "
                         f"dk={w.dk} dv={w.dv} bf16 in/out, dual head-softmax gates, no state cotangents"
-                        + (", wide tensors laid out [B,H,T,d]" if hm else ""),
+                        + (", wide tensors laid out [B,H,T,d]" if hm else "")
+                        + (f", {nseg} segments per batch row" if nseg > 1 else ""),
             "kernel": ("sla_backward_gdn: sla_bwd_gates_kernel, gdn_bwd_state_kernel, gdn_bwd_cotangent_kernel, "
                        "gdn_bwd_key_kernel x2, gdn_bwd_finish_kernel, gdn_bwd_decay_scan_kernel") if gdn else
                       "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
-                      "sla_bwd_logits_kernel x2",
+                      "sla_bwd_logits_kernel x2"
+                      + (" after the segment pre-passes (sla_fwd_kernel state-only, sla_segment_combine_kernel, "
+                         "sla_bwd_dv_kernel state-only, sla_bwd_segment_combine_kernel)" if nseg > 1 else ""),
         },
         "roofline": {
             "bound": "alu",
@@ -197,7 +201,7 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "kernel_us": call_ms * 1e3,
             "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
             "algorithmic_bytes": abytes,
-            "note": "whole call (six launches); achieved = algorithmic bytes / call time",
+            "note": "whole call (%s launches); achieved = algorithmic bytes / call time" % ("six" if nseg == 1 else "thirteen"),
         },
     }
     if not args.no_cpu_baseline or not args.no_parity:

@@ -146,8 +146,12 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
  * gradients that training through the chunkwise form of Sec. 3.2 ("Chunkwise Parallel Form") needs.  With the
  * scalar objective L = sum(out * d_out) + sum(final_state * d_final_state) it writes dL/d(input) for every
  * differentiable input of the forward call made with the same p, q, k, v, logits, log_decay and initial_state.
- * bf16 tensors only (p->dtype == SLA_BF16); the delta rule is not covered (SLA_ERR_UNSUPPORTED).
- * p->dv_split and p->segments are ignored.
+ * bf16 tensors only (p->dtype == SLA_BF16); the delta rule has its own entry point, sla_backward_gdn.
+ * p->dv_split is ignored.  p->segments >= 2 asks for the segment-parallel schedule (for batches with few sequences,
+ * as in sla_forward_ws): every batch row is cut into that many segments (of a multiple of 64 tokens, at least 256)
+ * which run in parallel; the entry state and the end cotangent of every segment come from two pre-passes.  It needs
+ * the [B,T,H,d] layout (p->flags == 0) and a larger workspace (sla_backward_workspace_bytes accounts for it); 0 and 1
+ * run the single pass.
  *
  *   q, k, v, q_head_logits, k_head_logits, log_decay, initial_state   as for sla_forward (device, read only)
  *   d_out            [B,T,H,dv]  dtype   cotangent of out; required

@@ -330,10 +330,12 @@ def sla_backward(params, q, k, v, q_head_logits, k_head_logits, log_decay, initi
 
 
 def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_out, initial_state=None,
-             d_final_state=None, *, want_d_initial_state: bool = False, workspace=None, head_major: bool = False):
+             d_final_state=None, *, want_d_initial_state: bool = False, workspace=None, head_major: bool = False,
+             segments: int = 1):
     """Gradients of ``forward`` (RetNet, GLA; bfloat16) on the current CUDA(HIP) device and stream.  Returns a dict
     of new tensors: dq, dk, dv, dq_head_logits, dk_head_logits (None without k_head_logits), dlog_decay (GLA only,
-    else None) and d_initial_state (None unless asked for)."""
+    else None) and d_initial_state (None unless asked for).  ``segments`` >= 2 cuts every batch row into that many
+    segments that run in parallel (for batches with few sequences)."""
     import torch
 
     assert q.is_cuda and q.dtype == torch.bfloat16
@@ -360,7 +362,7 @@ def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_o
         "dlog_decay": torch.empty_like(log_decay) if variant == GLA else None,
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, FLAG_HEAD_MAJOR if head_major else 0, 1)
+    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, FLAG_HEAD_MAJOR if head_major else 0, int(segments))
     need = sla_backward_workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)

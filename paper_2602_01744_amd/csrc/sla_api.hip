@@ -15,6 +15,12 @@ size_t backward_workspace_floats(const sla_params& p, bool packed);
 int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                     const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
                     float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu, hipStream_t stream);
+size_t backward_segment_extra_floats(const sla_params& p, int nseg);
+sla_params packed_segments(const sla_params& p, int nseg);
+int launch_backward_segments(const sla_params& p, int nseg, int seg_len, int dvw, const void* q, const void* k,
+                             const void* v, const float* ql, const float* kl, const void* ld, const float* s0,
+                             const void* dout, const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl,
+                             void* dld, float* ds0, float* ws, hipStream_t stream);
 size_t backward_gdn_workspace_floats(const sla_params& p);
 int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
                         const float* kl, const float* ld, const float* beta, const float* s0, const void* dout,
@@ -202,6 +208,22 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
                               (hipStream_t)stream);
 }
 
+// The backward pass cuts batch rows into segments only on request (p->segments >= 2), so that its workspace size
+// does not depend on the device; the cut itself is the forward's.
+static int backward_segments(const sla_params& p, bool packed, int* seg_len) {
+    *seg_len = p.T;
+    if (packed || p.segments < 2 || p.T == 0) return 1;
+    return choose_segments(p, 1, seg_len);
+}
+
+static size_t backward_floats(const sla_params& p, bool packed) {
+    int len = 0;
+    const int nseg = backward_segments(p, packed, &len);
+    if (nseg <= 1) return sla::backward_workspace_floats(p, packed);
+    return sla::backward_workspace_floats(sla::packed_segments(p, nseg), true) +
+           sla::backward_segment_extra_floats(p, nseg);
+}
+
 static int backward_impl(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
                          const float* k_head_logits, const void* log_decay, const float* initial_state,
                          const void* d_out, const float* d_final_state, void* dq, void* dk, void* dv,
@@ -225,8 +247,16 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 3u)) return SLA_ERR_ALIGN;
     if (p->B == 0) return SLA_OK;
     if (p->T == 0 && !d_initial_state) return SLA_OK;
-    if (!workspace || sla::backward_workspace_floats(*p, packed) * sizeof(float) > workspace_bytes)
-        return SLA_ERR_WORKSPACE;
+    if (!workspace || backward_floats(*p, packed) * sizeof(float) > workspace_bytes) return SLA_ERR_WORKSPACE;
+    int seg_len = 0;
+    const int nseg = backward_segments(*p, packed, &seg_len);
+    if (nseg > 1) {
+        if (p->flags != 0) return SLA_ERR_UNSUPPORTED;  // the segments run as a packed batch: [B,T,H,d] only
+        return sla::launch_backward_segments(*p, nseg, seg_len, 64, q, k, v, q_head_logits, k_head_logits, log_decay,
+                                             initial_state, d_out, d_final_state, dq, dk, dv, dq_head_logits,
+                                             dk_head_logits, dlog_decay, d_initial_state, (float*)workspace,
+                                             (hipStream_t)stream);
+    }
     return sla::launch_backward(*p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out,
                                 d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
                                 d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr,
@@ -317,7 +347,7 @@ int sla_short_conv_silu(int dtype, int B, int T, int channels, int taps, const v
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {
     if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16) return 0;
-    return sla::backward_workspace_floats(*p, false) * sizeof(float);
+    return backward_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_varlen_workspace_bytes(const sla_params* p) {

@@ -76,6 +76,8 @@ struct BArgs {
     size_t rows;             // tokens in all: B * T, or the packed total
     const int* cu;           // packed variable-length batch: sequence b is tokens cu[b] .. cu[b+1]-1 of T; else null
     bool head_major;         // q, k, v, d_out, the GLA decay and their gradients are [B,H,T,d] instead of [B,T,H,d]
+    int sweeps;              // which of the three sweeps to launch: 1 = dq, 2 = dv, 4 = dk (all: 7)
+    bool dv_state_only;      // the dv sweep writes d_initial_state but not dv (pre-pass of the segment schedule)
 };
 
 __device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
@@ -1052,7 +1054,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
         }
         consumer_release(ring, blk);  // every operand of the block is in registers
         const int tok = t0 + r;
-        if (tok < T) {
+        if (tok < T && !a.dv_state_only) {
             *(u2*)(a.dv + (wide0 + (size_t)tok * wstep) * DV + sbase + cb + 4 * g) =
                 u2{pack2(gk * (Ys[0] + Yi[0]), gk * (Ys[1] + Yi[1])), pack2(gk * (Ys[2] + Yi[2]), gk * (Ys[3] + Yi[3]))};
         }
@@ -1154,9 +1156,12 @@ int launch_sweeps(const BArgs& a, hipStream_t stream) {
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kBwdThreads);
     auto grid = [bh](unsigned slices) { return dim3(((bh + 7u) / 8u) * 8u * slices); };  // see logical_workgroup()
-    hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), grid(DK / kCols), block, (size_t)ldsF, stream, a);
-    hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), grid(DV / kCols), block, (size_t)ldsV, stream, a);
-    hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), grid(DK / kCols), block, (size_t)ldsK, stream, a);
+    if (a.sweeps & 1)
+        hipLaunchKernelGGL((sla_bwd_dq_kernel<VAR, DK, DV>), grid(DK / kCols), block, (size_t)ldsF, stream, a);
+    if (a.sweeps & 2)
+        hipLaunchKernelGGL((sla_bwd_dv_kernel<VAR, DK, DV>), grid(DV / kCols), block, (size_t)ldsV, stream, a);
+    if (a.sweeps & 4)
+        hipLaunchKernelGGL((sla_bwd_dk_kernel<VAR, DK, DV>), grid(DK / kCols), block, (size_t)ldsK, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
@@ -1202,11 +1207,139 @@ size_t backward_workspace_floats(const sla_params& p, bool packed) {
     return total;
 }
 
+namespace {
+
+// Segment schedule of the backward pass (rectangular batch with few sequences): see launch_backward_segments.
+__global__ __launch_bounds__(kEwThreads) void sla_bwd_segment_offsets_kernel(int* cu, int B, int T, int nseg, int len) {
+    const int i = blockIdx.x * kEwThreads + threadIdx.x;
+    if (i > B * nseg) return;
+    const int b = i / nseg, s = i - b * nseg;
+    cu[i] = i == B * nseg ? B * T : b * T + min(s * len, T);
+}
+
+// dsf[b][s] = the caller's final-state cotangent for the last segment of a batch row, zero for the others.
+__global__ __launch_bounds__(kEwThreads) void sla_bwd_segment_seed_kernel(const f4* dsf_user, f4* dsf, int nseg,
+                                                                          size_t per_row, size_t count) {
+    const size_t i = (size_t)blockIdx.x * kEwThreads + threadIdx.x;
+    if (i >= count) return;
+    const size_t bs = i / per_row, b = bs / nseg, s = bs - b * nseg;
+    dsf[i] = (dsf_user && s == (size_t)nseg - 1) ? dsf_user[b * per_row + (i - bs * per_row)] : f4{0.f, 0.f, 0.f, 0.f};
+}
+
+// part[b][s] holds the state cotangent at the START of segment s when the cotangent at its end is zero (the last
+// segment: the caller's).  By linearity the true one is T_s = part_s + diag(D_s) T_{s+1}, and the cotangent at the
+// END of segment s is T_{s+1}: written to dsf[b][s] (s < nseg - 1; the last keeps the caller's).  T_0 is the gradient
+// with respect to the initial state.  One thread per (batch, head, key row, 4 value columns).
+template <int VAR>
+__global__ __launch_bounds__(kEwThreads) void sla_bwd_segment_combine_kernel(const float* part, const float* totals,
+                                                                             const float* ld_head, float* dsf,
+                                                                             float* ds0_user, int B, int H, int dk,
+                                                                             int dv, int nseg, int len) {
+    const int dv4 = dv / 4;
+    const size_t per_head = (size_t)dk * dv4, idx = (size_t)blockIdx.x * kEwThreads + threadIdx.x;
+    if (idx >= (size_t)B * H * per_head) return;
+    const int bh = (int)(idx / per_head), b = bh / H, h = bh % H;
+    const int d = (int)((idx % per_head) / dv4), n = (int)(idx % dv4) * 4;
+    const size_t head_sz = (size_t)dk * dv, off = (size_t)d * dv + n;
+    auto at = [&](int s) { return ((size_t)(b * nseg + s) * H + h) * head_sz + off; };
+    f4 t = *(const f4*)(part + at(nseg - 1));
+    for (int s = nseg - 2; s >= 0; --s) {
+        *(f4*)(dsf + at(s)) = t;
+        const float D = VAR == SLA_GLA ? totals[((size_t)(b * (nseg - 1) + s) * H + h) * dk + d]
+                                       : ex2(ld_head[h] * kLog2e * (float)len);  // segments before the last are full
+        const f4 x = *(const f4*)(part + at(s));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = x[i] + D * t[i];
+    }
+    if (ds0_user) *(f4*)(ds0_user + (size_t)bh * head_sz + off) = t;
+}
+
+}  // namespace
+
+int launch_segment_states(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k,
+                          const void* v, const float* ql, const float* kl, const void* ld, const float* s0,
+                          float* workspace, float* totals, hipStream_t stream);
+size_t segment_workspace_floats(const sla_params& p, int nseg);
+
+// Floats the segment schedule adds to the workspace of the packed backward over B * nseg sequences: the forward
+// pre-pass's own workspace, segment decay totals, two state-sized arrays per segment and the segment offsets.
+size_t backward_segment_extra_floats(const sla_params& p, int nseg) {
+    const size_t states = (size_t)p.B * nseg * p.H * p.dk * p.dv;
+    return round4(segment_workspace_floats(p, nseg)) + round4((size_t)p.B * (nseg - 1) * p.H * p.dk) + 2 * states +
+           round4((size_t)p.B * nseg + 1);
+}
+
+sla_params packed_segments(const sla_params& p, int nseg) {
+    sla_params pk = p;
+    pk.B = p.B * nseg;
+    pk.T = p.B * p.T;
+    pk.segments = 1;
+    return pk;
+}
+
+int launch_backward_some(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
+                         const float* kl, const void* ld, const float* s0, const void* dout, const float* dsf, void* dq,
+                         void* dk, void* dv, float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu,
+                         hipStream_t stream, int sweeps, bool dv_state_only);
+
+// Few sequences (B * H * slices below the number of compute units): every batch row is cut into nseg segments of
+// seg_len tokens, which then run as B * nseg packed sequences, each with its own entry state and end cotangent:
+//   1. entry states of the segments: the forward pass's pre-pass and combine kernel;
+//   2. the dv sweep alone over the segments with zero end cotangents (the last segment: the caller's), which leaves
+//      each segment's start cotangent; 3. a combine kernel turns those into the true end cotangents;
+//   4. the packed backward pass over the segments.
+int launch_backward_segments(const sla_params& p, int nseg, int seg_len, int dvw, const void* q, const void* k,
+                             const void* v, const float* ql, const float* kl, const void* ld, const float* s0,
+                             const void* dout, const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl,
+                             void* dld, float* ds0, float* ws, hipStream_t stream) {
+    const sla_params pk = packed_segments(p, nseg);
+    const size_t states = (size_t)pk.B * p.H * p.dk * p.dv;
+    float* w = ws + backward_workspace_floats(pk, true);
+    float* fwd = w; w += round4(segment_workspace_floats(p, nseg));  // entry states first
+    float* totals = w; w += round4((size_t)p.B * (nseg - 1) * p.H * p.dk);
+    float* part = w; w += states;
+    float* seg_dsf = w; w += states;
+    int* cu = (int*)w;
+    const unsigned eb = kEwThreads;
+    hipLaunchKernelGGL(sla_bwd_segment_offsets_kernel, dim3((unsigned)(pk.B + eb) / eb), dim3(eb), 0, stream, cu, p.B,
+                       p.T, nseg, seg_len);
+    hipLaunchKernelGGL(sla_bwd_segment_seed_kernel, dim3((unsigned)((states / 4 + eb - 1) / eb)), dim3(eb), 0, stream,
+                       (const f4*)dsf, (f4*)seg_dsf, nseg, (size_t)p.H * p.dk * p.dv / 4, states / 4);
+    if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
+    int rc = launch_segment_states(p, dvw, nseg, seg_len, q, k, v, ql, kl, ld, s0, fwd, totals, stream);
+    if (rc != SLA_OK) return rc;
+    rc = launch_backward_some(pk, q, k, v, ql, kl, ld, nullptr, dout, seg_dsf, dq, dk, dv, dql, dkl, dld, part, ws, cu,
+                              stream, 2, true);
+    if (rc != SLA_OK) return rc;
+    const size_t n = (size_t)p.B * p.H * p.dk * (p.dv / 4);
+    if (p.variant == SLA_GLA)
+        hipLaunchKernelGGL(sla_bwd_segment_combine_kernel<SLA_GLA>, dim3((unsigned)((n + eb - 1) / eb)), dim3(eb), 0,
+                           stream, (const float*)part, (const float*)totals, (const float*)nullptr, seg_dsf, ds0, p.B,
+                           p.H, p.dk, p.dv, nseg, seg_len);
+    else
+        hipLaunchKernelGGL(sla_bwd_segment_combine_kernel<SLA_RETNET>, dim3((unsigned)((n + eb - 1) / eb)), dim3(eb), 0,
+                           stream, (const float*)part, (const float*)nullptr, (const float*)ld, seg_dsf, ds0, p.B, p.H,
+                           p.dk, p.dv, nseg, seg_len);
+    if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
+    return launch_backward_some(pk, q, k, v, ql, kl, ld, fwd, dout, seg_dsf, dq, dk, dv, dql, dkl, dld, nullptr, ws, cu,
+                                stream, 7, false);
+}
+
 int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                     const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
                     float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu, hipStream_t stream) {
+    return launch_backward_some(p, q, k, v, ql, kl, ld, s0, dout, dsf, dq, dk, dv, dql, dkl, dld, ds0, ws, cu, stream, 7,
+                                false);
+}
+
+int launch_backward_some(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
+                         const float* kl, const void* ld, const float* s0, const void* dout, const float* dsf, void* dq,
+                         void* dk, void* dv, float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu,
+                         hipStream_t stream, int sweeps, bool dv_state_only) {
     const size_t rows = cu ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
     BArgs a;
+    a.sweeps = sweeps;
+    a.dv_state_only = dv_state_only;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
     a.ld = p.variant == SLA_GLA ? (const uint16_t*)ld : nullptr;
     a.ld_head = p.variant == SLA_RETNET ? (const float*)ld : nullptr;
@@ -1234,7 +1367,7 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
     }
     const int rc = p.variant == SLA_GLA ? launch_dk<SLA_GLA>(a, p.dk, p.dv, stream)
                                         : launch_dk<SLA_RETNET>(a, p.dk, p.dv, stream);
-    if (rc != SLA_OK || rows == 0) return rc;
+    if (rc != SLA_OK || rows == 0 || sweeps != 7) return rc;
     // the planes of one gate are n floats apart (n >= rows * H); the kernel indexes them by rows * H
     hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gq, (const float*)a.part_q,
                        p.dk / 16, dql, rows, p.H);

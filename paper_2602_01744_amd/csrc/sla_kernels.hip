@@ -79,6 +79,11 @@ struct KArgs {
     int nparts;  // producer waves of the pre-pass: partial decay products per segment in ws_decay
     float* ws_state;
     float* ws_decay;
+    // Used by the backward pass's segment schedule, which wants only what the pre-pass and the combine kernel
+    // produce: the entry state of every segment (ws_state) and, in ws_total[b][s][h][dk], the total decay of each
+    // segment but the last.  states_only stops the call after the combine kernel.
+    float* ws_total;
+    bool states_only;
     // Packed variable-length batch: B sequences laid end to end in tensors of T tokens in all; sequence b covers
     // tokens cu[b] .. cu[b + 1] - 1.  Null for the rectangular layout.
     const int* cu;
@@ -1277,6 +1282,7 @@ __global__ void sla_segment_combine_kernel(const KArgs a, int dk) {
         } else {
             D = fast_exp2(((const float*)a.ld)[h] * kLog2e * (float)a.Ls);  // segments before the last are full
         }
+        if (a.ws_total && n == 0) a.ws_total[((size_t)(b * (a.nseg - 1) + s) * a.H + h) * dk + d] = D;
         f32x4* Lp = (f32x4*)(a.ws_state + ((size_t)(b * a.nseg + s + 1) * a.H + h) * head_sz + off);
         const f32x4 Lseg = *Lp;
 #pragma unroll
@@ -1301,6 +1307,7 @@ static int launch(const KArgs& a, hipStream_t stream) {
         const size_t n = (size_t)a.B * a.H * DK * (a.dv / 4);
         hipLaunchKernelGGL(sla_segment_combine_kernel<VAR>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, mid, DK);
         if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
+        if (a.states_only) return SLA_OK;
         return launch_one<P, VAR, DK, DVW, HG, false>(a, stream);
     }
 }
@@ -1358,6 +1365,8 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
     a.nseg = nseg; a.nseg_grid = nseg; a.nparts = 0; a.Ls = nseg > 1 ? seg_len : p.T;
     a.ws_state = workspace;
     a.ws_decay = workspace ? workspace + (size_t)p.B * nseg * p.H * p.dk * p.dv : nullptr;
+    a.ws_total = nullptr;
+    a.states_only = false;
     a.cu = cu;
     if (p.T == 0) {
         if (!sT) return SLA_OK;
@@ -1365,6 +1374,29 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
         hipLaunchKernelGGL(sla_state_passthrough_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, sT, n);
         return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
     }
+    if (p.dtype == SLA_BF16) return dispatch_variant<PrecBF16>(a, p.variant, p.dk, dvw, stream);
+    return dispatch_variant<PrecF32>(a, p.variant, p.dk, dvw, stream);
+}
+
+// The first two steps of the segment-parallel schedule alone (RetNet, GLA; nseg >= 2; rectangular batch): on return
+// (in stream order) workspace holds the state entering every segment, [B * nseg][H][dk][dv], followed by scratch of
+// the pre-pass, and totals the decay of every segment but the last, [B][nseg - 1][H][dk].  workspace needs
+// segment_workspace_floats(p, nseg) floats.
+int launch_segment_states(const sla_params& p, int dvw, int nseg, int seg_len, const void* q, const void* k,
+                          const void* v, const float* ql, const float* kl, const void* ld, const float* s0,
+                          float* workspace, float* totals, hipStream_t stream) {
+    if (nseg < 2 || p.variant == SLA_GDN || p.T == 0) return SLA_ERR_UNSUPPORTED;
+    KArgs a;
+    a.head_major = false;
+    a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = nullptr; a.s0 = s0; a.out = nullptr;
+    a.sT = nullptr;
+    a.B = p.B; a.T = p.T; a.H = p.H; a.dv = p.dv; a.nslice = p.dv / dvw;
+    a.nseg = nseg; a.nseg_grid = nseg; a.nparts = 0; a.Ls = seg_len;
+    a.ws_state = workspace;
+    a.ws_decay = workspace + (size_t)p.B * nseg * p.H * p.dk * p.dv;
+    a.ws_total = totals;
+    a.states_only = true;
+    a.cu = nullptr;
     if (p.dtype == SLA_BF16) return dispatch_variant<PrecBF16>(a, p.variant, p.dk, dvw, stream);
     return dispatch_variant<PrecF32>(a, p.variant, p.dk, dvw, stream);
 }

@@ -177,7 +177,7 @@ def _bwd(p, **kw):
 
 def test_backward_rejects_bad_calls(lib):
     ok = _ok_params()
-    assert _bwd(_ok_params(variant=sla.GDN)) == -3           # the delta rule has no backward here
+    assert _bwd(_ok_params(variant=sla.GDN)) == -3           # the delta rule's backward is sla_backward_gdn
     assert _bwd(_ok_params(dtype=sla.F32)) == -3             # bf16 only
     assert _bwd(_ok_params(dk=96)) == -3
     assert _bwd(ok, dout=0) == -1
@@ -287,3 +287,21 @@ def test_backward_gdn_workspace_size(lib):
     assert got == 4 * (n * (3 + 3 * planes) + planes * B * H + 2 * n * dv + n * dk)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32)) == 0
+
+
+def test_backward_segment_schedule_workspace_and_validation(lib):
+    # p->segments >= 2 cuts every batch row: the packed workspace of B * nseg sequences plus the pre-passes' own
+    B, T, H, dk, dv, nseg = 2, 1024, 4, 128, 64, 4
+    one = sla.sla_backward_workspace_bytes(_ok_params(B=B, T=T, H=H, dk=dk, dv=dv))
+    seg = sla.sla_backward_workspace_bytes(_ok_params(B=B, T=T, H=H, dk=dk, dv=dv, segments=nseg))
+    packed = sla.sla_backward_varlen_workspace_bytes(_ok_params(B=B * nseg, T=B * T, H=H, dk=dk, dv=dv))
+    state = H * dk * dv
+    forward_ws = B * H * (nseg * dk * dv + (nseg - 1) * 8 * dk)      # entry states, partial decay products
+    extra = forward_ws + B * (nseg - 1) * H * dk + 2 * B * nseg * state + (B * nseg + 1 + 3) // 4 * 4
+    assert seg == packed + 4 * extra and seg > one
+    # a request that yields a single segment is the plain pass
+    assert sla.sla_backward_workspace_bytes(_ok_params(B=B, T=200, H=H, dk=dk, dv=dv, segments=4)) == \
+        sla.sla_backward_workspace_bytes(_ok_params(B=B, T=200, H=H, dk=dk, dv=dv))
+    hm = _ok_params(flags=1, segments=2, T=1024)
+    assert _bwd(hm, ws_bytes=1 << 40) == -3                   # segments run as a packed batch: [B,T,H,d] only
+    assert _bwd(_ok_params(segments=2, T=1024), ws_bytes=sla.sla_backward_workspace_bytes(_ok_params(T=1024))) == -6

@@ -15,7 +15,7 @@ NAMES = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_head_logits": "dq_logits", "dk_
          "dlog_decay": "dlog_decay", "d_initial_state": "dinitial_state"}
 
 
-def run_backward(variant, d, cot, s0=None, want_ds0=False):
+def run_backward(variant, d, cot, s0=None, want_ds0=False, segments=1):
     import torch
     import paper_2602_01744_amd as sla
 
@@ -24,13 +24,13 @@ def run_backward(variant, d, cot, s0=None, want_ds0=False):
     up = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
     res = sla.backward(variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"],
                        up(cot["d_out"], torch.bfloat16), up(s0, torch.float32), up(cot["d_final_state"], torch.float32),
-                       want_d_initial_state=want_ds0)
+                       want_d_initial_state=want_ds0, segments=segments)
     torch.cuda.synchronize()
     return {n: None if t is None else t.to(torch.float32).cpu().numpy().astype(np.float64) for n, t in res.items()}
 
 
-def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_rows=None):
-    got = run_backward(variant, d, cot, s0, want_ds0)
+def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_rows=None, segments=1):
+    got = run_backward(variant, d, cot, s0, want_ds0, segments)
     rows = slice(None) if batch_rows is None else batch_rows
     sub = lambda a: None if a is None else (a if a.ndim == 1 else a[rows])
     ref = ob.backward(variant, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
@@ -144,6 +144,26 @@ def test_long_sequences_keep_the_decay_gradient_accurate(T, dv, states):
     scale = np.abs(ref["dlog_decay"]).max()
     early = np.abs(got["dlog_decay"][:, :512] - ref["dlog_decay"][:, :512]).max() / scale
     assert early <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("variant", [RETNET, GLA])
+@pytest.mark.parametrize("T,segments,states", [(700, 2, True), (1000, 3, False), (2048 + 37, 4, True), (512, 2, True)])
+def test_segment_schedule(variant, T, segments, states):
+    """Batch rows cut into segments that run as packed sequences: entry states from the forward's pre-pass, end
+    cotangents from a dv-sweep pre-pass and a combine kernel.  Same answers as the single pass, to the same bar."""
+    B, H, dk, dv = 2, 2, 128, 128
+    d = si.custom(variant, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=990 + T + variant)
+    cot = si.cotangents(B, T, H, dk, dv, seed=991 + T, final_state=states)
+    s0 = si.initial_state(B, H, dk, dv, seed=992 + T) if states else None
+    check_backward(variant, d, cot, s0=s0, want_ds0=True, label=f"T={T} in {segments} segments", segments=segments)
+
+
+def test_segment_schedule_on_the_paper_shape():
+    """gla_paper_h4 (B=8, T=4096, H=4, dk=128, dv=256: 32 sequences) in 4 segments; the oracle runs on one row."""
+    w = si.workload("gla_paper_h4")
+    d = si.generate(w)
+    cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
+    check_backward(w.variant, d, cot, label="gla_paper_h4, 4 segments", batch_rows=slice(0, 1), segments=4)
 
 
 @pytest.mark.parametrize("name", ["gla_train", "retnet_train"])
