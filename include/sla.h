@@ -209,6 +209,20 @@ int sla_backward_gdn(const sla_params* p, const void* q, const void* k, const vo
 size_t sla_backward_gdn_workspace_bytes(const sla_params* p);
 
 /*
+ * The same on a packed batch of sequences of different lengths, with the conventions of sla_forward_varlen /
+ * sla_backward_varlen: p->T is the total number of tokens, p->B the number of sequences, cu_seqlens [B+1] int32 in
+ * DEVICE memory (clamped into [0, p->T] by the kernels), one state per sequence; log_decay, beta and their gradients
+ * are [T,H].  Needs sla_backward_gdn_varlen_workspace_bytes(p) bytes of workspace.
+ */
+int sla_backward_gdn_varlen(const sla_params* p, const void* q, const void* k, const void* v,
+                            const float* q_head_logits, const float* k_head_logits, const float* log_decay,
+                            const float* beta, const int32_t* cu_seqlens, const float* initial_state,
+                            const void* d_out, const float* d_final_state, void* dq, void* dk, void* dv,
+                            float* dq_head_logits, float* dk_head_logits, float* dlog_decay, float* dbeta,
+                            float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream);
+size_t sla_backward_gdn_varlen_workspace_bytes(const sla_params* p);
+
+/*
  * Gate logits: the scores Eq. 4 takes the head softmax of, from the (feature-mapped) queries and keys and the
  * two gate matrices W_GQ, W_GK in R^{d x H} of Sec. 3.2, with d the head width (the reading under which the two
  * matrices add the 0.05 M parameters that the "Parameter Efficiency" paragraph counts):

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     sla_backward_workspace_bytes,
     sla_backward_gdn,
     sla_backward_gdn_workspace_bytes,
+    sla_backward_gdn_varlen,
+    sla_backward_gdn_varlen_workspace_bytes,
     sla_check_args,
     sla_gate_logits,
     sla_short_conv_silu,
@@ -39,6 +41,7 @@ from .binding import (  # noqa: F401
     forward_varlen,
     backward,
     backward_gdn,
+    backward_gdn_varlen,
     backward_varlen,
     gate_logits,
     short_conv_silu,

@@ -80,6 +80,10 @@ def load_library():
     lib.sla_backward_gdn.argtypes = [pp] + [vp] * 19 + [ctypes.c_size_t, vp]
     lib.sla_backward_gdn_workspace_bytes.restype = ctypes.c_size_t
     lib.sla_backward_gdn_workspace_bytes.argtypes = [pp]
+    lib.sla_backward_gdn_varlen.restype = ctypes.c_int
+    lib.sla_backward_gdn_varlen.argtypes = [pp] + [vp] * 20 + [ctypes.c_size_t, vp]
+    lib.sla_backward_gdn_varlen_workspace_bytes.restype = ctypes.c_size_t
+    lib.sla_backward_gdn_varlen_workspace_bytes.argtypes = [pp]
     lib.sla_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.sla_backward_workspace_bytes.argtypes = [pp]
     lib.sla_workspace_bytes.restype = ctypes.c_size_t
@@ -395,6 +399,62 @@ def sla_backward_gdn(params, q, k, v, q_head_logits, k_head_logits, log_decay, b
             ctypes.c_size_t(int(workspace_bytes)), _p(stream),
         )
     )
+
+
+def sla_backward_gdn_varlen_workspace_bytes(params: SlaParams) -> int:
+    return int(load_library().sla_backward_gdn_varlen_workspace_bytes(ctypes.byref(params)))
+
+
+def sla_backward_gdn_varlen(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, cu_seqlens, initial_state,
+                            d_out, d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, dbeta,
+                            d_initial_state, workspace, workspace_bytes, stream) -> int:
+    """Raw call of the packed variable-length backward of the gated delta rule."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_backward_gdn_varlen(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta), _p(cu_seqlens),
+            _p(initial_state), _p(d_out), _p(d_final_state), _p(dq), _p(dk), _p(dv), _p(dq_head_logits),
+            _p(dk_head_logits), _p(dlog_decay), _p(dbeta), _p(d_initial_state), _p(workspace),
+            ctypes.c_size_t(int(workspace_bytes)), _p(stream),
+        )
+    )
+
+
+def backward_gdn_varlen(q, k, v, q_head_logits, k_head_logits, log_decay, beta, d_out, cu_seqlens, initial_state=None,
+                        d_final_state=None, *, want_d_initial_state: bool = False):
+    """Gradients of ``forward_varlen(GDN, ...)``: q, k [T,H,dk], v, d_out [T,H,dv] bfloat16; logits, log_decay, beta
+    [T,H] float32; cu_seqlens [B+1] int32 on the device; states [B,H,dk,dv].  Returns a dict as ``backward_gdn``."""
+    import torch
+
+    assert q.is_cuda and q.dtype == torch.bfloat16 and q.dim() == 3
+    T, H, dk = q.shape
+    dv = v.shape[-1]
+    B = cu_seqlens.numel() - 1
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_cuda
+    dev = q.device
+    g = {
+        "dq": torch.empty_like(q),
+        "dk": torch.empty_like(k),
+        "dv": torch.empty_like(v),
+        "dq_head_logits": torch.empty_like(q_head_logits),
+        "dk_head_logits": None if k_head_logits is None else torch.empty_like(k_head_logits),
+        "dlog_decay": torch.empty_like(log_decay),
+        "dbeta": torch.empty_like(beta),
+        "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
+    }
+    params = SlaParams(GDN, BF16, B, T, H, dk, dv, 0, 0, 1)
+    need = sla_backward_gdn_varlen_workspace_bytes(params)
+    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = sla_backward_gdn_varlen(
+        params, ptr(q), ptr(k), ptr(v), ptr(q_head_logits), ptr(k_head_logits), ptr(log_decay), ptr(beta),
+        ptr(cu_seqlens), ptr(initial_state), ptr(d_out), ptr(d_final_state), ptr(g["dq"]), ptr(g["dk"]), ptr(g["dv"]),
+        ptr(g["dq_head_logits"]), ptr(g["dk_head_logits"]), ptr(g["dlog_decay"]), ptr(g["dbeta"]),
+        ptr(g["d_initial_state"]), ptr(workspace), workspace.numel(), torch.cuda.current_stream(dev).cuda_stream,
+    )
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return g
 
 
 def backward_gdn(q, k, v, q_head_logits, k_head_logits, log_decay, beta, d_out, initial_state=None,

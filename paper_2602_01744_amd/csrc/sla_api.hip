@@ -21,11 +21,11 @@ int launch_backward_segments(const sla_params& p, int nseg, int seg_len, int dvw
                              const void* v, const float* ql, const float* kl, const void* ld, const float* s0,
                              const void* dout, const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl,
                              void* dld, float* ds0, float* ws, hipStream_t stream);
-size_t backward_gdn_workspace_floats(const sla_params& p);
+size_t backward_gdn_workspace_floats(const sla_params& p, bool packed);
 int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
                         const float* kl, const float* ld, const float* beta, const float* s0, const void* dout,
                         const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
-                        float* dbeta, float* ds0, float* ws, hipStream_t stream);
+                        float* dbeta, float* ds0, float* ws, const int* cu, hipStream_t stream);
 int launch_gate_logits(const sla_params& p, const void* q, const void* k, const float* wq, const float* wk, float* ql,
                        float* kl, int compute_units, hipStream_t stream);
 int launch_short_conv_silu(int dtype, int B, int T, int C, int taps, const void* x, const float* w, void* y,
@@ -283,11 +283,12 @@ int sla_backward_varlen(const sla_params* p, const void* q, const void* k, const
                          workspace_bytes, cu_seqlens, true, stream);
 }
 
-int sla_backward_gdn(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
-                     const float* k_head_logits, const float* log_decay, const float* beta,
-                     const float* initial_state, const void* d_out, const float* d_final_state, void* dq, void* dk,
-                     void* dv, float* dq_head_logits, float* dk_head_logits, float* dlog_decay, float* dbeta,
-                     float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
+static int backward_gdn_impl(const sla_params* p, const void* q, const void* k, const void* v,
+                             const float* q_head_logits, const float* k_head_logits, const float* log_decay,
+                             const float* beta, const int32_t* cu, bool packed, const float* initial_state,
+                             const void* d_out, const float* d_final_state, void* dq, void* dk, void* dv,
+                             float* dq_head_logits, float* dk_head_logits, float* dlog_decay, float* dbeta,
+                             float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
     if (p->variant != SLA_GDN || p->dtype != SLA_BF16 || p->flags != 0) return SLA_ERR_UNSUPPORTED;
@@ -297,23 +298,52 @@ int sla_backward_gdn(const sla_params* p, const void* q, const void* k, const vo
             return SLA_ERR_NULL;
     }
     if ((k_head_logits != nullptr) != (dk_head_logits != nullptr)) return SLA_ERR_NULL;
+    if (packed && p->B > 0 && !cu) return SLA_ERR_NULL;
     const void* ptrs[] = {q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, d_out,
                           d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, dbeta,
                           d_initial_state, workspace};
     for (const void* x : ptrs)
         if (x && !aligned16(x)) return SLA_ERR_ALIGN;
+    if (cu && (reinterpret_cast<uintptr_t>(cu) & 3u)) return SLA_ERR_ALIGN;
     if (p->B == 0) return SLA_OK;
     if (p->T == 0 && !d_initial_state) return SLA_OK;
-    if (p->T > 0 && (!workspace || sla::backward_gdn_workspace_floats(*p) * sizeof(float) > workspace_bytes))
+    if (p->T > 0 && (!workspace || sla::backward_gdn_workspace_floats(*p, packed) * sizeof(float) > workspace_bytes))
         return SLA_ERR_WORKSPACE;
     return sla::launch_backward_gdn(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, d_out,
                                     d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, dbeta,
-                                    d_initial_state, (float*)workspace, (hipStream_t)stream);
+                                    d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr,
+                                    (hipStream_t)stream);
+}
+
+int sla_backward_gdn(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                     const float* k_head_logits, const float* log_decay, const float* beta,
+                     const float* initial_state, const void* d_out, const float* d_final_state, void* dq, void* dk,
+                     void* dv, float* dq_head_logits, float* dk_head_logits, float* dlog_decay, float* dbeta,
+                     float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_gdn_impl(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, nullptr, false, initial_state,
+                             d_out, d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, dbeta,
+                             d_initial_state, workspace, workspace_bytes, stream);
+}
+
+int sla_backward_gdn_varlen(const sla_params* p, const void* q, const void* k, const void* v,
+                            const float* q_head_logits, const float* k_head_logits, const float* log_decay,
+                            const float* beta, const int32_t* cu_seqlens, const float* initial_state,
+                            const void* d_out, const float* d_final_state, void* dq, void* dk, void* dv,
+                            float* dq_head_logits, float* dk_head_logits, float* dlog_decay, float* dbeta,
+                            float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_gdn_impl(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, cu_seqlens, true,
+                             initial_state, d_out, d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits,
+                             dlog_decay, dbeta, d_initial_state, workspace, workspace_bytes, stream);
 }
 
 size_t sla_backward_gdn_workspace_bytes(const sla_params* p) {
     if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dtype != SLA_BF16) return 0;
-    return sla::backward_gdn_workspace_floats(*p) * sizeof(float);
+    return sla::backward_gdn_workspace_floats(*p, false) * sizeof(float);
+}
+
+size_t sla_backward_gdn_varlen_workspace_bytes(const sla_params* p) {
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dtype != SLA_BF16) return 0;
+    return sla::backward_gdn_workspace_floats(*p, true) * sizeof(float);
 }
 
 int sla_gate_logits(const sla_params* p, const void* q, const void* k, const float* w_gq, const float* w_gk,

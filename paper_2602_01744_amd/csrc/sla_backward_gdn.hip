@@ -77,7 +77,9 @@ struct GArgs {
     float* part_k;          // [dv/8][plane]: partial beta du . v
     float* part_b;          // [dv/8][plane]: partial du . res
     float* corr;            // [dv/8][B*H]: partial <d_final, S_T>
-    size_t plane;           // floats between partial planes (>= B*T*H)
+    size_t plane;           // floats between partial planes (>= rows * H)
+    size_t rows;            // tokens in all: B * T, or the packed total T
+    const int* cu;          // packed batch: sequence b is tokens cu[b] .. cu[b+1]-1 of the T in all; else null
     int B, T, H;
 };
 
@@ -232,7 +234,8 @@ __device__ __forceinline__ void get_rows(float (&x)[RT], const float* src) {  //
 struct Where {  // what a workgroup and its lanes own
     int tid, wave, lane, rg, cg, slice, bh, b, h, col;  // col: first of the lane's CW columns of the sliced dim
     int lcol;                                            // the same inside the workgroup's 64-column slice
-    size_t tok0;
+    int T;                                               // tokens of this sequence
+    size_t tok0;                                         // index of its first token
 };
 __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
     Where w;
@@ -247,7 +250,13 @@ __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
     w.h = w.bh % a.H;
     w.col = w.slice * kSlice + (w.wave & (kWaves - 1)) * 4 * CW + w.cg * CW;
     w.lcol = w.col - w.slice * kSlice;
+    w.T = a.T;
     w.tok0 = (size_t)w.b * a.T;
+    if (a.cu) {  // offsets are clamped into the tensors whatever cu holds
+        const int start = min(max(a.cu[w.b], 0), a.T), end = min(max(a.cu[w.b + 1], start), a.T);
+        w.T = end - start;
+        w.tok0 = (size_t)start;
+    }
     return w;
 }
 
@@ -262,7 +271,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
-    const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
+    const int T = me.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
         const int lt = me.tid - 64 * kWaves;
@@ -370,7 +379,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
-    const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
+    const int T = me.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {  // step c of the sweep covers tokens (nch - 1 - c) * 16 ...
         const int lt = me.tid - 64 * kWaves;
@@ -485,7 +494,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DK / kSlice);
-    const int T = a.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
+    const int T = me.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
         const int lt = me.tid - 64 * kWaves;
@@ -605,7 +614,7 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int 
                                                              float* dbeta, float* e) {
     __shared__ float sx[kEw];
     const int H = a.H, per = kEw / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
-    const size_t rows = (size_t)a.B * a.T, row = (size_t)blockIdx.x * per + lr;
+    const size_t rows = a.rows, row = (size_t)blockIdx.x * per + lr;
     const bool ok = lr < per && row < rows;
     const size_t i = ok ? row * H + h : 0;
     float dgq = 0.f, dgk = 0.f, db = 0.f, gq = 0.f, gk = 0.f;
@@ -640,11 +649,18 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int 
 
 // dlog_decay[b,t,h] = <d_final, S_T>[b,h] + sum_{s >= t} e[b,s,h]; one workgroup per (b, h).
 __global__ __launch_bounds__(kEw) void gdn_bwd_decay_scan_kernel(const float* e, const float* corr, int planes, int B,
-                                                                 int T, int H, float* dld) {
+                                                                 int Ttot, int H, const int* cu, float* dld) {
     __shared__ float sx[kEw];
     const int bh = blockIdx.x, b = bh / H, h = bh % H, tid = threadIdx.x;
+    int T = Ttot;
+    size_t tok0 = (size_t)b * Ttot;
+    if (cu) {
+        const int start = min(max(cu[b], 0), Ttot), end = min(max(cu[b + 1], start), Ttot);
+        T = end - start;
+        tok0 = (size_t)start;
+    }
     const int per = (T + kEw - 1) / kEw, lo = min(tid * per, T), hi = min(lo + per, T);
-    const float* src = e + (size_t)b * T * H + h;
+    const float* src = e + tok0 * H + h;
     float own = 0.f;
     for (int t = lo; t < hi; ++t) own += src[(size_t)t * H];
     sx[tid] = own;
@@ -653,7 +669,7 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_decay_scan_kernel(const float* e,
     if (corr)
         for (int p = 0; p < planes; ++p) run += corr[(size_t)p * B * H + bh];
     for (int j = tid + 1; j < kEw; ++j) run += sx[j];
-    float* dst = dld + (size_t)b * T * H + h;
+    float* dst = dld + tok0 * H + h;
     for (int t = hi - 1; t >= lo; --t) {
         run += src[(size_t)t * H];
         dst[(size_t)t * H] = run;
@@ -711,8 +727,9 @@ int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
 
 // Workspace, in floats: gates 2 [B,T,H]; three sets of dv/8 partial planes; the decay scalar [B,T,H];
 // dv/8 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
-size_t backward_gdn_workspace_floats(const sla_params& p) {
-    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H), planes = (size_t)p.dv / (4 * CW);
+size_t backward_gdn_workspace_floats(const sla_params& p, bool packed) {
+    const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
+    const size_t planes = (size_t)p.dv / (4 * CW);
     return n * (3 + 3 * planes) + round4(planes * p.B * p.H) + 2 * round4(rows * p.H * p.dv) +
            round4(rows * p.H * p.dk);
 }
@@ -720,8 +737,8 @@ size_t backward_gdn_workspace_floats(const sla_params& p) {
 int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
                         const float* kl, const float* ld, const float* beta, const float* s0, const void* dout,
                         const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
-                        float* dbeta, float* ds0, float* ws, hipStream_t stream) {
-    const size_t rows = (size_t)p.B * p.T, n = round4(rows * p.H);
+                        float* dbeta, float* ds0, float* ws, const int* cu, hipStream_t stream) {
+    const size_t rows = cu ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
     const int planes = p.dv / (4 * CW);  // one per compute wave and slice
     if (rows == 0) {
         if (ds0 && p.B > 0) {  // no tokens: the cotangent of the final state is that of the initial state
@@ -749,6 +766,8 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
     a.w = w; w += round4(rows * p.H * p.dv);
     a.dk1 = w;
     a.plane = n;
+    a.rows = rows;
+    a.cu = cu;
     a.B = p.B; a.T = p.T; a.H = p.H;
 
     int rc = launch_bwd_gates(ql, kl, gq, gk, rows, p.H, stream);
@@ -759,7 +778,7 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
     hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, planes, dql, kl ? dkl : nullptr,
                        dbeta, e);
     hipLaunchKernelGGL(gdn_bwd_decay_scan_kernel, dim3((unsigned)(p.B * p.H)), dim3(kEw), 0, stream, (const float*)e,
-                       dsf ? (const float*)a.corr : nullptr, planes, p.B, p.T, p.H, dld);
+                       dsf ? (const float*)a.corr : nullptr, planes, p.B, p.T, p.H, cu, dld);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -305,3 +305,17 @@ def test_backward_segment_schedule_workspace_and_validation(lib):
     hm = _ok_params(flags=1, segments=2, T=1024)
     assert _bwd(hm, ws_bytes=1 << 40) == -3                   # segments run as a packed batch: [B,T,H,d] only
     assert _bwd(_ok_params(segments=2, T=1024), ws_bytes=sla.sla_backward_workspace_bytes(_ok_params(T=1024))) == -6
+
+
+def test_backward_gdn_varlen_validation_and_workspace(lib):
+    ok = _ok_params(variant=sla.GDN)
+    call = lambda p, cu=A: sla.sla_backward_gdn_varlen(p, A, A, A, A, A, A, A, cu, 0, A, 0, A, A, A, A, A, A, A, 0, A,
+                                                       1 << 40, 0)
+    assert call(ok, cu=0) == -1 and call(ok, cu=A + 2) == -4
+    assert call(_ok_params(variant=sla.GLA)) == -3
+    assert call(_ok_params(variant=sla.GDN, B=0), cu=0) == 0
+    # sized by the total token count p->T, not B * T
+    p, one = _ok_params(variant=sla.GDN, B=5, T=1000), _ok_params(variant=sla.GDN, B=1, T=1000)
+    planes = p.dv // 8
+    assert sla.sla_backward_gdn_varlen_workspace_bytes(p) == \
+        sla.sla_backward_gdn_workspace_bytes(one) + 4 * ((planes * 5 * p.H + 3) // 4 * 4 - (planes * p.H + 3) // 4 * 4)

@@ -95,6 +95,42 @@ def test_backward_varlen(variant):
             assert e <= TOL["bf16"], (i, n, e)
 
 
+def test_backward_varlen_gdn():
+    import torch
+    import paper_2602_01744_amd as sla
+
+    H, dk, dv = 3, 64, 128
+    d, cu = pack(GDN, "bf16", LENGTHS, H, dk, dv, seed=1420)
+    B, T = len(LENGTHS), int(cu[-1])
+    s0 = si.initial_state(B, H, dk, dv, seed=17)
+    cot = si.cotangents(1, T, H, dk, dv, seed=1421)
+    dsf = si.initial_state(B, H, dk, dv, seed=18)
+    g, _ = to_device(d, "bf16", GDN)
+    sq = lambda t: None if t is None else t[0].contiguous()
+    res = sla.backward_gdn_varlen(sq(g["q"]), sq(g["k"]), sq(g["v"]), sq(g["q_logits"]), sq(g["k_logits"]),
+                                  sq(g["log_decay"]), sq(g["beta"]),
+                                  torch.from_numpy(cot["d_out"][0]).to(torch.bfloat16).cuda(),
+                                  torch.from_numpy(cu).cuda(), torch.from_numpy(s0).cuda(), torch.from_numpy(dsf).cuda(),
+                                  want_d_initial_state=True)
+    torch.cuda.synchronize()
+    got = {n: None if t is None else t.float().cpu().numpy().astype(np.float64) for n, t in res.items()}
+    names = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_head_logits": "dq_logits", "dk_head_logits": "dk_logits",
+             "dlog_decay": "dlog_decay", "dbeta": "dbeta"}
+    for i in range(B):
+        ds, a, b = seq(d, GDN, cu, i)
+        if b == a:
+            assert np.array_equal(got["d_initial_state"][i], dsf[i].astype(np.float64))
+            continue
+        ref = ob.backward(GDN, ds["q"], ds["k"], ds["v"], ds["q_logits"], ds["k_logits"], ds["log_decay"],
+                          cot["d_out"][:, a:b], s0[i:i + 1], dsf[i:i + 1], beta=ds["beta"])
+        errs = {n: rel_err(got[n][a:b], ref[rn][0]) for n, rn in names.items()}
+        errs["d_initial_state"] = rel_err(got["d_initial_state"][i], ref["dinitial_state"][0])
+        print(f"[varlen backward] gdn seq {i} len {b - a}: " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()),
+              flush=True)
+        for n, e in errs.items():
+            assert e <= TOL["bf16"], (i, n, e)
+
+
 def test_varlen_equals_batch_for_equal_lengths():
     """A pack of equal-length sequences is the rectangular batch: the two entry points agree bit for bit."""
     import torch
