@@ -78,6 +78,7 @@ struct BArgs {
     bool head_major;         // q, k, v, d_out, the GLA decay and their gradients are [B,H,T,d] instead of [B,T,H,d]
     int sweeps;              // which of the three sweeps to launch: 1 = dq, 2 = dv, 4 = dk (all: 7)
     bool dv_state_only;      // the dv sweep writes d_initial_state but not dv (pre-pass of the segment schedule)
+    int skip_every;          // > 0: the dv sweep skips every sequence whose index is a multiple of it
 };
 
 __device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
@@ -917,6 +918,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     const int wg = logical_workgroup(NSL, a.B * a.H, a.cu != nullptr);
     if (wg < 0) return;
     const int slice = wg % NSL, bh = wg / NSL, b = bh / a.H, h = bh % a.H;
+    if (a.skip_every > 0 && b % a.skip_every == 0) return;  // pre-pass: the first segment of a row is not needed
     const int sbase = slice * kCols;
     const int H = a.H;
     int T = a.T;                    // tokens of this sequence and the index of its first token
@@ -1027,21 +1029,23 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
         const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
         const uint16_t* KDp = (const uint16_t*)(buf + L::oKD);
         const uint16_t* KBp = (const uint16_t*)(buf + L::oKB);
-        // Pq[t][j] = qa_t . kd_j, kept for j <= t
-        f4 Pq = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < DK / 32; ++c) mma32(Pq, get_perm<DK>(QAp, r, g, c), get_perm<DK>(KDp, r, g, c));
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (r > 4 * g + i) Pq[i] = 0.f;
-        const s4 fp = pack4(Pq);
-        // dv'^T[n][j] = sum_d dS[d][n] kb_j[d] + sum_t dy_t[n] Pq[t][j]
         f4 Ys = {0.f, 0.f, 0.f, 0.f}, Yi = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < DK / 32; ++c)
-            mma32(Ys, join(pack4(DS[2 * c]), pack4(DS[2 * c + 1])), get_perm<DK>(KBp, r, g, c));
         const s4 fdy = get_T((const uint16_t*)(buf + L::oDYT), cb + r, g);
-        mma16(Yi, fdy, fp);
+        if (!a.dv_state_only) {  // the pre-pass of the segment schedule wants the state recurrence alone
+            // Pq[t][j] = qa_t . kd_j, kept for j <= t
+            f4 Pq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < DK / 32; ++c) mma32(Pq, get_perm<DK>(QAp, r, g, c), get_perm<DK>(KDp, r, g, c));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (r > 4 * g + i) Pq[i] = 0.f;
+            const s4 fp = pack4(Pq);
+            // dv'^T[n][j] = sum_d dS[d][n] kb_j[d] + sum_t dy_t[n] Pq[t][j]
+#pragma unroll
+            for (int c = 0; c < DK / 32; ++c)
+                mma32(Ys, join(pack4(DS[2 * c]), pack4(DS[2 * c + 1])), get_perm<DK>(KBp, r, g, c));
+            mma16(Yi, fdy, fp);
+        }
         const float gk = ((const float*)(buf + L::oGK))[r];
         const uint16_t* QAT = (const uint16_t*)(buf + L::oQAT);
         const float* AT = (const float*)(buf + L::oAT);
@@ -1280,7 +1284,7 @@ sla_params packed_segments(const sla_params& p, int nseg) {
 int launch_backward_some(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
                          const float* kl, const void* ld, const float* s0, const void* dout, const float* dsf, void* dq,
                          void* dk, void* dv, float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu,
-                         hipStream_t stream, int sweeps, bool dv_state_only);
+                         hipStream_t stream, int sweeps, bool dv_state_only, int skip_every = 0);
 
 // Few sequences (B * H * slices below the number of compute units): every batch row is cut into nseg segments of
 // seg_len tokens, which then run as B * nseg packed sequences, each with its own entry state and end cotangent:
@@ -1308,8 +1312,9 @@ int launch_backward_segments(const sla_params& p, int nseg, int seg_len, int dvw
     if (hipGetLastError() != hipSuccess) return SLA_ERR_HIP;
     int rc = launch_segment_states(p, dvw, nseg, seg_len, q, k, v, ql, kl, ld, s0, fwd, totals, stream);
     if (rc != SLA_OK) return rc;
+    // the start cotangent of a row's first segment is wanted only as the gradient of the initial state
     rc = launch_backward_some(pk, q, k, v, ql, kl, ld, nullptr, dout, seg_dsf, dq, dk, dv, dql, dkl, dld, part, ws, cu,
-                              stream, 2, true);
+                              stream, 2, true, ds0 ? 0 : nseg);
     if (rc != SLA_OK) return rc;
     const size_t n = (size_t)p.B * p.H * p.dk * (p.dv / 4);
     if (p.variant == SLA_GLA)
@@ -1335,11 +1340,12 @@ int launch_backward(const sla_params& p, const void* q, const void* k, const voi
 int launch_backward_some(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
                          const float* kl, const void* ld, const float* s0, const void* dout, const float* dsf, void* dq,
                          void* dk, void* dv, float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu,
-                         hipStream_t stream, int sweeps, bool dv_state_only) {
+                         hipStream_t stream, int sweeps, bool dv_state_only, int skip_every) {
     const size_t rows = cu ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
     BArgs a;
     a.sweeps = sweeps;
     a.dv_state_only = dv_state_only;
+    a.skip_every = skip_every;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
     a.ld = p.variant == SLA_GLA ? (const uint16_t*)ld : nullptr;
     a.ld_head = p.variant == SLA_RETNET ? (const float*)ld : nullptr;
