@@ -83,7 +83,8 @@ typedef struct {
                          from a zero entry state, a small kernel chains them through the segments' decays, the
                          main pass starts every segment from its entry state).  0 = the library chooses when a
                          workspace is given (1 when there are enough rows to fill the device); 1 = one fused
-                         pass.  The result is the same up to fp32 rounding of the chained states. */
+                         pass.  The result is the same up to fp32 rounding of the chained states.  sla_backward
+                         cuts only on request (>= 2), see there. */
 } sla_params;
 
 /*
