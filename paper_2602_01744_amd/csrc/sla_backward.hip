@@ -381,15 +381,19 @@ __device__ __forceinline__ void put_row(uint16_t* row, const float* x) {
 // (token = lane % 16), and their totals.
 template <int VAR>
 __device__ __forceinline__ void block_decay(const u4& ldx, float head_step, bool ok, float* c, float* tot) {
+    if constexpr (VAR == SLA_GLA) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        float l;
-        if constexpr (VAR == SLA_GLA)
-            l = bf_at(ldx, i) * kLog2e;  // zero outside the sequence
-        else
-            l = ok ? head_step : 0.f;
-        c[i] = row_prefix(l);
-        tot[i] = row_last(c[i]);
+        for (int i = 0; i < 8; ++i) {
+            c[i] = row_prefix(bf_at(ldx, i) * kLog2e);  // zero outside the sequence
+            tot[i] = row_last(c[i]);
+        }
+    } else {  // one decay for all columns: one scan, and the exponentials of the eight columns are common too
+        const float c0 = row_prefix(ok ? head_step : 0.f), t0 = row_last(c0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            c[i] = c0;
+            tot[i] = t0;
+        }
     }
 }
 
@@ -973,13 +977,18 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                     float c[8], tot[8];
                     block_decay<VAR>(keep(p.ld[j], ok), head_step, ok, c, tot);
                     const u4 qx = keep(p.qx[j], ok), kx = keep(p.kx[j], ok);
+                    // kb = k A / p as (k / p) A: the block's decay A is one exponential per column, which the state
+                    // update wants anyway, instead of one more per element (the quarter-rate unit is the busiest)
+                    float A[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) A[i] = ex2(tot[i]);
                     u4 qa, kd, kb;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
+                        const float kl = bf_lo(kx[i]) * ex2(-c[2 * i]), kh = bf_hi(kx[i]) * ex2(-c[2 * i + 1]);
                         qa[i] = pack2(bf_lo(qx[i]) * ex2(c[2 * i]), bf_hi(qx[i]) * ex2(c[2 * i + 1]));
-                        kd[i] = pack2(bf_lo(kx[i]) * ex2(-c[2 * i]), bf_hi(kx[i]) * ex2(-c[2 * i + 1]));
-                        kb[i] = pack2(bf_lo(kx[i]) * ex2(tot[2 * i] - c[2 * i]),
-                                      bf_hi(kx[i]) * ex2(tot[2 * i + 1] - c[2 * i + 1]));
+                        kd[i] = pack2(kl, kh);
+                        kb[i] = pack2(kl * A[2 * i], kh * A[2 * i + 1]);
                     }
                     put_perm<DK>((uint16_t*)(buf + L::oQA), t, c0 >> 3, qa);
                     put_perm<DK>((uint16_t*)(buf + L::oKD), t, c0 >> 3, kd);
@@ -987,8 +996,8 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
                     put_T((uint16_t*)(buf + L::oQAT), c0, t, qa);
                     if (t == 0) {
                         float* at = (float*)(buf + L::oAT) + c0;
-                        *(f4*)at = f4{ex2(tot[0]), ex2(tot[1]), ex2(tot[2]), ex2(tot[3])};
-                        *(f4*)(at + 4) = f4{ex2(tot[4]), ex2(tot[5]), ex2(tot[6]), ex2(tot[7])};
+                        *(f4*)at = f4{A[0], A[1], A[2], A[3]};
+                        *(f4*)(at + 4) = f4{A[4], A[5], A[6], A[7]};
                     }
                 }
                 if (m == 0 && g == 0) ((float*)(buf + L::oGK))[t] = ok ? p.gk : 0.f;
