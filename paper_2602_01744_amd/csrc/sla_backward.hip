@@ -555,6 +555,23 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
 #pragma unroll
         for (int i = 0; i < DV / 16; ++i) fvt[i] = get_T(VT, 16 * i + r, g);
         consumer_release(ring, blk);  // every operand of the block is in registers
+        // The state update first: it is what the next block waits for, and the vector work below hides its latency.
+        if constexpr (VAR == SLA_GLA) {
+            if (is_anchor(blk)) {  // the state entering this block, for the dk sweep: bf16, each lane its own tiles
+                u4* st = a.anchor + anchor_offset<DK, DV>(anchor_id(tok0, t0) * H + h, slice, wave) + lane;
+#pragma unroll
+                for (int c = 0; c < DV / 32; ++c) {
+                    const s8 x = join(pack4(ST[2 * c]), pack4(ST[2 * c + 1]));
+                    st[64 * c] = *(const u4*)&x;
+                }
+            }
+        }
+        // S^T <- S^T A + v^T kb'
+#pragma unroll
+        for (int i = 0; i < DV / 16; ++i) {
+            ST[i] = ST[i] * Ad;
+            mma16(ST[i], fvt[i], fkb);
+        }
         float dqp[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) dqp[i] = (oS[i] + oP[i]) * pt[i];
@@ -577,22 +594,6 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
 #pragma unroll
             for (int i = 0; i < 4; ++i) bs[i] = row_suffix(tok < T ? qf[i] * gq * dqp[i] : 0.f);
             if (r == 0) *(f4*)(a.bsum + (block_id(tok0, t0, b) * H + h) * DK + sbase + cb + 4 * g) = bs;
-        }
-        if constexpr (VAR == SLA_GLA) {
-            if (is_anchor(blk)) {  // the state entering this block, for the dk sweep: bf16, each lane its own tiles
-                u4* st = a.anchor + anchor_offset<DK, DV>(anchor_id(tok0, t0) * H + h, slice, wave) + lane;
-#pragma unroll
-                for (int c = 0; c < DV / 32; ++c) {
-                    const s8 x = join(pack4(ST[2 * c]), pack4(ST[2 * c + 1]));
-                    st[64 * c] = *(const u4*)&x;
-                }
-            }
-        }
-        // S^T <- S^T A + v^T kb'
-#pragma unroll
-        for (int i = 0; i < DV / 16; ++i) {
-            ST[i] = ST[i] * Ad;
-            mma16(ST[i], fvt[i], fkb);
         }
     }
 
@@ -833,6 +834,17 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
 #pragma unroll
         for (int i = 0; i < DV / 16; ++i) fdy[i] = get_T(DYT, 16 * i + r, g);
         consumer_release(ring, blk);  // every operand of the block is in registers
+        // dS^T <- dS^T A + dy^T qa.  It is what the next block waits for: issued first where nothing else is kept alive
+        // across it (RetNet: 109 -> 101 us per sweep); GLA's decay-gradient work holds too many registers for that
+        // and ran 2 us slower, so there it stays last.
+        auto update_state = [&]() {
+#pragma unroll
+            for (int i = 0; i < DV / 16; ++i) {
+                DST[i] = DST[i] * Ad;
+                mma16(DST[i], fdy[i], fqa);
+            }
+        };
+        if constexpr (VAR != SLA_GLA) update_state();
         float dkp[4], dkv[4];  // before and after the write gate
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -861,12 +873,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
             }
             if (ok) *(u2*)(a.dld + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
         }
-        // dS^T <- dS^T A + dy^T qa
-#pragma unroll
-        for (int i = 0; i < DV / 16; ++i) {
-            DST[i] = DST[i] * Ad;
-            mma16(DST[i], fdy[i], fqa);
-        }
+        if constexpr (VAR == SLA_GLA) update_state();
         if (anchored) {  // the sum over all later tokens equals rowsum(dS * S) at this boundary: take it from there
             float z = 0.f;
 #pragma unroll
