@@ -243,6 +243,109 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     return 0
 
 
+def bench_train_step(args, w, sla, si, torch, np) -> int:
+    """--train-step: a step is everything the mixer's hot path does in one training iteration: the gate logits
+    (sla_gate_logits), the forward (sla_forward) and the backward (sla_backward / sla_backward_gdn), launched back to
+    back on one stream with all buffers allocated up front."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import to_device
+
+    if w.dtype != "bf16":
+        print("bench.py: --train-step covers the bf16 workloads", file=sys.stderr)
+        return 2
+    d = si.generate(w)
+    g, tdt = to_device(d, w.dtype, w.variant)
+    dev = torch.device("cuda:0")
+    gw = si.gate_weights(w.H, w.dk, seed=w.seed + 60)
+    wq, wk = torch.from_numpy(gw["w_gq"]).to(dev), torch.from_numpy(gw["w_gk"]).to(dev)
+    dout = torch.from_numpy(si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)["d_out"]).to(torch.bfloat16).to(dev)
+    gdn = w.variant == 2
+    nseg = max(args.segments, 1) if not gdn else 1
+    pf = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 1)
+    pb = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, 0, nseg)
+    ql = torch.empty((w.B, w.T, w.H), dtype=torch.float32, device=dev)
+    kl = torch.empty_like(ql)
+    out = torch.empty_like(g["v"])
+    fin = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+    grads = [torch.empty_like(g["q"]), torch.empty_like(g["k"]), torch.empty_like(g["v"]), torch.empty_like(ql),
+             torch.empty_like(kl)]
+    dld = torch.empty_like(g["log_decay"]) if w.variant != 0 else None
+    dbeta = torch.empty_like(g["beta"]) if gdn else None
+    need = sla.sla_backward_gdn_workspace_bytes(pb) if gdn else sla.sla_backward_workspace_bytes(pb)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    st = torch.cuda.current_stream(dev).cuda_stream
+
+    def step():
+        rc = sla.sla_gate_logits(pf, ptr(g["q"]), ptr(g["k"]), ptr(wq), ptr(wk), ptr(ql), ptr(kl), st)
+        rc = rc or sla.sla_forward(pf, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]),
+                                   ptr(g["beta"]), None, ptr(out), ptr(fin), st)
+        if gdn:
+            rc = rc or sla.sla_backward_gdn(pb, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl),
+                                            ptr(g["log_decay"]), ptr(g["beta"]), None, ptr(dout), None,
+                                            *(ptr(t) for t in grads), ptr(dld), ptr(dbeta), None, ptr(ws), need, st)
+        else:
+            rc = rc or sla.sla_backward(pb, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]),
+                                        None, ptr(dout), None, *(ptr(t) for t in grads), ptr(dld), None, ptr(ws), need, st)
+        if rc != 0:
+            raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    settle = min(args.settle, 50) if gdn else args.settle
+    for _ in range(settle + args.warmup):
+        step()
+    torch.cuda.synchronize()
+    steps = min(args.steps, 50) if gdn else args.steps
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    call_ms = float(np.mean(per_ms))
+    ms_per_step = wall * 1e3 / steps
+    es = 2
+    abytes = (2 * w.B * w.T * w.H * (w.dk * es + 4) + 2 * w.H * w.dk * 4) + algorithmic_bytes(w) + backward_bytes(w)
+    achieved = abytes / (call_ms * 1e-3) / 1e9
+    result = {
+        "metric": f"tokens/sec SLA-{si.VARIANT_NAMES[w.variant].upper()} mixer training step (gate logits + fwd + bwd)",
+        "value": w.tokens() / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": args.warmup,
+        "settle_launches": settle,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: gate logits, forward and backward of SLA-{si.VARIANT_NAMES[w.variant].upper()} "
+                        f"B={w.B} T={w.T} H={w.H} dk={w.dk} dv={w.dv} bf16"
+                        + (f", backward in {nseg} segments per batch row" if nseg > 1 else ""),
+            "kernel": "sla_gate_logits + sla_forward + " + ("sla_backward_gdn" if gdn else "sla_backward"),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "kernel_us": call_ms * 1e3,
+            "kernel_us_min": float(np.min(per_ms)) * 1e3,
+            "algorithmic_bytes": abytes,
+            "note": "three entry points back to back; achieved = the sum of their algorithmic bytes / step time",
+        },
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def bench_prologue(args, w, sla, si, torch, np) -> int:
     """--prologue: a step is one sla_gate_logits call (both gates) over the workload's q and k."""
     sys.path.insert(0, os.path.join(ROOT, "tests"))
@@ -583,6 +686,8 @@ def main() -> int:
     ap.add_argument("--graph", type=int, default=50,
                     help="decode workloads only: steps per captured HIP graph (0 = plain launches).  A decode step "
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
+    ap.add_argument("--train-step", action="store_true",
+                    help="time gate logits + forward + backward of the workload, back to back")
     ap.add_argument("--backward", action="store_true",
                     help="time sla_backward (RetNet / GLA) or sla_backward_gdn (--workload gdn) instead of the forward")
     ap.add_argument("--flush-mb", type=int, default=0,
@@ -625,6 +730,8 @@ def main() -> int:
         return bench_decode(args, w, sla, si, torch, np)
     if args.backward:
         return bench_backward(args, w, sla, si, torch, np)
+    if args.train_step:
+        return bench_train_step(args, w, sla, si, torch, np)
     if args.prologue:
         return bench_prologue(args, w, sla, si, torch, np)
     if args.short_conv:
