@@ -183,7 +183,7 @@ size_t sla_backward_workspace_bytes(const sla_params* p);
 
 /*
  * Backward pass of sla_forward for the gated delta rule (Softmax-GatedDeltaNet, Sec. 5.1, with the gates of
- * Eq. 4-6): p->variant must be SLA_GDN, p->dtype SLA_BF16, p->flags 0 (else SLA_ERR_UNSUPPORTED).  Same objective
+ * Eq. 4-6): p->variant must be SLA_GDN and p->flags 0 (else SLA_ERR_UNSUPPORTED); bf16 or fp32 tensors.  Same objective
  * and conventions as sla_backward; the step differentiated is
  *     Sb = exp(log_decay_t) S_{t-1},  u = beta_t (G^K_t v_t - k_t Sb),  S_t = Sb + k_t^T u,  out_t = G^Q_t q_t S_t.
  *
@@ -197,7 +197,8 @@ size_t sla_backward_workspace_bytes(const sla_params* p);
  *                    partial sums, and three fp32 tensors the size of v, v and k that pass the delta rule's
  *                    feedback terms between the four sweeps).  Contents on entry are ignored; calls that share a
  *                    workspace must not overlap.
- * The sweeps run token by token in fp32 vector arithmetic (inputs are read as bf16, outputs rounded once).
+ * The sweeps run token by token in fp32 vector arithmetic (bf16 inputs are widened on the way in, bf16 outputs
+ * rounded once).
  * Everything is enqueued on `stream`; nothing is allocated, freed or synchronised.  Returns a status code; on error
  * nothing is launched.
  */

@@ -426,7 +426,7 @@ def backward_gdn_varlen(q, k, v, q_head_logits, k_head_logits, log_decay, beta, 
     [T,H] float32; cu_seqlens [B+1] int32 on the device; states [B,H,dk,dv].  Returns a dict as ``backward_gdn``."""
     import torch
 
-    assert q.is_cuda and q.dtype == torch.bfloat16 and q.dim() == 3
+    assert q.is_cuda and q.dtype in (torch.bfloat16, torch.float32) and q.dim() == 3
     T, H, dk = q.shape
     dv = v.shape[-1]
     B = cu_seqlens.numel() - 1
@@ -442,7 +442,7 @@ def backward_gdn_varlen(q, k, v, q_head_logits, k_head_logits, log_decay, beta, 
         "dbeta": torch.empty_like(beta),
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(GDN, BF16, B, T, H, dk, dv, 0, 0, 1)
+    params = SlaParams(GDN, BF16 if q.dtype == torch.bfloat16 else F32, B, T, H, dk, dv, 0, 0, 1)
     need = sla_backward_gdn_varlen_workspace_bytes(params)
     workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     ptr = lambda t: None if t is None else t.data_ptr()
@@ -459,13 +459,13 @@ def backward_gdn_varlen(q, k, v, q_head_logits, k_head_logits, log_decay, beta, 
 
 def backward_gdn(q, k, v, q_head_logits, k_head_logits, log_decay, beta, d_out, initial_state=None,
                  d_final_state=None, *, want_d_initial_state: bool = False, workspace=None):
-    """Gradients of ``forward(GDN, ...)`` (bfloat16 q, k, v, d_out [B,T,H,d]; float32 logits, log_decay and beta
+    """Gradients of ``forward(GDN, ...)`` (bfloat16 or float32 q, k, v, d_out [B,T,H,d]; float32 logits, log_decay and beta
     [B,T,H]) on the current CUDA(HIP) device and stream.  Returns a dict of new tensors: dq, dk, dv,
     dq_head_logits, dk_head_logits (None without k_head_logits), dlog_decay, dbeta and d_initial_state (None unless
     asked for)."""
     import torch
 
-    assert q.is_cuda and q.dtype == torch.bfloat16
+    assert q.is_cuda and q.dtype in (torch.bfloat16, torch.float32)
     B, T, H, dk = q.shape
     dv = v.shape[-1]
     for t, shape, dt in ((q, (B, T, H, dk), q.dtype), (k, (B, T, H, dk), q.dtype), (v, (B, T, H, dv), q.dtype),
@@ -485,7 +485,7 @@ def backward_gdn(q, k, v, q_head_logits, k_head_logits, log_decay, beta, d_out, 
         "dbeta": torch.empty_like(beta),
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(GDN, BF16, B, T, H, dk, dv, 0, 0, 1)
+    params = SlaParams(GDN, BF16 if q.dtype == torch.bfloat16 else F32, B, T, H, dk, dv, 0, 0, 1)
     need = sla_backward_gdn_workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)

@@ -291,7 +291,7 @@ static int backward_gdn_impl(const sla_params* p, const void* q, const void* k, 
                              float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant != SLA_GDN || p->dtype != SLA_BF16 || p->flags != 0) return SLA_ERR_UNSUPPORTED;
+    if (p->variant != SLA_GDN || p->flags != 0) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !beta || !d_out || !dq || !dk || !dv ||
             !dq_head_logits || !dlog_decay || !dbeta)
@@ -337,12 +337,12 @@ int sla_backward_gdn_varlen(const sla_params* p, const void* q, const void* k, c
 }
 
 size_t sla_backward_gdn_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dtype != SLA_BF16) return 0;
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN) return 0;
     return sla::backward_gdn_workspace_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_gdn_varlen_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dtype != SLA_BF16) return 0;
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN) return 0;
     return sla::backward_gdn_workspace_floats(*p, true) * sizeof(float);
 }
 

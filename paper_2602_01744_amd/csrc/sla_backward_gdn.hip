@@ -1,4 +1,4 @@
-// Backward pass of the gated delta rule with SLA's head gates (Softmax-GatedDeltaNet, Sec. 5.1), bf16 tensors.
+// Backward pass of the gated delta rule with SLA's head gates (Softmax-GatedDeltaNet, Sec. 5.1), bf16 or fp32 tensors.
 //
 // Forward step, per head, with a scalar decay a_t = exp(log_decay_t) and write strength beta_t:
 //     Sb = a_t S_{t-1}      res_t = G^K_t v_t - k_t Sb      u_t = beta_t res_t      S_t = Sb + k_t^T u_t
@@ -56,19 +56,19 @@ constexpr int kEw = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct GArgs {
-    const uint16_t* q;      // [B,T,H,dk]
-    const uint16_t* k;
-    const uint16_t* v;      // [B,T,H,dv]
-    const uint16_t* dout;
+    const void* q;          // [B,T,H,dk], bf16 or fp32 (the kernels' element type E)
+    const void* k;
+    const void* v;          // [B,T,H,dv]
+    const void* dout;
     const float* ld;        // [B,T,H]
     const float* beta;
     const float* gq;        // gates [B,T,H]
     const float* gk;
     const float* s0;        // [B,H,dk,dv] or null
     const float* dsf;
-    uint16_t* dq;
-    uint16_t* dk;
-    uint16_t* dv;
+    void* dq;
+    void* dk;
+    void* dv;
     float* ds0;
     float* res;             // [B,T,H,dv] fp32: G^K v - k Sb
     float* w;               // [B,T,H,dv] fp32: beta * (k X)
@@ -190,6 +190,13 @@ struct RegsF {
         }
     }
 };
+// Staging registers for a tensor of element type E (uint16_t: bf16, float), and a store of two adjacent outputs.
+template <class E, int NC> struct PickRegs { typedef RegsB<NC> type; };
+template <int NC> struct PickRegs<float, NC> { typedef RegsF<NC> type; };
+template <class E, int NC> using RegsIn = typename PickRegs<E, NC>::type;
+__device__ __forceinline__ void store2(uint16_t* p, float lo, float hi) { *(uint32_t*)p = pack2(lo, hi); }
+__device__ __forceinline__ void store2(float* p, float lo, float hi) { *(fc*)p = fc{lo, hi}; }
+
 // Per-token scalars {a, beta, G^Q, G^K, F, 1/F, R, 1/R}; a token past the end leaves every state unchanged (a = 1,
 // the gates and beta 0).  The sweeps keep their state tile divided by a running decay product so that the decay costs
 // no multiplication per tile element: inside a group of kNorm tokens a forward sweep holds S / F_t with
@@ -263,7 +270,7 @@ __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
 // ------------------------------------------------------------------------------------------------------------
 // Sweep 1: forward in time, S[dk rows, value columns] -> res, partial dG^Q, <d_final, S_T>.
 // ------------------------------------------------------------------------------------------------------------
-template <int DK, int DV>
+template <class E, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) {
     constexpr int RT = DK / 16;
     constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
@@ -275,16 +282,16 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
         const int lt = me.tid - 64 * kWaves;
-        const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK;
-        const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK;
-        const uint16_t* vb = a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
-        const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const E* kb = (const E*)a.k + (me.tok0 * H + me.h) * DK;
+        const E* qb = (const E*)a.q + (me.tok0 * H + me.h) * DK;
+        const E* vb = (const E*)a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const E* db = (const E*)a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
         for (int c = 0; c <= nch; ++c) {
             if (c < nch) {
                 const int t0 = c * kChunk;
                 float* buf = lds + (c & 1) * kBuf;
-                RegsB<DK> rk, rq;
-                RegsB<kSlice> rv, rd;
+                RegsIn<E, DK> rk, rq;
+                RegsIn<E, kSlice> rv, rd;
                 RegsS rs;
                 rk.load(kb, sk, t0, T, lt); rq.load(qb, sk, t0, T, lt);
                 rv.load(vb, sv, t0, T, lt); rd.load(db, sv, t0, T, lt);
@@ -371,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
 // ------------------------------------------------------------------------------------------------------------
 // Sweep 2: backward in time, X[dk rows, value columns] -> w, dv, partial dG^K and dbeta, d_initial_state.
 // ------------------------------------------------------------------------------------------------------------
-template <int DK, int DV>
+template <class E, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs a) {
     constexpr int RT = DK / 16;
     constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
@@ -383,17 +390,17 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {  // step c of the sweep covers tokens (nch - 1 - c) * 16 ...
         const int lt = me.tid - 64 * kWaves;
-        const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK;
-        const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK;
-        const uint16_t* vb = a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
-        const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const E* kb = (const E*)a.k + (me.tok0 * H + me.h) * DK;
+        const E* qb = (const E*)a.q + (me.tok0 * H + me.h) * DK;
+        const E* vb = (const E*)a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
+        const E* db = (const E*)a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
         const float* rb = a.res + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
         for (int c = 0; c <= nch; ++c) {
             if (c < nch) {
                 const int t0 = (nch - 1 - c) * kChunk;
                 float* buf = lds + (c & 1) * kBuf;
-                RegsB<DK> rk, rq;
-                RegsB<kSlice> rv, rd;
+                RegsIn<E, DK> rk, rq;
+                RegsIn<E, kSlice> rv, rd;
                 RegsF<kSlice> rr;
                 RegsS rs;
                 rk.load(kb, sk, t0, T, lt); rq.load(qb, sk, t0, T, lt);
@@ -466,7 +473,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
                 }
                 if (me.rg == 0) {
                     *(fc*)(a.w + row * DV + me.col) = w;
-                    *(uint32_t*)(a.dv + row * DV + me.col) = pack2(gk * w[0], gk * w[1]);
+                    store2((E*)a.dv + row * DV + me.col, gk * w[0], gk * w[1]);
                 }
             }
         }
@@ -485,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
 //   FWD = true  (sweep 4, forward in time):   pk = w S^T;     S^T = a S^T + u^T k;   dq = G^Q dout S^T;
 //                                             dk = dk1 - a pk
 // ------------------------------------------------------------------------------------------------------------
-template <int DK, int DV, bool FWD>
+template <class E, int DK, int DV, bool FWD>
 __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     constexpr int RT = DV / 16;
     constexpr int oDO = 0, oR = oDO + kChunk * DV, oW = oR + kChunk * DV, oK = oW + kChunk * DV,
@@ -498,19 +505,19 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
         const int lt = me.tid - 64 * kWaves;
-        const uint16_t* db = a.dout + (me.tok0 * H + me.h) * DV;
+        const E* db = (const E*)a.dout + (me.tok0 * H + me.h) * DV;
         const float* rb = a.res + (me.tok0 * H + me.h) * DV;
         const float* wb = a.w + (me.tok0 * H + me.h) * DV;
-        const uint16_t* kb = a.k + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
-        const uint16_t* qb = a.q + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
+        const E* kb = (const E*)a.k + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
+        const E* qb = (const E*)a.q + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
         const float* d1 = a.dk1 + (me.tok0 * H + me.h) * DK + me.slice * kSlice;
         for (int c = 0; c <= nch; ++c) {
             if (c < nch) {
                 const int t0 = (FWD ? c : nch - 1 - c) * kChunk;
                 float* buf = lds + (c & 1) * kBuf;
-                RegsB<DV> rd;
+                RegsIn<E, DV> rd;
                 RegsF<DV> rr, rw;
-                RegsB<kSlice> rk, rq;
+                RegsIn<E, kSlice> rk, rq;
                 RegsF<kSlice> r1;
                 RegsS rs;
                 rd.load(db, sv, t0, T, lt); rr.load(rb, sv, t0, T, lt); rw.load(wb, sv, t0, T, lt);
@@ -576,8 +583,8 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
                         for (int j = 0; j < CW; ++j) M[r][j] *= N;
                 }
                 if (t < T && me.rg == 0) {
-                    *(uint32_t*)(a.dq + row * DK + me.col) = pack2(dq[0], dq[1]);
-                    *(uint32_t*)(a.dk + row * DK + me.col) = pack2(dk[0], dk[1]);
+                    store2((E*)a.dq + row * DK + me.col, dq[0], dq[1]);
+                    store2((E*)a.dk + row * DK + me.col, dk[0], dk[1]);
                 }
             } else {
                 float d1[CW] = {};
@@ -691,7 +698,7 @@ bool allow_lds(K kernel, int lds) {
     return false;
 }
 
-template <int DK, int DV>
+template <class E, int DK, int DV>
 int launch_sweeps(const GArgs& a, hipStream_t stream) {
     constexpr int lds1 = 2 * 4 * (2 * kChunk * DK + 2 * kChunk * kSlice + kScal * kChunk);
     constexpr int lds2 = 2 * 4 * (2 * kChunk * DK + 3 * kChunk * kSlice + kScal * kChunk);
@@ -699,26 +706,26 @@ int launch_sweeps(const GArgs& a, hipStream_t stream) {
     static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024, "fits the LDS of a compute unit");
     static bool configured = false;  // once per instantiation; not a stream operation
     if (!configured) {
-        if (!allow_lds(gdn_bwd_state_kernel<DK, DV>, lds1) || !allow_lds(gdn_bwd_cotangent_kernel<DK, DV>, lds2) ||
-            !allow_lds(gdn_bwd_key_kernel<DK, DV, false>, lds3) || !allow_lds(gdn_bwd_key_kernel<DK, DV, true>, lds3))
+        if (!allow_lds(gdn_bwd_state_kernel<E, DK, DV>, lds1) || !allow_lds(gdn_bwd_cotangent_kernel<E, DK, DV>, lds2) ||
+            !allow_lds(gdn_bwd_key_kernel<E, DK, DV, false>, lds3) || !allow_lds(gdn_bwd_key_kernel<E, DK, DV, true>, lds3))
             return SLA_ERR_HIP;
         configured = true;
     }
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kThreads);
-    hipLaunchKernelGGL((gdn_bwd_state_kernel<DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds1, stream, a);
-    hipLaunchKernelGGL((gdn_bwd_cotangent_kernel<DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds2, stream, a);
-    hipLaunchKernelGGL((gdn_bwd_key_kernel<DK, DV, false>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
-    hipLaunchKernelGGL((gdn_bwd_key_kernel<DK, DV, true>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_state_kernel<E, DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds1, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_cotangent_kernel<E, DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds2, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_key_kernel<E, DK, DV, false>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_key_kernel<E, DK, DV, true>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
-template <int DK>
+template <class E, int DK>
 int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
     switch (dv) {
-        case 64: return launch_sweeps<DK, 64>(a, stream);
-        case 128: return launch_sweeps<DK, 128>(a, stream);
-        case 256: return launch_sweeps<DK, 256>(a, stream);
+        case 64: return launch_sweeps<E, DK, 64>(a, stream);
+        case 128: return launch_sweeps<E, DK, 128>(a, stream);
+        case 256: return launch_sweeps<E, DK, 256>(a, stream);
         default: return SLA_ERR_UNSUPPORTED;
     }
 }
@@ -750,9 +757,9 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
         return SLA_OK;
     }
     GArgs a;
-    a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
+    a.q = q; a.k = k; a.v = v; a.dout = dout;
     a.ld = ld; a.beta = beta; a.s0 = s0; a.dsf = dsf;
-    a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv; a.ds0 = ds0;
+    a.dq = dq; a.dk = dk; a.dv = dv; a.ds0 = ds0;
     float* w = ws;
     float* gq = w; w += n;
     float* gk = w; w += n;
@@ -772,7 +779,10 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
 
     int rc = launch_bwd_gates(ql, kl, gq, gk, rows, p.H, stream);
     if (rc != SLA_OK) return rc;
-    rc = p.dk == 64 ? launch_dv<64>(a, p.dv, stream) : launch_dv<128>(a, p.dv, stream);
+    if (p.dtype == SLA_BF16)
+        rc = p.dk == 64 ? launch_dv<uint16_t, 64>(a, p.dv, stream) : launch_dv<uint16_t, 128>(a, p.dv, stream);
+    else
+        rc = p.dk == 64 ? launch_dv<float, 64>(a, p.dv, stream) : launch_dv<float, 128>(a, p.dv, stream);
     if (rc != SLA_OK) return rc;
     const unsigned per = kEw / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
     hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, planes, dql, kl ? dkl : nullptr,

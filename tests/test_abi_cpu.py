@@ -266,7 +266,7 @@ def test_backward_gdn_rejects_bad_calls(lib):
 
     assert call(None) == -1
     assert call(_ok_params(variant=sla.GLA)) == -3 and call(_ok_params(variant=sla.RETNET)) == -3
-    assert call(_ok_params(variant=sla.GDN, dtype=sla.F32)) == -3
+    assert call(_ok_params(variant=sla.GDN, dtype=sla.F32), ws_bytes=16) == -6    # fp32 tensors are covered too
     assert call(_ok_params(variant=sla.GDN, flags=1)) == -3
     assert call(ok, q=0) == -1 and call(ok, ld=0) == -1 and call(ok, beta=0) == -1
     assert call(ok, dld=0) == -1 and call(ok, dbeta=0) == -1
@@ -286,7 +286,7 @@ def test_backward_gdn_workspace_size(lib):
     # two fp32 tensors like v and one like k
     assert got == 4 * (n * (3 + 3 * planes) + planes * B * H + 2 * n * dv + n * dk)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
-    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32)) == 0
+    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv)) == got
 
 
 def test_backward_segment_schedule_workspace_and_validation(lib):

@@ -17,22 +17,22 @@ NAMES = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_head_logits": "dq_logits", "dk_
 TIGHT = {"dq_head_logits": 1e-4, "dk_head_logits": 1e-4, "dlog_decay": 1e-4, "dbeta": 1e-4, "d_initial_state": 1e-4}
 
 
-def run_backward_gdn(d, cot, s0=None, want_ds0=False):
+def run_backward_gdn(d, cot, s0=None, want_ds0=False, dtype="bf16"):
     import torch
     import paper_2602_01744_amd as sla
 
-    g, _ = to_device(d, "bf16", GDN)
+    g, tdt = to_device(d, dtype, GDN)
     dev = torch.device("cuda:0")
     up = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
     res = sla.backward_gdn(g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], g["beta"],
-                           up(cot["d_out"], torch.bfloat16), up(s0, torch.float32),
+                           up(cot["d_out"], tdt), up(s0, torch.float32),
                            up(cot["d_final_state"], torch.float32), want_d_initial_state=want_ds0)
     torch.cuda.synchronize()
     return {n: None if t is None else t.to(torch.float32).cpu().numpy().astype(np.float64) for n, t in res.items()}
 
 
-def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=None):
-    got = run_backward_gdn(d, cot, s0, want_ds0)
+def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=None, dtype="bf16"):
+    got = run_backward_gdn(d, cot, s0, want_ds0, dtype)
     rows = slice(None) if batch_rows is None else batch_rows
     sub = lambda a: None if a is None else a[rows]
     ref = ob.backward(GDN, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
@@ -50,7 +50,7 @@ def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=Non
         errs[n] = rel_err(x, r)
     print(f"[gdn backward parity] {label} " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
     for n, e in errs.items():
-        assert e <= TOL["bf16"], f"{label}: {n} error {e:.3e} > {TOL['bf16']}"
+        assert e <= TOL[dtype], f"{label}: {n} error {e:.3e} > {TOL[dtype]}"
         if n in TIGHT:
             assert e <= TIGHT[n], f"{label}: {n} error {e:.3e} > {TIGHT[n]} (fp32 output)"
     return got, ref
@@ -118,6 +118,16 @@ def test_strong_decay_domain():
     d["log_decay"] = (-5.0 * r.random(size=d["log_decay"].shape)).astype(np.float32)
     d["log_decay"][:, 40:48] = -20.0
     check_backward_gdn(d, cot, s0=s0, want_ds0=True, label="decay in [-5, 0], eight tokens at -20")
+
+
+@pytest.mark.parametrize("dk,dv,T", [(128, 128, 203), (64, 256, 77), (128, 64, 16)])
+def test_fp32_tensors(dk, dv, T):
+    """fp32 q, k, v, d_out and gradients: every output to the fp32 bar (1e-4)."""
+    B, H = 2, 3
+    d = si.custom(GDN, "f32", B=B, T=T, H=H, dk=dk, dv=dv, seed=1180 + T)
+    cot = si.cotangents(B, T, H, dk, dv, seed=1181 + T, dtype="f32", final_state=True)
+    s0 = si.initial_state(B, H, dk, dv, seed=1182 + T)
+    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"fp32 dk={dk} dv={dv} T={T}", dtype="f32")
 
 
 def test_long_sequence():
