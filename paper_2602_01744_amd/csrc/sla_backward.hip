@@ -69,7 +69,7 @@ struct BArgs {
     float* ds0;
     float* part_q;           // [dk/16][B,T,H] partial dG^Q
     float* part_k;           // [dk/16][B,T,H] partial dG^K
-    float* bsum;             // [blocks][H][dk] fp32: sum of q * dq over each 16-token block (GLA); block id below
+    float* bsum;             // [blocks][H][dk] fp32: per 16-token block, sum of q * (dq - bf16(dq)) (GLA); block id below
     float* corr;             // [B,H,dk] rowsum(dS_T * S_T) (GLA with a final-state cotangent)
     u4* anchor;              // [anchors][H] states (dk x dv, bf16) entering every kAnchor-th block (GLA); layout below
     int B, T, H;
@@ -588,11 +588,16 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
             *(u2*)(a.dq + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dqv[0], dqv[1]), pack2(dqv[2], dqv[3])};
         }
         if constexpr (VAR == SLA_GLA) {
-            // sum of q * dq over the block (fp32, from the unrounded dq): the dk sweep needs it exactly for the
-            // running sum behind dlog_decay, and takes the per-token values from the bf16 dq
+            // The dk sweep forms q * dq per token from the bf16 dq it reads back, but the running sum behind
+            // dlog_decay must advance by the block's exact sum: leave the difference, the block's sum of
+            // q * (dq - bf16(dq)) in fp32 (the product of two bf16 values is exact in fp32, so the dk sweep's
+            // per-token values add up to exactly the other part).
             f4 bs;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) bs[i] = row_suffix(tok < T ? qf[i] * gq * dqp[i] : 0.f);
+            for (int i = 0; i < 4; ++i) {
+                const float exact = gq * dqp[i], rounded = i & 1 ? bf_hi(pack2(0.f, exact)) : bf_lo(pack2(exact, 0.f));
+                bs[i] = row_suffix(tok < T ? qf[i] * (exact - rounded) : 0.f);
+            }
             if (r == 0) *(f4*)(a.bsum + (block_id(tok0, t0, b) * H + h) * DK + sbase + cb + 4 * g) = bs;
         }
     }
@@ -692,7 +697,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                 },
                 [&](int I, const PreKeysE& p, unsigned char* buf) {
                     const bool ok = (nb - 1 - I) * kTok + t < T;
-                    if constexpr (VAR == SLA_GLA) {  // q * dq per token from the bf16 dq; the block's exact sums
+                    if constexpr (VAR == SLA_GLA) {  // q * dq per token from the bf16 dq; the block's correction to the exact sum
                         float* qd = (float*)(buf + L::oQDQ) + t * kFS + 8 * g;
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
@@ -862,14 +867,15 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
             *(u2*)(a.dk + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
         }
         if constexpr (VAR == SLA_GLA) {
-            // dlog_decay_t = sum_{s >= t} (q_s dq_s - k_s dk_s): inside the block from the staged per-token values,
-            // beyond it from the running sum, which advances by the block's exact q * dq sum
+            // dlog_decay_t = sum_{s >= t} (q_s dq_s - k_s dk_s): inside the block one suffix scan of the per-token
+            // differences, beyond it the running sum, which advances by the block's total plus the dq sweep's
+            // correction of the bf16-derived q * dq values to their exact sum
             float dl[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float sq = row_suffix(e[i]), sk = row_suffix(kf[i] * dkv[i]);
-                dl[i] = sq - sk + run[i];
-                run[i] += bs4[i] - row_first(sk);
+                const float s = row_suffix(e[i] - kf[i] * dkv[i]);
+                dl[i] = s + run[i];
+                run[i] += bs4[i] + row_first(s);
             }
             if (ok) *(u2*)(a.dld + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
         }
