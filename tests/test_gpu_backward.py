@@ -172,4 +172,11 @@ def test_full_size(name):
     w = si.workload(name)
     d = si.generate(w)
     cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
-    check_backward(w.variant, d, cot, label=name, batch_rows=slice(0, 2))
+    got, _ = check_backward(w.variant, d, cot, label=name, batch_rows=slice(0, 2))
+    # properties that hold for every batch row, whatever the size: all values finite, and the logit gradients of a
+    # token sum to zero over the heads (Eq. 4's softmax)
+    for n, x in got.items():
+        assert x is None or np.all(np.isfinite(x)), n
+    for n in ("dq_head_logits", "dk_head_logits"):
+        scale = np.max(np.abs(got[n]))
+        assert np.max(np.abs(got[n].sum(axis=-1))) <= 1e-5 * scale * w.H, n

@@ -140,4 +140,8 @@ def test_full_size():
     w = si.workload("gdn")
     d = si.generate(w)
     cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
-    check_backward_gdn(d, cot, label="gdn", batch_rows=slice(0, 1))
+    got, _ = check_backward_gdn(d, cot, label="gdn", batch_rows=slice(0, 1))
+    for n, x in got.items():  # every batch row: finite, and logit gradients summing to zero over the heads
+        assert x is None or np.all(np.isfinite(x)), n
+    for n in ("dq_head_logits", "dk_head_logits"):
+        assert np.max(np.abs(got[n].sum(axis=-1))) <= 1e-5 * np.max(np.abs(got[n])) * w.H, n
