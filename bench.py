@@ -106,8 +106,11 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             g[n] = g[n].permute(0, 2, 1, 3).contiguous()
         dout = dout.permute(0, 2, 1, 3).contiguous()
     gdn = w.variant == 2
-    nseg = max(args.segments, 1) if not (gdn or hm) else 1  # the backward cuts rows into segments only on request
-    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, sla.FLAG_HEAD_MAJOR if hm else 0, nseg)
+    params = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, sla.FLAG_HEAD_MAJOR if hm else 0, 1)
+    # the backward cuts rows into segments only when told to; --segments 0 (the default) takes the library's advice
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    nseg = 1 if (gdn or hm) else (args.segments if args.segments > 0 else max(sla.sla_backward_segments(params, cus), 1))
+    params.segments = nseg
     need = sla.sla_backward_gdn_workspace_bytes(params) if gdn else sla.sla_backward_workspace_bytes(params)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     gr = {
@@ -260,8 +263,9 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
     wq, wk = torch.from_numpy(gw["w_gq"]).to(dev), torch.from_numpy(gw["w_gk"]).to(dev)
     dout = torch.from_numpy(si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)["d_out"]).to(torch.bfloat16).to(dev)
     gdn = w.variant == 2
-    nseg = max(args.segments, 1) if not gdn else 1
     pf = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 1)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    nseg = 1 if gdn else (args.segments if args.segments > 0 else max(sla.sla_backward_segments(pf, cus), 1))
     pb = sla.SlaParams(w.variant, 1, w.B, w.T, w.H, w.dk, w.dv, 0, 0, nseg)
     ql = torch.empty((w.B, w.T, w.H), dtype=torch.float32, device=dev)
     kl = torch.empty_like(ql)

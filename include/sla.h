@@ -290,6 +290,14 @@ size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 int sla_segments(const sla_params* p, int compute_units);
 
 /*
+ * Number of segments to put into p->segments for sla_backward on a device with that many compute units (>= 1; 1 when
+ * the single pass already gives every compute unit a workgroup, or for the delta rule); <0 on error.  The narrowest
+ * of the three sweeps runs B * H * min(dk, dv) / 64 workgroups per segment.  sla_backward itself never chooses:
+ * its workspace size must not depend on the device.
+ */
+int sla_backward_segments(const sla_params* p, int compute_units);
+
+/*
  * Validates the same arguments as sla_forward (host-side checks only, touches no
  * device and launches nothing).  Returns what sla_forward would return before
  * its first HIP call.

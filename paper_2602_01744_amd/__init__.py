@@ -33,6 +33,7 @@ from .binding import (  # noqa: F401
     sla_backward_varlen,
     sla_backward_varlen_workspace_bytes,
     sla_segments,
+    sla_backward_segments,
     sla_workspace_bytes,
     sla_kernel_name,
     sla_status_string,

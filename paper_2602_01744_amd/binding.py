@@ -90,6 +90,8 @@ def load_library():
     lib.sla_workspace_bytes.argtypes = [pp, ctypes.c_int]
     lib.sla_segments.restype = ctypes.c_int
     lib.sla_segments.argtypes = [pp, ctypes.c_int]
+    lib.sla_backward_segments.restype = ctypes.c_int
+    lib.sla_backward_segments.argtypes = [pp, ctypes.c_int]
     lib.sla_check_args.restype = ctypes.c_int
     lib.sla_check_args.argtypes = [pp] + [vp] * 10
     lib.sla_default_dv_split.restype = ctypes.c_int
@@ -126,6 +128,11 @@ def sla_workspace_bytes(params: SlaParams, compute_units: int) -> int:
 
 def sla_segments(params: SlaParams, compute_units: int) -> int:
     return int(load_library().sla_segments(ctypes.byref(params), int(compute_units)))
+
+
+def sla_backward_segments(params: SlaParams, compute_units: int) -> int:
+    pr = ctypes.byref(params) if params is not None else None
+    return int(load_library().sla_backward_segments(pr, int(compute_units)))
 
 
 def sla_kernel_name(params: SlaParams) -> Optional[str]:
@@ -339,7 +346,8 @@ def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_o
     """Gradients of ``forward`` (RetNet, GLA; bfloat16) on the current CUDA(HIP) device and stream.  Returns a dict
     of new tensors: dq, dk, dv, dq_head_logits, dk_head_logits (None without k_head_logits), dlog_decay (GLA only,
     else None) and d_initial_state (None unless asked for).  ``segments`` >= 2 cuts every batch row into that many
-    segments that run in parallel (for batches with few sequences)."""
+    segments that run in parallel (for batches with few sequences); 0 asks ``sla_backward_segments`` for the count
+    that fills this device."""
     import torch
 
     assert q.is_cuda and q.dtype == torch.bfloat16
@@ -366,7 +374,10 @@ def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_o
         "dlog_decay": torch.empty_like(log_decay) if variant == GLA else None,
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, FLAG_HEAD_MAJOR if head_major else 0, int(segments))
+    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, FLAG_HEAD_MAJOR if head_major else 0, max(int(segments), 1))
+    if int(segments) == 0:
+        cus = torch.cuda.get_device_properties(q.device).multi_processor_count
+        params.segments = max(sla_backward_segments(params, cus), 1)
     need = sla_backward_workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)

@@ -392,6 +392,20 @@ size_t sla_workspace_bytes(const sla_params* p, int compute_units) {
     return sla::segment_workspace_floats(*p, nseg) * sizeof(float);
 }
 
+int sla_backward_segments(const sla_params* p, int compute_units) {
+    const int rc = check_params(p);
+    if (rc != SLA_OK) return rc;
+    if (compute_units <= 0) return SLA_ERR_SHAPE;
+    if (p->B == 0 || p->T == 0 || p->variant == SLA_GDN || p->flags != 0) return 1;
+    const int64_t wgs = (int64_t)p->B * p->H * ((p->dk < p->dv ? p->dk : p->dv) / 64);
+    const int want = (int)((compute_units + wgs - 1) / wgs);
+    if (want <= 1) return 1;
+    sla_params q = *p;
+    q.segments = want;
+    int seg_len = 0;
+    return choose_segments(q, 1, &seg_len);
+}
+
 int sla_segments(const sla_params* p, int compute_units) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -319,3 +319,13 @@ def test_backward_gdn_varlen_validation_and_workspace(lib):
     planes = p.dv // 8
     assert sla.sla_backward_gdn_varlen_workspace_bytes(p) == \
         sla.sla_backward_gdn_workspace_bytes(one) + 4 * ((planes * 5 * p.H + 3) // 4 * 4 - (planes * p.H + 3) // 4 * 4)
+
+
+def test_backward_segment_recommendation(lib):
+    # the narrowest sweep runs B * H * min(dk, dv) / 64 workgroups per segment
+    assert sla.sla_backward_segments(_ok_params(B=8, T=2048, H=16, dk=128, dv=128), 256) == 1     # 256 workgroups
+    assert sla.sla_backward_segments(_ok_params(B=8, T=4096, H=4, dk=128, dv=256), 256) == 4      # 64
+    assert sla.sla_backward_segments(_ok_params(B=8, T=4096, H=8, dk=64, dv=128), 256) == 4       # 64
+    assert sla.sla_backward_segments(_ok_params(B=1, T=512, H=2, dk=64, dv=64), 256) == 2         # segments >= 256 tokens
+    assert sla.sla_backward_segments(_ok_params(variant=sla.GDN, B=1, T=4096, H=2), 256) == 1
+    assert sla.sla_backward_segments(_ok_params(), 0) == -2 and sla.sla_backward_segments(None, 256) == -1

@@ -158,6 +158,20 @@ def test_segment_schedule(variant, T, segments, states):
     check_backward(variant, d, cot, s0=s0, want_ds0=True, label=f"T={T} in {segments} segments", segments=segments)
 
 
+def test_segment_count_chosen_for_the_device():
+    """segments = 0 in the binding asks sla_backward_segments: few sequences, so the rows are cut."""
+    import torch
+    import paper_2602_01744_amd as sla
+
+    B, T, H, dk, dv = 1, 1500, 2, 64, 128
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert sla.sla_backward_segments(sla.SlaParams(GLA, sla.BF16, B, T, H, dk, dv, 0, 0, 1), cus) > 1
+    d = si.custom(GLA, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=995)
+    cot = si.cotangents(B, T, H, dk, dv, seed=996, final_state=True)
+    check_backward(GLA, d, cot, s0=si.initial_state(B, H, dk, dv, seed=997), want_ds0=True,
+                   label="segments chosen by the library", segments=0)
+
+
 def test_segment_schedule_on_the_paper_shape():
     """gla_paper_h4 (B=8, T=4096, H=4, dk=128, dv=256: 32 sequences) in 4 segments; the oracle runs on one row."""
     w = si.workload("gla_paper_h4")
