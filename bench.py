@@ -33,6 +33,7 @@ MEASURED_TRAFFIC_BYTES = {
     "decode_gdn": 135.7e6,    # same file
     "gla_train:backward": 1.369e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
     "retnet_train:backward": 0.990e9,  # same file
+    "gdn:backward": 7.27e9,            # profiles/sla_bwd_gdn_bf16_gdn.md (seven launches; fp32 intermediates)
     "gla_train:prologue": 136.5e6,     # profiles/sla_gate_logits_bf16_gla_train.md
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
@@ -186,7 +187,7 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": gdn_flops / (call_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name + ":backward"),
             "kernel_us": call_ms * 1e3,
             "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
             "algorithmic_flops": gdn_flops,
