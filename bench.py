@@ -33,7 +33,7 @@ MEASURED_TRAFFIC_BYTES = {
     "decode_gdn": 135.7e6,    # same file
     "gla_train:backward": 1.369e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
     "retnet_train:backward": 0.990e9,  # same file
-    "gdn:backward": 7.27e9,            # profiles/sla_bwd_gdn_bf16_gdn.md (seven launches; fp32 intermediates)
+    "gdn:backward": 5.16e9,            # profiles/sla_bwd_gdn_bf16_gdn.md (seven launches; fp32 intermediates)
     "gla_train:prologue": 136.5e6,     # profiles/sla_gate_logits_bf16_gla_train.md
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published

@@ -251,8 +251,28 @@ __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
     w.lane = w.tid & 63;
     w.rg = w.lane & 15;
     w.cg = w.lane >> 4;
-    w.slice = blockIdx.x % nslices;
-    w.bh = blockIdx.x / nslices;
+    // blockIdx.x % 8 is the XCD a workgroup lands on; the slices of a (sequence, head) pair go to one XCD so that
+    // the L2 they share fetches k, q, d_out and the intermediates once.  Rectangular batches: every XCD a contiguous
+    // range of pairs; packed ones: pairs dealt round-robin, which spreads the heads of one long sequence over all
+    // XCDs.  The grid is 8 * nslices * ceil(pairs / 8); the padding gets bh = -1 and leaves at once.
+    {
+        const int pairs = a.B * a.H, xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
+        int wg;
+        if (a.cu) {
+            const int pair = (place / nslices) * 8 + xcd;
+            wg = pair < pairs ? pair * nslices + place % nslices : -1;
+        } else {
+            wg = xcd * (int)(gridDim.x >> 3) + place;
+            if (wg >= pairs * nslices) wg = -1;
+        }
+        w.slice = wg < 0 ? 0 : wg % nslices;
+        w.bh = wg < 0 ? -1 : wg / nslices;
+    }
+    if (w.bh < 0) {
+        w.b = w.h = w.col = w.lcol = w.T = 0;
+        w.tok0 = 0;
+        return w;
+    }
     w.b = w.bh / a.H;
     w.h = w.bh % a.H;
     w.col = w.slice * kSlice + (w.wave & (kWaves - 1)) * 4 * CW + w.cg * CW;
@@ -278,6 +298,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
+    if (me.bh < 0) return;
     const int T = me.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
@@ -386,6 +407,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_cotangent_kernel(const GArgs
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
+    if (me.bh < 0) return;
     const int T = me.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {  // step c of the sweep covers tokens (nch - 1 - c) * 16 ...
@@ -501,6 +523,7 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DK / kSlice);
+    if (me.bh < 0) return;
     const int T = me.T, H = a.H, nch = (T + kChunk - 1) / kChunk;
     const size_t sk = (size_t)H * DK, sv = (size_t)H * DV;
     if (me.wave >= kWaves) {
@@ -713,10 +736,11 @@ int launch_sweeps(const GArgs& a, hipStream_t stream) {
     }
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kThreads);
-    hipLaunchKernelGGL((gdn_bwd_state_kernel<E, DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds1, stream, a);
-    hipLaunchKernelGGL((gdn_bwd_cotangent_kernel<E, DK, DV>), dim3(bh * (DV / kSlice)), block, (size_t)lds2, stream, a);
-    hipLaunchKernelGGL((gdn_bwd_key_kernel<E, DK, DV, false>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
-    hipLaunchKernelGGL((gdn_bwd_key_kernel<E, DK, DV, true>), dim3(bh * (DK / kSlice)), block, (size_t)lds3, stream, a);
+    auto grid = [bh](unsigned slices) { return dim3(((bh + 7u) / 8u) * 8u * slices); };  // see where()
+    hipLaunchKernelGGL((gdn_bwd_state_kernel<E, DK, DV>), grid(DV / kSlice), block, (size_t)lds1, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_cotangent_kernel<E, DK, DV>), grid(DV / kSlice), block, (size_t)lds2, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_key_kernel<E, DK, DV, false>), grid(DK / kSlice), block, (size_t)lds3, stream, a);
+    hipLaunchKernelGGL((gdn_bwd_key_kernel<E, DK, DV, true>), grid(DK / kSlice), block, (size_t)lds3, stream, a);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
