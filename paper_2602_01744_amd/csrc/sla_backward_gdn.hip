@@ -15,11 +15,11 @@
 // Once they are known every state recurrence is linear, so the pass is four sweeps that each carry one state tile in
 // registers, token by token, in plain fp32 vector arithmetic (the feedback makes tokens of a block depend on each
 // other; no matrix-core block form is used here):
-//   1. state sweep, forward in time, state tile [dk rows, 8 value columns] per wave: res_t, partial dG^Q,
-//      <d_final, S_T>;
+//   1. state sweep, forward in time, state tile [dk rows, 8 value columns] per wave: res_t;
 //   2. cotangent sweep, backward in time, same tile shape: w_t, dv, partial dG^K and dbeta, d_initial_state;
 //   3. key sweep, backward in time, tile [dv rows, 8 key columns] of X^T: the first part of dk, X_t u_t;
-//   4. query sweep, forward in time, tile [dv rows, 8 key columns] of S^T: dq, and dk completed.
+//   4. query sweep, forward in time, tile [dv rows, 8 key columns] of S^T: dq, partial dG^Q, dk completed,
+//      <d_final, S_T>.
 // A finishing kernel sums the partial planes, takes the gate gradients through the head softmax of Eq. 4 and writes
 // dbeta; a scan kernel forms dlog_decay.
 //
@@ -73,10 +73,10 @@ struct GArgs {
     float* res;             // [B,T,H,dv] fp32: G^K v - k Sb
     float* w;               // [B,T,H,dv] fp32: beta * (k X)
     float* dk1;             // [B,T,H,dk] fp32: X u
-    float* part_q;          // [dv/8][plane]: partial dout . (q S)
+    float* part_q;          // [dk/8][plane]: partial q . (dout S^T)
     float* part_k;          // [dv/8][plane]: partial beta du . v
     float* part_b;          // [dv/8][plane]: partial du . res
-    float* corr;            // [dv/8][B*H]: partial <d_final, S_T>
+    float* corr;            // [dk/8][B*H]: partial <d_final, S_T>
     size_t plane;           // floats between partial planes (>= rows * H)
     size_t rows;            // tokens in all: B * T, or the packed total T
     const int* cu;          // packed batch: sequence b is tokens cu[b] .. cu[b+1]-1 of the T in all; else null
@@ -288,13 +288,12 @@ __device__ __forceinline__ Where where(const GArgs& a, int nslices) {
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// Sweep 1: forward in time, S[dk rows, value columns] -> res, partial dG^Q, <d_final, S_T>.
+// Sweep 1: forward in time, S[dk rows, value columns] -> res.
 // ------------------------------------------------------------------------------------------------------------
 template <class E, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) {
     constexpr int RT = DK / 16;
-    constexpr int oK = 0, oQ = oK + kChunk * DK, oV = oQ + kChunk * DK, oDO = oV + kChunk * kSlice,
-                  oSC = oDO + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
+    constexpr int oK = 0, oV = oK + kChunk * DK, oSC = oV + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DV / kSlice);
@@ -304,21 +303,19 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
     if (me.wave >= kWaves) {
         const int lt = me.tid - 64 * kWaves;
         const E* kb = (const E*)a.k + (me.tok0 * H + me.h) * DK;
-        const E* qb = (const E*)a.q + (me.tok0 * H + me.h) * DK;
         const E* vb = (const E*)a.v + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
-        const E* db = (const E*)a.dout + (me.tok0 * H + me.h) * DV + me.slice * kSlice;
         for (int c = 0; c <= nch; ++c) {
             if (c < nch) {
                 const int t0 = c * kChunk;
                 float* buf = lds + (c & 1) * kBuf;
-                RegsIn<E, DK> rk, rq;
-                RegsIn<E, kSlice> rv, rd;
+                RegsIn<E, DK> rk;
+                RegsIn<E, kSlice> rv;
                 RegsS rs;
-                rk.load(kb, sk, t0, T, lt); rq.load(qb, sk, t0, T, lt);
-                rv.load(vb, sv, t0, T, lt); rd.load(db, sv, t0, T, lt);
+                rk.load(kb, sk, t0, T, lt);
+                rv.load(vb, sv, t0, T, lt);
                 rs.load(a, me.tok0, me.h, t0, T, lt);
-                rk.put_rows(buf + oK, t0, T, lt); rq.put_rows(buf + oQ, t0, T, lt);
-                rv.put(buf + oV, t0, T, lt); rd.put(buf + oDO, t0, T, lt);
+                rk.put_rows(buf + oK, t0, T, lt);
+                rv.put(buf + oV, t0, T, lt);
                 rs.put(buf + oSC, t0, T, lt);
             }
             __syncthreads();
@@ -339,11 +336,9 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
         for (int i = 0; i < kChunk; ++i) {
             const f4 sc = *(const f4*)(buf + oSC + kScal * i), sn = *(const f4*)(buf + oSC + kScal * i + 4);
             const float be = sc[1], gk = sc[3], F = sn[0], Fi = sn[1];  // M holds S / F
-            float kf[RT], qf[RT];
+            float kf[RT];
             get_rows<RT>(kf, buf + oK + i * DK + me.rg * 4);
-            get_rows<RT>(qf, buf + oQ + i * DK + me.rg * 4);
             const fc vv = *(const fc*)(buf + oV + i * kSlice + me.lcol);
-            const fc dd = *(const fc*)(buf + oDO + i * kSlice + me.lcol);
             float p[CW] = {};
 #pragma unroll
             for (int r = 0; r < RT; ++r)
@@ -356,18 +351,10 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
                 res[j] = gk * vv[j] - F * row_all(p[j]);  // k Sb = a k S_{t-1} = F_t k (S_{t-1} / F_{t-1})
                 u[j] = be * res[j] * Fi;
             }
-            float y[CW] = {};
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < CW; ++j) {
-                    M[r][j] += kf[r] * u[j];
-                    y[j] += qf[r] * M[r][j];
-                }
-            float s = 0.f;
-#pragma unroll
-            for (int j = 0; j < CW; ++j) s += dd[j] * row_all(y[j]);
-            s = all_groups(s) * F;
+                for (int j = 0; j < CW; ++j) M[r][j] += kf[r] * u[j];
             if ((i & (kNorm - 1)) == kNorm - 1) {
 #pragma unroll
                 for (int r = 0; r < RT; ++r)
@@ -377,22 +364,10 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_state_kernel(const GArgs a) 
             const int t = c * kChunk + i;
             if (t < T) {
                 const size_t row = (me.tok0 + t) * H + me.h;
-                if (me.lane == 0) a.part_q[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = s;
                 if (me.rg == 0) *(fc*)(a.res + row * DV + me.col) = res;
             }
         }
         __syncthreads();
-    }
-    if (a.dsf) {
-        float s = 0.f;
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            const fc x = *(const fc*)(a.dsf + ((size_t)me.bh * DK + me.rg * RT + r) * DV + me.col);
-#pragma unroll
-            for (int j = 0; j < CW; ++j) s += x[j] * M[r][j];
-        }
-        s = all_groups(row_all(s));
-        if (me.lane == 0) a.corr[(size_t)(me.slice * kWaves + me.wave) * a.B * H + me.bh] = s;
     }
 }
 
@@ -519,7 +494,8 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
     constexpr int RT = DV / 16;
     constexpr int oDO = 0, oR = oDO + kChunk * DV, oW = oR + kChunk * DV, oK = oW + kChunk * DV,
                   oX = oK + kChunk * kSlice,  // sweep 3: q slice; sweep 4: dk1 slice
-        oSC = oX + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
+        oQ = oX + kChunk * kSlice,              // sweep 4: q slice (for dG^Q = q . dq')
+        oSC = oQ + kChunk * kSlice, kBuf = oSC + kScal * kChunk;
     extern __shared__ __align__(16) unsigned char smem[];
     float* lds = (float*)smem;
     const Where me = where(a, DK / kSlice);
@@ -545,13 +521,17 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
                 RegsS rs;
                 rd.load(db, sv, t0, T, lt); rr.load(rb, sv, t0, T, lt); rw.load(wb, sv, t0, T, lt);
                 rk.load(kb, sk, t0, T, lt);
+                rq.load(qb, sk, t0, T, lt);
                 if constexpr (FWD) r1.load(d1, sk, t0, T, lt);
-                else rq.load(qb, sk, t0, T, lt);
                 rs.load(a, me.tok0, me.h, t0, T, lt);
                 rd.put_rows(buf + oDO, t0, T, lt); rr.put_rows(buf + oR, t0, T, lt); rw.put_rows(buf + oW, t0, T, lt);
                 rk.put(buf + oK, t0, T, lt);
-                if constexpr (FWD) r1.put(buf + oX, t0, T, lt);
-                else rq.put(buf + oX, t0, T, lt);
+                if constexpr (FWD) {
+                    r1.put(buf + oX, t0, T, lt);
+                    rq.put(buf + oQ, t0, T, lt);
+                } else {
+                    rq.put(buf + oX, t0, T, lt);
+                }
                 rs.put(buf + oSC, t0, T, lt);
             }
             __syncthreads();
@@ -593,12 +573,17 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
                         M[r][j] += (be * Ni * rr[r]) * kf[j];
                         y[j] += dd[r] * M[r][j];
                     }
-                float dq[CW], dk[CW];
+                const fc qf = *(const fc*)(buf + oQ + lc);
+                float dq[CW], dk[CW], pq = 0.f;
 #pragma unroll
                 for (int j = 0; j < CW; ++j) {
-                    dq[j] = gq * N * row_all(y[j]);
+                    const float dqp = N * row_all(y[j]);  // before the read gate: dG^Q = q . dq'
+                    pq += qf[j] * dqp;
+                    dq[j] = gq * dqp;
                     dk[j] = xf[j] - N * row_all(pk[j]);  // a w S_{t-1}^T = F_t w (S_{t-1} / F_{t-1})^T
                 }
+                pq = all_groups(pq);
+                if (t < T && me.lane == 0) a.part_q[(size_t)(me.slice * kWaves + me.wave) * a.plane + row] = pq;
                 if ((i & (kNorm - 1)) == kNorm - 1) {
 #pragma unroll
                     for (int r = 0; r < RT; ++r)
@@ -634,14 +619,26 @@ __global__ __launch_bounds__(kThreads) void gdn_bwd_key_kernel(const GArgs a) {
         }
         __syncthreads();
     }
+    if constexpr (FWD) {
+        if (a.dsf) {  // <d_final, S_T> over this wave's key columns (the tile was multiplied out after the last token)
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < CW; ++j)
+                    s += a.dsf[((size_t)me.bh * DK + me.col + j) * DV + me.rg * RT + r] * M[r][j];
+            s = all_groups(row_all(s));
+            if (me.lane == 0) a.corr[(size_t)(me.slice * kWaves + me.wave) * a.B * a.H + me.bh] = s;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------------------
 // Finishing: sums of the partial planes; gate gradients through the head softmax (Eq. 4); dbeta; the per-token
 // scalar G^Q dG^Q - G^K dG^K whose suffix sums are dlog_decay.
 // ------------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int planes, float* dql, float* dkl,
-                                                             float* dbeta, float* e) {
+__global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int planes_q, int planes_v, float* dql,
+                                                             float* dkl, float* dbeta, float* e) {
     __shared__ float sx[kEw];
     const int H = a.H, per = kEw / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
     const size_t rows = a.rows, row = (size_t)blockIdx.x * per + lr;
@@ -649,8 +646,8 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int 
     const size_t i = ok ? row * H + h : 0;
     float dgq = 0.f, dgk = 0.f, db = 0.f, gq = 0.f, gk = 0.f;
     if (ok) {
-        for (int p = 0; p < planes; ++p) {
-            dgq += a.part_q[(size_t)p * a.plane + i];
+        for (int p = 0; p < planes_q; ++p) dgq += a.part_q[(size_t)p * a.plane + i];
+        for (int p = 0; p < planes_v; ++p) {
             dgk += a.part_k[(size_t)p * a.plane + i];
             db += a.part_b[(size_t)p * a.plane + i];
         }
@@ -723,9 +720,9 @@ bool allow_lds(K kernel, int lds) {
 
 template <class E, int DK, int DV>
 int launch_sweeps(const GArgs& a, hipStream_t stream) {
-    constexpr int lds1 = 2 * 4 * (2 * kChunk * DK + 2 * kChunk * kSlice + kScal * kChunk);
+    constexpr int lds1 = 2 * 4 * (kChunk * DK + kChunk * kSlice + kScal * kChunk);
     constexpr int lds2 = 2 * 4 * (2 * kChunk * DK + 3 * kChunk * kSlice + kScal * kChunk);
-    constexpr int lds3 = 2 * 4 * (3 * kChunk * DV + 2 * kChunk * kSlice + kScal * kChunk);
+    constexpr int lds3 = 2 * 4 * (3 * kChunk * DV + 3 * kChunk * kSlice + kScal * kChunk);
     static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024, "fits the LDS of a compute unit");
     static bool configured = false;  // once per instantiation; not a stream operation
     if (!configured) {
@@ -756,13 +753,12 @@ int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
 
 }  // namespace
 
-// Workspace, in floats: gates 2 [B,T,H]; three sets of dv/8 partial planes; the decay scalar [B,T,H];
-// dv/8 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
+// Workspace, in floats: gates 2 [B,T,H]; dk/8 partial planes of dG^Q, dv/8 each of dG^K and dbeta; the decay scalar
+// [B,T,H]; dk/8 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
 size_t backward_gdn_workspace_floats(const sla_params& p, bool packed) {
     const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
-    const size_t planes = (size_t)p.dv / (4 * CW);
-    return n * (3 + 3 * planes) + round4(planes * p.B * p.H) + 2 * round4(rows * p.H * p.dv) +
-           round4(rows * p.H * p.dk);
+    const size_t pv = (size_t)p.dv / (4 * CW), pk = (size_t)p.dk / (4 * CW);  // planes per compute wave and slice
+    return n * (3 + 2 * pv + pk) + round4(pk * p.B * p.H) + 2 * round4(rows * p.H * p.dv) + round4(rows * p.H * p.dk);
 }
 
 int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
@@ -770,7 +766,7 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
                         const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
                         float* dbeta, float* ds0, float* ws, const int* cu, hipStream_t stream) {
     const size_t rows = cu ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
-    const int planes = p.dv / (4 * CW);  // one per compute wave and slice
+    const int pv = p.dv / (4 * CW), pk = p.dk / (4 * CW);  // partial planes: one per compute wave and slice
     if (rows == 0) {
         if (ds0 && p.B > 0) {  // no tokens: the cotangent of the final state is that of the initial state
             const size_t count = (size_t)p.B * p.H * p.dk * p.dv / 4;
@@ -789,10 +785,10 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
     float* gk = w; w += n;
     float* e = w; w += n;
     a.gq = gq; a.gk = gk;
-    a.part_q = w; w += n * planes;
-    a.part_k = w; w += n * planes;
-    a.part_b = w; w += n * planes;
-    a.corr = w; w += round4((size_t)planes * p.B * p.H);
+    a.part_q = w; w += n * pk;
+    a.part_k = w; w += n * pv;
+    a.part_b = w; w += n * pv;
+    a.corr = w; w += round4((size_t)pk * p.B * p.H);
     a.res = w; w += round4(rows * p.H * p.dv);
     a.w = w; w += round4(rows * p.H * p.dv);
     a.dk1 = w;
@@ -809,10 +805,10 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
         rc = p.dk == 64 ? launch_dv<float, 64>(a, p.dv, stream) : launch_dv<float, 128>(a, p.dv, stream);
     if (rc != SLA_OK) return rc;
     const unsigned per = kEw / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
-    hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, planes, dql, kl ? dkl : nullptr,
+    hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, pk, pv, dql, kl ? dkl : nullptr,
                        dbeta, e);
     hipLaunchKernelGGL(gdn_bwd_decay_scan_kernel, dim3((unsigned)(p.B * p.H)), dim3(kEw), 0, stream, (const float*)e,
-                       dsf ? (const float*)a.corr : nullptr, planes, p.B, p.T, p.H, cu, dld);
+                       dsf ? (const float*)a.corr : nullptr, pk, p.B, p.T, p.H, cu, dld);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 

@@ -281,10 +281,10 @@ def test_backward_gdn_workspace_size(lib):
     B, T, H, dk, dv = 2, 100, 4, 128, 64
     n = B * T * H
     got = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, B=B, T=T, H=H, dk=dk, dv=dv))
-    planes = dv // 8
-    # gates and the decay scalar (3 planes), three sets of dv/8 partial planes, <d_final, S_T> partials,
-    # two fp32 tensors like v and one like k
-    assert got == 4 * (n * (3 + 3 * planes) + planes * B * H + 2 * n * dv + n * dk)
+    pv, pk = dv // 8, dk // 8
+    # gates and the decay scalar (3 planes), dk/8 partial planes of dG^Q and dv/8 each of dG^K and dbeta,
+    # <d_final, S_T> partials, two fp32 tensors like v and one like k
+    assert got == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + 2 * n * dv + n * dk)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv)) == got
 
@@ -316,7 +316,7 @@ def test_backward_gdn_varlen_validation_and_workspace(lib):
     assert call(_ok_params(variant=sla.GDN, B=0), cu=0) == 0
     # sized by the total token count p->T, not B * T
     p, one = _ok_params(variant=sla.GDN, B=5, T=1000), _ok_params(variant=sla.GDN, B=1, T=1000)
-    planes = p.dv // 8
+    planes = p.dk // 8
     assert sla.sla_backward_gdn_varlen_workspace_bytes(p) == \
         sla.sla_backward_gdn_workspace_bytes(one) + 4 * ((planes * 5 * p.H + 3) // 4 * 4 - (planes * p.H + 3) // 4 * 4)
 
