@@ -55,7 +55,8 @@ typedef enum {
     SLA_ERR_UNSUPPORTED = -3, /* variant / dtype / head dimension not built */
     SLA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
     SLA_ERR_HIP = -5,         /* the HIP runtime refused the launch (no device, bad stream, ...) */
-    SLA_ERR_WORKSPACE = -6    /* segments > 1 asked for, but no workspace or too small a one was given */
+    SLA_ERR_WORKSPACE = -6,   /* segments > 1 asked for, but no workspace or too small a one was given */
+    SLA_ERR_SCRATCH = -7      /* sla_forward_static: the schedule needs more than SLA_STATIC_SCRATCH_BYTES */
 } sla_status;
 
 /* sla_params.flags.  SLA_FLAG_HEAD_MAJOR: q, k, v, out and the GLA log_decay are laid out [B,H,T,d] instead of
@@ -123,6 +124,32 @@ int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void
                    const float* q_head_logits, const float* k_head_logits,
                    const void* log_decay, const float* beta, const float* initial_state,
                    void* out, float* final_state, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * sla_forward_ws for callers that cannot allocate device memory and have no workspace to hand in: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as sla_forward;
+ * the schedule is the one sla_forward_ws would choose with a large enough workspace (p->segments as there), and the
+ * workspace is a buffer of SLA_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the
+ * library runs on holds one copy until the process ends).  The call allocates and frees nothing.
+ *
+ * Limit: a shape whose segment schedule needs more than SLA_STATIC_SCRATCH_BYTES is rejected with SLA_ERR_SCRATCH
+ * and nothing is launched (the five benchmark shapes and the paper-shape workloads need at most 8.8 MB; shapes
+ * that run as one fused pass, the delta rule among them, need none).  Use sla_forward_ws for larger ones.
+ * All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU (different streams,
+ * different host threads) race on it and must be serialised by the caller.  Nothing in the buffer has to survive
+ * between calls and nothing in it has to start at zero; its contents after a call are undefined.
+ *
+ * sla_init resolves the buffer's device address for the current device ahead of time (optional: the first
+ * sla_forward_static on a device does the same); call it once per device before capturing a graph, so that the
+ * captured call itself only launches kernels.  Returns SLA_OK or SLA_ERR_HIP.
+ */
+#define SLA_STATIC_SCRATCH_BYTES (16u << 20)
+int sla_init(void);
+size_t sla_static_scratch_bytes(void);
+int sla_forward_static(const sla_params* p, const void* q, const void* k, const void* v,
+                       const float* q_head_logits, const float* k_head_logits,
+                       const void* log_decay, const float* beta, const float* initial_state,
+                       void* out, float* final_state, void* stream);
 
 /*
  * One recurrent decode step: Eq. 5-6 with the Sec. 5.1 recurrences for a single token per (batch, head), the

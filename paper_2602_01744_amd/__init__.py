@@ -29,6 +29,9 @@ from .binding import (  # noqa: F401
     sla_default_dv_split,
     sla_forward,
     sla_forward_ws,
+    sla_forward_static,
+    sla_init,
+    sla_static_scratch_bytes,
     sla_forward_varlen,
     sla_backward_varlen,
     sla_backward_varlen_workspace_bytes,

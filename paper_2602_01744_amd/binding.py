@@ -62,6 +62,12 @@ def load_library():
     lib.sla_forward.argtypes = [pp] + [vp] * 11
     lib.sla_forward_ws.restype = ctypes.c_int
     lib.sla_forward_ws.argtypes = [pp] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.sla_forward_static.restype = ctypes.c_int
+    lib.sla_forward_static.argtypes = [pp] + [vp] * 11
+    lib.sla_init.restype = ctypes.c_int
+    lib.sla_init.argtypes = []
+    lib.sla_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.sla_static_scratch_bytes.argtypes = []
     lib.sla_decode_step.restype = ctypes.c_int
     lib.sla_decode_step.argtypes = [pp] + [vp] * 10
     lib.sla_forward_varlen.restype = ctypes.c_int
@@ -171,6 +177,26 @@ def sla_forward_ws(params, q, k, v, q_head_logits, k_head_logits, log_decay, bet
         load_library().sla_forward_ws(
             pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta),
             _p(initial_state), _p(out), _p(final_state), _p(workspace), int(workspace_bytes), _p(stream),
+        )
+    )
+
+
+def sla_init() -> int:
+    return int(load_library().sla_init())
+
+
+def sla_static_scratch_bytes() -> int:
+    return int(load_library().sla_static_scratch_bytes())
+
+
+def sla_forward_static(params, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out,
+                       final_state, stream) -> int:
+    """Raw call of the entry point that allocates nothing (same conventions as sla_forward)."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_forward_static(
+            pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta),
+            _p(initial_state), _p(out), _p(final_state), _p(stream),
         )
     )
 

@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "sla.h"
 
 namespace sla {
@@ -34,10 +36,38 @@ int launch_decode(const sla_params& p, const void* q, const void* k, const void*
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
 
+// Library-owned scratch memory for sla_forward_static: the segment-parallel schedule's workspace for callers that
+// cannot allocate.  In host code this name is only a handle for hipGetSymbolAddress; the device address is looked
+// up once per device (static_scratch below) and that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[SLA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 101;  // 0.1.1
 constexpr int kMaxHeads = 64;
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device (every device holds its own copy at its own address); NULL if
+// the runtime refuses.  The first call on a device resolves the symbol; later calls read the table.
+void* static_scratch() {
+    static std::mutex lock;
+    static void* table[kMaxDevices] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(lock);
+    if (!table[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        table[dev] = ptr;
+    }
+    return table[dev];
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -168,6 +198,36 @@ int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void
     const int dvw = choose_dv_split(*p, cus, nseg);
     return sla::launch_forward(*p, dvw, nseg, seg_len, q, k, v, q_head_logits, k_head_logits, log_decay, beta,
                                initial_state, out, final_state, (float*)workspace, nullptr, (hipStream_t)stream);
+}
+
+int sla_init(void) { return static_scratch() ? SLA_OK : SLA_ERR_HIP; }
+
+size_t sla_static_scratch_bytes(void) { return SLA_STATIC_SCRATCH_BYTES; }
+
+int sla_forward_static(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
+                       const float* k_head_logits, const void* log_decay, const float* beta,
+                       const float* initial_state, void* out, float* final_state, void* stream) {
+    const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, out, final_state);
+    if (rc != SLA_OK) return rc;
+    if (p->B == 0) return SLA_OK;
+    if (p->T == 0 && !final_state) return SLA_OK;
+    int seg_len = p->T;
+    if (p->segments > 1) {  // an explicit request does not depend on the device: reject it before any HIP call
+        const int n = choose_segments(*p, 1, &seg_len);
+        if (sla::segment_workspace_floats(*p, n) * sizeof(float) > SLA_STATIC_SCRATCH_BYTES) return SLA_ERR_SCRATCH;
+    }
+    const int cus = device_compute_units();
+    if (cus <= 0) return SLA_ERR_HIP;
+    const int nseg = choose_segments(*p, cus, &seg_len);
+    if (sla::segment_workspace_floats(*p, nseg) * sizeof(float) > SLA_STATIC_SCRATCH_BYTES) return SLA_ERR_SCRATCH;
+    float* ws = nullptr;
+    if (nseg > 1) {
+        ws = (float*)static_scratch();
+        if (!ws) return SLA_ERR_HIP;
+    }
+    const int dvw = choose_dv_split(*p, cus, nseg);
+    return sla::launch_forward(*p, dvw, nseg, seg_len, q, k, v, q_head_logits, k_head_logits, log_decay, beta,
+                               initial_state, out, final_state, ws, nullptr, (hipStream_t)stream);
 }
 
 int sla_forward_varlen(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
@@ -449,6 +509,7 @@ const char* sla_status_string(int status) {
         case SLA_ERR_ALIGN: return "a pointer is not 16-byte aligned";
         case SLA_ERR_HIP: return "the HIP runtime refused the call";
         case SLA_ERR_WORKSPACE: return "segments requested but the workspace is missing or too small";
+        case SLA_ERR_SCRATCH: return "the schedule for this shape needs more than the library's static scratch buffer holds";
         default: return "unknown status";
     }
 }

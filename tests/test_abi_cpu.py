@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_forward_static", "sla_init", "sla_static_scratch_bytes", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert sla.sla_version() >= 100
-    for code in (0, -1, -2, -3, -4, -5, -6):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
         assert sla.sla_status_string(code)
     assert "unknown" in sla.sla_status_string(-99)
 
@@ -329,3 +329,16 @@ def test_backward_segment_recommendation(lib):
     assert sla.sla_backward_segments(_ok_params(B=1, T=512, H=2, dk=64, dv=64), 256) == 2         # segments >= 256 tokens
     assert sla.sla_backward_segments(_ok_params(variant=sla.GDN, B=1, T=4096, H=2), 256) == 1
     assert sla.sla_backward_segments(_ok_params(), 0) == -2 and sla.sla_backward_segments(None, 256) == -1
+
+
+def test_static_entry_point_validates_before_any_device_work(lib):
+    """sla_forward_static: the same host-side checks as sla_forward, and a segment request whose workspace would
+    exceed the static buffer is refused before the device is touched."""
+    assert sla.sla_static_scratch_bytes() == 16 << 20
+    assert sla.sla_forward_static(None, A, A, A, A, A, A, 0, 0, A, A, 0) == -1
+    assert sla.sla_forward_static(_ok_params(dk=96), A, A, A, A, A, A, 0, 0, A, A, 0) == -3
+    assert sla.sla_forward_static(_ok_params(), A, A + 4, A, A, A, A, 0, 0, A, A, 0) == -4
+    assert sla.sla_forward_static(_ok_params(B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
+    # 8 segments of a 64-head batch: 8 * 64 * 128 * 128 floats of entry states alone = 32 MiB > 16 MiB
+    big = _ok_params(B=4, T=8192, H=16, segments=8)
+    assert sla.sla_forward_static(big, A, A, A, A, A, A, 0, 0, A, A, 0) == -7
