@@ -9,7 +9,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsla.so")
-SOURCES = ["sla_api.hip", "sla_kernels.hip", "sla_decode.hip", "sla_backward.hip", "sla_backward_gdn.hip", "sla_prologue.hip"]
+SOURCES = ["sla_api.hip", "sla_kernels.hip", "sla_kernels_bf16.hip", "sla_kernels_f32.hip", "sla_decode.hip",
+           "sla_backward.hip", "sla_backward_gdn.hip", "sla_prologue.hip"]
+OBJ_DIR = os.path.join(_HERE, "_build")
 
 # Packed-fp32 VALU instructions are switched off for all device code (a hipcc flag; the host pass
 # prints a harmless "not a recognized feature" note).
@@ -18,16 +20,13 @@ FLAGS = [
     "-O3",
     "-std=c++17",
     "-fPIC",
-    "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
     "-I", os.path.join(_ROOT, "include"),
 ]
 
 
-def build(verbose: bool = False, extra=(), out: str = LIB) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -37,6 +36,20 @@ def build(verbose: bool = False, extra=(), out: str = LIB) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def build(verbose: bool = False, extra=(), out: str = LIB, sources=None, jobs: int = 8) -> str:
+    """Compile every source to an object (in parallel; always recompiles) and link them into the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    sources = list(sources or SOURCES)
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in sources]
+    cmds = [[hipcc] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(sources, objs)]
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(cmds)))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", out], verbose)
     return out
 
 
