@@ -218,7 +218,12 @@ struct Smem {
     static constexpr size_t oP1 = oPT + 64 * 4 * sizeof(elem);
     static constexpr size_t oBT = oP1 + sizeof(float) * kBlock;
     static constexpr size_t oTM = oBT + sizeof(float) * kBlock;
-    static constexpr size_t bytes = oTM + (VAR == SLA_GDN ? sizeof(float) * kBlock * kBlock : 0);
+    // The block's output tile [16 tokens][DVW], written by the consumer waves (each its 16 columns) and stored to
+    // global memory by the slot's producer wave as whole rows.  A row is UPR units of four elements; unit c of
+    // token t sits at position c ^ (t % UPR) of its row, which spreads both access patterns over the banks.
+    static constexpr int UPR = DVW / 4;
+    static constexpr size_t oOUT = oTM + (VAR == SLA_GDN ? sizeof(float) * kBlock * kBlock : 0);
+    static constexpr size_t bytes = oOUT + sizeof(elem) * kBlock * DVW;
     static_assert(bytes % 16 == 0, "slots keep 16-byte alignment");
     static constexpr size_t limit = 160 * 1024;
     static constexpr size_t flag_bytes = 2 * kMaxSlots * sizeof(int);  // ready[] and done[] counters
@@ -231,6 +236,46 @@ struct Smem {
     static constexpr size_t total = oFlags + flag_bytes;
     static constexpr int threads = (kWaves + slots) * 64;
 };
+
+// Output of a block.  A consumer lane holds four adjacent value columns (unit 4 cw + g) of token r and parks them
+// in the slot's output tile; the slot's producer wave later writes the tile to global memory, a whole row of the
+// slice per token, with the non-temporal hint.  Measured on the benchmark's address streams (loads as the kernel
+// issues them, no arithmetic): 32-byte pieces written by four waves at different times with ordinary stores 84 us,
+// whole 128-byte rows with streaming stores 48.5 us (reads alone: 40 us) -- written lines otherwise compete with
+// the input streams in the L2.
+template <class P, int DVW>
+__device__ __forceinline__ void park_out4(typename P::elem* tile, int r, int unit, const float (&x)[4]) {
+    constexpr int UPR = DVW / 4;
+    typename P::elem* dst = tile + (r * UPR + (unit ^ (r & (UPR - 1)))) * 4;
+    if constexpr (sizeof(typename P::elem) == 2) {
+        *(u32x2*)dst = u32x2{pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+    } else {
+        *(f32x4*)dst = f32x4{x[0], x[1], x[2], x[3]};
+    }
+}
+
+// out_row: address of column n0 of the block's first token; tstride: elements per token; nvalid: tokens of the
+// block inside the sequence.  Lane l handles unit l % UPR of tokens l / UPR, l / UPR + 64 / UPR, ...
+template <class P, int DVW>
+__device__ __forceinline__ void store_out_tile(const typename P::elem* tile, typename P::elem* out_row, size_t tstride,
+                                               int nvalid, int lane) {
+    constexpr int UPR = DVW / 4;
+    constexpr int TPI = 64 / UPR;  // tokens per store instruction
+    const int u = lane % UPR;
+#pragma unroll
+    for (int i = 0; i < kBlock / TPI; ++i) {
+        const int t = lane / UPR + TPI * i;
+        const typename P::elem* src = tile + (t * UPR + (u ^ (t & (UPR - 1)))) * 4;
+        typename P::elem* dst = out_row + (size_t)t * tstride + 4 * u;
+        if constexpr (sizeof(typename P::elem) == 2) {
+            const u32x2 w = *(const u32x2*)src;
+            if (t < nvalid) __builtin_nontemporal_store(w, (u32x2*)dst);
+        } else {
+            const f32x4 w = *(const f32x4*)src;
+            if (t < nvalid) __builtin_nontemporal_store(w, (f32x4*)dst);
+        }
+    }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Per-lane staging registers for one 16-token block (what a producer wave works on).
@@ -870,8 +915,8 @@ __device__ __forceinline__ void flag_signal(lds_int* f, int) {
 // store.  cur holds every LDS operand of the block (requested a block earlier), so nothing in here
 // waits for LDS and the whole block is one scheduling region.
 template <class P, int VAR, int DK, int DVW, bool SO>
-__device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFrags<P, VAR, DK>& cur, bool in_range,
-                                              typename P::elem* out_ptr) {
+__device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFrags<P, VAR, DK>& cur,
+                                              typename P::elem* out_tile, int r, int unit) {
     typedef typename P::frag frag;
     constexpr int NTILE = DK / 16;
 
@@ -928,12 +973,12 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
         P::mma16_only(S[s], cur.fk[s], fv2);
     }
 
-    // epilogue: read gate, cast, store 4 adjacent value columns of token t
+    // epilogue: read gate, cast, park 4 adjacent value columns of token t in the slot's output tile
     if constexpr (!SO) {
         float o[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[i] = (VAR != SLA_GLA ? oS[i] * p_t + oP[i] : oS[i] + oP[i]) * cur.gq;
-        if (in_range) store_run<P, 4>(out_ptr, o);
+        park_out4<P, DVW>(out_tile, r, unit, o);
     }
 }
 
@@ -1012,12 +1057,30 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
 #pragma unroll
         for (int e = 0; e < DK / 64; ++e) dacc[e] = 1.f;
         unsigned char* buf = smem + (size_t)pw * L::bytes;
-        for (int I = pw, use = 0; I < nblocks; I += NP, ++use) {
-            flag_wait(done + pw, NCW * use);  // the consumers have finished the block that was here
+        // The slot's output tile goes to global memory from here: column n0 of the row's first token.
+        const size_t out_tstride = a.head_major ? (size_t)dv : (size_t)H * dv;
+        const size_t out_tok = a.head_major ? ((row_tok / a.T) * H + h) * a.T + row_tok % a.T : row_tok * H + h;
+        [[maybe_unused]] elem* out_row = (elem*)a.out + out_tok * dv + n0;
+        [[maybe_unused]] const elem* tile = (const elem*)(buf + L::oOUT);
+        int use = 0;
+        for (int I = pw; I < nblocks; I += NP, ++use) {
+            flag_wait(done + pw, NCW * use);  // the consumers have finished the block that was here ...
+            if constexpr (!SO) {                // ... and left its output in the slot: store it
+                if (use > 0)
+                    store_out_tile<P, DVW>(tile, out_row + (size_t)(kBlock * (I - NP)) * out_tstride, out_tstride,
+                                           T - kBlock * (I - NP), lane);
+            }
             ldr.advance(kBlock * NP);          // every staging register is refilled for block I + NP
             produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, 0, kBlock * I, kBlock * (I + NP), T, decay_const, dacc,
                                                    lane);
             flag_signal(ready + pw, lane);
+        }
+        if constexpr (!SO) {  // the output of this wave's last block
+            if (use > 0) {
+                const int I = pw + NP * (use - 1);
+                flag_wait(done + pw, NCW * use);
+                store_out_tile<P, DVW>(tile, out_row + (size_t)(kBlock * I) * out_tstride, out_tstride, T - kBlock * I, lane);
+            }
         }
         if constexpr (SO && VAR == SLA_GLA) {
             float* dp = a.ws_decay + (((size_t)(b * (a.nseg - 1) + seg) * H + h) * kMaxSlots + pw) * DK + (DK / 64) * lane;
@@ -1057,28 +1120,27 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
 #pragma unroll
             for (int i = 0; i < 4; ++i) S[s][i] = s_in[(size_t)(16 * s + i) * dv];
     }
-    // this lane stores 4 adjacent value columns of token r of every block
-    const size_t out_tstride = a.head_major ? (size_t)dv : (size_t)H * dv;
-    const size_t out_tok = a.head_major ? ((row_tok / a.T) * H + h) * a.T + row_tok % a.T : row_tok * H + h;
-    elem* out_ptr = (elem*)a.out + out_tok * dv + n0 + 16 * cw + 4 * g + (size_t)r * out_tstride;
+    // this lane parks 4 adjacent value columns (unit 4 cw + g of the slice) of token r of every block
+    const int unit = 4 * cw + g;
+    auto out_tile = [&](int slot) { return (elem*)(smem + (size_t)slot * L::bytes + L::oOUT); };
     int seen = 0;
     if constexpr (L::prefetch) {
         BlockFrags<P, VAR, DK> fa, fb;
         // Block I.  On entry every LDS operand of the block has been requested (a block ago, into cur) and
-        // so has the counter of block I + 1.  Once they have landed, slot I % NP is handed back at once --
-        // the block is computed from registers -- and, block I + 1 being staged, its operands are
-        // requested into nxt together with the counter of block I + 2.  Past the last block the requests
-        // read slots that hold older data; nothing uses it.
+        // so has the counter of block I + 1.  Once they have landed -- and with them the output of block
+        // I - 1 has reached its slot's tile -- slot (I - 1) % NP is handed back to its producer; block I is
+        // computed from registers, and, block I + 1 being staged, its operands are requested into nxt
+        // together with the counter of block I + 2.  Past the last block the requests read slots that
+        // hold older data; nothing uses it.
         auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
             const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            flag_signal_now(done + sl);
+            if (I > 0) flag_signal_now(done + ((I - 1) & (NP - 1)));
             if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
             asm volatile("" ::: "memory");
             load_block_frags<P, VAR, DK, DVW, SO>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
             seen = flag_peek(ready + sl2);
-            consume_block<P, VAR, DK, DVW, SO>(S, cur, kBlock * I + r < T, out_ptr);
-            out_ptr += (size_t)kBlock * out_tstride;
+            consume_block<P, VAR, DK, DVW, SO>(S, cur, out_tile(sl), r, unit);
         };
         if (nblocks > 0) flag_wait(ready, 1);
         load_block_frags<P, VAR, DK, DVW, SO>(fa, smem, cw, lane);
@@ -1086,6 +1148,10 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         for (int I = 0; I < nblocks; I += 2) {
             step(I, fa, fb);
             if (I + 1 < nblocks) step(I + 1, fb, fa);
+        }
+        if (nblocks > 0) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            flag_signal_now(done + ((nblocks - 1) & (NP - 1)));
         }
     } else {
         // Delta rule: two full sets of operand registers would cost the registers that eight producer waves
@@ -1100,8 +1166,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             load_block_frags<P, VAR, DK, DVW, SO, 2>(cur, smem + (size_t)sl * L::bytes, cw, lane);
             load_block_frags<P, VAR, DK, DVW, SO, 1>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
             seen = flag_peek(ready + sl2);
-            consume_block<P, VAR, DK, DVW, SO>(S, cur, kBlock * I + r < T, out_ptr);
-            out_ptr += (size_t)kBlock * out_tstride;
+            consume_block<P, VAR, DK, DVW, SO>(S, cur, out_tile(sl), r, unit);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             flag_signal_now(done + sl);
         };
