@@ -29,7 +29,9 @@
  * Domain: every log-decay must be <= 0; for GLA each must also be >= -5
  * (the blocked evaluation divides keys by the decay accumulated inside a block of
  * 16 tokens; below e^-5 per token that quotient leaves the fp32 range and results
- * may be inf/NaN).  RetNet and GDN take any decay <= 0.
+ * may be inf/NaN).  RetNet and GDN take any decay <= 0.  A GLA block whose
+ * accumulated decay falls below e^-80 is reported: the kernels set
+ * SLA_DEVICE_DECAY_RANGE in the device status word (sla_device_status).
  * NaN or infinite inputs propagate to the outputs; they are not trapped.
  */
 #ifndef SLA_H_
@@ -74,8 +76,8 @@ typedef struct {
     int32_t H;       /* heads                 1..64 */
     int32_t dk;      /* key/query head width  64 or 128 */
     int32_t dv;      /* value head width      64, 128 or 256 */
-    int32_t dv_split; /* 0 = let the library choose; else value columns per workgroup: 16, 32, 64 or 128 (<= dv).
-                        A scheduling knob only: the result does not depend on it beyond nothing at all
+    int32_t dv_split; /* 0 = let the library choose; else value columns per workgroup: 16, 32 or 64 (<= dv).
+                        A scheduling knob only: results are bit-identical for every width
                         (each output column is computed by exactly one workgroup in a fixed order). */
     int32_t flags;   /* 0, or SLA_FLAG_HEAD_MAJOR for sla_forward / sla_forward_ws / sla_backward (every other entry
                         point: 0) */
@@ -116,7 +118,7 @@ int sla_forward(const sla_params* p, const void* q, const void* k, const void* v
 /*
  * sla_forward with a workspace (device memory, 16-byte aligned, owned by the caller, contents undefined on
  * return), which lets the library use the segment-parallel schedule described at sla_params.segments: the
- * sequential state carry of Sec. 3.2 ("passing the recurrent state between chunks") becomes a two-level scan.
+ * sequential state carry between chunks of Sec. 3.2 (Chunkwise Parallel Training) becomes a two-level scan.
  * workspace may be NULL (then this is sla_forward).  With p->segments == 0 a workspace that is too small makes
  * the call fall back to one fused pass; with p->segments > 1 it is SLA_ERR_WORKSPACE.
  */
@@ -153,7 +155,8 @@ int sla_forward_static(const sla_params* p, const void* q, const void* k, const 
 
 /*
  * One recurrent decode step: Eq. 5-6 with the Sec. 5.1 recurrences for a single token per (batch, head), the
- * constant-memory inference form of Appendix A ("Recurrent Form"; Sec. 5.7 "Inference latency").  Exactly
+ * constant-memory inference form (Sec. 3.2, Recurrent Implementation; Appendix A, Derivation of Recurrent
+ * Implementation; decode latency is what Sec. 5.7, Training Efficiency, reports for it).  Exactly
  * sla_forward for T = 1 with initial_state = final_state = state, as one streaming read-modify-write of the
  * state.  p->T must be 1; dv_split and segments are ignored.
  *
@@ -171,7 +174,7 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
 
 /*
  * Backward pass of sla_forward for the RetNet and GLA recurrences (Sec. 5.1) with the gates of Eq. 4-6: the
- * gradients that training through the chunkwise form of Sec. 3.2 ("Chunkwise Parallel Form") needs.  With the
+ * gradients that training through the chunkwise form of Sec. 3.2 (Chunkwise Parallel Training) needs.  With the
  * scalar objective L = sum(out * d_out) + sum(final_state * d_final_state) it writes dL/d(input) for every
  * differentiable input of the forward call made with the same p, q, k, v, logits, log_decay and initial_state.
  * bf16 tensors only (p->dtype == SLA_BF16); the delta rule has its own entry point, sla_backward_gdn.
@@ -341,6 +344,22 @@ int sla_default_dv_split(const sla_params* p, int compute_units);
 /* Name of the device kernel that sla_forward launches for *p (static string, host memory); NULL on error.
  * Lets a profiler summary be matched to a call. */
 const char* sla_kernel_name(const sla_params* p);
+
+/*
+ * Device status word: things a kernel noticed that no return code can carry, because every entry point returns
+ * before its kernels run.  One sticky word per GPU, OR-ed into by the kernels of every call on that GPU:
+ *   SLA_DEVICE_WAIT_EXPIRED  a producer/consumer hand-over inside a workgroup gave up waiting (each wait is bounded
+ *                            so that no wave can hang).  It cannot happen in a correct run; if it is ever set, the
+ *                            outputs of the calls since the last reset are invalid.
+ *   SLA_DEVICE_DECAY_RANGE   a GLA forward saw a 16-token block whose accumulated decay is below e^-80 (a log-decay
+ *                            under the documented -5 per token, or a NaN): results may hold inf/NaN.
+ * sla_device_status copies the word of the current device to *status (host memory) after waiting for `stream`, and
+ * clears it when `reset` is non-zero.  It synchronises the stream: not for use under graph capture.  Returns SLA_OK,
+ * SLA_ERR_NULL or SLA_ERR_HIP.
+ */
+#define SLA_DEVICE_WAIT_EXPIRED 1u
+#define SLA_DEVICE_DECAY_RANGE 2u
+int sla_device_status(uint32_t* status, int reset, void* stream);
 
 /* Human-readable text for a status code (static string, host memory). */
 const char* sla_status_string(int status);

@@ -3,7 +3,7 @@
 TEST INFRASTRUCTURE ONLY: the GPU library never imports this module and shares no code with it.
 
 The training objective reaches the mixer only through its outputs, so the backward pass of the
-chunkwise form of Sec. 3.2 ("Chunkwise Parallel Form") is, by definition, the derivative of the
+chunkwise form of Sec. 3.2 (Chunkwise Parallel Training) is, by definition, the derivative of the
 recurrence of Eq. 5-6.  ``backward`` is that derivative taken the plain way: reverse-mode
 differentiation of the token-by-token recurrence, one token at a time, in the order the recurrence
 was run.  With the scalar objective

@@ -31,6 +31,9 @@ from .binding import (  # noqa: F401
     sla_forward_ws,
     sla_forward_static,
     sla_init,
+    sla_device_status,
+    DEVICE_WAIT_EXPIRED,
+    DEVICE_DECAY_RANGE,
     sla_static_scratch_bytes,
     sla_forward_varlen,
     sla_backward_varlen,

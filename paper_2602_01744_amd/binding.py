@@ -64,6 +64,8 @@ def load_library():
     lib.sla_forward_ws.argtypes = [pp] + [vp] * 11 + [ctypes.c_size_t, vp]
     lib.sla_forward_static.restype = ctypes.c_int
     lib.sla_forward_static.argtypes = [pp] + [vp] * 11
+    lib.sla_device_status.restype = ctypes.c_int
+    lib.sla_device_status.argtypes = [ctypes.POINTER(ctypes.c_uint32), ctypes.c_int, vp]
     lib.sla_init.restype = ctypes.c_int
     lib.sla_init.argtypes = []
     lib.sla_static_scratch_bytes.restype = ctypes.c_size_t
@@ -183,6 +185,16 @@ def sla_forward_ws(params, q, k, v, q_head_logits, k_head_logits, log_decay, bet
 
 def sla_init() -> int:
     return int(load_library().sla_init())
+
+
+DEVICE_WAIT_EXPIRED, DEVICE_DECAY_RANGE = 1, 2
+
+
+def sla_device_status(reset: bool = False, stream=None):
+    """Returns (status code, device status word) of the current device; waits for ``stream`` first."""
+    word = ctypes.c_uint32(0)
+    rc = int(load_library().sla_device_status(ctypes.byref(word), int(bool(reset)), _p(stream)))
+    return rc, int(word.value)
 
 
 def sla_static_scratch_bytes() -> int:

@@ -32,6 +32,7 @@ int launch_gate_logits(const sla_params& p, const void* q, const void* k, const 
                        float* kl, int compute_units, hipStream_t stream);
 int launch_short_conv_silu(int dtype, int B, int T, int C, int taps, const void* x, const float* w, void* y,
                            hipStream_t stream);
+unsigned int* device_status_word();
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
@@ -41,32 +42,50 @@ int launch_decode(const sla_params& p, const void* q, const void* k, const void*
 // up once per device (static_scratch below) and that pointer is what the kernels receive.
 static __device__ __align__(256) unsigned char scratch[SLA_STATIC_SCRATCH_BYTES];
 
+// Sticky status word of the device (bits SLA_DEVICE_*), written by the kernels of the other translation units
+// through the pointer that device_status_word() hands to their launchers.
+static __device__ unsigned int device_status;
+
 namespace {
 
-constexpr int kVersion = 101;  // 0.1.1
+constexpr int kVersion = 102;  // 0.1.2
 constexpr int kMaxHeads = 64;
 constexpr int kMaxDevices = 64;
 
-// Device address of `scratch` on the current device (every device holds its own copy at its own address); NULL if
-// the runtime refuses.  The first call on a device resolves the symbol; later calls read the table.
-void* static_scratch() {
-    static std::mutex lock;
-    static void* table[kMaxDevices] = {nullptr};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    std::lock_guard<std::mutex> hold(lock);
-    if (!table[dev]) {
-        void* ptr = nullptr;
-        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+// Device address of a __device__ symbol of this file on the current device (every device holds its own copy at its
+// own address); NULL if the runtime refuses.  The first call on a device resolves the symbol; later calls read the
+// table.
+struct SymbolTable {
+    std::mutex lock;
+    void* addr[kMaxDevices] = {nullptr};
+    template <typename Resolve>
+    void* get(Resolve resolve) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
             (void)hipGetLastError();
             return nullptr;
         }
-        table[dev] = ptr;
+        std::lock_guard<std::mutex> hold(lock);
+        if (!addr[dev]) {
+            void* ptr = nullptr;
+            if (resolve(&ptr) != hipSuccess || !ptr) {
+                (void)hipGetLastError();
+                return nullptr;
+            }
+            addr[dev] = ptr;
+        }
+        return addr[dev];
     }
-    return table[dev];
+};
+
+void* static_scratch() {
+    static SymbolTable table;
+    return table.get([](void** ptr) { return hipGetSymbolAddress(ptr, HIP_SYMBOL(scratch)); });
+}
+
+void* status_word() {
+    static SymbolTable table;
+    return table.get([](void** ptr) { return hipGetSymbolAddress(ptr, HIP_SYMBOL(device_status)); });
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -166,6 +185,10 @@ int choose_dv_split(const sla_params& p, int cus, int nseg = 1) {
 
 }  // namespace
 
+namespace sla {
+unsigned int* device_status_word() { return (unsigned int*)status_word(); }
+}
+
 extern "C" {
 
 int sla_check_args(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
@@ -200,7 +223,30 @@ int sla_forward_ws(const sla_params* p, const void* q, const void* k, const void
                                initial_state, out, final_state, (float*)workspace, nullptr, (hipStream_t)stream);
 }
 
-int sla_init(void) { return static_scratch() ? SLA_OK : SLA_ERR_HIP; }
+int sla_init(void) { return (static_scratch() && status_word()) ? SLA_OK : SLA_ERR_HIP; }
+
+int sla_device_status(uint32_t* status, int reset, void* stream) {
+    if (!status) return SLA_ERR_NULL;
+    void* word = status_word();
+    if (!word) return SLA_ERR_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t value = 0;
+    if (hipMemcpyAsync(&value, word, sizeof(value), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        (void)hipGetLastError();
+        return SLA_ERR_HIP;
+    }
+    if (reset && value != 0) {
+        const uint32_t zero = 0;
+        if (hipMemcpyAsync(word, &zero, sizeof(zero), hipMemcpyHostToDevice, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) {
+            (void)hipGetLastError();
+            return SLA_ERR_HIP;
+        }
+    }
+    *status = value;
+    return SLA_OK;
+}
 
 size_t sla_static_scratch_bytes(void) { return SLA_STATIC_SCRATCH_BYTES; }
 

@@ -1,5 +1,5 @@
 // SLA backward pass for gfx950 (MI355X): gradients of the chunkwise forward of Sec. 3.2 ("Chunkwise Parallel
-// Form") with the head-softmax gates of Eq. 4-6, for the RetNet and GLA recurrences of Sec. 5.1.
+// Training") with the head-softmax gates of Eq. 4-6, for the RetNet and GLA recurrences of Sec. 5.1.
 //
 // With S_t = diag(alpha_t) S_{t-1} + G^K_t k_t^T v_t and out_t = G^Q_t q_t S_t, and dS_t the gradient with respect
 // to S_t (dS_t = G^Q_t q_t^T dout_t + diag(alpha_{t+1}) dS_{t+1}):
@@ -33,6 +33,8 @@
 #include "sla.h"
 
 namespace sla {
+
+unsigned int* device_status_word();  // sla_api.hip
 
 namespace {
 
@@ -79,6 +81,7 @@ struct BArgs {
     int sweeps;              // which of the three sweeps to launch: 1 = dq, 2 = dv, 4 = dk (all: 7)
     bool dv_state_only;      // the dv sweep writes d_initial_state but not dv (pre-pass of the segment schedule)
     int skip_every;          // > 0: the dv sweep skips every sequence whose index is a multiple of it
+    unsigned int* status;    // sticky device status word (SLA_DEVICE_*): a bounded wait that expired is recorded here
 };
 
 __device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
@@ -218,9 +221,10 @@ __device__ __forceinline__ size_t anchor_offset(size_t state, int slice, int wav
 constexpr int kSpinLimit = 1 << 22;
 typedef __attribute__((address_space(3))) int lds_int;
 
-__device__ __forceinline__ void flag_wait(const lds_int* f, int target) {
+__device__ __forceinline__ void flag_wait(const lds_int* f, int target, unsigned int* status) {
     int spin = 0;
     while (*(const volatile lds_int*)f < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
+    if (spin >= kSpinLimit && (threadIdx.x & 63) == 0) atomicOr(status, (unsigned int)SLA_DEVICE_WAIT_EXPIRED);
     asm volatile("" ::: "memory");
 }
 // All 64 lanes active on entry; drains the wave's LDS traffic, then lane 0 alone adds one.
@@ -237,23 +241,17 @@ __device__ __forceinline__ void flag_signal(lds_int* f) {
         : "memory");
 }
 
-// Developer switch for timing one half of a workgroup alone (results are then meaningless): 1 = the consumers
-// only pass the hand-over, 2 = the producers only load and signal.
-#ifndef SLA_BWD_EXP
-#define SLA_BWD_EXP 0
-#endif
-constexpr int kExp = SLA_BWD_EXP;
-
 struct Ring {
     lds_int* ready;
     lds_int* done;
+    unsigned int* status;  // where an expired wait is recorded
 };
 // The counters sit behind the slots; zeroed by the first eight threads before anyone uses them.
-__device__ __forceinline__ Ring ring_init(unsigned char* smem, int slot_bytes, int tid) {
+__device__ __forceinline__ Ring ring_init(unsigned char* smem, int slot_bytes, int tid, unsigned int* status) {
     lds_int* f = (lds_int*)(smem + kSlots * slot_bytes);
     if (tid < 2 * kSlots) f[tid] = 0;
     __syncthreads();
-    return Ring{f, f + kSlots};
+    return Ring{f, f + kSlots, status};
 }
 
 // One member wave of a producer team: load(block, regs) issues the global loads of a block, stage(block, regs,
@@ -269,14 +267,14 @@ __device__ __forceinline__ void producer_run(const Ring& ring, unsigned char* sm
     load(min(team + kSlots, nb - 1), rb);
     int I = team, use = 0;
     while (true) {
-        flag_wait(ring.done + team, kConsumers * use);  // the consumers have left the block that was here
-        if (kExp != 2) stage(I, ra, smem + team * slot_bytes);
+        flag_wait(ring.done + team, kConsumers * use, ring.status);  // the consumers have left the block that was here
+        stage(I, ra, smem + team * slot_bytes);
         load(min(I + 2 * kSlots, nb - 1), ra);
         flag_signal(ring.ready + team);
         I += kSlots, ++use;
         if (I >= nb) break;
-        flag_wait(ring.done + team, kConsumers * use);
-        if (kExp != 2) stage(I, rb, smem + team * slot_bytes);
+        flag_wait(ring.done + team, kConsumers * use, ring.status);
+        stage(I, rb, smem + team * slot_bytes);
         load(min(I + 2 * kSlots, nb - 1), rb);
         flag_signal(ring.ready + team);
         I += kSlots, ++use;
@@ -285,7 +283,7 @@ __device__ __forceinline__ void producer_run(const Ring& ring, unsigned char* sm
 }
 
 __device__ __forceinline__ void consumer_acquire(const Ring& ring, int I) {
-    flag_wait(ring.ready + (I & (kSlots - 1)), kTeamWaves * (I / kSlots + 1));
+    flag_wait(ring.ready + (I & (kSlots - 1)), kTeamWaves * (I / kSlots + 1), ring.status);
 }
 __device__ __forceinline__ void consumer_release(const Ring& ring, int I) { flag_signal(ring.done + (I & (kSlots - 1))); }
 
@@ -443,7 +441,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     // rows of the d-wide tensors: token tau of this sequence and head is row wide0 + tau * wstep
     const size_t wide0 = a.head_major ? (size_t)bh * a.T : tok0 * H + h, wstep = a.head_major ? 1 : H;
     const int nb = (T + kTok - 1) / kTok;
-    const Ring ring = ring_init(smem, L::bytes, tid);
+    const Ring ring = ring_init(smem, L::bytes, tid, a.status);
 
     if (wave >= kConsumers) {
         const int team = (wave - kConsumers) >> 1;
@@ -522,10 +520,6 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     }
     for (int blk = 0; blk < nb; ++blk) {
         consumer_acquire(ring, blk);
-        if (kExp == 1) {
-            consumer_release(ring, blk);
-            continue;
-        }
         const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = blk * kTok;
         const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
@@ -665,7 +659,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     // rows of the d-wide tensors: token tau of this sequence and head is row wide0 + tau * wstep
     const size_t wide0 = a.head_major ? (size_t)bh * a.T : tok0 * H + h, wstep = a.head_major ? 1 : H;
     const int nb = (T + kTok - 1) / kTok;
-    const Ring ring = ring_init(smem, L::bytes, tid);
+    const Ring ring = ring_init(smem, L::bytes, tid, a.status);
 
     if (wave >= kConsumers) {  // block number I of the sweep covers tokens (nb - 1 - I) * 16 ...
         const int team = (wave - kConsumers) >> 1;
@@ -787,10 +781,6 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     }
     for (int blk = 0; blk < nb; ++blk) {
         consumer_acquire(ring, blk);
-        if (kExp == 1) {
-            consumer_release(ring, blk);
-            continue;
-        }
         const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
         const bool anchored = VAR == SLA_GLA && is_anchor(nb - 1 - blk);
@@ -948,7 +938,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     // rows of the d-wide tensors: token tau of this sequence and head is row wide0 + tau * wstep
     const size_t wide0 = a.head_major ? (size_t)bh * a.T : tok0 * H + h, wstep = a.head_major ? 1 : H;
     const int nb = (T + kTok - 1) / kTok;
-    const Ring ring = ring_init(smem, L::bytes, tid);
+    const Ring ring = ring_init(smem, L::bytes, tid, a.status);
 
     if (wave >= kConsumers) {
         // member m: key columns m DK/2 + 8 (lane / 16) + 32 j ..., token lane % 16; member 0 also stages the slice of
@@ -1042,10 +1032,6 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     }
     for (int blk = 0; blk < nb; ++blk) {
         consumer_acquire(ring, blk);
-        if (kExp == 1) {
-            consumer_release(ring, blk);
-            continue;
-        }
         const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
         const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
@@ -1368,6 +1354,8 @@ int launch_backward_some(const sla_params& p, const void* q, const void* k, cons
     a.sweeps = sweeps;
     a.dv_state_only = dv_state_only;
     a.skip_every = skip_every;
+    a.status = device_status_word();
+    if (!a.status) return SLA_ERR_HIP;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.dout = (const uint16_t*)dout;
     a.ld = p.variant == SLA_GLA ? (const uint16_t*)ld : nullptr;
     a.ld_head = p.variant == SLA_RETNET ? (const float*)ld : nullptr;

@@ -1,5 +1,5 @@
 // SLA recurrent decode step for gfx950 (MI355X): Eq. 5-6 with the Sec. 5.1 recurrences for ONE token per
-// (batch, head), the constant-memory inference form of Appendix A ("Recurrent Form").
+// (batch, head), the constant-memory inference form (Sec. 3.2, Recurrent Implementation; derived in Appendix A).
 //
 // The step reads and rewrites the whole state, 2 * dk * dv * 4 bytes per head against O(dk * dv) flops: it is
 // HBM-bound, so the kernel is a streaming read-modify-write.  One workgroup of 256 threads per (batch, head);

@@ -41,6 +41,9 @@ struct KArgs {
     // q, k, v, out and the GLA decay laid out [B,H,T,d] instead of [B,T,H,d]: every (batch, head) streams one
     // contiguous region.  Logits, beta, the delta rule's decay and the states keep their layouts.
     bool head_major;
+    // Sticky device status word (bits of SLA_DEVICE_*): a bounded wait that expired, a GLA block decay outside the
+    // documented range.  Never null.
+    unsigned int* status;
 };
 
 }  // namespace sla

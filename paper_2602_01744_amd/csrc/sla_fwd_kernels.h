@@ -53,6 +53,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 static constexpr float kLog2e = 1.4426950408889634f;
+static constexpr float kMinBlockDecay = 1.0e-35f;  // just under e^-80 = 1.8e-35, the smallest in-range decay of a block
 static constexpr int kBlock = 16;   // tokens per state step
 static constexpr int kWaves = 4;
 static constexpr uint32_t kRsrcWord3 = 0x00020000u;  // raw buffer descriptor, 32-bit data format
@@ -697,7 +698,8 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 template <class P, int VAR, int DK, int DVW, int HG, bool SO>
 __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
                                               unsigned char* buf, int blk, int tok0, int next_tok0, int T,
-                                              float decay_const, float (&dacc)[DK / 64], int lane) {
+                                              float decay_const, float (&dacc)[DK / 64], int lane,
+                                              unsigned int* status) {
     if constexpr (VAR != SLA_GLA) {
         produce_block_scalar<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, blk, tok0, next_tok0, T, decay_const, lane);
         return;
@@ -739,12 +741,17 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         }
     }
     float invA[EPL];
+    bool in_range = true;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
         invA[e] = fast_rcp(pre[e]);
         EA[blk * DK + EPL * lane + e] = pre[e];
         if constexpr (SO) dacc[e] *= pre[e];
+        in_range = in_range && pre[e] >= kMinBlockDecay;
     }
+    // A block decay below e^-80 means a log-decay under -5 somewhere in the block (or a NaN): the quotients
+    // below may then leave the fp32 range.  The call goes on; the status word tells the caller.
+    if (!in_range) atomicOr(status, (unsigned int)SLA_DEVICE_DECAY_RANGE);
     // backward: kb_j = k_j prod_{i>j} alpha_i ; kd_j = kb_j / A
     float suf[EPL], kb[EPL][kBlock];
 #pragma unroll
@@ -871,16 +878,19 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
 // operations of a wave complete in order: once lgkmcnt has drained, everything the wave wrote is in
 // LDS and everything it read is in its registers, and the counter update that follows is ordered
 // behind them.  Every wait is bounded: the hand-over cannot deadlock (a block depends only on blocks
-// with smaller indices), and should a wait ever exhaust its budget the wave goes on rather than hang.
+// with smaller indices); should a wait ever exhaust its budget the wave records SLA_DEVICE_WAIT_EXPIRED in
+// the device status word and goes on rather than hang (the call's results are then invalid, and
+// sla_device_status tells the caller so).
 // ---------------------------------------------------------------------------------------------
 static constexpr int kSpinLimit = 1 << 22;
 typedef __attribute__((address_space(3))) int lds_int;  // the counters are addressed as LDS, never as flat memory
 
 __device__ __forceinline__ int flag_peek(const lds_int* f) { return *(const volatile lds_int*)f; }
 
-__device__ __forceinline__ void flag_wait(const lds_int* f, int target) {
+__device__ __forceinline__ void flag_wait(const lds_int* f, int target, unsigned int* status) {
     int spin = 0;
     while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
+    if (spin >= kSpinLimit && (threadIdx.x & 63) == 0) atomicOr(status, (unsigned int)SLA_DEVICE_WAIT_EXPIRED);
     asm volatile("" ::: "memory");
 }
 
@@ -1064,7 +1074,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         [[maybe_unused]] const elem* tile = (const elem*)(buf + L::oOUT);
         int use = 0;
         for (int I = pw; I < nblocks; I += NP, ++use) {
-            flag_wait(done + pw, NCW * use);  // the consumers have finished the block that was here ...
+            flag_wait(done + pw, NCW * use, a.status);  // the consumers have finished the block that was here ...
             if constexpr (!SO) {                // ... and left its output in the slot: store it
                 if (use > 0)
                     store_out_tile<P, DVW>(tile, out_row + (size_t)(kBlock * (I - NP)) * out_tstride, out_tstride,
@@ -1072,13 +1082,13 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             }
             ldr.advance(kBlock * NP);          // every staging register is refilled for block I + NP
             produce_block<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, 0, kBlock * I, kBlock * (I + NP), T, decay_const, dacc,
-                                                   lane);
+                                                   lane, a.status);
             flag_signal(ready + pw, lane);
         }
         if constexpr (!SO) {  // the output of this wave's last block
             if (use > 0) {
                 const int I = pw + NP * (use - 1);
-                flag_wait(done + pw, NCW * use);
+                flag_wait(done + pw, NCW * use, a.status);
                 store_out_tile<P, DVW>(tile, out_row + (size_t)(kBlock * I) * out_tstride, out_tstride, T - kBlock * I, lane);
             }
         }
@@ -1136,13 +1146,13 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             if (I > 0) flag_signal_now(done + ((I - 1) & (NP - 1)));
-            if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
+            if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1, a.status);
             asm volatile("" ::: "memory");
             load_block_frags<P, VAR, DK, DVW, SO>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
             seen = flag_peek(ready + sl2);
             consume_block<P, VAR, DK, DVW, SO>(S, cur, out_tile(sl), r, unit);
         };
-        if (nblocks > 0) flag_wait(ready, 1);
+        if (nblocks > 0) flag_wait(ready, 1, a.status);
         load_block_frags<P, VAR, DK, DVW, SO>(fa, smem, cw, lane);
         seen = flag_peek(ready + (1 & (NP - 1)));
         for (int I = 0; I < nblocks; I += 2) {
@@ -1161,7 +1171,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         BlockFrags<P, VAR, DK> fa, fb;
         auto step = [&](int I, BlockFrags<P, VAR, DK>& cur, BlockFrags<P, VAR, DK>& nxt) {
             const int sl = I & (NP - 1), sl1 = (I + 1) & (NP - 1), sl2 = (I + 2) & (NP - 1);
-            if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1);
+            if (I + 1 < nblocks && seen < (I + 1) / NP + 1) flag_wait(ready + sl1, (I + 1) / NP + 1, a.status);
             asm volatile("" ::: "memory");
             load_block_frags<P, VAR, DK, DVW, SO, 2>(cur, smem + (size_t)sl * L::bytes, cw, lane);
             load_block_frags<P, VAR, DK, DVW, SO, 1>(nxt, smem + (size_t)sl1 * L::bytes, cw, lane);
@@ -1170,7 +1180,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             flag_signal_now(done + sl);
         };
-        if (nblocks > 0) flag_wait(ready, 1);
+        if (nblocks > 0) flag_wait(ready, 1, a.status);
         load_block_frags<P, VAR, DK, DVW, SO, 1>(fa, smem, cw, lane);
         seen = flag_peek(ready + (1 & (NP - 1)));
         for (int I = 0; I < nblocks; I += 2) {

@@ -10,6 +10,7 @@ namespace sla {
 
 int dispatch_forward_bf16(const KArgs& a, int variant, int dk, int dvw, hipStream_t stream);
 int dispatch_forward_f32(const KArgs& a, int variant, int dk, int dvw, hipStream_t stream);
+unsigned int* device_status_word();  // sla_api.hip
 
 // T == 0: the state passes through unchanged.
 __global__ void sla_state_passthrough_kernel(const float* s0, float* sT, size_t n) {
@@ -37,6 +38,8 @@ int launch_forward(const sla_params& p, int dvw, int nseg, int seg_len, const vo
     a.ws_total = nullptr;
     a.states_only = false;
     a.cu = cu;
+    a.status = device_status_word();
+    if (!a.status) return SLA_ERR_HIP;
     if (p.T == 0) {
         if (!sT) return SLA_OK;
         const size_t n = (size_t)p.B * p.H * p.dk * p.dv;
@@ -66,6 +69,8 @@ int launch_segment_states(const sla_params& p, int dvw, int nseg, int seg_len, c
     a.ws_total = totals;
     a.states_only = true;
     a.cu = nullptr;
+    a.status = device_status_word();
+    if (!a.status) return SLA_ERR_HIP;
     if (p.dtype == SLA_BF16) return dispatch_forward_bf16(a, p.variant, p.dk, dvw, stream);
     return dispatch_forward_f32(a, p.variant, p.dk, dvw, stream);
 }

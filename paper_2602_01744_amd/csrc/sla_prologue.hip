@@ -157,10 +157,10 @@ __device__ __forceinline__ void store8(void* y, size_t off, const float* f) {
             t.y = (__bf16)f[2 * i + 1];
             v[i] = __builtin_bit_cast(uint32_t, t);
         }
-        *(pu4*)((uint16_t*)y + off) = v;
+        __builtin_nontemporal_store(v, (pu4*)((uint16_t*)y + off));
     } else {
-        *(pf4*)((float*)y + off) = pf4{f[0], f[1], f[2], f[3]};
-        *(pf4*)((float*)y + off + 4) = pf4{f[4], f[5], f[6], f[7]};
+        __builtin_nontemporal_store(pf4{f[0], f[1], f[2], f[3]}, (pf4*)((float*)y + off));
+        __builtin_nontemporal_store(pf4{f[4], f[5], f[6], f[7]}, (pf4*)((float*)y + off + 4));
     }
 }
 

@@ -67,7 +67,8 @@ def rel_err(x, ref):
 
 
 def worst_slice_err(x, ref, head_axis):
-    """Largest max-abs-error / max-abs-reference over (batch, head) slices (reported, not gated)."""
+    """Largest max-abs-error / max-abs-reference over (batch, head) slices: every head is held to the tolerance on
+    its own scale, so a head with small outputs (a low gate) cannot hide behind a loud one."""
     axes = tuple(i for i in range(ref.ndim) if i not in (0, head_axis))
     num = np.max(np.abs(x - ref), axis=axes)
     den = np.max(np.abs(ref), axis=axes)
@@ -83,8 +84,11 @@ def check(variant, d, dtype, initial_state=None, dv_split=0, tol=None, label="",
     assert np.all(np.isfinite(o)), f"{label}: non-finite output"
     assert np.all(np.isfinite(f)), f"{label}: non-finite state"
     eo, ef = rel_err(o, ro), rel_err(f, rf)
+    so, sf = worst_slice_err(o, ro, 2), worst_slice_err(f, rf, 1)
     print(f"[parity] {label} dtype={dtype} dv_split={dv_split} segments={segments} out_err={eo:.3e} state_err={ef:.3e} "
-          f"worst_head_out={worst_slice_err(o, ro, 2):.3e}", flush=True)
+          f"worst_head_out={so:.3e} worst_head_state={sf:.3e}", flush=True)
     assert eo <= tol, f"{label}: output error {eo:.3e} > {tol}"
     assert ef <= tol, f"{label}: state error {ef:.3e} > {tol}"
+    assert so <= tol, f"{label}: output error of the worst (batch, head) slice {so:.3e} > {tol}"
+    assert sf <= tol, f"{label}: state error of the worst (batch, head) slice {sf:.3e} > {tol}"
     return o, f, ro, rf

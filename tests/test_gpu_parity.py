@@ -186,3 +186,28 @@ def test_final_state_may_be_skipped_and_may_alias_initial_state():
     out2, fin2 = sla.forward(GLA, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], None, st, final_state=st)
     torch.cuda.synchronize()
     assert torch.equal(out, ref_out) and torch.equal(out2, ref_out) and torch.equal(fin2, ref_fin)
+
+
+def test_device_status_word_reports_out_of_range_decay():
+    """The sticky device status word: zero after ordinary calls (no hand-over wait ever expired), and a GLA block
+    whose accumulated decay leaves the documented range sets SLA_DEVICE_DECAY_RANGE; the reset clears it."""
+    import paper_2602_01744_amd as sla
+
+    rc, _ = sla.sla_device_status(reset=True)
+    assert rc == 0
+    for variant in VARIANTS:
+        d = si.custom(variant, "bf16", B=2, T=200, H=4, dk=128, dv=128, seed=1900 + variant)
+        run_gpu(variant, d, "bf16")
+        run_gpu(variant, d, "f32")
+    rc, word = sla.sla_device_status()
+    assert rc == 0 and word == 0, word
+    # log-decay -8 per token on a few key dimensions: 16 tokens accumulate e^-128, below e^-80
+    d = si.custom(GLA, "bf16", B=1, T=64, H=2, dk=128, dv=64, seed=1950)
+    ld = d["log_decay"].copy()
+    ld[:, :, :, :4] = -8.0
+    d["log_decay"] = si.round_to_bf16(ld)
+    run_gpu(GLA, d, "bf16")
+    rc, word = sla.sla_device_status(reset=True)
+    assert rc == 0 and word == sla.DEVICE_DECAY_RANGE, word
+    rc, word = sla.sla_device_status()
+    assert rc == 0 and word == 0, word
