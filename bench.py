@@ -21,21 +21,63 @@ sys.path.insert(0, ROOT)
 METRIC = "tokens/sec SLA-GLA chunked fwd (B=8,T=2048,H=16,d=128 bf16); % MFMA peak"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flops x 2.4 GHz)
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for a workload, calibrated
-# against a plain copy of known size in the same run (figures and commands: profiles/*.md).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "gla_train": 346.2e6,     # profiles/sla_fwd_bf16_gla_train.md
-    "retnet_train": 279.1e6,  # profiles/sla_fwd_bf16_retnet_train.md
-    "gdn": 553.8e6,           # profiles/sla_fwd_bf16_gdn.md
-    "retnet": 125.1e6,        # profiles/sla_fwd_bf16_segmented_retnet_gla_long.md (three kernels)
-    "gla_long": 4.063e9,      # same file
-    "decode_gla": 135.7e6,    # profiles/sla_decode_bf16.md
-    "decode_gdn": 135.7e6,    # same file
-    "gla_train:backward": 1.369e9,     # profiles/sla_bwd_bf16_gla_train_retnet_train.md (six launches)
-    "retnet_train:backward": 0.990e9,  # same file
-    "gdn:backward": 5.16e9,            # profiles/sla_bwd_gdn_bf16_gdn.md (seven launches; fp32 intermediates)
-    "gla_train:prologue": 136.5e6,     # profiles/sla_gate_logits_bf16_gla_train.md
-}
+
+
+def rel_err(x, ref) -> float:
+    """max|x - ref| / max|ref| (the parity gate's error measure)."""
+    import numpy as np
+
+    denom = float(np.max(np.abs(ref)))
+    if denom == 0.0:
+        return float(np.max(np.abs(x)))
+    return float(np.max(np.abs(x - ref))) / denom
+
+
+def source_digest() -> str:
+    """sha256 over the kernel sources (csrc/*, include/sla.h), in name order: what a profile summary was taken from."""
+    import hashlib
+
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_01744_amd", "csrc")
+    files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    for f in files + [os.path.join(ROOT, "include", "sla.h")]:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key: str):
+    """HBM bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and calibrated against a plain copy
+    of known size, as recorded in the summaries under profiles/ (a line `traffic-json: {...}` per summary; commands
+    and raw counters are in the same file).  Returns {"bytes", "profile", "commit", "stale"} or None.  stale = the
+    kernel sources have changed since the summary was taken."""
+    pdir = os.path.join(ROOT, "profiles")
+    best = None
+    for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not name.endswith(".md"):
+            continue
+        for line in open(os.path.join(pdir, name), encoding="utf-8"):
+            if line.startswith("traffic-json:"):
+                try:
+                    rec = json.loads(line[len("traffic-json:"):])
+                except ValueError:
+                    continue
+                if key in rec.get("bytes", {}):
+                    best = {"bytes": rec["bytes"][key], "profile": "profiles/" + name, "commit": rec.get("commit"),
+                            "stale": rec.get("sources") != source_digest()}
+    return best
+
+
+def traffic_fields(key: str) -> dict:
+    t = measured_traffic(key)
+    if t is None:
+        return {"traffic": None}
+    out = {"traffic": t["bytes"], "traffic_source": t["profile"], "traffic_commit": t["commit"]}
+    if t["stale"]:
+        out["traffic_warning"] = "kernel sources changed since this profile summary was taken"
+    return out
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 BLOCK = 16                      # tokens per state step in the kernels (for the causal flop count)
 
@@ -89,8 +131,7 @@ def backward_bytes(w) -> int:
 def bench_backward(args, w, sla, si, torch, np) -> int:
     """--backward: a step is one sla_backward call (gate evaluation, the dq / dv / dk sweeps, softmax backward)
     over the workload's batch, inputs and cotangents resident in HBM."""
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import rel_err, to_device
+    to_device = si.to_device
 
     if w.dtype != "bf16" or (w.variant == 2 and args.head_major):
         print("bench.py: --backward covers the bf16 workloads ([B,T,H,d] layout only for the delta rule)",
@@ -187,7 +228,7 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": gdn_flops / (call_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name + ":backward"),
+            **traffic_fields(w.name + ":backward"),
             "kernel_us": call_ms * 1e3,
             "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
             "algorithmic_flops": gdn_flops,
@@ -201,7 +242,7 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None if hm else MEASURED_TRAFFIC_BYTES.get(w.name + ":backward"),
+            **({"traffic": None} if hm else traffic_fields(w.name + ":backward")),
             "kernel_us": call_ms * 1e3,
             "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
             "algorithmic_bytes": abytes,
@@ -251,8 +292,7 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
     """--train-step: a step is everything the mixer's hot path does in one training iteration: the gate logits
     (sla_gate_logits), the forward (sla_forward) and the backward (sla_backward / sla_backward_gdn), launched back to
     back on one stream with all buffers allocated up front."""
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import to_device
+    to_device = si.to_device
 
     if w.dtype != "bf16":
         print("bench.py: --train-step covers the bf16 workloads", file=sys.stderr)
@@ -353,8 +393,7 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
 
 def bench_prologue(args, w, sla, si, torch, np) -> int:
     """--prologue: a step is one sla_gate_logits call (both gates) over the workload's q and k."""
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import rel_err, to_device
+    to_device = si.to_device
 
     d = si.generate(w)
     gw = si.gate_weights(w.H, w.dk, seed=w.seed + 60)
@@ -414,7 +453,7 @@ def bench_prologue(args, w, sla, si, torch, np) -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name + ":prologue"),
+            **traffic_fields(w.name + ":prologue"),
             "kernel_us": kernel_ms * 1e3,
             "kernel_us_min": float(np.min(per_ms)) * 1e3,
             "algorithmic_bytes": abytes,
@@ -455,9 +494,6 @@ def bench_prologue(args, w, sla, si, torch, np) -> int:
 def bench_short_conv(args, w, sla, si, torch, np) -> int:
     """--short-conv: a step is one sla_short_conv_silu call (4 taps) over a [B, T, H*dk] tensor of the workload's
     dtype, the shape of the query projection in front of the mixer."""
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import rel_err
-
     dev = torch.device("cuda:0")
     C, taps = w.H * w.dk, 4
     r = np.random.default_rng(w.seed + 80)
@@ -552,8 +588,7 @@ def bench_short_conv(args, w, sla, si, torch, np) -> int:
 def bench_decode(args, w, sla, si, torch, np) -> int:
     """--workload decode_*: a step is one recurrent decode step (sla_decode_step) over the batch; the state
     stays resident and is updated in place, as in serving."""
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import rel_err, to_device
+    to_device = si.to_device
 
     d = si.generate(w)
     s0 = si.initial_state(w.B, w.H, w.dk, w.dv, seed=w.seed)
@@ -652,7 +687,7 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            **traffic_fields(w.name),
             "kernel_us": kernel_ms * 1e3,
             "kernel_us_min": float(np.min(per_launch_ms)) * 1e3,
             "algorithmic_bytes": abytes,
@@ -670,6 +705,63 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
         result["parity"] = result_parity
     print(json.dumps(result), flush=True)
     return 0
+
+
+def measure_config(name, sla, si, torch, np, steps, warmup, settle):
+    """One of the benchmark definition's other configurations, timed like the headline (raw C-ABI call, HIP events
+    on the launch stream, the library's own schedule) and checked against the oracle on the full workload."""
+    import oracle
+
+    w = si.workload(name)
+    d = si.generate(w)
+    g, tdt = si.to_device(d, w.dtype, w.variant)
+    dev = torch.device("cuda:0")
+    out = torch.empty((w.B, w.T, w.H, w.dv), dtype=tdt, device=dev)
+    fin = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    params = sla.SlaParams(w.variant, 1 if w.dtype == "bf16" else 0, w.B, w.T, w.H, w.dk, w.dv, 0, 0, 0)
+    nseg = sla.sla_segments(params, cus)
+    ws_bytes = sla.sla_workspace_bytes(params, cus)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+    params.segments = nseg
+    ptr = lambda t: None if t is None else t.data_ptr()
+    raw = (ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(g["q_logits"]), ptr(g["k_logits"]), ptr(g["log_decay"]),
+           ptr(g["beta"]), None, ptr(out), ptr(fin), ptr(ws), ws_bytes, torch.cuda.current_stream(dev).cuda_stream)
+
+    def step():
+        rc = sla.sla_forward_ws(params, *raw)
+        if rc != 0:
+            raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+    for _ in range(settle + warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    call_ms = float(np.mean(per_ms))
+    abytes = algorithmic_bytes(w)
+    ro, rf = oracle.forward(w.variant, d["q"], d["k"], d["v"], d["q_logits"], d["k_logits"], d["log_decay"], d["beta"], None)
+    return {
+        "workload": f"{w.name}: SLA-{si.VARIANT_NAMES[w.variant].upper()} B={w.B} T={w.T} H={w.H} dk={w.dk} dv={w.dv} {w.dtype}",
+        "segments": nseg,
+        "launches_per_call": 1 if nseg == 1 else 3,
+        "steps": steps,
+        "ms_per_step": wall * 1e3 / steps,
+        "call_us": call_ms * 1e3,
+        "tokens_per_s": w.tokens() / (wall / steps),
+        "algorithmic_bytes": abytes,
+        "frac": abytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        **traffic_fields(w.name),
+        "out_rel_err": rel_err(out.to(torch.float32).cpu().numpy().astype(np.float64), ro),
+        "state_rel_err": rel_err(fin.cpu().numpy().astype(np.float64), rf),
+    }
 
 
 def main() -> int:
@@ -712,6 +804,8 @@ def main() -> int:
                     help="time sla_short_conv_silu (the delta-rule blocks' feature map) on a [B,T,H*dk] tensor")
     ap.add_argument("--prologue", action="store_true",
                     help="time sla_gate_logits (the projections in front of the head softmax) on the workload's q, k")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="headline run only: do not also time the benchmark definition's other four configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     args = ap.parse_args()
@@ -743,8 +837,7 @@ def main() -> int:
         return bench_short_conv(args, w, sla, si, torch, np)
     d = si.generate(w)
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import rel_err, to_device
+    to_device = si.to_device
 
     g, tdt = to_device(d, w.dtype, w.variant)
     dev = torch.device("cuda:0")
@@ -803,9 +896,19 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.settle + args.warmup):
-        step()
+    # The settle phase is timed too, so that what it hides is on record: the mean of the burst's first launches
+    # (after one untimed call, which loads the kernel's code object).
+    step()
     torch.cuda.synchronize()
+    nfirst = min(100, args.settle + args.warmup)
+    f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    f0.record()
+    for i in range(args.settle + args.warmup):
+        step()
+        if i + 1 == nfirst:
+            f1.record()
+    torch.cuda.synchronize()
+    first_burst_us = f0.elapsed_time(f1) * 1e3 / nfirst if nfirst > 0 else None
     # per-launch kernel time: HIP events on the stream the kernel is enqueued on (torch's current stream)
     if args.flush_mb > 0:
         scratch = torch.zeros(args.flush_mb * (1 << 20) // 4, dtype=torch.float32, device=dev)
@@ -875,9 +978,11 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
-            "traffic": None if (args.varlen or args.head_major) else MEASURED_TRAFFIC_BYTES.get(w.name),
+            **({"traffic": None} if (args.varlen or args.head_major) else traffic_fields(w.name)),
             "kernel_us": kernel_ms * 1e3,
             "kernel_us_min": float(np.min(per_launch_ms)) * 1e3,
+            "unsettled_first_launches_us": first_burst_us,
+            "unsettled_first_launches": nfirst,
             "algorithmic_bytes": abytes,
             "mfma_tflops_causal": aflops / (kernel_ms * 1e-3) / 1e12,
             "mfma_frac_of_bf16_peak": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
@@ -931,6 +1036,15 @@ def main() -> int:
             result["parity"] = {"out_rel_err": eo, "state_rel_err": ef,
                                 "definition": "max|x - oracle| / max|oracle| over three sequences of the pack, each "
                                               "against the oracle run on that sequence alone"}
+    plain = not (args.varlen or args.head_major or args.flush_mb or args.dv_split or args.segments)
+    if w.name == "gla_train" and plain and not args.no_configs:
+        # The other configurations of the benchmark definition (the headline is the third), each a few hundred
+        # launches: the tiny fp32 correctness shape, the two few-sequence shapes (segment schedule), the delta rule.
+        result["configs"] = {
+            n: measure_config(n, sla, si, torch, np, steps=(50 if n == "gla_long" else 200), warmup=args.warmup,
+                              settle=(50 if n == "gla_long" else 200))
+            for n in ("gla_tiny", "retnet", "gdn", "gla_long")
+        }
     print(json.dumps(result), flush=True)
     return 0
 

@@ -255,3 +255,28 @@ def packed_lengths(total: int, seed: int, longest: int = 4096, shortest: int = 6
         out.append(n)
         left -= n
     return np.array(sorted(out, reverse=True), dtype=np.int32)
+
+
+def to_device(d: Dict[str, np.ndarray], dtype: str, variant: int):
+    """The generated arrays as torch tensors on cuda:0 (marshalling only: bf16 workloads hold bf16-representable
+    values, which is asserted, so narrowing them changes nothing).  Returns (dict of tensors, torch dtype)."""
+    import torch
+
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    def t(a, narrow):
+        if a is None:
+            return None
+        x = torch.from_numpy(np.ascontiguousarray(a))
+        if narrow and dtype == "bf16":
+            y = x.to(torch.bfloat16)
+            assert torch.equal(y.to(torch.float32), x), "inputs must be bf16-representable"
+            x = y
+        return x.to(dev).contiguous()
+
+    return dict(
+        q=t(d["q"], True), k=t(d["k"], True), v=t(d["v"], True),
+        q_logits=t(d["q_logits"], False), k_logits=t(d["k_logits"], False),
+        log_decay=t(d["log_decay"], variant == GLA), beta=t(d["beta"], False),
+    ), tdt

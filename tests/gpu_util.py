@@ -17,27 +17,7 @@ RETNET, GLA, GDN = 0, 1, 2
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def to_device(d, dtype: str, variant: int):
-    import torch
-
-    dev = torch.device("cuda:0")
-    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
-
-    def t(a, narrow):
-        if a is None:
-            return None
-        x = torch.from_numpy(np.ascontiguousarray(a))
-        if narrow and dtype == "bf16":
-            y = x.to(torch.bfloat16)
-            assert torch.equal(y.to(torch.float32), x), "inputs must be bf16-representable"
-            x = y
-        return x.to(dev).contiguous()
-
-    return dict(
-        q=t(d["q"], True), k=t(d["k"], True), v=t(d["v"], True),
-        q_logits=t(d["q_logits"], False), k_logits=t(d["k_logits"], False),
-        log_decay=t(d["log_decay"], variant == GLA), beta=t(d["beta"], False),
-    ), tdt
+to_device = si.to_device  # numpy inputs -> device tensors (marshalling only)
 
 
 def run_gpu(variant, d, dtype, initial_state=None, dv_split=0, want_final_state=True, segments=1):
