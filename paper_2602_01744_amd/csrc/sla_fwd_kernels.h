@@ -215,10 +215,15 @@ struct Smem {
     // masked scores P^T of the block as the consumers' MFMA operand: one 4-slot fragment per lane
     static constexpr size_t oPT = oGK + sizeof(float) * kBlock;
     // scalar-decay variants: per token the cumulative log2-decay c_t ("P1") and beta_t ("BT"); delta
-    // rule: the inverse Tm = (I + L)^-1 [16][16] of the block
+    // rule: the inverse Tm = (I + L)^-1 [16][16] of the block (built in fp32 in this area, left in the element type)
     static constexpr size_t oP1 = oPT + 64 * 4 * sizeof(elem);
     static constexpr size_t oBT = oP1 + sizeof(float) * kBlock;
-    static constexpr size_t oTM = oBT + sizeof(float) * kBlock;
+    // scalar-decay variants, for the consumers: per token 2^c_t ("E1"), 2^(c_16 - c_t) ("EB") and, delta rule,
+    // beta_t 2^c_t ("EJ"), so that the consumer waves spend no transcendental instructions on them
+    static constexpr size_t oE1 = oBT + sizeof(float) * kBlock;
+    static constexpr size_t oEB = oE1 + (VAR != SLA_GLA ? sizeof(float) * kBlock : 0);
+    static constexpr size_t oEJ = oEB + (VAR != SLA_GLA ? sizeof(float) * kBlock : 0);
+    static constexpr size_t oTM = oEJ + (VAR == SLA_GDN ? sizeof(float) * kBlock : 0);
     // The block's output tile [16 tokens][DVW], written by the consumer waves (each its 16 columns) and stored to
     // global memory by the slot's producer wave as whole rows.  A row is UPR units of four elements; unit c of
     // token t sits at position c ^ (t % UPR) of its row, which spreads both access patterns over the banks.
@@ -591,7 +596,13 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
         c_lane = row_prefix_sum(st.sc_ld * kLog2e);
         if (lane < kBlock) BT[lane] = st.sc_beta;
     }
-    if (lane < kBlock) C2[lane] = c_lane;
+    if (lane < kBlock) {
+        C2[lane] = c_lane;
+        const float e1 = fast_exp2(c_lane);
+        ((float*)(buf + L::oE1))[blk * kBlock + lane] = e1;
+        ((float*)(buf + L::oEB))[blk * kBlock + lane] = fast_exp2(row_bcast<15>(c_lane) - c_lane);
+        if constexpr (VAR == SLA_GDN) ((float*)(buf + L::oEJ))[blk * kBlock + lane] = st.sc_beta * e1;
+    }
     ldr.load_scalars(st);
 
     stage_gates<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
@@ -681,9 +692,11 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
         float x[kBlock];
         tm_substitute<0>(x, Lc, r);
         __builtin_amdgcn_wave_barrier();  // every lane has read L before it is overwritten
+        // the inverse replaces L in the same area, in the element type, ready as the consumers' MFMA operand
         if (g == 0) {
+            elem* TMo = (elem*)TM;
 #pragma unroll
-            for (int j = 0; j < kBlock; ++j) TM[j * kBlock + r] = x[j];
+            for (int j = 0; j < kBlock; ++j) P::store1(TMo + j * kBlock + r, x[j]);
         }
     }
 }
@@ -818,10 +831,11 @@ struct BlockFrags {
     frag fv;                                   // v' of this wave's columns
     float gq;                                  // read gate of token r
     float ea0, ea1;                            // GLA: block decay of the state rows this lane hands out by DPP
-    // scalar-decay variants: cumulative log2-decay of token r, of tokens 4g..4g+3, of the block's last token
-    float ct, c16;
-    f32x4 cj;
-    f32x4 bt, tm;                              // delta rule: beta_j (j = 4g..4g+3), Tm[r][4g..4g+3]
+    // scalar-decay variants: 2^c_t of token r, log2 of the block's decay, 2^(c_16 - c_j) for j = 4g..4g+3
+    float e1, c16;
+    f32x4 eb;
+    f32x4 ej;                                  // delta rule: beta_j 2^c_j (j = 4g..4g+3)
+    frag tm;                                   // delta rule: Tm[r][4g..4g+3], staged as an MFMA operand
 };
 
 // Requests the LDS operands of one block.  PART 0: all of them.  The delta rule asks in two parts: 1 = what
@@ -842,17 +856,16 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
         f.gq = ((const float*)(buf + L::oGQ))[r];
     }
     if constexpr (VAR != SLA_GLA && EARLY) {
-        const float* C2 = (const float*)(buf + L::oP1);
-        f.ct = C2[r];
-        f.c16 = C2[kBlock - 1];
-        f.cj = *(const f32x4*)(C2 + 4 * g);
+        f.e1 = ((const float*)(buf + L::oE1))[r];
+        f.c16 = ((const float*)(buf + L::oP1))[kBlock - 1];
+        f.eb = *(const f32x4*)((const float*)(buf + L::oEB) + 4 * g);
     }
     if constexpr (VAR == SLA_GDN && EARLY) {
         const elem* KD = (const elem*)(buf + L::oKD);
 #pragma unroll
         for (int s = 0; s < NTILE; ++s) f.fkd[s] = *(const frag*)(KD + r * L::RS + 32 * (s / 2) + 8 * g + 4 * (s & 1));
-        f.bt = *(const f32x4*)((const float*)(buf + L::oBT) + 4 * g);
-        f.tm = *(const f32x4*)((const float*)(buf + L::oTM) + r * kBlock + 4 * g);
+        f.ej = *(const f32x4*)((const float*)(buf + L::oEJ) + 4 * g);
+        f.tm = *(const frag*)((const elem*)(buf + L::oTM) + r * kBlock + 4 * g);
     }
     if constexpr (EARLY) f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + 4 * g);
     if constexpr (LATE) {
@@ -889,6 +902,7 @@ __device__ __forceinline__ int flag_peek(const lds_int* f) { return *(const vola
 
 __device__ __forceinline__ void flag_wait(const lds_int* f, int target, unsigned int* status) {
     int spin = 0;
+#pragma nounroll
     while (flag_peek(f) < target && ++spin < kSpinLimit) __builtin_amdgcn_s_sleep(1);
     if (spin >= kSpinLimit && (threadIdx.x & 63) == 0) atomicOr(status, (unsigned int)SLA_DEVICE_WAIT_EXPIRED);
     asm volatile("" ::: "memory");
@@ -932,9 +946,8 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
 
     frag fv = cur.fv;    // v' for the read-out
     frag fv2 = cur.fv;   // v' for the state step (scalar-decay variants: times 2^(c_16 - c_j))
-    [[maybe_unused]] float p_t = 1.f, A = 1.f;
+    [[maybe_unused]] float A = 1.f;
     if constexpr (VAR != SLA_GLA) {
-        p_t = fast_exp2(cur.ct);
         A = fast_exp2(cur.c16);
         f32x4 vs = P::to_acc(cur.fv);
         if constexpr (VAR == SLA_GDN) {
@@ -951,14 +964,14 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
             }
             f32x4 R;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.bt[i] * fast_exp2(cur.cj[i]) * (X[i] + X2[i]);
+            for (int i = 0; i < 4; ++i) R[i] = vs[i] - cur.ej[i] * (X[i] + X2[i]);
             f32x4 U = {0.f, 0.f, 0.f, 0.f};
-            P::mma16_only(U, P::from_acc(cur.tm), P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
+            P::mma16_only(U, cur.tm, P::from_acc(R));  // U[t][n] = sum_j Tm[t][j] R[j][n]
             vs = U;
             fv = P::from_acc(U);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vs[i] *= fast_exp2(cur.c16 - cur.cj[i]);
+        for (int i = 0; i < 4; ++i) vs[i] *= cur.eb[i];
         fv2 = P::from_acc(vs);
     }
 
@@ -987,7 +1000,7 @@ __device__ __forceinline__ void consume_block(f32x4 (&S)[DK / 16], const BlockFr
     if constexpr (!SO) {
         float o[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (VAR != SLA_GLA ? oS[i] * p_t + oP[i] : oS[i] + oP[i]) * cur.gq;
+        for (int i = 0; i < 4; ++i) o[i] = (VAR != SLA_GLA ? oS[i] * cur.e1 + oP[i] : oS[i] + oP[i]) * cur.gq;
         park_out4<P, DVW>(out_tile, r, unit, o);
     }
 }

@@ -211,3 +211,22 @@ def test_device_status_word_reports_out_of_range_decay():
     assert rc == 0 and word == sla.DEVICE_DECAY_RANGE, word
     rc, word = sla.sla_device_status()
     assert rc == 0 and word == 0, word
+
+
+@pytest.mark.parametrize("variant", [RETNET, GDN])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scalar_decay_of_any_strength(variant, dtype):
+    """RetNet and the delta rule take any decay <= 0.  Their kernels keep the state divided by a pending decay
+    factor and fold it in when it gets small: weak decay (folded every few hundred tokens), strong decay (every
+    block) and changes between the two within a sequence must all agree with the oracle."""
+    d = si.custom(variant, dtype, B=2, T=700, H=5, dk=128, dv=64, seed=2000 + variant)
+    rng = np.random.default_rng(21)
+    if variant == RETNET:
+        d["log_decay"] = np.array([-1e-4, -0.05, -0.9, -3.0, -7.0], dtype=np.float32)
+    else:
+        ld = -rng.choice([1e-4, 0.02, 0.3, 2.0, 6.0], size=d["log_decay"].shape).astype(np.float32)
+        ld[:, 200:330] = -1e-3   # a long stretch of weak decay after strong ones, then strong again
+        ld[:, 330:360] = -5.0
+        d["log_decay"] = ld
+    s0 = si.initial_state(2, 5, 128, 64, seed=22)
+    check(variant, d, dtype, s0, label=f"{si.VARIANT_NAMES[variant]} mixed decay strengths")
