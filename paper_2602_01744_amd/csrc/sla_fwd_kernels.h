@@ -447,25 +447,25 @@ __device__ __forceinline__ void scale_state_rows(f32x4 (&S)[NT], float ea0, floa
 }
 
 // Forward substitution for the 16x16 unit-lower-triangular inverse of the delta rule, one column per lane:
-// x[j] = [j == c] - sum_{i<j} L[j][i] x[i], where lane i of the row holds Lc[j] = -L[j][i].
-template <int J, int I>
-__device__ __forceinline__ float tm_row(const float (&x)[kBlock], float neg_lcj, float acc) {
-    if constexpr (I < J) {
-        // acc += (-L[j][i] from lane i of the row) * x[i] in one instruction.  neg_lcj was written long before,
-        // so the DPP read needs no wait states; x and acc are ordinary operands.
+// x[j] = [j == c] - sum_{i<j} L[j][i] x[i], where lane i of the row holds Lc[j] = -L[j][i].  The sums are taken
+// column by column ("right-looking"): once x[i] is final, every later row takes its term L[j][i] x[i], so that
+// consecutive instructions write different registers and none waits for the one before it.
+template <int I, int J>
+__device__ __forceinline__ void tm_update(float (&x)[kBlock], const float (&Lc)[kBlock]) {
+    if constexpr (J < kBlock) {
+        // x[j] += (-L[j][i] from lane i of the row) * x[i] in one instruction.  Lc was written long before, so
+        // the DPP read needs no wait states; x[i] and x[j] are ordinary operands.
         asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
-            : "+v"(acc)
-            : "v"(neg_lcj), "v"(x[I]), "n"(I));
-        return tm_row<J, I + 1>(x, neg_lcj, acc);
-    } else {
-        return acc;
+            : "+v"(x[J])
+            : "v"(Lc[J]), "v"(x[I]), "n"(I));
+        tm_update<I, J + 1>(x, Lc);
     }
 }
-template <int J>
-__device__ __forceinline__ void tm_substitute(float (&x)[kBlock], const float (&Lc)[kBlock], int c) {
-    if constexpr (J < kBlock) {
-        x[J] = tm_row<J, 0>(x, Lc[J], (J == c) ? 1.f : 0.f);  // Lc holds -L
-        tm_substitute<J + 1>(x, Lc, c);
+template <int I>
+__device__ __forceinline__ void tm_substitute(float (&x)[kBlock], const float (&Lc)[kBlock]) {
+    if constexpr (I + 1 < kBlock) {
+        tm_update<I, I + 1>(x, Lc);
+        tm_substitute<I + 1>(x, Lc);
     }
 }
 
@@ -672,14 +672,14 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
         // taken from lane i of the row by a DPP broadcast.
         f32x4 lv;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lv[i] = (4 * g + i > r) ? btj[i] * fast_exp2(cj[i] - c_lane) * G[i] : 0.f;
+        for (int i = 0; i < 4; ++i) lv[i] = (4 * g + i > r) ? -(btj[i] * fast_exp2(cj[i] - c_lane) * G[i]) : 0.f;  // -L
         *(f32x4*)(TM + r * kBlock + 4 * g) = lv;
         __builtin_amdgcn_wave_barrier();
         float Lc[kBlock];
 #pragma unroll
         for (int j4 = 0; j4 < kBlock; j4 += 4) {
             const f32x4 t = *(const f32x4*)(TM + r * kBlock + j4);
-            Lc[j4] = -t[0]; Lc[j4 + 1] = -t[1]; Lc[j4 + 2] = -t[2]; Lc[j4 + 3] = -t[3];  // negated for the fmac
+            Lc[j4] = t[0]; Lc[j4 + 1] = t[1]; Lc[j4 + 2] = t[2]; Lc[j4 + 3] = t[3];  // -L, for the fmac
         }
         // forward substitution, column c = r of the inverse in every lane (the four lane groups repeat it):
         // x_j = [j == c] - sum_{i<j} L[j][i] x_i
@@ -690,7 +690,9 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
                        "+v"(Lc[8]), "+v"(Lc[9]), "+v"(Lc[10]), "+v"(Lc[11]), "+v"(Lc[12]), "+v"(Lc[13]), "+v"(Lc[14]),
                        "+v"(Lc[15]));
         float x[kBlock];
-        tm_substitute<0>(x, Lc, r);
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) x[j] = (j == r) ? 1.f : 0.f;
+        tm_substitute<0>(x, Lc);
         __builtin_amdgcn_wave_barrier();  // every lane has read L before it is overwritten
         // the inverse replaces L in the same area, in the element type, ready as the consumers' MFMA operand
         if (g == 0) {
