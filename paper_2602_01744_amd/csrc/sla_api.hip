@@ -99,7 +99,8 @@ int check_params(const sla_params* p) {
     if (p->segments > 1 && p->variant == SLA_GDN) return SLA_ERR_UNSUPPORTED;
     if (p->B < 0 || p->T < 0 || p->H < 1 || p->H > kMaxHeads) return SLA_ERR_SHAPE;
     if (p->dk < 1 || p->dv < 1) return SLA_ERR_SHAPE;
-    if ((p->dk != 64 && p->dk != 128) || (p->dv != 64 && p->dv != 128 && p->dv != 256)) return SLA_ERR_UNSUPPORTED;
+    if ((p->dk != 32 && p->dk != 64 && p->dk != 128) || (p->dv != 64 && p->dv != 128 && p->dv != 256))
+        return SLA_ERR_UNSUPPORTED;
     if (p->dv_split != 0) {
         const int s = p->dv_split;
         if (s != 16 && s != 32 && s != 64 && s != 128) return SLA_ERR_SHAPE;
@@ -307,6 +308,7 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
     const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out, state);
     if (rc != SLA_OK) return rc;
     if (p->T != 1) return SLA_ERR_SHAPE;
+    if (p->dk < 64) return SLA_ERR_UNSUPPORTED;
     if (p->B == 0) return SLA_OK;
     if (!state) return SLA_ERR_NULL;
     // one token per sequence: [B,1,H,d] and [B,H,1,d] are the same memory, so the layout flag changes nothing
@@ -337,7 +339,7 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
                          void* workspace, size_t workspace_bytes, const int32_t* cu, bool packed, void* stream) {
     int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant == SLA_GDN || p->dtype != SLA_BF16 || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
+    if (p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->dk < 64 || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !d_out || !dq || !dk || !dv || !dq_head_logits)
             return SLA_ERR_NULL;
@@ -397,7 +399,7 @@ static int backward_gdn_impl(const sla_params* p, const void* q, const void* k, 
                              float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant != SLA_GDN || p->flags != 0) return SLA_ERR_UNSUPPORTED;
+    if (p->variant != SLA_GDN || p->flags != 0 || p->dk < 64) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !beta || !d_out || !dq || !dk || !dv ||
             !dq_head_logits || !dlog_decay || !dbeta)
@@ -443,12 +445,12 @@ int sla_backward_gdn_varlen(const sla_params* p, const void* q, const void* k, c
 }
 
 size_t sla_backward_gdn_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant != SLA_GDN) return 0;
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dk < 64) return 0;
     return sla::backward_gdn_workspace_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_gdn_varlen_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant != SLA_GDN) return 0;
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dk < 64) return 0;
     return sla::backward_gdn_workspace_floats(*p, true) * sizeof(float);
 }
 
@@ -482,12 +484,12 @@ int sla_short_conv_silu(int dtype, int B, int T, int channels, int taps, const v
 }
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16) return 0;
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->dk < 64) return 0;
     return backward_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_varlen_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16) return 0;
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->dk < 64) return 0;
     return sla::backward_workspace_floats(*p, true) * sizeof(float);
 }
 

@@ -55,6 +55,10 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 static constexpr float kLog2e = 1.4426950408889634f;
 static constexpr float kMinBlockDecay = 1.0e-35f;  // just under e^-80 = 1.8e-35, the smallest in-range decay of a block
 static constexpr int kBlock = 16;   // tokens per state step
+// A producer lane owns kEPL<DK> adjacent key dimensions of all 16 tokens of a block; with dk = 32 only the first
+// 32 lanes of the wave own any (the others run along and store nothing).
+template <int DK> inline constexpr int kEPL = DK >= 64 ? DK / 64 : 1;
+template <int DK> inline constexpr int kOwners = DK / kEPL<DK>;
 static constexpr int kWaves = 4;
 static constexpr uint32_t kRsrcWord3 = 0x00020000u;  // raw buffer descriptor, 32-bit data format
 
@@ -285,7 +289,7 @@ __device__ __forceinline__ void store_out_tile(const typename P::elem* tile, typ
 
 // ---------------------------------------------------------------------------------------------
 // Per-lane staging registers for one 16-token block (what a producer wave works on).
-// Lane l owns EPL = DK/64 adjacent key dimensions (d = EPL*l ...) of all 16 tokens of the block,
+// Lane l owns EPL = max(DK/64, 1) adjacent key dimensions (d = EPL*l ...) of all 16 tokens of the block,
 // and for V two adjacent value columns of NI = DVW/8 consecutive tokens.  For the gates, lane l
 // holds the logits of token l/4 for heads l%4, l%4 + 4, ... (HG registers per gate), so that the
 // reduction over heads stays inside a quad and runs on DPP.
@@ -308,7 +312,7 @@ template <class P, int VAR, int DK, int DVW, int HG>
 struct Loader {
     typedef typename P::elem elem;
     typedef Stage<P, VAR, DK, DVW, HG> stage_t;
-    static constexpr int EPL = DK / 64;
+    static constexpr int EPL = kEPL<DK>;
     static constexpr int NI = DVW / 8;
     static constexpr int LPR = DVW / 2;
     __amdgpu_buffer_rsrc_t rq, rk, rv, rld, rql, rkl, rbt;
@@ -575,7 +579,8 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
     typedef typename P::pair pair;
     typedef typename P::frag frag;
     typedef Smem<P, VAR, DK, DVW> L;
-    constexpr int EPL = DK / 64;
+    constexpr int EPL = kEPL<DK>;
+    const bool owner = lane < kOwners<DK>;  // always true for dk >= 64
     constexpr int NTILE = DK / 16;
     elem* QA = (elem*)(buf + L::oQA);
     elem* KD = (elem*)(buf + L::oKD);
@@ -616,7 +621,7 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
             if constexpr (EPL == 2) {
                 *(pair*)(qrow + i * L::RS) = st.q[i];
                 *(pair*)(krow + i * L::RS) = st.k[i];
-            } else {
+            } else if (owner) {
                 P::store1(qrow + i * L::RS, P::lo(st.q[i]));
                 P::store1(krow + i * L::RS, P::lo(st.k[i]));
             }
@@ -633,7 +638,7 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 #pragma unroll
         for (int tg = 0; tg < 4; ++tg) {
             const float four[4] = {kt[4 * tg], kt[4 * tg + 1], kt[4 * tg + 2], kt[4 * tg + 3]};
-            store_run<P, 4>(dst + 8 * tg, four);
+            if (owner) store_run<P, 4>(dst + 8 * tg, four);
         }
     }
 #pragma unroll
@@ -713,7 +718,7 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 template <class P, int VAR, int DK, int DVW, int HG, bool SO>
 __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, const Loader<P, VAR, DK, DVW, HG>& ldr,
                                               unsigned char* buf, int blk, int tok0, int next_tok0, int T,
-                                              float decay_const, float (&dacc)[DK / 64], int lane,
+                                              float decay_const, float (&dacc)[kEPL<DK>], int lane,
                                               unsigned int* status) {
     if constexpr (VAR != SLA_GLA) {
         produce_block_scalar<P, VAR, DK, DVW, HG, SO>(st, ldr, buf, blk, tok0, next_tok0, T, decay_const, lane);
@@ -722,7 +727,8 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
     typedef typename P::elem elem;
     typedef typename P::pair pair;
     typedef Smem<P, VAR, DK, DVW> L;
-    constexpr int EPL = DK / 64;
+    constexpr int EPL = kEPL<DK>;
+    const bool owner = lane < kOwners<DK>;  // always true for dk >= 64
     elem* QA = (elem*)(buf + L::oQA);
     elem* KD = (elem*)(buf + L::oKD);
     elem* KBT = (elem*)(buf + L::oKBT);
@@ -750,7 +756,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         if constexpr (!SO) {
             if constexpr (EPL == 2)
                 *(pair*)(qrow + i * L::RS) = P::make(P::lo(st.q[i]) * pre[0], P::hi(st.q[i]) * pre[1]);
-            else
+            else if (owner)
                 P::store1(qrow + i * L::RS, P::lo(st.q[i]) * pre[0]);
             ldr.load_q(st, i);
         }
@@ -760,9 +766,9 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
         invA[e] = fast_rcp(pre[e]);
-        EA[blk * DK + EPL * lane + e] = pre[e];
+        if (owner) EA[blk * DK + EPL * lane + e] = pre[e];
         if constexpr (SO) dacc[e] *= pre[e];
-        in_range = in_range && pre[e] >= kMinBlockDecay;
+        in_range = in_range && (pre[e] >= kMinBlockDecay || !owner);
     }
     // A block decay below e^-80 means a log-decay under -5 somewhere in the block (or a NaN): the quotients
     // below may then leave the fp32 range.  The call goes on; the status word tells the caller.
@@ -779,7 +785,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
         if constexpr (!SO) {
             if constexpr (EPL == 2)
                 *(pair*)(krow + i * L::RS) = P::make(kb[0][i] * invA[0], kb[1][i] * invA[1]);
-            else
+            else if (owner)
                 P::store1(krow + i * L::RS, kb[0][i] * invA[0]);
         }
 #pragma unroll
@@ -791,7 +797,7 @@ __device__ __forceinline__ void produce_block(Stage<P, VAR, DK, DVW, HG>& st, co
 #pragma unroll
         for (int tg = 0; tg < 4; ++tg) {
             const float four[4] = {kb[e][4 * tg], kb[e][4 * tg + 1], kb[e][4 * tg + 2], kb[e][4 * tg + 3]};
-            store_run<P, 4>(dst + 8 * tg, four);
+            if (owner) store_run<P, 4>(dst + 8 * tg, four);
         }
     }
     // Scores of the block, P^T[j][t] = kd_j . qa_t for j <= t (else 0), from this wave's own rows
@@ -1020,7 +1026,7 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
     constexpr int NTILE = DK / 16;
     constexpr int NCW = DVW / 16;  // consumer waves that have columns
     constexpr int NP = L::slots;   // producer waves = ring slots
-    static_assert(DK == 64 || DK == 128, "dk");
+    static_assert(DK == 32 || DK == 64 || DK == 128, "dk");
     static_assert(DVW == 16 || DVW == 32 || DVW == 64, "value columns per workgroup");
     static_assert((NP & (NP - 1)) == 0, "slot index is taken with a mask");
 
@@ -1078,9 +1084,9 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
         Stage<P, VAR, DK, DVW, HG> st;
         ldr.advance(kBlock * pw);
         ldr.load(st, lane);
-        float dacc[DK / 64];  // pre-pass, GLA: decay of the blocks this wave staged, per owned key dimension
+        float dacc[kEPL<DK>];  // pre-pass, GLA: decay of the blocks this wave staged, per owned key dimension
 #pragma unroll
-        for (int e = 0; e < DK / 64; ++e) dacc[e] = 1.f;
+        for (int e = 0; e < kEPL<DK>; ++e) dacc[e] = 1.f;
         unsigned char* buf = smem + (size_t)pw * L::bytes;
         // The slot's output tile goes to global memory from here: column n0 of the row's first token.
         const size_t out_tstride = a.head_major ? (size_t)dv : (size_t)H * dv;
@@ -1108,9 +1114,11 @@ __global__ __launch_bounds__((Smem<P, VAR, DK, DVW>::threads)) void sla_fwd_kern
             }
         }
         if constexpr (SO && VAR == SLA_GLA) {
-            float* dp = a.ws_decay + (((size_t)(b * (a.nseg - 1) + seg) * H + h) * kMaxSlots + pw) * DK + (DK / 64) * lane;
+            float* dp = a.ws_decay + (((size_t)(b * (a.nseg - 1) + seg) * H + h) * kMaxSlots + pw) * DK + kEPL<DK> * lane;
+            if (lane < kOwners<DK>) {
 #pragma unroll
-            for (int e = 0; e < DK / 64; ++e) dp[e] = dacc[e];
+                for (int e = 0; e < kEPL<DK>; ++e) dp[e] = dacc[e];
+            }
         }
         return;
     }
@@ -1317,6 +1325,7 @@ static int dispatch_dvw(const KArgs& a, int dvw, hipStream_t stream) {
 template <class P, int VAR>
 static int dispatch_dk(const KArgs& a, int dk, int dvw, hipStream_t stream) {
     switch (dk) {
+        case 32: return dispatch_dvw<P, VAR, 32>(a, dvw, stream);
         case 64: return dispatch_dvw<P, VAR, 64>(a, dvw, stream);
         case 128: return dispatch_dvw<P, VAR, 128>(a, dvw, stream);
         default: return SLA_ERR_UNSUPPORTED;

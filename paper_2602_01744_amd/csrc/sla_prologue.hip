@@ -45,12 +45,12 @@ __device__ __forceinline__ float dot8(const void* row, int off, const float* w) 
     return s;
 }
 
-// sum over the LPH adjacent lanes of one head (LPH = 8 or 16, aligned inside a 16-lane row); valid in the last lane
+// sum over the LPH adjacent lanes of one head (LPH = 4, 8 or 16, aligned inside a 16-lane row); valid in the last lane
 template <int LPH>
 __device__ __forceinline__ float head_sum(float s) {
     s += pdpp<0x111>(s);
     s += pdpp<0x112>(s);
-    s += pdpp<0x114>(s);
+    if constexpr (LPH >= 8) s += pdpp<0x114>(s);
     if constexpr (LPH == 16) s += pdpp<0x118>(s);
     return s;
 }
@@ -103,6 +103,10 @@ template <bool BF16>
 int launch_dk(int dk, dim3 grid, hipStream_t stream, const void* q, const void* k, const float* wq, const float* wk,
               float* ql, float* kl, size_t rows, int H, int groups) {
     switch (dk) {
+        case 32:
+            hipLaunchKernelGGL((sla_gate_logits_kernel<BF16, 32>), grid, dim3(kPThreads), 0, stream, q, k, wq, wk, ql,
+                               kl, rows, H, groups);
+            break;
         case 64:
             hipLaunchKernelGGL((sla_gate_logits_kernel<BF16, 64>), grid, dim3(kPThreads), 0, stream, q, k, wq, wk, ql,
                                kl, rows, H, groups);

@@ -101,6 +101,9 @@ def workload(name: str) -> Workload:
         # at half width) at its training length, and the H = 8 point of its head ablation at the same width.
         "gla_paper_h4": Workload("gla_paper_h4", GLA, "bf16", 8, 4096, 4, 128, 256, SEED_BASE + 10),
         "gla_paper_h8": Workload("gla_paper_h8", GLA, "bf16", 8, 4096, 8, 64, 128, SEED_BASE + 11),
+        # ... and its H = 16 point (Sec. 5.6: the gain of the head competition grows with the head count): keys of
+        # width 32, values of width 64.
+        "gla_paper_h16": Workload("gla_paper_h16", GLA, "bf16", 8, 4096, 16, 32, 64, SEED_BASE + 12),
         # One decode step (T = 1) over a serving-sized batch: the recurrent form, one token per sequence.
         "decode_gla": Workload("decode_gla", GLA, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 7),
         "decode_retnet": Workload("decode_retnet", RETNET, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 8),
@@ -112,7 +115,7 @@ def workload(name: str) -> Workload:
 
 
 WORKLOAD_NAMES = ("gla_tiny", "retnet", "gla_train", "gdn", "gla_long", "retnet_train", "gdn_train", "gla_paper_h4",
-                  "gla_paper_h8")
+                  "gla_paper_h8", "gla_paper_h16")
 DECODE_WORKLOAD_NAMES = ("decode_gla", "decode_retnet", "decode_gdn")
 
 

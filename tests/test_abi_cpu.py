@@ -215,7 +215,7 @@ def test_gate_logits_rejects_bad_calls(lib):
     assert call(ok, q=0) == -1 and call(ok, wq=0) == -1 and call(ok, ql=0) == -1
     assert call(ok, k=0) == -1 and call(ok, wk=0) == -1 and call(ok, kl=0) == -1  # k, w_gk, k logits go together
     assert call(ok, wq=A + 8) == -4
-    assert call(_ok_params(dk=32)) == -3
+    assert call(_ok_params(dk=48)) == -3
     assert call(None) == -1
     assert call(_ok_params(B=0)) == 0 and call(_ok_params(T=0)) == 0
 
@@ -342,3 +342,14 @@ def test_static_entry_point_validates_before_any_device_work(lib):
     # 8 segments of a 64-head batch: 8 * 64 * 128 * 128 floats of entry states alone = 32 MiB > 16 MiB
     big = _ok_params(B=4, T=8192, H=16, segments=8)
     assert sla.sla_forward_static(big, A, A, A, A, A, A, 0, 0, A, A, 0) == -7
+
+
+def test_narrow_keys_are_forward_only(lib):
+    """dk = 32 passes the forward's validation; the backward, the decode step and their workspace queries refuse it."""
+    p = _ok_params(dk=32, dv=64)
+    assert _call(p) == 0
+    assert _bwd(p) == -3
+    assert sla.sla_backward_workspace_bytes(p) == 0
+    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dk=32, dv=64)) == 0
+    args = (A, A, A, A, A, A, 0)
+    assert sla.sla_decode_step(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) == -3

@@ -10,7 +10,7 @@ from gpu_util import check, rel_err, run_gpu
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
-@pytest.mark.parametrize("name", ["retnet", "gla_train", "gdn", "retnet_train", "gdn_train"])
+@pytest.mark.parametrize("name", ["retnet", "gla_train", "gdn", "retnet_train", "gdn_train", "gla_paper_h16"])
 def test_full_size_workload(name):
     w = si.workload(name)
     check(w.variant, si.generate(w), w.dtype, label=f"full {name}")

@@ -31,7 +31,7 @@ def test_ragged_multi_tile(variant, dtype, dv_split):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-@pytest.mark.parametrize("dk,dv", [(64, 64), (64, 128), (128, 64)])
+@pytest.mark.parametrize("dk,dv", [(64, 64), (64, 128), (128, 64), (32, 64), (32, 128)])
 def test_head_widths(variant, dk, dv):
     for dtype in ("f32", "bf16"):
         d = si.custom(variant, dtype, B=1, T=130, H=3, dk=dk, dv=dv, seed=200 + dk + dv)
@@ -230,3 +230,17 @@ def test_scalar_decay_of_any_strength(variant, dtype):
         d["log_decay"] = ld
     s0 = si.initial_state(2, 5, 128, 64, seed=22)
     check(variant, d, dtype, s0, label=f"{si.VARIANT_NAMES[variant]} mixed decay strengths")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_narrow_keys_ragged_segments_and_state(variant):
+    """dk = 32 (the H = 16 point of the head ablation at fixed model width): half of a producer wave's lanes own no
+    key dimension.  Ragged length, an initial state, every slice width, and the segment schedule."""
+    d = si.custom(variant, "bf16", B=2, T=333, H=16, dk=32, dv=64, seed=2100 + variant)
+    s0 = si.initial_state(2, 16, 32, 64, seed=23)
+    for dv_split in (0, 16, 32):
+        check(variant, d, "bf16", s0, dv_split, label=f"{_name(variant)} dk=32 dv=64 H=16")
+    check(variant, d, "f32", s0, label=f"{_name(variant)} dk=32 dv=64 H=16 fp32")
+    if variant != GDN:
+        d = si.custom(variant, "bf16", B=1, T=900, H=4, dk=32, dv=64, seed=2200 + variant)
+        check(variant, d, "bf16", label=f"{_name(variant)} dk=32, 3 segments", segments=3)

@@ -27,7 +27,7 @@ LOGIT_TOL = 1e-5
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("H,dk", [(1, 64), (3, 64), (4, 128), (5, 128), (16, 128), (64, 64), (64, 128)])
+@pytest.mark.parametrize("H,dk", [(1, 64), (3, 64), (4, 128), (5, 128), (16, 128), (64, 64), (64, 128), (16, 32), (5, 32)])
 def test_gate_logits_parity(dtype, H, dk):
     B, T = 2, 203
     d = si.custom(GLA, dtype, B=B, T=T, H=H, dk=dk, dv=64, seed=1000 + H + dk)
