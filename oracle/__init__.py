@@ -8,6 +8,9 @@
                    differentiation token by token, fp64 numpy; pinned by finite
                    differences and by autograd through the parallel form.
 
+``sla_prologue`` – gate projections, short convolution + SiLU (+ L2 normalisation) and their
+                   backward, fp64 numpy; pinned by finite differences and library autograd.
+
 Nothing under the GPU package imports this package; only ``tests/``, the smoke
 check and the benchmark's cpu_baseline leg do.
 """
@@ -20,7 +23,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-from . import sla_backward, sla_numpy  # noqa: F401
+from . import sla_backward, sla_numpy, sla_prologue  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sla_oracle.c")
