@@ -318,6 +318,9 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
     dbeta = torch.empty_like(g["beta"]) if gdn else None
     need = sla.sla_backward_gdn_workspace_bytes(pb) if gdn else sla.sla_backward_workspace_bytes(pb)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    dwq, dwk = torch.empty_like(wq), torch.empty_like(wk)
+    gneed = sla.sla_gate_logits_backward_workspace_bytes(pf)
+    gws = torch.empty(max(gneed, 16), dtype=torch.uint8, device=dev)
     ptr = lambda t: None if t is None else t.data_ptr()
     st = torch.cuda.current_stream(dev).cuda_stream
 
@@ -332,6 +335,11 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
         else:
             rc = rc or sla.sla_backward(pb, ptr(g["q"]), ptr(g["k"]), ptr(g["v"]), ptr(ql), ptr(kl), ptr(g["log_decay"]),
                                         None, ptr(dout), None, *(ptr(t) for t in grads), ptr(dld), None, ptr(ws), need, st)
+        # the projections' share of dq, dk (added in place) and the gate matrices' gradients
+        rc = rc or sla.sla_gate_logits_backward(pf, ptr(g["q"]), ptr(wq), ptr(grads[3]), ptr(grads[0]), ptr(dwq),
+                                                ptr(gws), gneed, st)
+        rc = rc or sla.sla_gate_logits_backward(pf, ptr(g["k"]), ptr(wk), ptr(grads[4]), ptr(grads[1]), ptr(dwk),
+                                                ptr(gws), gneed, st)
         if rc != 0:
             raise sla.SlaError(rc, sla.sla_status_string(rc))
 
@@ -352,10 +360,13 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
     call_ms = float(np.mean(per_ms))
     ms_per_step = wall * 1e3 / steps
     es = 2
-    abytes = (2 * w.B * w.T * w.H * (w.dk * es + 4) + 2 * w.H * w.dk * 4) + algorithmic_bytes(w) + backward_bytes(w)
+    # gate logits: q, k read, two logit tensors written; their backward: q, k, dq, dk, the logit cotangents read,
+    # dq, dk written, the gate matrices' gradients written
+    abytes = ((2 * w.B * w.T * w.H * (w.dk * es + 4) + 2 * w.H * w.dk * 4) + algorithmic_bytes(w) + backward_bytes(w)
+              + 2 * w.B * w.T * w.H * (3 * w.dk * es + 4) + 2 * w.H * w.dk * 4)
     achieved = abytes / (call_ms * 1e-3) / 1e9
     result = {
-        "metric": f"tokens/sec SLA-{si.VARIANT_NAMES[w.variant].upper()} mixer training step (gate logits + fwd + bwd)",
+        "metric": f"tokens/sec SLA-{si.VARIANT_NAMES[w.variant].upper()} mixer training step (gate logits + fwd + bwd + gate projections' bwd)",
         "value": w.tokens() / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -372,7 +383,8 @@ def bench_train_step(args, w, sla, si, torch, np) -> int:
             "workload": f"{w.name}: gate logits, forward and backward of SLA-{si.VARIANT_NAMES[w.variant].upper()} "
                         f"B={w.B} T={w.T} H={w.H} dk={w.dk} dv={w.dv} bf16"
                         + (f", backward in {nseg} segments per batch row" if nseg > 1 else ""),
-            "kernel": "sla_gate_logits + sla_forward + " + ("sla_backward_gdn" if gdn else "sla_backward"),
+            "kernel": "sla_gate_logits + sla_forward + " + ("sla_backward_gdn" if gdn else "sla_backward")
+                      + " + 2 x sla_gate_logits_backward",
         },
         "roofline": {
             "bound": "hbm",

@@ -313,6 +313,45 @@ size_t sla_backward_varlen_workspace_bytes(const sla_params* p);
 int sla_short_conv_silu(int dtype, int B, int T, int channels, int taps, const void* x, const float* w, void* y,
                         void* stream);
 
+/*
+ * The same feature map with an optional L2 normalisation of every head's vector behind it (the benchmark's delta-rule
+ * workload feeds L2-normalised queries and keys; the paper's Sec. 5.1 names only the convolution and SiLU, so this
+ * is an option): with head_width > 0 every group of head_width adjacent channels of a token is divided by
+ * sqrt(sum of its squares + eps).  head_width 0 (no normalisation), 32, 64 or 128; with head_width > 0 channels must
+ * be a multiple of 128 and eps >= 0.  Otherwise as sla_short_conv_silu.
+ */
+int sla_short_conv_silu_l2(int dtype, int B, int T, int channels, int taps, int head_width, float eps, const void* x,
+                           const float* w, void* y, void* stream);
+
+/*
+ * Backward of sla_short_conv_silu_l2 (of sla_short_conv_silu with head_width = 0): for the cotangent dy of y,
+ *     dx [B,T,channels] dtype  written (must not overlap x, dy)
+ *     dw [channels,taps] fp32  written (sum over all tokens, taken in a fixed order: bitwise reproducible)
+ * The convolution is recomputed from x and w, nothing is kept from the forward call.  workspace: device memory of
+ * sla_short_conv_silu_l2_backward_workspace_bytes(B, T, channels, taps) bytes (partial sums of dw), 16-byte aligned.
+ * B == 0 or T == 0 is a no-op that leaves dw untouched.
+ */
+int sla_short_conv_silu_l2_backward(int dtype, int B, int T, int channels, int taps, int head_width, float eps,
+                                    const void* x, const float* w, const void* dy, void* dx, float* dw,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+size_t sla_short_conv_silu_l2_backward_workspace_bytes(int B, int T, int channels, int taps);
+
+/*
+ * Backward of one gate projection of sla_gate_logits (Eq. 4's scores, logits[b,t,h] = x[b,t,h,:] . W[:,h]); call it
+ * once for the queries (x = q, w = w_gq, the mixer's dq_head_logits and dq) and once for the keys:
+ *     x              [B,T,H,dk] dtype   the projected tensor (device, read only)
+ *     w              [H,dk] fp32        as for sla_gate_logits
+ *     d_head_logits  [B,T,H] fp32       cotangent of the logits (what sla_backward / sla_backward_gdn return)
+ *     dx             [B,T,H,dk] dtype   READ AND UPDATED IN PLACE: dx[b,t,h,:] += d_head_logits[b,t,h] w[h,:]
+ *                                       (pass the dq / dk that the mixer's backward has written)
+ *     dw             [H,dk] fp32        written: sum over b, t of d_head_logits[b,t,h] x[b,t,h,:] (fixed order)
+ *     workspace      sla_gate_logits_backward_workspace_bytes(p) bytes of device memory, 16-byte aligned
+ * Uses p->dtype, B, T, H, dk; p->flags must be 0.
+ */
+int sla_gate_logits_backward(const sla_params* p, const void* x, const float* w, const float* d_head_logits, void* dx,
+                             float* dw, void* workspace, size_t workspace_bytes, void* stream);
+size_t sla_gate_logits_backward_workspace_bytes(const sla_params* p);
+
 /* Bytes of workspace sla_forward_ws wants for *p on a device with that many compute units (0: none needed). */
 size_t sla_workspace_bytes(const sla_params* p, int compute_units);
 

@@ -25,6 +25,14 @@ from .binding import (  # noqa: F401
     sla_check_args,
     sla_gate_logits,
     sla_short_conv_silu,
+    sla_short_conv_silu_l2,
+    sla_short_conv_silu_l2_backward,
+    sla_short_conv_silu_l2_backward_workspace_bytes,
+    sla_gate_logits_backward,
+    sla_gate_logits_backward_workspace_bytes,
+    short_conv_silu_l2,
+    short_conv_silu_l2_backward,
+    gate_logits_backward,
     sla_decode_step,
     sla_default_dv_split,
     sla_forward,

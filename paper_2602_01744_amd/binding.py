@@ -80,6 +80,16 @@ def load_library():
     lib.sla_backward_varlen_workspace_bytes.argtypes = [pp]
     lib.sla_short_conv_silu.restype = ctypes.c_int
     lib.sla_short_conv_silu.argtypes = [ctypes.c_int] * 5 + [vp] * 4
+    lib.sla_short_conv_silu_l2.restype = ctypes.c_int
+    lib.sla_short_conv_silu_l2.argtypes = [ctypes.c_int] * 6 + [ctypes.c_float] + [vp] * 4
+    lib.sla_short_conv_silu_l2_backward.restype = ctypes.c_int
+    lib.sla_short_conv_silu_l2_backward.argtypes = [ctypes.c_int] * 6 + [ctypes.c_float] + [vp] * 6 + [ctypes.c_size_t, vp]
+    lib.sla_short_conv_silu_l2_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.sla_short_conv_silu_l2_backward_workspace_bytes.argtypes = [ctypes.c_int] * 4
+    lib.sla_gate_logits_backward.restype = ctypes.c_int
+    lib.sla_gate_logits_backward.argtypes = [pp] + [vp] * 6 + [ctypes.c_size_t, vp]
+    lib.sla_gate_logits_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.sla_gate_logits_backward_workspace_bytes.argtypes = [pp]
     lib.sla_gate_logits.restype = ctypes.c_int
     lib.sla_gate_logits.argtypes = [pp] + [vp] * 7
     lib.sla_backward.restype = ctypes.c_int
@@ -327,6 +337,86 @@ def short_conv_silu(x, w):
     if rc != 0:
         raise SlaError(rc, sla_status_string(rc))
     return y
+
+
+def sla_short_conv_silu_l2(dtype, B, T, channels, taps, head_width, eps, x, w, y, stream) -> int:
+    """Raw call of the feature map with the L2 option (integer device addresses or None)."""
+    return int(load_library().sla_short_conv_silu_l2(int(dtype), int(B), int(T), int(channels), int(taps),
+                                                      int(head_width), float(eps), _p(x), _p(w), _p(y), _p(stream)))
+
+
+def sla_short_conv_silu_l2_backward_workspace_bytes(B, T, channels, taps) -> int:
+    return int(load_library().sla_short_conv_silu_l2_backward_workspace_bytes(int(B), int(T), int(channels), int(taps)))
+
+
+def sla_short_conv_silu_l2_backward(dtype, B, T, channels, taps, head_width, eps, x, w, dy, dx, dw, workspace,
+                                    workspace_bytes, stream) -> int:
+    """Raw call of the feature map's backward (integer device addresses or None)."""
+    return int(load_library().sla_short_conv_silu_l2_backward(
+        int(dtype), int(B), int(T), int(channels), int(taps), int(head_width), float(eps), _p(x), _p(w), _p(dy), _p(dx),
+        _p(dw), _p(workspace), int(workspace_bytes), _p(stream)))
+
+
+def sla_gate_logits_backward_workspace_bytes(params: SlaParams) -> int:
+    return int(load_library().sla_gate_logits_backward_workspace_bytes(ctypes.byref(params)))
+
+
+def sla_gate_logits_backward(params, x, w, d_head_logits, dx, dw, workspace, workspace_bytes, stream) -> int:
+    """Raw call of one gate projection's backward (integer device addresses or None); dx is updated in place."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(load_library().sla_gate_logits_backward(pr, _p(x), _p(w), _p(d_head_logits), _p(dx), _p(dw),
+                                                        _p(workspace), int(workspace_bytes), _p(stream)))
+
+
+def short_conv_silu_l2(x, w, head_width: int = 0, eps: float = 1e-6):
+    """x [B,T,C], w [C,taps] float32 -> silu(conv) with every head of head_width channels L2-normalised."""
+    import torch
+
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 3
+    B, T, C = x.shape
+    y = torch.empty_like(x)
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    rc = sla_short_conv_silu_l2(dtype, B, T, C, w.shape[1], head_width, eps, x.data_ptr(), w.data_ptr(), y.data_ptr(),
+                                torch.cuda.current_stream(x.device).cuda_stream)
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return y
+
+
+def short_conv_silu_l2_backward(x, w, dy, head_width: int = 0, eps: float = 1e-6):
+    """Gradients (dx like x, dw [C,taps] float32) of ``short_conv_silu_l2`` for the cotangent dy."""
+    import torch
+
+    B, T, C = x.shape
+    K = w.shape[1]
+    dx = torch.empty_like(x)
+    dw = torch.empty((C, K), dtype=torch.float32, device=x.device)
+    need = sla_short_conv_silu_l2_backward_workspace_bytes(B, T, C, K)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    rc = sla_short_conv_silu_l2_backward(dtype, B, T, C, K, head_width, eps, x.data_ptr(), w.data_ptr(), dy.data_ptr(),
+                                         dx.data_ptr(), dw.data_ptr(), ws.data_ptr(), ws.numel(),
+                                         torch.cuda.current_stream(x.device).cuda_stream)
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return dx, dw
+
+
+def gate_logits_backward(x, w, d_head_logits, dx):
+    """dx [B,T,H,dk] += d_head_logits[..., None] * w (in place); returns dw [H,dk] float32."""
+    import torch
+
+    B, T, H, dk = x.shape
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    params = SlaParams(GLA, dtype, B, T, H, dk, 64, 0, 0, 1)
+    dw = torch.empty((H, dk), dtype=torch.float32, device=x.device)
+    need = sla_gate_logits_backward_workspace_bytes(params)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    rc = sla_gate_logits_backward(params, x.data_ptr(), w.data_ptr(), d_head_logits.data_ptr(), dx.data_ptr(),
+                                  dw.data_ptr(), ws.data_ptr(), ws.numel(), torch.cuda.current_stream(x.device).cuda_stream)
+    if rc != 0:
+        raise SlaError(rc, sla_status_string(rc))
+    return dw
 
 
 def sla_gate_logits(params, q, k, w_gq, w_gk, q_head_logits, k_head_logits, stream) -> int:

@@ -32,6 +32,15 @@ int launch_gate_logits(const sla_params& p, const void* q, const void* k, const 
                        float* kl, int compute_units, hipStream_t stream);
 int launch_short_conv_silu(int dtype, int B, int T, int C, int taps, const void* x, const float* w, void* y,
                            hipStream_t stream);
+size_t feature_map_partials(int B, int T);
+int launch_feature_map(int dtype, int B, int T, int C, int taps, int head_width, float eps, const void* x, const float* w,
+                       void* y, hipStream_t stream);
+int launch_feature_map_backward(int dtype, int B, int T, int C, int taps, int head_width, float eps, const void* x,
+                                const float* w, const void* dy, void* dx, float* dw, float* workspace,
+                                hipStream_t stream);
+int launch_gate_logits_backward(const sla_params& p, const void* x, const float* w, const float* dl, void* dx, float* dw,
+                                float* workspace, hipStream_t stream);
+size_t gate_logits_backward_workspace_floats(const sla_params& p);
 unsigned int* device_status_word();
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
@@ -481,6 +490,72 @@ int sla_short_conv_silu(int dtype, int B, int T, int channels, int taps, const v
     if ((x && !aligned16(x)) || (y && !aligned16(y)) || (w && !aligned16(w))) return SLA_ERR_ALIGN;
     if (B == 0 || T == 0) return SLA_OK;
     return sla::launch_short_conv_silu(dtype, B, T, channels, taps, x, w, y, (hipStream_t)stream);
+}
+
+static int check_feature_map(int dtype, int B, int T, int channels, int taps, int head_width, float eps) {
+    if (dtype != SLA_F32 && dtype != SLA_BF16) return SLA_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0 || channels < 8 || channels > 65536 || (channels & 7)) return SLA_ERR_SHAPE;
+    if (taps < 1 || taps > 4) return SLA_ERR_UNSUPPORTED;
+    if ((int64_t)B * T > (int64_t)1 << 30) return SLA_ERR_SHAPE;
+    if (head_width != 0) {
+        if (head_width != 32 && head_width != 64 && head_width != 128) return SLA_ERR_UNSUPPORTED;
+        // the lanes of a head must share one 16-lane row of a wave: whole rows of 128 channels
+        if (channels % 128 != 0) return SLA_ERR_SHAPE;
+        if (!(eps >= 0.f)) return SLA_ERR_SHAPE;
+    }
+    return SLA_OK;
+}
+
+int sla_short_conv_silu_l2(int dtype, int B, int T, int channels, int taps, int head_width, float eps, const void* x,
+                           const float* w, void* y, void* stream) {
+    const int rc = check_feature_map(dtype, B, T, channels, taps, head_width, eps);
+    if (rc != SLA_OK) return rc;
+    if (B > 0 && T > 0 && (!x || !w || !y)) return SLA_ERR_NULL;
+    if ((x && !aligned16(x)) || (y && !aligned16(y)) || (w && !aligned16(w))) return SLA_ERR_ALIGN;
+    if (B == 0 || T == 0) return SLA_OK;
+    return sla::launch_feature_map(dtype, B, T, channels, taps, head_width, eps, x, w, y, (hipStream_t)stream);
+}
+
+size_t sla_short_conv_silu_l2_backward_workspace_bytes(int B, int T, int channels, int taps) {
+    if (B <= 0 || T <= 0 || channels < 8 || taps < 1 || taps > 4) return 0;
+    return sla::feature_map_partials(B, T) * (size_t)channels * taps * sizeof(float);
+}
+
+int sla_short_conv_silu_l2_backward(int dtype, int B, int T, int channels, int taps, int head_width, float eps,
+                                    const void* x, const float* w, const void* dy, void* dx, float* dw,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_feature_map(dtype, B, T, channels, taps, head_width, eps);
+    if (rc != SLA_OK) return rc;
+    if (!dw && channels > 0) return SLA_ERR_NULL;
+    if (B > 0 && T > 0 && (!x || !w || !dy || !dx)) return SLA_ERR_NULL;
+    const void* ptrs[] = {x, w, dy, dx, dw, workspace};
+    for (const void* q : ptrs)
+        if (q && !aligned16(q)) return SLA_ERR_ALIGN;
+    if (B == 0 || T == 0) return SLA_OK;  // nothing flows; dw is left untouched
+    if (!workspace || sla_short_conv_silu_l2_backward_workspace_bytes(B, T, channels, taps) > workspace_bytes)
+        return SLA_ERR_WORKSPACE;
+    return sla::launch_feature_map_backward(dtype, B, T, channels, taps, head_width, eps, x, w, dy, dx, dw,
+                                            (float*)workspace, (hipStream_t)stream);
+}
+
+size_t sla_gate_logits_backward_workspace_bytes(const sla_params* p) {
+    if (check_params(p) != SLA_OK || p->B == 0 || p->T == 0) return 0;
+    return sla::gate_logits_backward_workspace_floats(*p) * sizeof(float);
+}
+
+int sla_gate_logits_backward(const sla_params* p, const void* x, const float* w, const float* d_head_logits, void* dx,
+                             float* dw, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_params(p);
+    if (rc != SLA_OK) return rc;
+    if (p->flags != 0) return SLA_ERR_UNSUPPORTED;
+    const bool work = p->B > 0 && p->T > 0;
+    if (work && (!x || !w || !d_head_logits || !dx || !dw)) return SLA_ERR_NULL;
+    const void* ptrs[] = {x, w, d_head_logits, dx, dw, workspace};
+    for (const void* q : ptrs)
+        if (q && !aligned16(q)) return SLA_ERR_ALIGN;
+    if (!work) return SLA_OK;
+    if (!workspace || sla_gate_logits_backward_workspace_bytes(p) > workspace_bytes) return SLA_ERR_WORKSPACE;
+    return sla::launch_gate_logits_backward(*p, x, w, d_head_logits, dx, dw, (float*)workspace, (hipStream_t)stream);
 }
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {

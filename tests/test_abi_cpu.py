@@ -25,8 +25,8 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = re.findall(r"\b(sla_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_forward_static", "sla_init", "sla_device_status", "sla_static_scratch_bytes", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    names = re.findall(r"\b(sla_[a-z0-9_]+)\s*\(", header)
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_forward_static", "sla_init", "sla_device_status", "sla_static_scratch_bytes", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_short_conv_silu_l2", "sla_short_conv_silu_l2_backward", "sla_short_conv_silu_l2_backward_workspace_bytes", "sla_gate_logits_backward", "sla_gate_logits_backward_workspace_bytes", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -353,3 +353,28 @@ def test_narrow_keys_are_forward_only(lib):
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dk=32, dv=64)) == 0
     args = (A, A, A, A, A, A, 0)
     assert sla.sla_decode_step(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) == -3
+
+
+def test_prologue_gradient_entry_points_validate(lib):
+    fm = sla.sla_short_conv_silu_l2
+    assert fm(sla.BF16, 2, 64, 256, 4, 64, 1e-6, A, A, A, 0) in (0, -5)  # valid: reaches the launch (no device here)
+    assert fm(sla.BF16, 2, 64, 256, 4, 48, 1e-6, A, A, A, 0) == -3         # head width not built
+    assert fm(sla.BF16, 2, 64, 200, 4, 64, 1e-6, A, A, A, 0) == -2         # channels not whole rows of 128
+    assert fm(sla.BF16, 2, 64, 256, 5, 64, 1e-6, A, A, A, 0) == -3
+    assert fm(sla.BF16, 2, 64, 256, 4, 64, -1.0, A, A, A, 0) == -2
+    assert fm(sla.BF16, 2, 64, 256, 4, 0, 0.0, 0, A, A, 0) == -1
+    assert fm(sla.BF16, 0, 64, 256, 4, 64, 1e-6, 0, 0, 0, 0) == 0
+    bw = sla.sla_short_conv_silu_l2_backward
+    need = sla.sla_short_conv_silu_l2_backward_workspace_bytes(2, 100, 256, 4)
+    assert need == 2 * 2 * 256 * 4 * 4
+    assert bw(sla.BF16, 2, 100, 256, 4, 64, 1e-6, A, A, A, A, A, A, need - 1, 0) == -6
+    assert bw(sla.BF16, 2, 100, 256, 4, 64, 1e-6, A, A, A, A, 0, A, need, 0) == -1
+    assert bw(sla.BF16, 2, 100, 256, 4, 64, 1e-6, A, A, A + 2, A, A, A, need, 0) == -4
+    gl = sla.sla_gate_logits_backward
+    p = _ok_params()
+    n = sla.sla_gate_logits_backward_workspace_bytes(p)
+    assert n > 0 and n % (4 * 128 * 4) == 0
+    assert gl(p, A, A, A, A, A, A, n - 1, 0) == -6
+    assert gl(p, A, A, 0, A, A, A, n, 0) == -1
+    assert gl(_ok_params(dk=48), A, A, A, A, A, A, n, 0) == -3
+    assert gl(_ok_params(B=0), 0, 0, 0, 0, 0, 0, 0, 0) == 0
