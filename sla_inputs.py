@@ -104,6 +104,13 @@ def workload(name: str) -> Workload:
         # ... and its H = 16 point (Sec. 5.6: the gain of the head competition grows with the head count): keys of
         # width 32, values of width 64.
         "gla_paper_h16": Workload("gla_paper_h16", GLA, "bf16", 8, 4096, 16, 32, 64, SEED_BASE + 12),
+        # The same 4-head, 4K-token, batch-8 regime for the two other variants (32 sequences: the few-sequence case).
+        # Their reference models use key heads of width 256, which the kernels do not tile; keys are taken at width
+        # 128 as for GLA, values at 256.
+        "retnet_paper_h4": Workload("retnet_paper_h4", RETNET, "bf16", 8, 4096, 4, 128, 256, SEED_BASE + 13),
+        "gdn_paper_h4": Workload(
+            "gdn_paper_h4", GDN, "bf16", 8, 4096, 4, 128, 256, SEED_BASE + 14, qk_prep="l2", decay_div=8.0
+        ),
         # One decode step (T = 1) over a serving-sized batch: the recurrent form, one token per sequence.
         "decode_gla": Workload("decode_gla", GLA, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 7),
         "decode_retnet": Workload("decode_retnet", RETNET, "bf16", 64, 1, 16, 128, 128, SEED_BASE + 8),
@@ -115,7 +122,7 @@ def workload(name: str) -> Workload:
 
 
 WORKLOAD_NAMES = ("gla_tiny", "retnet", "gla_train", "gdn", "gla_long", "retnet_train", "gdn_train", "gla_paper_h4",
-                  "gla_paper_h8", "gla_paper_h16")
+                  "gla_paper_h8", "gla_paper_h16", "retnet_paper_h4", "gdn_paper_h4")
 DECODE_WORKLOAD_NAMES = ("decode_gla", "decode_retnet", "decode_gdn")
 
 

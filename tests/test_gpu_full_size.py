@@ -10,13 +10,13 @@ from gpu_util import check, rel_err, run_gpu
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
-@pytest.mark.parametrize("name", ["retnet", "gla_train", "gdn", "retnet_train", "gdn_train", "gla_paper_h16"])
+@pytest.mark.parametrize("name", ["retnet", "gla_train", "gdn", "retnet_train", "gdn_train", "gla_paper_h16", "gdn_paper_h4"])
 def test_full_size_workload(name):
     w = si.workload(name)
     check(w.variant, si.generate(w), w.dtype, label=f"full {name}")
 
 
-@pytest.mark.parametrize("name", ["retnet", "gla_long", "gla_paper_h4", "gla_paper_h8"])
+@pytest.mark.parametrize("name", ["retnet", "gla_long", "gla_paper_h4", "gla_paper_h8", "retnet_paper_h4"])
 def test_full_size_segmented(name):
     """The 32-sequence workloads in the schedule bench.py times: the library's own choice of segments."""
     import torch
