@@ -244,41 +244,90 @@ __device__ __forceinline__ void flag_signal(lds_int* f) {
 struct Ring {
     lds_int* ready;
     lds_int* done;
+    lds_int* out;          // consumer waves that have left the block's output tile(s) in the slot
     unsigned int* status;  // where an expired wait is recorded
 };
-// The counters sit behind the slots; zeroed by the first eight threads before anyone uses them.
+// The counters sit behind the slots; zeroed by the first twelve threads before anyone uses them.
 __device__ __forceinline__ Ring ring_init(unsigned char* smem, int slot_bytes, int tid, unsigned int* status) {
     lds_int* f = (lds_int*)(smem + kSlots * slot_bytes);
-    if (tid < 2 * kSlots) f[tid] = 0;
+    if (tid < 3 * kSlots) f[tid] = 0;
     __syncthreads();
-    return Ring{f, f + kSlots, status};
+    return Ring{f, f + kSlots, f + 2 * kSlots, status};
 }
 
 // One member wave of a producer team: load(block, regs) issues the global loads of a block, stage(block, regs,
 // slot) turns them into LDS tiles.  Two register sets: the loads of the team's next two blocks are in flight while
 // a block is staged, and every step issues exactly one set of loads (past the end it re-reads the last block), so
 // the wait in front of stage() leaves the newer set in flight on every path.
-template <typename Pre, typename Load, typename Stage>
+//
+// Output tiles (dk sweep; the dq and dv sweeps are not bound by their stores and ran slower with the extra LDS
+// traffic): the consumers leave a block's results in the slot ([16 tokens][64 columns] tiles) and raise ring.out; the
+// team member given a `flush` writes the tiles of the block that was in the slot to global memory (whole 128-byte
+// rows, streaming stores) before it stages the next one, and the last ones after its loop.
+struct NoFlush {
+    __device__ __forceinline__ void operator()(int, unsigned char*) const {}
+};
+template <typename Pre, typename Load, typename Stage, typename Flush = NoFlush>
 __device__ __forceinline__ void producer_run(const Ring& ring, unsigned char* smem, int slot_bytes, int team, int nb,
-                                             Load load, Stage stage) {
+                                             Load load, Stage stage, Flush flush = Flush()) {
     if (team >= nb) return;
+    constexpr bool kFlush = !__is_same(Flush, NoFlush);
     Pre ra, rb;
     load(team, ra);
     load(min(team + kSlots, nb - 1), rb);
+    unsigned char* buf = smem + team * slot_bytes;
     int I = team, use = 0;
+    auto drain = [&]() {  // the output of block I - kSlots, once every consumer wave has left it in the slot
+        if constexpr (kFlush) {
+            if (use > 0) {
+                flag_wait(ring.out + team, kConsumers * use, ring.status);
+                flush(I - kSlots, buf);
+            }
+        }
+    };
     while (true) {
         flag_wait(ring.done + team, kConsumers * use, ring.status);  // the consumers have left the block that was here
-        stage(I, ra, smem + team * slot_bytes);
+        drain();
+        stage(I, ra, buf);
         load(min(I + 2 * kSlots, nb - 1), ra);
         flag_signal(ring.ready + team);
         I += kSlots, ++use;
         if (I >= nb) break;
         flag_wait(ring.done + team, kConsumers * use, ring.status);
-        stage(I, rb, smem + team * slot_bytes);
+        drain();
+        stage(I, rb, buf);
         load(min(I + 2 * kSlots, nb - 1), rb);
         flag_signal(ring.ready + team);
         I += kSlots, ++use;
         if (I >= nb) break;
+    }
+    drain();
+}
+
+// A [16 tokens][64 columns] bf16 output tile.  A row is 16 units of four columns; unit c of token t sits at
+// position c ^ t of its row, which spreads the consumers' writes (one unit per lane, 16 tokens apart) and the
+// flushing wave's reads (a whole row per 16 lanes) over the banks.
+constexpr int kTileBytes = kTok * kCols * 2;
+__device__ __forceinline__ void tile_put(unsigned char* tile, int t, int unit, u2 v) {
+    *(u2*)(tile + ((t * 16 + (unit ^ t)) << 3)) = v;
+}
+// Tokens t0 .. t0 + 15 of the sequence (those below T), columns col0 .. col0 + 63 of a tensor of width D whose row of
+// token tau is wide0 + tau * wstep.  STREAM: non-temporal stores (the tensor is not read again by this call).
+template <bool STREAM>
+__device__ __forceinline__ void tile_flush(const unsigned char* tile, uint16_t* dst, size_t wide0, size_t wstep, int D,
+                                           int col0, int t0, int T, int lane) {
+    const int unit = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = (lane >> 4) + 4 * i;
+        const u2 v = *(const u2*)(tile + ((t * 16 + (unit ^ t)) << 3));
+        if (t0 + t < T) {
+            u2* p = (u2*)(dst + (wide0 + (size_t)(t0 + t) * wstep) * D + col0 + 4 * unit);
+            if constexpr (STREAM)
+                __builtin_nontemporal_store(v, p);
+            else
+                *p = v;
+        }
     }
 }
 
@@ -410,7 +459,7 @@ struct SmemF {
     static constexpr int oQS = oTOT + kCols * 4;
     static constexpr int oGQ = oQS + kTok * kFS * 2;
     static constexpr int bytes = oGQ + kTok * 4;
-    static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
+    static constexpr int total = kSlots * bytes + 3 * kSlots * 4;
     static_assert(oV % 16 == 0 && oVT % 16 == 0 && oKDT % 16 == 0 && oPF % 16 == 0 && oTOT % 16 == 0 &&
                       oQS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
@@ -520,7 +569,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dq_kernel(const BArgs a) 
     }
     for (int blk = 0; blk < nb; ++blk) {
         consumer_acquire(ring, blk);
-        const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
+        unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = blk * kTok;
         const uint16_t* DOp = (const uint16_t*)(buf + L::oDO);
         const uint16_t* Vp = (const uint16_t*)(buf + L::oV);
@@ -624,11 +673,13 @@ struct SmemK {
     static constexpr int oKS = oQDQ + kTok * kFS * 4;
     static constexpr int oGQ = oKS + kTok * kFS * 2;
     static constexpr int oGK = oGQ + kTok * 4;
-    static constexpr int bytes = oGK + kTok * 4;
+    static constexpr int oTILE = oGK + kTok * 4;  // the block's dk and (GLA) dlog_decay tiles, where they fit
+    static constexpr bool tiled = kSlots * (oTILE + 2 * kTileBytes) + 3 * kSlots * 4 <= 160 * 1024;
+    static constexpr int bytes = oTILE + (tiled ? 2 * kTileBytes : 0);
     // The block's q * dq sums (64 floats, GLA) live in the four padding columns of the 16 rows of the q * dq tile:
     // the sums of key columns 4 m .. 4 m + 3 are floats 64 .. 67 of row m.
     static constexpr int bs_offset(int d) { return oQDQ + ((d >> 2) * kFS + kCols + (d & 3)) * 4; }
-    static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
+    static constexpr int total = kSlots * bytes + 3 * kSlots * 4;
     static_assert(oV % 16 == 0 && oDYT % 16 == 0 && oQAT % 16 == 0 && oCUM % 16 == 0 && oQDQ % 16 == 0 &&
                       oKS % 16 == 0 && oGQ % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
@@ -729,35 +780,45 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                         ((float*)(buf + L::oGK))[t] = ok ? p.gk : 0.f;
                     }
                 });
-        } else {
-            producer_run<PreRows<R>>(
-                ring, smem, L::bytes, team, nb,
-                [&](int I, PreRows<R>& p) {
+        } else {  // dout and v; this member also writes the finished dk (and dlog_decay) tiles out
+            auto load_rows = [&](int I, PreRows<R>& p) {
 #pragma unroll
-                    for (int rep = 0; rep < R; ++rep) {
-                        const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
-                        const int tau = min((nb - 1 - I) * kTok + t, T - 1);
-                        const size_t row = (tok0 + tau) * H + h, wrow = wide0 + (size_t)tau * wstep;
-                        p.a[rep] = load16(a.dout + wrow * DV + 8 * e8);
-                        p.b[rep] = load16(a.v + wrow * DV + 8 * e8);
-                        p.gq[rep] = a.gq[row];
-                    }
-                },
-                [&](int I, const PreRows<R>& p, unsigned char* buf) {
+                for (int rep = 0; rep < R; ++rep) {
+                    const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
+                    const int tau = min((nb - 1 - I) * kTok + t, T - 1);
+                    const size_t row = (tok0 + tau) * H + h, wrow = wide0 + (size_t)tau * wstep;
+                    p.a[rep] = load16(a.dout + wrow * DV + 8 * e8);
+                    p.b[rep] = load16(a.v + wrow * DV + 8 * e8);
+                    p.gq[rep] = a.gq[row];
+                }
+            };
+            auto stage_rows = [&](int I, const PreRows<R>& p, unsigned char* buf) {
 #pragma unroll
-                    for (int rep = 0; rep < R; ++rep) {
-                        const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
-                        const bool ok = (nb - 1 - I) * kTok + t < T;
-                        const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
-                        put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
-                        put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
-                        u4 dy;
+                for (int rep = 0; rep < R; ++rep) {
+                    const int t = r, e8 = g + 4 * rep;  // token = lane % 16: the transposed stores of a wave hit disjoint banks
+                    const bool ok = (nb - 1 - I) * kTok + t < T;
+                    const u4 dx = keep(p.a[rep], ok), vx = keep(p.b[rep], ok);
+                    put_perm<DV>((uint16_t*)(buf + L::oDO), t, e8, dx);
+                    put_perm<DV>((uint16_t*)(buf + L::oV), t, e8, vx);
+                    u4 dy;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            dy[j] = pack2(p.gq[rep] * bf_lo(dx[j]), p.gq[rep] * bf_hi(dx[j]));
-                        put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
-                    }
-                });
+                    for (int j = 0; j < 4; ++j)
+                        dy[j] = pack2(p.gq[rep] * bf_lo(dx[j]), p.gq[rep] * bf_hi(dx[j]));
+                    put_T((uint16_t*)(buf + L::oDYT), 8 * e8, t, dy);
+                }
+            };
+            if constexpr (L::tiled) {
+                producer_run<PreRows<R>>(ring, smem, L::bytes, team, nb, load_rows, stage_rows,
+                                         [&](int I, unsigned char* buf) {
+                                             const int t0 = (nb - 1 - I) * kTok;
+                                             tile_flush<true>(buf + L::oTILE, a.dk, wide0, wstep, DK, sbase, t0, T, lane);
+                                             if constexpr (VAR == SLA_GLA)
+                                                 tile_flush<true>(buf + L::oTILE + kTileBytes, a.dld, wide0, wstep, DK,
+                                                                  sbase, t0, T, lane);
+                                         });
+            } else {
+                producer_run<PreRows<R>>(ring, smem, L::bytes, team, nb, load_rows, stage_rows);
+            }
         }
         return;
     }
@@ -781,7 +842,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
     }
     for (int blk = 0; blk < nb; ++blk) {
         consumer_acquire(ring, blk);
-        const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
+        unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
         const bool anchored = VAR == SLA_GLA && is_anchor(nb - 1 - blk);
         // The state entering this block, kept by the dq sweep: asked for here and used after the update, where the
@@ -852,9 +913,11 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
         const int tok = t0 + r;
         const bool ok = tok < T;
         const size_t row = (tok0 + (ok ? tok : 0)) * H + h, wrow = wide0 + (size_t)(ok ? tok : 0) * wstep;
+        const u2 dk4 = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+        if constexpr (L::tiled) tile_put(buf + L::oTILE, r, 4 * wave + g, dk4);
         if (ok) {
             if (g == 0) a.part_k[((size_t)(slice * 4 + wave) * a.rows * H) + row] = part;
-            *(u2*)(a.dk + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dkv[0], dkv[1]), pack2(dkv[2], dkv[3])};
+            if constexpr (!L::tiled) *(u2*)(a.dk + wrow * DK + sbase + cb + 4 * g) = dk4;
         }
         if constexpr (VAR == SLA_GLA) {
             // dlog_decay_t = sum_{s >= t} (q_s dq_s - k_s dk_s): inside the block one suffix scan of the per-token
@@ -867,8 +930,13 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dk_kernel(const BArgs a) 
                 dl[i] = s + run[i];
                 run[i] += bs4[i] + row_first(s);
             }
-            if (ok) *(u2*)(a.dld + wrow * DK + sbase + cb + 4 * g) = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
+            const u2 dl4 = u2{pack2(dl[0], dl[1]), pack2(dl[2], dl[3])};
+            if constexpr (L::tiled)
+                tile_put(buf + L::oTILE + kTileBytes, r, 4 * wave + g, dl4);
+            else if (ok)
+                *(u2*)(a.dld + wrow * DK + sbase + cb + 4 * g) = dl4;
         }
+        if constexpr (L::tiled) flag_signal(ring.out + (blk & (kSlots - 1)));
         if constexpr (VAR == SLA_GLA) update_state();
         if (anchored) {  // the sum over all later tokens equals rowsum(dS * S) at this boundary: take it from there
             float z = 0.f;
@@ -899,7 +967,7 @@ struct SmemV {
     static constexpr int oAT = oDYT + kCols * kTS * 2;
     static constexpr int oGK = oAT + DK * 4;
     static constexpr int bytes = oGK + kTok * 4;
-    static constexpr int total = kSlots * bytes + 2 * kSlots * 4;
+    static constexpr int total = kSlots * bytes + 3 * kSlots * 4;
     static_assert(oKD % 16 == 0 && oKB % 16 == 0 && oQAT % 16 == 0 && oDYT % 16 == 0 &&
                       oAT % 16 == 0 && oGK % 16 == 0 && bytes % 16 == 0,
                   "tiles stay 16-byte aligned");
@@ -1032,7 +1100,7 @@ __global__ __launch_bounds__(kBwdThreads) void sla_bwd_dv_kernel(const BArgs a) 
     }
     for (int blk = 0; blk < nb; ++blk) {
         consumer_acquire(ring, blk);
-        const unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
+        unsigned char* buf = smem + (blk & (kSlots - 1)) * L::bytes;
         const int t0 = (nb - 1 - blk) * kTok;
         const uint16_t* QAp = (const uint16_t*)(buf + L::oQA);
         const uint16_t* KDp = (const uint16_t*)(buf + L::oKD);
