@@ -30,6 +30,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "sla.h"
 
 namespace sla {
@@ -1193,12 +1195,19 @@ __global__ __launch_bounds__(kEwThreads) void sla_bwd_gates_kernel(const float* 
 }
 
 // dlogits = G * (dG - sum_h G dG), dG summed over its partial planes
+// Packed batches (cu != null): rows outside [cu[0], cu[B]) belong to no sequence; the sweeps never wrote their
+// partial planes, and their gradients are not written either.
 __global__ __launch_bounds__(kEwThreads) void sla_bwd_logits_kernel(const float* g, const float* part, int planes,
-                                                                     float* dl, size_t rows, int H) {
+                                                                     float* dl, size_t rows, int H, const int* cu,
+                                                                     int B) {
     __shared__ float sx[kEwThreads];
     const int per = kEwThreads / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
     const size_t row = (size_t)blockIdx.x * per + lr;
-    const bool ok = lr < per && row < rows;
+    bool ok = lr < per && row < rows;
+    if (cu) {
+        const int total = (int)rows, lo = min(max(cu[0], 0), total), hi = min(max(cu[B], lo), total);
+        ok = ok && row >= (size_t)lo && row < (size_t)hi;
+    }
     float dg = 0.f, gv = 0.f;
     if (ok) {
         for (int p = 0; p < planes; ++p) dg += part[(size_t)p * rows * H + row * H + h];
@@ -1226,12 +1235,18 @@ bool allow_lds(K kernel, int lds) {
 template <int VAR, int DK, int DV>
 int launch_sweeps(const BArgs& a, hipStream_t stream) {
     constexpr int ldsF = SmemF<DV>::total, ldsV = SmemV<DK>::total, ldsK = SmemK<DV>::total;
-    static bool configured = false;  // once per instantiation; not a stream operation
-    if (!configured) {
+    // once per device and instantiation (bit d = done on device d); not a stream operation
+    static std::atomic<uint64_t> configured{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return SLA_ERR_HIP;
+    }
+    if (!((configured.load(std::memory_order_acquire) >> dev) & 1u)) {
         if (!allow_lds(sla_bwd_dq_kernel<VAR, DK, DV>, ldsF) || !allow_lds(sla_bwd_dv_kernel<VAR, DK, DV>, ldsV) ||
             !allow_lds(sla_bwd_dk_kernel<VAR, DK, DV>, ldsK))
             return SLA_ERR_HIP;
-        configured = true;
+        configured.fetch_or(uint64_t(1) << dev, std::memory_order_release);
     }
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kBwdThreads);
@@ -1454,10 +1469,10 @@ int launch_backward_some(const sla_params& p, const void* q, const void* k, cons
     if (rc != SLA_OK || rows == 0 || sweeps != 7) return rc;
     // the planes of one gate are n floats apart (n >= rows * H); the kernel indexes them by rows * H
     hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gq, (const float*)a.part_q,
-                       p.dk / 16, dql, rows, p.H);
+                       p.dk / 16, dql, rows, p.H, cu, p.B);
     if (kl)
         hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gk,
-                           (const float*)a.part_k, p.dk / 16, dkl, rows, p.H);
+                           (const float*)a.part_k, p.dk / 16, dkl, rows, p.H, cu, p.B);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 

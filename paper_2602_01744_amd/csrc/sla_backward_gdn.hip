@@ -32,6 +32,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "sla.h"
 
 namespace sla {
@@ -642,7 +644,11 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int 
     __shared__ float sx[kEw];
     const int H = a.H, per = kEw / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
     const size_t rows = a.rows, row = (size_t)blockIdx.x * per + lr;
-    const bool ok = lr < per && row < rows;
+    bool ok = lr < per && row < rows;
+    if (a.cu) {  // packed batch: rows outside [cu[0], cu[B]) belong to no sequence and are left untouched
+        const int total = (int)rows, lo = min(max(a.cu[0], 0), total), hi = min(max(a.cu[a.B], lo), total);
+        ok = ok && row >= (size_t)lo && row < (size_t)hi;
+    }
     const size_t i = ok ? row * H + h : 0;
     float dgq = 0.f, dgk = 0.f, db = 0.f, gq = 0.f, gk = 0.f;
     if (ok) {
@@ -724,12 +730,18 @@ int launch_sweeps(const GArgs& a, hipStream_t stream) {
     constexpr int lds2 = 2 * 4 * (2 * kChunk * DK + 3 * kChunk * kSlice + kScal * kChunk);
     constexpr int lds3 = 2 * 4 * (3 * kChunk * DV + 3 * kChunk * kSlice + kScal * kChunk);
     static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024, "fits the LDS of a compute unit");
-    static bool configured = false;  // once per instantiation; not a stream operation
-    if (!configured) {
+    // once per device and instantiation (bit d = done on device d); not a stream operation
+    static std::atomic<uint64_t> configured{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return SLA_ERR_HIP;
+    }
+    if (!((configured.load(std::memory_order_acquire) >> dev) & 1u)) {
         if (!allow_lds(gdn_bwd_state_kernel<E, DK, DV>, lds1) || !allow_lds(gdn_bwd_cotangent_kernel<E, DK, DV>, lds2) ||
             !allow_lds(gdn_bwd_key_kernel<E, DK, DV, false>, lds3) || !allow_lds(gdn_bwd_key_kernel<E, DK, DV, true>, lds3))
             return SLA_ERR_HIP;
-        configured = true;
+        configured.fetch_or(uint64_t(1) << dev, std::memory_order_release);
     }
     const unsigned bh = (unsigned)(a.B * a.H);
     const dim3 block(kThreads);

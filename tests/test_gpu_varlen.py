@@ -146,3 +146,71 @@ def test_varlen_equals_batch_for_equal_lengths():
                                     fl(g["log_decay"]), None, cu)
     torch.cuda.synchronize()
     assert torch.equal(fl(out), out2) and torch.equal(fin, fin2)
+
+
+@pytest.mark.parametrize("variant", [GLA, GDN])
+def test_tokens_outside_every_sequence_are_left_untouched(variant):
+    """cu_seqlens[0] > 0 and cu_seqlens[B] < T: the tokens before the first and after the last sequence belong to no
+    sequence.  Forward and backward must neither read them into a result nor write their rows: every output tensor
+    is pre-filled with a canary, which must survive there, while the sequences still agree with the oracle."""
+    import torch
+    import paper_2602_01744_amd as sla
+
+    H, dk, dv, lead, tail = 3, 64, 64, 11, 5
+    lengths = [40, 0, 70]
+    T = lead + sum(lengths) + tail
+    d = si.custom(variant, "bf16", B=1, T=T, H=H, dk=dk, dv=dv, seed=1430 + variant)
+    cu = (lead + np.concatenate([[0], np.cumsum(lengths)])).astype(np.int32)
+    B = len(lengths)
+    cot = si.cotangents(1, T, H, dk, dv, seed=1431)
+    g, _ = to_device(d, "bf16", variant)
+    sq = lambda t: None if t is None else (t if t.dim() == 1 else t[0].contiguous())
+    q, k, v, ql, kl, ld, beta = (sq(g[n]) for n in ("q", "k", "v", "q_logits", "k_logits", "log_decay", "beta"))
+    dout = torch.from_numpy(cot["d_out"][0]).to(torch.bfloat16).cuda()
+    cud = torch.from_numpy(cu).cuda()
+    CAN = 7.0
+    can = lambda like: torch.full_like(like, CAN)
+    out, fin = can(v), torch.empty((B, H, dk, dv), dtype=torch.float32, device="cuda")
+    ptr = lambda t: None if t is None else t.data_ptr()
+    st = torch.cuda.current_stream().cuda_stream
+    params = sla.SlaParams(variant, sla.BF16, B, T, H, dk, dv, 0, 0, 1)
+    rc = sla.sla_forward_varlen(params, ptr(q), ptr(k), ptr(v), ptr(ql), ptr(kl), ptr(ld), ptr(beta), ptr(cud), None,
+                                ptr(out), ptr(fin), st)
+    assert rc == 0
+    gr = {n: can(t) for n, t in (("dq", q), ("dk", k), ("dv", v), ("dql", ql), ("dkl", kl))}
+    if variant == GLA:
+        gr["dld"] = can(ld)
+        need = sla.sla_backward_varlen_workspace_bytes(params)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        rc = sla.sla_backward_varlen(params, ptr(q), ptr(k), ptr(v), ptr(ql), ptr(kl), ptr(ld), ptr(cud), None, ptr(dout),
+                                     None, ptr(gr["dq"]), ptr(gr["dk"]), ptr(gr["dv"]), ptr(gr["dql"]), ptr(gr["dkl"]),
+                                     ptr(gr["dld"]), None, ptr(ws), need, st)
+    else:
+        gr["dld"], gr["dbeta"] = can(ld), can(beta)
+        need = sla.sla_backward_gdn_varlen_workspace_bytes(params)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        rc = sla.sla_backward_gdn_varlen(params, ptr(q), ptr(k), ptr(v), ptr(ql), ptr(kl), ptr(ld), ptr(beta), ptr(cud),
+                                         None, ptr(dout), None, ptr(gr["dq"]), ptr(gr["dk"]), ptr(gr["dv"]),
+                                         ptr(gr["dql"]), ptr(gr["dkl"]), ptr(gr["dld"]), ptr(gr["dbeta"]), None, ptr(ws),
+                                         need, st)
+    assert rc == 0
+    torch.cuda.synchronize()
+    lo, hi = int(cu[0]), int(cu[-1])
+    for name, t in [("out", out)] + list(gr.items()):
+        x = t.float().cpu().numpy()
+        assert np.all(x[:lo] == CAN) and np.all(x[hi:] == CAN), f"{name}: rows outside the sequences were written"
+        assert np.all(np.isfinite(x[lo:hi])), name
+    # the sequences themselves: first and last against the oracle
+    names = {"dq": "dq", "dk": "dk", "dv": "dv", "dql": "dq_logits", "dkl": "dk_logits", "dld": "dlog_decay"}
+    if variant == GDN:
+        names["dbeta"] = "dbeta"
+    for i in (0, 2):
+        ds, a, b = seq(d, variant, cu, i)
+        ro, _ = oracle.forward(variant, ds["q"], ds["k"], ds["v"], ds["q_logits"], ds["k_logits"], ds["log_decay"],
+                               ds["beta"], None)
+        assert rel_err(out.float().cpu().numpy().astype(np.float64)[a:b], ro[0]) <= TOL["bf16"]
+        ref = ob.backward(variant, ds["q"], ds["k"], ds["v"], ds["q_logits"], ds["k_logits"], ds["log_decay"],
+                          cot["d_out"][:, a:b], beta=ds["beta"])
+        for n, rn in names.items():
+            e = rel_err(gr[n].float().cpu().numpy().astype(np.float64)[a:b], ref[rn][0])
+            assert e <= TOL["bf16"], (i, n, e)
