@@ -579,7 +579,7 @@ int sla_backward_segments(const sla_params* p, int compute_units) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
     if (compute_units <= 0) return SLA_ERR_SHAPE;
-    if (p->B == 0 || p->T == 0 || p->variant == SLA_GDN || p->flags != 0) return 1;
+    if (p->B == 0 || p->T == 0 || p->variant == SLA_GDN || p->flags != 0 || p->dk < 64) return 1;  // no backward there
     const int64_t wgs = (int64_t)p->B * p->H * ((p->dk < p->dv ? p->dk : p->dv) / 64);
     const int want = (int)((compute_units + wgs - 1) / wgs);
     if (want <= 1) return 1;
