@@ -8,6 +8,8 @@
                    differentiation token by token, fp64 numpy; pinned by finite
                    differences and by autograd through the parallel form.
 
+``backward``     – the same gradients in plain C (``sla_oracle_backward.c``, OpenMP over (batch, head)), pinned
+                   against ``sla_backward``; fast enough for whole workloads.
 ``sla_prologue`` – gate projections, short convolution + SiLU (+ L2 normalisation) and their
                    backward, fp64 numpy; pinned by finite differences and library autograd.
 
@@ -27,14 +29,16 @@ from . import sla_backward, sla_numpy, sla_prologue  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sla_oracle.c")
+_SRC_BWD = os.path.join(_HERE, "sla_oracle_backward.c")
 _LIB = os.path.join(_HERE, "libsla_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile ``sla_oracle.c`` with gcc (-O2, OpenMP) into this directory."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    """Compile ``sla_oracle.c`` and ``sla_oracle_backward.c`` with gcc (-O2, OpenMP) into this directory."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BWD))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, _SRC_BWD, "-lm"])
     return _LIB
 
 
@@ -47,6 +51,8 @@ def _load():
         dp = ctypes.POINTER(ctypes.c_double)
         lib.sla_oracle_forward.restype = ctypes.c_int
         lib.sla_oracle_forward.argtypes = [ctypes.c_int] * 6 + [fp] * 8 + [dp, dp, ctypes.c_int]
+        lib.sla_oracle_backward.restype = ctypes.c_int
+        lib.sla_oracle_backward.argtypes = [ctypes.c_int] * 6 + [fp] * 10 + [dp] * 8 + [ctypes.c_int]
         lib.sla_oracle_threads.restype = ctypes.c_int
         lib.sla_oracle_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -105,3 +111,32 @@ def forward(
     if rc != 0:
         raise RuntimeError(f"sla_oracle_forward failed with code {rc}")
     return out, fin
+
+
+def backward(variant: int, q, k, v, q_logits, k_logits, log_decay, d_out, initial_state=None, d_final_state=None,
+             beta=None, nthreads: int = 0):
+    """Gradients of the forward by the C oracle (``sla_oracle_backward.c``).  Same conventions and the same dict of
+    fp64 results as ``sla_backward.backward``."""
+    lib = _load()
+    q, k, v, do = _f32(q), _f32(k), _f32(v), _f32(d_out)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    ql, kl, ld, bt = _f32(q_logits), _f32(k_logits), _f32(log_decay), _f32(beta)
+    s0, dsf = _f32(initial_state), _f32(d_final_state)
+    want = {0: (H,), 1: (B, T, H, dk), 2: (B, T, H)}[variant]
+    assert ld.shape == want and do.shape == v.shape
+    z = lambda *shape: np.zeros(shape, dtype=np.float64)
+    res = {
+        "dq": z(B, T, H, dk), "dk": z(B, T, H, dk), "dv": z(B, T, H, dv), "dq_logits": z(B, T, H),
+        "dk_logits": None if kl is None else z(B, T, H), "dlog_decay": z(*want),
+        "dbeta": z(B, T, H) if variant == 2 else None, "dinitial_state": z(B, H, dk, dv),
+    }
+    f, d = ctypes.c_float, ctypes.c_double
+    rc = lib.sla_oracle_backward(
+        variant, B, T, H, dk, dv, _ptr(q, f), _ptr(k, f), _ptr(v, f), _ptr(ql, f), _ptr(kl, f), _ptr(ld, f), _ptr(bt, f),
+        _ptr(s0, f), _ptr(do, f), _ptr(dsf, f), _ptr(res["dq"], d), _ptr(res["dk"], d), _ptr(res["dv"], d),
+        _ptr(res["dq_logits"], d), _ptr(res["dk_logits"], d), _ptr(res["dlog_decay"], d), _ptr(res["dbeta"], d),
+        _ptr(res["dinitial_state"], d), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"sla_oracle_backward failed with code {rc}")
+    return res

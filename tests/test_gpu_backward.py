@@ -6,7 +6,8 @@ import numpy as np
 import pytest
 
 import sla_inputs as si
-from gpu_util import GLA, RETNET, TOL, rel_err, to_device
+import oracle
+from gpu_util import GLA, RETNET, TOL, rel_err, to_device, worst_slice_err
 from oracle import sla_backward as ob
 
 pytestmark = pytest.mark.gpu
@@ -29,13 +30,21 @@ def run_backward(variant, d, cot, s0=None, want_ds0=False, segments=1):
     return {n: None if t is None else t.to(torch.float32).cpu().numpy().astype(np.float64) for n, t in res.items()}
 
 
-def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_rows=None, segments=1):
+# Worst (batch, head) slice, each on its own scale, at the same bar.  The quantities that are small by cancellation
+# where a head's own values are (logit gradients; the GLA decay gradient, a difference of two running sums) are held
+# to the bar on the scale of their batch row instead.
+SLICE_TOL = {}
+
+
+def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_rows=None, segments=1, c_oracle=False):
+    """c_oracle: the reference is the C gradient oracle (whole workloads in seconds) instead of the numpy one."""
     got = run_backward(variant, d, cot, s0, want_ds0, segments)
     rows = slice(None) if batch_rows is None else batch_rows
     sub = lambda a: None if a is None else (a if a.ndim == 1 else a[rows])
-    ref = ob.backward(variant, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
-                      sub(d["log_decay"]), sub(cot["d_out"]), sub(s0), sub(cot["d_final_state"]))
-    errs = {}
+    fn = oracle.backward if c_oracle else ob.backward
+    ref = fn(variant, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
+             sub(d["log_decay"]), sub(cot["d_out"]), sub(s0), sub(cot["d_final_state"]))
+    errs, slices = {}, {}
     for n, rn in NAMES.items():
         x, r = got[n], ref[rn]
         if n == "dlog_decay" and variant == RETNET:
@@ -49,9 +58,17 @@ def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_row
         x = x[rows]
         assert np.all(np.isfinite(x)), f"{label}: non-finite {n}"
         errs[n] = rel_err(x, r)
-    print(f"[backward parity] {label} " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
+        if n.endswith("_head_logits") or n == "dlog_decay":
+            # a head's logit gradient is G (dG - sum_h G dG), small by cancellation where the gate is: held to the
+            # tolerance on the scale of its batch row, not on its own
+            slices[n] = max(rel_err(x[i], r[i]) for i in range(r.shape[0]))
+        else:
+            slices[n] = worst_slice_err(x, r, 1 if n == "d_initial_state" else 2)
+    print(f"[backward parity] {label} " + " ".join(f"{n}={e:.2e}/{slices[n]:.2e}" for n, e in errs.items()), flush=True)
     for n, e in errs.items():
         assert e <= TOL["bf16"], f"{label}: {n} error {e:.3e} > {TOL['bf16']}"
+        bar = SLICE_TOL.get(n, TOL["bf16"])
+        assert slices[n] <= bar, f"{label}: {n} error of the worst (batch, head) slice {slices[n]:.3e} > {bar}"
     return got, ref
 
 
@@ -173,20 +190,20 @@ def test_segment_count_chosen_for_the_device():
 
 
 def test_segment_schedule_on_the_paper_shape():
-    """gla_paper_h4 (B=8, T=4096, H=4, dk=128, dv=256: 32 sequences) in 4 segments; the oracle runs on one row."""
+    """gla_paper_h4 (B=8, T=4096, H=4, dk=128, dv=256: 32 sequences) in 4 segments; every batch row is compared."""
     w = si.workload("gla_paper_h4")
     d = si.generate(w)
     cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
-    check_backward(w.variant, d, cot, label="gla_paper_h4, 4 segments", batch_rows=slice(0, 1), segments=4)
+    check_backward(w.variant, d, cot, label="gla_paper_h4, 4 segments", segments=4, c_oracle=True)
 
 
 @pytest.mark.parametrize("name", ["gla_train", "retnet_train"])
 def test_full_size(name):
-    """The bench workload, in the launch configuration bench.py times; the oracle runs on two batch rows."""
+    """The bench workload, in the launch configuration bench.py times; every batch row against the C gradient oracle."""
     w = si.workload(name)
     d = si.generate(w)
     cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
-    got, _ = check_backward(w.variant, d, cot, label=name, batch_rows=slice(0, 2))
+    got, _ = check_backward(w.variant, d, cot, label=name, c_oracle=True)
     # properties that hold for every batch row, whatever the size: all values finite, and the logit gradients of a
     # token sum to zero over the heads (Eq. 4's softmax)
     for n, x in got.items():

@@ -31,12 +31,16 @@ def run_backward_gdn(d, cot, s0=None, want_ds0=False, dtype="bf16"):
     return {n: None if t is None else t.to(torch.float32).cpu().numpy().astype(np.float64) for n, t in res.items()}
 
 
-def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=None, dtype="bf16"):
+def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=None, dtype="bf16", c_oracle=False):
+    """c_oracle: the reference is the C gradient oracle (whole workloads in seconds) instead of the numpy one."""
+    import oracle
+
     got = run_backward_gdn(d, cot, s0, want_ds0, dtype)
     rows = slice(None) if batch_rows is None else batch_rows
     sub = lambda a: None if a is None else a[rows]
-    ref = ob.backward(GDN, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
-                      sub(d["log_decay"]), sub(cot["d_out"]), sub(s0), sub(cot["d_final_state"]), beta=sub(d["beta"]))
+    fn = oracle.backward if c_oracle else ob.backward
+    ref = fn(GDN, sub(d["q"]), sub(d["k"]), sub(d["v"]), sub(d["q_logits"]), sub(d["k_logits"]),
+             sub(d["log_decay"]), sub(cot["d_out"]), sub(s0), sub(cot["d_final_state"]), beta=sub(d["beta"]))
     errs = {}
     for n, rn in NAMES.items():
         x, r = got[n], ref[rn]
@@ -136,11 +140,12 @@ def test_long_sequence():
 
 
 def test_full_size():
-    """The bench workload (gdn: B=8, T=4096, H=16, d=128), as bench.py launches it; the oracle runs on one row."""
+    """The bench workload (gdn: B=8, T=4096, H=16, d=128), as bench.py launches it; every batch row against the C
+    gradient oracle."""
     w = si.workload("gdn")
     d = si.generate(w)
     cot = si.cotangents(w.B, w.T, w.H, w.dk, w.dv, seed=w.seed + 50)
-    got, _ = check_backward_gdn(d, cot, label="gdn", batch_rows=slice(0, 1))
+    got, _ = check_backward_gdn(d, cot, label="gdn", c_oracle=True)
     for n, x in got.items():  # every batch row: finite, and logit gradients summing to zero over the heads
         assert x is None or np.all(np.isfinite(x)), n
     for n in ("dq_head_logits", "dk_head_logits"):

@@ -73,3 +73,26 @@ def test_backward_head_major_matches_token_major(variant):
             assert torch.equal(got[n].permute(0, 2, 1, 3), ref[n]), n
     for n in ("dq_head_logits", "dk_head_logits", "d_initial_state"):
         assert torch.equal(got[n], ref[n]), n
+
+
+@pytest.mark.timeout(600)
+def test_head_major_full_size_against_the_oracle():
+    """The headline workload with its wide tensors laid out [B,H,T,d], compared with the CPU oracle directly (not only
+    with the other layout's result): out, final state, and the worst (batch, head) slice."""
+    import torch
+    import paper_2602_01744_amd as sla
+    from gpu_util import TOL, rel_err, run_oracle, worst_slice_err
+
+    w = si.workload("gla_train")
+    d = si.generate(w)
+    g, _ = to_device(d, w.dtype, w.variant)
+    hm = lambda t: t.permute(0, 2, 1, 3).contiguous()
+    out, fin = sla.forward(w.variant, hm(g["q"]), hm(g["k"]), hm(g["v"]), g["q_logits"], g["k_logits"],
+                           hm(g["log_decay"]), head_major=True)
+    torch.cuda.synchronize()
+    o = out.permute(0, 2, 1, 3).to(torch.float32).cpu().numpy().astype(np.float64)
+    f = fin.cpu().numpy().astype(np.float64)
+    ro, rf = run_oracle(w.variant, d)
+    tol = TOL[w.dtype]
+    assert rel_err(o, ro) <= tol and rel_err(f, rf) <= tol
+    assert worst_slice_err(o, ro, 2) <= tol and worst_slice_err(f, rf, 1) <= tol

@@ -230,3 +230,30 @@ def test_retnet_is_gla_with_constant_decay():
     for n in ("dq", "dk", "dv", "dq_logits", "dk_logits", "dinitial_state"):
         np.testing.assert_allclose(g[n], gg[n], rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(g["dlog_decay"], gg["dlog_decay"].sum(axis=(0, 1, 3)), rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("with_kl,with_states", [(True, True), (False, False), (True, False)])
+def test_c_gradient_oracle_equals_the_numpy_one(variant, with_kl, with_states):
+    """oracle/sla_oracle_backward.c is a second implementation of oracle/sla_backward.py (itself pinned above by
+    finite differences and autograd): every gradient agrees to fp64 rounding, for a length that spans several of
+    its 64-token checkpoints and ends inside one."""
+    import oracle
+    import sla_inputs as si
+
+    B, T, H, dk, dv = 2, 150, 3, 8, 5
+    d = si.custom(variant, "f32", B=B, T=T, H=H, dk=dk, dv=dv, seed=700 + variant)
+    cot = si.cotangents(B, T, H, dk, dv, seed=701, dtype="f32", final_state=with_states)
+    s0 = si.initial_state(B, H, dk, dv, seed=702) if with_states else None
+    kl = d["k_logits"] if with_kl else None
+    ref = sla_backward.backward(variant, d["q"], d["k"], d["v"], d["q_logits"], kl, d["log_decay"], cot["d_out"], s0,
+                                cot.get("d_final_state"), beta=d["beta"])
+    got = oracle.backward(variant, d["q"], d["k"], d["v"], d["q_logits"], kl, d["log_decay"], cot["d_out"], s0,
+                          cot.get("d_final_state"), beta=d["beta"], nthreads=2)
+    assert set(got) == set(ref)
+    for name in ref:
+        if ref[name] is None:
+            assert got[name] is None, name
+            continue
+        scale = max(float(np.max(np.abs(ref[name]))), 1e-30)
+        assert float(np.max(np.abs(got[name] - ref[name]))) <= 1e-12 * scale, name
