@@ -35,6 +35,7 @@
 #include <atomic>
 
 #include "sla.h"
+#include "sla_gdn_block.h"
 
 namespace sla {
 
@@ -769,6 +770,11 @@ int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
 // [B,T,H]; dk/8 planes of <d_final, S_T> [B,H]; res and w [B,T,H,dv]; the first part of dk [B,T,H,dk].
 size_t backward_gdn_workspace_floats(const sla_params& p, bool packed) {
     const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
+    if (p.dtype == SLA_BF16) {  // block form: a plane per 16 columns; the sweeps' own workspace behind them
+        const size_t pv = (size_t)p.dv / 16, pk = (size_t)p.dk / 16;
+        return n * (3 + 2 * pv + pk) + round4(pk * p.B * p.H) +
+               gdn_block_workspace_floats(p.B, p.T, p.H, p.dk, p.dv, packed);
+    }
     const size_t pv = (size_t)p.dv / (4 * CW), pk = (size_t)p.dk / (4 * CW);  // planes per compute wave and slice
     return n * (3 + 2 * pv + pk) + round4(pk * p.B * p.H) + 2 * round4(rows * p.H * p.dv) + round4(rows * p.H * p.dk);
 }
@@ -778,7 +784,9 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
                         const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
                         float* dbeta, float* ds0, float* ws, const int* cu, hipStream_t stream) {
     const size_t rows = cu ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
-    const int pv = p.dv / (4 * CW), pk = p.dk / (4 * CW);  // partial planes: one per compute wave and slice
+    const bool block_form = p.dtype == SLA_BF16;  // bf16: block form on the matrix cores; fp32: token by token
+    // partial planes: one per compute wave and slice
+    const int pv = block_form ? p.dv / 16 : p.dv / (4 * CW), pk = block_form ? p.dk / 16 : p.dk / (4 * CW);
     if (rows == 0) {
         if (ds0 && p.B > 0) {  // no tokens: the cotangent of the final state is that of the initial state
             const size_t count = (size_t)p.B * p.H * p.dk * p.dv / 4;
@@ -811,10 +819,20 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
 
     int rc = launch_bwd_gates(ql, kl, gq, gk, rows, p.H, stream);
     if (rc != SLA_OK) return rc;
-    if (p.dtype == SLA_BF16)
-        rc = p.dk == 64 ? launch_dv<uint16_t, 64>(a, p.dv, stream) : launch_dv<uint16_t, 128>(a, p.dv, stream);
-    else
+    if (block_form) {
+        GdnBlockArgs g;
+        g.q = (const uint16_t*)q; g.k = (const uint16_t*)k; g.v = (const uint16_t*)v; g.dout = (const uint16_t*)dout;
+        g.ld = ld; g.beta = beta; g.gq = gq; g.gk = gk; g.s0 = s0; g.dsf = dsf;
+        g.dq = (uint16_t*)dq; g.dk = (uint16_t*)dk; g.dv = (uint16_t*)dv; g.ds0 = ds0;
+        g.part_q = a.part_q; g.part_k = a.part_k; g.part_b = a.part_b; g.corr = a.corr;
+        g.plane = n;
+        g.block_ws = a.res;  // everything behind the planes
+        g.rows = rows; g.cu = cu;
+        g.B = p.B; g.T = p.T; g.H = p.H; g.dim_k = p.dk; g.dim_v = p.dv;
+        rc = launch_gdn_block_sweeps(g, stream);
+    } else {
         rc = p.dk == 64 ? launch_dv<float, 64>(a, p.dv, stream) : launch_dv<float, 128>(a, p.dv, stream);
+    }
     if (rc != SLA_OK) return rc;
     const unsigned per = kEw / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
     hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, pk, pv, dql, kl ? dkl : nullptr,

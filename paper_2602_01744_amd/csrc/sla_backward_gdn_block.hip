@@ -1,0 +1,1022 @@
+// Backward pass of the gated delta rule (Softmax-GatedDeltaNet, Sec. 5.1) in block form on the matrix cores, bf16.
+//
+// Tokens are taken in blocks of C = 32.  Inside a block, with c_t the running sum of the log-decays, p_t = e^(c_t),
+// A = p_C and D[t][j] = p_t / p_j (j <= t), the recurrence
+//     res_t = G^K_t v_t - k_t (a_t S_{t-1})      u_t = beta_t res_t      S_t = a_t S_{t-1} + k_t^T u_t
+// (the chunkwise form of Sec. 3.2 applied to the delta rule) becomes, for the block's entry state S0,
+//     (I + Lk diag(beta)) Res = G^K V - diag(p) K S0,    Lk = strict_tril(D * K K^T),      U = diag(beta) Res,
+//     S_C = A S0 + K^T diag(A / p) U,                     Y = diag(p) Q S0 + Lq U,          Lq = tril(D * Q K^T),
+// and its derivative, for the cotangent X1 of S_C and dY = diag(G^Q) dOut:
+//     dU  = Lq^T dY + diag(A / p) K X1
+//     w   = (I + Lk diag(beta))^-T (beta * dU)      (the cotangent of res, what the token recurrence calls beta du)
+//     du  = dU - Lk^T w
+//     dv  = G^K w      dG^K = w . v      dbeta = du . res
+//     X0  = A X1 + Q^T diag(p) dY - K^T diag(p) w
+//     dq' = diag(p) dOut S0^T + N' K                 N' = tril(D * dOut U^T)      dq = G^Q dq'    dG^Q = q . dq'
+//     dk  = diag(A / p) U X1^T - diag(p) w S0^T + (M + M^T) K + N^T Q
+//           M = strict_tril(-D * w U^T)              N = diag(G^Q) N'
+// The decay gradient needs no state product (see sla_backward_gdn.hip).  The 32 x 32 matrices depend on one block
+// only and are produced by two kernels that run over all blocks in parallel (`pre`: from q, k, the decays and beta;
+// `mid`: from res, w and dOut); what remains serial are four sweeps that each carry one state tile in fp32 matrix-core
+// accumulators, as in the token-recurrent version: (1) forward, S sliced over value columns -> res; (2) backward, X
+// sliced over value columns -> w, dv, dG^K, dbeta, d_initial_state; (3) backward, X^T sliced over key columns -> the
+// part of dk that needs X; (4) forward, S^T sliced over key columns -> dq, dG^Q, dk, <d_final, S_T>.
+//
+// A sweep workgroup: four compute waves (16 columns of the 64-column slice each, the whole contraction dimension)
+// and four loader waves that copy the next block's rows from global memory to LDS, row-major and unchanged, into the
+// other half of a double buffer; one barrier per block.  Every operand orientation comes from the same row-major
+// arrays: rows as they are (`op_rows`), columns through the transposing LDS read of gfx950 (`op_cols`,
+// ds_read_b64_tr_b16: the 16 lanes of a group fetch 4 rows x 16 columns and each receives one column), and an
+// accumulator tile serves directly as the next product's operand (rows 4g..4g+3 of lane group g are its contraction
+// slots).  All products are v_mfma_f32_16x16x32_bf16; the contraction index of slot (half, g, e) is 16 half + 4 g + e
+// in both operands.
+//
+// Intermediates in the workspace: res and w as bf16 [block][head][column][32 tokens] (a lane's four tokens of an
+// accumulator tile are one 8-byte store), the 32 x 32 matrices as bf16, per-token scalars as fp32, the X-part of dk as
+// fp32 [token][head][dk].
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <atomic>
+
+#include "sla.h"
+#include "sla_gdn_block.h"
+
+namespace sla {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+typedef __attribute__((ext_vector_type(4))) short s4;
+typedef __attribute__((ext_vector_type(8))) short s8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf8;
+typedef uint16_t bf;
+typedef __attribute__((address_space(3))) s4 lds_s4;
+
+constexpr int C = 32;            // tokens per block
+constexpr int kThreads = 512;    // four compute waves + four loader waves
+constexpr int kLoaders = 256;
+constexpr int kCols = 64;        // columns of a state slice per workgroup
+constexpr int kSm = 40;          // LDS row stride, in elements, of an array with 32 elements per row
+constexpr int kSl = 72;          // ... of a 64-column slice of token rows
+constexpr float kLog2e = 1.4426950408889634f;
+
+// per-token scalars of a block: kinds x 32 floats
+enum { kP = 0, kAP = 1, kBeta = 2, kGq = 3, kGk = 4, kCl = 5, kA = 6, kKinds = 8 };
+constexpr int kScal = kKinds * C;            // floats per (block, head)
+constexpr int kMat = C * C;                  // elements of a 32 x 32 matrix
+enum { mT1 = 0, mT2 = 1, mT3 = 2, mT4 = 3, kPreMats = 4 };   // pre-pass: T', (T' diag-beta)^T, (diag(G^Q) Lq)^T, -Lk^T
+enum { mMs = 0, mNT = 1, mNp = 2, kMidMats = 3 };            // mid pass: M + M^T, N^T, N'
+
+__device__ __forceinline__ float bf_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // the hardware conversion: nearest even, NaN kept
+    bf2 t;
+    t.x = (__bf16)lo;
+    t.y = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, t);
+}
+__device__ __forceinline__ u2 pack4(f4 x) { return u2{pack2(x[0], x[1]), pack2(x[2], x[3])}; }
+__device__ __forceinline__ s8 pack8(f4 x, f4 y) {
+    const u4 t = {pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(y[0], y[1]), pack2(y[2], y[3])};
+    return __builtin_bit_cast(s8, t);
+}
+__device__ __forceinline__ f4 unpack4(u2 t) { return f4{bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y)}; }
+__device__ __forceinline__ f4 unpack4(s4 v) { return unpack4(__builtin_bit_cast(u2, v)); }
+// the operand with slot (half, g, e) multiplied by lo[e] (half 0) or hi[e] (half 1)
+__device__ __forceinline__ s8 scale8(s8 v, f4 lo, f4 hi) {
+    const u4 t = __builtin_bit_cast(u4, v);
+    return pack8(unpack4(u2{t.x, t.y}) * lo, unpack4(u2{t.z, t.w}) * hi);
+}
+__device__ __forceinline__ s8 join(s4 a, s4 b) { return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7); }
+__device__ __forceinline__ void mma(f4& c, s8 a, s8 b) {
+    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), c, 0, 0, 0);
+}
+
+// Operand of a 32-slot product from a row-major LDS array: lane (r, g) takes row `row`, slots k0 + 4g .. and
+// k0 + 16 + 4g ..
+__device__ __forceinline__ s8 op_rows(const bf* base, int stride, int row, int k0, int g) {
+    const bf* p = base + row * stride + k0 + 4 * g;
+    return join(*(const s4*)p, *(const s4*)(p + 16));
+}
+// The same from the array's columns: lane (r, g) takes column c0 + r, slot rows j0 + 4g .. and j0 + 16 + 4g ..
+// (transposing read: lane l of a group of 16 addresses row l/4, columns 4 (l%4) .. +3, and receives column l of the
+// four rows).
+__device__ __forceinline__ s4 lds_tr(const bf* p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)p); }
+__device__ __forceinline__ s8 op_cols(const bf* base, int stride, int j0, int c0, int r, int g) {
+    const bf* p = base + (j0 + 4 * g + (r >> 2)) * stride + c0 + 4 * (r & 3);
+    return join(lds_tr(p), lds_tr(p + 16 * stride));
+}
+// Four rows j0 + 4g .. +3 of column c0 + r (an accumulator-shaped piece of a row-major array).
+__device__ __forceinline__ f4 tile_cols(const bf* base, int stride, int j0, int c0, int r, int g) {
+    return unpack4(lds_tr(base + (j0 + 4 * g + (r >> 2)) * stride + c0 + 4 * (r & 3)));
+}
+__device__ __forceinline__ f4 sc4(const float* sc, int kind, int t) { return *(const f4*)(sc + kind * C + t); }
+
+// Sum over the four lane groups of the wave; every lane gets the total.
+__device__ __forceinline__ float all_groups(float x) {
+    const uint32_t xi = __float_as_uint(x);
+    const u2 a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    const uint32_t yi = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    const u2 b = __builtin_amdgcn_permlane32_swap(yi, yi, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row_all(float x) {  // sum over the 16 lanes of a group
+    x += dpp_move<0x128>(x);
+    x += dpp_move<0x124>(x);
+    x += dpp_move<0x122>(x);
+    x += dpp_move<0x121>(x);
+    return x;
+}
+
+// ---- rows of a 2-D array, global -> registers -> LDS, by the 256 loader threads, 16 bytes a piece -----------
+template <int R, int RB>
+struct Rows {
+    static constexpr int per = RB / 16, pieces = R * per, N = (pieces + kLoaders - 1) / kLoaders;
+    u4 x[N];
+    // rows >= valid read as zero (valid >= 1)
+    __device__ __forceinline__ void load(const void* g, size_t gstride, int valid, int lt) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = lt + kLoaders * n, row = it / per, c = it - row * per;
+            const bool ok = it < pieces && row < valid;
+            const u4 v = *(const u4*)((const unsigned char*)g + (size_t)(ok ? row : 0) * gstride + 16 * (ok ? c : 0));
+            x[n] = ok ? v : u4{0u, 0u, 0u, 0u};
+        }
+    }
+    __device__ __forceinline__ void put(unsigned char* lds, int lstride, int lt) const {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int it = lt + kLoaders * n, row = it / per, c = it - row * per;
+            if (it < pieces) *(u4*)(lds + row * lstride + 16 * c) = x[n];
+        }
+    }
+};
+
+// ---- what a workgroup owns ----------------------------------------------------------------------------------
+struct Seq {
+    int bh, b, h, slice;   // bh < 0: nothing to do
+    int T, nblk;           // tokens and blocks of the sequence
+    size_t tok0;           // its first token
+    size_t blk0;           // its first block in the workspace
+};
+// blocks of the workspace: rectangular batches B * ceil(T/C); packed ones floor(T/C) + B + 1, sequence b starting at
+// block cu[b]/C + b (the ranges of consecutive sequences cannot overlap: floor(x) + ceil(y) <= floor(x + y) + 1).
+__host__ __device__ inline size_t ws_blocks(int B, int T, bool packed) {
+    return packed ? (size_t)T / C + (size_t)B + 1 : (size_t)B * ((T + C - 1) / C);
+}
+__device__ __forceinline__ void seq_of(const GdnBlockArgs& a, int b, Seq& s) {
+    s.T = a.T;
+    s.tok0 = (size_t)b * a.T;
+    s.blk0 = (size_t)b * ((a.T + C - 1) / C);
+    if (a.cu) {  // offsets are clamped into the tensors whatever cu holds
+        const int start = min(max(a.cu[b], 0), a.T), end = min(max(a.cu[b + 1], start), a.T);
+        s.T = end - start;
+        s.tok0 = (size_t)start;
+        s.blk0 = (size_t)(start / C) + (size_t)b;
+    }
+    s.nblk = (s.T + C - 1) / C;
+}
+// blockIdx.x % 8 is the XCD a workgroup lands on; the slices of a (sequence, head) pair go to one XCD, whose L2 then
+// fetches what they share once.  The grid is 8 * nslices * ceil(pairs / 8); the padding has nothing to do.
+__device__ __forceinline__ Seq where(const GdnBlockArgs& a, int nslices) {
+    Seq s;
+    const int pairs = a.B * a.H, xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
+    int wg;
+    if (a.cu) {
+        const int pair = (place / nslices) * 8 + xcd;
+        wg = pair < pairs ? pair * nslices + place % nslices : -1;
+    } else {
+        wg = xcd * (int)(gridDim.x >> 3) + place;
+        if (wg >= pairs * nslices) wg = -1;
+    }
+    s.bh = wg < 0 ? -1 : wg / nslices;
+    s.slice = wg < 0 ? 0 : wg % nslices;
+    s.b = s.h = s.T = s.nblk = 0;
+    s.tok0 = s.blk0 = 0;
+    if (s.bh >= 0) {
+        s.b = s.bh / a.H;
+        s.h = s.bh % a.H;
+        seq_of(a, s.b, s);
+    }
+    return s;
+}
+
+// workspace areas
+struct Areas {
+    float* scal;   // [blocks][H][kKinds][C]
+    bf* pre;       // [blocks][H][kPreMats][C][C]
+    bf* mid;       // [blocks][H][kMidMats][C][C]
+    bf* res;       // [blocks][H][dv][C]
+    bf* w;         // [blocks][H][dv][C]
+    float* dk2;    // [rows][H][dk]
+};
+__host__ __device__ inline size_t round4(size_t n) { return (n + 3) & ~(size_t)3; }
+__host__ __device__ inline Areas areas(float* ws, size_t blocks, size_t rows, int H, int dk, int dv) {
+    Areas r;
+    const size_t bh = blocks * (size_t)H;
+    float* p = ws;
+    r.scal = p; p += bh * kScal;
+    r.pre = (bf*)p; p += bh * kPreMats * kMat / 2;
+    r.mid = (bf*)p; p += bh * kMidMats * kMat / 2;
+    r.res = (bf*)p; p += bh * (size_t)dv * C / 2;
+    r.w = (bf*)p; p += bh * (size_t)dv * C / 2;
+    r.dk2 = p;
+    (void)rows; (void)dk;
+    return r;
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Pre-pass: one wave per (block, head).  Scalars, T' = (I + Lk diag(beta))^-1, and the matrices of sweep 2.
+// ------------------------------------------------------------------------------------------------------------
+// The workspace block `wb` belongs to sequence b when blk0(b) <= wb < blk0(b) + nblk(b).
+__device__ __forceinline__ bool find_block(const GdnBlockArgs& a, size_t wb, Seq& s, int& I) {
+    if (!a.cu) {
+        const int per = (a.T + C - 1) / C;
+        if (per == 0) return false;
+        s.b = (int)(wb / per);
+        if (s.b >= a.B) return false;
+        seq_of(a, s.b, s);
+        I = (int)(wb - s.blk0);
+        return true;
+    }
+    int lo = 0, hi = a.B - 1;  // last sequence whose first block is <= wb
+    while (lo < hi) {
+        const int m = (lo + hi + 1) >> 1;
+        const size_t first = (size_t)(min(max(a.cu[m], 0), a.T) / C) + (size_t)m;
+        if (first <= wb) lo = m; else hi = m - 1;
+    }
+    s.b = lo;
+    seq_of(a, lo, s);
+    if (wb < s.blk0 || wb >= s.blk0 + (size_t)s.nblk) return false;
+    I = (int)(wb - s.blk0);
+    return true;
+}
+
+template <int DK>
+__global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, const Areas ar) {
+    constexpr int RK = DK + 8;
+    __shared__ __align__(16) bf Kr[C * RK];
+    __shared__ __align__(16) bf Qr[C * RK];
+    __shared__ __align__(16) float Lf[C * 36];
+    __shared__ __align__(16) float cs[C], bs[C], gqs[C];
+    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
+    const int h = blockIdx.x % a.H;
+    const size_t wb = blockIdx.x / a.H;
+    Seq s;
+    int I = 0;
+    if (!find_block(a, wb, s, I)) return;
+    const int valid = min(C, s.T - C * I);
+    const size_t row0 = s.tok0 + (size_t)C * I;
+    // rows of k and q (zero past the sequence)
+    {
+        const size_t gstride = (size_t)a.H * DK;
+        const bf* kg = a.k + (row0 * a.H + h) * DK;
+        const bf* qg = a.q + (row0 * a.H + h) * DK;
+        constexpr int per = DK / 8;
+#pragma unroll
+        for (int n = 0; n < C * per / 64; ++n) {
+            const int it = lane + 64 * n, row = it / per, c = it - row * per;
+            const bool ok = row < valid;
+            const u4 z = {0u, 0u, 0u, 0u};
+            const u4 kv = ok ? *(const u4*)(kg + (size_t)row * gstride + 8 * c) : z;
+            const u4 qv = ok ? *(const u4*)(qg + (size_t)row * gstride + 8 * c) : z;
+            *(u4*)(Kr + row * RK + 8 * c) = kv;
+            *(u4*)(Qr + row * RK + 8 * c) = qv;
+        }
+    }
+    // per-token scalars: lane t (and t + 32, which repeats it)
+    const int t = lane & 31;
+    const bool tv = t < valid;
+    const size_t si = (row0 + (tv ? t : 0)) * a.H + h;
+    const float ldt = tv ? a.ld[si] * kLog2e : 0.f;
+    const float bt = tv ? a.beta[si] : 0.f, gqt = tv ? a.gq[si] : 0.f, gkt = tv ? a.gk[si] : 0.f;
+    float c = ldt;  // inclusive running sum over the 32 tokens (both halves of the wave run the same scan)
+#pragma unroll
+    for (int d = 1; d < C; d *= 2) {
+        const float o = __shfl_up(c, d, C);
+        if (t >= d) c += o;
+    }
+    const float c_end = __shfl(c, C - 1, C);
+    if (lane < C) {
+        cs[t] = c;
+        bs[t] = bt;
+        gqs[t] = gqt;
+        float* sc = ar.scal + ((wb * a.H + h) * (size_t)kScal);
+        sc[kP * C + t] = __builtin_amdgcn_exp2f(c);
+        sc[kAP * C + t] = __builtin_amdgcn_exp2f(c_end - c);
+        sc[kBeta * C + t] = bt;
+        sc[kGq * C + t] = gqt;
+        sc[kGk * C + t] = gkt;
+        sc[kCl * C + t] = c;
+        sc[kA * C + t] = __builtin_amdgcn_exp2f(c_end);
+        sc[7 * C + t] = 0.f;
+    }
+    __syncthreads();
+    bf* mats = ar.pre + (wb * a.H + h) * (size_t)(kPreMats * kMat);
+    // Gram tiles (tau, tau'): lane (r, g) holds rows t = 16 tau + 4g + i, column j = 16 tau' + r
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile) {
+        const int ta = tile >> 1, tb = tile & 1;
+        u2 zq = {0u, 0u};
+        bf* t3 = mats + mT3 * kMat + (16 * tb + r) * C + 16 * ta + 4 * g;
+        bf* t4 = mats + mT4 * kMat + (16 * tb + r) * C + 16 * ta + 4 * g;
+        if (tb > ta) {  // above the diagonal: zero
+            *(u2*)t3 = zq;
+            *(u2*)t4 = zq;
+            continue;
+        }
+        f4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kq = 0; kq < DK; kq += 32) {
+            const s8 bk = op_rows(Kr, RK, 16 * tb + r, kq, g);
+            mma(kk, op_rows(Kr, RK, 16 * ta + r, kq, g), bk);
+            mma(qk, op_rows(Qr, RK, 16 * ta + r, kq, g), bk);
+        }
+        const int j = 16 * tb + r;
+        const float cj = cs[j], bj = bs[j];
+        const f4 ct = *(const f4*)(cs + 16 * ta + 4 * g), gq4 = *(const f4*)(gqs + 16 * ta + 4 * g);
+        f4 lq, lk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tt = 16 * ta + 4 * g + i;
+            const float d = __builtin_amdgcn_exp2f(ct[i] - cj);
+            lq[i] = j <= tt ? d * qk[i] * gq4[i] : 0.f;
+            lk[i] = j < tt ? d * kk[i] : 0.f;
+            Lf[tt * 36 + j] = lk[i] * bj;
+        }
+        *(u2*)t3 = pack4(lq);
+        *(u2*)t4 = pack4(-lk);
+    }
+    __syncthreads();
+    // T' = (I + Lk diag(beta))^-1 by forward substitution, column `t` of the inverse in lane t:
+    //   x_j = [j == t] - sum_{i<j} Lf[j][i] x_i
+    float x[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        float acc = (j == t) ? 1.f : 0.f;
+#pragma unroll
+        for (int i4 = 0; i4 < j; i4 += 4) {
+            const f4 l = *(const f4*)(Lf + j * 36 + i4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i4 + e < j) acc -= l[e] * x[i4 + e];
+        }
+        x[j] = acc;
+    }
+    if (lane < C) {
+        bf* t1 = mats + mT1 * kMat;  // T1[j][t] = T'[j][t]: lane t holds column t
+#pragma unroll
+        for (int j = 0; j < C; ++j) t1[j * C + t] = (bf)(pack2(x[j], 0.f) & 0xffffu);
+        bf* t2 = mats + mT2 * kMat + t * C;  // T2[t][j] = T'[j][t] beta_j: row t
+#pragma unroll
+        for (int j = 0; j < C; j += 8) {
+            const f4 b0 = *(const f4*)(bs + j), b1 = *(const f4*)(bs + j + 4);
+            const u4 o = {pack2(x[j] * b0[0], x[j + 1] * b0[1]), pack2(x[j + 2] * b0[2], x[j + 3] * b0[3]),
+                          pack2(x[j + 4] * b1[0], x[j + 5] * b1[1]), pack2(x[j + 6] * b1[2], x[j + 7] * b1[3])};
+            *(u4*)(t2 + j) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Mid pass (after sweep 2): one wave per (block, head).  M + M^T, N^T, N' from res, w and dOut.
+// ------------------------------------------------------------------------------------------------------------
+template <int DV>
+__global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, const Areas ar) {
+    constexpr int RD = DV + 8;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf* Wf = (bf*)smem;                  // [DV][kSm]
+    bf* RSf = Wf + DV * kSm;             // [DV][kSm]
+    bf* dOf = RSf + DV * kSm;            // [C][RD]
+    float* Mf = (float*)(dOf + C * RD);  // [C][36]
+    float* Nf = Mf + C * 36;
+    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
+    const int h = blockIdx.x % a.H;
+    const size_t wb = blockIdx.x / a.H;
+    Seq s;
+    int I = 0;
+    if (!find_block(a, wb, s, I)) return;
+    const int valid = min(C, s.T - C * I);
+    const size_t row0 = s.tok0 + (size_t)C * I, bhi = wb * a.H + h;
+    {
+        const bf* wg = ar.w + bhi * (size_t)DV * C;
+        const bf* rg = ar.res + bhi * (size_t)DV * C;
+#pragma unroll
+        for (int n = 0; n < DV * 4 / 64; ++n) {
+            const int it = lane + 64 * n, row = it >> 2, c = it & 3;
+            *(u4*)(Wf + row * kSm + 8 * c) = *(const u4*)(wg + row * C + 8 * c);
+            *(u4*)(RSf + row * kSm + 8 * c) = *(const u4*)(rg + row * C + 8 * c);
+        }
+        const bf* og = a.dout + (row0 * a.H + h) * DV;
+        const size_t gstride = (size_t)a.H * DV;
+        constexpr int per = DV / 8;
+#pragma unroll
+        for (int n = 0; n < C * per / 64; ++n) {
+            const int it = lane + 64 * n, row = it / per, c = it - row * per;
+            const u4 z = {0u, 0u, 0u, 0u};
+            *(u4*)(dOf + row * RD + 8 * c) = row < valid ? *(const u4*)(og + (size_t)row * gstride + 8 * c) : z;
+        }
+    }
+    __syncthreads();
+    const float* sc = ar.scal + bhi * (size_t)kScal;
+    bf* mats = ar.mid + bhi * (size_t)(kMidMats * kMat);
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile) {
+        const int ta = tile >> 1, tb = tile & 1;
+        bf* nt = mats + mNT * kMat + (16 * tb + r) * C + 16 * ta + 4 * g;
+        f4 wu = {0.f, 0.f, 0.f, 0.f}, ou = {0.f, 0.f, 0.f, 0.f};
+        if (tb <= ta) {
+#pragma unroll
+            for (int n0 = 0; n0 < DV; n0 += 32) {
+                const s8 bu = op_cols(RSf, kSm, n0, 16 * tb, r, g);
+                mma(wu, op_cols(Wf, kSm, n0, 16 * ta, r, g), bu);
+                mma(ou, op_rows(dOf, RD, 16 * ta + r, n0, g), bu);
+            }
+        }
+        const int j = 16 * tb + r;
+        const float cj = sc[kCl * C + j], bj = sc[kBeta * C + j];
+        const f4 ct = sc4(sc, kCl, 16 * ta + 4 * g), gq4 = sc4(sc, kGq, 16 * ta + 4 * g);
+        f4 nn;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tt = 16 * ta + 4 * g + i;
+            const float d = __builtin_amdgcn_exp2f(ct[i] - cj) * bj;
+            const float m = j < tt ? -d * wu[i] : 0.f, np = j <= tt ? d * ou[i] : 0.f;
+            Mf[tt * 36 + j] = m;
+            Nf[tt * 36 + j] = np;
+            nn[i] = np * gq4[i];
+        }
+        *(u2*)nt = pack4(nn);
+    }
+    __syncthreads();
+    {
+        const int t = lane & 31, j0 = 16 * (lane >> 5);
+        bf* ms = mats + mMs * kMat + t * C + j0;
+        bf* np = mats + mNp * kMat + t * C + j0;
+        float m[16], n[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            m[j] = Mf[t * 36 + j0 + j] + Mf[(j0 + j) * 36 + t];
+            n[j] = Nf[t * 36 + j0 + j];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; j += 8) {
+            *(u4*)(ms + j) = u4{pack2(m[j], m[j + 1]), pack2(m[j + 2], m[j + 3]), pack2(m[j + 4], m[j + 5]),
+                                pack2(m[j + 6], m[j + 7])};
+            *(u4*)(np + j) = u4{pack2(n[j], n[j + 1]), pack2(n[j + 2], n[j + 3]), pack2(n[j + 4], n[j + 5]),
+                                pack2(n[j + 6], n[j + 7])};
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// The sweeps.  Common frame: loaders fill stage (step + 1) % 2 while the compute waves work on stage step % 2.
+// ------------------------------------------------------------------------------------------------------------
+struct Frame {
+    const GdnBlockArgs& a;
+    const Areas& ar;
+    const Seq& s;
+    __device__ __forceinline__ int valid(int I) const { return min(C, s.T - C * I); }
+    __device__ __forceinline__ size_t row0(int I) const { return s.tok0 + (size_t)C * I; }
+    __device__ __forceinline__ size_t bhi(int I) const { return (s.blk0 + (size_t)I) * a.H + s.h; }
+};
+
+// LOADER: struct with load(frame, I, lt) and put(stage, lt); BODY: callable (stage, I).
+template <bool FWD, class LOADER, class BODY, class INIT, class FINI>
+__device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, int stage_bytes, INIT&& init, BODY&& body,
+                                          FINI&& fini) {
+    const int tid = threadIdx.x, nblk = f.s.nblk;
+    auto blk = [&](int step) { return FWD ? step : nblk - 1 - step; };
+    if (tid >= kThreads - kLoaders) {
+        const int lt = tid - (kThreads - kLoaders);
+        LOADER R;
+        if (nblk > 0) {
+            R.load(f, blk(0), lt);
+            R.put(smem, lt);
+        }
+        if (nblk > 1) R.load(f, blk(1), lt);
+        __syncthreads();
+        for (int step = 0; step < nblk; ++step) {
+            if (step + 1 < nblk) R.put(smem + ((step + 1) & 1) * stage_bytes, lt);
+            if (step + 2 < nblk) R.load(f, blk(step + 2), lt);
+            __syncthreads();
+        }
+    } else {
+        init();
+        __syncthreads();
+        for (int step = 0; step < nblk; ++step) {
+            body(smem + (step & 1) * stage_bytes, blk(step));
+            __syncthreads();
+        }
+        fini();
+    }
+}
+
+// ---- sweep 1: forward, S[dk, 16 value columns per wave] -> res ------------------------------------------------
+template <int DK>
+struct Stage1 {
+    static constexpr int RK = DK + 8;
+    static constexpr int oK = 0, oV = oK + C * RK * 2, oT = oV + C * kSl * 2, oS = oT + C * kSm * 2,
+                         bytes = oS + kScal * 4;
+};
+template <int DK, int DV>
+struct Load1 {
+    Rows<C, DK * 2> k;
+    Rows<C, kCols * 2> v;
+    Rows<C, 64> t1;
+    Rows<kKinds, C * 4> sc;
+    __device__ __forceinline__ void load(const Frame& f, int I, int lt) {
+        const size_t row = f.row0(I) * f.a.H + f.s.h, bhi = f.bhi(I);
+        k.load(f.a.k + row * DK, (size_t)f.a.H * DK * 2, f.valid(I), lt);
+        v.load(f.a.v + row * DV + f.s.slice * kCols, (size_t)f.a.H * DV * 2, f.valid(I), lt);
+        t1.load(f.ar.pre + bhi * (size_t)(kPreMats * kMat) + mT1 * kMat, C * 2, C, lt);
+        sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
+    }
+    __device__ __forceinline__ void put(unsigned char* st, int lt) const {
+        typedef Stage1<DK> L;
+        k.put(st + L::oK, L::RK * 2, lt);
+        v.put(st + L::oV, kSl * 2, lt);
+        t1.put(st + L::oT, kSm * 2, lt);
+        sc.put(st + L::oS, C * 4, lt);
+    }
+};
+
+template <int DK, int DV>
+__global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockArgs a, const Areas ar) {
+    typedef Stage1<DK> L;
+    constexpr int NT = DK / 16, RK = L::RK;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Seq s = where(a, DV / kCols);
+    if (s.bh < 0) return;
+    const Frame f{a, ar, s};
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3), r = lane & 15,
+              g = lane >> 4;
+    const int n = s.slice * kCols + 16 * w + r;  // this lane's value column
+    f4 S[NT];
+    run_sweep<true, Load1<DK, DV>>(
+        f, smem, L::bytes,
+        [&]() {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    S[t][i] = a.s0 ? a.s0[((size_t)s.bh * DK + 16 * t + 4 * g + i) * DV + n] : 0.f;
+        },
+        [&](const unsigned char* st, int I) {
+            const bf* Kr = (const bf*)(st + L::oK);
+            const bf* Vs = (const bf*)(st + L::oV);
+            const bf* T1 = (const bf*)(st + L::oT);
+            const float* sc = (const float*)(st + L::oS);
+            f4 X[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 bS = pack8(S[t], S[t + 1]);
+                mma(X[0], op_rows(Kr, RK, r, 16 * t, g), bS);
+                mma(X[1], op_rows(Kr, RK, 16 + r, 16 * t, g), bS);
+            }
+            f4 Rp[2];
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta)
+                Rp[ta] = sc4(sc, kGk, 16 * ta + 4 * g) * tile_cols(Vs, kSl, 16 * ta, 16 * w, r, g) -
+                         sc4(sc, kP, 16 * ta + 4 * g) * X[ta];
+            const s8 bR = pack8(Rp[0], Rp[1]);
+            bf* dst = ar.res + (f.bhi(I) * (size_t)DV + n) * C + 4 * g;
+            f4 Up[2];
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                f4 rs = {0.f, 0.f, 0.f, 0.f};
+                mma(rs, op_rows(T1, kSm, 16 * ta + r, 0, g), bR);
+                const u2 pk = pack4(rs);
+                *(u2*)(dst + 16 * ta) = pk;
+                Up[ta] = sc4(sc, kBeta, 16 * ta + 4 * g) * sc4(sc, kAP, 16 * ta + 4 * g) * unpack4(pk);
+            }
+            const s8 bU = pack8(Up[0], Up[1]);
+            const float A = sc[kA * C];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                S[t] *= A;
+                mma(S[t], op_cols(Kr, RK, 0, 16 * t, r, g), bU);
+            }
+        },
+        [&]() {});
+}
+
+// ---- sweep 2: backward, X[dk, 16 value columns per wave] -> w, dv, dG^K, dbeta, d_initial_state -----------------
+template <int DK>
+struct Stage2 {
+    static constexpr int RK = DK + 8;
+    static constexpr int oK = 0, oQ = oK + C * RK * 2, oO = oQ + C * RK * 2, oV = oO + C * kSl * 2,
+                         oR = oV + C * kSl * 2, oT = oR + kCols * kSm * 2, oS = oT + 3 * C * kSm * 2,
+                         bytes = oS + kScal * 4;
+};
+template <int DK, int DV>
+struct Load2 {
+    Rows<C, DK * 2> k, q;
+    Rows<C, kCols * 2> o, v;
+    Rows<kCols, 64> rs;
+    Rows<3 * C, 64> t;
+    Rows<kKinds, C * 4> sc;
+    __device__ __forceinline__ void load(const Frame& f, int I, int lt) {
+        const size_t row = f.row0(I) * f.a.H + f.s.h, bhi = f.bhi(I);
+        const int valid = f.valid(I), n0 = f.s.slice * kCols;
+        k.load(f.a.k + row * DK, (size_t)f.a.H * DK * 2, valid, lt);
+        q.load(f.a.q + row * DK, (size_t)f.a.H * DK * 2, valid, lt);
+        o.load(f.a.dout + row * DV + n0, (size_t)f.a.H * DV * 2, valid, lt);
+        v.load(f.a.v + row * DV + n0, (size_t)f.a.H * DV * 2, valid, lt);
+        rs.load(f.ar.res + (bhi * (size_t)DV + n0) * C, C * 2, kCols, lt);
+        t.load(f.ar.pre + bhi * (size_t)(kPreMats * kMat) + mT2 * kMat, C * 2, 3 * C, lt);
+        sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
+    }
+    __device__ __forceinline__ void put(unsigned char* st, int lt) const {
+        typedef Stage2<DK> L;
+        k.put(st + L::oK, L::RK * 2, lt);
+        q.put(st + L::oQ, L::RK * 2, lt);
+        o.put(st + L::oO, kSl * 2, lt);
+        v.put(st + L::oV, kSl * 2, lt);
+        rs.put(st + L::oR, kSm * 2, lt);
+        t.put(st + L::oT, kSm * 2, lt);
+        sc.put(st + L::oS, C * 4, lt);
+    }
+};
+
+template <int DK, int DV>
+__global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBlockArgs a, const Areas ar) {
+    typedef Stage2<DK> L;
+    constexpr int NT = DK / 16, RK = L::RK;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Seq s = where(a, DV / kCols);
+    if (s.bh < 0) return;
+    const Frame f{a, ar, s};
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3), r = lane & 15,
+              g = lane >> 4;
+    const int n0 = s.slice * kCols, n = n0 + 16 * w + r;
+    const int plane = (n0 >> 4) + w;
+    f4 X[NT];
+    run_sweep<false, Load2<DK, DV>>(
+        f, smem, L::bytes,
+        [&]() {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    X[t][i] = a.dsf ? a.dsf[((size_t)s.bh * DK + 16 * t + 4 * g + i) * DV + n] : 0.f;
+        },
+        [&](const unsigned char* st, int I) {
+            const bf* Kr = (const bf*)(st + L::oK);
+            const bf* Qr = (const bf*)(st + L::oQ);
+            const bf* Os = (const bf*)(st + L::oO);
+            const bf* Vs = (const bf*)(st + L::oV);
+            const bf* Rs = (const bf*)(st + L::oR);
+            const bf* T2 = (const bf*)(st + L::oT);
+            const bf* T3 = T2 + C * kSm;
+            const bf* T4 = T3 + C * kSm;
+            const float* sc = (const float*)(st + L::oS);
+            f4 dU[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 bX = pack8(X[t], X[t + 1]);
+                mma(dU[0], op_rows(Kr, RK, r, 16 * t, g), bX);
+                mma(dU[1], op_rows(Kr, RK, 16 + r, 16 * t, g), bX);
+            }
+            const s8 bO = op_cols(Os, kSl, 0, 16 * w, r, g);  // dOut[t slots][column n]
+            const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                dU[ta] *= sc4(sc, kAP, 16 * ta + 4 * g);
+                mma(dU[ta], op_rows(T3, kSm, 16 * ta + r, 0, g), bO);
+            }
+            const s8 pdU = pack8(dU[0], dU[1]);
+            // identity as an operand: slot (half, g, e) is token 16 half + 4g + e; column 16 tau + r
+            s8 id[2];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const short one = (4 * g + e == r) ? (short)0x3f80 : (short)0;
+                id[0][e] = one; id[0][4 + e] = 0;
+                id[1][e] = 0;   id[1][4 + e] = one;
+            }
+            f4 wv[2], wT[2], duT[2];
+            s8 aT2[2];
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                aT2[ta] = op_rows(T2, kSm, 16 * ta + r, 0, g);
+                wv[ta] = f4{0.f, 0.f, 0.f, 0.f};
+                wT[ta] = f4{0.f, 0.f, 0.f, 0.f};
+                duT[ta] = f4{0.f, 0.f, 0.f, 0.f};
+                mma(wv[ta], aT2[ta], pdU);   // w[t = 16 ta + 4g + i][column r]
+                mma(wT[ta], pdU, aT2[ta]);   // w[t = 16 ta + r][column 4g + i]
+                mma(duT[ta], pdU, id[ta]);   // dU, transposed the same way
+            }
+            const u2 pw0 = pack4(wv[0]), pw1 = pack4(wv[1]);
+            const s8 pw = __builtin_bit_cast(s8, u4{pw0.x, pw0.y, pw1.x, pw1.y});
+            {
+                bf* dst = ar.w + (f.bhi(I) * (size_t)DV + n) * C + 4 * g;
+                *(u2*)dst = pw0;
+                *(u2*)(dst + 16) = pw1;
+            }
+            const int valid = f.valid(I);
+            const size_t row0 = f.row0(I);
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                mma(duT[ta], pw, op_rows(T4, kSm, 16 * ta + r, 0, g));  // du = dU - Lk^T w, token 16 ta + r
+                const int tt = 16 * ta + r;
+                const f4 rs4 = tile_cols(Rs, kSm, 16 * w, 16 * ta, r, g);            // res[token tt][column 16w + 4g + i]
+                const f4 v4 = unpack4(*(const s4*)(Vs + tt * kSl + 16 * w + 4 * g));  // v[token tt][the same columns]
+                float pb = 0.f, pk = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pb += duT[ta][i] * rs4[i];
+                    pk += wT[ta][i] * v4[i];
+                }
+                pb = all_groups(pb);
+                pk = all_groups(pk);
+                if (tt < valid) {
+                    const size_t at = (row0 + tt) * a.H + s.h;
+                    if (g == 0) {
+                        a.part_b[(size_t)plane * a.plane + at] = pb;
+                        a.part_k[(size_t)plane * a.plane + at] = pk;
+                    }
+                    *(u2*)(a.dv + at * DV + n0 + 16 * w + 4 * g) = pack4(wT[ta] * sc[kGk * C + tt]);
+                }
+            }
+            const f4 q0 = p0 * sc4(sc, kGq, 4 * g), q1 = p1 * sc4(sc, kGq, 16 + 4 * g);
+            const s8 bq = scale8(bO, q0, q1), bw = scale8(pw, -p0, -p1);
+            const float A = sc[kA * C];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                X[t] *= A;
+                mma(X[t], op_cols(Qr, RK, 0, 16 * t, r, g), bq);
+                mma(X[t], op_cols(Kr, RK, 0, 16 * t, r, g), bw);
+            }
+        },
+        [&]() {
+            if (a.ds0) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) a.ds0[((size_t)s.bh * DK + 16 * t + 4 * g + i) * DV + n] = X[t][i];
+            }
+        });
+}
+
+// ---- sweeps 3 and 4: X^T / S^T [dv, 16 key columns per wave] ---------------------------------------------------
+template <int DV>
+struct Stage3 {
+    static constexpr int RD = DV + 8;
+    static constexpr int oR = 0, oW = oR + DV * kSm * 2, oO = oW + DV * kSm * 2, oQ = oO + C * RD * 2,
+                         oK = oQ + C * kSl * 2, oM = oK + C * kSl * 2, oS = oM + 2 * C * kSm * 2,
+                         bytes = oS + kScal * 4;
+};
+template <int DK, int DV, int FIRST, int NMAT>  // the mid-pass matrices FIRST .. FIRST + NMAT - 1
+struct Load3 {
+    Rows<DV, 64> rs, wv;
+    Rows<C, DV * 2> o;
+    Rows<C, kCols * 2> q, k;
+    Rows<NMAT * C, 64> m;
+    Rows<kKinds, C * 4> sc;
+    __device__ __forceinline__ void load(const Frame& f, int I, int lt) {
+        const size_t row = f.row0(I) * f.a.H + f.s.h, bhi = f.bhi(I);
+        const int valid = f.valid(I), d0 = f.s.slice * kCols;
+        rs.load(f.ar.res + bhi * (size_t)DV * C, C * 2, DV, lt);
+        wv.load(f.ar.w + bhi * (size_t)DV * C, C * 2, DV, lt);
+        o.load(f.a.dout + row * DV, (size_t)f.a.H * DV * 2, valid, lt);
+        q.load(f.a.q + row * DK + d0, (size_t)f.a.H * DK * 2, valid, lt);
+        k.load(f.a.k + row * DK + d0, (size_t)f.a.H * DK * 2, valid, lt);
+        m.load(f.ar.mid + bhi * (size_t)(kMidMats * kMat) + FIRST * kMat, C * 2, NMAT * C, lt);
+        sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
+    }
+    __device__ __forceinline__ void put(unsigned char* st, int lt) const {
+        typedef Stage3<DV> L;
+        rs.put(st + L::oR, kSm * 2, lt);
+        wv.put(st + L::oW, kSm * 2, lt);
+        o.put(st + L::oO, L::RD * 2, lt);
+        q.put(st + L::oQ, kSl * 2, lt);
+        k.put(st + L::oK, kSl * 2, lt);
+        m.put(st + L::oM, kSm * 2, lt);
+        sc.put(st + L::oS, C * 4, lt);
+    }
+};
+
+template <int DK, int DV>
+__global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArgs a, const Areas ar) {
+    typedef Stage3<DV> L;
+    constexpr int NT = DV / 16, RD = L::RD;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Seq s = where(a, DK / kCols);
+    if (s.bh < 0) return;
+    const Frame f{a, ar, s};
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3), r = lane & 15,
+              g = lane >> 4;
+    const int d0 = s.slice * kCols, d = d0 + 16 * w + r;  // this lane's key column
+    f4 Xt[NT];  // Xt[t][i] = X[d][16 t + 4g + i]
+    run_sweep<false, Load3<DK, DV, mMs, 2>>(
+        f, smem, L::bytes,
+        [&]() {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                Xt[t] = a.dsf ? *(const f4*)(a.dsf + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g)
+                              : f4{0.f, 0.f, 0.f, 0.f};
+        },
+        [&](const unsigned char* st, int I) {
+            const bf* Rf = (const bf*)(st + L::oR);
+            const bf* Wf = (const bf*)(st + L::oW);
+            const bf* Of = (const bf*)(st + L::oO);
+            const bf* Qs = (const bf*)(st + L::oQ);
+            const bf* Ks = (const bf*)(st + L::oK);
+            const bf* Ms = (const bf*)(st + L::oM);
+            const bf* Nt = Ms + C * kSm;
+            const float* sc = (const float*)(st + L::oS);
+            // dk2^T[key column 4g + i][token 16 tau + r] = (A/p beta)_t sum_n X[d][n] res[t][n] + local terms
+            f4 dkT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 aX = pack8(Xt[t], Xt[t + 1]);
+                mma(dkT[0], aX, op_cols(Rf, kSm, 16 * t, 0, r, g));
+                mma(dkT[1], aX, op_cols(Rf, kSm, 16 * t, 16, r, g));
+            }
+            const s8 aK = op_cols(Ks, kSl, 0, 16 * w, r, g), aQ = op_cols(Qs, kSl, 0, 16 * w, r, g);
+            const int valid = f.valid(I);
+            const size_t row0 = f.row0(I);
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                const int tt = 16 * ta + r;
+                dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
+                mma(dkT[ta], aK, op_rows(Ms, kSm, tt, 0, g));
+                mma(dkT[ta], aQ, op_rows(Nt, kSm, tt, 0, g));
+                if (tt < valid) *(f4*)(ar.dk2 + ((row0 + tt) * a.H + s.h) * DK + d0 + 16 * w + 4 * g) = dkT[ta];
+            }
+            const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
+            const s8 bq = scale8(aQ, p0 * sc4(sc, kGq, 4 * g), p1 * sc4(sc, kGq, 16 + 4 * g));
+            const s8 bk = scale8(aK, -p0, -p1);
+            const float A = sc[kA * C];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                Xt[t] *= A;
+                mma(Xt[t], op_cols(Of, RD, 0, 16 * t, r, g), bq);
+                mma(Xt[t], op_rows(Wf, kSm, 16 * t + r, 0, g), bk);
+            }
+        },
+        [&]() {});
+}
+
+template <int DK, int DV>
+__global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockArgs a, const Areas ar) {
+    typedef Stage3<DV> L;
+    constexpr int NT = DV / 16, RD = L::RD;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Seq s = where(a, DK / kCols);
+    if (s.bh < 0) return;
+    const Frame f{a, ar, s};
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3), r = lane & 15,
+              g = lane >> 4;
+    const int d0 = s.slice * kCols, d = d0 + 16 * w + r;
+    const int plane = (d0 >> 4) + w;
+    f4 St[NT];  // St[t][i] = S[d][16 t + 4g + i]
+    run_sweep<true, Load3<DK, DV, mNp, 1>>(
+        f, smem, L::bytes,
+        [&]() {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                St[t] = a.s0 ? *(const f4*)(a.s0 + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g)
+                             : f4{0.f, 0.f, 0.f, 0.f};
+        },
+        [&](const unsigned char* st, int I) {
+            const bf* Rf = (const bf*)(st + L::oR);
+            const bf* Wf = (const bf*)(st + L::oW);
+            const bf* Of = (const bf*)(st + L::oO);
+            const bf* Qs = (const bf*)(st + L::oQ);
+            const bf* Ks = (const bf*)(st + L::oK);
+            const bf* Np = (const bf*)(st + L::oM);
+            const float* sc = (const float*)(st + L::oS);
+            const int valid = f.valid(I);
+            const size_t row0 = f.row0(I);
+            f4 dk2[2];
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                const int tt = 16 * ta + r;
+                dk2[ta] = tt < valid ? *(const f4*)(ar.dk2 + ((row0 + tt) * a.H + s.h) * DK + d0 + 16 * w + 4 * g)
+                                     : f4{0.f, 0.f, 0.f, 0.f};
+            }
+            f4 dqT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            f4 dkT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 aS = pack8(St[t], St[t + 1]);
+                mma(dqT[0], aS, op_rows(Of, RD, r, 16 * t, g));
+                mma(dqT[1], aS, op_rows(Of, RD, 16 + r, 16 * t, g));
+                mma(dkT[0], aS, op_cols(Wf, kSm, 16 * t, 0, r, g));
+                mma(dkT[1], aS, op_cols(Wf, kSm, 16 * t, 16, r, g));
+            }
+            const s8 aK = op_cols(Ks, kSl, 0, 16 * w, r, g);
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                const int tt = 16 * ta + r;
+                const float pt = sc[kP * C + tt];
+                dqT[ta] *= pt;
+                mma(dqT[ta], aK, op_rows(Np, kSm, tt, 0, g));
+                const f4 q4 = unpack4(*(const s4*)(Qs + tt * kSl + 16 * w + 4 * g));
+                float pq = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pq += q4[i] * dqT[ta][i];
+                pq = all_groups(pq);
+                if (tt < valid) {
+                    const size_t at = (row0 + tt) * a.H + s.h;
+                    if (g == 0) a.part_q[(size_t)plane * a.plane + at] = pq;
+                    *(u2*)(a.dq + at * DK + d0 + 16 * w + 4 * g) = pack4(dqT[ta] * sc[kGq * C + tt]);
+                    *(u2*)(a.dk + at * DK + d0 + 16 * w + 4 * g) = pack4(dk2[ta] - pt * dkT[ta]);
+                }
+            }
+            const s8 bk = scale8(aK, sc4(sc, kBeta, 4 * g) * sc4(sc, kAP, 4 * g),
+                                 sc4(sc, kBeta, 16 + 4 * g) * sc4(sc, kAP, 16 + 4 * g));
+            const float A = sc[kA * C];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                St[t] *= A;
+                mma(St[t], op_rows(Rf, kSm, 16 * t + r, 0, g), bk);
+            }
+        },
+        [&]() {
+            if (a.dsf) {  // <d_final, S_T> over this wave's 16 key columns
+                float acc = 0.f;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const f4 x = *(const f4*)(a.dsf + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc += x[i] * St[t][i];
+                }
+                acc = all_groups(row_all(acc));
+                if (lane == 0) a.corr[(size_t)plane * a.B * a.H + s.bh] = acc;
+            }
+        });
+}
+
+template <typename K>
+bool allow_lds(K kernel, int lds) {
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess)
+        return true;
+    (void)hipGetLastError();
+    return false;
+}
+
+template <int DK, int DV>
+int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t stream) {
+    constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 2 * Stage2<DK>::bytes, lds3 = 2 * Stage3<DV>::bytes;
+    constexpr int ldsm = 2 * DV * kSm * 2 + C * (DV + 8) * 2 + 2 * C * 36 * 4;
+    static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && ldsm <= 160 * 1024, "LDS");
+    static std::atomic<uint64_t> configured{0};  // bit d: attributes set on device d
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return SLA_ERR_HIP;
+    }
+    if (!((configured.load(std::memory_order_acquire) >> dev) & 1u)) {
+        if (!allow_lds(gdn_blk_state_kernel<DK, DV>, lds1) || !allow_lds(gdn_blk_cotangent_kernel<DK, DV>, lds2) ||
+            !allow_lds(gdn_blk_key_kernel<DK, DV>, lds3) || !allow_lds(gdn_blk_query_kernel<DK, DV>, lds3) ||
+            !allow_lds(gdn_blk_mid_kernel<DV>, ldsm))
+            return SLA_ERR_HIP;
+        configured.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+    }
+    const unsigned bh = (unsigned)(a.B * a.H), local = (unsigned)(blocks * (size_t)a.H);
+    auto grid = [bh](unsigned slices) { return dim3(((bh + 7u) / 8u) * 8u * slices); };
+    hipLaunchKernelGGL((gdn_blk_pre_kernel<DK>), dim3(local), dim3(64), 0, stream, a, ar);
+    hipLaunchKernelGGL((gdn_blk_state_kernel<DK, DV>), grid(DV / kCols), dim3(kThreads), (size_t)lds1, stream, a, ar);
+    hipLaunchKernelGGL((gdn_blk_cotangent_kernel<DK, DV>), grid(DV / kCols), dim3(kThreads), (size_t)lds2, stream, a, ar);
+    hipLaunchKernelGGL((gdn_blk_mid_kernel<DV>), dim3(local), dim3(64), (size_t)ldsm, stream, a, ar);
+    hipLaunchKernelGGL((gdn_blk_key_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds3, stream, a, ar);
+    hipLaunchKernelGGL((gdn_blk_query_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds3, stream, a, ar);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+template <int DK>
+int launch_dv(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t stream) {
+    switch (a.dim_v) {
+        case 64: return launch_all<DK, 64>(a, ar, blocks, stream);
+        case 128: return launch_all<DK, 128>(a, ar, blocks, stream);
+        case 256: return launch_all<DK, 256>(a, ar, blocks, stream);
+        default: return SLA_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+size_t gdn_block_workspace_floats(int B, int T, int H, int dk, int dv, bool packed) {
+    const size_t blocks = ws_blocks(B, T, packed), rows = packed ? (size_t)T : (size_t)B * T, bh = blocks * (size_t)H;
+    return bh * kScal + bh * (kPreMats + kMidMats) * kMat / 2 + 2 * (bh * (size_t)dv * C / 2) + round4(rows * H * dk);
+}
+
+int launch_gdn_block_sweeps(const GdnBlockArgs& a, hipStream_t stream) {
+    const size_t blocks = ws_blocks(a.B, a.T, a.cu != nullptr);
+    if (blocks == 0 || a.rows == 0) return SLA_OK;
+    const Areas ar = areas(a.block_ws, blocks, a.rows, a.H, a.dim_k, a.dim_v);
+    if (a.dim_k == 64) return launch_dv<64>(a, ar, blocks, stream);
+    if (a.dim_k == 128) return launch_dv<128>(a, ar, blocks, stream);
+    return SLA_ERR_UNSUPPORTED;
+}
+
+}  // namespace sla

@@ -1,7 +1,8 @@
 """GPU parity of the gated delta rule's backward pass (sla_backward_gdn through the C ABI) against the gradient
 oracle on the same seeded inputs and cotangents.  Tolerance: the bf16 bar of the other parity tests,
-max|x - x*| / max|x*| <= 2e-2 per gradient tensor; the sweeps compute in fp32 from bf16 inputs, so the measured
-errors are those of rounding dq, dk, dv to bf16 once (about 2e-3) and fp32 summation for the fp32 outputs."""
+max|x - x*| / max|x*| <= 2e-2 per gradient tensor.  bf16 tensors take the block form on the matrix cores (bf16
+operands, fp32 accumulation; intermediates pass through the workspace in bf16): measured errors 2e-3 to 7e-3 for
+every output.  fp32 tensors take the token-recurrent fp32 path, whose fp32 outputs are held to 1e-4."""
 import numpy as np
 import pytest
 
@@ -13,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 NAMES = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_head_logits": "dq_logits", "dk_head_logits": "dk_logits",
          "dlog_decay": "dlog_decay", "dbeta": "dbeta", "d_initial_state": "dinitial_state"}
-# fp32 outputs of fp32 arithmetic: far below the bf16 bar
+# fp32 tensors: fp32 outputs of fp32 arithmetic, far below the bf16 bar
 TIGHT = {"dq_head_logits": 1e-4, "dk_head_logits": 1e-4, "dlog_decay": 1e-4, "dbeta": 1e-4, "d_initial_state": 1e-4}
 
 
@@ -55,7 +56,7 @@ def check_backward_gdn(d, cot, s0=None, want_ds0=False, label="", batch_rows=Non
     print(f"[gdn backward parity] {label} " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
     for n, e in errs.items():
         assert e <= TOL[dtype], f"{label}: {n} error {e:.3e} > {TOL[dtype]}"
-        if n in TIGHT:
+        if dtype == "f32" and n in TIGHT:
             assert e <= TIGHT[n], f"{label}: {n} error {e:.3e} > {TIGHT[n]} (fp32 output)"
     return got, ref
 
