@@ -20,7 +20,6 @@ sys.path.insert(0, ROOT)
 
 METRIC = "tokens/sec SLA-GLA chunked fwd (B=8,T=2048,H=16,d=128 bf16); % MFMA peak"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flops x 2.4 GHz)
 
 
 def rel_err(x, ref) -> float:
@@ -191,11 +190,6 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
     ms_per_step = wall * 1e3 / args.steps
     abytes = backward_bytes(w)
     achieved = abytes / (call_ms * 1e-3) / 1e9
-    # The delta rule's backward runs token by token in fp32 vector arithmetic: its bound is the vector ALU.
-    # Arithmetic of the recurrence and its reverse walk, per token and head, in units of dk * dv: forward step
-    # a S (1), k Sb (2), S + k^T u (2), q S (2); reverse step dS + q^T dy (2), k dS (2), dS u (2), w Sb^T (2),
-    # dSb - k^T w (2), a dSb (1), dy S^T (2): 20 dk dv flops.
-    gdn_flops = 20 * w.dk * w.dv * w.B * w.T * w.H
     result = {
         "metric": f"tokens/sec SLA-{si.VARIANT_NAMES[w.variant].upper()} chunked bwd",
         "value": w.tokens() / (ms_per_step * 1e-3),
@@ -215,28 +209,15 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
                         f"dk={w.dk} dv={w.dv} bf16 in/out, dual head-softmax gates, no state cotangents"
                         + (", wide tensors laid out [B,H,T,d]" if hm else "")
                         + (f", {nseg} segments per batch row" if nseg > 1 else ""),
-            "kernel": ("sla_backward_gdn: sla_bwd_gates_kernel, gdn_bwd_state_kernel, gdn_bwd_cotangent_kernel, "
-                       "gdn_bwd_key_kernel x2, gdn_bwd_finish_kernel, gdn_bwd_decay_scan_kernel") if gdn else
+            "kernel": ("sla_backward_gdn (block form): sla_bwd_gates_kernel, gdn_blk_pre_kernel, gdn_blk_state_kernel, "
+                       "gdn_blk_cotangent_kernel, gdn_blk_mid_kernel, gdn_blk_key_kernel, gdn_blk_query_kernel, "
+                       "gdn_bwd_finish_kernel, gdn_bwd_decay_scan_kernel") if gdn else
                       "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
                       "sla_bwd_logits_kernel x2"
                       + (" after the segment pre-passes (sla_fwd_kernel state-only, sla_segment_combine_kernel, "
                          "sla_bwd_dv_kernel state-only, sla_bwd_segment_combine_kernel)" if nseg > 1 else ""),
         },
         "roofline": {
-            "bound": "alu",
-            "achieved": gdn_flops / (call_ms * 1e-3) / 1e12,
-            "peak": FP32_VECTOR_PEAK_TFLOPS,
-            "unit": "TFLOP/s",
-            "frac": gdn_flops / (call_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
-            **traffic_fields(w.name + ":backward"),
-            "kernel_us": call_ms * 1e3,
-            "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
-            "algorithmic_flops": gdn_flops,
-            "algorithmic_bytes": abytes,
-            "hbm_frac": achieved / HBM_PEAK_GBS,
-            "note": "whole call (seven launches); achieved = 20 dk dv flops per token and head / call time, against "
-                    "the published fp32 vector peak (which counts packed issue; this build issues unpacked fp32)",
-        } if gdn else {
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
@@ -246,7 +227,10 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
             "kernel_us": call_ms * 1e3,
             "kernel_us_min": float(np.min(per_call_ms)) * 1e3,
             "algorithmic_bytes": abytes,
-            "note": "whole call (%s launches); achieved = algorithmic bytes / call time" % ("six" if nseg == 1 else "thirteen"),
+            "note": "whole call (%s launches); achieved = algorithmic bytes / call time"
+                    % ("nine" if gdn else "six" if nseg == 1 else "thirteen")
+                    + ("; the sweeps pass res, w, the 32 x 32 block matrices and part of dk through the workspace, "
+                       "about five times the algorithmic bytes, and run at the memory system's speed on those" if gdn else ""),
         },
     }
     if not args.no_cpu_baseline or not args.no_parity:

@@ -140,21 +140,26 @@ template <int R, int RB>
 struct Rows {
     static constexpr int per = RB / 16, pieces = R * per, N = (pieces + kLoaders - 1) / kLoaders;
     u4 x[N];
-    // rows >= valid read as zero (valid >= 1)
-    __device__ __forceinline__ void load(const void* g, size_t gstride, int valid, int lt) {
+    int valid;  // rows >= valid are written as zero
+    // Nothing here looks at the loaded values (a piece outside the array reads its first piece instead, valid >= 1;
+    // the zeroing happens in put), so the loads stay in flight until the block is due.
+    __device__ __forceinline__ void load(const void* g, size_t gstride, int valid_rows, int lt) {
+        valid = valid_rows;
 #pragma unroll
         for (int n = 0; n < N; ++n) {
             const int it = lt + kLoaders * n, row = it / per, c = it - row * per;
-            const bool ok = it < pieces && row < valid;
-            const u4 v = *(const u4*)((const unsigned char*)g + (size_t)(ok ? row : 0) * gstride + 16 * (ok ? c : 0));
-            x[n] = ok ? v : u4{0u, 0u, 0u, 0u};
+            const bool ok = it < pieces && row < valid_rows;
+            x[n] = *(const u4*)((const unsigned char*)g + (size_t)(ok ? row : 0) * gstride + 16 * (ok ? c : 0));
         }
     }
+    // A thread without a piece of its own holds piece 0 (see load) and writes it where piece 0 goes: no branch.
     __device__ __forceinline__ void put(unsigned char* lds, int lstride, int lt) const {
 #pragma unroll
         for (int n = 0; n < N; ++n) {
-            const int it = lt + kLoaders * n, row = it / per, c = it - row * per;
-            if (it < pieces) *(u4*)(lds + row * lstride + 16 * c) = x[n];
+            const int it = lt + kLoaders * n, row0 = it / per;
+            const bool in = it < pieces;
+            const int row = in ? row0 : 0, c = in ? it - row0 * per : 0;
+            *(u4*)(lds + row * lstride + 16 * c) = row < valid ? x[n] : u4{0u, 0u, 0u, 0u};
         }
     }
 };
@@ -259,12 +264,20 @@ __device__ __forceinline__ bool find_block(const GdnBlockArgs& a, size_t wb, Seq
     return true;
 }
 
+// 16 bytes of a row of k or q as half an operand: slot (g, e) is element k0 + 8g + e (both operands of the Gram
+// products come from memory, so any slot order they share will do).
+__device__ __forceinline__ s8 gram_op(const bf* rows, size_t gstride, int row, int valid, int k0, int g) {
+    const u4 z = {0u, 0u, 0u, 0u};
+    const u4 v = row < valid ? *(const u4*)(rows + (size_t)row * gstride + k0 + 8 * g) : z;
+    return __builtin_bit_cast(s8, v);
+}
+__device__ __forceinline__ void mma_f32(f4& c, float a, float b) { c = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+
 template <int DK>
 __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, const Areas ar) {
-    constexpr int RK = DK + 8;
-    __shared__ __align__(16) bf Kr[C * RK];
-    __shared__ __align__(16) bf Qr[C * RK];
-    __shared__ __align__(16) float Lf[C * 36];
+    constexpr int LS = 36;  // row stride of the fp32 matrices
+    __shared__ __align__(16) float Lf[C * LS];   // Lk diag(beta)
+    __shared__ __align__(16) float Tf[C * LS];   // T'
     __shared__ __align__(16) float cs[C], bs[C], gqs[C];
     const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
     const int h = blockIdx.x % a.H;
@@ -274,23 +287,6 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
     if (!find_block(a, wb, s, I)) return;
     const int valid = min(C, s.T - C * I);
     const size_t row0 = s.tok0 + (size_t)C * I;
-    // rows of k and q (zero past the sequence)
-    {
-        const size_t gstride = (size_t)a.H * DK;
-        const bf* kg = a.k + (row0 * a.H + h) * DK;
-        const bf* qg = a.q + (row0 * a.H + h) * DK;
-        constexpr int per = DK / 8;
-#pragma unroll
-        for (int n = 0; n < C * per / 64; ++n) {
-            const int it = lane + 64 * n, row = it / per, c = it - row * per;
-            const bool ok = row < valid;
-            const u4 z = {0u, 0u, 0u, 0u};
-            const u4 kv = ok ? *(const u4*)(kg + (size_t)row * gstride + 8 * c) : z;
-            const u4 qv = ok ? *(const u4*)(qg + (size_t)row * gstride + 8 * c) : z;
-            *(u4*)(Kr + row * RK + 8 * c) = kv;
-            *(u4*)(Qr + row * RK + 8 * c) = qv;
-        }
-    }
     // per-token scalars: lane t (and t + 32, which repeats it)
     const int t = lane & 31;
     const bool tv = t < valid;
@@ -318,27 +314,35 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
         sc[kA * C + t] = __builtin_amdgcn_exp2f(c_end);
         sc[7 * C + t] = 0.f;
     }
+    // Gram tiles (tau, tau') of K K^T and Q K^T, operands straight from global memory: lane (r, g) ends up with rows
+    // t = 16 tau + 4g + i, column j = 16 tau' + r
+    const size_t gstride = (size_t)a.H * DK;
+    const bf* kg = a.k + (row0 * a.H + h) * DK;
+    const bf* qg = a.q + (row0 * a.H + h) * DK;
+    f4 kk[3], qk[3];  // tiles (0,0), (1,0), (1,1)
+#pragma unroll
+    for (int i = 0; i < 3; ++i) kk[i] = qk[i] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k0 = 0; k0 < DK; k0 += 32) {
+        const s8 k_lo = gram_op(kg, gstride, r, valid, k0, g), k_hi = gram_op(kg, gstride, 16 + r, valid, k0, g);
+        const s8 q_lo = gram_op(qg, gstride, r, valid, k0, g), q_hi = gram_op(qg, gstride, 16 + r, valid, k0, g);
+        mma(kk[0], k_lo, k_lo);
+        mma(kk[1], k_hi, k_lo);
+        mma(kk[2], k_hi, k_hi);
+        mma(qk[0], q_lo, k_lo);
+        mma(qk[1], q_hi, k_lo);
+        mma(qk[2], q_hi, k_hi);
+    }
     __syncthreads();
     bf* mats = ar.pre + (wb * a.H + h) * (size_t)(kPreMats * kMat);
-    // Gram tiles (tau, tau'): lane (r, g) holds rows t = 16 tau + 4g + i, column j = 16 tau' + r
+    {   // the tile above the diagonal (t < 16 <= j) is zero
+        const u2 zq = {0u, 0u};
+        *(u2*)(mats + mT3 * kMat + (16 + r) * C + 4 * g) = zq;
+        *(u2*)(mats + mT4 * kMat + (16 + r) * C + 4 * g) = zq;
+    }
 #pragma unroll
-    for (int tile = 0; tile < 4; ++tile) {
-        const int ta = tile >> 1, tb = tile & 1;
-        u2 zq = {0u, 0u};
-        bf* t3 = mats + mT3 * kMat + (16 * tb + r) * C + 16 * ta + 4 * g;
-        bf* t4 = mats + mT4 * kMat + (16 * tb + r) * C + 16 * ta + 4 * g;
-        if (tb > ta) {  // above the diagonal: zero
-            *(u2*)t3 = zq;
-            *(u2*)t4 = zq;
-            continue;
-        }
-        f4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kq = 0; kq < DK; kq += 32) {
-            const s8 bk = op_rows(Kr, RK, 16 * tb + r, kq, g);
-            mma(kk, op_rows(Kr, RK, 16 * ta + r, kq, g), bk);
-            mma(qk, op_rows(Qr, RK, 16 * ta + r, kq, g), bk);
-        }
+    for (int tile = 0; tile < 3; ++tile) {
+        const int ta = tile > 0, tb = tile > 1;
         const int j = 16 * tb + r;
         const float cj = cs[j], bj = bs[j];
         const f4 ct = *(const f4*)(cs + 16 * ta + 4 * g), gq4 = *(const f4*)(gqs + 16 * ta + 4 * g);
@@ -347,40 +351,69 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
         for (int i = 0; i < 4; ++i) {
             const int tt = 16 * ta + 4 * g + i;
             const float d = __builtin_amdgcn_exp2f(ct[i] - cj);
-            lq[i] = j <= tt ? d * qk[i] * gq4[i] : 0.f;
-            lk[i] = j < tt ? d * kk[i] : 0.f;
-            Lf[tt * 36 + j] = lk[i] * bj;
+            lq[i] = j <= tt ? d * qk[tile][i] * gq4[i] : 0.f;
+            lk[i] = j < tt ? d * kk[tile][i] : 0.f;
+            Lf[tt * LS + j] = lk[i] * bj;
         }
-        *(u2*)t3 = pack4(lq);
-        *(u2*)t4 = pack4(-lk);
+        *(u2*)(mats + mT3 * kMat + j * C + 16 * ta + 4 * g) = pack4(lq);   // T3[j][t] = G^Q_t Lq[t][j]
+        *(u2*)(mats + mT4 * kMat + j * C + 16 * ta + 4 * g) = pack4(-lk);  // T4[j][t] = -Lk[t][j]
     }
     __syncthreads();
-    // T' = (I + Lk diag(beta))^-1 by forward substitution, column `t` of the inverse in lane t:
-    //   x_j = [j == t] - sum_{i<j} Lf[j][i] x_i
-    float x[C];
+    // T' = (I + L)^-1, L = Lk diag(beta) strictly lower, by 16 x 16 blocks: T11 = (I + L11)^-1 and T22 = (I + L22)^-1
+    // by forward substitution (lane groups 0 and 2: column r of T11; groups 1 and 3: column r of T22), then
+    // T21 = -T22 L21 T11 as two fp32 matrix-core products.
+    {
+        const int o = 16 * (g & 1);  // this lane's diagonal block
+        float x[16];
 #pragma unroll
-    for (int j = 0; j < C; ++j) {
-        float acc = (j == t) ? 1.f : 0.f;
+        for (int j = 0; j < 16; ++j) {
+            float acc = (j == r) ? 1.f : 0.f;
 #pragma unroll
-        for (int i4 = 0; i4 < j; i4 += 4) {
-            const f4 l = *(const f4*)(Lf + j * 36 + i4);
+            for (int i4 = 0; i4 < j; i4 += 4) {
+                const f4 l = *(const f4*)(Lf + (o + j) * LS + o + i4);
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (i4 + e < j) acc -= l[e] * x[i4 + e];
+                for (int e = 0; e < 4; ++e)
+                    if (i4 + e < j) acc -= l[e] * x[i4 + e];
+            }
+            x[j] = acc;
         }
-        x[j] = acc;
-    }
-    if (lane < C) {
-        bf* t1 = mats + mT1 * kMat;  // T1[j][t] = T'[j][t]: lane t holds column t
+        if (g < 2) {
 #pragma unroll
-        for (int j = 0; j < C; ++j) t1[j * C + t] = (bf)(pack2(x[j], 0.f) & 0xffffu);
-        bf* t2 = mats + mT2 * kMat + t * C;  // T2[t][j] = T'[j][t] beta_j: row t
+            for (int j = 0; j < 16; ++j) {
+                Tf[(o + j) * LS + o + r] = x[j];
+                if (g == 0) Tf[j * LS + 16 + r] = 0.f;  // the block above the diagonal
+            }
+        }
+    }
+    __syncthreads();
+    f4 pr = {0.f, 0.f, 0.f, 0.f};  // P = L21 T11: rows 4g + i, column r
+#pragma unroll
+    for (int k4 = 0; k4 < 16; k4 += 4) mma_f32(pr, Lf[(16 + r) * LS + k4 + g], Tf[(k4 + g) * LS + r]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Tf[(16 + 4 * g + i) * LS + r] = pr[i];
+    __syncthreads();
+    f4 t21 = {0.f, 0.f, 0.f, 0.f};  // T22 P
+#pragma unroll
+    for (int k4 = 0; k4 < 16; k4 += 4) mma_f32(t21, Tf[(16 + r) * LS + 16 + k4 + g], Tf[(16 + k4 + g) * LS + r]);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Tf[(16 + 4 * g + i) * LS + r] = -t21[i];
+    __syncthreads();
+    if (lane < C) {  // T1[t][j] = T'[t][j]: row t
+        bf* t1 = mats + mT1 * kMat + t * C;
 #pragma unroll
         for (int j = 0; j < C; j += 8) {
-            const f4 b0 = *(const f4*)(bs + j), b1 = *(const f4*)(bs + j + 4);
-            const u4 o = {pack2(x[j] * b0[0], x[j + 1] * b0[1]), pack2(x[j + 2] * b0[2], x[j + 3] * b0[3]),
-                          pack2(x[j + 4] * b1[0], x[j + 5] * b1[1]), pack2(x[j + 6] * b1[2], x[j + 7] * b1[3])};
-            *(u4*)(t2 + j) = o;
+            const f4 lo = *(const f4*)(Tf + t * LS + j), hi = *(const f4*)(Tf + t * LS + j + 4);
+            *(u4*)(t1 + j) = u4{pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])};
+        }
+    } else {  // T2[j][t'] = T'[t'][j] beta_t': row j
+        bf* t2 = mats + mT2 * kMat + t * C;
+#pragma unroll
+        for (int u = 0; u < C; u += 8) {
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = Tf[(u + e) * LS + t] * bs[u + e];
+            *(u4*)(t2 + u) = u4{pack2(y[0], y[1]), pack2(y[2], y[3]), pack2(y[4], y[5]), pack2(y[6], y[7])};
         }
     }
 }
@@ -388,15 +421,23 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
 // ------------------------------------------------------------------------------------------------------------
 // Mid pass (after sweep 2): one wave per (block, head).  M + M^T, N^T, N' from res, w and dOut.
 // ------------------------------------------------------------------------------------------------------------
+// op_rows from global memory (rows >= valid read as zero)
+__device__ __forceinline__ s8 op_rows_global(const bf* rows, size_t gstride, int row, int valid, int k0, int g) {
+    const u2 z = {0u, 0u};
+    const bf* p = rows + (size_t)row * gstride + k0 + 4 * g;
+    const u2 lo = row < valid ? *(const u2*)p : z, hi = row < valid ? *(const u2*)(p + 16) : z;
+    return __builtin_bit_cast(s8, u4{lo.x, lo.y, hi.x, hi.y});
+}
+
 template <int DV>
 __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, const Areas ar) {
-    constexpr int RD = DV + 8;
+    constexpr int LS = 36;
     extern __shared__ __align__(16) unsigned char smem[];
     bf* Wf = (bf*)smem;                  // [DV][kSm]
     bf* RSf = Wf + DV * kSm;             // [DV][kSm]
-    bf* dOf = RSf + DV * kSm;            // [C][RD]
-    float* Mf = (float*)(dOf + C * RD);  // [C][36]
-    float* Nf = Mf + C * 36;
+    float* Mf = (float*)smem;            // [C][LS], over Wf once the products are done
+    float* Nf = Mf + C * LS;
+    static_assert(2 * C * LS * 4 <= 2 * DV * kSm * 2, "the fp32 matrices fit over the staged operands");
     const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
     const int h = blockIdx.x % a.H;
     const size_t wb = blockIdx.x / a.H;
@@ -414,32 +455,37 @@ __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, c
             *(u4*)(Wf + row * kSm + 8 * c) = *(const u4*)(wg + row * C + 8 * c);
             *(u4*)(RSf + row * kSm + 8 * c) = *(const u4*)(rg + row * C + 8 * c);
         }
-        const bf* og = a.dout + (row0 * a.H + h) * DV;
-        const size_t gstride = (size_t)a.H * DV;
-        constexpr int per = DV / 8;
-#pragma unroll
-        for (int n = 0; n < C * per / 64; ++n) {
-            const int it = lane + 64 * n, row = it / per, c = it - row * per;
-            const u4 z = {0u, 0u, 0u, 0u};
-            *(u4*)(dOf + row * RD + 8 * c) = row < valid ? *(const u4*)(og + (size_t)row * gstride + 8 * c) : z;
-        }
     }
     __syncthreads();
+    const bf* og = a.dout + (row0 * a.H + h) * DV;
+    const size_t gstride = (size_t)a.H * DV;
+    f4 wu[3], ou[3];  // tiles (0,0), (1,0), (1,1): rows t = 16 tau + 4g + i, column j = 16 tau' + r
+#pragma unroll
+    for (int i = 0; i < 3; ++i) wu[i] = ou[i] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int n0 = 0; n0 < DV; n0 += 32) {
+        const s8 u_lo = op_cols(RSf, kSm, n0, 0, r, g), u_hi = op_cols(RSf, kSm, n0, 16, r, g);
+        const s8 w_lo = op_cols(Wf, kSm, n0, 0, r, g), w_hi = op_cols(Wf, kSm, n0, 16, r, g);
+        const s8 o_lo = op_rows_global(og, gstride, r, valid, n0, g), o_hi = op_rows_global(og, gstride, 16 + r, valid, n0, g);
+        mma(wu[0], w_lo, u_lo);
+        mma(wu[1], w_hi, u_lo);
+        mma(wu[2], w_hi, u_hi);
+        mma(ou[0], o_lo, u_lo);
+        mma(ou[1], o_hi, u_lo);
+        mma(ou[2], o_hi, u_hi);
+    }
+    __syncthreads();  // the staged operands are dead: their place takes M and N'
     const float* sc = ar.scal + bhi * (size_t)kScal;
     bf* mats = ar.mid + bhi * (size_t)(kMidMats * kMat);
+    *(u2*)(mats + mNT * kMat + (16 + r) * C + 4 * g) = u2{0u, 0u};  // N^T[j >= 16][t < 16] = 0
 #pragma unroll
-    for (int tile = 0; tile < 4; ++tile) {
-        const int ta = tile >> 1, tb = tile & 1;
-        bf* nt = mats + mNT * kMat + (16 * tb + r) * C + 16 * ta + 4 * g;
-        f4 wu = {0.f, 0.f, 0.f, 0.f}, ou = {0.f, 0.f, 0.f, 0.f};
-        if (tb <= ta) {
+    for (int i = 0; i < 4; ++i) {  // above the diagonal: t = 4g + i < 16 <= j = 16 + r
+        Mf[(4 * g + i) * LS + 16 + r] = 0.f;
+        Nf[(4 * g + i) * LS + 16 + r] = 0.f;
+    }
 #pragma unroll
-            for (int n0 = 0; n0 < DV; n0 += 32) {
-                const s8 bu = op_cols(RSf, kSm, n0, 16 * tb, r, g);
-                mma(wu, op_cols(Wf, kSm, n0, 16 * ta, r, g), bu);
-                mma(ou, op_rows(dOf, RD, 16 * ta + r, n0, g), bu);
-            }
-        }
+    for (int tile = 0; tile < 3; ++tile) {
+        const int ta = tile > 0, tb = tile > 1;
         const int j = 16 * tb + r;
         const float cj = sc[kCl * C + j], bj = sc[kBeta * C + j];
         const f4 ct = sc4(sc, kCl, 16 * ta + 4 * g), gq4 = sc4(sc, kGq, 16 * ta + 4 * g);
@@ -448,12 +494,12 @@ __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, c
         for (int i = 0; i < 4; ++i) {
             const int tt = 16 * ta + 4 * g + i;
             const float d = __builtin_amdgcn_exp2f(ct[i] - cj) * bj;
-            const float m = j < tt ? -d * wu[i] : 0.f, np = j <= tt ? d * ou[i] : 0.f;
-            Mf[tt * 36 + j] = m;
-            Nf[tt * 36 + j] = np;
+            const float m = j < tt ? -d * wu[tile][i] : 0.f, np = j <= tt ? d * ou[tile][i] : 0.f;
+            Mf[tt * LS + j] = m;
+            Nf[tt * LS + j] = np;
             nn[i] = np * gq4[i];
         }
-        *(u2*)nt = pack4(nn);
+        *(u2*)(mats + mNT * kMat + j * C + 16 * ta + 4 * g) = pack4(nn);  // N^T[j][t] = G^Q_t N'[t][j]
     }
     __syncthreads();
     {
@@ -463,8 +509,8 @@ __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, c
         float m[16], n[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            m[j] = Mf[t * 36 + j0 + j] + Mf[(j0 + j) * 36 + t];
-            n[j] = Nf[t * 36 + j0 + j];
+            m[j] = Mf[t * LS + j0 + j] + Mf[(j0 + j) * LS + t];
+            n[j] = Nf[t * LS + j0 + j];
         }
 #pragma unroll
         for (int j = 0; j < 16; j += 8) {
@@ -488,32 +534,48 @@ struct Frame {
     __device__ __forceinline__ size_t bhi(int I) const { return (s.blk0 + (size_t)I) * a.H + s.h; }
 };
 
-// LOADER: struct with load(frame, I, lt) and put(stage, lt); BODY: callable (stage, I).
-template <bool FWD, class LOADER, class BODY, class INIT, class FINI>
+// LOADER: struct with load(frame, I, lt) and put(stage, lt); BODY: callable (stage, I).  The loaders keep PF blocks in
+// flight in registers (block b in set b % PF): a block's rows are requested PF + 1 steps before the compute waves
+// need them, which covers the latency of HBM under load (with one block in flight a step lasted as long as a load).
+template <bool FWD, int PF, class LOADER, class BODY, class INIT, class FINI>
 __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, int stage_bytes, INIT&& init, BODY&& body,
                                           FINI&& fini) {
     const int tid = threadIdx.x, nblk = f.s.nblk;
-    auto blk = [&](int step) { return FWD ? step : nblk - 1 - step; };
+    // Both sides run the same number of steps, a multiple of PF, so that the loaders' loop body has no branch in it
+    // (the compiler then lets the loads of the other register sets stay outstanding across a put); steps past the
+    // last block stage that block again and compute nothing.
+    const int nsteps = (nblk + PF - 1) / PF * PF;
+    auto blk = [&](int step) {
+        const int sclamp = min(step, nblk - 1);
+        return FWD ? sclamp : nblk - 1 - sclamp;
+    };
     if (tid >= kThreads - kLoaders) {
+        if (nblk == 0) return;
         const int lt = tid - (kThreads - kLoaders);
-        LOADER R;
-        if (nblk > 0) {
-            R.load(f, blk(0), lt);
-            R.put(smem, lt);
-        }
-        if (nblk > 1) R.load(f, blk(1), lt);
+        LOADER R[PF];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) R[u].load(f, blk(u), lt);
+        R[0].put(smem, lt);
+        R[0].load(f, blk(PF), lt);
         __syncthreads();
-        for (int step = 0; step < nblk; ++step) {
-            if (step + 1 < nblk) R.put(smem + ((step + 1) & 1) * stage_bytes, lt);
-            if (step + 2 < nblk) R.load(f, blk(step + 2), lt);
-            __syncthreads();
+        for (int base = 0; base < nsteps; base += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int step = base + u;
+                LOADER& set = R[(u + 1) % PF];  // holds block step + 1 (base is a multiple of PF)
+                set.put(smem + ((step + 1) & 1) * stage_bytes, lt);
+                set.load(f, blk(step + 1 + PF), lt);
+                __syncthreads();
+            }
         }
     } else {
         init();
-        __syncthreads();
-        for (int step = 0; step < nblk; ++step) {
-            body(smem + (step & 1) * stage_bytes, blk(step));
+        if (nblk > 0) {
             __syncthreads();
+            for (int step = 0; step < nsteps; ++step) {
+                if (step < nblk) body(smem + (step & 1) * stage_bytes, blk(step));
+                __syncthreads();
+            }
         }
         fini();
     }
@@ -522,7 +584,7 @@ __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, i
 // ---- sweep 1: forward, S[dk, 16 value columns per wave] -> res ------------------------------------------------
 template <int DK>
 struct Stage1 {
-    static constexpr int RK = DK + 8;
+    static constexpr int RK = DK + 16;
     static constexpr int oK = 0, oV = oK + C * RK * 2, oT = oV + C * kSl * 2, oS = oT + C * kSm * 2,
                          bytes = oS + kScal * 4;
 };
@@ -560,7 +622,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
               g = lane >> 4;
     const int n = s.slice * kCols + 16 * w + r;  // this lane's value column
     f4 S[NT];
-    run_sweep<true, Load1<DK, DV>>(
+    run_sweep<true, 4, Load1<DK, DV>>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -611,7 +673,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
 // ---- sweep 2: backward, X[dk, 16 value columns per wave] -> w, dv, dG^K, dbeta, d_initial_state -----------------
 template <int DK>
 struct Stage2 {
-    static constexpr int RK = DK + 8;
+    static constexpr int RK = DK + 16;
     static constexpr int oK = 0, oQ = oK + C * RK * 2, oO = oQ + C * RK * 2, oV = oO + C * kSl * 2,
                          oR = oV + C * kSl * 2, oT = oR + kCols * kSm * 2, oS = oT + 3 * C * kSm * 2,
                          bytes = oS + kScal * 4;
@@ -659,7 +721,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
     const int n0 = s.slice * kCols, n = n0 + 16 * w + r;
     const int plane = (n0 >> 4) + w;
     f4 X[NT];
-    run_sweep<false, Load2<DK, DV>>(
+    run_sweep<false, 4, Load2<DK, DV>>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -768,7 +830,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
 // ---- sweeps 3 and 4: X^T / S^T [dv, 16 key columns per wave] ---------------------------------------------------
 template <int DV>
 struct Stage3 {
-    static constexpr int RD = DV + 8;
+    static constexpr int RD = DV + 16;
     static constexpr int oR = 0, oW = oR + DV * kSm * 2, oO = oW + DV * kSm * 2, oQ = oO + C * RD * 2,
                          oK = oQ + C * kSl * 2, oM = oK + C * kSl * 2, oS = oM + 2 * C * kSm * 2,
                          bytes = oS + kScal * 4;
@@ -815,7 +877,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
               g = lane >> 4;
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;  // this lane's key column
     f4 Xt[NT];  // Xt[t][i] = X[d][16 t + 4g + i]
-    run_sweep<false, Load3<DK, DV, mMs, 2>>(
+    run_sweep<false, (DV > 128 ? 2 : 4), Load3<DK, DV, mMs, 2>>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -878,7 +940,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;
     const int plane = (d0 >> 4) + w;
     f4 St[NT];  // St[t][i] = S[d][16 t + 4g + i]
-    run_sweep<true, Load3<DK, DV, mNp, 1>>(
+    run_sweep<true, (DV > 128 ? 2 : 4), Load3<DK, DV, mNp, 1>>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -967,7 +1029,7 @@ bool allow_lds(K kernel, int lds) {
 template <int DK, int DV>
 int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t stream) {
     constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 2 * Stage2<DK>::bytes, lds3 = 2 * Stage3<DV>::bytes;
-    constexpr int ldsm = 2 * DV * kSm * 2 + C * (DV + 8) * 2 + 2 * C * 36 * 4;
+    constexpr int ldsm = 2 * DV * kSm * 2;
     static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && ldsm <= 160 * 1024, "LDS");
     static std::atomic<uint64_t> configured{0};  // bit d: attributes set on device d
     int dev = 0;
