@@ -173,6 +173,22 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
                     const void* log_decay, const float* beta, float* state, void* out, void* stream);
 
 /*
+ * The decode step with the gate projection of Sec. 3.2 fused in: instead of logits it takes the two gate matrices
+ * (as sla_gate_logits does) and forms q_head_logits[b,h'] = q[b,h',:] . W_GQ[:,h'] (and the same for k) for every
+ * head h' of the token inside the kernel, then the head softmax of Eq. 4 and the step of sla_decode_step.  A
+ * decode step sees the whole token anyway, so the projection costs 2 H dk multiply-adds per workgroup and saves a
+ * launch per generated token.  The logits are formed in fp32 from the tensors as given; the result equals
+ * sla_gate_logits followed by sla_decode_step up to the order of the fp32 sums.
+ *
+ *   w_gq   [H,dk] fp32   device, read only: row h is column h of the paper's matrix; required
+ *   w_gk   [H,dk] fp32   or NULL (G^K = 1)
+ * Everything else as sla_decode_step.
+ */
+int sla_decode_step_fused(const sla_params* p, const void* q, const void* k, const void* v,
+                          const float* w_gq, const float* w_gk,
+                          const void* log_decay, const float* beta, float* state, void* out, void* stream);
+
+/*
  * Backward pass of sla_forward for the RetNet and GLA recurrences (Sec. 5.1) with the gates of Eq. 4-6: the
  * gradients that training through the chunkwise form of Sec. 3.2 (Chunkwise Parallel Training) needs.  With the
  * scalar objective L = sum(out * d_out) + sum(final_state * d_final_state) it writes dL/d(input) for every

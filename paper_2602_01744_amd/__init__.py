@@ -34,6 +34,7 @@ from .binding import (  # noqa: F401
     short_conv_silu_l2_backward,
     gate_logits_backward,
     sla_decode_step,
+    sla_decode_step_fused,
     sla_default_dv_split,
     sla_forward,
     sla_forward_ws,

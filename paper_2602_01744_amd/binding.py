@@ -72,6 +72,8 @@ def load_library():
     lib.sla_static_scratch_bytes.argtypes = []
     lib.sla_decode_step.restype = ctypes.c_int
     lib.sla_decode_step.argtypes = [pp] + [vp] * 10
+    lib.sla_decode_step_fused.restype = ctypes.c_int
+    lib.sla_decode_step_fused.argtypes = [pp] + [vp] * 10
     lib.sla_forward_varlen.restype = ctypes.c_int
     lib.sla_forward_varlen.argtypes = [pp] + [vp] * 12
     lib.sla_backward_varlen.restype = ctypes.c_int
@@ -230,6 +232,16 @@ def sla_decode_step(params, q, k, v, q_head_logits, k_head_logits, log_decay, be
         load_library().sla_decode_step(
             pr, _p(q), _p(k), _p(v), _p(q_head_logits), _p(k_head_logits), _p(log_decay), _p(beta), _p(state),
             _p(out), _p(stream),
+        )
+    )
+
+
+def sla_decode_step_fused(params, q, k, v, w_gq, w_gk, log_decay, beta, state, out, stream) -> int:
+    """Raw call of the decode entry point that forms the gate logits itself."""
+    pr = ctypes.byref(params) if params is not None else None
+    return int(
+        load_library().sla_decode_step_fused(
+            pr, _p(q), _p(k), _p(v), _p(w_gq), _p(w_gk), _p(log_decay), _p(beta), _p(state), _p(out), _p(stream),
         )
     )
 
@@ -641,10 +653,31 @@ def backward_gdn(q, k, v, q_head_logits, k_head_logits, log_decay, beta, d_out, 
     return g
 
 
-def decode_step(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, *, out=None):
+def decode_step(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, *, out=None,
+                w_gq=None, w_gk=None):
     """One recurrent step on the current CUDA(HIP) device and stream: q, k [B,H,dk], v [B,H,dv], logits / beta
-    [B,H] float32, state [B,H,dk,dv] float32 (updated in place).  Returns out [B,H,dv]."""
+    [B,H] float32, state [B,H,dk,dv] float32 (updated in place).  Returns out [B,H,dv].  With w_gq (and
+    optionally w_gk) [H,dk] float32 the kernel forms the logits itself (sla_decode_step_fused) and the two logits
+    arguments must be None."""
     import torch
+
+    if w_gq is not None:
+        assert q_head_logits is None and k_head_logits is None
+        B, H, dk = q.shape
+        dv = v.shape[-1]
+        for w in (w_gq, w_gk):
+            assert w is None or (w.dtype == torch.float32 and tuple(w.shape) == (H, dk) and w.is_contiguous())
+        assert state.dtype == torch.float32 and state.shape == (B, H, dk, dv) and state.is_contiguous()
+        dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+        if out is None:
+            out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+        params = SlaParams(variant, dtype, B, 1, H, dk, dv, 0, 0, 1)
+        ptr = lambda t: None if t is None else t.data_ptr()
+        rc = sla_decode_step_fused(params, ptr(q), ptr(k), ptr(v), ptr(w_gq), ptr(w_gk), ptr(log_decay), ptr(beta),
+                                   ptr(state), ptr(out), torch.cuda.current_stream(q.device).cuda_stream)
+        if rc != 0:
+            raise SlaError(rc, sla_status_string(rc))
+        return out
 
     assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
     B, H, dk = q.shape

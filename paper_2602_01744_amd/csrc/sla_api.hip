@@ -43,6 +43,7 @@ int launch_gate_logits_backward(const sla_params& p, const void* x, const float*
 size_t gate_logits_backward_workspace_floats(const sla_params& p);
 unsigned int* device_status_word();
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
+                  const float* wq, const float* wk,
                   const void* ld, const float* beta, float* state, void* out, hipStream_t stream);
 }
 
@@ -321,7 +322,21 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
     if (p->B == 0) return SLA_OK;
     if (!state) return SLA_ERR_NULL;
     // one token per sequence: [B,1,H,d] and [B,H,1,d] are the same memory, so the layout flag changes nothing
-    return sla::launch_decode(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out,
+    return sla::launch_decode(*p, q, k, v, q_head_logits, k_head_logits, nullptr, nullptr, log_decay, beta, state, out,
+                              (hipStream_t)stream);
+}
+
+int sla_decode_step_fused(const sla_params* p, const void* q, const void* k, const void* v, const float* w_gq,
+                          const float* w_gk, const void* log_decay, const float* beta, float* state, void* out,
+                          void* stream) {
+    // w_gq / w_gk take the place of the logits: same rules (w_gq required, w_gk optional, both 16-byte aligned)
+    const int rc = check(p, q, k, v, w_gq, w_gk, log_decay, beta, state, out, state);
+    if (rc != SLA_OK) return rc;
+    if (p->T != 1) return SLA_ERR_SHAPE;
+    if (p->dk < 64) return SLA_ERR_UNSUPPORTED;
+    if (p->B == 0) return SLA_OK;
+    if (!state) return SLA_ERR_NULL;
+    return sla::launch_decode(*p, q, k, v, nullptr, nullptr, w_gq, w_gk, log_decay, beta, state, out,
                               (hipStream_t)stream);
 }
 

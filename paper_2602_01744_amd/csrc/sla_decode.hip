@@ -27,6 +27,8 @@ struct DArgs {
     const void* v;
     const float* ql;
     const float* kl;
+    const float* wq;        // fused gate projection: [H,dk] fp32 (then ql, kl are not read), else null
+    const float* wk;        // [H,dk] fp32 or null (G^K = 1)
     const void* ld;
     const float* beta;
     float* state;
@@ -76,8 +78,36 @@ __global__ __launch_bounds__(kDecThreads) void sla_decode_kernel(const DArgs a) 
     const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
     const int c4 = tid % NC4, rg = tid / NC4;
 
-    const float gq = decode_gate(a.ql + (size_t)b * a.H, a.H, h, lane);
-    const float gk = a.kl ? decode_gate(a.kl + (size_t)b * a.H, a.H, h, lane) : 1.f;
+    float gq, gk;
+    if (a.wq) {
+        // Fused gate projection (Eq. 4 needs the logits of every head of the token): wave w takes heads w, w + 4, ...
+        // and forms q[b,h',:] . W_GQ[:,h'] and k[b,h',:] . W_GK[:,h'] -- 2 H dk multiply-adds against the dk dv of
+        // the state update, and one launch less in front of every decode step.
+        __shared__ float lg[2][64];
+        for (int h2 = tid >> 6; h2 < a.H; h2 += kDecThreads / 64) {
+            float sq = 0.f, sk = 0.f;
+            for (int d = lane; d < DK; d += 64) {
+                const size_t at = ((size_t)b * a.H + h2) * DK + d;
+                sq += load_elem<BF16>(a.q, at) * a.wq[(size_t)h2 * DK + d];
+                if (a.wk) sk += load_elem<BF16>(a.k, at) * a.wk[(size_t)h2 * DK + d];
+            }
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) {
+                sq += __shfl_xor(sq, o);
+                sk += __shfl_xor(sk, o);
+            }
+            if (lane == 0) {
+                lg[0][h2] = sq;
+                lg[1][h2] = sk;
+            }
+        }
+        __syncthreads();
+        gq = decode_gate(lg[0], a.H, h, lane);
+        gk = a.wk ? decode_gate(lg[1], a.H, h, lane) : 1.f;
+    } else {
+        gq = decode_gate(a.ql + (size_t)b * a.H, a.H, h, lane);
+        gk = a.kl ? decode_gate(a.kl + (size_t)b * a.H, a.H, h, lane) : 1.f;
+    }
 
     // the state tile of this thread: issue every load before anything waits for one
     d_f32x4* srow = (d_f32x4*)(a.state + (size_t)bh * DK * DV) + c4;
@@ -194,9 +224,11 @@ int launch_var(const DArgs& a, int variant, int dk, int dv, hipStream_t stream) 
 }  // namespace
 
 int launch_decode(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
-                  const void* ld, const float* beta, float* state, void* out, hipStream_t stream) {
+                  const float* wq, const float* wk, const void* ld, const float* beta, float* state, void* out,
+                  hipStream_t stream) {
     DArgs a;
-    a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.ld = ld; a.beta = beta; a.state = state; a.out = out;
+    a.q = q; a.k = k; a.v = v; a.ql = ql; a.kl = kl; a.wq = wq; a.wk = wk; a.ld = ld; a.beta = beta; a.state = state;
+    a.out = out;
     a.B = p.B; a.H = p.H;
     if (p.dtype == SLA_BF16) return launch_var<true>(a, p.variant, p.dk, p.dv, stream);
     return launch_var<false>(a, p.variant, p.dk, p.dv, stream);

@@ -44,8 +44,8 @@ int launch_feature_map_backward(int, int, int, int, int, int, float, const void*
 int launch_gate_logits_backward(const sla_params&, const void*, const float*, const float*, void*, float*, float*,
                                 hipStream_t) { return reached("gate logits backward"); }
 size_t gate_logits_backward_workspace_floats(const sla_params& p) { return (size_t)1024 * p.H * p.dk; }
-int launch_decode(const sla_params&, const void*, const void*, const void*, const float*, const float*, const void*,
-                  const float*, float*, void*, hipStream_t) { return reached("decode"); }
+int launch_decode(const sla_params&, const void*, const void*, const void*, const float*, const float*, const float*,
+                  const float*, const void*, const float*, float*, void*, hipStream_t) { return reached("decode"); }
 }  // namespace sla
 
 static int failures = 0;

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(sla_[a-z0-9_]+)\s*\(", header)
-    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_forward_static", "sla_init", "sla_device_status", "sla_static_scratch_bytes", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_short_conv_silu_l2", "sla_short_conv_silu_l2_backward", "sla_short_conv_silu_l2_backward_workspace_bytes", "sla_gate_logits_backward", "sla_gate_logits_backward_workspace_bytes", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
+    assert set(names) >= {"sla_forward", "sla_forward_ws", "sla_forward_static", "sla_init", "sla_device_status", "sla_static_scratch_bytes", "sla_backward", "sla_backward_workspace_bytes", "sla_backward_gdn", "sla_backward_gdn_workspace_bytes", "sla_backward_gdn_varlen", "sla_backward_gdn_varlen_workspace_bytes", "sla_gate_logits", "sla_short_conv_silu", "sla_short_conv_silu_l2", "sla_short_conv_silu_l2_backward", "sla_short_conv_silu_l2_backward_workspace_bytes", "sla_gate_logits_backward", "sla_gate_logits_backward_workspace_bytes", "sla_forward_varlen", "sla_backward_varlen", "sla_backward_varlen_workspace_bytes", "sla_decode_step", "sla_decode_step_fused", "sla_workspace_bytes", "sla_segments", "sla_backward_segments", "sla_check_args", "sla_default_dv_split", "sla_kernel_name",
                           "sla_status_string", "sla_version"}
     for n in set(names):
         assert hasattr(lib, n), n
@@ -155,6 +155,13 @@ def test_decode_step_validation(lib):
     assert sla.sla_decode_step(one, *args, A + 4, A, 0) == -4
     assert sla.sla_decode_step(_ok_params(T=1, variant=sla.GDN), *args, A, A, 0) == -1   # GDN needs beta
     assert sla.sla_decode_step(_ok_params(T=1, B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
+    # the fused form: the gate matrices take the place of the logits, with the same rules
+    assert sla.sla_decode_step_fused(_ok_params(T=2), *args, A, A, 0) == -2
+    assert sla.sla_decode_step_fused(one, A, A, A, 0, A, A, 0, A, A, 0) == -1  # w_gq missing
+    assert sla.sla_decode_step_fused(one, A, A, A, A + 4, A, A, 0, A, A, 0) == -4
+    assert sla.sla_decode_step_fused(one, *args, 0, A, 0) == -1
+    assert sla.sla_decode_step_fused(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) == -3
+    assert sla.sla_decode_step_fused(_ok_params(T=1, B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):
@@ -280,13 +287,22 @@ def test_backward_gdn_rejects_bad_calls(lib):
 def test_backward_gdn_workspace_size(lib):
     B, T, H, dk, dv = 2, 100, 4, 128, 64
     n = B * T * H
-    got = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, B=B, T=T, H=H, dk=dk, dv=dv))
+    # fp32 tensors (token-recurrent sweeps): gates and the decay scalar (3 planes), dk/8 partial planes of dG^Q and
+    # dv/8 each of dG^K and dbeta, <d_final, S_T> partials, two fp32 tensors like v and one like k
+    f32 = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv))
     pv, pk = dv // 8, dk // 8
-    # gates and the decay scalar (3 planes), dk/8 partial planes of dG^Q and dv/8 each of dG^K and dbeta,
-    # <d_final, S_T> partials, two fp32 tensors like v and one like k
-    assert got == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + 2 * n * dv + n * dk)
+    assert f32 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + 2 * n * dv + n * dk)
+    # bf16 tensors (block form): a plane per 16 columns; per 32-token block and head 8 x 32 scalars, seven 32 x 32
+    # bf16 matrices and two bf16 [dv][32] tiles; one fp32 tensor like k
+    bf16 = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.BF16, B=B, T=T, H=H, dk=dk, dv=dv))
+    pv, pk = dv // 16, dk // 16
+    bh = B * ((T + 31) // 32) * H
+    assert bf16 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + bh * 256 + bh * 7 * 1024 // 2 + 2 * (bh * dv * 32 // 2) + n * dk)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
-    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv)) == got
+    # packed batches: floor(T / 32) + B + 1 blocks whatever the sequence lengths are
+    packed = sla.sla_backward_gdn_varlen_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.BF16, B=3, T=200, H=H, dk=dk, dv=dv))
+    n, bh = 200 * H, (200 // 32 + 3 + 1) * H
+    assert packed == 4 * (n * (3 + 2 * pv + pk) + pk * 3 * H + bh * 256 + bh * 7 * 1024 // 2 + 2 * (bh * dv * 32 // 2) + n * dk)
 
 
 def test_backward_segment_schedule_workspace_and_validation(lib):
@@ -315,10 +331,12 @@ def test_backward_gdn_varlen_validation_and_workspace(lib):
     assert call(_ok_params(variant=sla.GLA)) == -3
     assert call(_ok_params(variant=sla.GDN, B=0), cu=0) == 0
     # sized by the total token count p->T, not B * T
-    p, one = _ok_params(variant=sla.GDN, B=5, T=1000), _ok_params(variant=sla.GDN, B=1, T=1000)
+    p, one = (_ok_params(variant=sla.GDN, dtype=sla.F32, B=5, T=1000),
+              _ok_params(variant=sla.GDN, dtype=sla.F32, B=1, T=1000))
     planes = p.dk // 8
     assert sla.sla_backward_gdn_varlen_workspace_bytes(p) == \
         sla.sla_backward_gdn_workspace_bytes(one) + 4 * ((planes * 5 * p.H + 3) // 4 * 4 - (planes * p.H + 3) // 4 * 4)
+    # (the bf16 sizes are spelled out in test_backward_gdn_workspace_size)
 
 
 def test_backward_segment_recommendation(lib):

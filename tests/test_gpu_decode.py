@@ -122,3 +122,35 @@ def test_full_size_decode_batch():
     o, f = decode_chain(GLA, d, "bf16", s0)
     ro, rf = run_oracle(GLA, d, s0)
     assert rel_err(o, ro) <= TOL["bf16"] and rel_err(f, rf) <= 1e-5
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H,dk,dv,both", [(16, 128, 128, True), (5, 64, 256, True), (33, 128, 64, False), (1, 64, 64, True)])
+def test_fused_gate_projection_matches_oracle(variant, dtype, H, dk, dv, both):
+    """sla_decode_step_fused: logits formed in the kernel from q, k and the gate matrices.  The reference is the
+    oracle's projection (q . W_GQ per head) followed by the oracle's forward on those logits."""
+    import torch
+    import paper_2602_01744_amd as sla
+    from oracle import sla_numpy
+
+    B = 3
+    d = si.custom(variant, dtype, B=B, T=1, H=H, dk=dk, dv=dv, seed=2700 + variant + H + dk)
+    w = si.gate_weights(H, dk, seed=2701 + H)
+    d["q_logits"] = sla_numpy.gate_logits(d["q"], w["w_gq"])
+    d["k_logits"] = sla_numpy.gate_logits(d["k"], w["w_gk"]) if both else None
+    s0 = si.initial_state(B, H, dk, dv, seed=27)
+    ro, rf = run_oracle(variant, d, s0)
+    state = torch.from_numpy(np.ascontiguousarray(s0, dtype=np.float32)).cuda()
+    q, k, v = (_dev(d[n][:, 0], dtype, True) for n in ("q", "k", "v"))
+    ld = _dev(d["log_decay"] if variant == RETNET else d["log_decay"][:, 0], dtype, variant == GLA)
+    beta = None if d["beta"] is None else _dev(d["beta"][:, 0], dtype, False)
+    wq = torch.from_numpy(w["w_gq"]).cuda()
+    wk = torch.from_numpy(w["w_gk"]).cuda() if both else None
+    o = sla.decode_step(variant, q, k, v, None, None, ld, beta, state, w_gq=wq, w_gk=wk)
+    torch.cuda.synchronize()
+    eo = rel_err(o.to(torch.float32).cpu().numpy().astype(np.float64)[:, None], ro)
+    ef = rel_err(state.cpu().numpy().astype(np.float64), rf)
+    print(f"[parity] fused decode {_name(variant)} {dtype} H={H} dk={dk} dv={dv} out_err={eo:.3e} state_err={ef:.3e}",
+          flush=True)
+    assert eo <= TOL[dtype] and ef <= 1e-5
