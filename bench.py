@@ -600,6 +600,41 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
         if rc != 0:
             raise sla.SlaError(rc, sla.sla_status_string(rc))
 
+    chain_us, raw_f = None, None
+    if args.fused_gates:
+        # The logits come from q, k and seeded gate matrices: either by sla_gate_logits in front of the step (two
+        # launches) or inside sla_decode_step_fused (one).  Both are timed; the fused one is the reported step.
+        from oracle import sla_numpy
+
+        wts = si.gate_weights(w.H, w.dk, seed=w.seed + 77)
+        wq, wk = torch.from_numpy(wts["w_gq"]).to(dev), torch.from_numpy(wts["w_gk"]).to(dev)
+        d["q_logits"] = sla_numpy.gate_logits(d["q"], wts["w_gq"])
+        d["k_logits"] = sla_numpy.gate_logits(d["k"], wts["w_gk"])
+        raw_f = (ptr(q), ptr(k), ptr(v), ptr(wq), ptr(wk), ptr(ld), ptr(beta), ptr(state), ptr(out), raw[-1])
+        gl = (ptr(q), ptr(k), ptr(wq), ptr(wk), ptr(ql), ptr(kl), raw[-1])
+
+        def chain():
+            rc = sla.sla_gate_logits(params, *gl) or sla.sla_decode_step(params, *raw)
+            if rc != 0:
+                raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+        def step():  # noqa: F811
+            rc = sla.sla_decode_step_fused(params, *raw_f)
+            if rc != 0:
+                raise sla.SlaError(rc, sla.sla_status_string(rc))
+
+        keep = state.clone()
+        for _ in range(args.settle + args.warmup):
+            chain()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            chain()
+        e1.record()
+        torch.cuda.synchronize()
+        chain_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        state.copy_(keep)
+
     result_parity = None
     if not args.no_parity or not args.no_cpu_baseline:
         import oracle
@@ -630,6 +665,8 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         raw = raw[:-1] + (side.cuda_stream,)  # the captured calls go to the capture stream
+        if args.fused_gates:
+            raw_f = raw_f[:-1] + (side.cuda_stream,)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             for _ in range(per):
@@ -669,8 +706,10 @@ def bench_decode(args, w, sla, si, torch, np) -> int:
         "config": {
             "workload": f"{w.name}: SLA-{si.VARIANT_NAMES[w.variant].upper()} decode step B={w.B} H={w.H} dk={w.dk} "
                         f"dv={w.dv} {w.dtype} in/out, fp32 state updated in place, dual head-softmax gates",
-            "kernel": "sla_decode_kernel",
+            "kernel": "sla_decode_kernel" + (" with the gate projection fused (sla_decode_step_fused)" if args.fused_gates else ""),
             "launch": f"HIP graph of {per} steps per replay" if args.graph > 0 else "one launch per step",
+            **({"unfused_chain_us": chain_us,
+                "unfused_chain": "sla_gate_logits + sla_decode_step, back to back, same inputs"} if chain_us else {}),
         },
         "roofline": {
             "bound": "hbm",
@@ -776,6 +815,9 @@ def main() -> int:
                          "is shorter than the gap between two launches from Python; a serving loop replays a graph")
     ap.add_argument("--train-step", action="store_true",
                     help="time gate logits + forward + backward of the workload, back to back")
+    ap.add_argument("--fused-gates", action="store_true",
+                    help="decode workloads only: time sla_decode_step_fused (gate logits formed in the kernel) and, "
+                         "beside it, the two-launch chain sla_gate_logits + sla_decode_step")
     ap.add_argument("--backward", action="store_true",
                     help="time sla_backward (RetNet / GLA) or sla_backward_gdn (--workload gdn) instead of the forward")
     ap.add_argument("--flush-mb", type=int, default=0,

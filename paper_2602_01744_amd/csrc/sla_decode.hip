@@ -46,6 +46,28 @@ __device__ __forceinline__ float load_elem(const void* p, size_t i) {
         return ((const float*)p)[i];
 }
 
+// N adjacent elements starting at element i (N a multiple of 4; the address is 8- or 16-byte aligned), as wide loads
+template <bool BF16, int N>
+__device__ __forceinline__ void load_run(const void* p, size_t i, float (&x)[N]) {
+    if constexpr (BF16) {
+        typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+#pragma unroll
+        for (int e = 0; e < N; e += 4) {
+            const u2 t = *(const u2*)((const uint16_t*)p + i + e);
+            x[e] = __uint_as_float(t.x << 16);
+            x[e + 1] = __uint_as_float(t.x & 0xffff0000u);
+            x[e + 2] = __uint_as_float(t.y << 16);
+            x[e + 3] = __uint_as_float(t.y & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < N; e += 4) {
+            const d_f32x4 t = *(const d_f32x4*)((const float*)p + i + e);
+            x[e] = t[0]; x[e + 1] = t[1]; x[e + 2] = t[2]; x[e + 3] = t[3];
+        }
+    }
+}
+
 __device__ __forceinline__ uint32_t dec_pack_bf16(float lo, float hi) {
     typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
     bf2 t;
@@ -78,25 +100,43 @@ __global__ __launch_bounds__(kDecThreads) void sla_decode_kernel(const DArgs a) 
     const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
     const int c4 = tid % NC4, rg = tid / NC4;
 
+    // the state tile of this thread: issue every load before anything waits for one (the gates, which need a
+    // round trip of their own, are formed while these are in flight)
+    d_f32x4* srow = (d_f32x4*)(a.state + (size_t)bh * DK * DV) + c4;
+    d_f32x4 S[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) S[i] = srow[(size_t)(rg + NRG * i) * NC4];
+
     float gq, gk;
     if (a.wq) {
-        // Fused gate projection (Eq. 4 needs the logits of every head of the token): wave w takes heads w, w + 4, ...
-        // and forms q[b,h',:] . W_GQ[:,h'] and k[b,h',:] . W_GK[:,h'] -- 2 H dk multiply-adds against the dk dv of
-        // the state update, and one launch less in front of every decode step.
+        // Fused gate projection (Eq. 4 needs the logits of every head of the token): 16 threads per head, 16 heads
+        // per pass, each thread DK/16 adjacent elements of q[b,h',:] . W_GQ[:,h'] and k[b,h',:] . W_GK[:,h'], summed
+        // over the 16 threads with shuffles -- 2 H dk multiply-adds against the dk dv of the state update, and one
+        // launch less in front of every decode step.
         __shared__ float lg[2][64];
-        for (int h2 = tid >> 6; h2 < a.H; h2 += kDecThreads / 64) {
+        constexpr int EPT = DK / 16;
+        const int sub = tid & 15;
+        for (int h2 = tid >> 4; h2 < a.H; h2 += kDecThreads / 16) {
+            const size_t at = ((size_t)b * a.H + h2) * DK + sub * EPT, wat = (size_t)h2 * DK + sub * EPT;
+            float xq[EPT], xk[EPT], wq[EPT], wk[EPT];
+            load_run<BF16, EPT>(a.q, at, xq);
+            load_run<false, EPT>(a.wq, wat, wq);
+            if (a.wk) {
+                load_run<BF16, EPT>(a.k, at, xk);
+                load_run<false, EPT>(a.wk, wat, wk);
+            }
             float sq = 0.f, sk = 0.f;
-            for (int d = lane; d < DK; d += 64) {
-                const size_t at = ((size_t)b * a.H + h2) * DK + d;
-                sq += load_elem<BF16>(a.q, at) * a.wq[(size_t)h2 * DK + d];
-                if (a.wk) sk += load_elem<BF16>(a.k, at) * a.wk[(size_t)h2 * DK + d];
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                sq += xq[e] * wq[e];
+                if (a.wk) sk += xk[e] * wk[e];
             }
 #pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) {
+            for (int o = 8; o >= 1; o >>= 1) {
                 sq += __shfl_xor(sq, o);
                 sk += __shfl_xor(sk, o);
             }
-            if (lane == 0) {
+            if (sub == 0) {
                 lg[0][h2] = sq;
                 lg[1][h2] = sk;
             }
@@ -108,12 +148,6 @@ __global__ __launch_bounds__(kDecThreads) void sla_decode_kernel(const DArgs a) 
         gq = decode_gate(a.ql + (size_t)b * a.H, a.H, h, lane);
         gk = a.kl ? decode_gate(a.kl + (size_t)b * a.H, a.H, h, lane) : 1.f;
     }
-
-    // the state tile of this thread: issue every load before anything waits for one
-    d_f32x4* srow = (d_f32x4*)(a.state + (size_t)bh * DK * DV) + c4;
-    d_f32x4 S[RPT];
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) S[i] = srow[(size_t)(rg + NRG * i) * NC4];
 
     float qd[RPT], kd[RPT], ad[RPT];
     float a_scalar = 1.f;
