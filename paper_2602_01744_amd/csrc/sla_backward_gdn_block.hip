@@ -59,8 +59,14 @@ constexpr int C = 32;            // tokens per block
 constexpr int kThreads = 512;    // four compute waves + four loader waves
 constexpr int kLoaders = 256;
 constexpr int kCols = 64;        // columns of a state slice per workgroup
-constexpr int kSm = 40;          // LDS row stride, in elements, of an array with 32 elements per row
-constexpr int kSl = 72;          // ... of a 64-column slice of token rows
+// LDS row strides, in elements.  A row read (op_rows: 16 rows x 16 bytes per half-wave) is conflict-free when
+// consecutive rows are 16 bytes apart modulo the 256 bytes of the 64 banks, a column read (op_cols: 8 rows x 32 bytes
+// per half-wave) when they are 32 bytes apart: arrays get 8 or 16 elements of padding according to how the sweep
+// reads them (k, which sweeps 1 and 2 read both ways, is staged twice).
+constexpr int kSmR = 40, kSmC = 48;   // 32 elements per row: read by rows / by columns
+constexpr int kSlR = 72, kSlC = 80;   // a 64-column slice of token rows
+constexpr int rows_stride(int width) { return width + 8; }
+constexpr int cols_stride(int width) { return width + 16; }
 constexpr float kLog2e = 1.4426950408889634f;
 
 // per-token scalars of a block: kinds x 32 floats
@@ -433,11 +439,11 @@ template <int DV>
 __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, const Areas ar) {
     constexpr int LS = 36;
     extern __shared__ __align__(16) unsigned char smem[];
-    bf* Wf = (bf*)smem;                  // [DV][kSm]
-    bf* RSf = Wf + DV * kSm;             // [DV][kSm]
+    bf* Wf = (bf*)smem;                  // [DV][kSmC]
+    bf* RSf = Wf + DV * kSmC;            // [DV][kSmC]
     float* Mf = (float*)smem;            // [C][LS], over Wf once the products are done
     float* Nf = Mf + C * LS;
-    static_assert(2 * C * LS * 4 <= 2 * DV * kSm * 2, "the fp32 matrices fit over the staged operands");
+    static_assert(2 * C * LS * 4 <= 2 * DV * kSmC * 2, "the fp32 matrices fit over the staged operands");
     const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
     const int h = blockIdx.x % a.H;
     const size_t wb = blockIdx.x / a.H;
@@ -452,8 +458,8 @@ __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, c
 #pragma unroll
         for (int n = 0; n < DV * 4 / 64; ++n) {
             const int it = lane + 64 * n, row = it >> 2, c = it & 3;
-            *(u4*)(Wf + row * kSm + 8 * c) = *(const u4*)(wg + row * C + 8 * c);
-            *(u4*)(RSf + row * kSm + 8 * c) = *(const u4*)(rg + row * C + 8 * c);
+            *(u4*)(Wf + row * kSmC + 8 * c) = *(const u4*)(wg + row * C + 8 * c);
+            *(u4*)(RSf + row * kSmC + 8 * c) = *(const u4*)(rg + row * C + 8 * c);
         }
     }
     __syncthreads();
@@ -464,8 +470,8 @@ __global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, c
     for (int i = 0; i < 3; ++i) wu[i] = ou[i] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int n0 = 0; n0 < DV; n0 += 32) {
-        const s8 u_lo = op_cols(RSf, kSm, n0, 0, r, g), u_hi = op_cols(RSf, kSm, n0, 16, r, g);
-        const s8 w_lo = op_cols(Wf, kSm, n0, 0, r, g), w_hi = op_cols(Wf, kSm, n0, 16, r, g);
+        const s8 u_lo = op_cols(RSf, kSmC, n0, 0, r, g), u_hi = op_cols(RSf, kSmC, n0, 16, r, g);
+        const s8 w_lo = op_cols(Wf, kSmC, n0, 0, r, g), w_hi = op_cols(Wf, kSmC, n0, 16, r, g);
         const s8 o_lo = op_rows_global(og, gstride, r, valid, n0, g), o_hi = op_rows_global(og, gstride, 16 + r, valid, n0, g);
         mma(wu[0], w_lo, u_lo);
         mma(wu[1], w_hi, u_lo);
@@ -584,9 +590,9 @@ __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, i
 // ---- sweep 1: forward, S[dk, 16 value columns per wave] -> res ------------------------------------------------
 template <int DK>
 struct Stage1 {
-    static constexpr int RK = DK + 16;
-    static constexpr int oK = 0, oV = oK + C * RK * 2, oT = oV + C * kSl * 2, oS = oT + C * kSm * 2,
-                         bytes = oS + kScal * 4;
+    static constexpr int RKr = rows_stride(DK), RKc = cols_stride(DK);
+    static constexpr int oK = 0, oKc = oK + C * RKr * 2, oV = oKc + C * RKc * 2, oT = oV + C * kSlC * 2,
+                         oS = oT + C * kSmR * 2, bytes = oS + kScal * 4;
 };
 template <int DK, int DV>
 struct Load1 {
@@ -603,9 +609,10 @@ struct Load1 {
     }
     __device__ __forceinline__ void put(unsigned char* st, int lt) const {
         typedef Stage1<DK> L;
-        k.put(st + L::oK, L::RK * 2, lt);
-        v.put(st + L::oV, kSl * 2, lt);
-        t1.put(st + L::oT, kSm * 2, lt);
+        k.put(st + L::oK, L::RKr * 2, lt);
+        k.put(st + L::oKc, L::RKc * 2, lt);
+        v.put(st + L::oV, kSlC * 2, lt);
+        t1.put(st + L::oT, kSmR * 2, lt);
         sc.put(st + L::oS, C * 4, lt);
     }
 };
@@ -613,7 +620,7 @@ struct Load1 {
 template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockArgs a, const Areas ar) {
     typedef Stage1<DK> L;
-    constexpr int NT = DK / 16, RK = L::RK;
+    constexpr int NT = DK / 16, RKr = L::RKr, RKc = L::RKc;
     extern __shared__ __align__(16) unsigned char smem[];
     const Seq s = where(a, DV / kCols);
     if (s.bh < 0) return;
@@ -633,6 +640,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
         },
         [&](const unsigned char* st, int I) {
             const bf* Kr = (const bf*)(st + L::oK);
+            const bf* Kc = (const bf*)(st + L::oKc);
             const bf* Vs = (const bf*)(st + L::oV);
             const bf* T1 = (const bf*)(st + L::oT);
             const float* sc = (const float*)(st + L::oS);
@@ -640,13 +648,13 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
 #pragma unroll
             for (int t = 0; t < NT; t += 2) {
                 const s8 bS = pack8(S[t], S[t + 1]);
-                mma(X[0], op_rows(Kr, RK, r, 16 * t, g), bS);
-                mma(X[1], op_rows(Kr, RK, 16 + r, 16 * t, g), bS);
+                mma(X[0], op_rows(Kr, RKr, r, 16 * t, g), bS);
+                mma(X[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bS);
             }
             f4 Rp[2];
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta)
-                Rp[ta] = sc4(sc, kGk, 16 * ta + 4 * g) * tile_cols(Vs, kSl, 16 * ta, 16 * w, r, g) -
+                Rp[ta] = sc4(sc, kGk, 16 * ta + 4 * g) * tile_cols(Vs, kSlC, 16 * ta, 16 * w, r, g) -
                          sc4(sc, kP, 16 * ta + 4 * g) * X[ta];
             const s8 bR = pack8(Rp[0], Rp[1]);
             bf* dst = ar.res + (f.bhi(I) * (size_t)DV + n) * C + 4 * g;
@@ -654,7 +662,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 f4 rs = {0.f, 0.f, 0.f, 0.f};
-                mma(rs, op_rows(T1, kSm, 16 * ta + r, 0, g), bR);
+                mma(rs, op_rows(T1, kSmR, 16 * ta + r, 0, g), bR);
                 const u2 pk = pack4(rs);
                 *(u2*)(dst + 16 * ta) = pk;
                 Up[ta] = sc4(sc, kBeta, 16 * ta + 4 * g) * sc4(sc, kAP, 16 * ta + 4 * g) * unpack4(pk);
@@ -664,7 +672,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 S[t] *= A;
-                mma(S[t], op_cols(Kr, RK, 0, 16 * t, r, g), bU);
+                mma(S[t], op_cols(Kc, RKc, 0, 16 * t, r, g), bU);
             }
         },
         [&]() {});
@@ -673,10 +681,10 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_state_kernel(const GdnBlockA
 // ---- sweep 2: backward, X[dk, 16 value columns per wave] -> w, dv, dG^K, dbeta, d_initial_state -----------------
 template <int DK>
 struct Stage2 {
-    static constexpr int RK = DK + 16;
-    static constexpr int oK = 0, oQ = oK + C * RK * 2, oO = oQ + C * RK * 2, oV = oO + C * kSl * 2,
-                         oR = oV + C * kSl * 2, oT = oR + kCols * kSm * 2, oS = oT + 3 * C * kSm * 2,
-                         bytes = oS + kScal * 4;
+    static constexpr int RKr = rows_stride(DK), RKc = cols_stride(DK);
+    static constexpr int oK = 0, oKc = oK + C * RKr * 2, oQ = oKc + C * RKc * 2, oO = oQ + C * RKc * 2,
+                         oV = oO + C * kSlC * 2, oR = oV + C * kSlR * 2, oT = oR + kCols * kSmC * 2,
+                         oS = oT + 3 * C * kSmR * 2, bytes = oS + kScal * 4;
 };
 template <int DK, int DV>
 struct Load2 {
@@ -698,12 +706,13 @@ struct Load2 {
     }
     __device__ __forceinline__ void put(unsigned char* st, int lt) const {
         typedef Stage2<DK> L;
-        k.put(st + L::oK, L::RK * 2, lt);
-        q.put(st + L::oQ, L::RK * 2, lt);
-        o.put(st + L::oO, kSl * 2, lt);
-        v.put(st + L::oV, kSl * 2, lt);
-        rs.put(st + L::oR, kSm * 2, lt);
-        t.put(st + L::oT, kSm * 2, lt);
+        k.put(st + L::oK, L::RKr * 2, lt);
+        k.put(st + L::oKc, L::RKc * 2, lt);
+        q.put(st + L::oQ, L::RKc * 2, lt);
+        o.put(st + L::oO, kSlC * 2, lt);
+        v.put(st + L::oV, kSlR * 2, lt);
+        rs.put(st + L::oR, kSmC * 2, lt);
+        t.put(st + L::oT, kSmR * 2, lt);
         sc.put(st + L::oS, C * 4, lt);
     }
 };
@@ -711,7 +720,7 @@ struct Load2 {
 template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBlockArgs a, const Areas ar) {
     typedef Stage2<DK> L;
-    constexpr int NT = DK / 16, RK = L::RK;
+    constexpr int NT = DK / 16, RKr = L::RKr, RKc = L::RKc;
     extern __shared__ __align__(16) unsigned char smem[];
     const Seq s = where(a, DV / kCols);
     if (s.bh < 0) return;
@@ -732,27 +741,28 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
         },
         [&](const unsigned char* st, int I) {
             const bf* Kr = (const bf*)(st + L::oK);
+            const bf* Kc = (const bf*)(st + L::oKc);
             const bf* Qr = (const bf*)(st + L::oQ);
             const bf* Os = (const bf*)(st + L::oO);
             const bf* Vs = (const bf*)(st + L::oV);
             const bf* Rs = (const bf*)(st + L::oR);
             const bf* T2 = (const bf*)(st + L::oT);
-            const bf* T3 = T2 + C * kSm;
-            const bf* T4 = T3 + C * kSm;
+            const bf* T3 = T2 + C * kSmR;
+            const bf* T4 = T3 + C * kSmR;
             const float* sc = (const float*)(st + L::oS);
             f4 dU[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int t = 0; t < NT; t += 2) {
                 const s8 bX = pack8(X[t], X[t + 1]);
-                mma(dU[0], op_rows(Kr, RK, r, 16 * t, g), bX);
-                mma(dU[1], op_rows(Kr, RK, 16 + r, 16 * t, g), bX);
+                mma(dU[0], op_rows(Kr, RKr, r, 16 * t, g), bX);
+                mma(dU[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bX);
             }
-            const s8 bO = op_cols(Os, kSl, 0, 16 * w, r, g);  // dOut[t slots][column n]
+            const s8 bO = op_cols(Os, kSlC, 0, 16 * w, r, g);  // dOut[t slots][column n]
             const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 dU[ta] *= sc4(sc, kAP, 16 * ta + 4 * g);
-                mma(dU[ta], op_rows(T3, kSm, 16 * ta + r, 0, g), bO);
+                mma(dU[ta], op_rows(T3, kSmR, 16 * ta + r, 0, g), bO);
             }
             const s8 pdU = pack8(dU[0], dU[1]);
             // identity as an operand: slot (half, g, e) is token 16 half + 4g + e; column 16 tau + r
@@ -767,7 +777,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
             s8 aT2[2];
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
-                aT2[ta] = op_rows(T2, kSm, 16 * ta + r, 0, g);
+                aT2[ta] = op_rows(T2, kSmR, 16 * ta + r, 0, g);
                 wv[ta] = f4{0.f, 0.f, 0.f, 0.f};
                 wT[ta] = f4{0.f, 0.f, 0.f, 0.f};
                 duT[ta] = f4{0.f, 0.f, 0.f, 0.f};
@@ -786,10 +796,10 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
             const size_t row0 = f.row0(I);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
-                mma(duT[ta], pw, op_rows(T4, kSm, 16 * ta + r, 0, g));  // du = dU - Lk^T w, token 16 ta + r
+                mma(duT[ta], pw, op_rows(T4, kSmR, 16 * ta + r, 0, g));  // du = dU - Lk^T w, token 16 ta + r
                 const int tt = 16 * ta + r;
-                const f4 rs4 = tile_cols(Rs, kSm, 16 * w, 16 * ta, r, g);            // res[token tt][column 16w + 4g + i]
-                const f4 v4 = unpack4(*(const s4*)(Vs + tt * kSl + 16 * w + 4 * g));  // v[token tt][the same columns]
+                const f4 rs4 = tile_cols(Rs, kSmC, 16 * w, 16 * ta, r, g);            // res[token tt][column 16w + 4g + i]
+                const f4 v4 = unpack4(*(const s4*)(Vs + tt * kSlR + 16 * w + 4 * g));  // v[token tt][the same columns]
                 float pb = 0.f, pk = 0.f;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -813,8 +823,8 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 X[t] *= A;
-                mma(X[t], op_cols(Qr, RK, 0, 16 * t, r, g), bq);
-                mma(X[t], op_cols(Kr, RK, 0, 16 * t, r, g), bw);
+                mma(X[t], op_cols(Qr, RKc, 0, 16 * t, r, g), bq);
+                mma(X[t], op_cols(Kc, RKc, 0, 16 * t, r, g), bw);
             }
         },
         [&]() {
@@ -828,14 +838,17 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
 }
 
 // ---- sweeps 3 and 4: X^T / S^T [dv, 16 key columns per wave] ---------------------------------------------------
-template <int DV>
+// FWD = false: sweep 3 reads res and d_out by columns and w by rows; FWD = true: sweep 4, the other way round.
+template <int DV, bool FWD>
 struct Stage3 {
-    static constexpr int RD = DV + 16;
-    static constexpr int oR = 0, oW = oR + DV * kSm * 2, oO = oW + DV * kSm * 2, oQ = oO + C * RD * 2,
-                         oK = oQ + C * kSl * 2, oM = oK + C * kSl * 2, oS = oM + 2 * C * kSm * 2,
+    static constexpr int RD = FWD ? rows_stride(DV) : cols_stride(DV);   // d_out rows
+    static constexpr int SR = FWD ? kSmR : kSmC, SW = FWD ? kSmC : kSmR;  // res, w
+    static constexpr int SQ = FWD ? kSlR : kSlC;                          // the q slice (k slice: by columns in both)
+    static constexpr int oR = 0, oW = oR + DV * SR * 2, oO = oW + DV * SW * 2, oQ = oO + C * RD * 2,
+                         oK = oQ + C * SQ * 2, oM = oK + C * kSlC * 2, oS = oM + 2 * C * kSmR * 2,
                          bytes = oS + kScal * 4;
 };
-template <int DK, int DV, int FIRST, int NMAT>  // the mid-pass matrices FIRST .. FIRST + NMAT - 1
+template <int DK, int DV, int FIRST, int NMAT, bool FWD>  // the mid-pass matrices FIRST .. FIRST + NMAT - 1
 struct Load3 {
     Rows<DV, 64> rs, wv;
     Rows<C, DV * 2> o;
@@ -854,20 +867,20 @@ struct Load3 {
         sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
     }
     __device__ __forceinline__ void put(unsigned char* st, int lt) const {
-        typedef Stage3<DV> L;
-        rs.put(st + L::oR, kSm * 2, lt);
-        wv.put(st + L::oW, kSm * 2, lt);
+        typedef Stage3<DV, FWD> L;
+        rs.put(st + L::oR, L::SR * 2, lt);
+        wv.put(st + L::oW, L::SW * 2, lt);
         o.put(st + L::oO, L::RD * 2, lt);
-        q.put(st + L::oQ, kSl * 2, lt);
-        k.put(st + L::oK, kSl * 2, lt);
-        m.put(st + L::oM, kSm * 2, lt);
+        q.put(st + L::oQ, L::SQ * 2, lt);
+        k.put(st + L::oK, kSlC * 2, lt);
+        m.put(st + L::oM, kSmR * 2, lt);
         sc.put(st + L::oS, C * 4, lt);
     }
 };
 
 template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArgs a, const Areas ar) {
-    typedef Stage3<DV> L;
+    typedef Stage3<DV, false> L;
     constexpr int NT = DV / 16, RD = L::RD;
     extern __shared__ __align__(16) unsigned char smem[];
     const Seq s = where(a, DK / kCols);
@@ -877,7 +890,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
               g = lane >> 4;
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;  // this lane's key column
     f4 Xt[NT];  // Xt[t][i] = X[d][16 t + 4g + i]
-    run_sweep<false, (DV > 128 ? 2 : 4), Load3<DK, DV, mMs, 2>>(
+    run_sweep<false, (DV > 128 ? 2 : 4), Load3<DK, DV, mMs, 2, false>>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -892,25 +905,25 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
             const bf* Qs = (const bf*)(st + L::oQ);
             const bf* Ks = (const bf*)(st + L::oK);
             const bf* Ms = (const bf*)(st + L::oM);
-            const bf* Nt = Ms + C * kSm;
+            const bf* Nt = Ms + C * kSmR;
             const float* sc = (const float*)(st + L::oS);
             // dk2^T[key column 4g + i][token 16 tau + r] = (A/p beta)_t sum_n X[d][n] res[t][n] + local terms
             f4 dkT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int t = 0; t < NT; t += 2) {
                 const s8 aX = pack8(Xt[t], Xt[t + 1]);
-                mma(dkT[0], aX, op_cols(Rf, kSm, 16 * t, 0, r, g));
-                mma(dkT[1], aX, op_cols(Rf, kSm, 16 * t, 16, r, g));
+                mma(dkT[0], aX, op_cols(Rf, kSmC, 16 * t, 0, r, g));
+                mma(dkT[1], aX, op_cols(Rf, kSmC, 16 * t, 16, r, g));
             }
-            const s8 aK = op_cols(Ks, kSl, 0, 16 * w, r, g), aQ = op_cols(Qs, kSl, 0, 16 * w, r, g);
+            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
             const int valid = f.valid(I);
             const size_t row0 = f.row0(I);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 const int tt = 16 * ta + r;
                 dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
-                mma(dkT[ta], aK, op_rows(Ms, kSm, tt, 0, g));
-                mma(dkT[ta], aQ, op_rows(Nt, kSm, tt, 0, g));
+                mma(dkT[ta], aK, op_rows(Ms, kSmR, tt, 0, g));
+                mma(dkT[ta], aQ, op_rows(Nt, kSmR, tt, 0, g));
                 if (tt < valid) *(f4*)(ar.dk2 + ((row0 + tt) * a.H + s.h) * DK + d0 + 16 * w + 4 * g) = dkT[ta];
             }
             const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
@@ -921,7 +934,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
             for (int t = 0; t < NT; ++t) {
                 Xt[t] *= A;
                 mma(Xt[t], op_cols(Of, RD, 0, 16 * t, r, g), bq);
-                mma(Xt[t], op_rows(Wf, kSm, 16 * t + r, 0, g), bk);
+                mma(Xt[t], op_rows(Wf, kSmR, 16 * t + r, 0, g), bk);
             }
         },
         [&]() {});
@@ -929,7 +942,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
 
 template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockArgs a, const Areas ar) {
-    typedef Stage3<DV> L;
+    typedef Stage3<DV, true> L;
     constexpr int NT = DV / 16, RD = L::RD;
     extern __shared__ __align__(16) unsigned char smem[];
     const Seq s = where(a, DK / kCols);
@@ -940,7 +953,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;
     const int plane = (d0 >> 4) + w;
     f4 St[NT];  // St[t][i] = S[d][16 t + 4g + i]
-    run_sweep<true, (DV > 128 ? 2 : 4), Load3<DK, DV, mNp, 1>>(
+    run_sweep<true, (DV > 128 ? 2 : 4), Load3<DK, DV, mNp, 1, true>>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -972,17 +985,17 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
                 const s8 aS = pack8(St[t], St[t + 1]);
                 mma(dqT[0], aS, op_rows(Of, RD, r, 16 * t, g));
                 mma(dqT[1], aS, op_rows(Of, RD, 16 + r, 16 * t, g));
-                mma(dkT[0], aS, op_cols(Wf, kSm, 16 * t, 0, r, g));
-                mma(dkT[1], aS, op_cols(Wf, kSm, 16 * t, 16, r, g));
+                mma(dkT[0], aS, op_cols(Wf, kSmC, 16 * t, 0, r, g));
+                mma(dkT[1], aS, op_cols(Wf, kSmC, 16 * t, 16, r, g));
             }
-            const s8 aK = op_cols(Ks, kSl, 0, 16 * w, r, g);
+            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 const int tt = 16 * ta + r;
                 const float pt = sc[kP * C + tt];
                 dqT[ta] *= pt;
-                mma(dqT[ta], aK, op_rows(Np, kSm, tt, 0, g));
-                const f4 q4 = unpack4(*(const s4*)(Qs + tt * kSl + 16 * w + 4 * g));
+                mma(dqT[ta], aK, op_rows(Np, kSmR, tt, 0, g));
+                const f4 q4 = unpack4(*(const s4*)(Qs + tt * kSlR + 16 * w + 4 * g));
                 float pq = 0.f;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) pq += q4[i] * dqT[ta][i];
@@ -1000,7 +1013,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 St[t] *= A;
-                mma(St[t], op_rows(Rf, kSm, 16 * t + r, 0, g), bk);
+                mma(St[t], op_rows(Rf, kSmR, 16 * t + r, 0, g), bk);
             }
         },
         [&]() {
@@ -1028,9 +1041,10 @@ bool allow_lds(K kernel, int lds) {
 
 template <int DK, int DV>
 int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t stream) {
-    constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 2 * Stage2<DK>::bytes, lds3 = 2 * Stage3<DV>::bytes;
-    constexpr int ldsm = 2 * DV * kSm * 2;
-    static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && ldsm <= 160 * 1024, "LDS");
+    constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 2 * Stage2<DK>::bytes, lds3 = 2 * Stage3<DV, false>::bytes, lds4 = 2 * Stage3<DV, true>::bytes;
+    constexpr int ldsm = 2 * DV * kSmC * 2;
+    static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && lds4 <= 160 * 1024 &&
+                      ldsm <= 160 * 1024, "LDS");
     static std::atomic<uint64_t> configured{0};  // bit d: attributes set on device d
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
@@ -1039,7 +1053,7 @@ int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_
     }
     if (!((configured.load(std::memory_order_acquire) >> dev) & 1u)) {
         if (!allow_lds(gdn_blk_state_kernel<DK, DV>, lds1) || !allow_lds(gdn_blk_cotangent_kernel<DK, DV>, lds2) ||
-            !allow_lds(gdn_blk_key_kernel<DK, DV>, lds3) || !allow_lds(gdn_blk_query_kernel<DK, DV>, lds3) ||
+            !allow_lds(gdn_blk_key_kernel<DK, DV>, lds3) || !allow_lds(gdn_blk_query_kernel<DK, DV>, lds4) ||
             !allow_lds(gdn_blk_mid_kernel<DV>, ldsm))
             return SLA_ERR_HIP;
         configured.fetch_or(uint64_t(1) << dev, std::memory_order_release);
@@ -1051,7 +1065,7 @@ int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_
     hipLaunchKernelGGL((gdn_blk_cotangent_kernel<DK, DV>), grid(DV / kCols), dim3(kThreads), (size_t)lds2, stream, a, ar);
     hipLaunchKernelGGL((gdn_blk_mid_kernel<DV>), dim3(local), dim3(64), (size_t)ldsm, stream, a, ar);
     hipLaunchKernelGGL((gdn_blk_key_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds3, stream, a, ar);
-    hipLaunchKernelGGL((gdn_blk_query_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds3, stream, a, ar);
+    hipLaunchKernelGGL((gdn_blk_query_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds4, stream, a, ar);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
