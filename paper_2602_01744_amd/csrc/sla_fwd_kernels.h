@@ -212,7 +212,10 @@ struct Smem {
     static constexpr size_t oQA = 0;
     static constexpr size_t oKD = oQA + sizeof(elem) * kBlock * RS;
     static constexpr size_t oKBT = oKD + sizeof(elem) * kBlock * RS;
-    static constexpr size_t oVT = oKBT + sizeof(elem) * (DK / 2) * KTS;
+    // Scalar-decay variants with 2-byte elements stage no k^T: their k rows go to LDS unscaled, and the consumers take
+    // the transposed fragments from those rows with the transposing LDS read (ds_read_b64_tr_b16).
+    static constexpr bool kTR = VAR != SLA_GLA && sizeof(elem) == 2;
+    static constexpr size_t oVT = oKBT + (kTR ? 0 : sizeof(elem) * (DK / 2) * KTS);
     static constexpr size_t oEA = oVT + sizeof(elem) * DVW * TS;
     static constexpr size_t oGQ = oEA + (VAR == SLA_GLA ? sizeof(float) * DK : 0);
     static constexpr size_t oGK = oGQ + sizeof(float) * kBlock;
@@ -612,25 +615,25 @@ __device__ __forceinline__ void produce_block_scalar(Stage<P, VAR, DK, DVW, HG>&
 
     stage_gates<P, VAR, DK, DVW, HG>(st, ldr, buf, blk, next_tok0, lane);
 
-    // q and k as loaded
+    // q and k as loaded (the state-only pass needs the k rows only where the consumers read k^T from them)
     elem* qrow = QA + (kBlock * blk) * L::RS + perm32(EPL * lane);
     elem* krow = KD + (kBlock * blk) * L::RS + perm32(EPL * lane);
-    if constexpr (!SO) {
+    if constexpr (!SO || L::kTR) {
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) {
             if constexpr (EPL == 2) {
-                *(pair*)(qrow + i * L::RS) = st.q[i];
+                if constexpr (!SO) *(pair*)(qrow + i * L::RS) = st.q[i];
                 *(pair*)(krow + i * L::RS) = st.k[i];
             } else if (owner) {
-                P::store1(qrow + i * L::RS, P::lo(st.q[i]));
+                if constexpr (!SO) P::store1(qrow + i * L::RS, P::lo(st.q[i]));
                 P::store1(krow + i * L::RS, P::lo(st.k[i]));
             }
-            ldr.load_q(st, i);
+            if constexpr (!SO) ldr.load_q(st, i);
         }
     }
-    // k transposed
+    // k transposed (variants whose consumers cannot take it from the rows)
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
+    for (int e = 0; e < (L::kTR ? 0 : EPL); ++e) {
         float kt[kBlock];
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) kt[i] = (EPL == 2 && e == 1) ? P::hi(st.k[i]) : P::lo(st.k[i]);
@@ -876,7 +879,16 @@ __device__ __forceinline__ void load_block_frags(BlockFrags<P, VAR, DK>& f, cons
         f.tm = *(const frag*)((const elem*)(buf + L::oTM) + r * kBlock + 4 * g);
     }
     if constexpr (EARLY) f.fv = *(const frag*)((const elem*)(buf + L::oVT) + (16 * cw + r) * L::TS + 4 * g);
-    if constexpr (LATE) {
+    if constexpr (LATE && L::kTR) {
+        // k^T of tile s (rows d = 16 s + r, slots tokens 4g .. 4g + 3) from the k rows: lane l of a group of 16
+        // addresses four stored elements of token 4g + l / 4 -- dimensions 16 s + 4 (l % 4) .. + 3, which the rows'
+        // permutation keeps adjacent -- and receives dimension 16 s + l of the group's four tokens.
+        typedef __attribute__((address_space(3))) frag lds_frag;
+        const elem* kp = (const elem*)(buf + L::oKD) + (4 * g + (r >> 2)) * L::RS + 8 * (r & 3);
+#pragma unroll
+        for (int s = 0; s < NTILE; ++s)
+            f.fk[s] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_frag*)(kp + 32 * (s / 2) + 4 * (s & 1)));
+    } else if constexpr (LATE) {
         const elem* KBT = (const elem*)(buf + L::oKBT);
 #pragma unroll
         for (int s = 0; s < NTILE; ++s)
