@@ -193,7 +193,9 @@ int sla_decode_step_fused(const sla_params* p, const void* q, const void* k, con
  * gradients that training through the chunkwise form of Sec. 3.2 (Chunkwise Parallel Training) needs.  With the
  * scalar objective L = sum(out * d_out) + sum(final_state * d_final_state) it writes dL/d(input) for every
  * differentiable input of the forward call made with the same p, q, k, v, logits, log_decay and initial_state.
- * bf16 tensors only (p->dtype == SLA_BF16); the delta rule has its own entry point, sla_backward_gdn.
+ * bf16 tensors run in block form on the matrix cores; fp32 tensors (p->dtype == SLA_F32) run token by token in fp32
+ * vector arithmetic (gradients to fp32 rounding, any log_decay <= 0, single pass only: p->segments >= 2 is
+ * SLA_ERR_UNSUPPORTED).  The delta rule has its own entry point, sla_backward_gdn.
  * p->dv_split is ignored.  p->segments >= 2 asks for the segment-parallel schedule (for batches with few sequences,
  * as in sla_forward_ws): every batch row is cut into that many segments (of a multiple of 64 tokens, at least 256)
  * which run in parallel; the entry state and the end cotangent of every segment come from two pre-passes.  It needs
@@ -210,7 +212,7 @@ int sla_decode_step_fused(const sla_params* p, const void* q, const void* k, con
  *   dlog_decay       GLA: [B,T,H,dk] dtype, written, required;  RetNet: must be NULL (the decay is a constant)
  *   d_initial_state  [B,H,dk,dv] fp32    written, or NULL (not wanted)
  *   workspace        device memory of at least sla_backward_workspace_bytes(p) bytes, 16-byte aligned; holds
- *                    the gates, partial gate gradients and (GLA) block sums of q * dq and the state entering
+ *                    the gates, partial gate gradients and (GLA, bf16) block sums of q * dq and the state entering
  *                    every 512th token of a sequence (dlog_decay is re-derived from rowsum(dS * S) there, so its
  *                    error does not grow with the sequence length).  Contents on entry are ignored; calls that
  *                    share a workspace must not overlap.

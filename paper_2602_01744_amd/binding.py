@@ -296,11 +296,11 @@ def forward_varlen(variant: int, q, k, v, q_head_logits, k_head_logits, log_deca
 
 def backward_varlen(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_out, cu_seqlens,
                     initial_state=None, d_final_state=None, *, want_d_initial_state: bool = False):
-    """Gradients of ``forward_varlen`` (RetNet, GLA; bfloat16); tensors packed as there.  Returns a dict as
-    ``backward`` does, with d_initial_state [B,H,dk,dv]."""
+    """Gradients of ``forward_varlen`` (RetNet, GLA; bfloat16 or float32); tensors packed as there.  Returns a dict
+    as ``backward`` does, with d_initial_state [B,H,dk,dv]."""
     import torch
 
-    assert q.is_cuda and q.dtype == torch.bfloat16
+    assert q.is_cuda and q.dtype in (torch.bfloat16, torch.float32)
     T, H, dk = q.shape
     dv = v.shape[-1]
     B = cu_seqlens.numel() - 1
@@ -314,7 +314,7 @@ def backward_varlen(variant: int, q, k, v, q_head_logits, k_head_logits, log_dec
         "dlog_decay": torch.empty_like(log_decay) if variant == GLA else None,
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, 0, 1)
+    params = SlaParams(variant, BF16 if q.dtype == torch.bfloat16 else F32, B, T, H, dk, dv, 0, 0, 1)
     need = sla_backward_varlen_workspace_bytes(params)
     workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     ptr = lambda t: None if t is None else t.data_ptr()
@@ -483,14 +483,15 @@ def sla_backward(params, q, k, v, q_head_logits, k_head_logits, log_decay, initi
 def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_out, initial_state=None,
              d_final_state=None, *, want_d_initial_state: bool = False, workspace=None, head_major: bool = False,
              segments: int = 1):
-    """Gradients of ``forward`` (RetNet, GLA; bfloat16) on the current CUDA(HIP) device and stream.  Returns a dict
+    """Gradients of ``forward`` (RetNet, GLA; bfloat16, or float32 in the single pass) on the current CUDA(HIP) device
+    and stream.  Returns a dict
     of new tensors: dq, dk, dv, dq_head_logits, dk_head_logits (None without k_head_logits), dlog_decay (GLA only,
     else None) and d_initial_state (None unless asked for).  ``segments`` >= 2 cuts every batch row into that many
     segments that run in parallel (for batches with few sequences); 0 asks ``sla_backward_segments`` for the count
     that fills this device."""
     import torch
 
-    assert q.is_cuda and q.dtype == torch.bfloat16
+    assert q.is_cuda and q.dtype in (torch.bfloat16, torch.float32)
     if head_major:  # q, k, v, d_out, the GLA decay and their gradients are [B,H,T,d]
         B, H, T, dk = q.shape
     else:
@@ -514,7 +515,8 @@ def backward(variant: int, q, k, v, q_head_logits, k_head_logits, log_decay, d_o
         "dlog_decay": torch.empty_like(log_decay) if variant == GLA else None,
         "d_initial_state": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None,
     }
-    params = SlaParams(variant, BF16, B, T, H, dk, dv, 0, FLAG_HEAD_MAJOR if head_major else 0, max(int(segments), 1))
+    params = SlaParams(variant, BF16 if q.dtype == torch.bfloat16 else F32, B, T, H, dk, dv, 0,
+                       FLAG_HEAD_MAJOR if head_major else 0, max(int(segments), 1))
     if int(segments) == 0:
         cus = torch.cuda.get_device_properties(q.device).multi_processor_count
         params.segments = max(sla_backward_segments(params, cus), 1)

@@ -363,7 +363,8 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
                          void* workspace, size_t workspace_bytes, const int32_t* cu, bool packed, void* stream) {
     int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->dk < 64 || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
+    if (p->variant == SLA_GDN || p->dk < 64 || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
+    if (p->dtype == SLA_F32 && p->segments >= 2) return SLA_ERR_UNSUPPORTED;  // fp32 tensors: the single pass only
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !d_out || !dq || !dk || !dv || !dq_head_logits)
             return SLA_ERR_NULL;
@@ -574,12 +575,13 @@ int sla_gate_logits_backward(const sla_params* p, const void* x, const float* w,
 }
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->dk < 64) return 0;
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dk < 64) return 0;
+    if (p->dtype == SLA_F32 && p->segments >= 2) return 0;
     return backward_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_varlen_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dtype != SLA_BF16 || p->dk < 64) return 0;
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dk < 64) return 0;
     return sla::backward_workspace_floats(*p, true) * sizeof(float);
 }
 
@@ -594,7 +596,8 @@ int sla_backward_segments(const sla_params* p, int compute_units) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
     if (compute_units <= 0) return SLA_ERR_SHAPE;
-    if (p->B == 0 || p->T == 0 || p->variant == SLA_GDN || p->flags != 0 || p->dk < 64) return 1;  // no backward there
+    if (p->B == 0 || p->T == 0 || p->variant == SLA_GDN || p->flags != 0 || p->dk < 64 || p->dtype == SLA_F32)
+        return 1;  // no backward, or no segment schedule, there
     const int64_t wgs = (int64_t)p->B * p->H * ((p->dk < p->dv ? p->dk : p->dv) / 64);
     const int want = (int)((compute_units + wgs - 1) / wgs);
     if (want <= 1) return 1;

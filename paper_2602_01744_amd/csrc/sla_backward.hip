@@ -1198,8 +1198,8 @@ __global__ __launch_bounds__(kEwThreads) void sla_bwd_gates_kernel(const float* 
 // Packed batches (cu != null): rows outside [cu[0], cu[B]) belong to no sequence; the sweeps never wrote their
 // partial planes, and their gradients are not written either.
 __global__ __launch_bounds__(kEwThreads) void sla_bwd_logits_kernel(const float* g, const float* part, int planes,
-                                                                     float* dl, size_t rows, int H, const int* cu,
-                                                                     int B) {
+                                                                     size_t plane, float* dl, size_t rows, int H,
+                                                                     const int* cu, int B) {
     __shared__ float sx[kEwThreads];
     const int per = kEwThreads / H, tid = threadIdx.x, lr = tid / H, h = tid - lr * H;
     const size_t row = (size_t)blockIdx.x * per + lr;
@@ -1210,7 +1210,7 @@ __global__ __launch_bounds__(kEwThreads) void sla_bwd_logits_kernel(const float*
     }
     float dg = 0.f, gv = 0.f;
     if (ok) {
-        for (int p = 0; p < planes; ++p) dg += part[(size_t)p * rows * H + row * H + h];
+        for (int p = 0; p < planes; ++p) dg += part[(size_t)p * plane + row * H + h];
         gv = g[row * H + h];
     }
     sx[tid] = gv * dg;
@@ -1289,10 +1289,28 @@ int launch_bwd_gates(const float* ql, const float* kl, float* gq, float* gk, siz
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 
+// dlogits = G * (dG - sum_h G dG) with dG the sum of `planes` partial planes, `plane` floats apart (shared with the
+// fp32 path).
+int launch_bwd_logits(const float* g, const float* part, int planes, size_t plane, float* dl, size_t rows, int H,
+                      const int* cu, int B, hipStream_t stream) {
+    if (rows == 0) return SLA_OK;
+    const unsigned per = kEwThreads / (unsigned)H, eg = (unsigned)((rows + per - 1) / per);
+    hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(kEwThreads), 0, stream, g, part, planes, plane, dl, rows,
+                       H, cu, B);
+    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+}
+
+size_t backward_f32_workspace_floats(const sla_params& p, bool packed);  // sla_backward_f32.hip
+int launch_backward_f32(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
+                        const float* kl, const void* ld, const float* s0, const void* dout, const float* dsf, void* dq,
+                        void* dk, void* dv, float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu,
+                        hipStream_t stream);
+
 // Workspace, in floats: gates G^Q, G^K [B,T,H]; partial dG^Q and dG^K (dk/16 planes each); for GLA the sums of
 // q * dq over every 16-token block [rows/16 + B + 1][H,dk], the final-state term of dlog_decay [B,H,dk] and the
 // states kept every 512 tokens [rows/512 + 1][H,dk,dv] in bf16.
 size_t backward_workspace_floats(const sla_params& p, bool packed) {
+    if (p.dtype == SLA_F32) return backward_f32_workspace_floats(p, packed);
     const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T;
     const size_t n = round4(rows * p.H);
     size_t total = n * (2 + 2 * (p.dk / 16));
@@ -1424,6 +1442,8 @@ int launch_backward_segments(const sla_params& p, int nseg, int seg_len, int dvw
 int launch_backward(const sla_params& p, const void* q, const void* k, const void* v, const float* ql, const float* kl,
                     const void* ld, const float* s0, const void* dout, const float* dsf, void* dq, void* dk, void* dv,
                     float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu, hipStream_t stream) {
+    if (p.dtype == SLA_F32)  // fp32 tensors: token by token in fp32 vector arithmetic
+        return launch_backward_f32(p, q, k, v, ql, kl, ld, s0, dout, dsf, dq, dk, dv, dql, dkl, dld, ds0, ws, cu, stream);
     return launch_backward_some(p, q, k, v, ql, kl, ld, s0, dout, dsf, dq, dk, dv, dql, dkl, dld, ds0, ws, cu, stream, 7,
                                 false);
 }
@@ -1467,13 +1487,10 @@ int launch_backward_some(const sla_params& p, const void* q, const void* k, cons
     const int rc = p.variant == SLA_GLA ? launch_dk<SLA_GLA>(a, p.dk, p.dv, stream)
                                         : launch_dk<SLA_RETNET>(a, p.dk, p.dv, stream);
     if (rc != SLA_OK || rows == 0 || sweeps != 7) return rc;
-    // the planes of one gate are n floats apart (n >= rows * H); the kernel indexes them by rows * H
-    hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gq, (const float*)a.part_q,
-                       p.dk / 16, dql, rows, p.H, cu, p.B);
-    if (kl)
-        hipLaunchKernelGGL(sla_bwd_logits_kernel, dim3(eg), dim3(eb), 0, stream, (const float*)gk,
-                           (const float*)a.part_k, p.dk / 16, dkl, rows, p.H, cu, p.B);
-    return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
+    // the sweeps write the planes of one gate rows * H floats apart (the space reserved per plane is n >= rows * H)
+    int rl = launch_bwd_logits(gq, a.part_q, p.dk / 16, rows * p.H, dql, rows, p.H, cu, p.B, stream);
+    if (rl == SLA_OK && kl) rl = launch_bwd_logits(gk, a.part_k, p.dk / 16, rows * p.H, dkl, rows, p.H, cu, p.B, stream);
+    return rl;
 }
 
 }  // namespace sla

@@ -185,7 +185,7 @@ def _bwd(p, **kw):
 def test_backward_rejects_bad_calls(lib):
     ok = _ok_params()
     assert _bwd(_ok_params(variant=sla.GDN)) == -3           # the delta rule's backward is sla_backward_gdn
-    assert _bwd(_ok_params(dtype=sla.F32)) == -3             # bf16 only
+    assert _bwd(_ok_params(dtype=sla.F32, segments=2, T=1024)) == -3   # fp32 tensors: the single pass only
     assert _bwd(_ok_params(dk=96)) == -3
     assert _bwd(ok, dout=0) == -1
     assert _bwd(ok, dq=0) == -1
@@ -213,7 +213,12 @@ def test_backward_workspace_size(lib):
     big = sla.sla_backward_workspace_bytes(_ok_params(B=8, T=2048, H=16, dk=128, dv=128))
     assert big == 4 * (8 * 2048 * 16 * 18 + (1024 + 9) * 2048 + 8 * 2048 + 33 * 16 * 128 * 128 // 2)
     assert sla.sla_backward_workspace_bytes(_ok_params(variant=sla.GDN)) == 0
-    assert sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32)) == 0
+    # fp32 tensors: gates, dk/8 + dv/8 partial planes, GLA the final-state term of the decay gradient [B,H,dk]
+    f32 = sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv))
+    assert f32 == 4 * (n * (2 + dk // 8 + dv // 8) + B * H * dk)
+    f32r = sla.sla_backward_workspace_bytes(_ok_params(variant=sla.RETNET, dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv))
+    assert f32r == 4 * n * (2 + dk // 8 + dv // 8)
+    assert sla.sla_backward_workspace_bytes(_ok_params(dtype=sla.F32, B=B, T=1024, H=H, dk=dk, dv=dv, segments=2)) == 0
 
 
 def test_gate_logits_rejects_bad_calls(lib):

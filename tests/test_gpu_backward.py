@@ -16,15 +16,15 @@ NAMES = {"dq": "dq", "dk": "dk", "dv": "dv", "dq_head_logits": "dq_logits", "dk_
          "dlog_decay": "dlog_decay", "d_initial_state": "dinitial_state"}
 
 
-def run_backward(variant, d, cot, s0=None, want_ds0=False, segments=1):
+def run_backward(variant, d, cot, s0=None, want_ds0=False, segments=1, dtype="bf16"):
     import torch
     import paper_2602_01744_amd as sla
 
-    g, _ = to_device(d, "bf16", variant)
+    g, tdt = to_device(d, dtype, variant)
     dev = torch.device("cuda:0")
     up = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
     res = sla.backward(variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"],
-                       up(cot["d_out"], torch.bfloat16), up(s0, torch.float32), up(cot["d_final_state"], torch.float32),
+                       up(cot["d_out"], tdt), up(s0, torch.float32), up(cot["d_final_state"], torch.float32),
                        want_d_initial_state=want_ds0, segments=segments)
     torch.cuda.synchronize()
     return {n: None if t is None else t.to(torch.float32).cpu().numpy().astype(np.float64) for n, t in res.items()}
@@ -36,9 +36,11 @@ def run_backward(variant, d, cot, s0=None, want_ds0=False, segments=1):
 SLICE_TOL = {}
 
 
-def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_rows=None, segments=1, c_oracle=False):
-    """c_oracle: the reference is the C gradient oracle (whole workloads in seconds) instead of the numpy one."""
-    got = run_backward(variant, d, cot, s0, want_ds0, segments)
+def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_rows=None, segments=1, c_oracle=False,
+                   dtype="bf16"):
+    """c_oracle: the reference is the C gradient oracle (whole workloads in seconds) instead of the numpy one.
+    dtype: the tensors' element type; the bar is TOL[dtype]."""
+    got = run_backward(variant, d, cot, s0, want_ds0, segments, dtype)
     rows = slice(None) if batch_rows is None else batch_rows
     sub = lambda a: None if a is None else (a if a.ndim == 1 else a[rows])
     fn = oracle.backward if c_oracle else ob.backward
@@ -66,8 +68,8 @@ def check_backward(variant, d, cot, s0=None, want_ds0=False, label="", batch_row
             slices[n] = worst_slice_err(x, r, 1 if n == "d_initial_state" else 2)
     print(f"[backward parity] {label} " + " ".join(f"{n}={e:.2e}/{slices[n]:.2e}" for n, e in errs.items()), flush=True)
     for n, e in errs.items():
-        assert e <= TOL["bf16"], f"{label}: {n} error {e:.3e} > {TOL['bf16']}"
-        bar = SLICE_TOL.get(n, TOL["bf16"])
+        assert e <= TOL[dtype], f"{label}: {n} error {e:.3e} > {TOL[dtype]}"
+        bar = SLICE_TOL.get(n, TOL[dtype])
         assert slices[n] <= bar, f"{label}: {n} error of the worst (batch, head) slice {slices[n]:.3e} > {bar}"
     return got, ref
 

@@ -50,15 +50,16 @@ def test_head_major_widths_and_ragged_length():
 
 
 @pytest.mark.parametrize("variant", [RETNET, GLA])
-def test_backward_head_major_matches_token_major(variant):
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_backward_head_major_matches_token_major(variant, dtype):
     import torch
     import paper_2602_01744_amd as sla
 
     B, T, H, dk, dv = 2, 203, 5, 128, 64
-    d = si.custom(variant, "bf16", B=B, T=T, H=H, dk=dk, dv=dv, seed=3300 + variant)
-    g, _ = to_device(d, "bf16", variant)
+    d = si.custom(variant, dtype, B=B, T=T, H=H, dk=dk, dv=dv, seed=3300 + variant)
+    g, tdt = to_device(d, dtype, variant)
     cot = si.cotangents(B, T, H, dk, dv, seed=3301, final_state=True)
-    dout = torch.from_numpy(cot["d_out"]).to(torch.bfloat16).cuda()
+    dout = torch.from_numpy(cot["d_out"]).to(tdt).cuda()
     dsf = torch.from_numpy(cot["d_final_state"]).cuda()
     s0 = torch.from_numpy(si.initial_state(B, H, dk, dv, seed=33)).cuda()
     ref = sla.backward(variant, g["q"], g["k"], g["v"], g["q_logits"], g["k_logits"], g["log_decay"], dout, s0, dsf,

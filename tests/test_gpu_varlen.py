@@ -59,20 +59,21 @@ def test_forward_varlen(variant, dtype):
 
 
 @pytest.mark.parametrize("variant", [RETNET, GLA])
-def test_backward_varlen(variant):
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_backward_varlen(variant, dtype):
     import torch
     import paper_2602_01744_amd as sla
 
     H, dk, dv = 3, 128, 64
-    d, cu = pack(variant, "bf16", LENGTHS, H, dk, dv, seed=1410 + variant)
+    d, cu = pack(variant, dtype, LENGTHS, H, dk, dv, seed=1410 + variant)
     B, T = len(LENGTHS), int(cu[-1])
     s0 = si.initial_state(B, H, dk, dv, seed=15)
     cot = si.cotangents(1, T, H, dk, dv, seed=1411)
     dsf = si.initial_state(B, H, dk, dv, seed=16)
-    g, _ = to_device(d, "bf16", variant)
+    g, tdt = to_device(d, dtype, variant)
     sq = lambda t: None if t is None else (t if t.dim() == 1 else t[0].contiguous())
     res = sla.backward_varlen(variant, sq(g["q"]), sq(g["k"]), sq(g["v"]), sq(g["q_logits"]), sq(g["k_logits"]),
-                              sq(g["log_decay"]), torch.from_numpy(cot["d_out"][0]).to(torch.bfloat16).cuda(),
+                              sq(g["log_decay"]), torch.from_numpy(cot["d_out"][0]).to(tdt).cuda(),
                               torch.from_numpy(cu).cuda(), torch.from_numpy(s0).cuda(), torch.from_numpy(dsf).cuda(),
                               want_d_initial_state=True)
     torch.cuda.synchronize()
@@ -89,10 +90,10 @@ def test_backward_varlen(variant):
                           cot["d_out"][:, a:b], s0[i:i + 1], dsf[i:i + 1])
         errs = {n: rel_err(got[n][a:b], ref[rn][0]) for n, rn in names.items()}
         errs["d_initial_state"] = rel_err(got["d_initial_state"][i], ref["dinitial_state"][0])
-        print(f"[varlen backward] {si.VARIANT_NAMES[variant]} seq {i} len {b - a}: " +
+        print(f"[varlen backward] {dtype} {si.VARIANT_NAMES[variant]} seq {i} len {b - a}: " +
               " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
         for n, e in errs.items():
-            assert e <= TOL["bf16"], (i, n, e)
+            assert e <= TOL[dtype], (i, n, e)
 
 
 def test_backward_varlen_gdn():
