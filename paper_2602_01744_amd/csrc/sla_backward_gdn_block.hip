@@ -140,7 +140,7 @@ struct Areas {
     bf* mid;       // [blocks][H][kMidMats][C][C]
     bf* res;       // [blocks][H][dv][C]
     bf* w;         // [blocks][H][dv][C]
-    float* dk2;    // [rows][H][dk]
+    bf* dk2;       // [blocks][H][dk/4][C][4]: the X-part of dk, four adjacent key columns of a token together
 };
 __host__ __device__ inline size_t round4(size_t n) { return (n + 3) & ~(size_t)3; }
 __host__ __device__ inline Areas areas(float* ws, size_t blocks, size_t rows, int H, int dk, int dv) {
@@ -152,7 +152,7 @@ __host__ __device__ inline Areas areas(float* ws, size_t blocks, size_t rows, in
     r.mid = (bf*)p; p += bh * kMidMats * kMat / 2;
     r.res = (bf*)p; p += bh * (size_t)dv * C / 2;
     r.w = (bf*)p; p += bh * (size_t)dv * C / 2;
-    r.dk2 = p;
+    r.dk2 = (bf*)p;
     (void)rows; (void)dk;
     return r;
 }
@@ -757,8 +757,10 @@ struct Stage3 {
     static constexpr int RD = FWD ? rows_stride(DV) : cols_stride(DV);   // d_out rows
     static constexpr int SR = FWD ? kSmR : kSmC, SW = FWD ? kSmC : kSmR;  // res, w
     static constexpr int SQ = FWD ? kSlR : kSlC;                          // the q slice (k slice: by columns in both)
+    static constexpr int NM = FWD ? 1 : 2;                                // matrices of the mid pass
     static constexpr int oR = 0, oW = oR + DV * SR * 2, oO = oW + DV * SW * 2, oQ = oO + C * RD * 2,
-                         oK = oQ + C * SQ * 2, oM = oK + C * kSlC * 2, oS = oM + 2 * C * kSmR * 2,
+                         oK = oQ + C * SQ * 2, oM = oK + C * kSlC * 2, oD = oM + NM * C * kSmR * 2,
+                         oS = oD + (FWD ? kCols * C * 2 : 0),             // sweep 4: the slice's X-part of dk
                          bytes = oS + kScal * 4;
 };
 template <int DK, int DV, int FIRST, int NMAT, bool FWD>  // the mid-pass matrices FIRST .. FIRST + NMAT - 1
@@ -768,6 +770,7 @@ struct Load3 {
     Rows<C, kCols * 2> q, k;
     Rows<NMAT * C, 64> m;
     Rows<kKinds, C * 4> sc;
+    Rows<C, 128> d2;  // sweep 4: [16 groups of four key columns][32 tokens][4], contiguous
     __device__ __forceinline__ void load(const Frame& f, int I, int lt) {
         const size_t row = f.row0(I) * f.a.H + f.s.h, bhi = f.bhi(I);
         const int valid = f.valid(I), d0 = f.s.slice * kCols;
@@ -778,9 +781,11 @@ struct Load3 {
         k.load(f.a.k + row * DK + d0, (size_t)f.a.H * DK * 2, valid, lt);
         m.load(f.ar.mid + bhi * (size_t)(kMidMats * kMat) + FIRST * kMat, C * 2, NMAT * C, lt);
         sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
+        if constexpr (FWD) d2.load(f.ar.dk2 + bhi * (size_t)(DK * C) + (size_t)d0 * C, 128, C, lt);
     }
     __device__ __forceinline__ void put(unsigned char* st, int lt) const {
         typedef Stage3<DV, FWD> L;
+        static_assert(L::NM == NMAT, "the stage holds the matrices this sweep loads");
         rs.put(st + L::oR, L::SR * 2, lt);
         wv.put(st + L::oW, L::SW * 2, lt);
         o.put(st + L::oO, L::RD * 2, lt);
@@ -788,6 +793,7 @@ struct Load3 {
         k.put(st + L::oK, kSlC * 2, lt);
         m.put(st + L::oM, kSmR * 2, lt);
         sc.put(st + L::oS, C * 4, lt);
+        if constexpr (FWD) d2.put(st + L::oD, 128, lt);
     }
 };
 
@@ -829,15 +835,14 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
                 mma(dkT[1], aX, op_cols(Rf, kSmC, 16 * t, 16, r, g));
             }
             const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
-            const int valid = f.valid(I);
-            const size_t row0 = f.row0(I);
+            bf* dk2 = ar.dk2 + f.bhi(I) * (size_t)(DK * C);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 const int tt = 16 * ta + r;
                 dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
                 mma(dkT[ta], aK, op_rows(Ms, kSmR, tt, 0, g));
                 mma(dkT[ta], aQ, op_rows(Nt, kSmR, tt, 0, g));
-                if (tt < valid) *(f4*)(ar.dk2 + ((row0 + tt) * a.H + s.h) * DK + d0 + 16 * w + 4 * g) = dkT[ta];
+                *(u2*)(dk2 + ((size_t)(((d0 + 16 * w) >> 2) + g) * C + tt) * 4) = pack4(dkT[ta]);  // rows >= valid: never read
             }
             const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
             const s8 bq = scale8(aQ, p0 * sc4(sc, kGq, 4 * g), p1 * sc4(sc, kGq, 16 + 4 * g));
@@ -884,13 +889,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
             const float* sc = (const float*)(st + L::oS);
             const int valid = f.valid(I);
             const size_t row0 = f.row0(I);
-            f4 dk2[2];
-#pragma unroll
-            for (int ta = 0; ta < 2; ++ta) {
-                const int tt = 16 * ta + r;
-                dk2[ta] = tt < valid ? *(const f4*)(ar.dk2 + ((row0 + tt) * a.H + s.h) * DK + d0 + 16 * w + 4 * g)
-                                     : f4{0.f, 0.f, 0.f, 0.f};
-            }
+            const bf* D2 = (const bf*)(st + L::oD) + ((4 * w + g) * C + r) * 4;  // the X-part of dk, this lane's columns
             f4 dqT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
             f4 dkT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
@@ -917,7 +916,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
                     const size_t at = (row0 + tt) * a.H + s.h;
                     if (g == 0) a.part_q[(size_t)plane * a.plane + at] = pq;
                     *(u2*)(a.dq + at * DK + d0 + 16 * w + 4 * g) = pack4(dqT[ta] * sc[kGq * C + tt]);
-                    *(u2*)(a.dk + at * DK + d0 + 16 * w + 4 * g) = pack4(dk2[ta] - pt * dkT[ta]);
+                    *(u2*)(a.dk + at * DK + d0 + 16 * w + 4 * g) = pack4(unpack4(*(const s4*)(D2 + 16 * ta * 4)) - pt * dkT[ta]);
                 }
             }
             const s8 bk = scale8(aK, sc4(sc, kBeta, 4 * g) * sc4(sc, kAP, 4 * g),
@@ -996,7 +995,8 @@ int launch_dv(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t
 
 size_t gdn_block_workspace_floats(int B, int T, int H, int dk, int dv, bool packed) {
     const size_t blocks = ws_blocks(B, T, packed), rows = packed ? (size_t)T : (size_t)B * T, bh = blocks * (size_t)H;
-    return bh * kScal + bh * (kPreMats + kMidMats) * kMat / 2 + 2 * (bh * (size_t)dv * C / 2) + round4(rows * H * dk);
+    (void)rows;
+    return bh * kScal + bh * (kPreMats + kMidMats) * kMat / 2 + 2 * (bh * (size_t)dv * C / 2) + bh * (size_t)dk * C / 2;
 }
 
 int launch_gdn_block_sweeps(const GdnBlockArgs& a, hipStream_t stream) {
