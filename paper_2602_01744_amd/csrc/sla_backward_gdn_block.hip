@@ -16,8 +16,9 @@
 //     dk  = diag(A / p) U X1^T - diag(p) w S0^T + (M + M^T) K + N^T Q
 //           M = strict_tril(-D * w U^T)              N = diag(G^Q) N'
 // The decay gradient needs no state product (see sla_backward_gdn.hip).  The 32 x 32 matrices depend on one block
-// only and are produced by two kernels that run over all blocks in parallel (`pre`: from q, k, the decays and beta;
-// `mid`: from res, w and dOut); what remains serial are four sweeps that each carry one state tile in fp32 matrix-core
+// only: those made of q, k, the decays and beta come from a kernel that runs over all blocks in parallel (`pre`);
+// M and N', made of res, w and dOut, are formed by sweeps 3 and 4 themselves from the rows they hold anyway; what
+// remains serial are four sweeps that each carry one state tile in fp32 matrix-core
 // accumulators, as in the token-recurrent version: (1) forward, S sliced over value columns -> res; (2) backward, X
 // sliced over value columns -> w, dv, dG^K, dbeta, d_initial_state; (3) backward, X^T sliced over key columns -> the
 // part of dk that needs X; (4) forward, S^T sliced over key columns -> dq, dG^Q, dk, <d_final, S_T>.
@@ -33,7 +34,7 @@
 //
 // Intermediates in the workspace: res and w as bf16 [block][head][column][32 tokens] (a lane's four tokens of an
 // accumulator tile are one 8-byte store), the 32 x 32 matrices as bf16, per-token scalars as fp32, the X-part of dk as
-// fp32 [token][head][dk].
+// bf16 [block][head][dk/4][32 tokens][4].
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -53,7 +54,6 @@ constexpr int kLoaders = 256;
 constexpr int kCols = 64;        // columns of a state slice per workgroup
 constexpr int kMat = C * C;                  // elements of a 32 x 32 matrix
 enum { mT1 = 0, mT2 = 1, mT3 = 2, mT4 = 3, kPreMats = 4 };   // pre-pass: T', (T' diag-beta)^T, (diag(G^Q) Lq)^T, -Lk^T
-enum { mMs = 0, mNT = 1, mNp = 2, kMidMats = 3 };            // mid pass: M + M^T, N^T, N'
 
 // ---- rows of a 2-D array, global -> registers -> LDS, by the 256 loader threads, 16 bytes a piece -----------
 template <int R, int RB>
@@ -137,7 +137,6 @@ __device__ __forceinline__ Seq where(const GdnBlockArgs& a, int nslices) {
 struct Areas {
     float* scal;   // [blocks][H][kKinds][C]
     bf* pre;       // [blocks][H][kPreMats][C][C]
-    bf* mid;       // [blocks][H][kMidMats][C][C]
     bf* res;       // [blocks][H][dv][C]
     bf* w;         // [blocks][H][dv][C]
     bf* dk2;       // [blocks][H][dk/4][C][4]: the X-part of dk, four adjacent key columns of a token together
@@ -149,7 +148,6 @@ __host__ __device__ inline Areas areas(float* ws, size_t blocks, size_t rows, in
     float* p = ws;
     r.scal = p; p += bh * kScal;
     r.pre = (bf*)p; p += bh * kPreMats * kMat / 2;
-    r.mid = (bf*)p; p += bh * kMidMats * kMat / 2;
     r.res = (bf*)p; p += bh * (size_t)dv * C / 2;
     r.w = (bf*)p; p += bh * (size_t)dv * C / 2;
     r.dk2 = (bf*)p;
@@ -338,110 +336,6 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// Mid pass (after sweep 2): one wave per (block, head).  M + M^T, N^T, N' from res, w and dOut.
-// ------------------------------------------------------------------------------------------------------------
-// op_rows from global memory (rows >= valid read as zero)
-__device__ __forceinline__ s8 op_rows_global(const bf* rows, size_t gstride, int row, int valid, int k0, int g) {
-    const u2 z = {0u, 0u};
-    const bf* p = rows + (size_t)row * gstride + k0 + 4 * g;
-    const u2 lo = row < valid ? *(const u2*)p : z, hi = row < valid ? *(const u2*)(p + 16) : z;
-    return __builtin_bit_cast(s8, u4{lo.x, lo.y, hi.x, hi.y});
-}
-
-template <int DV>
-__global__ __launch_bounds__(64) void gdn_blk_mid_kernel(const GdnBlockArgs a, const Areas ar) {
-    constexpr int LS = 36;
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf* Wf = (bf*)smem;                  // [DV][kSmC]
-    bf* RSf = Wf + DV * kSmC;            // [DV][kSmC]
-    float* Mf = (float*)smem;            // [C][LS], over Wf once the products are done
-    float* Nf = Mf + C * LS;
-    static_assert(2 * C * LS * 4 <= 2 * DV * kSmC * 2, "the fp32 matrices fit over the staged operands");
-    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
-    const int h = blockIdx.x % a.H;
-    const size_t wb = blockIdx.x / a.H;
-    Seq s;
-    int I = 0;
-    if (!find_block(a, wb, s, I)) return;
-    const int valid = min(C, s.T - C * I);
-    const size_t row0 = s.tok0 + (size_t)C * I, bhi = wb * a.H + h;
-    {
-        const bf* wg = ar.w + bhi * (size_t)DV * C;
-        const bf* rg = ar.res + bhi * (size_t)DV * C;
-#pragma unroll
-        for (int n = 0; n < DV * 4 / 64; ++n) {
-            const int it = lane + 64 * n, row = it >> 2, c = it & 3;
-            *(u4*)(Wf + row * kSmC + 8 * c) = *(const u4*)(wg + row * C + 8 * c);
-            *(u4*)(RSf + row * kSmC + 8 * c) = *(const u4*)(rg + row * C + 8 * c);
-        }
-    }
-    __syncthreads();
-    const bf* og = a.dout + (row0 * a.H + h) * DV;
-    const size_t gstride = (size_t)a.H * DV;
-    f4 wu[3], ou[3];  // tiles (0,0), (1,0), (1,1): rows t = 16 tau + 4g + i, column j = 16 tau' + r
-#pragma unroll
-    for (int i = 0; i < 3; ++i) wu[i] = ou[i] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int n0 = 0; n0 < DV; n0 += 32) {
-        const s8 u_lo = op_cols(RSf, kSmC, n0, 0, r, g), u_hi = op_cols(RSf, kSmC, n0, 16, r, g);
-        const s8 w_lo = op_cols(Wf, kSmC, n0, 0, r, g), w_hi = op_cols(Wf, kSmC, n0, 16, r, g);
-        const s8 o_lo = op_rows_global(og, gstride, r, valid, n0, g), o_hi = op_rows_global(og, gstride, 16 + r, valid, n0, g);
-        mma(wu[0], w_lo, u_lo);
-        mma(wu[1], w_hi, u_lo);
-        mma(wu[2], w_hi, u_hi);
-        mma(ou[0], o_lo, u_lo);
-        mma(ou[1], o_hi, u_lo);
-        mma(ou[2], o_hi, u_hi);
-    }
-    __syncthreads();  // the staged operands are dead: their place takes M and N'
-    const float* sc = ar.scal + bhi * (size_t)kScal;
-    bf* mats = ar.mid + bhi * (size_t)(kMidMats * kMat);
-    *(u2*)(mats + mNT * kMat + (16 + r) * C + 4 * g) = u2{0u, 0u};  // N^T[j >= 16][t < 16] = 0
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {  // above the diagonal: t = 4g + i < 16 <= j = 16 + r
-        Mf[(4 * g + i) * LS + 16 + r] = 0.f;
-        Nf[(4 * g + i) * LS + 16 + r] = 0.f;
-    }
-#pragma unroll
-    for (int tile = 0; tile < 3; ++tile) {
-        const int ta = tile > 0, tb = tile > 1;
-        const int j = 16 * tb + r;
-        const float cj = sc[kCl * C + j], bj = sc[kBeta * C + j];
-        const f4 ct = sc4(sc, kCl, 16 * ta + 4 * g), gq4 = sc4(sc, kGq, 16 * ta + 4 * g);
-        f4 nn;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int tt = 16 * ta + 4 * g + i;
-            const float d = __builtin_amdgcn_exp2f(ct[i] - cj) * bj;
-            const float m = j < tt ? -d * wu[tile][i] : 0.f, np = j <= tt ? d * ou[tile][i] : 0.f;
-            Mf[tt * LS + j] = m;
-            Nf[tt * LS + j] = np;
-            nn[i] = np * gq4[i];
-        }
-        *(u2*)(mats + mNT * kMat + j * C + 16 * ta + 4 * g) = pack4(nn);  // N^T[j][t] = G^Q_t N'[t][j]
-    }
-    __syncthreads();
-    {
-        const int t = lane & 31, j0 = 16 * (lane >> 5);
-        bf* ms = mats + mMs * kMat + t * C + j0;
-        bf* np = mats + mNp * kMat + t * C + j0;
-        float m[16], n[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            m[j] = Mf[t * LS + j0 + j] + Mf[(j0 + j) * LS + t];
-            n[j] = Nf[t * LS + j0 + j];
-        }
-#pragma unroll
-        for (int j = 0; j < 16; j += 8) {
-            *(u4*)(ms + j) = u4{pack2(m[j], m[j + 1]), pack2(m[j + 2], m[j + 3]), pack2(m[j + 4], m[j + 5]),
-                                pack2(m[j + 6], m[j + 7])};
-            *(u4*)(np + j) = u4{pack2(n[j], n[j + 1]), pack2(n[j + 2], n[j + 3]), pack2(n[j + 4], n[j + 5]),
-                                pack2(n[j + 6], n[j + 7])};
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------------------------------
 // The sweeps.  Common frame: loaders fill stage (step + 1) % 2 while the compute waves work on stage step % 2.
 // ------------------------------------------------------------------------------------------------------------
 struct Frame {
@@ -456,9 +350,14 @@ struct Frame {
 // LOADER: struct with load(frame, I, lt) and put(stage, lt); BODY: callable (stage, I).  The loaders keep PF blocks in
 // flight in registers (block b in set b % PF): a block's rows are requested PF + 1 steps before the compute waves
 // need them, which covers the latency of HBM under load (with one block in flight a step lasted as long as a load).
-template <bool FWD, int PF, class LOADER, class BODY, class INIT, class FINI>
+// TWO: a step has two halves with a barrier between them: FIRST (stage, I) lets the compute waves write something
+// into the stage (matrices of the block) that all of them read in BODY.
+struct NoFirst {
+    __device__ __forceinline__ void operator()(unsigned char*, int) const {}
+};
+template <bool FWD, int PF, class LOADER, bool TWO = false, class BODY, class INIT, class FINI, class FIRST = NoFirst>
 __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, int stage_bytes, INIT&& init, BODY&& body,
-                                          FINI&& fini) {
+                                          FINI&& fini, FIRST&& first = NoFirst()) {
     const int tid = threadIdx.x, nblk = f.s.nblk;
     // Both sides run the same number of steps, a multiple of PF, so that the loaders' loop body has no branch in it
     // (the compiler then lets the loads of the other register sets stay outstanding across a put); steps past the
@@ -484,6 +383,7 @@ __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, i
                 LOADER& set = R[(u + 1) % PF];  // holds block step + 1 (base is a multiple of PF)
                 set.put(smem + ((step + 1) & 1) * stage_bytes, lt);
                 set.load(f, blk(step + 1 + PF), lt);
+                if constexpr (TWO) __syncthreads();
                 __syncthreads();
             }
         }
@@ -492,6 +392,10 @@ __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, i
         if (nblk > 0) {
             __syncthreads();
             for (int step = 0; step < nsteps; ++step) {
+                if constexpr (TWO) {
+                    if (step < nblk) first(smem + (step & 1) * stage_bytes, blk(step));
+                    __syncthreads();
+                }
                 if (step < nblk) body(smem + (step & 1) * stage_bytes, blk(step));
                 __syncthreads();
             }
@@ -751,24 +655,57 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
 }
 
 // ---- sweeps 3 and 4: X^T / S^T [dv, 16 key columns per wave] ---------------------------------------------------
+// The block-local matrices of these sweeps, M = strict_tril(-D * w U^T) (sweep 3 only) and N' = tril(D * dOut U^T),
+// made by the compute waves themselves from the rows the stage already holds (res and w as [dv][C], d_out as
+// [C][dv]): wave 0, 1, 2 the 16 x 16 tile (0,0), (1,0), (1,1), transposed so that a lane ends with four adjacent
+// columns of one row, wave 3 the zeros of tile (0,1).  Written as bf16 [C][kSmR]; read after a barrier.
+template <int DV, bool WITH_M>
+__device__ __forceinline__ void local_matrices(const bf* Rf, int SR, const bf* Wf, int SW, const bf* Of, int RD,
+                                               const float* sc, bf* Mm, bf* Np, int w, int r, int g) {
+    if (w == 3) {
+        if (WITH_M) *(u2*)(Mm + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
+        *(u2*)(Np + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
+        return;
+    }
+    const int ta = w > 0, tb = w > 1, tt = 16 * ta + r;
+    f4 wu = {0.f, 0.f, 0.f, 0.f}, ou = {0.f, 0.f, 0.f, 0.f};  // [i]: row tt, column 16 tb + 4g + i
+#pragma unroll
+    for (int n0 = 0; n0 < DV; n0 += 32) {
+        const s8 aU = op_cols(Rf, SR, n0, 16 * tb, r, g);
+        if (WITH_M) mma(wu, aU, op_cols(Wf, SW, n0, 16 * ta, r, g));
+        mma(ou, aU, op_rows(Of, RD, tt, n0, g));
+    }
+    const float ct = sc[kCl * C + tt];
+    const f4 cj = sc4(sc, kCl, 16 * tb + 4 * g), bj = sc4(sc, kBeta, 16 * tb + 4 * g);
+    f4 m, np;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = 16 * tb + 4 * g + i;
+        const float d = __builtin_amdgcn_exp2f(ct - cj[i]) * bj[i];
+        m[i] = j < tt ? -d * wu[i] : 0.f;
+        np[i] = j <= tt ? d * ou[i] : 0.f;
+    }
+    if (WITH_M) *(u2*)(Mm + tt * kSmR + 16 * tb + 4 * g) = pack4(m);
+    *(u2*)(Np + tt * kSmR + 16 * tb + 4 * g) = pack4(np);
+}
+
 // FWD = false: sweep 3 reads res and d_out by columns and w by rows; FWD = true: sweep 4, the other way round.
 template <int DV, bool FWD>
 struct Stage3 {
     static constexpr int RD = FWD ? rows_stride(DV) : cols_stride(DV);   // d_out rows
     static constexpr int SR = FWD ? kSmR : kSmC, SW = FWD ? kSmC : kSmR;  // res, w
     static constexpr int SQ = FWD ? kSlR : kSlC;                          // the q slice (k slice: by columns in both)
-    static constexpr int NM = FWD ? 1 : 2;                                // matrices of the mid pass
+    static constexpr int NM = FWD ? 1 : 2;                                // block-local matrices the compute waves make
     static constexpr int oR = 0, oW = oR + DV * SR * 2, oO = oW + DV * SW * 2, oQ = oO + C * RD * 2,
                          oK = oQ + C * SQ * 2, oM = oK + C * kSlC * 2, oD = oM + NM * C * kSmR * 2,
                          oS = oD + (FWD ? kCols * C * 2 : 0),             // sweep 4: the slice's X-part of dk
                          bytes = oS + kScal * 4;
 };
-template <int DK, int DV, int FIRST, int NMAT, bool FWD>  // the mid-pass matrices FIRST .. FIRST + NMAT - 1
+template <int DK, int DV, bool FWD>
 struct Load3 {
     Rows<DV, 64> rs, wv;
     Rows<C, DV * 2> o;
     Rows<C, kCols * 2> q, k;
-    Rows<NMAT * C, 64> m;
     Rows<kKinds, C * 4> sc;
     Rows<C, 128> d2;  // sweep 4: [16 groups of four key columns][32 tokens][4], contiguous
     __device__ __forceinline__ void load(const Frame& f, int I, int lt) {
@@ -779,19 +716,16 @@ struct Load3 {
         o.load(f.a.dout + row * DV, (size_t)f.a.H * DV * 2, valid, lt);
         q.load(f.a.q + row * DK + d0, (size_t)f.a.H * DK * 2, valid, lt);
         k.load(f.a.k + row * DK + d0, (size_t)f.a.H * DK * 2, valid, lt);
-        m.load(f.ar.mid + bhi * (size_t)(kMidMats * kMat) + FIRST * kMat, C * 2, NMAT * C, lt);
         sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
         if constexpr (FWD) d2.load(f.ar.dk2 + bhi * (size_t)(DK * C) + (size_t)d0 * C, 128, C, lt);
     }
     __device__ __forceinline__ void put(unsigned char* st, int lt) const {
         typedef Stage3<DV, FWD> L;
-        static_assert(L::NM == NMAT, "the stage holds the matrices this sweep loads");
         rs.put(st + L::oR, L::SR * 2, lt);
         wv.put(st + L::oW, L::SW * 2, lt);
         o.put(st + L::oO, L::RD * 2, lt);
         q.put(st + L::oQ, L::SQ * 2, lt);
         k.put(st + L::oK, kSlC * 2, lt);
-        m.put(st + L::oM, kSmR * 2, lt);
         sc.put(st + L::oS, C * 4, lt);
         if constexpr (FWD) d2.put(st + L::oD, 128, lt);
     }
@@ -809,7 +743,10 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
               g = lane >> 4;
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;  // this lane's key column
     f4 Xt[NT];  // Xt[t][i] = X[d][16 t + 4g + i]
-    run_sweep<false, (DV > 128 ? 2 : 4), Load3<DK, DV, mMs, 2, false>>(
+    f4 dkT[2];  // dk2^T[key column 4g + i][token 16 tau + r]: from the first half of a step to the second
+    // First half of a step: the block's M and N' (waves 0..2 a tile each), and everything that needs only the staged
+    // rows and X: the X-part of dk and the step of X itself.  Second half, after the barrier: the local terms.
+    run_sweep<false, (DV > 128 ? 2 : 4), Load3<DK, DV, false>, true>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -818,16 +755,36 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
                               : f4{0.f, 0.f, 0.f, 0.f};
         },
         [&](const unsigned char* st, int I) {
+            const bf* Qs = (const bf*)(st + L::oQ);
+            const bf* Ks = (const bf*)(st + L::oK);
+            const bf* Mm = (const bf*)(st + L::oM);
+            const bf* Np = Mm + C * kSmR;
+            const float* sc = (const float*)(st + L::oS);
+            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
+            const s8 aQg = scale8(aQ, sc4(sc, kGq, 4 * g), sc4(sc, kGq, 16 + 4 * g));  // N = diag(G^Q) N'
+            bf* dk2 = ar.dk2 + f.bhi(I) * (size_t)(DK * C);
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+                const int tt = 16 * ta + r;
+                dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
+                mma(dkT[ta], aK, op_rows(Mm, kSmR, tt, 0, g));            // M K
+                mma(dkT[ta], aK, op_cols(Mm, kSmR, 0, 16 * ta, r, g));   // M^T K
+                mma(dkT[ta], aQg, op_cols(Np, kSmR, 0, 16 * ta, r, g));  // N^T Q
+                *(u2*)(dk2 + ((size_t)(((d0 + 16 * w) >> 2) + g) * C + tt) * 4) = pack4(dkT[ta]);  // rows >= valid: never read
+            }
+        },
+        [&]() {},
+        [&](unsigned char* st, int) {
             const bf* Rf = (const bf*)(st + L::oR);
             const bf* Wf = (const bf*)(st + L::oW);
             const bf* Of = (const bf*)(st + L::oO);
             const bf* Qs = (const bf*)(st + L::oQ);
             const bf* Ks = (const bf*)(st + L::oK);
-            const bf* Ms = (const bf*)(st + L::oM);
-            const bf* Nt = Ms + C * kSmR;
             const float* sc = (const float*)(st + L::oS);
-            // dk2^T[key column 4g + i][token 16 tau + r] = (A/p beta)_t sum_n X[d][n] res[t][n] + local terms
-            f4 dkT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            bf* Mm = (bf*)(st + L::oM);
+            local_matrices<DV, true>(Rf, L::SR, Wf, L::SW, Of, RD, sc, Mm, Mm + C * kSmR, w, r, g);
+            // (A/p beta)_t sum_n X[d][n] res[t][n], scaled in the second half
+            dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < NT; t += 2) {
                 const s8 aX = pack8(Xt[t], Xt[t + 1]);
@@ -835,15 +792,6 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
                 mma(dkT[1], aX, op_cols(Rf, kSmC, 16 * t, 16, r, g));
             }
             const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
-            bf* dk2 = ar.dk2 + f.bhi(I) * (size_t)(DK * C);
-#pragma unroll
-            for (int ta = 0; ta < 2; ++ta) {
-                const int tt = 16 * ta + r;
-                dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
-                mma(dkT[ta], aK, op_rows(Ms, kSmR, tt, 0, g));
-                mma(dkT[ta], aQ, op_rows(Nt, kSmR, tt, 0, g));
-                *(u2*)(dk2 + ((size_t)(((d0 + 16 * w) >> 2) + g) * C + tt) * 4) = pack4(dkT[ta]);  // rows >= valid: never read
-            }
             const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
             const s8 bq = scale8(aQ, p0 * sc4(sc, kGq, 4 * g), p1 * sc4(sc, kGq, 16 + 4 * g));
             const s8 bk = scale8(aK, -p0, -p1);
@@ -854,8 +802,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
                 mma(Xt[t], op_cols(Of, RD, 0, 16 * t, r, g), bq);
                 mma(Xt[t], op_rows(Wf, kSmR, 16 * t + r, 0, g), bk);
             }
-        },
-        [&]() {});
+        });
 }
 
 template <int DK, int DV>
@@ -871,7 +818,8 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;
     const int plane = (d0 >> 4) + w;
     f4 St[NT];  // St[t][i] = S[d][16 t + 4g + i]
-    run_sweep<true, (DV > 128 ? 2 : 4), Load3<DK, DV, mNp, 1, true>>(
+    f4 dqT[2], dkT[2];  // from the first half of a step (the products with S0) to the second (local terms, stores)
+    run_sweep<true, (DV > 128 ? 2 : 4), Load3<DK, DV, true>, true>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -880,9 +828,6 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
                              : f4{0.f, 0.f, 0.f, 0.f};
         },
         [&](const unsigned char* st, int I) {
-            const bf* Rf = (const bf*)(st + L::oR);
-            const bf* Wf = (const bf*)(st + L::oW);
-            const bf* Of = (const bf*)(st + L::oO);
             const bf* Qs = (const bf*)(st + L::oQ);
             const bf* Ks = (const bf*)(st + L::oK);
             const bf* Np = (const bf*)(st + L::oM);
@@ -890,16 +835,6 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
             const int valid = f.valid(I);
             const size_t row0 = f.row0(I);
             const bf* D2 = (const bf*)(st + L::oD) + ((4 * w + g) * C + r) * 4;  // the X-part of dk, this lane's columns
-            f4 dqT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-            f4 dkT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-            for (int t = 0; t < NT; t += 2) {
-                const s8 aS = pack8(St[t], St[t + 1]);
-                mma(dqT[0], aS, op_rows(Of, RD, r, 16 * t, g));
-                mma(dqT[1], aS, op_rows(Of, RD, 16 + r, 16 * t, g));
-                mma(dkT[0], aS, op_cols(Wf, kSmC, 16 * t, 0, r, g));
-                mma(dkT[1], aS, op_cols(Wf, kSmC, 16 * t, 16, r, g));
-            }
             const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
@@ -919,14 +854,6 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
                     *(u2*)(a.dk + at * DK + d0 + 16 * w + 4 * g) = pack4(unpack4(*(const s4*)(D2 + 16 * ta * 4)) - pt * dkT[ta]);
                 }
             }
-            const s8 bk = scale8(aK, sc4(sc, kBeta, 4 * g) * sc4(sc, kAP, 4 * g),
-                                 sc4(sc, kBeta, 16 + 4 * g) * sc4(sc, kAP, 16 + 4 * g));
-            const float A = sc[kA * C];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                St[t] *= A;
-                mma(St[t], op_rows(Rf, kSmR, 16 * t + r, 0, g), bk);
-            }
         },
         [&]() {
             if (a.dsf) {  // <d_final, S_T> over this wave's 16 key columns
@@ -939,6 +866,32 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
                 }
                 acc = all_groups(row_all(acc));
                 if (lane == 0) a.corr[(size_t)plane * a.B * a.H + s.bh] = acc;
+            }
+        },
+        [&](unsigned char* st, int) {
+            const bf* Rf = (const bf*)(st + L::oR);
+            const bf* Wf = (const bf*)(st + L::oW);
+            const bf* Of = (const bf*)(st + L::oO);
+            const bf* Ks = (const bf*)(st + L::oK);
+            const float* sc = (const float*)(st + L::oS);
+            local_matrices<DV, false>(Rf, L::SR, nullptr, 0, Of, RD, sc, nullptr, (bf*)(st + L::oM), w, r, g);
+            dqT[0] = dqT[1] = dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 aS = pack8(St[t], St[t + 1]);
+                mma(dqT[0], aS, op_rows(Of, RD, r, 16 * t, g));
+                mma(dqT[1], aS, op_rows(Of, RD, 16 + r, 16 * t, g));
+                mma(dkT[0], aS, op_cols(Wf, kSmC, 16 * t, 0, r, g));
+                mma(dkT[1], aS, op_cols(Wf, kSmC, 16 * t, 16, r, g));
+            }
+            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
+            const s8 bk = scale8(aK, sc4(sc, kBeta, 4 * g) * sc4(sc, kAP, 4 * g),
+                                 sc4(sc, kBeta, 16 + 4 * g) * sc4(sc, kAP, 16 + 4 * g));
+            const float A = sc[kA * C];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                St[t] *= A;
+                mma(St[t], op_rows(Rf, kSmR, 16 * t + r, 0, g), bk);
             }
         });
 }
@@ -954,9 +907,7 @@ bool allow_lds(K kernel, int lds) {
 template <int DK, int DV>
 int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t stream) {
     constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 2 * Stage2<DK>::bytes, lds3 = 2 * Stage3<DV, false>::bytes, lds4 = 2 * Stage3<DV, true>::bytes;
-    constexpr int ldsm = 2 * DV * kSmC * 2;
-    static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && lds4 <= 160 * 1024 &&
-                      ldsm <= 160 * 1024, "LDS");
+    static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && lds4 <= 160 * 1024, "LDS");
     static std::atomic<uint64_t> configured{0};  // bit d: attributes set on device d
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
@@ -965,8 +916,7 @@ int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_
     }
     if (!((configured.load(std::memory_order_acquire) >> dev) & 1u)) {
         if (!allow_lds(gdn_blk_state_kernel<DK, DV>, lds1) || !allow_lds(gdn_blk_cotangent_kernel<DK, DV>, lds2) ||
-            !allow_lds(gdn_blk_key_kernel<DK, DV>, lds3) || !allow_lds(gdn_blk_query_kernel<DK, DV>, lds4) ||
-            !allow_lds(gdn_blk_mid_kernel<DV>, ldsm))
+            !allow_lds(gdn_blk_key_kernel<DK, DV>, lds3) || !allow_lds(gdn_blk_query_kernel<DK, DV>, lds4))
             return SLA_ERR_HIP;
         configured.fetch_or(uint64_t(1) << dev, std::memory_order_release);
     }
@@ -975,7 +925,6 @@ int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_
     hipLaunchKernelGGL((gdn_blk_pre_kernel<DK>), dim3(local), dim3(64), 0, stream, a, ar);
     hipLaunchKernelGGL((gdn_blk_state_kernel<DK, DV>), grid(DV / kCols), dim3(kThreads), (size_t)lds1, stream, a, ar);
     hipLaunchKernelGGL((gdn_blk_cotangent_kernel<DK, DV>), grid(DV / kCols), dim3(kThreads), (size_t)lds2, stream, a, ar);
-    hipLaunchKernelGGL((gdn_blk_mid_kernel<DV>), dim3(local), dim3(64), (size_t)ldsm, stream, a, ar);
     hipLaunchKernelGGL((gdn_blk_key_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds3, stream, a, ar);
     hipLaunchKernelGGL((gdn_blk_query_kernel<DK, DV>), grid(DK / kCols), dim3(kThreads), (size_t)lds4, stream, a, ar);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
@@ -996,7 +945,7 @@ int launch_dv(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t
 size_t gdn_block_workspace_floats(int B, int T, int H, int dk, int dv, bool packed) {
     const size_t blocks = ws_blocks(B, T, packed), rows = packed ? (size_t)T : (size_t)B * T, bh = blocks * (size_t)H;
     (void)rows;
-    return bh * kScal + bh * (kPreMats + kMidMats) * kMat / 2 + 2 * (bh * (size_t)dv * C / 2) + bh * (size_t)dk * C / 2;
+    return bh * kScal + bh * kPreMats * kMat / 2 + 2 * (bh * (size_t)dv * C / 2) + bh * (size_t)dk * C / 2;
 }
 
 int launch_gdn_block_sweeps(const GdnBlockArgs& a, hipStream_t stream) {
