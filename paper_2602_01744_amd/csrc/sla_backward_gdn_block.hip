@@ -53,7 +53,7 @@ constexpr int kThreads = 512;    // four compute waves + four loader waves
 constexpr int kLoaders = 256;
 constexpr int kCols = 64;        // columns of a state slice per workgroup
 constexpr int kMat = C * C;                  // elements of a 32 x 32 matrix
-enum { mT1 = 0, mT2 = 1, mT3 = 2, mT4 = 3, kPreMats = 4 };   // pre-pass: T', (T' diag-beta)^T, (diag(G^Q) Lq)^T, -Lk^T
+enum { mT1 = 0, kPreMats = 1 };   // pre-pass: T' 
 
 // ---- rows of a 2-D array, global -> registers -> LDS, by the 256 loader threads, 16 bytes a piece -----------
 template <int R, int RB>
@@ -156,7 +156,7 @@ __host__ __device__ inline Areas areas(float* ws, size_t blocks, size_t rows, in
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// Pre-pass: one wave per (block, head).  Scalars, T' = (I + Lk diag(beta))^-1, and the matrices of sweep 2.
+// Pre-pass: one wave per (block, head).  The per-token scalars and T' = (I + Lk diag(beta))^-1.
 // ------------------------------------------------------------------------------------------------------------
 // The workspace block `wb` belongs to sequence b when blk0(b) <= wb < blk0(b) + nblk(b).
 __device__ __forceinline__ bool find_block(const GdnBlockArgs& a, size_t wb, Seq& s, int& I) {
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
     constexpr int LS = 36;  // row stride of the fp32 matrices
     __shared__ __align__(16) float Lf[C * LS];   // Lk diag(beta)
     __shared__ __align__(16) float Tf[C * LS];   // T'
-    __shared__ __align__(16) float cs[C], bs[C], gqs[C];
+    __shared__ __align__(16) float cs[C], bs[C];
     const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
     const int h = blockIdx.x % a.H;
     const size_t wb = blockIdx.x / a.H;
@@ -220,7 +220,6 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
     if (lane < C) {
         cs[t] = c;
         bs[t] = bt;
-        gqs[t] = gqt;
         float* sc = ar.scal + ((wb * a.H + h) * (size_t)kScal);
         sc[kP * C + t] = __builtin_amdgcn_exp2f(c);
         sc[kAP * C + t] = __builtin_amdgcn_exp2f(c_end - c);
@@ -231,49 +230,33 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
         sc[kA * C + t] = __builtin_amdgcn_exp2f(c_end);
         sc[7 * C + t] = 0.f;
     }
-    // Gram tiles (tau, tau') of K K^T and Q K^T, operands straight from global memory: lane (r, g) ends up with rows
+    // Gram tiles (tau, tau') of K K^T, operands straight from global memory: lane (r, g) ends up with rows
     // t = 16 tau + 4g + i, column j = 16 tau' + r
     const size_t gstride = (size_t)a.H * DK;
     const bf* kg = a.k + (row0 * a.H + h) * DK;
-    const bf* qg = a.q + (row0 * a.H + h) * DK;
-    f4 kk[3], qk[3];  // tiles (0,0), (1,0), (1,1)
+    f4 kk[3];  // tiles (0,0), (1,0), (1,1)
 #pragma unroll
-    for (int i = 0; i < 3; ++i) kk[i] = qk[i] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < 3; ++i) kk[i] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int k0 = 0; k0 < DK; k0 += 32) {
         const s8 k_lo = gram_op(kg, gstride, r, valid, k0, g), k_hi = gram_op(kg, gstride, 16 + r, valid, k0, g);
-        const s8 q_lo = gram_op(qg, gstride, r, valid, k0, g), q_hi = gram_op(qg, gstride, 16 + r, valid, k0, g);
         mma(kk[0], k_lo, k_lo);
         mma(kk[1], k_hi, k_lo);
         mma(kk[2], k_hi, k_hi);
-        mma(qk[0], q_lo, k_lo);
-        mma(qk[1], q_hi, k_lo);
-        mma(qk[2], q_hi, k_hi);
     }
     __syncthreads();
     bf* mats = ar.pre + (wb * a.H + h) * (size_t)(kPreMats * kMat);
-    {   // the tile above the diagonal (t < 16 <= j) is zero
-        const u2 zq = {0u, 0u};
-        *(u2*)(mats + mT3 * kMat + (16 + r) * C + 4 * g) = zq;
-        *(u2*)(mats + mT4 * kMat + (16 + r) * C + 4 * g) = zq;
-    }
 #pragma unroll
     for (int tile = 0; tile < 3; ++tile) {
         const int ta = tile > 0, tb = tile > 1;
         const int j = 16 * tb + r;
         const float cj = cs[j], bj = bs[j];
-        const f4 ct = *(const f4*)(cs + 16 * ta + 4 * g), gq4 = *(const f4*)(gqs + 16 * ta + 4 * g);
-        f4 lq, lk;
+        const f4 ct = *(const f4*)(cs + 16 * ta + 4 * g);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int tt = 16 * ta + 4 * g + i;
-            const float d = __builtin_amdgcn_exp2f(ct[i] - cj);
-            lq[i] = j <= tt ? d * qk[tile][i] * gq4[i] : 0.f;
-            lk[i] = j < tt ? d * kk[tile][i] : 0.f;
-            Lf[tt * LS + j] = lk[i] * bj;
+            Lf[tt * LS + j] = j < tt ? __builtin_amdgcn_exp2f(ct[i] - cj) * kk[tile][i] * bj : 0.f;
         }
-        *(u2*)(mats + mT3 * kMat + j * C + 16 * ta + 4 * g) = pack4(lq);   // T3[j][t] = G^Q_t Lq[t][j]
-        *(u2*)(mats + mT4 * kMat + j * C + 16 * ta + 4 * g) = pack4(-lk);  // T4[j][t] = -Lk[t][j]
     }
     __syncthreads();
     // T' = (I + L)^-1, L = Lk diag(beta) strictly lower, by 16 x 16 blocks: T11 = (I + L11)^-1 and T22 = (I + L22)^-1
@@ -322,15 +305,6 @@ __global__ __launch_bounds__(64) void gdn_blk_pre_kernel(const GdnBlockArgs a, c
         for (int j = 0; j < C; j += 8) {
             const f4 lo = *(const f4*)(Tf + t * LS + j), hi = *(const f4*)(Tf + t * LS + j + 4);
             *(u4*)(t1 + j) = u4{pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])};
-        }
-    } else {  // T2[j][t'] = T'[t'][j] beta_t': row j
-        bf* t2 = mats + mT2 * kMat + t * C;
-#pragma unroll
-        for (int u = 0; u < C; u += 8) {
-            float y[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = Tf[(u + e) * LS + t] * bs[u + e];
-            *(u4*)(t2 + u) = u4{pack2(y[0], y[1]), pack2(y[2], y[3]), pack2(y[4], y[5]), pack2(y[6], y[7])};
         }
     }
 }
@@ -500,15 +474,16 @@ template <int DK>
 struct Stage2 {
     static constexpr int RKr = rows_stride(DK), RKc = cols_stride(DK);
     static constexpr int oK = 0, oKc = oK + C * RKr * 2, oQ = oKc + C * RKc * 2, oO = oQ + C * RKc * 2,
-                         oV = oO + C * kSlC * 2, oR = oV + C * kSlR * 2, oT = oR + kCols * kSmC * 2,
-                         oS = oT + 3 * C * kSmR * 2, bytes = oS + kScal * 4;
+                         oV = oO + C * kSlC * 2, oR = oV + C * kSlR * 2, oT = oR + kCols * kSmC * 2,  // T' (by columns)
+                         oL = oT + C * kSmC * 2,                                             // Lq, -Lk: made by the sweep
+                         oS = oL + 2 * C * kSmR * 2, bytes = oS + kScal * 4;
 };
 template <int DK, int DV>
 struct Load2 {
     Rows<C, DK * 2> k, q;
     Rows<C, kCols * 2> o, v;
     Rows<kCols, 64> rs;
-    Rows<3 * C, 64> t;
+    Rows<C, 64> t;
     Rows<kKinds, C * 4> sc;
     __device__ __forceinline__ void load(const Frame& f, int I, int lt) {
         const size_t row = f.row0(I) * f.a.H + f.s.h, bhi = f.bhi(I);
@@ -518,7 +493,7 @@ struct Load2 {
         o.load(f.a.dout + row * DV + n0, (size_t)f.a.H * DV * 2, valid, lt);
         v.load(f.a.v + row * DV + n0, (size_t)f.a.H * DV * 2, valid, lt);
         rs.load(f.ar.res + (bhi * (size_t)DV + n0) * C, C * 2, kCols, lt);
-        t.load(f.ar.pre + bhi * (size_t)(kPreMats * kMat) + mT2 * kMat, C * 2, 3 * C, lt);
+        t.load(f.ar.pre + bhi * (size_t)(kPreMats * kMat) + mT1 * kMat, C * 2, C, lt);
         sc.load(f.ar.scal + bhi * (size_t)kScal, C * 4, kKinds, lt);
     }
     __device__ __forceinline__ void put(unsigned char* st, int lt) const {
@@ -529,7 +504,7 @@ struct Load2 {
         o.put(st + L::oO, kSlC * 2, lt);
         v.put(st + L::oV, kSlR * 2, lt);
         rs.put(st + L::oR, kSmC * 2, lt);
-        t.put(st + L::oT, kSmR * 2, lt);
+        t.put(st + L::oT, kSmC * 2, lt);
         sc.put(st + L::oS, C * 4, lt);
     }
 };
@@ -547,7 +522,8 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
     const int n0 = s.slice * kCols, n = n0 + 16 * w + r;
     const int plane = (n0 >> 4) + w;
     f4 X[NT];
-    run_sweep<false, 4, Load2<DK, DV>>(
+    f4 dU[2];  // (K X1) for this wave's columns: from the first half of a step to the second
+    run_sweep<false, 4, Load2<DK, DV>, true>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -563,24 +539,19 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
             const bf* Os = (const bf*)(st + L::oO);
             const bf* Vs = (const bf*)(st + L::oV);
             const bf* Rs = (const bf*)(st + L::oR);
-            const bf* T2 = (const bf*)(st + L::oT);
-            const bf* T3 = T2 + C * kSmR;
-            const bf* T4 = T3 + C * kSmR;
+            const bf* T1 = (const bf*)(st + L::oT);
+            const bf* Lq = (const bf*)(st + L::oL);
+            const bf* Lkn = Lq + C * kSmR;
             const float* sc = (const float*)(st + L::oS);
-            f4 dU[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-            for (int t = 0; t < NT; t += 2) {
-                const s8 bX = pack8(X[t], X[t + 1]);
-                mma(dU[0], op_rows(Kr, RKr, r, 16 * t, g), bX);
-                mma(dU[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bX);
-            }
             const s8 bO = op_cols(Os, kSlC, 0, 16 * w, r, g);  // dOut[t slots][column n]
             const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
+            const f4 gq0 = sc4(sc, kGq, 4 * g), gq1 = sc4(sc, kGq, 16 + 4 * g);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 dU[ta] *= sc4(sc, kAP, 16 * ta + 4 * g);
-                mma(dU[ta], op_rows(T3, kSmR, 16 * ta + r, 0, g), bO);
+                mma(dU[ta], op_cols(Lq, kSmR, 0, 16 * ta, r, g), bO);  // Lq^T dY, G^Q folded into Lq's rows
             }
+            const f4 be0 = sc4(sc, kBeta, 4 * g), be1 = sc4(sc, kBeta, 16 + 4 * g);
             const s8 pdU = pack8(dU[0], dU[1]);
             // identity as an operand: slot (half, g, e) is token 16 half + 4g + e; column 16 tau + r
             s8 id[2];
@@ -594,7 +565,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
             s8 aT2[2];
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
-                aT2[ta] = op_rows(T2, kSmR, 16 * ta + r, 0, g);
+                aT2[ta] = scale8(op_cols(T1, kSmC, 0, 16 * ta, r, g), be0, be1);  // (T' diag(beta))^T, row 16 ta + r
                 wv[ta] = f4{0.f, 0.f, 0.f, 0.f};
                 wT[ta] = f4{0.f, 0.f, 0.f, 0.f};
                 duT[ta] = f4{0.f, 0.f, 0.f, 0.f};
@@ -613,7 +584,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
             const size_t row0 = f.row0(I);
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
-                mma(duT[ta], pw, op_rows(T4, kSmR, 16 * ta + r, 0, g));  // du = dU - Lk^T w, token 16 ta + r
+                mma(duT[ta], pw, op_cols(Lkn, kSmR, 0, 16 * ta, r, g));  // du = dU - Lk^T w, token 16 ta + r
                 const int tt = 16 * ta + r;
                 const f4 rs4 = tile_cols(Rs, kSmC, 16 * w, 16 * ta, r, g);            // res[token tt][column 16w + 4g + i]
                 const f4 v4 = unpack4(*(const s4*)(Vs + tt * kSlR + 16 * w + 4 * g));  // v[token tt][the same columns]
@@ -634,7 +605,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
                     *(u2*)(a.dv + at * DV + n0 + 16 * w + 4 * g) = pack4(wT[ta] * sc[kGk * C + tt]);
                 }
             }
-            const f4 q0 = p0 * sc4(sc, kGq, 4 * g), q1 = p1 * sc4(sc, kGq, 16 + 4 * g);
+            const f4 q0 = p0 * gq0, q1 = p1 * gq1;
             const s8 bq = scale8(bO, q0, q1), bw = scale8(pw, -p0, -p1);
             const float A = sc[kA * C];
 #pragma unroll
@@ -650,6 +621,47 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) a.ds0[((size_t)s.bh * DK + 16 * t + 4 * g + i) * DV + n] = X[t][i];
+            }
+        },
+        [&](unsigned char* st, int) {
+            // First half of a step: the block's diag(G^Q) Lq = diag(G^Q) tril(D * Q K^T) and -Lk = -strict_tril(D * K K^T) (waves 0..2 a
+            // 16 x 16 tile each, a lane four adjacent columns of one row; wave 3 the zeros above the diagonal), and K X1.
+            const bf* Kr = (const bf*)(st + L::oK);
+            const bf* Qr = (const bf*)(st + L::oQ);
+            const float* sc = (const float*)(st + L::oS);
+            bf* Lq = (bf*)(st + L::oL);
+            bf* Lkn = Lq + C * kSmR;
+            if (w == 3) {
+                *(u2*)(Lq + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
+                *(u2*)(Lkn + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
+            } else {
+                const int ta = w > 0, tb = w > 1, tt = 16 * ta + r;
+                f4 qk = {0.f, 0.f, 0.f, 0.f}, kk = {0.f, 0.f, 0.f, 0.f};  // [i]: row tt, column 16 tb + 4g + i
+#pragma unroll
+                for (int k0 = 0; k0 < DK; k0 += 32) {
+                    const s8 aK = op_rows(Kr, RKr, 16 * tb + r, k0, g);
+                    mma(qk, aK, op_rows(Qr, RKc, tt, k0, g));
+                    mma(kk, aK, op_rows(Kr, RKr, tt, k0, g));
+                }
+                const float ct = sc[kCl * C + tt], gqt = sc[kGq * C + tt];
+                const f4 cj = sc4(sc, kCl, 16 * tb + 4 * g);
+                f4 lq, lk;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int j = 16 * tb + 4 * g + i;
+                    const float d = __builtin_amdgcn_exp2f(ct - cj[i]);
+                    lq[i] = j <= tt ? d * qk[i] * gqt : 0.f;
+                    lk[i] = j < tt ? -d * kk[i] : 0.f;
+                }
+                *(u2*)(Lq + tt * kSmR + 16 * tb + 4 * g) = pack4(lq);
+                *(u2*)(Lkn + tt * kSmR + 16 * tb + 4 * g) = pack4(lk);
+            }
+            dU[0] = dU[1] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 bX = pack8(X[t], X[t + 1]);
+                mma(dU[0], op_rows(Kr, RKr, r, 16 * t, g), bX);
+                mma(dU[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bX);
             }
         });
 }

@@ -297,17 +297,17 @@ def test_backward_gdn_workspace_size(lib):
     f32 = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.F32, B=B, T=T, H=H, dk=dk, dv=dv))
     pv, pk = dv // 8, dk // 8
     assert f32 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + 2 * n * dv + n * dk)
-    # bf16 tensors (block form): a plane per 16 columns; per 32-token block and head 8 x 32 scalars, four 32 x 32
-    # bf16 matrices, two bf16 [dv][32] tiles and one bf16 [dk][32] tile
+    # bf16 tensors (block form): a plane per 16 columns; per 32-token block and head 8 x 32 scalars, one 32 x 32
+    # bf16 matrix, two bf16 [dv][32] tiles and one bf16 [dk][32] tile
     bf16 = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.BF16, B=B, T=T, H=H, dk=dk, dv=dv))
     pv, pk = dv // 16, dk // 16
     bh = B * ((T + 31) // 32) * H
-    assert bf16 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + bh * 256 + bh * 4 * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
+    assert bf16 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + bh * 256 + bh * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
     # packed batches: floor(T / 32) + B + 1 blocks whatever the sequence lengths are
     packed = sla.sla_backward_gdn_varlen_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.BF16, B=3, T=200, H=H, dk=dk, dv=dv))
     n, bh = 200 * H, (200 // 32 + 3 + 1) * H
-    assert packed == 4 * (n * (3 + 2 * pv + pk) + pk * 3 * H + bh * 256 + bh * 4 * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
+    assert packed == 4 * (n * (3 + 2 * pv + pk) + pk * 3 * H + bh * 256 + bh * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
 
 
 def test_backward_segment_schedule_workspace_and_validation(lib):
