@@ -501,9 +501,15 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_finish_kernel(const GArgs a, int 
     }
 }
 
-// dlog_decay[b,t,h] = <d_final, S_T>[b,h] + sum_{s >= t} e[b,s,h]; one workgroup per (b, h).
+// dlog_decay[b,t,h] = <d_final, S_T>[b,h] + sum_{s >= t} e[b,s,h], in spans of 2 * kEw tokens.  With anchors
+// (phi != null) the sum restarts at every span boundary from the exact value there, the sum over `planes` partials
+// of <X, S> entering that token, so the spans are independent: grid (B * H, spans).  Without, one workgroup per
+// (b, h) takes the spans from the last to the first: grid (B * H, 1).
+constexpr int kSpan = 2 * kEw;
+static_assert(kSpan == kGdnAnchor, "one span of the scan per anchor interval");
 __global__ __launch_bounds__(kEw) void gdn_bwd_decay_scan_kernel(const float* e, const float* corr, int planes, int B,
-                                                                 int Ttot, int H, const int* cu, float* dld) {
+                                                                 int Ttot, int H, const int* cu, const float* phi,
+                                                                 float* dld) {
     __shared__ float sx[kEw];
     const int bh = blockIdx.x, b = bh / H, h = bh % H, tid = threadIdx.x;
     int T = Ttot;
@@ -513,20 +519,34 @@ __global__ __launch_bounds__(kEw) void gdn_bwd_decay_scan_kernel(const float* e,
         T = end - start;
         tok0 = (size_t)start;
     }
-    const int per = (T + kEw - 1) / kEw, lo = min(tid * per, T), hi = min(lo + per, T);
     const float* src = e + tok0 * H + h;
-    float own = 0.f;
-    for (int t = lo; t < hi; ++t) own += src[(size_t)t * H];
-    sx[tid] = own;
-    __syncthreads();
-    float run = 0.f;
-    if (corr)
-        for (int p = 0; p < planes; ++p) run += corr[(size_t)p * B * H + bh];
-    for (int j = tid + 1; j < kEw; ++j) run += sx[j];
     float* dst = dld + tok0 * H + h;
-    for (int t = hi - 1; t >= lo; --t) {
-        run += src[(size_t)t * H];
-        dst[(size_t)t * H] = run;
+    float carry = 0.f;  // the value at the end of the span in hand
+    if (corr)
+        for (int p = 0; p < planes; ++p) carry += corr[(size_t)p * B * H + bh];
+    const int nspan = (T + kSpan - 1) / kSpan;
+    const int first = phi ? (int)blockIdx.y : 0, last = phi ? (int)blockIdx.y : nspan - 1;
+    if (first >= nspan) return;
+    for (int m = last; m >= first; --m) {
+        const int t0 = m * kSpan + 2 * tid;
+        const float v0 = t0 < T ? src[(size_t)t0 * H] : 0.f, v1 = t0 + 1 < T ? src[(size_t)(t0 + 1) * H] : 0.f;
+        if (phi && m < nspan - 1) {
+            const size_t aid = (tok0 + (size_t)(m + 1) * kSpan) / kGdnAnchor;
+            carry = 0.f;
+            for (int p = 0; p < planes; ++p) carry += phi[(aid * H + h) * (size_t)planes + p];
+        }
+        sx[tid] = v0 + v1;
+        __syncthreads();
+        float run = carry, total = 0.f;
+        for (int j = 0; j < kEw; ++j) {
+            const float x = sx[j];
+            total += x;
+            if (j > tid) run += x;
+        }
+        if (t0 + 1 < T) dst[(size_t)(t0 + 1) * H] = run + v1;
+        if (t0 < T) dst[(size_t)t0 * H] = run + v1 + v0;
+        carry += total;
+        __syncthreads();
     }
 }
 
@@ -591,8 +611,8 @@ int launch_dv(const GArgs& a, int dv, hipStream_t stream) {
 size_t backward_gdn_workspace_floats(const sla_params& p, bool packed) {
     const size_t rows = packed ? (size_t)p.T : (size_t)p.B * p.T, n = round4(rows * p.H);
     if (p.dtype == SLA_BF16) {  // block form: a plane per 16 columns; the sweeps' own workspace behind them
-        const size_t pv = (size_t)p.dv / 16, pk = (size_t)p.dk / 16;
-        return n * (3 + 2 * pv + pk) + round4(pk * p.B * p.H) +
+        const size_t pv = (size_t)p.dv / 16, pk = (size_t)p.dk / 16, na = gdn_anchor_count(rows);
+        return n * (3 + 2 * pv + pk) + round4(pk * p.B * p.H) + round4(na * p.H * pk) + na * p.H * p.dk * p.dv +
                gdn_block_workspace_floats(p.B, p.T, p.H, p.dk, p.dv, packed);
     }
     const size_t pv = (size_t)p.dv / (4 * CW), pk = (size_t)p.dk / (4 * CW);  // planes per compute wave and slice
@@ -629,6 +649,13 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
     a.part_k = w; w += n * pv;
     a.part_b = w; w += n * pv;
     a.corr = w; w += round4((size_t)pk * p.B * p.H);
+    float* anchor_phi = nullptr;
+    float* anchor_x = nullptr;
+    if (block_form) {  // the exact decay gradient every 512 tokens
+        const size_t na = gdn_anchor_count(rows);
+        anchor_phi = w; w += round4(na * p.H * pk);
+        anchor_x = w; w += na * p.H * p.dk * p.dv;
+    }
     a.res = w; w += round4(rows * p.H * p.dv);
     a.w = w; w += round4(rows * p.H * p.dv);
     a.dk1 = w;
@@ -645,6 +672,7 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
         g.ld = ld; g.beta = beta; g.gq = gq; g.gk = gk; g.s0 = s0; g.dsf = dsf;
         g.dq = (uint16_t*)dq; g.dk = (uint16_t*)dk; g.dv = (uint16_t*)dv; g.ds0 = ds0;
         g.part_q = a.part_q; g.part_k = a.part_k; g.part_b = a.part_b; g.corr = a.corr;
+        g.anchor_x = anchor_x; g.anchor_phi = anchor_phi;
         g.plane = n;
         g.block_ws = a.res;  // everything behind the planes
         g.rows = rows; g.cu = cu;
@@ -657,8 +685,9 @@ int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const
     const unsigned per = kEw / (unsigned)p.H, eg = (unsigned)((rows + per - 1) / per);
     hipLaunchKernelGGL(gdn_bwd_finish_kernel, dim3(eg), dim3(kEw), 0, stream, a, pk, pv, dql, kl ? dkl : nullptr,
                        dbeta, e);
-    hipLaunchKernelGGL(gdn_bwd_decay_scan_kernel, dim3((unsigned)(p.B * p.H)), dim3(kEw), 0, stream, (const float*)e,
-                       dsf ? (const float*)a.corr : nullptr, pk, p.B, p.T, p.H, cu, dld);
+    const unsigned spans = anchor_phi ? (unsigned)((p.T + kSpan - 1) / kSpan) : 1u;
+    hipLaunchKernelGGL(gdn_bwd_decay_scan_kernel, dim3((unsigned)(p.B * p.H), spans), dim3(kEw), 0, stream, (const float*)e,
+                       dsf ? (const float*)a.corr : nullptr, pk, p.B, p.T, p.H, cu, (const float*)anchor_phi, dld);
     return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP;
 }
 

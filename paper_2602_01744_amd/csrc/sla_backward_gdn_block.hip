@@ -108,6 +108,8 @@ __device__ __forceinline__ void seq_of(const GdnBlockArgs& a, int b, Seq& s) {
     }
     s.nblk = (s.T + C - 1) / C;
 }
+constexpr int kAnchorBlocks = kGdnAnchor / C;
+__device__ __forceinline__ size_t anchor_id(const Seq& s, int I) { return (s.tok0 + (size_t)C * I) / kGdnAnchor; }
 // blockIdx.x % 8 is the XCD a workgroup lands on; the slices of a (sequence, head) pair go to one XCD, whose L2 then
 // fetches what they share once.  The grid is 8 * nslices * ceil(pairs / 8); the padding has nothing to do.
 __device__ __forceinline__ Seq where(const GdnBlockArgs& a, int nslices) {
@@ -605,15 +607,9 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
                     *(u2*)(a.dv + at * DV + n0 + 16 * w + 4 * g) = pack4(wT[ta] * sc[kGk * C + tt]);
                 }
             }
-            const f4 q0 = p0 * gq0, q1 = p1 * gq1;
-            const s8 bq = scale8(bO, q0, q1), bw = scale8(pw, -p0, -p1);
-            const float A = sc[kA * C];
+            const s8 bw = scale8(pw, -p0, -p1);  // X0 = (A X1 + Q^T diag(p) dY: first half) - K^T diag(p) w
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                X[t] *= A;
-                mma(X[t], op_cols(Qr, RKc, 0, 16 * t, r, g), bq);
-                mma(X[t], op_cols(Kc, RKc, 0, 16 * t, r, g), bw);
-            }
+            for (int t = 0; t < NT; ++t) mma(X[t], op_cols(Kc, RKc, 0, 16 * t, r, g), bw);
         },
         [&]() {
             if (a.ds0) {
@@ -662,6 +658,16 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
                 const s8 bX = pack8(X[t], X[t + 1]);
                 mma(dU[0], op_rows(Kr, RKr, r, 16 * t, g), bX);
                 mma(dU[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bX);
+            }
+            // the part of X's step that does not need w
+            const bf* Os = (const bf*)(st + L::oO);
+            const s8 bq = scale8(op_cols(Os, kSlC, 0, 16 * w, r, g), sc4(sc, kP, 4 * g) * sc4(sc, kGq, 4 * g),
+                                 sc4(sc, kP, 16 + 4 * g) * sc4(sc, kGq, 16 + 4 * g));
+            const float A = sc[kA * C];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                X[t] *= A;
+                mma(X[t], op_cols(Qr, RKc, 0, 16 * t, r, g), bq);
             }
         });
 }
@@ -786,7 +792,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
             }
         },
         [&]() {},
-        [&](unsigned char* st, int) {
+        [&](unsigned char* st, int I) {
             const bf* Rf = (const bf*)(st + L::oR);
             const bf* Wf = (const bf*)(st + L::oW);
             const bf* Of = (const bf*)(st + L::oO);
@@ -813,6 +819,11 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
                 Xt[t] *= A;
                 mma(Xt[t], op_cols(Of, RD, 0, 16 * t, r, g), bq);
                 mma(Xt[t], op_rows(Wf, kSmR, 16 * t + r, 0, g), bk);
+            }
+            if (I > 0 && (I & (kAnchorBlocks - 1)) == 0) {  // X entering token C * I: kept for the decay gradient
+                float* dst = a.anchor_x + ((anchor_id(s, I) * a.H + s.h) * DK + d) * (size_t)DV + 4 * g;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) *(f4*)(dst + 16 * t) = Xt[t];
             }
         });
 }
@@ -880,12 +891,21 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
                 if (lane == 0) a.corr[(size_t)plane * a.B * a.H + s.bh] = acc;
             }
         },
-        [&](unsigned char* st, int) {
+        [&](unsigned char* st, int I) {
             const bf* Rf = (const bf*)(st + L::oR);
             const bf* Wf = (const bf*)(st + L::oW);
             const bf* Of = (const bf*)(st + L::oO);
             const bf* Ks = (const bf*)(st + L::oK);
             const float* sc = (const float*)(st + L::oS);
+            // <X, S> at an anchor, the end of this block (this wave's 16 key columns): X is requested here and used
+            // once S has moved on to the end of the block
+            const bool anchored = I + 1 < s.nblk && ((I + 1) & (kAnchorBlocks - 1)) == 0;
+            f4 xa[NT];
+            if (anchored) {
+                const float* src = a.anchor_x + ((anchor_id(s, I + 1) * a.H + s.h) * DK + d) * (size_t)DV + 4 * g;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) xa[t] = *(const f4*)(src + 16 * t);
+            }
             local_matrices<DV, false>(Rf, L::SR, nullptr, 0, Of, RD, sc, nullptr, (bf*)(st + L::oM), w, r, g);
             dqT[0] = dqT[1] = dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -904,6 +924,15 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
             for (int t = 0; t < NT; ++t) {
                 St[t] *= A;
                 mma(St[t], op_rows(Rf, kSmR, 16 * t + r, 0, g), bk);
+            }
+            if (anchored) {
+                float acc = 0.f;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc += xa[t][i] * St[t][i];
+                acc = all_groups(row_all(acc));
+                if (lane == 0) a.anchor_phi[(anchor_id(s, I + 1) * a.H + s.h) * (size_t)(DK / 16) + plane] = acc;
             }
         });
 }

@@ -28,6 +28,8 @@ struct GdnBlockArgs {
     float* part_k;          // [dv/16][plane]: partial w . v
     float* part_b;          // [dv/16][plane]: partial du . res
     float* corr;            // [dk/16][B*H]: partial <d_final, S_T>
+    float* anchor_x;        // [rows/512 + 1][H][dk][dv]: the state cotangent entering every 512th token of a sequence
+    float* anchor_phi;      // [rows/512 + 1][H][dk/16]: partial <that cotangent, the state there>
     size_t plane;           // floats between partial planes (>= rows * H)
     float* block_ws;        // gdn_block_workspace_floats() floats, 16-byte aligned
     size_t rows;            // tokens in all: B * T, or the packed total T
@@ -35,9 +37,15 @@ struct GdnBlockArgs {
     int B, T, H, dim_k, dim_v;
 };
 
+// The decay gradient is a suffix sum of per-token scalars built from bf16-operand products, whose rounding adds up
+// like a random walk over the tokens behind; every kGdnAnchor tokens of a sequence it is re-derived exactly as
+// <X, S> at that boundary (sweep 3 leaves X there, sweep 4 forms the product).  Anchors are numbered by absolute
+// token position / kGdnAnchor: sequences do not overlap, so neither do their anchors (fewer than rows / 512 + 1).
+constexpr int kGdnAnchor = 512;
+inline size_t gdn_anchor_count(size_t rows) { return rows / kGdnAnchor + 1; }
 // Floats of block_ws for this shape.
 size_t gdn_block_workspace_floats(int B, int T, int H, int dk, int dv, bool packed);
-// Runs the block-local pre-pass, the four state sweeps and the block-local pass between them on `stream`.
+// Runs the block-local pre-pass and the four state sweeps on `stream`.
 int launch_gdn_block_sweeps(const GdnBlockArgs& a, hipStream_t stream);
 
 }  // namespace sla

@@ -302,12 +302,15 @@ def test_backward_gdn_workspace_size(lib):
     bf16 = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.BF16, B=B, T=T, H=H, dk=dk, dv=dv))
     pv, pk = dv // 16, dk // 16
     bh = B * ((T + 31) // 32) * H
-    assert bf16 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + bh * 256 + bh * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
+    na = B * T // 512 + 1  # anchors of the decay gradient: partial <X, S> [na][H][dk/16] and X [na][H][dk][dv]
+    assert bf16 == 4 * (n * (3 + 2 * pv + pk) + pk * B * H + na * H * pk + na * H * dk * dv +
+                        bh * 256 + bh * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
     assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GLA)) == 0
     # packed batches: floor(T / 32) + B + 1 blocks whatever the sequence lengths are
     packed = sla.sla_backward_gdn_varlen_workspace_bytes(_ok_params(variant=sla.GDN, dtype=sla.BF16, B=3, T=200, H=H, dk=dk, dv=dv))
     n, bh = 200 * H, (200 // 32 + 3 + 1) * H
-    assert packed == 4 * (n * (3 + 2 * pv + pk) + pk * 3 * H + bh * 256 + bh * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
+    assert packed == 4 * (n * (3 + 2 * pv + pk) + pk * 3 * H + H * pk + H * dk * dv +
+                          bh * 256 + bh * 1024 // 2 + 2 * (bh * dv * 32 // 2) + bh * dk * 32 // 2)
 
 
 def test_backward_segment_schedule_workspace_and_validation(lib):

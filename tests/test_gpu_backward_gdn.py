@@ -135,9 +135,16 @@ def test_fp32_tensors(dk, dv, T):
     check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"fp32 dk={dk} dv={dv} T={T}", dtype="f32")
 
 
-def test_long_sequence():
-    d, cot, s0 = make(1, 4096 + 24, 2, 128, 128, seed=1170, states=True)
-    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label="T=4120")
+@pytest.mark.parametrize("T", [4096 + 24, 8192 + 40])
+def test_long_sequence(T):
+    """dlog_decay is a suffix sum of per-token scalars made of bf16-operand products; the block form re-derives it
+    exactly (as <X, S>) every 512 tokens, so its error does not grow with the length: held to half the bar here, on
+    the earliest tokens (the longest sums) too."""
+    d, cot, s0 = make(1, T, 2, 128, 128, seed=1170, states=True)
+    got, ref = check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"T={T}")
+    scale = np.abs(ref["dlog_decay"]).max()
+    assert np.abs(got["dlog_decay"] - ref["dlog_decay"]).max() / scale <= 0.5 * TOL["bf16"]
+    assert np.abs(got["dlog_decay"][:, :512] - ref["dlog_decay"][:, :512]).max() / scale <= 0.5 * TOL["bf16"]
 
 
 def test_full_size():
