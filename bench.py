@@ -210,7 +210,7 @@ def bench_backward(args, w, sla, si, torch, np) -> int:
                         + (", wide tensors laid out [B,H,T,d]" if hm else "")
                         + (f", {nseg} segments per batch row" if nseg > 1 else ""),
             "kernel": ("sla_backward_gdn (block form): sla_bwd_gates_kernel, gdn_blk_pre_kernel, gdn_blk_state_kernel, "
-                       "gdn_blk_cotangent_kernel, gdn_blk_mid_kernel, gdn_blk_key_kernel, gdn_blk_query_kernel, "
+                       "gdn_blk_cotangent_kernel, gdn_blk_key_kernel, gdn_blk_query_kernel, "
                        "gdn_bwd_finish_kernel, gdn_bwd_decay_scan_kernel") if gdn else
                       "sla_backward: sla_bwd_gates_kernel, sla_bwd_dq_kernel, sla_bwd_dv_kernel, sla_bwd_dk_kernel, "
                       "sla_bwd_logits_kernel x2"
