@@ -323,17 +323,33 @@ struct Frame {
     __device__ __forceinline__ size_t bhi(int I) const { return (s.blk0 + (size_t)I) * a.H + s.h; }
 };
 
+// The 16 x 16 tile of a block-local 32 x 32 matrix that wave w of four makes: (0,0), (1,0), (1,1), (0,1).
+__device__ __forceinline__ void tile_of_wave(int w, int& ta, int& tb) {
+    ta = ((w + 1) >> 1) & 1;
+    tb = w >> 1;
+}
+
 // LOADER: struct with load(frame, I, lt) and put(stage, lt); BODY: callable (stage, I).  The loaders keep PF blocks in
 // flight in registers (block b in set b % PF): a block's rows are requested PF + 1 steps before the compute waves
 // need them, which covers the latency of HBM under load (with one block in flight a step lasted as long as a load).
-// TWO: a step has two halves with a barrier between them: FIRST (stage, I) lets the compute waves write something
-// into the stage (matrices of the block) that all of them read in BODY.
+// How the block-local matrices that a sweep forms itself get into the stage:
+//   kPlain  none; two stages, one barrier per step;
+//   kHalves two stages; a step has two halves with a barrier between them: FIRST (stage, I) lets the compute waves
+//           write the matrices (and do what needs only the carried state), BODY reads them;
+//   kAhead  three stages: the loader waves, otherwise idle between their copies, make the matrices of block
+//           step + 1 with MATS (stage, loader wave, lane) from the rows they staged a step earlier, while the
+//           compute waves work on block step and the copies of block step + 2 land; one barrier per step.
+enum { kPlain = 0, kHalves = 1, kAhead = 2 };
 struct NoFirst {
     __device__ __forceinline__ void operator()(unsigned char*, int) const {}
 };
-template <bool FWD, int PF, class LOADER, bool TWO = false, class BODY, class INIT, class FINI, class FIRST = NoFirst>
+struct NoMats {
+    __device__ __forceinline__ void operator()(unsigned char*, int, int) const {}
+};
+template <bool FWD, int PF, class LOADER, int MODE = kPlain, class BODY, class INIT, class FINI, class FIRST = NoFirst,
+          class MATS = NoMats>
 __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, int stage_bytes, INIT&& init, BODY&& body,
-                                          FINI&& fini, FIRST&& first = NoFirst()) {
+                                          FINI&& fini, FIRST&& first = NoFirst(), MATS&& mats = NoMats()) {
     const int tid = threadIdx.x, nblk = f.s.nblk;
     // Both sides run the same number of steps, a multiple of PF, so that the loaders' loop body has no branch in it
     // (the compiler then lets the loads of the other register sets stay outstanding across a put); steps past the
@@ -343,6 +359,8 @@ __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, i
         const int sclamp = min(step, nblk - 1);
         return FWD ? sclamp : nblk - 1 - sclamp;
     };
+    constexpr int NS = MODE == kAhead ? 3 : 2;
+    auto stage = [&](int step) { return smem + (step % NS) * stage_bytes; };
     if (tid >= kThreads - kLoaders) {
         if (nblk == 0) return;
         const int lt = tid - (kThreads - kLoaders);
@@ -352,27 +370,48 @@ __device__ __forceinline__ void run_sweep(const Frame& f, unsigned char* smem, i
         R[0].put(smem, lt);
         R[0].load(f, blk(PF), lt);
         __syncthreads();
-        for (int base = 0; base < nsteps; base += PF) {
+        if constexpr (MODE == kAhead) {
+            static_assert(PF >= 2, "two blocks are staged before the first step");
+            const int lw = __builtin_amdgcn_readfirstlane(lt >> 6), lane = lt & 63;
+            R[1].put(stage(1), lt);
+            R[1].load(f, blk(PF + 1), lt);
+            mats(stage(0), lw, lane);
+            __syncthreads();
+            for (int base = 0; base < nsteps; base += PF) {
 #pragma unroll
-            for (int u = 0; u < PF; ++u) {
-                const int step = base + u;
-                LOADER& set = R[(u + 1) % PF];  // holds block step + 1 (base is a multiple of PF)
-                set.put(smem + ((step + 1) & 1) * stage_bytes, lt);
-                set.load(f, blk(step + 1 + PF), lt);
-                if constexpr (TWO) __syncthreads();
-                __syncthreads();
+                for (int u = 0; u < PF; ++u) {
+                    const int step = base + u;
+                    LOADER& set = R[(u + 2) % PF];  // holds block step + 2 (base is a multiple of PF)
+                    set.put(stage(step + 2), lt);
+                    set.load(f, blk(step + 2 + PF), lt);
+                    mats(stage(step + 1), lw, lane);
+                    __syncthreads();
+                }
+            }
+        } else {
+            for (int base = 0; base < nsteps; base += PF) {
+#pragma unroll
+                for (int u = 0; u < PF; ++u) {
+                    const int step = base + u;
+                    LOADER& set = R[(u + 1) % PF];  // holds block step + 1 (base is a multiple of PF)
+                    set.put(stage(step + 1), lt);
+                    set.load(f, blk(step + 1 + PF), lt);
+                    if constexpr (MODE == kHalves) __syncthreads();
+                    __syncthreads();
+                }
             }
         }
     } else {
         init();
         if (nblk > 0) {
             __syncthreads();
+            if constexpr (MODE == kAhead) __syncthreads();
             for (int step = 0; step < nsteps; ++step) {
-                if constexpr (TWO) {
-                    if (step < nblk) first(smem + (step & 1) * stage_bytes, blk(step));
+                if constexpr (MODE == kHalves) {
+                    if (step < nblk) first(stage(step), blk(step));
                     __syncthreads();
                 }
-                if (step < nblk) body(smem + (step & 1) * stage_bytes, blk(step));
+                if (step < nblk) body(stage(step), blk(step));
                 __syncthreads();
             }
         }
@@ -511,6 +550,40 @@ struct Load2 {
     }
 };
 
+// Sweep 2's block-local matrices, diag(G^Q) Lq = diag(G^Q) tril(D * Q K^T) and -Lk = -strict_tril(D * K K^T), from
+// the staged rows of q and k; one 16 x 16 tile per wave as in local_matrices().
+template <int DK>
+__device__ __forceinline__ void gram_matrices(unsigned char* st, int w, int r, int g) {
+    typedef Stage2<DK> L;
+    const bf* Kr = (const bf*)(st + L::oK);
+    const bf* Qr = (const bf*)(st + L::oQ);
+    const float* sc = (const float*)(st + L::oS);
+    bf* Lq = (bf*)(st + L::oL);
+    bf* Lkn = Lq + C * kSmR;
+    int ta, tb;
+    tile_of_wave(w, ta, tb);
+    const int tt = 16 * ta + r;
+    f4 qk = {0.f, 0.f, 0.f, 0.f}, kk = {0.f, 0.f, 0.f, 0.f};  // [i]: row tt, column 16 tb + 4g + i
+#pragma unroll
+    for (int k0 = 0; k0 < DK; k0 += 32) {
+        const s8 aK = op_rows(Kr, L::RKr, 16 * tb + r, k0, g);
+        mma(qk, aK, op_rows(Qr, L::RKc, tt, k0, g));
+        mma(kk, aK, op_rows(Kr, L::RKr, tt, k0, g));
+    }
+    const float ct = sc[kCl * C + tt], gqt = sc[kGq * C + tt];
+    const f4 cj = sc4(sc, kCl, 16 * tb + 4 * g);
+    f4 lq, lk;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = 16 * tb + 4 * g + i;
+        const float d = __builtin_amdgcn_exp2f(ct - cj[i]);
+        lq[i] = j <= tt ? d * qk[i] * gqt : 0.f;
+        lk[i] = j < tt ? -d * kk[i] : 0.f;
+    }
+    *(u2*)(Lq + tt * kSmR + 16 * tb + 4 * g) = pack4(lq);
+    *(u2*)(Lkn + tt * kSmR + 16 * tb + 4 * g) = pack4(lk);
+}
+
 template <int DK, int DV>
 __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBlockArgs a, const Areas ar) {
     typedef Stage2<DK> L;
@@ -524,8 +597,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
     const int n0 = s.slice * kCols, n = n0 + 16 * w + r;
     const int plane = (n0 >> 4) + w;
     f4 X[NT];
-    f4 dU[2];  // (K X1) for this wave's columns: from the first half of a step to the second
-    run_sweep<false, 4, Load2<DK, DV>, true>(
+    run_sweep<false, 4, Load2<DK, DV>, kAhead>(
         f, smem, L::bytes,
         [&]() {
 #pragma unroll
@@ -548,6 +620,22 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
             const s8 bO = op_cols(Os, kSlC, 0, 16 * w, r, g);  // dOut[t slots][column n]
             const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
             const f4 gq0 = sc4(sc, kGq, 4 * g), gq1 = sc4(sc, kGq, 16 + 4 * g);
+            f4 dU[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};  // K X1, this wave's columns
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const s8 bX = pack8(X[t], X[t + 1]);
+                mma(dU[0], op_rows(Kr, RKr, r, 16 * t, g), bX);
+                mma(dU[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bX);
+            }
+            {   // the part of X's step that does not need w: A X1 + Q^T diag(p) dY
+                const s8 bq = scale8(bO, p0 * gq0, p1 * gq1);
+                const float A = sc[kA * C];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    X[t] *= A;
+                    mma(X[t], op_cols(Qr, RKc, 0, 16 * t, r, g), bq);
+                }
+            }
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta) {
                 dU[ta] *= sc4(sc, kAP, 16 * ta + 4 * g);
@@ -607,7 +695,7 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
                     *(u2*)(a.dv + at * DV + n0 + 16 * w + 4 * g) = pack4(wT[ta] * sc[kGk * C + tt]);
                 }
             }
-            const s8 bw = scale8(pw, -p0, -p1);  // X0 = (A X1 + Q^T diag(p) dY: first half) - K^T diag(p) w
+            const s8 bw = scale8(pw, -p0, -p1);  // X0 = (A X1 + Q^T diag(p) dY: above) - K^T diag(p) w
 #pragma unroll
             for (int t = 0; t < NT; ++t) mma(X[t], op_cols(Kc, RKc, 0, 16 * t, r, g), bw);
         },
@@ -619,73 +707,27 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_cotangent_kernel(const GdnBl
                     for (int i = 0; i < 4; ++i) a.ds0[((size_t)s.bh * DK + 16 * t + 4 * g + i) * DV + n] = X[t][i];
             }
         },
-        [&](unsigned char* st, int) {
-            // First half of a step: the block's diag(G^Q) Lq = diag(G^Q) tril(D * Q K^T) and -Lk = -strict_tril(D * K K^T) (waves 0..2 a
-            // 16 x 16 tile each, a lane four adjacent columns of one row; wave 3 the zeros above the diagonal), and K X1.
-            const bf* Kr = (const bf*)(st + L::oK);
-            const bf* Qr = (const bf*)(st + L::oQ);
-            const float* sc = (const float*)(st + L::oS);
-            bf* Lq = (bf*)(st + L::oL);
-            bf* Lkn = Lq + C * kSmR;
-            if (w == 3) {
-                *(u2*)(Lq + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
-                *(u2*)(Lkn + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
-            } else {
-                const int ta = w > 0, tb = w > 1, tt = 16 * ta + r;
-                f4 qk = {0.f, 0.f, 0.f, 0.f}, kk = {0.f, 0.f, 0.f, 0.f};  // [i]: row tt, column 16 tb + 4g + i
-#pragma unroll
-                for (int k0 = 0; k0 < DK; k0 += 32) {
-                    const s8 aK = op_rows(Kr, RKr, 16 * tb + r, k0, g);
-                    mma(qk, aK, op_rows(Qr, RKc, tt, k0, g));
-                    mma(kk, aK, op_rows(Kr, RKr, tt, k0, g));
-                }
-                const float ct = sc[kCl * C + tt], gqt = sc[kGq * C + tt];
-                const f4 cj = sc4(sc, kCl, 16 * tb + 4 * g);
-                f4 lq, lk;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int j = 16 * tb + 4 * g + i;
-                    const float d = __builtin_amdgcn_exp2f(ct - cj[i]);
-                    lq[i] = j <= tt ? d * qk[i] * gqt : 0.f;
-                    lk[i] = j < tt ? -d * kk[i] : 0.f;
-                }
-                *(u2*)(Lq + tt * kSmR + 16 * tb + 4 * g) = pack4(lq);
-                *(u2*)(Lkn + tt * kSmR + 16 * tb + 4 * g) = pack4(lk);
-            }
-            dU[0] = dU[1] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < NT; t += 2) {
-                const s8 bX = pack8(X[t], X[t + 1]);
-                mma(dU[0], op_rows(Kr, RKr, r, 16 * t, g), bX);
-                mma(dU[1], op_rows(Kr, RKr, 16 + r, 16 * t, g), bX);
-            }
-            // the part of X's step that does not need w
-            const bf* Os = (const bf*)(st + L::oO);
-            const s8 bq = scale8(op_cols(Os, kSlC, 0, 16 * w, r, g), sc4(sc, kP, 4 * g) * sc4(sc, kGq, 4 * g),
-                                 sc4(sc, kP, 16 + 4 * g) * sc4(sc, kGq, 16 + 4 * g));
-            const float A = sc[kA * C];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                X[t] *= A;
-                mma(X[t], op_cols(Qr, RKc, 0, 16 * t, r, g), bq);
-            }
-        });
+        NoFirst(), [&](unsigned char* st, int lw, int ll) { gram_matrices<DK>(st, lw, ll & 15, ll >> 4); });
 }
 
 // ---- sweeps 3 and 4: X^T / S^T [dv, 16 key columns per wave] ---------------------------------------------------
 // The block-local matrices of these sweeps, M = strict_tril(-D * w U^T) (sweep 3 only) and N' = tril(D * dOut U^T),
-// made by the compute waves themselves from the rows the stage already holds (res and w as [dv][C], d_out as
-// [C][dv]): wave 0, 1, 2 the 16 x 16 tile (0,0), (1,0), (1,1), transposed so that a lane ends with four adjacent
-// columns of one row, wave 3 the zeros of tile (0,1).  Written as bf16 [C][kSmR]; read after a barrier.
-template <int DV, bool WITH_M>
+// made from the rows the stage already holds (res and w as [dv][C], d_out as [C][dv]) by four waves (the compute waves
+// in the first half of a step, or the loader waves a step ahead): wave 0, 1, 2, 3 the 16 x 16 tile (0,0), (1,0),
+// (1,1), (0,1), transposed so that a lane ends with four adjacent columns of one row; the triangular mask makes tile
+// (0,1) zero, so the four waves run the same code.  Written as bf16 [C][kSmR].
+// BRANCH: wave 3 only writes its zeros (for the compute waves; the loader waves' loop must stay free of branches).
+template <int DV, bool WITH_M, bool BRANCH = false>
 __device__ __forceinline__ void local_matrices(const bf* Rf, int SR, const bf* Wf, int SW, const bf* Of, int RD,
                                                const float* sc, bf* Mm, bf* Np, int w, int r, int g) {
-    if (w == 3) {
+    if (BRANCH && w == 3) {
         if (WITH_M) *(u2*)(Mm + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
         *(u2*)(Np + r * kSmR + 16 + 4 * g) = u2{0u, 0u};
         return;
     }
-    const int ta = w > 0, tb = w > 1, tt = 16 * ta + r;
+    int ta, tb;
+    tile_of_wave(w, ta, tb);
+    const int tt = 16 * ta + r;
     f4 wu = {0.f, 0.f, 0.f, 0.f}, ou = {0.f, 0.f, 0.f, 0.f};  // [i]: row tt, column 16 tb + 4g + i
 #pragma unroll
     for (int n0 = 0; n0 < DV; n0 += 32) {
@@ -707,7 +749,6 @@ __device__ __forceinline__ void local_matrices(const bf* Rf, int SR, const bf* W
     *(u2*)(Np + tt * kSmR + 16 * tb + 4 * g) = pack4(np);
 }
 
-// FWD = false: sweep 3 reads res and d_out by columns and w by rows; FWD = true: sweep 4, the other way round.
 template <int DV, bool FWD>
 struct Stage3 {
     static constexpr int RD = FWD ? rows_stride(DV) : cols_stride(DV);   // d_out rows
@@ -762,70 +803,88 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_key_kernel(const GdnBlockArg
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;  // this lane's key column
     f4 Xt[NT];  // Xt[t][i] = X[d][16 t + 4g + i]
     f4 dkT[2];  // dk2^T[key column 4g + i][token 16 tau + r]: from the first half of a step to the second
-    // First half of a step: the block's M and N' (waves 0..2 a tile each), and everything that needs only the staged
-    // rows and X: the X-part of dk and the step of X itself.  Second half, after the barrier: the local terms.
-    run_sweep<false, (DV > 128 ? 2 : 4), Load3<DK, DV, false>, true>(
-        f, smem, L::bytes,
-        [&]() {
+    auto init = [&]() {
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                Xt[t] = a.dsf ? *(const f4*)(a.dsf + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g)
-                              : f4{0.f, 0.f, 0.f, 0.f};
-        },
-        [&](const unsigned char* st, int I) {
-            const bf* Qs = (const bf*)(st + L::oQ);
-            const bf* Ks = (const bf*)(st + L::oK);
-            const bf* Mm = (const bf*)(st + L::oM);
-            const bf* Np = Mm + C * kSmR;
-            const float* sc = (const float*)(st + L::oS);
-            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
-            const s8 aQg = scale8(aQ, sc4(sc, kGq, 4 * g), sc4(sc, kGq, 16 + 4 * g));  // N = diag(G^Q) N'
-            bf* dk2 = ar.dk2 + f.bhi(I) * (size_t)(DK * C);
+        for (int t = 0; t < NT; ++t)
+            Xt[t] = a.dsf ? *(const f4*)(a.dsf + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g)
+                          : f4{0.f, 0.f, 0.f, 0.f};
+    };
+    // what needs only the staged rows and the carried state
+    auto state = [&](unsigned char* st, int I) {
+        const bf* Rf = (const bf*)(st + L::oR);
+        const bf* Wf = (const bf*)(st + L::oW);
+        const bf* Of = (const bf*)(st + L::oO);
+        const bf* Qs = (const bf*)(st + L::oQ);
+        const bf* Ks = (const bf*)(st + L::oK);
+        const float* sc = (const float*)(st + L::oS);
+        // (A/p beta)_t sum_n X[d][n] res[t][n], scaled in the second half
+        dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ta = 0; ta < 2; ++ta) {
-                const int tt = 16 * ta + r;
-                dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
-                mma(dkT[ta], aK, op_rows(Mm, kSmR, tt, 0, g));            // M K
-                mma(dkT[ta], aK, op_cols(Mm, kSmR, 0, 16 * ta, r, g));   // M^T K
-                mma(dkT[ta], aQg, op_cols(Np, kSmR, 0, 16 * ta, r, g));  // N^T Q
-                *(u2*)(dk2 + ((size_t)(((d0 + 16 * w) >> 2) + g) * C + tt) * 4) = pack4(dkT[ta]);  // rows >= valid: never read
-            }
-        },
-        [&]() {},
-        [&](unsigned char* st, int I) {
-            const bf* Rf = (const bf*)(st + L::oR);
-            const bf* Wf = (const bf*)(st + L::oW);
-            const bf* Of = (const bf*)(st + L::oO);
-            const bf* Qs = (const bf*)(st + L::oQ);
-            const bf* Ks = (const bf*)(st + L::oK);
-            const float* sc = (const float*)(st + L::oS);
-            bf* Mm = (bf*)(st + L::oM);
-            local_matrices<DV, true>(Rf, L::SR, Wf, L::SW, Of, RD, sc, Mm, Mm + C * kSmR, w, r, g);
-            // (A/p beta)_t sum_n X[d][n] res[t][n], scaled in the second half
-            dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NT; t += 2) {
+            const s8 aX = pack8(Xt[t], Xt[t + 1]);
+            mma(dkT[0], aX, op_cols(Rf, kSmC, 16 * t, 0, r, g));
+            mma(dkT[1], aX, op_cols(Rf, kSmC, 16 * t, 16, r, g));
+        }
+        const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
+        const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
+        const s8 bq = scale8(aQ, p0 * sc4(sc, kGq, 4 * g), p1 * sc4(sc, kGq, 16 + 4 * g));
+        const s8 bk = scale8(aK, -p0, -p1);
+        const float A = sc[kA * C];
 #pragma unroll
-            for (int t = 0; t < NT; t += 2) {
-                const s8 aX = pack8(Xt[t], Xt[t + 1]);
-                mma(dkT[0], aX, op_cols(Rf, kSmC, 16 * t, 0, r, g));
-                mma(dkT[1], aX, op_cols(Rf, kSmC, 16 * t, 16, r, g));
-            }
-            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
-            const f4 p0 = sc4(sc, kP, 4 * g), p1 = sc4(sc, kP, 16 + 4 * g);
-            const s8 bq = scale8(aQ, p0 * sc4(sc, kGq, 4 * g), p1 * sc4(sc, kGq, 16 + 4 * g));
-            const s8 bk = scale8(aK, -p0, -p1);
-            const float A = sc[kA * C];
+        for (int t = 0; t < NT; ++t) {
+            Xt[t] *= A;
+            mma(Xt[t], op_cols(Of, RD, 0, 16 * t, r, g), bq);
+            mma(Xt[t], op_rows(Wf, kSmR, 16 * t + r, 0, g), bk);
+        }
+        if (I > 0 && (I & (kAnchorBlocks - 1)) == 0) {  // X entering token C * I: kept for the decay gradient
+            float* dst = a.anchor_x + ((anchor_id(s, I) * a.H + s.h) * DK + d) * (size_t)DV + 4 * g;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                Xt[t] *= A;
-                mma(Xt[t], op_cols(Of, RD, 0, 16 * t, r, g), bq);
-                mma(Xt[t], op_rows(Wf, kSmR, 16 * t + r, 0, g), bk);
-            }
-            if (I > 0 && (I & (kAnchorBlocks - 1)) == 0) {  // X entering token C * I: kept for the decay gradient
-                float* dst = a.anchor_x + ((anchor_id(s, I) * a.H + s.h) * DK + d) * (size_t)DV + 4 * g;
+            for (int t = 0; t < NT; ++t) *(f4*)(dst + 16 * t) = Xt[t];
+        }
+    };
+    // the local terms, which read the block's matrices
+    auto local = [&](const unsigned char* st, int I) {
+        const bf* Qs = (const bf*)(st + L::oQ);
+        const bf* Ks = (const bf*)(st + L::oK);
+        const bf* Mm = (const bf*)(st + L::oM);
+        const bf* Np = Mm + C * kSmR;
+        const float* sc = (const float*)(st + L::oS);
+        const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g), aQ = op_cols(Qs, kSlC, 0, 16 * w, r, g);
+        const s8 aQg = scale8(aQ, sc4(sc, kGq, 4 * g), sc4(sc, kGq, 16 + 4 * g));  // N = diag(G^Q) N'
+        bf* dk2 = ar.dk2 + f.bhi(I) * (size_t)(DK * C);
 #pragma unroll
-                for (int t = 0; t < NT; ++t) *(f4*)(dst + 16 * t) = Xt[t];
-            }
-        });
+        for (int ta = 0; ta < 2; ++ta) {
+            const int tt = 16 * ta + r;
+            dkT[ta] *= sc[kAP * C + tt] * sc[kBeta * C + tt];
+            mma(dkT[ta], aK, op_rows(Mm, kSmR, tt, 0, g));            // M K
+            mma(dkT[ta], aK, op_cols(Mm, kSmR, 0, 16 * ta, r, g));   // M^T K
+            mma(dkT[ta], aQg, op_cols(Np, kSmR, 0, 16 * ta, r, g));  // N^T Q
+            *(u2*)(dk2 + ((size_t)(((d0 + 16 * w) >> 2) + g) * C + tt) * 4) = pack4(dkT[ta]);  // rows >= valid: never read
+        }
+    };
+    auto fini = [&]() {
+    };
+    auto mats = [&](unsigned char* st, int mw, int ml) {
+        bf* Mm = (bf*)(st + L::oM);
+        local_matrices<DV, true>((const bf*)(st + L::oR), L::SR, (const bf*)(st + L::oW), L::SW, (const bf*)(st + L::oO),
+                                 RD, (const float*)(st + L::oS), Mm, Mm + C * kSmR, mw, ml & 15, ml >> 4);
+    };
+    constexpr int PF = DV > 128 ? 2 : 3;  // register sets of the loaders: what fits next to the code that makes the matrices
+    if constexpr (DV > 128) {  // three stages do not fit: the compute waves make the matrices, a barrier, the local terms
+        run_sweep<false, PF, Load3<DK, DV, false>, kHalves>(f, smem, L::bytes, init, local, fini,
+                                                          [&](unsigned char* st, int I) {
+                                                              mats(st, w, lane);
+                                                              state(st, I);
+                                                          });
+    } else {  // the loader waves make them a step ahead
+        run_sweep<false, PF, Load3<DK, DV, false>, kAhead>(
+            f, smem, L::bytes, init,
+            [&](const unsigned char* st, int I) {
+                state(const_cast<unsigned char*>(st), I);
+                local(st, I);
+            },
+            fini, NoFirst(), mats);
+    }
 }
 
 template <int DK, int DV>
@@ -840,101 +899,124 @@ __global__ __launch_bounds__(kThreads) void gdn_blk_query_kernel(const GdnBlockA
               g = lane >> 4;
     const int d0 = s.slice * kCols, d = d0 + 16 * w + r;
     const int plane = (d0 >> 4) + w;
+    constexpr bool kLoadersMakeThem = false;
     f4 St[NT];  // St[t][i] = S[d][16 t + 4g + i]
     f4 dqT[2], dkT[2];  // from the first half of a step (the products with S0) to the second (local terms, stores)
-    run_sweep<true, (DV > 128 ? 2 : 4), Load3<DK, DV, true>, true>(
-        f, smem, L::bytes,
-        [&]() {
+    auto init = [&]() {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            St[t] = a.s0 ? *(const f4*)(a.s0 + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g)
+                         : f4{0.f, 0.f, 0.f, 0.f};
+    };
+    // what needs only the staged rows and the carried state
+    auto state = [&](unsigned char* st, int I) {
+        const bf* Rf = (const bf*)(st + L::oR);
+        const bf* Wf = (const bf*)(st + L::oW);
+        const bf* Of = (const bf*)(st + L::oO);
+        const bf* Ks = (const bf*)(st + L::oK);
+        const float* sc = (const float*)(st + L::oS);
+        // <X, S> at an anchor, the end of this block (this wave's 16 key columns): X is requested here and used
+        // once S has moved on to the end of the block
+        const bool anchored = I + 1 < s.nblk && ((I + 1) & (kAnchorBlocks - 1)) == 0;
+        f4 xa[NT];
+        if (anchored) {
+            const float* src = a.anchor_x + ((anchor_id(s, I + 1) * a.H + s.h) * DK + d) * (size_t)DV + 4 * g;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) xa[t] = *(const f4*)(src + 16 * t);
+        }
+        dqT[0] = dqT[1] = dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < NT; t += 2) {
+            const s8 aS = pack8(St[t], St[t + 1]);
+            mma(dqT[0], aS, op_rows(Of, RD, r, 16 * t, g));
+            mma(dqT[1], aS, op_rows(Of, RD, 16 + r, 16 * t, g));
+            mma(dkT[0], aS, op_cols(Wf, kSmC, 16 * t, 0, r, g));
+            mma(dkT[1], aS, op_cols(Wf, kSmC, 16 * t, 16, r, g));
+        }
+        const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
+        const s8 bk = scale8(aK, sc4(sc, kBeta, 4 * g) * sc4(sc, kAP, 4 * g),
+                             sc4(sc, kBeta, 16 + 4 * g) * sc4(sc, kAP, 16 + 4 * g));
+        const float A = sc[kA * C];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            St[t] *= A;
+            mma(St[t], op_rows(Rf, kSmR, 16 * t + r, 0, g), bk);
+        }
+        if (anchored) {
+            float acc = 0.f;
 #pragma unroll
             for (int t = 0; t < NT; ++t)
-                St[t] = a.s0 ? *(const f4*)(a.s0 + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g)
-                             : f4{0.f, 0.f, 0.f, 0.f};
-        },
-        [&](const unsigned char* st, int I) {
-            const bf* Qs = (const bf*)(st + L::oQ);
-            const bf* Ks = (const bf*)(st + L::oK);
-            const bf* Np = (const bf*)(st + L::oM);
-            const float* sc = (const float*)(st + L::oS);
-            const int valid = f.valid(I);
-            const size_t row0 = f.row0(I);
-            const bf* D2 = (const bf*)(st + L::oD) + ((4 * w + g) * C + r) * 4;  // the X-part of dk, this lane's columns
-            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
 #pragma unroll
-            for (int ta = 0; ta < 2; ++ta) {
-                const int tt = 16 * ta + r;
-                const float pt = sc[kP * C + tt];
-                dqT[ta] *= pt;
-                mma(dqT[ta], aK, op_rows(Np, kSmR, tt, 0, g));
-                const f4 q4 = unpack4(*(const s4*)(Qs + tt * kSlR + 16 * w + 4 * g));
-                float pq = 0.f;
+                for (int i = 0; i < 4; ++i) acc += xa[t][i] * St[t][i];
+            acc = all_groups(row_all(acc));
+            if (lane == 0) a.anchor_phi[(anchor_id(s, I + 1) * a.H + s.h) * (size_t)(DK / 16) + plane] = acc;
+        }
+    };
+    // the local terms, which read the block's matrices
+    auto local = [&](const unsigned char* st, int I) {
+        const bf* Qs = (const bf*)(st + L::oQ);
+        const bf* Ks = (const bf*)(st + L::oK);
+        const bf* Np = (const bf*)(st + L::oM);
+        const float* sc = (const float*)(st + L::oS);
+        const int valid = f.valid(I);
+        const size_t row0 = f.row0(I);
+        const bf* D2 = (const bf*)(st + L::oD) + ((4 * w + g) * C + r) * 4;  // the X-part of dk, this lane's columns
+        const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pq += q4[i] * dqT[ta][i];
-                pq = all_groups(pq);
-                if (tt < valid) {
-                    const size_t at = (row0 + tt) * a.H + s.h;
-                    if (g == 0) a.part_q[(size_t)plane * a.plane + at] = pq;
-                    *(u2*)(a.dq + at * DK + d0 + 16 * w + 4 * g) = pack4(dqT[ta] * sc[kGq * C + tt]);
-                    *(u2*)(a.dk + at * DK + d0 + 16 * w + 4 * g) = pack4(unpack4(*(const s4*)(D2 + 16 * ta * 4)) - pt * dkT[ta]);
-                }
+        for (int ta = 0; ta < 2; ++ta) {
+            const int tt = 16 * ta + r;
+            const float pt = sc[kP * C + tt];
+            dqT[ta] *= pt;
+            mma(dqT[ta], aK, op_rows(Np, kSmR, tt, 0, g));
+            const f4 q4 = unpack4(*(const s4*)(Qs + tt * kSlR + 16 * w + 4 * g));
+            float pq = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pq += q4[i] * dqT[ta][i];
+            pq = all_groups(pq);
+            if (tt < valid) {
+                const size_t at = (row0 + tt) * a.H + s.h;
+                if (g == 0) a.part_q[(size_t)plane * a.plane + at] = pq;
+                *(u2*)(a.dq + at * DK + d0 + 16 * w + 4 * g) = pack4(dqT[ta] * sc[kGq * C + tt]);
+                *(u2*)(a.dk + at * DK + d0 + 16 * w + 4 * g) = pack4(unpack4(*(const s4*)(D2 + 16 * ta * 4)) - pt * dkT[ta]);
             }
-        },
-        [&]() {
-            if (a.dsf) {  // <d_final, S_T> over this wave's 16 key columns
-                float acc = 0.f;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const f4 x = *(const f4*)(a.dsf + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) acc += x[i] * St[t][i];
-                }
-                acc = all_groups(row_all(acc));
-                if (lane == 0) a.corr[(size_t)plane * a.B * a.H + s.bh] = acc;
-            }
-        },
-        [&](unsigned char* st, int I) {
-            const bf* Rf = (const bf*)(st + L::oR);
-            const bf* Wf = (const bf*)(st + L::oW);
-            const bf* Of = (const bf*)(st + L::oO);
-            const bf* Ks = (const bf*)(st + L::oK);
-            const float* sc = (const float*)(st + L::oS);
-            // <X, S> at an anchor, the end of this block (this wave's 16 key columns): X is requested here and used
-            // once S has moved on to the end of the block
-            const bool anchored = I + 1 < s.nblk && ((I + 1) & (kAnchorBlocks - 1)) == 0;
-            f4 xa[NT];
-            if (anchored) {
-                const float* src = a.anchor_x + ((anchor_id(s, I + 1) * a.H + s.h) * DK + d) * (size_t)DV + 4 * g;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) xa[t] = *(const f4*)(src + 16 * t);
-            }
-            local_matrices<DV, false>(Rf, L::SR, nullptr, 0, Of, RD, sc, nullptr, (bf*)(st + L::oM), w, r, g);
-            dqT[0] = dqT[1] = dkT[0] = dkT[1] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < NT; t += 2) {
-                const s8 aS = pack8(St[t], St[t + 1]);
-                mma(dqT[0], aS, op_rows(Of, RD, r, 16 * t, g));
-                mma(dqT[1], aS, op_rows(Of, RD, 16 + r, 16 * t, g));
-                mma(dkT[0], aS, op_cols(Wf, kSmC, 16 * t, 0, r, g));
-                mma(dkT[1], aS, op_cols(Wf, kSmC, 16 * t, 16, r, g));
-            }
-            const s8 aK = op_cols(Ks, kSlC, 0, 16 * w, r, g);
-            const s8 bk = scale8(aK, sc4(sc, kBeta, 4 * g) * sc4(sc, kAP, 4 * g),
-                                 sc4(sc, kBeta, 16 + 4 * g) * sc4(sc, kAP, 16 + 4 * g));
-            const float A = sc[kA * C];
+        }
+    };
+    auto fini = [&]() {
+        if (a.dsf) {  // <d_final, S_T> over this wave's 16 key columns
+            float acc = 0.f;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                St[t] *= A;
-                mma(St[t], op_rows(Rf, kSmR, 16 * t + r, 0, g), bk);
-            }
-            if (anchored) {
-                float acc = 0.f;
+                const f4 x = *(const f4*)(a.dsf + ((size_t)s.bh * DK + d) * DV + 16 * t + 4 * g);
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) acc += xa[t][i] * St[t][i];
-                acc = all_groups(row_all(acc));
-                if (lane == 0) a.anchor_phi[(anchor_id(s, I + 1) * a.H + s.h) * (size_t)(DK / 16) + plane] = acc;
+                for (int i = 0; i < 4; ++i) acc += x[i] * St[t][i];
             }
-        });
+            acc = all_groups(row_all(acc));
+            if (lane == 0) a.corr[(size_t)plane * a.B * a.H + s.bh] = acc;
+        }
+    };
+    auto mats = [&](unsigned char* st, int mw, int ml) {
+        local_matrices<DV, false, !kLoadersMakeThem>((const bf*)(st + L::oR), L::SR, nullptr, 0, (const bf*)(st + L::oO),
+                                                     RD, (const float*)(st + L::oS), nullptr, (bf*)(st + L::oM), mw,
+                                                     ml & 15, ml >> 4);
+    };
+    // This sweep moves the most bytes and wants four blocks in flight, which leaves its loader waves no registers for
+    // the matrix code: the compute waves make N' in the first half of a step (measured: 259 us against 277 us).
+    constexpr int PF = DV > 128 ? 2 : 4;
+    if constexpr (DV > 128 || !kLoadersMakeThem) {
+        run_sweep<true, PF, Load3<DK, DV, true>, kHalves>(f, smem, L::bytes, init, local, fini,
+                                                          [&](unsigned char* st, int I) {
+                                                              mats(st, w, lane);
+                                                              state(st, I);
+                                                          });
+    } else {  // the loader waves make them a step ahead
+        run_sweep<true, PF, Load3<DK, DV, true>, kAhead>(
+            f, smem, L::bytes, init,
+            [&](const unsigned char* st, int I) {
+                state(const_cast<unsigned char*>(st), I);
+                local(st, I);
+            },
+            fini, NoFirst(), mats);
+    }
 }
 
 template <typename K>
@@ -947,7 +1029,9 @@ bool allow_lds(K kernel, int lds) {
 
 template <int DK, int DV>
 int launch_all(const GdnBlockArgs& a, const Areas& ar, size_t blocks, hipStream_t stream) {
-    constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 2 * Stage2<DK>::bytes, lds3 = 2 * Stage3<DV, false>::bytes, lds4 = 2 * Stage3<DV, true>::bytes;
+    constexpr int ns3 = DV > 128 ? 2 : 3;  // stages of sweep 3 (see run_sweep); sweep 2 has three, sweep 4 two
+    constexpr int lds1 = 2 * Stage1<DK>::bytes, lds2 = 3 * Stage2<DK>::bytes, lds3 = ns3 * Stage3<DV, false>::bytes,
+                  lds4 = 2 * Stage3<DV, true>::bytes;
     static_assert(lds1 <= 160 * 1024 && lds2 <= 160 * 1024 && lds3 <= 160 * 1024 && lds4 <= 160 * 1024, "LDS");
     static std::atomic<uint64_t> configured{0};  // bit d: attributes set on device d
     int dev = 0;
