@@ -237,16 +237,19 @@ size_t sla_backward_workspace_bytes(const sla_params* p);
  *
  *   q, k, v, q_head_logits, k_head_logits, initial_state, d_out, d_final_state,
  *   dq, dk, dv, dq_head_logits, dk_head_logits, d_initial_state      as for sla_backward
- *   log_decay, beta  [B,T,H] fp32   as for sla_forward; required.  log_decay >= -20 per token (the sweeps keep
- *                                   their state divided by the decay product of up to four tokens)
+ *   log_decay, beta  [B,T,H] fp32   as for sla_forward; required.  fp32 tensors: log_decay >= -20 per token (those
+ *                                   sweeps keep their state divided by the decay product of up to four tokens)
  *   dlog_decay       [B,T,H] fp32   written; required
  *   dbeta            [B,T,H] fp32   written; required
  *   workspace        device memory of at least sla_backward_gdn_workspace_bytes(p) bytes, 16-byte aligned (gates,
- *                    partial sums, and three fp32 tensors the size of v, v and k that pass the delta rule's
- *                    feedback terms between the four sweeps).  Contents on entry are ignored; calls that share a
- *                    workspace must not overlap.
- * The sweeps run token by token in fp32 vector arithmetic (bf16 inputs are widened on the way in, bf16 outputs
- * rounded once).
+ *                    partial sums, and what passes the delta rule's feedback terms between the four sweeps: three
+ *                    tensors the size of v, v and k, in fp32 for fp32 tensors; in bf16, with one 32 x 32 matrix and
+ *                    256 scalars per 32-token block and head and the state cotangent at every 512th token of a
+ *                    sequence, for bf16 tensors).  Contents on entry are ignored; calls that share a workspace must
+ *                    not overlap.
+ * bf16 tensors run in block form on the matrix cores (32-token blocks, fp32 accumulation, every decay factor <= 1;
+ * dlog_decay is re-derived exactly every 512 tokens, so its error does not grow with the sequence length); fp32
+ * tensors run token by token in fp32 vector arithmetic.
  * Everything is enqueued on `stream`; nothing is allocated, freed or synchronised.  Returns a status code; on error
  * nothing is launched.
  */
