@@ -87,6 +87,15 @@ def test_head_widths(dk, dv):
     check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"dk={dk} dv={dv}")
 
 
+@pytest.mark.parametrize("dk,dv,T", [(128, 256, 1100), (64, 64, 1300), (64, 128, 520), (128, 64, 1024 + 31)])
+def test_head_widths_across_anchors(dk, dv, T):
+    """Every width pair over sequences long enough for the loaders' register sets to go round several times, for the
+    three-stage and the two-half step (value heads of width 256 take the latter) and for one or two anchors of the
+    decay gradient; two batch rows, so a row's anchors sit next to another row's in the workspace."""
+    d, cot, s0 = make(2, T, 2, dk, dv, seed=1125 + dk + dv, states=True)
+    check_backward_gdn(d, cot, s0=s0, want_ds0=True, label=f"dk={dk} dv={dv} T={T}")
+
+
 @pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 33])
 def test_short_sequences(T):
     d, cot, s0 = make(2, T, 2, 64, 64, seed=1130 + T, states=True)
