@@ -10,7 +10,7 @@ _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsla.so")
 SOURCES = ["sla_api.hip", "sla_kernels.hip", "sla_kernels_bf16.hip", "sla_kernels_f32.hip", "sla_decode.hip",
-           "sla_backward.hip", "sla_backward_f32.hip", "sla_backward_gdn.hip", "sla_backward_gdn_block.hip", "sla_prologue.hip", "sla_prologue_grad.hip"]
+           "sla_backward.hip", "sla_backward_f32.hip", "sla_backward_narrow.hip", "sla_backward_gdn.hip", "sla_backward_gdn_block.hip", "sla_prologue.hip", "sla_prologue_grad.hip"]
 OBJ_DIR = os.path.join(_HERE, "_build")
 
 # Packed-fp32 VALU instructions are switched off for all device code (a hipcc flag; the host pass

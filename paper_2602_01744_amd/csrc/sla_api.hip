@@ -24,6 +24,17 @@ int launch_backward_segments(const sla_params& p, int nseg, int seg_len, int dvw
                              const void* dout, const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl,
                              void* dld, float* ds0, float* ws, hipStream_t stream);
 size_t backward_gdn_workspace_floats(const sla_params& p, bool packed);
+// any supported key width: heads of width 32 run zero-padded to 64 (sla_backward_narrow.hip)
+size_t backward_any_workspace_floats(const sla_params& p, bool packed);
+int launch_backward_any(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
+                        const float* kl, const void* ld, const float* s0, const void* dout, const float* dsf, void* dq,
+                        void* dk, void* dv, float* dql, float* dkl, void* dld, float* ds0, float* ws, const int* cu,
+                        bool packed, hipStream_t stream);
+size_t backward_gdn_any_workspace_floats(const sla_params& p, bool packed);
+int launch_backward_gdn_any(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
+                            const float* kl, const float* ld, const float* beta, const float* s0, const void* dout,
+                            const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
+                            float* dbeta, float* ds0, float* ws, const int* cu, bool packed, hipStream_t stream);
 int launch_backward_gdn(const sla_params& p, const void* q, const void* k, const void* v, const float* ql,
                         const float* kl, const float* ld, const float* beta, const float* s0, const void* dout,
                         const float* dsf, void* dq, void* dk, void* dv, float* dql, float* dkl, float* dld,
@@ -351,7 +362,7 @@ static int backward_segments(const sla_params& p, bool packed, int* seg_len) {
 static size_t backward_floats(const sla_params& p, bool packed) {
     int len = 0;
     const int nseg = backward_segments(p, packed, &len);
-    if (nseg <= 1) return sla::backward_workspace_floats(p, packed);
+    if (nseg <= 1) return sla::backward_any_workspace_floats(p, packed);
     return sla::backward_workspace_floats(sla::packed_segments(p, nseg), true) +
            sla::backward_segment_extra_floats(p, nseg);
 }
@@ -363,8 +374,9 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
                          void* workspace, size_t workspace_bytes, const int32_t* cu, bool packed, void* stream) {
     int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant == SLA_GDN || p->dk < 64 || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
-    if (p->dtype == SLA_F32 && p->segments >= 2) return SLA_ERR_UNSUPPORTED;  // fp32 tensors: the single pass only
+    if (p->variant == SLA_GDN || (packed && p->flags != 0)) return SLA_ERR_UNSUPPORTED;
+    // fp32 tensors and key heads of width 32: the single pass only
+    if ((p->dtype == SLA_F32 || p->dk < 64) && p->segments >= 2) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !d_out || !dq || !dk || !dv || !dq_head_logits)
             return SLA_ERR_NULL;
@@ -390,10 +402,10 @@ static int backward_impl(const sla_params* p, const void* q, const void* k, cons
                                              dk_head_logits, dlog_decay, d_initial_state, (float*)workspace,
                                              (hipStream_t)stream);
     }
-    return sla::launch_backward(*p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out,
-                                d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
-                                d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr,
-                                (hipStream_t)stream);
+    return sla::launch_backward_any(*p, q, k, v, q_head_logits, k_head_logits, log_decay, initial_state, d_out,
+                                    d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
+                                    d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr, packed,
+                                    (hipStream_t)stream);
 }
 
 int sla_backward(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
@@ -424,7 +436,7 @@ static int backward_gdn_impl(const sla_params* p, const void* q, const void* k, 
                              float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_params(p);
     if (rc != SLA_OK) return rc;
-    if (p->variant != SLA_GDN || p->flags != 0 || p->dk < 64) return SLA_ERR_UNSUPPORTED;
+    if (p->variant != SLA_GDN || p->flags != 0) return SLA_ERR_UNSUPPORTED;
     if (p->B > 0 && p->T > 0) {
         if (!q || !k || !v || !q_head_logits || !log_decay || !beta || !d_out || !dq || !dk || !dv ||
             !dq_head_logits || !dlog_decay || !dbeta)
@@ -440,12 +452,12 @@ static int backward_gdn_impl(const sla_params* p, const void* q, const void* k, 
     if (cu && (reinterpret_cast<uintptr_t>(cu) & 3u)) return SLA_ERR_ALIGN;
     if (p->B == 0) return SLA_OK;
     if (p->T == 0 && !d_initial_state) return SLA_OK;
-    if (p->T > 0 && (!workspace || sla::backward_gdn_workspace_floats(*p, packed) * sizeof(float) > workspace_bytes))
+    if (p->T > 0 && (!workspace || sla::backward_gdn_any_workspace_floats(*p, packed) * sizeof(float) > workspace_bytes))
         return SLA_ERR_WORKSPACE;
-    return sla::launch_backward_gdn(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state, d_out,
-                                    d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay, dbeta,
-                                    d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr,
-                                    (hipStream_t)stream);
+    return sla::launch_backward_gdn_any(*p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, initial_state,
+                                        d_out, d_final_state, dq, dk, dv, dq_head_logits, dk_head_logits, dlog_decay,
+                                        dbeta, d_initial_state, (float*)workspace, packed && p->T > 0 ? cu : nullptr,
+                                        packed, (hipStream_t)stream);
 }
 
 int sla_backward_gdn(const sla_params* p, const void* q, const void* k, const void* v, const float* q_head_logits,
@@ -470,13 +482,13 @@ int sla_backward_gdn_varlen(const sla_params* p, const void* q, const void* k, c
 }
 
 size_t sla_backward_gdn_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dk < 64) return 0;
-    return sla::backward_gdn_workspace_floats(*p, false) * sizeof(float);
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN) return 0;
+    return sla::backward_gdn_any_workspace_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_gdn_varlen_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant != SLA_GDN || p->dk < 64) return 0;
-    return sla::backward_gdn_workspace_floats(*p, true) * sizeof(float);
+    if (check_params(p) != SLA_OK || p->variant != SLA_GDN) return 0;
+    return sla::backward_gdn_any_workspace_floats(*p, true) * sizeof(float);
 }
 
 int sla_gate_logits(const sla_params* p, const void* q, const void* k, const float* w_gq, const float* w_gk,
@@ -575,14 +587,14 @@ int sla_gate_logits_backward(const sla_params* p, const void* x, const float* w,
 }
 
 size_t sla_backward_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dk < 64) return 0;
-    if (p->dtype == SLA_F32 && p->segments >= 2) return 0;
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN) return 0;
+    if ((p->dtype == SLA_F32 || p->dk < 64) && p->segments >= 2) return 0;
     return backward_floats(*p, false) * sizeof(float);
 }
 
 size_t sla_backward_varlen_workspace_bytes(const sla_params* p) {
-    if (check_params(p) != SLA_OK || p->variant == SLA_GDN || p->dk < 64) return 0;
-    return sla::backward_workspace_floats(*p, true) * sizeof(float);
+    if (check_params(p) != SLA_OK || p->variant == SLA_GDN) return 0;
+    return sla::backward_any_workspace_floats(*p, true) * sizeof(float);
 }
 
 size_t sla_workspace_bytes(const sla_params* p, int compute_units) {

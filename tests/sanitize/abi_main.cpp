@@ -34,6 +34,16 @@ size_t backward_gdn_workspace_floats(const sla_params& p, bool) { return (size_t
 int launch_backward_gdn(const sla_params&, const void*, const void*, const void*, const float*, const float*,
                         const float*, const float*, const float*, const void*, const float*, void*, void*, void*,
                         float*, float*, float*, float*, float*, float*, const int*, hipStream_t) { return reached("backward gdn"); }
+size_t backward_any_workspace_floats(const sla_params& p, bool packed) { return backward_workspace_floats(p, packed); }
+int launch_backward_any(const sla_params&, const void*, const void*, const void*, const float*, const float*, const void*,
+                        const float*, const void*, const float*, void*, void*, void*, float*, float*, void*, float*,
+                        float*, const int*, bool, hipStream_t) { return reached("backward"); }
+size_t backward_gdn_any_workspace_floats(const sla_params& p, bool packed) { return backward_gdn_workspace_floats(p, packed); }
+int launch_backward_gdn_any(const sla_params&, const void*, const void*, const void*, const float*, const float*,
+                            const float*, const float*, const float*, const void*, const float*, void*, void*, void*,
+                            float*, float*, float*, float*, float*, float*, const int*, bool, hipStream_t) {
+    return reached("backward gdn");
+}
 int launch_gate_logits(const sla_params&, const void*, const void*, const float*, const float*, float*, float*, int,
                        hipStream_t) { return reached("gate logits"); }
 int launch_short_conv_silu(int, int, int, int, int, const void*, const float*, void*, hipStream_t) { return reached("conv"); }

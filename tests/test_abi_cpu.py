@@ -370,13 +370,26 @@ def test_static_entry_point_validates_before_any_device_work(lib):
     assert sla.sla_forward_static(big, A, A, A, A, A, A, 0, 0, A, A, 0) == -7
 
 
-def test_narrow_keys_are_forward_only(lib):
-    """dk = 32 passes the forward's validation; the backward, the decode step and their workspace queries refuse it."""
+def test_narrow_keys(lib):
+    """dk = 32 passes the forward's validation; the backward passes run it zero-padded to 64 (single pass only) with
+    the padded copies in the workspace; the decode step refuses it."""
     p = _ok_params(dk=32, dv=64)
     assert _call(p) == 0
-    assert _bwd(p) == -3
-    assert sla.sla_backward_workspace_bytes(p) == 0
-    assert sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dk=32, dv=64)) == 0
+    assert _bwd(p) in (0, -5)                                # valid: reaches the launch (no device here)
+    assert _bwd(_ok_params(dk=32, dv=64, segments=2, T=1024)) == -3
+    B, T, H, dv = 2, 128, 4, 64
+    n = B * T * H
+    for dt, es in ((sla.BF16, 2), (sla.F32, 4)):
+        wide, state = n * 64 * es // 4, B * H * 64 * dv      # floats of a padded [rows,H,64] tensor and of a padded state
+        for variant in (sla.GLA, sla.RETNET):
+            narrow = sla.sla_backward_workspace_bytes(_ok_params(variant=variant, dtype=dt, B=B, T=T, H=H, dk=32, dv=dv))
+            inner = sla.sla_backward_workspace_bytes(_ok_params(variant=variant, dtype=dt, B=B, T=T, H=H, dk=64, dv=dv))
+            assert narrow == inner + 4 * (6 * wide + 3 * state)
+        narrow = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=dt, B=B, T=T, H=H, dk=32, dv=dv))
+        inner = sla.sla_backward_gdn_workspace_bytes(_ok_params(variant=sla.GDN, dtype=dt, B=B, T=T, H=H, dk=64, dv=dv))
+        assert narrow == inner + 4 * (4 * wide + 3 * state)
+    assert sla.sla_backward_workspace_bytes(_ok_params(dk=32, dv=64, segments=2, T=1024)) == 0
+    assert sla.sla_backward_segments(_ok_params(B=1, T=4096, H=2, dk=32, dv=64), 256) == 1
     args = (A, A, A, A, A, A, 0)
     assert sla.sla_decode_step(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) == -3
 
