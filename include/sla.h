@@ -74,8 +74,8 @@ typedef struct {
     int32_t B;       /* batch size            >= 0 */
     int32_t T;       /* tokens per sequence   >= 0 */
     int32_t H;       /* heads                 1..64 */
-    int32_t dk;      /* key/query head width  32, 64 or 128 (32: not in the decode step; the backward passes run it
-                        zero-padded to 64, single pass only, with the padded copies in their workspace) */
+    int32_t dk;      /* key/query head width  32, 64 or 128 (32: the backward passes run it zero-padded to 64, single
+                        pass only, with the padded copies in their workspace) */
     int32_t dv;      /* value head width      64, 128 or 256 */
     int32_t dv_split; /* 0 = let the library choose; else value columns per workgroup: 16, 32 or 64 (<= dv).
                         A scheduling knob only: results are bit-identical for every width

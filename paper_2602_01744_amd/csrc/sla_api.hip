@@ -329,7 +329,6 @@ int sla_decode_step(const sla_params* p, const void* q, const void* k, const voi
     const int rc = check(p, q, k, v, q_head_logits, k_head_logits, log_decay, beta, state, out, state);
     if (rc != SLA_OK) return rc;
     if (p->T != 1) return SLA_ERR_SHAPE;
-    if (p->dk < 64) return SLA_ERR_UNSUPPORTED;
     if (p->B == 0) return SLA_OK;
     if (!state) return SLA_ERR_NULL;
     // one token per sequence: [B,1,H,d] and [B,H,1,d] are the same memory, so the layout flag changes nothing
@@ -344,7 +343,6 @@ int sla_decode_step_fused(const sla_params* p, const void* q, const void* k, con
     const int rc = check(p, q, k, v, w_gq, w_gk, log_decay, beta, state, out, state);
     if (rc != SLA_OK) return rc;
     if (p->T != 1) return SLA_ERR_SHAPE;
-    if (p->dk < 64) return SLA_ERR_UNSUPPORTED;
     if (p->B == 0) return SLA_OK;
     if (!state) return SLA_ERR_NULL;
     return sla::launch_decode(*p, q, k, v, nullptr, nullptr, w_gq, w_gk, log_decay, beta, state, out,

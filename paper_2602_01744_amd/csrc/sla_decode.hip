@@ -109,14 +109,14 @@ __global__ __launch_bounds__(kDecThreads) void sla_decode_kernel(const DArgs a) 
 
     float gq, gk;
     if (a.wq) {
-        // Fused gate projection (Eq. 4 needs the logits of every head of the token): 16 threads per head, 16 heads
-        // per pass, each thread DK/16 adjacent elements of q[b,h',:] . W_GQ[:,h'] and k[b,h',:] . W_GK[:,h'], summed
-        // over the 16 threads with shuffles -- 2 H dk multiply-adds against the dk dv of the state update, and one
-        // launch less in front of every decode step.
+        // Fused gate projection (Eq. 4 needs the logits of every head of the token): TPH threads per head (16; 8 for
+        // dk = 32), each thread DK/TPH >= 4 adjacent elements of q[b,h',:] . W_GQ[:,h'] and k[b,h',:] . W_GK[:,h'],
+        // summed over the TPH threads with shuffles -- 2 H dk multiply-adds against the dk dv of the state update, and
+        // one launch less in front of every decode step.
         __shared__ float lg[2][64];
-        constexpr int EPT = DK / 16;
-        const int sub = tid & 15;
-        for (int h2 = tid >> 4; h2 < a.H; h2 += kDecThreads / 16) {
+        constexpr int TPH = DK >= 64 ? 16 : 8, EPT = DK / TPH;
+        const int sub = tid % TPH;
+        for (int h2 = tid / TPH; h2 < a.H; h2 += kDecThreads / TPH) {
             const size_t at = ((size_t)b * a.H + h2) * DK + sub * EPT, wat = (size_t)h2 * DK + sub * EPT;
             float xq[EPT], xk[EPT], wq[EPT], wk[EPT];
             load_run<BF16, EPT>(a.q, at, xq);
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kDecThreads) void sla_decode_kernel(const DArgs a) 
                 if (a.wk) sk += xk[e] * wk[e];
             }
 #pragma unroll
-            for (int o = 8; o >= 1; o >>= 1) {
+            for (int o = TPH / 2; o >= 1; o >>= 1) {
                 sq += __shfl_xor(sq, o);
                 sk += __shfl_xor(sk, o);
             }
@@ -239,6 +239,7 @@ int launch_dv(const DArgs& a, int dv, hipStream_t stream) {
 template <bool BF16, int VAR>
 int launch_dk(const DArgs& a, int dk, int dv, hipStream_t stream) {
     switch (dk) {
+        case 32: return launch_dv<BF16, VAR, 32>(a, dv, stream);
         case 64: return launch_dv<BF16, VAR, 64>(a, dv, stream);
         case 128: return launch_dv<BF16, VAR, 128>(a, dv, stream);
         default: return SLA_ERR_UNSUPPORTED;

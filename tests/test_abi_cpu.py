@@ -160,7 +160,7 @@ def test_decode_step_validation(lib):
     assert sla.sla_decode_step_fused(one, A, A, A, 0, A, A, 0, A, A, 0) == -1  # w_gq missing
     assert sla.sla_decode_step_fused(one, A, A, A, A + 4, A, A, 0, A, A, 0) == -4
     assert sla.sla_decode_step_fused(one, *args, 0, A, 0) == -1
-    assert sla.sla_decode_step_fused(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) == -3
+    assert sla.sla_decode_step_fused(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) in (0, -5)  # valid: reaches the launch
     assert sla.sla_decode_step_fused(_ok_params(T=1, B=0), 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 0
 
 
@@ -372,7 +372,7 @@ def test_static_entry_point_validates_before_any_device_work(lib):
 
 def test_narrow_keys(lib):
     """dk = 32 passes the forward's validation; the backward passes run it zero-padded to 64 (single pass only) with
-    the padded copies in the workspace; the decode step refuses it."""
+    the padded copies in the workspace; the decode step takes it."""
     p = _ok_params(dk=32, dv=64)
     assert _call(p) == 0
     assert _bwd(p) in (0, -5)                                # valid: reaches the launch (no device here)
@@ -391,7 +391,7 @@ def test_narrow_keys(lib):
     assert sla.sla_backward_workspace_bytes(_ok_params(dk=32, dv=64, segments=2, T=1024)) == 0
     assert sla.sla_backward_segments(_ok_params(B=1, T=4096, H=2, dk=32, dv=64), 256) == 1
     args = (A, A, A, A, A, A, 0)
-    assert sla.sla_decode_step(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) == -3
+    assert sla.sla_decode_step(_ok_params(T=1, dk=32, dv=64), *args, A, A, 0) in (0, -5)  # valid: reaches the launch
 
 
 def test_prologue_gradient_entry_points_validate(lib):

@@ -50,7 +50,8 @@ def decode_chain(variant, d, dtype, state0):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("dk,dv", [(128, 128), (64, 64), (64, 128), (128, 64), (128, 256), (64, 256)])
+@pytest.mark.parametrize("dk,dv", [(128, 128), (64, 64), (64, 128), (128, 64), (128, 256), (64, 256), (32, 64), (32, 128),
+                                   (32, 256)])
 def test_single_step_matches_oracle(variant, dtype, dk, dv):
     d = si.custom(variant, dtype, B=3, T=1, H=5, dk=dk, dv=dv, seed=2100 + variant + dk + dv)
     s0 = si.initial_state(3, 5, dk, dv, seed=21)
@@ -126,7 +127,8 @@ def test_full_size_decode_batch():
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("H,dk,dv,both", [(16, 128, 128, True), (5, 64, 256, True), (33, 128, 64, False), (1, 64, 64, True)])
+@pytest.mark.parametrize("H,dk,dv,both", [(16, 128, 128, True), (5, 64, 256, True), (33, 128, 64, False), (1, 64, 64, True),
+                                          (16, 32, 64, True), (40, 32, 128, True)])
 def test_fused_gate_projection_matches_oracle(variant, dtype, H, dk, dv, both):
     """sla_decode_step_fused: logits formed in the kernel from q, k and the gate matrices.  The reference is the
     oracle's projection (q . W_GQ per head) followed by the oracle's forward on those logits."""
