@@ -15,17 +15,19 @@
 //     dq' = diag(p) dOut S0^T + N' K                 N' = tril(D * dOut U^T)      dq = G^Q dq'    dG^Q = q . dq'
 //     dk  = diag(A / p) U X1^T - diag(p) w S0^T + (M + M^T) K + N^T Q
 //           M = strict_tril(-D * w U^T)              N = diag(G^Q) N'
-// The decay gradient needs no state product (see sla_backward_gdn.hip).  The 32 x 32 matrices depend on one block
-// only: those made of q, k, the decays and beta come from a kernel that runs over all blocks in parallel (`pre`);
-// M and N', made of res, w and dOut, are formed by sweeps 3 and 4 themselves from the rows they hold anyway; what
-// remains serial are four sweeps that each carry one state tile in fp32 matrix-core
-// accumulators, as in the token-recurrent version: (1) forward, S sliced over value columns -> res; (2) backward, X
-// sliced over value columns -> w, dv, dG^K, dbeta, d_initial_state; (3) backward, X^T sliced over key columns -> the
-// part of dk that needs X; (4) forward, S^T sliced over key columns -> dq, dG^Q, dk, <d_final, S_T>.
+// The decay gradient needs no state product (see sla_backward_gdn.hip), but is re-derived as <X0, S0> at every 512th
+// token of a sequence, where its running sum would otherwise have drifted (kGdnAnchor in sla_gdn_block.h).  The
+// 32 x 32 matrices depend on one block only: T' = (I + Lk diag(beta))^-1 comes from a kernel that runs over all blocks
+// in parallel (`pre`); the others are formed by the sweep that uses them from the rows it holds anyway (Lq and Lk in
+// sweep 2, M and N' in sweep 3, N' in sweep 4).  What remains serial are four sweeps that each carry one state tile in
+// fp32 matrix-core accumulators, as in the token-recurrent version: (1) forward, S sliced over value columns -> res;
+// (2) backward, X sliced over value columns -> w, dv, dG^K, dbeta, d_initial_state; (3) backward, X^T sliced over key
+// columns -> the part of dk that needs X; (4) forward, S^T sliced over key columns -> dq, dG^Q, dk, <d_final, S_T>.
 //
 // A sweep workgroup: four compute waves (16 columns of the 64-column slice each, the whole contraction dimension)
-// and four loader waves that copy the next block's rows from global memory to LDS, row-major and unchanged, into the
-// other half of a double buffer; one barrier per block.  Every operand orientation comes from the same row-major
+// and four loader waves that copy the coming blocks' rows from global memory to LDS, row-major and unchanged, several
+// blocks ahead in registers, into the next of two or three LDS stages (run_sweep() and its modes: who makes the
+// block-local matrices, and when).  Every operand orientation comes from the same row-major
 // arrays: rows as they are (`op_rows`), columns through the transposing LDS read of gfx950 (`op_cols`,
 // ds_read_b64_tr_b16: the 16 lanes of a group fetch 4 rows x 16 columns and each receives one column), and an
 // accumulator tile serves directly as the next product's operand (rows 4g..4g+3 of lane group g are its contraction
@@ -33,8 +35,8 @@
 // in both operands.
 //
 // Intermediates in the workspace: res and w as bf16 [block][head][column][32 tokens] (a lane's four tokens of an
-// accumulator tile are one 8-byte store), the 32 x 32 matrices as bf16, per-token scalars as fp32, the X-part of dk as
-// bf16 [block][head][dk/4][32 tokens][4].
+// accumulator tile are one 8-byte store), T' as bf16, per-token scalars as fp32, the X-part of dk as
+// bf16 [block][head][dk/4][32 tokens][4], and at the anchors the state cotangent in fp32.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
